@@ -1,0 +1,185 @@
+"""ctypes front end of the CPU oracle (oracle/esc_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: used by tests/, the smoke check and the benchmark's
+cpu_baseline leg.  The product path never imports this module.
+
+Each function mirrors one C entry point; see the C file for the passages of the
+ESC paper (Sec. 3, Eq. 4 and the paragraph around Eq. 5) each one follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "esc_oracle.c")
+_LIB = os.path.join(_HERE, "libesc_oracle.so")
+
+F32 = 0
+BF16 = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (a second or two).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, ci, cl = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
+        lib.esc_oracle_gap.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp]
+        lib.esc_oracle_gap.restype = None
+        lib.esc_oracle_generator.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp]
+        lib.esc_oracle_generator.restype = None
+        lib.esc_oracle_lk_conv.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, cl, vp]
+        lib.esc_oracle_lk_conv.restype = None
+        lib.esc_oracle_dk_conv.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp]
+        lib.esc_oracle_dk_conv.restype = None
+        lib.esc_oracle_convattn_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, cl,
+                                                    ci, ci, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.esc_oracle_convattn_forward.restype = ci
+        lib.esc_oracle_f32_to_bf16.argtypes = [ctypes.c_float]
+        lib.esc_oracle_f32_to_bf16.restype = ctypes.c_uint16
+        lib.esc_oracle_threads.restype = ci
+        lib.esc_oracle_set_threads.argtypes = [ci]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _x(x: np.ndarray, dtype: int) -> np.ndarray:
+    want = np.float32 if dtype == F32 else np.uint16
+    if x.dtype != want:
+        raise TypeError(f"x must be {want} for dtype {dtype}")
+    if x.ndim != 4:
+        raise ValueError("x must be [N,C,H,W]")
+    return np.ascontiguousarray(x)
+
+
+def _f32(a: Optional[np.ndarray]) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def threads() -> int:
+    return _load().esc_oracle_threads()
+
+
+def set_threads(t: int) -> None:
+    _load().esc_oracle_set_threads(int(t))
+
+
+def f32_to_bf16(v: float) -> int:
+    return int(_load().esc_oracle_f32_to_bf16(ctypes.c_float(v)))
+
+
+def gap(x: np.ndarray, Ca: int, dtype: int = F32) -> np.ndarray:
+    """Global average pool of the attention slice -> [N,Ca] float64."""
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    g = np.empty((N, Ca), dtype=np.float64)
+    _load().esc_oracle_gap(_ptr(x), dtype, N, C, H, W, Ca, _ptr(g))
+    return g
+
+
+def generator(g: np.ndarray, hidden: int, w_up: np.ndarray, b_up=None, w_down=None,
+              b_down=None) -> np.ndarray:
+    """Kernel estimator -> DK [N,Ca,3,3] float64."""
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    N, Ca = g.shape
+    w_up, b_up, w_down, b_down = _f32(w_up), _f32(b_up), _f32(w_down), _f32(b_down)
+    K = hidden if hidden > 0 else Ca
+    assert w_up.shape == (9 * Ca, K), (w_up.shape, (9 * Ca, K))
+    if hidden > 0:
+        assert w_down.shape == (hidden, Ca)
+    dk = np.empty((N, Ca, 3, 3), dtype=np.float64)
+    _load().esc_oracle_generator(_ptr(g), N, Ca, hidden, _ptr(w_down), _ptr(b_down), _ptr(w_up),
+                                 _ptr(b_up), _ptr(dk))
+    return dk
+
+
+def _lk_stride(lk: np.ndarray, Ca: int):
+    lk = _f32(lk)
+    if lk.ndim == 2:
+        return lk, lk.shape[0], 0
+    assert lk.ndim == 3 and lk.shape[0] == Ca and lk.shape[1] == lk.shape[2]
+    return lk, lk.shape[1], lk.shape[1] * lk.shape[2]
+
+
+def lk_conv(x: np.ndarray, Ca: int, lk: np.ndarray, dtype: int = F32) -> np.ndarray:
+    """F_att cross-correlated with the large kernel -> [N,Ca,H,W] float64."""
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    lk, Ks, cs = _lk_stride(lk, Ca)
+    res = np.empty((N, Ca, H, W), dtype=np.float64)
+    _load().esc_oracle_lk_conv(_ptr(x), dtype, N, C, H, W, Ca, _ptr(lk), Ks, cs, _ptr(res))
+    return res
+
+
+def dk_conv(x: np.ndarray, Ca: int, dk: np.ndarray, dtype: int = F32) -> np.ndarray:
+    """F_att cross-correlated with a per-image 3x3 kernel -> [N,Ca,H,W] float64."""
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    dk = np.ascontiguousarray(dk, dtype=np.float64)
+    assert dk.shape == (N, Ca, 3, 3)
+    res = np.empty((N, Ca, H, W), dtype=np.float64)
+    _load().esc_oracle_dk_conv(_ptr(x), dtype, N, C, H, W, Ca, _ptr(dk), _ptr(res))
+    return res
+
+
+def convattn_forward(x: np.ndarray, Ca: int, lk: np.ndarray, dtype: int = F32, *,
+                     hidden: int = 0, w_up=None, b_up=None, w_down=None, b_down=None,
+                     dk_in=None, want_out: bool = True):
+    """Whole forward.  DK comes from the estimator when w_up is given, from
+    dk_in when that is given, and is zero when neither is.
+
+    Returns (res_att float64 [N,Ca,H,W], dk float64 [N,Ca,3,3], out in storage
+    dtype [N,C,H,W] or None).
+    """
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    lk, Ks, cs = _lk_stride(lk, Ca)
+    if w_up is not None and dk_in is not None:
+        raise ValueError("give either estimator weights or dk_in, not both")
+    mode = 1 if w_up is not None else (2 if dk_in is not None else 0)
+    w_up, b_up, w_down, b_down = _f32(w_up), _f32(b_up), _f32(w_down), _f32(b_down)
+    if mode == 1:
+        K = hidden if hidden > 0 else Ca
+        assert w_up.shape == (9 * Ca, K)
+        if hidden > 0:
+            assert w_down.shape == (hidden, Ca)
+    if dk_in is not None:
+        dk_in = np.ascontiguousarray(dk_in, dtype=np.float64)
+        assert dk_in.shape == (N, Ca, 3, 3)
+    res = np.empty((N, Ca, H, W), dtype=np.float64)
+    dk = np.empty((N, Ca, 3, 3), dtype=np.float64)
+    out = np.empty_like(x) if want_out else None
+    rc = _load().esc_oracle_convattn_forward(
+        _ptr(x), dtype, N, C, H, W, Ca, _ptr(lk), Ks, cs, mode, hidden,
+        _ptr(w_down), _ptr(b_down), _ptr(w_up), _ptr(b_up), _ptr(dk_in),
+        _ptr(res), _ptr(dk), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return res, dk, out
+
+
+def forward_workload(wl, want_out: bool = True):
+    """Run the whole forward on a workloads.Workload-like object."""
+    return convattn_forward(wl.x, wl.Ca, wl.lk, wl.dtype, hidden=wl.hidden, w_up=wl.w_up,
+                            b_up=wl.b_up, w_down=wl.w_down, b_down=wl.b_down, want_out=want_out)
