@@ -1,0 +1,110 @@
+/*
+ * esc_convattn.h - C ABI of the MI355X (gfx950) ConvAttn forward library.
+ *
+ * The operation is the Convolutional Attention Module of the ESC paper
+ * (Sec. 3, Eq. 4) with the depth-wise large kernel LK^s of the paragraph that
+ * introduces Eq. 5, stopped before the 1x1 fuse convolution:
+ *
+ *   F_att, F_idt = Split(x)                 first C_a channels / the rest   (Eq. 4 line 1)
+ *   DK           = Estimator(GAP(F_att))    one 3x3 kernel per image+channel (Eq. 4 line 2)
+ *   F_res        = F_att (*) DK + F_att (*) LK                               (Eq. 4 line 3)
+ *   out          = Concat(F_res, F_idt)                                      (Eq. 4 line 4)
+ *
+ * (*) is depth-wise cross-correlation, zero padding (K-1)/2, stride 1, so the
+ * output keeps H x W.  Accumulation is fp32; F_res is rounded once, at the
+ * store, to the storage type.  F_idt is copied bit for bit.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers, caller-owned, never freed, copied
+ *     or retained by the library.  `stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).  Calls only enqueue work on `stream` and
+ *     return; they never synchronise and never allocate.
+ *   - x and out are contiguous [N, C, H, W] in the storage type `dt`; out must
+ *     not overlap x.  lk, the estimator weights, dk and the workspace are fp32
+ *     in both storage modes.
+ *   - All arguments are validated on the host before the first launch; a call
+ *     that returns an error has enqueued nothing.
+ *   - The workspace must have been prepared once with esc_workspace_init on a
+ *     stream ordered before its first use.  A completed call leaves it ready
+ *     for the next call; two calls that share a workspace must be ordered (same
+ *     stream, or synchronised).  esc_workspace_bytes gives the size for a shape;
+ *     a workspace sized for a larger (N, C_a, H, W) in every argument also fits.
+ *   - Limits: 0 <= C_a <= min(C, 256); estimator hidden width <= 256; Ks odd,
+ *     1 <= Ks <= 31; H*W < 2^31; N, C, H, W >= 1.  No lower bound on H or W
+ *     relative to Ks.
+ */
+#ifndef ESC_CONVATTN_H
+#define ESC_CONVATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ESC_OK = 0,
+    ESC_ERR_NULL = 1,        /* a required pointer is NULL                         */
+    ESC_ERR_SHAPE = 2,       /* a size is out of its domain (N<1, C_a>C, ...)      */
+    ESC_ERR_DTYPE = 3,       /* dt is not a member of esc_dtype                    */
+    ESC_ERR_UNSUPPORTED = 4, /* valid for the method, outside the library's limits */
+    ESC_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or too small         */
+    ESC_ERR_ALIAS = 6,       /* out overlaps x                                     */
+    ESC_ERR_HIP = 7          /* the HIP runtime refused a launch                   */
+} esc_status;
+
+typedef enum { ESC_F32 = 0, ESC_BF16 = 1 } esc_dtype; /* storage type of x and out */
+
+/*
+ * The kernel estimator of Eq. 4 line 2, applied to g = GAP(F_att) of one image:
+ *   hidden == 0 : d = w_up[9*C_a, C_a] g + b_up                 (single linear layer)
+ *   hidden  > 0 : d = w_up[9*C_a, hidden] gelu(w_down[hidden, C_a] g + b_down) + b_up
+ * gelu is the exact erf form.  Matrices are row-major [out, in], fp32, device
+ * memory.  Either bias may be NULL (zero).  DK[c, i, j] = d[c*9 + i*3 + j].
+ */
+typedef struct esc_gen_params {
+    int hidden;
+    const float *w_down; /* [hidden, C_a]; ignored when hidden == 0 */
+    const float *b_down; /* [hidden] or NULL                        */
+    const float *w_up;   /* [9*C_a, hidden ? hidden : C_a]          */
+    const float *b_up;   /* [9*C_a] or NULL                         */
+} esc_gen_params;
+
+/* Bytes of workspace a call with this shape needs (256-byte aligned base). 0 on bad arguments. */
+size_t esc_workspace_bytes(int N, int C_a, int H, int W);
+
+/* Prepare a freshly allocated workspace (enqueues one small fill kernel on `stream`). */
+esc_status esc_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Eq. 4 line 2 alone: GAP over the attention slice, then the estimator.
+ *   x       [N,C,H,W] storage type dt (read)      dk_out [N,C_a,3,3] fp32 (written)
+ * C_a == 0 is accepted and does nothing.
+ */
+esc_status esc_dynkernel_gen(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                             const esc_gen_params *gen, float *dk_out,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Eq. 4 lines 1-4 (without Conv_fuse).
+ *   lk     [C_a, Ks, Ks] fp32, channel c at lk + c*lk_channel_stride; a stride of
+ *          0 applies one Ks x Ks filter to every channel; otherwise >= Ks*Ks.
+ *   gen    estimator weights; when non-NULL, DK is computed from x (dk_in ignored)
+ *   dk_in  [N,C_a,3,3] fp32 DK used as given when gen is NULL; both NULL => DK = 0
+ *   out    [N,C,H,W] storage type dt (written, every element)
+ *   workspace is only used (and only checked) when gen != NULL
+ * With gen != NULL the result equals esc_dynkernel_gen followed by this call
+ * with dk_in, bit for bit.
+ */
+esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                const float *lk, int Ks, long lk_channel_stride,
+                                const esc_gen_params *gen, const float *dk_in,
+                                void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *esc_status_string(esc_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESC_CONVATTN_H */

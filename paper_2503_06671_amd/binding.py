@@ -1,0 +1,170 @@
+"""Thin ctypes binding over libesc_convattn.so (include/esc_convattn.h).
+
+Argument marshalling only: every step of the ConvAttn forward (Eq. 4 of the ESC
+paper) runs in the HIP kernels.  torch supplies device memory and streams.
+There is no CPU fallback; a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libesc_convattn.so")
+
+ESC_F32 = 0
+ESC_BF16 = 1
+
+EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_dynkernel_gen",
+           "esc_convattn_forward", "esc_status_string")
+
+
+class EscError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"esc_convattn: status {status}: {message}")
+        self.status = status
+
+
+class _GenParams(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int),
+                ("w_down", ctypes.c_void_p), ("b_down", ctypes.c_void_p),
+                ("w_up", ctypes.c_void_p), ("b_up", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load_library():
+    """Load the built library; raise (never fall back) when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -m paper_2503_06671_amd.build` "
+                "(or __graft_entry__.build()) first")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, ci, cl, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_size_t
+        lib.esc_workspace_bytes.argtypes = [ci, ci, ci, ci]
+        lib.esc_workspace_bytes.restype = sz
+        lib.esc_workspace_init.argtypes = [vp, sz, vp]
+        lib.esc_workspace_init.restype = ci
+        lib.esc_dynkernel_gen.argtypes = [vp, ci, ci, ci, ci, ci, ci, ctypes.POINTER(_GenParams), vp,
+                                          vp, sz, vp]
+        lib.esc_dynkernel_gen.restype = ci
+        lib.esc_convattn_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, cl,
+                                             ctypes.POINTER(_GenParams), vp, vp, vp, sz, vp]
+        lib.esc_convattn_forward.restype = ci
+        lib.esc_status_string.argtypes = [ci]
+        lib.esc_status_string.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().esc_status_string(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise EscError(status, status_string(status))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _dtype_of(x: torch.Tensor) -> int:
+    if x.dtype == torch.float32:
+        return ESC_F32
+    if x.dtype == torch.bfloat16:
+        return ESC_BF16
+    raise TypeError(f"x must be float32 or bfloat16, got {x.dtype}")
+
+
+def _dev_f32(t: Optional[torch.Tensor], name: str) -> Optional[torch.Tensor]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous float32 device tensor")
+    return t
+
+
+class GenParams:
+    """Device weights of the kernel estimator (Eq. 4 line 2); see esc_gen_params."""
+
+    def __init__(self, w_up: torch.Tensor, b_up: Optional[torch.Tensor] = None, hidden: int = 0,
+                 w_down: Optional[torch.Tensor] = None, b_down: Optional[torch.Tensor] = None):
+        self.tensors = (_dev_f32(w_down, "w_down"), _dev_f32(b_down, "b_down"),
+                        _dev_f32(w_up, "w_up"), _dev_f32(b_up, "b_up"))
+        self.hidden = int(hidden)
+        self.c = _GenParams(self.hidden, *[_ptr(t) for t in self.tensors])
+
+
+def workspace_bytes(N: int, Ca: int, H: int, W: int) -> int:
+    return int(load_library().esc_workspace_bytes(N, Ca, H, W))
+
+
+def workspace_init(ws: torch.Tensor, stream=None) -> None:
+    _check(load_library().esc_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def new_workspace(N: int, Ca: int, H: int, W: int, device="cuda", stream=None) -> torch.Tensor:
+    """Allocate (with torch) and prepare a workspace for this shape."""
+    nbytes = workspace_bytes(N, Ca, H, W)
+    if nbytes == 0:
+        raise ValueError("bad shape for a workspace")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    workspace_init(ws, stream)
+    return ws
+
+
+def _x_checked(x: torch.Tensor):
+    if not x.is_cuda or x.dim() != 4 or not x.is_contiguous():
+        raise TypeError("x must be a contiguous [N,C,H,W] device tensor")
+    return _dtype_of(x), tuple(int(v) for v in x.shape)
+
+
+def dynkernel_gen(x: torch.Tensor, Ca: int, gen: GenParams, workspace: torch.Tensor,
+                  dk_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """esc_dynkernel_gen: DK [N,Ca,3,3] float32 from GAP of the attention slice."""
+    dt, (N, C, H, W) = _x_checked(x)
+    if dk_out is None:
+        dk_out = torch.empty((N, Ca, 3, 3), dtype=torch.float32, device=x.device)
+    _dev_f32(dk_out, "dk_out")
+    _check(load_library().esc_dynkernel_gen(
+        _ptr(x), dt, N, C, H, W, int(Ca), ctypes.byref(gen.c), _ptr(dk_out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    return dk_out
+
+
+def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, gen: Optional[GenParams] = None,
+                     dk_in: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """esc_convattn_forward.  lk is [Ca,Ks,Ks] (one filter per channel) or [Ks,Ks] (shared)."""
+    dt, (N, C, H, W) = _x_checked(x)
+    _dev_f32(lk, "lk")
+    if lk.dim() == 2:
+        Ks, stride = int(lk.shape[0]), 0
+    else:
+        Ks, stride = int(lk.shape[1]), int(lk.shape[1] * lk.shape[2])
+    if out is None:
+        out = torch.empty_like(x)
+    if out.dtype != x.dtype or out.shape != x.shape or not out.is_contiguous():
+        raise TypeError("out must match x in dtype and shape and be contiguous")
+    _dev_f32(dk_in, "dk_in")
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (
+        _ptr(workspace), workspace.numel() * workspace.element_size())
+    _check(load_library().esc_convattn_forward(
+        _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk), Ks, stride,
+        ctypes.byref(gen.c) if gen is not None else None, _ptr(dk_in), _ptr(out),
+        ws_ptr, ws_bytes, _stream(stream)))
+    return out

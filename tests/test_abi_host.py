@@ -1,0 +1,113 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header
+declares, and rejects bad arguments before anything is launched (so these run
+without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_06671_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_UNSUP, E_WS, E_ALIAS, E_HIP = range(8)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2503_06671_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "esc_convattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(esc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = header_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    seen = {binding.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and binding.status_string(0) == "ok"
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    a = lib.esc_workspace_bytes(1, 16, 180, 320)
+    assert a > 0 and a % 256 == 0
+    assert lib.esc_workspace_bytes(64, 16, 64, 64) > lib.esc_workspace_bytes(1, 16, 64, 64)
+    assert lib.esc_workspace_bytes(1, 16, 540, 960) >= a
+    assert lib.esc_workspace_bytes(0, 16, 8, 8) == 0
+    assert lib.esc_workspace_bytes(1, -1, 8, 8) == 0
+    assert lib.esc_workspace_bytes(1, 16, 0, 8) == 0
+    assert lib.esc_workspace_bytes(1, 16, 65536, 65536) == 0
+    assert lib.esc_workspace_bytes(1, 0, 8, 8) >= 256
+
+
+def fwd(lib, x=0x10000, dt=0, N=1, C=64, H=8, W=8, Ca=16, lk=0x20000, Ks=13, stride=169, gen=None,
+        dk=None, out=0x90000, ws=0x30000 * 256, ws_bytes=1 << 20):
+    return lib.esc_convattn_forward(x, dt, N, C, H, W, Ca, lk, Ks, stride, gen, dk, out, ws, ws_bytes, None)
+
+
+def gen_struct(hidden=0, w_down=None, b_down=None, w_up=0x40000, b_up=None):
+    return ctypes.byref(binding._GenParams(hidden, w_down, b_down, w_up, b_up))
+
+
+def test_forward_rejects_bad_arguments_before_launch(lib):
+    # the device "pointers" are fake: every call below must fail in validation
+    assert fwd(lib, x=None) == E_NULL
+    assert fwd(lib, out=None) == E_NULL
+    assert fwd(lib, lk=None) == E_NULL
+    assert fwd(lib, dt=2) == E_DTYPE
+    assert fwd(lib, N=0) == E_SHAPE
+    assert fwd(lib, H=0) == E_SHAPE
+    assert fwd(lib, Ca=65) == E_SHAPE
+    assert fwd(lib, Ca=-1) == E_SHAPE
+    assert fwd(lib, Ks=0) == E_SHAPE
+    assert fwd(lib, Ks=12) == E_UNSUP
+    assert fwd(lib, Ks=33) == E_UNSUP
+    assert fwd(lib, stride=100) == E_SHAPE
+    assert fwd(lib, C=512, Ca=300) == E_UNSUP
+    assert fwd(lib, H=65536, W=65536) == E_UNSUP
+    assert fwd(lib, out=0x10000 + 4 * 64 * 64 - 4) == E_ALIAS      # last element of x
+    assert fwd(lib, out=0x10000) == E_ALIAS
+    assert fwd(lib, x=0x10002) == E_SHAPE                           # misaligned for fp32
+    assert fwd(lib, gen=gen_struct(), ws=None) == E_WS
+    assert fwd(lib, gen=gen_struct(), ws=0x30000 * 256 + 8) == E_WS
+    assert fwd(lib, gen=gen_struct(), ws_bytes=16) == E_WS
+    assert fwd(lib, gen=gen_struct(w_up=None)) == E_NULL
+    assert fwd(lib, gen=gen_struct(hidden=8, w_down=None)) == E_NULL
+    assert fwd(lib, gen=gen_struct(hidden=-1)) == E_SHAPE
+    assert fwd(lib, gen=gen_struct(hidden=1000, w_down=0x50000)) == E_UNSUP
+
+
+def test_dynkernel_gen_rejects_bad_arguments_before_launch(lib):
+    def gen(x=0x10000, dt=0, N=1, C=64, H=8, W=8, Ca=16, g=gen_struct(), dk=0x60000, ws=0x30000 * 256,
+            ws_bytes=1 << 20):
+        return lib.esc_dynkernel_gen(x, dt, N, C, H, W, Ca, g, dk, ws, ws_bytes, None)
+    assert gen(x=None) == E_NULL
+    assert gen(g=None) == E_NULL
+    assert gen(dk=None) == E_NULL
+    assert gen(dt=7) == E_DTYPE
+    assert gen(W=-3) == E_SHAPE
+    assert gen(ws=None) == E_WS
+    assert gen(ws_bytes=0) == E_WS
+    assert gen(Ca=0) == OK          # nothing to do, nothing launched
+    assert lib.esc_workspace_init(None, 1024, None) == E_WS
+    assert lib.esc_workspace_init(0x1001, 1024, None) == E_WS
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    x = torch.zeros(1, 4, 8, 8)
+    with pytest.raises(TypeError):
+        binding.convattn_forward(x, 2, torch.zeros(2, 3, 3))

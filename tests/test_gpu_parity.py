@@ -1,0 +1,204 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bars: attention slice within 1e-5 (fp32 storage) / 2e-2 (bf16 storage, fp32
+accumulate) of the oracle's unrounded float64 result, normwise and elementwise
+(see gpu_util.assert_att_close); identity channels bit-exact; DK within 1e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_06671_amd import binding, workloads as wk
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16 = wk.F32, wk.BF16
+
+
+def check_forward(wl, oracle, what=None):
+    what = what or wl.name
+    print(f"[case] {what}", flush=True)
+    ref_att, ref_dk, _ = oracle.forward_workload(wl, want_out=False)
+    out = gu.run_forward(wl)
+    gu.assert_identity_bits(out, wl, what)
+    rel = gu.assert_att_close(gu.att_as_f64(out, wl), ref_att, wl.dtype, what)
+    dk = gu.run_dk(wl)
+    gu.assert_dk_close(dk, ref_dk, what)
+    return rel
+
+
+# ------------------------------------------------------------------ small shapes, every Ks
+
+@pytest.mark.parametrize("Ks", list(range(1, 32, 2)))
+def test_every_kernel_size_ragged_multi_tile(oracle, Ks):
+    # 3 column tiles and 3 row tiles with ragged tails; x has a non-zero mean so DK is O(1)
+    wl = wk.make_random(200 + Ks, 2, 6, 70, 150, 3, Ks, dtype=F32, x_mean=0.5)
+    check_forward(wl, oracle)
+
+
+@pytest.mark.parametrize("Ks", [3, 7, 13, 17, 31])
+def test_bf16_storage_ragged_multi_tile(oracle, Ks):
+    wl = wk.make_random(300 + Ks, 2, 5, 45, 136, 4, Ks, dtype=BF16, x_mean=0.5)
+    check_forward(wl, oracle)
+
+
+@pytest.mark.parametrize("N,C,H,W,Ca,Ks,dtype", [
+    (1, 3, 2, 3, 3, 31, F32),      # image smaller than the kernel, Ca == C
+    (2, 4, 5, 5, 2, 13, F32),      # odd plane size: unaligned planes, scalar stores and copy
+    (2, 4, 5, 5, 2, 13, BF16),
+    (1, 5, 1, 1, 2, 7, F32),       # a single pixel
+    (3, 7, 9, 130, 5, 9, BF16),    # W % 4 == 2
+    (1, 2, 33, 66, 1, 5, F32),     # W % 4 == 2, two column tiles
+    (1, 4, 1, 257, 2, 3, BF16),    # one row, W odd
+    (2, 3, 129, 3, 1, 17, F32),    # tall and thin
+    (300, 2, 6, 6, 1, 3, F32),     # many small images
+])
+def test_edge_shapes(oracle, N, C, H, W, Ca, Ks, dtype):
+    wl = wk.make_random(400 + H + W, N, C, H, W, Ca, Ks, dtype=dtype, x_mean=-0.25)
+    check_forward(wl, oracle)
+
+
+def test_no_attention_channels_is_a_pure_copy(oracle):
+    wl = wk.make_random(7, 2, 5, 17, 19, 0, 13)
+    out = gu.run_forward(wl)
+    assert np.array_equal(out.view(np.uint8), wl.x.view(np.uint8))
+
+
+def test_tall_register_block_variant_ragged(oracle):
+    # enough tiles that the library picks the 4-row register block; ragged in H and W
+    wl = wk.make_random(8, 40, 17, 70, 150, 16, 13, dtype=F32, x_mean=0.5)
+    check_forward(wl, oracle)
+    wl = wk.make_random(9, 40, 17, 70, 150, 16, 7, dtype=BF16, x_mean=0.5)
+    check_forward(wl, oracle)
+
+
+@pytest.mark.parametrize("Ca,hidden,bias,dtype", [(16, 8, False, F32), (16, 4, True, BF16), (48, 24, True, F32)])
+def test_two_layer_estimator(oracle, Ca, hidden, bias, dtype):
+    # the paper's estimator: 1x1 down, GELU, 1x1 up (hidden 8 / 4 / 24 in its variants)
+    wl = wk.make_random(500 + hidden, 2, Ca + 4, 40, 72, Ca, 13, dtype=dtype, hidden=hidden, bias=bias,
+                        x_mean=0.7)
+    check_forward(wl, oracle)
+
+
+def test_shared_single_filter(oracle):
+    wl = wk.make_random(11, 2, 6, 30, 70, 4, 13)
+    one = wl.lk[2].copy()
+    print("[case] shared filter", flush=True)
+    x = gu.to_dev_x(wl.x, wl.dtype)
+    out = torch.empty_like(x)
+    binding.convattn_forward(x, 4, gu.dev(one), out=out)
+    torch.cuda.synchronize()
+    ref, _, _ = oracle.convattn_forward(wl.x, 4, one, want_out=False)
+    gu.assert_att_close(gu.att_as_f64(out.cpu().numpy(), wl), ref, F32, "shared filter")
+
+
+# ------------------------------------------------------------------ exact special cases on the GPU
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_delta_kernel_is_exact_identity(dtype):
+    wl = wk.make_random(12, 2, 5, 50, 90, 3, 13, dtype=dtype)
+    lk = np.zeros((3, 13, 13), np.float32)
+    lk[:, 6, 6] = 1.0
+    out = gu.run_forward(wl, use_gen=False, lk=lk)
+    assert np.array_equal(out.view(np.uint8), wl.x.view(np.uint8))
+    # and through the dynamic path: LK = 0, DK = centre delta
+    dk = np.zeros((2, 3, 3, 3), np.float32)
+    dk[:, :, 1, 1] = 1.0
+    out = gu.run_forward(wl, use_gen=False, lk=np.zeros_like(lk), dk_in=dk)
+    assert np.array_equal(out.view(np.uint8), wl.x.view(np.uint8))
+
+
+@pytest.mark.parametrize("dtype,Ks", [(F32, 13), (BF16, 13), (F32, 31), (F32, 5)])
+def test_ones_conv_ones_is_exact(dtype, Ks):
+    H, W, p = 40, 100, (Ks - 1) // 2
+    wl = wk.make_random(13, 1, 2, H, W, 1, Ks, dtype=dtype)
+    ones = np.ones((1, 2, H, W), np.float32)
+    wl.x = wk.f32_to_bf16_bits(ones) if dtype == BF16 else ones
+    out = gu.run_forward(wl, use_gen=False, lk=np.ones((1, Ks, Ks), np.float32))
+    cnt = lambda L, t: min(t, p) + min(L - 1 - t, p) + 1
+    want = np.array([[cnt(H, y) * cnt(W, x) for x in range(W)] for y in range(H)], float)
+    assert np.array_equal(gu.att_as_f64(out, wl)[0, 0], want)
+
+
+def test_off_centre_delta_shift():
+    wl = wk.make_random(14, 1, 2, 40, 100, 1, 7)
+    lk = np.zeros((1, 7, 7), np.float32)
+    lk[0, 1, 5] = 1.0            # out[y,x] = x[y-2, x+2]
+    out = gu.run_forward(wl, use_gen=False, lk=lk)
+    want = np.zeros((40, 100), np.float32)
+    want[2:, :-2] = wl.x[0, 0, :-2, 2:]
+    assert np.array_equal(out[0, 0], want)
+
+
+def test_generated_dk_equals_given_dk_bit_for_bit():
+    wl = wk.make_random(15, 3, 6, 50, 70, 4, 13, x_mean=0.5)
+    full = gu.run_forward(wl)
+    dk = gu.run_dk(wl)
+    two_step = gu.run_forward(wl, use_gen=False, dk_in=dk)
+    assert np.array_equal(full.view(np.uint8), two_step.view(np.uint8))
+
+
+def test_batch_equals_single_images_bit_for_bit():
+    wl = wk.make_random(16, 3, 5, 37, 80, 3, 13, dtype=BF16, x_mean=0.3)
+    full = gu.run_forward(wl)
+    dk = gu.run_dk(wl)
+    for n in range(3):
+        one = wk.make_random(16, 3, 5, 37, 80, 3, 13, dtype=BF16, x_mean=0.3)
+        one.x = np.ascontiguousarray(wl.x[n:n + 1]); one.N = 1
+        assert np.array_equal(gu.run_forward(one)[0], full[n])
+        assert np.array_equal(gu.run_dk(one)[0], dk[n])
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_planted_non_finite_values_in_identity_channels(oracle, dtype):
+    wl = wk.make_random(17, 2, 6, 20, 36, 2, 7, dtype=dtype)
+    flat = wl.x.reshape(2, 6, -1)
+    if dtype == F32:
+        u = flat.view(np.uint32)
+        u[0, 3, 0], u[0, 4, 1], u[1, 5, 2], u[1, 2, 3] = 0x7FC00001, 0xFF800000, 0x00000001, 0x7FA00000
+    else:
+        flat[0, 3, 0], flat[0, 4, 1], flat[1, 5, 2], flat[1, 2, 3] = 0x7FC1, 0xFF80, 0x0001, 0x7FA0
+    check_forward(wl, oracle, "planted non-finite")
+
+
+def test_linearity_with_dk_fixed():
+    wl = wk.make_random(18, 1, 3, 40, 70, 2, 13)
+    rng = np.random.default_rng(19)
+    x2 = rng.standard_normal(wl.x.shape).astype(np.float32)
+    dk = rng.standard_normal((1, 2, 3, 3)).astype(np.float32)
+    f = lambda x: (setattr(wl, "x", x), gu.run_forward(wl, use_gen=False, dk_in=dk))[1][:, :2].astype(np.float64)
+    x1 = wl.x.copy()
+    lhs = f((2.0 * x1 - 0.5 * x2).astype(np.float32))
+    rhs = 2.0 * f(x1) - 0.5 * f(x2)
+    assert np.abs(lhs - rhs).max() <= 2e-5 * np.abs(rhs).max()
+
+
+# ------------------------------------------------------------------ the five benchmark workloads
+
+def visible_dk_variants(wl):
+    """Same workload with LK = 0, and with x shifted by 0.5 so DK is O(1)."""
+    a = wk.make_config(int(wl.name[3]), wl.Ks if wl.name.startswith("cfg4") else None)
+    a.lk = np.zeros_like(a.lk); a.name += "_lk0"
+    b = wk.make_config(int(wl.name[3]), wl.Ks if wl.name.startswith("cfg4") else None)
+    xf = b.x_as_f32() + np.float32(0.5)
+    b.x = wk.f32_to_bf16_bits(xf) if b.dtype == BF16 else xf
+    b.name += "_shift"
+    return a, b
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3])
+def test_benchmark_workloads_full_size(oracle, idx):
+    wl = wk.make_config(idx)
+    check_forward(wl, oracle)
+    for v in visible_dk_variants(wl):
+        check_forward(v, oracle)
+
+
+@pytest.mark.parametrize("Ks", wk.CFG4_KS)
+def test_benchmark_workload_4_full_size(oracle, Ks):
+    wl = wk.make_config(4, Ks)
+    check_forward(wl, oracle)
+    if Ks == 13:
+        for v in visible_dk_variants(wl):
+            check_forward(v, oracle)
