@@ -93,8 +93,7 @@ def main():
     stream = torch.cuda.Stream()
 
     def step(i):
-        binding.convattn_forward(xs[i % pairs], wl.Ca, lk, gen=gen, out=outs[i % pairs], workspace=ws,
-                                 stream=stream)
+        binding.convattn_forward(xs[i % pairs], wl.Ca, lk, ws, gen=gen, out=outs[i % pairs], stream=stream)
 
     with torch.cuda.stream(stream):
         for i in range(args.warmup):

@@ -24,11 +24,16 @@
  *     in both storage modes.
  *   - All arguments are validated on the host before the first launch; a call
  *     that returns an error has enqueued nothing.
- *   - The workspace must have been prepared once with esc_workspace_init on a
- *     stream ordered before its first use.  A completed call leaves it ready
- *     for the next call; two calls that share a workspace must be ordered (same
- *     stream, or synchronised).  esc_workspace_bytes gives the size for a shape;
- *     a workspace sized for a larger (N, C_a, H, W) in every argument also fits.
+ *   - Every compute call needs a workspace (work queue and the mailboxes blocks
+ *     use to hand over the GAP sums and DK).  It must have been prepared once with
+ *     esc_workspace_init on a stream ordered before its first use; calls leave it
+ *     ready for the next call, whatever its shape.  Two calls that share a
+ *     workspace must be ordered (same stream, or synchronised).
+ *     esc_workspace_bytes gives the size for a shape; it never shrinks when N,
+ *     C_a or H*W grow, so a workspace sized for the largest shape fits all.
+ *   - The forward is one persistent kernel whose blocks wait for one another
+ *     (bounded).  Should a wait ever expire, the result is undefined and the
+ *     workspace's error word is raised; esc_workspace_errors reads it.
  *   - Limits: 0 <= C_a <= min(C, 256); estimator hidden width <= 256; Ks odd,
  *     1 <= Ks <= 31; H*W < 2^31; N, C, H, W >= 1.  No lower bound on H or W
  *     relative to Ks.
@@ -77,6 +82,14 @@ size_t esc_workspace_bytes(int N, int C_a, int H, int W);
 esc_status esc_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Diagnostic, not part of the hot path: copies the workspace's error word to
+ * *errors_out (HOST pointer) and SYNCHRONISES `stream` to do so.  0 = no wait has
+ * expired in any call since esc_workspace_init.
+ */
+esc_status esc_workspace_errors(const void *workspace, size_t workspace_bytes, void *stream,
+                                unsigned *errors_out);
+
+/*
  * Eq. 4 line 2 alone: GAP over the attention slice, then the estimator.
  *   x       [N,C,H,W] storage type dt (read)      dk_out [N,C_a,3,3] fp32 (written)
  * C_a == 0 is accepted and does nothing.
@@ -92,7 +105,6 @@ esc_status esc_dynkernel_gen(const void *x, esc_dtype dt, int N, int C, int H, i
  *   gen    estimator weights; when non-NULL, DK is computed from x (dk_in ignored)
  *   dk_in  [N,C_a,3,3] fp32 DK used as given when gen is NULL; both NULL => DK = 0
  *   out    [N,C,H,W] storage type dt (written, every element)
- *   workspace is only used (and only checked) when gen != NULL
  * With gen != NULL the result equals esc_dynkernel_gen followed by this call
  * with dk_in, bit for bit.
  */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libesc_convattn.so")
 ESC_F32 = 0
 ESC_BF16 = 1
 
-EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_dynkernel_gen",
+EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_workspace_errors", "esc_dynkernel_gen",
            "esc_convattn_forward", "esc_status_string")
 
 
@@ -51,6 +51,8 @@ def load_library():
         lib.esc_workspace_bytes.restype = sz
         lib.esc_workspace_init.argtypes = [vp, sz, vp]
         lib.esc_workspace_init.restype = ci
+        lib.esc_workspace_errors.argtypes = [vp, sz, vp, ctypes.POINTER(ctypes.c_uint)]
+        lib.esc_workspace_errors.restype = ci
         lib.esc_dynkernel_gen.argtypes = [vp, ci, ci, ci, ci, ci, ci, ctypes.POINTER(_GenParams), vp,
                                           vp, sz, vp]
         lib.esc_dynkernel_gen.restype = ci
@@ -117,6 +119,14 @@ def workspace_init(ws: torch.Tensor, stream=None) -> None:
     _check(load_library().esc_workspace_init(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
+def workspace_errors(ws: torch.Tensor, stream=None) -> int:
+    """Diagnostic: synchronises the stream and returns the workspace's error word."""
+    v = ctypes.c_uint(0)
+    _check(load_library().esc_workspace_errors(_ptr(ws), ws.numel() * ws.element_size(), _stream(stream),
+                                               ctypes.byref(v)))
+    return int(v.value)
+
+
 def new_workspace(N: int, Ca: int, H: int, W: int, device="cuda", stream=None) -> torch.Tensor:
     """Allocate (with torch) and prepare a workspace for this shape."""
     nbytes = workspace_bytes(N, Ca, H, W)
@@ -146,9 +156,9 @@ def dynkernel_gen(x: torch.Tensor, Ca: int, gen: GenParams, workspace: torch.Ten
     return dk_out
 
 
-def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, gen: Optional[GenParams] = None,
-                     dk_in: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, workspace: torch.Tensor,
+                     gen: Optional[GenParams] = None, dk_in: Optional[torch.Tensor] = None,
+                     out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """esc_convattn_forward.  lk is [Ca,Ks,Ks] (one filter per channel) or [Ks,Ks] (shared)."""
     dt, (N, C, H, W) = _x_checked(x)
     _dev_f32(lk, "lk")
@@ -161,8 +171,7 @@ def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, gen: Optional[G
     if out.dtype != x.dtype or out.shape != x.shape or not out.is_contiguous():
         raise TypeError("out must match x in dtype and shape and be contiguous")
     _dev_f32(dk_in, "dk_in")
-    ws_ptr, ws_bytes = (None, 0) if workspace is None else (
-        _ptr(workspace), workspace.numel() * workspace.element_size())
+    ws_ptr, ws_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
     _check(load_library().esc_convattn_forward(
         _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk), Ks, stride,
         ctypes.byref(gen.c) if gen is not None else None, _ptr(dk_in), _ptr(out),

@@ -36,7 +36,8 @@ def run_forward(wl, use_gen=True, dk_in=None, lk=None):
     gen = gen_params(wl) if use_gen else None
     dk_d = dev(dk_in) if dk_in is not None else None
     out = torch.full_like(x, float("nan"))
-    binding.convattn_forward(x, wl.Ca, lk_d, gen=gen, dk_in=dk_d, out=out, workspace=ws)
+    binding.convattn_forward(x, wl.Ca, lk_d, ws, gen=gen, dk_in=dk_d, out=out)
+    assert binding.workspace_errors(ws) == 0
     torch.cuda.synchronize()
     return out_to_np(out, wl.dtype)
 

@@ -81,6 +81,7 @@ def test_forward_rejects_bad_arguments_before_launch(lib):
     assert fwd(lib, out=0x10000 + 4 * 64 * 64 - 4) == E_ALIAS      # last element of x
     assert fwd(lib, out=0x10000) == E_ALIAS
     assert fwd(lib, x=0x10002) == E_SHAPE                           # misaligned for fp32
+    assert fwd(lib, ws=None) == E_WS
     assert fwd(lib, gen=gen_struct(), ws=None) == E_WS
     assert fwd(lib, gen=gen_struct(), ws=0x30000 * 256 + 8) == E_WS
     assert fwd(lib, gen=gen_struct(), ws_bytes=16) == E_WS
@@ -110,4 +111,4 @@ def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(1, 4, 8, 8)
     with pytest.raises(TypeError):
-        binding.convattn_forward(x, 2, torch.zeros(2, 3, 3))
+        binding.convattn_forward(x, 2, torch.zeros(2, 3, 3), torch.zeros(1024, dtype=torch.uint8))

@@ -87,7 +87,7 @@ def test_shared_single_filter(oracle):
     print("[case] shared filter", flush=True)
     x = gu.to_dev_x(wl.x, wl.dtype)
     out = torch.empty_like(x)
-    binding.convattn_forward(x, 4, gu.dev(one), out=out)
+    binding.convattn_forward(x, 4, gu.dev(one), binding.new_workspace(2, 4, 30, 70), out=out)
     torch.cuda.synchronize()
     ref, _, _ = oracle.convattn_forward(wl.x, 4, one, want_out=False)
     gu.assert_att_close(gu.att_as_f64(out.cpu().numpy(), wl), ref, F32, "shared filter")
