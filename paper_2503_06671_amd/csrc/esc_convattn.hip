@@ -10,28 +10,45 @@
 // from a queue in this order:
 //
 //   pool items   GAP partial sums of the attention slice, one 4096-element slab each
-//   gen items    one per image: finish the GAP, run the kernel estimator, publish DK
+//   gen items    one per image, only when an image has many slabs: finish the GAP,
+//                run the kernel estimator, publish DK
 //   conv items   one 64 x (16*RY) output tile of one (image, channel) plane: LK taps
-//                from an LDS halo tile, then DK's nine taps once DK is published
-//   copy items   16 KiB of the identity channels (interleaved with the conv items so
-//                streaming and arithmetic overlap on every compute unit)
+//                from an LDS halo tile with the channel's weights staged in LDS, then
+//                DK's nine taps once DK is known
+//   copy items   16 KiB of the identity channels, interleaved with the conv items so
+//                streaming and arithmetic overlap on every compute unit
 //
-// A block's first item is its block index; further items come from an atomic
-// counter.  An item only ever waits for items with smaller indices (conv -> gen ->
-// pool), and pool items wait for nothing, so every wait ends as long as the blocks
-// of the grid are co-resident (the host sizes the grid to the occupancy limit) -
-// and each wait is bounded anyway: on expiry the block raises the error word of the
-// workspace and goes on.
+// Block b takes items b, b + grid, b + 2*grid, ...  An item only ever waits for
+// items with smaller indices (conv -> gen -> pool), pool items wait for nothing and
+// come first in every block's list, so every wait ends as long as the blocks of the
+// grid are co-resident (the host sizes the grid to what the kernel is compiled to
+// fit) - and each wait is bounded anyway: on expiry the block raises the error word
+// of the workspace and goes on.  The grid size is kept coprime with the length of
+// the conv/copy pattern so that every block meets both kinds of item.
 //
 // Blocks talk through 64-bit mailboxes {fp32 value, 32-bit call tag} written and
 // read with relaxed device-scope atomics.  A mailbox is valid when its tag equals
 // the tag of this call, so nothing has to be cleared between calls and no fence
-// (and no cache write-back) is needed: each datum validates itself.
+// (and no cache write-back) is needed: each datum validates itself.  The tag is a
+// call counter kept in the workspace, one copy per group of blocks (block index
+// modulo 64): a block reads its group's copy, and the last block of a group to
+// announce that it is leaving advances that copy.  Every copy advances exactly once
+// per call, so all agree at every launch, no address is hot, and a captured launch
+// can be replayed any number of times.
+//
+// Three facts about the machine shape the code (measured, not assumed):
+//   - an FMA whose multiplier sits in a scalar register issues at half the rate of
+//     one with both operands in vector registers, so the tap weights are read from
+//     LDS (a broadcast read) into vector registers;
+//   - vector-memory results return in order, so an atomic with a slow answer delays
+//     every later load of its wavefront: the leave announcement is issued after an
+//     item's loads, by a wavefront that polls no mailbox afterwards;
+//   - a thousand atomics on one address take tens of microseconds: nothing here
+//     has more than a handful of blocks on the same word.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
-
-#include <atomic>
 
 #include "esc_convattn.h"
 
@@ -44,15 +61,33 @@ constexpr int kMaxCa = 256;
 constexpr int kMaxHidden = 256;
 constexpr int kMaxKs = 31;
 constexpr size_t kWsAlign = 256;
-constexpr unsigned kSpinLimit = 1u << 20;  // bounded wait: seconds, far beyond any real wait
+constexpr unsigned kSpinLimit = 1u << 20;  // bounded wait: about a second, far beyond any real wait
+constexpr int kBlocksPerCu = 4;    // resident blocks per compute unit the kernel is compiled for (<= 128 VGPRs)
 constexpr int kCopyVecPerThread = 4;
 constexpr size_t kCopyChunk = (size_t)kThreads * 16 * kCopyVecPerThread;  // bytes per copy item
+constexpr int kStage = 1024;       // pool mailboxes staged in LDS per round (multiple of 64)
+constexpr int kPollThreads = 192;  // wavefronts 0-2 poll mailboxes; wavefront 3 carries the leave atomic
+constexpr int kStagePerThread = (kStage + kPollThreads - 1) / kPollThreads;
+constexpr int kGroups = 64;        // block groups with their own call counter and leave counter
+constexpr int kCtlStride = 16;     // 32-bit words between two groups' counters (one 64-byte line each)
 
 struct bf16_t {
     uint16_t bits;
 };
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
+
+// Optional per-item timeline (development builds only, -DESC_TRACE): 16 words per item.
+#ifdef ESC_TRACE
+#define ESC_STAMP(rec, k)                                                    \
+    do {                                                                     \
+        if ((rec) != nullptr && threadIdx.x == 0) (rec)[k] = wall_clock64(); \
+    } while (0)
+#else
+#define ESC_STAMP(rec, k) \
+    do {                  \
+    } while (0)
+#endif
 
 // ---------------------------------------------------------------------------
 // storage helpers
@@ -84,6 +119,33 @@ __device__ __forceinline__ void store4(bf16_t *p, const float *v)
     *reinterpret_cast<uint2 *>(p) = w;
 }
 
+// four consecutive elements from an address aligned to all four
+__device__ __forceinline__ void load4(const float *p, float *v)
+{
+    const float4 f = *reinterpret_cast<const float4 *>(p);
+    v[0] = f.x;
+    v[1] = f.y;
+    v[2] = f.z;
+    v[3] = f.w;
+}
+__device__ __forceinline__ void load4(const bf16_t *p, float *v)
+{
+    const uint2 w = *reinterpret_cast<const uint2 *>(p);
+    v[0] = __uint_as_float(w.x << 16);
+    v[1] = __uint_as_float(w.x & 0xffff0000u);
+    v[2] = __uint_as_float(w.y << 16);
+    v[3] = __uint_as_float(w.y & 0xffff0000u);
+}
+
+// x / d for x < 2^31 by multiply-high and shift (host fills mul and shift)
+struct FastDiv {
+    uint32_t d, mul, shift;
+};
+__device__ __forceinline__ uint32_t fdiv(uint32_t x, const FastDiv &f)
+{
+    return (__umulhi(x, f.mul) + x) >> f.shift;
+}
+
 // ---------------------------------------------------------------------------
 // mailboxes
 // ---------------------------------------------------------------------------
@@ -99,10 +161,43 @@ __device__ __forceinline__ float box_get(const u64 *box, uint32_t tag, unsigned 
     for (unsigned spin = 0; spin < kSpinLimit; ++spin) {
         const u64 v = __hip_atomic_load(box, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((uint32_t)(v >> 32) == tag) return __uint_as_float((uint32_t)v);
-        __builtin_amdgcn_s_sleep(4);
+        __builtin_amdgcn_s_sleep(2);
     }
     __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return 0.f;
+}
+
+// Whole block: waits for cnt (<= kStage) consecutive mailboxes and copies their values to
+// dst[0..cnt).  A thread's polls are issued together so their round trips overlap.
+__device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *dst, uint32_t tag, unsigned *err)
+{
+    bool pend[kStagePerThread];
+#pragma unroll
+    for (int u = 0; u < kStagePerThread; ++u)
+        pend[u] = threadIdx.x < kPollThreads && (int)threadIdx.x + u * kPollThreads < cnt;
+    bool any = false;
+    for (unsigned spin = 0; spin < kSpinLimit; ++spin) {
+        u64 v[kStagePerThread];
+#pragma unroll
+        for (int u = 0; u < kStagePerThread; ++u)
+            if (pend[u])
+                v[u] = __hip_atomic_load(boxes + threadIdx.x + u * kPollThreads, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+        any = false;
+#pragma unroll
+        for (int u = 0; u < kStagePerThread; ++u)
+            if (pend[u]) {
+                if ((uint32_t)(v[u] >> 32) == tag) {
+                    dst[threadIdx.x + u * kPollThreads] = __uint_as_float((uint32_t)v[u]);
+                    pend[u] = false;
+                } else {
+                    any = true;
+                }
+            }
+        if (!any) break;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    if (any) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __device__ __forceinline__ float wave_sum(float v)
@@ -115,6 +210,14 @@ __device__ __forceinline__ float wave_sum(float v)
 // ---------------------------------------------------------------------------
 // kernel arguments
 // ---------------------------------------------------------------------------
+enum : int {
+    kDkNone = 0,    // DK = 0
+    kDkGiven = 1,   // caller's dk_in
+    kDkBoxes = 2,   // published by a gen item
+    kDkDirect = 3   // each conv item finishes the GAP and runs its nine estimator outputs itself
+};
+constexpr int kDirectMaxBoxes = 512;  // direct mode while C_a * nslab mailboxes stay this few
+
 struct FwdParams {
     const void *x;
     void *out;
@@ -124,21 +227,62 @@ struct FwdParams {
     float *dk_out;       // esc_dynkernel_gen: where the estimator's DK goes, else NULL
     const float *w_down, *b_down, *w_up, *b_up;
     int hidden;
-    int has_gen;         // pool + gen items exist; conv items wait for the DK mailboxes
+    int dk_mode;         // where conv items take DK from (kDk*)
     int N, C, Ca, H, W;
     int nslab;           // pool slabs per (image, channel) plane
     float hw;            // H*W as a float, the GAP divisor
-    int tiles_x, tiles_y;
     unsigned n_pool, n_gen, n_conv, n_copy;  // item counts
-    unsigned copy_chunks;                    // copy items per image
+    // conv and copy items alternate in groups of mix_a conv + mix_b copy items while both
+    // last (mix_groups groups); the rest of the conv items follow, then the rest of the copy items
+    unsigned mix_a, mix_b, mix_groups;
+    FastDiv div_nslab, div_ca, div_tiles_x, div_tiles_y, div_chunks, div_mix;
     size_t img_bytes, idt_off, idt_len;      // pass-through range of one image, in bytes
-    int conv_vec_ok, copy_vec_ok, pool_vec_ok, elem_bytes;
+    int conv_vec_ok, conv_ld_vec, copy_vec_ok, pool_vec_ok, elem_bytes;
     u64 *pool_box;       // [N*Ca*nslab] partial sums
     u64 *dk_box;         // [N*Ca*9]
-    u64 *queue;          // work counter {tag, next item}
-    unsigned *err;
-    uint32_t tag;
+    unsigned *err;       // raised when a bounded wait expires
+    unsigned *epoch;     // [kGroups] call counters (kCtlStride words apart) = tag of the current call
+    unsigned *done;      // [kGroups] blocks of the group that have announced their leave
+    u64 *trace;          // development builds only
 };
+
+// Per-block state that item code touches.
+struct Ctx {
+    uint32_t tag;     // call tag, read lazily
+    bool have_tag;
+    bool last_item;   // the item being processed is the block's last
+    bool announced;   // leave already announced
+    unsigned left;    // thread kThreads-1 only: blocks of the group that had announced before this one
+};
+
+// Reads the call tag once per block, at a point where the caller's own loads are already
+// in flight (it must not sit in front of them: results return in order).  A plain cached
+// load: the value was written by the previous launch and only changes once this block's
+// whole group has announced its leave.
+__device__ __forceinline__ void need_tag(const FwdParams &p, Ctx &ctx)
+{
+    if (!ctx.have_tag) {
+        ctx.tag = *(const volatile unsigned *)(p.epoch + (blockIdx.x % kGroups) * kCtlStride);
+        ctx.have_tag = true;
+    }
+}
+
+// Called once the loads of the block's last item are in flight: announce the leave, so the
+// atomic's round trip is over long before the block ends.
+__device__ __forceinline__ void announce_leave(const FwdParams &p, Ctx &ctx)
+{
+    if (ctx.last_item && !ctx.announced) {
+        need_tag(p, ctx);
+        // Every wavefront's copy of the tag must have arrived before the announcement can be
+        // seen: once the whole group has announced, the group's counter advances.
+        asm volatile("" ::"v"(ctx.tag) : "memory");
+        __syncthreads();
+        if (threadIdx.x == kThreads - 1)
+            ctx.left = __hip_atomic_fetch_add(p.done + (blockIdx.x % kGroups) * kCtlStride, 1u,
+                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ctx.announced = true;
+    }
+}
 
 // ---------------------------------------------------------------------------
 // pool item (Eq. 4 line 2, first half).  Thread t adds elements
@@ -147,14 +291,15 @@ struct FwdParams {
 // decomposition depends on H*W only, so a batch reproduces its images run alone.
 // ---------------------------------------------------------------------------
 template <typename T>
-__device__ __forceinline__ void pool_item(const FwdParams &p, unsigned item, float *s_red)
+__device__ __forceinline__ void pool_item(const FwdParams &p, Ctx &ctx, unsigned item, float *s_red)
 {
     constexpr int V = 16 / (int)sizeof(T);  // elements per 16-byte load
     constexpr int K = kPoolSlab / (kThreads * V);
     const int HW = p.H * p.W;
-    const unsigned nc = item / (unsigned)p.nslab;
+    const unsigned nc = fdiv(item, p.div_nslab);
     const int slab = (int)(item - nc * (unsigned)p.nslab);
-    const int n = (int)(nc / (unsigned)p.Ca), c = (int)(nc % (unsigned)p.Ca);
+    const unsigned n = fdiv(nc, p.div_ca);
+    const unsigned c = nc - n * (unsigned)p.Ca;
     const T *plane = (const T *)p.x + ((size_t)n * p.C + c) * (size_t)HW;
     const int base = slab * kPoolSlab;
     float s = 0.f;
@@ -163,6 +308,8 @@ __device__ __forceinline__ void pool_item(const FwdParams &p, unsigned item, flo
 #pragma unroll
         for (int k = 0; k < K; ++k)
             raw[k] = *reinterpret_cast<const u32x4 *>(plane + base + (k * kThreads + (int)threadIdx.x) * V);
+        need_tag(p, ctx);
+        announce_leave(p, ctx);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             if (sizeof(T) == 4) {
@@ -184,6 +331,8 @@ __device__ __forceinline__ void pool_item(const FwdParams &p, unsigned item, flo
                 const int idx = base + (k * kThreads + (int)threadIdx.x) * V + q;
                 if (idx < HW) s += to_f32(plane[idx]);
             }
+        need_tag(p, ctx);
+        announce_leave(p, ctx);
     }
     s = wave_sum(s);
     if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = s;
@@ -192,58 +341,118 @@ __device__ __forceinline__ void pool_item(const FwdParams &p, unsigned item, flo
         float t = s_red[0];
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) t += s_red[w];
-        box_put(p.pool_box + item, t, p.tag);
+        box_put(p.pool_box + item, t, ctx.tag);
     }
 }
 
 // ---------------------------------------------------------------------------
-// gen item (Eq. 4 line 2, second half): image n.  Wavefront w finishes the GAP
-// of channels w, w+4, ...: lane l adds slabs l, l+64, ... in order, then the
-// wavefront tree.  Then the estimator, one output per thread.
+// The kernel estimator (Eq. 4 line 2, second half) of image n.  The GAP of a
+// channel is finished in one fixed order everywhere: lane l of a wavefront adds
+// slabs l, l+64, ... ascending, then the wavefront tree adds the lanes.  Then the
+// estimator, one output per thread.  A gen item publishes all 9*C_a outputs; when
+// an image has few slabs the conv items skip that hop and derive their own nine
+// values with the same arithmetic.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float gelu_erf(float v)
 {
     return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
 }
 
-__device__ __forceinline__ void gen_item(const FwdParams &p, unsigned n, float *s_g, float *s_t)
+// bias + sum_k w[k] * in[k], accumulated in ascending k.  Weights are fetched eight at
+// a time so their latencies overlap instead of adding up.
+__device__ __forceinline__ float dot_row(const float *w, const float *in, int K, float bias)
+{
+    float s = bias;
+    for (int k0 = 0; k0 < K; k0 += 8) {
+        float wv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) wv[u] = k0 + u < K ? w[k0 + u] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k0 + u < K) s = fmaf(wv[u], in[k0 + u], s);
+    }
+    return s;
+}
+
+// Whole block: waits for image n's pool mailboxes (staged through s_part), leaves the
+// pooled means in s_g and (two-layer estimator) the hidden activations in s_t.  Ends
+// with a barrier.
+__device__ __forceinline__ void estimator_front(const FwdParams &p, uint32_t tag, unsigned n, float *s_part,
+                                                float *s_g, float *s_t)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int c = wave; c < p.Ca; c += kThreads / 64) {
-        const u64 *boxes = p.pool_box + ((size_t)n * p.Ca + c) * p.nslab;
-        float s = 0.f;
-        for (int k = lane; k < p.nslab; k += 64) s += box_get(boxes + k, p.tag, p.err);
-        s = wave_sum(s);
-        if (lane == 0) s_g[c] = s / p.hw;
-    }
-    __syncthreads();
-    const float *in = s_g;
-    int K = p.Ca;
-    if (p.hidden > 0) {
-        for (int m = threadIdx.x; m < p.hidden; m += kThreads) {
-            float s = p.b_down ? p.b_down[m] : 0.f;
-            for (int k = 0; k < p.Ca; ++k) s = fmaf(p.w_down[(size_t)m * p.Ca + k], s_g[k], s);
-            s_t[m] = gelu_erf(s);
+    const int nslab = p.nslab, Ca = p.Ca;
+    const u64 *img_boxes = p.pool_box + (size_t)n * Ca * nslab;
+    if (nslab <= kStage) {
+        const int G = kStage / nslab;  // whole channels per round
+        for (int c0 = 0; c0 < Ca; c0 += G) {
+            const int gc = Ca - c0 < G ? Ca - c0 : G;
+            boxes_to_lds(img_boxes + (size_t)c0 * nslab, gc * nslab, s_part, tag, p.err);
+            __syncthreads();
+            for (int cg = wave; cg < gc; cg += kThreads / 64) {
+                float s = 0.f;
+                for (int k = lane; k < nslab; k += 64) s += s_part[cg * nslab + k];
+                s = wave_sum(s);
+                if (lane == 0) s_g[c0 + cg] = s / p.hw;
+            }
+            __syncthreads();
+        }
+    } else {
+        // a channel has more slabs than fit: kStage at a time; kStage % 64 == 0 keeps every
+        // slab on the lane its index selects
+        for (int c = 0; c < Ca; ++c) {
+            float s = 0.f;
+            for (int k0 = 0; k0 < nslab; k0 += kStage) {
+                const int cnt = nslab - k0 < kStage ? nslab - k0 : kStage;
+                boxes_to_lds(img_boxes + (size_t)c * nslab + k0, cnt, s_part, tag, p.err);
+                __syncthreads();
+                if (wave == 0)
+                    for (int k = lane; k < cnt; k += 64) s += s_part[k];
+                __syncthreads();
+            }
+            if (wave == 0) {
+                s = wave_sum(s);
+                if (lane == 0) s_g[c] = s / p.hw;
+            }
         }
         __syncthreads();
-        in = s_t;
-        K = p.hidden;
     }
+    if (p.hidden > 0) {
+        for (int m = threadIdx.x; m < p.hidden; m += kThreads)
+            s_t[m] = gelu_erf(dot_row(p.w_down + (size_t)m * Ca, s_g, Ca, p.b_down ? p.b_down[m] : 0.f));
+        __syncthreads();
+    }
+}
+
+// One thread: estimator output o (= DK entry c*9 + i*3 + j) from what estimator_front left.
+__device__ __forceinline__ float estimator_out(const FwdParams &p, int o, const float *s_g, const float *s_t)
+{
+    const float *in = p.hidden > 0 ? s_t : s_g;
+    const int K = p.hidden > 0 ? p.hidden : p.Ca;
+    return dot_row(p.w_up + (size_t)o * K, in, K, p.b_up ? p.b_up[o] : 0.f);
+}
+
+__device__ __forceinline__ void gen_item(const FwdParams &p, Ctx &ctx, unsigned n, float *s_part, float *s_g,
+                                         float *s_t, u64 *rec)
+{
+    need_tag(p, ctx);
+    announce_leave(p, ctx);
+    estimator_front(p, ctx.tag, n, s_part, s_g, s_t);
+    ESC_STAMP(rec, 3);
     for (int o = threadIdx.x; o < 9 * p.Ca; o += kThreads) {
-        float s = p.b_up ? p.b_up[o] : 0.f;
-        for (int k = 0; k < K; ++k) s = fmaf(p.w_up[(size_t)o * K + k], in[k], s);
+        const float s = estimator_out(p, o, s_g, s_t);
         const size_t idx = (size_t)n * 9 * p.Ca + o;
-        box_put(p.dk_box + idx, s, p.tag);
+        box_put(p.dk_box + idx, s, ctx.tag);
         if (p.dk_out) p.dk_out[idx] = s;
     }
 }
 
 // ---------------------------------------------------------------------------
-// conv item (Eq. 4 line 3).  The zero-extended halo tile sits in LDS as fp32;
-// thread (tx, ty) produces outputs x = 4*tx..4*tx+3 of rows ty*RY..ty*RY+RY-1.
-// Each LDS row segment it loads (KS+3 values, 16-byte reads) feeds up to RY kernel
-// rows, and the kernel weights are wave-uniform, so the tap loop is FMA with a
-// scalar-register multiplier.  DK's nine taps run afterwards from the same tile,
+// conv item (Eq. 4 line 3).  The zero-extended halo tile sits in LDS as fp32, and
+// so do the channel's Ks x Ks weights.  Thread (tx, ty) produces outputs
+// x = 4*tx..4*tx+3 of rows ty*RY..ty*RY+RY-1.  Each tile row segment it loads
+// (KS+3 values, 16-byte reads) feeds up to RY kernel rows; a kernel row comes in
+// with broadcast 16-byte reads.  DK's nine taps run afterwards from the same tile,
 // which is the only part that has to wait for the estimator.
 // ---------------------------------------------------------------------------
 template <int KS, int RY>
@@ -256,42 +465,100 @@ struct ConvGeom {
     static constexpr int HC = kTileW + 2 * PH;
     static constexpr int PITCH = (HC + 3) & ~3;
     static constexpr int NV = (KS + 3 + 3) & ~3;  // values a thread reads per tile row
-    static constexpr int LDS_FLOATS = HR * PITCH;
+    static constexpr int WP = (KS + 3) & ~3;      // pitch of a weight row in LDS
+    static constexpr int TILE_FLOATS = HR * PITCH;
+    static constexpr int W_FLOATS = KS * WP;
 };
 
 template <int KS, int RY, typename T>
-__device__ __forceinline__ void conv_item(const FwdParams &p, unsigned item, float *tile, float *s_dk)
+__device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned item, float *tile, float *wl,
+                                          float *s_dk, float *s_part, float *s_g, float *s_t, u64 *rec)
 {
     using G = ConvGeom<KS, RY>;
     constexpr int PH = G::PH, OFF = G::OFF, TH = G::TH, HR = G::HR, HC = G::HC, PITCH = G::PITCH,
-                  NV = G::NV;
-    constexpr bool kUnrollRows = (KS <= 13);
+                  NV = G::NV, WP = G::WP;
     const int H = p.H, W = p.W;
 
-    unsigned b = item;
-    const int txi = (int)(b % (unsigned)p.tiles_x);
-    b /= (unsigned)p.tiles_x;
-    const int tyi = (int)(b % (unsigned)p.tiles_y);
-    const unsigned nc = b / (unsigned)p.tiles_y;
-    const int n = (int)(nc / (unsigned)p.Ca), c = (int)(nc % (unsigned)p.Ca);
+    const unsigned b1 = fdiv(item, p.div_tiles_x);
+    const int txi = (int)(item - b1 * p.div_tiles_x.d);
+    const unsigned nc = fdiv(b1, p.div_tiles_y);
+    const int tyi = (int)(b1 - nc * p.div_tiles_y.d);
+    const unsigned n = fdiv(nc, p.div_ca);
+    const int c = (int)(nc - n * (unsigned)p.Ca);
     const size_t plane_off = ((size_t)n * p.C + c) * (size_t)H * (size_t)W;
     const T *xp = (const T *)p.x + plane_off;
     T *op = (T *)p.out + plane_off;
     const int x0 = txi * kTileW, y0 = tyi * TH;
 
+    // this channel's weights, fetched together with the tile
+    constexpr int KW = (KS * KS + kThreads - 1) / kThreads;
+    const float *lkc = p.lk + (size_t)c * p.lk_cstride;
+    float wreg[KW];
+#pragma unroll
+    for (int m = 0; m < KW; ++m) {
+        const int idx = m * kThreads + (int)threadIdx.x;
+        wreg[m] = idx < KS * KS ? lkc[idx] : 0.f;
+    }
+
     // halo tile -> LDS, zero outside the image
-    for (int idx = threadIdx.x; idx < HR * HC; idx += kThreads) {
-        const int r = idx / HC, cc = idx - r * HC;
-        const int gy = y0 - PH + r, gx = x0 - PH + cc;
-        float v = 0.f;
-        if (gy >= 0 && gy < H && gx >= 0 && gx < W) v = to_f32(xp[(size_t)gy * W + gx]);
-        tile[r * PITCH + cc] = v;
+    if (p.conv_ld_vec) {
+        // W % 4 == 0 and an aligned base: fetch whole 4-element chunks aligned in global
+        // memory (each lies entirely inside or outside the image), all loads in flight
+        // before the first LDS write.  A chunk lands at LDS column 4j - A.
+        constexpr int A = (4 - PH % 4) % 4;
+        constexpr int NCH = (HC + A + 3) / 4;
+        constexpr int TOT = HR * NCH;
+        constexpr int K = (TOT + kThreads - 1) / kThreads;
+        const int g0 = x0 - PH - A;
+        float v[K][4];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int q = k * kThreads + (int)threadIdx.x;
+            const int r = q / NCH, j = q - r * NCH;
+            const int gy = y0 - PH + r, gx = g0 + 4 * j;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[k][e] = 0.f;
+            if (q < TOT && gy >= 0 && gy < H && gx >= 0 && gx < W) load4(xp + (size_t)gy * W + gx, v[k]);
+        }
+        if (p.dk_mode >= kDkBoxes) need_tag(p, ctx);
+        announce_leave(p, ctx);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int q = k * kThreads + (int)threadIdx.x;
+            const int r = q / NCH, j = q - r * NCH;
+            if (q < TOT) {
+                float *dst = tile + r * PITCH + 4 * j - A;
+                if (A == 0) {
+                    *reinterpret_cast<float4 *>(dst) = make_float4(v[k][0], v[k][1], v[k][2], v[k][3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int cc = 4 * j - A + e;
+                        if (cc >= 0 && cc < HC) dst[e] = v[k][e];
+                    }
+                }
+            }
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < HR * HC; idx += kThreads) {
+            const int r = idx / HC, cc = idx - r * HC;
+            const int gy = y0 - PH + r, gx = x0 - PH + cc;
+            float v = 0.f;
+            if (gy >= 0 && gy < H && gx >= 0 && gx < W) v = to_f32(xp[(size_t)gy * W + gx]);
+            tile[r * PITCH + cc] = v;
+        }
+        if (p.dk_mode >= kDkBoxes) need_tag(p, ctx);
+        announce_leave(p, ctx);
+    }
+#pragma unroll
+    for (int m = 0; m < KW; ++m) {
+        const int idx = m * kThreads + (int)threadIdx.x;
+        if (idx < KS * KS) wl[(idx / KS) * WP + idx % KS] = wreg[m];
     }
     __syncthreads();
+    ESC_STAMP(rec, 3);
 
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    const float *lkc = p.lk + (size_t)c * p.lk_cstride;
-
     float acc[RY][4];
 #pragma unroll
     for (int oy = 0; oy < RY; ++oy)
@@ -300,13 +567,14 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, unsigned item, flo
 
     const float *trow = tile + (ty * RY) * PITCH + 4 * tx;
 
-    auto row_step = [&](int r) {
+#pragma unroll 1
+    for (int r = 0; r < RY + KS - 1; ++r) {
         float v[NV];
         if (OFF == 0) {
             const float4 *src = reinterpret_cast<const float4 *>(trow + r * PITCH);
 #pragma unroll
             for (int k = 0; k < NV / 4; ++k) {
-                float4 f = src[k];
+                const float4 f = src[k];
                 v[4 * k + 0] = f.x;
                 v[4 * k + 1] = f.y;
                 v[4 * k + 2] = f.z;
@@ -321,31 +589,47 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, unsigned item, flo
         for (int oy = 0; oy < RY; ++oy) {
             const int i = r - oy;  // kernel row that maps tile row r to output row oy
             if (i >= 0 && i < KS) {
-                const float *wrow = lkc + i * KS;
+                float w[WP];
+                const float4 *wsrc = reinterpret_cast<const float4 *>(wl + i * WP);
 #pragma unroll
-                for (int j = 0; j < KS; ++j) {
-                    const float w = wrow[j];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) acc[oy][q] = fmaf(w, v[j + q], acc[oy][q]);
+                for (int k = 0; k < WP / 4; ++k) {
+                    const float4 f = wsrc[k];
+                    w[4 * k + 0] = f.x;
+                    w[4 * k + 1] = f.y;
+                    w[4 * k + 2] = f.z;
+                    w[4 * k + 3] = f.w;
                 }
+#pragma unroll
+                for (int j = 0; j < KS; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[oy][q] = fmaf(w[j], v[j + q], acc[oy][q]);
             }
         }
-    };
-
-    if (kUnrollRows) {
-#pragma unroll
-        for (int r = 0; r < RY + KS - 1; ++r) row_step(r);
-    } else {
-#pragma unroll 1
-        for (int r = 0; r < RY + KS - 1; ++r) row_step(r);
     }
+#ifdef ESC_TRACE
+#pragma unroll
+    for (int oy = 0; oy < RY; ++oy)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) asm volatile("" ::"v"(acc[oy][q]));
+#endif
+    ESC_STAMP(rec, 4);
 
-    if (p.has_gen || p.dk_in != nullptr) {
+    if (p.dk_mode != kDkNone) {
         const size_t dk_idx = ((size_t)n * p.Ca + c) * 9;
-        if (threadIdx.x < 9)
-            s_dk[threadIdx.x] = p.has_gen ? box_get(p.dk_box + dk_idx + threadIdx.x, p.tag, p.err)
-                                          : p.dk_in[dk_idx + threadIdx.x];
+        if (p.dk_mode == kDkDirect) estimator_front(p, ctx.tag, n, s_part, s_g, s_t);
+        ESC_STAMP(rec, 12);
+        if (threadIdx.x < 9) {
+            float d;
+            if (p.dk_mode == kDkDirect)
+                d = estimator_out(p, c * 9 + (int)threadIdx.x, s_g, s_t);
+            else if (p.dk_mode == kDkBoxes)
+                d = box_get(p.dk_box + dk_idx + threadIdx.x, ctx.tag, p.err);
+            else
+                d = p.dk_in[dk_idx + threadIdx.x];
+            s_dk[threadIdx.x] = d;
+        }
         __syncthreads();
+        ESC_STAMP(rec, 5);
         float d[9];
 #pragma unroll
         for (int k = 0; k < 9; ++k) d[k] = s_dk[k];
@@ -389,10 +673,10 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, unsigned item, flo
 // copy item (Eq. 4 lines 1 and 4): 16 KiB of one image's identity channels,
 // streamed with 16-byte non-temporal accesses when both sides allow it.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void copy_item(const FwdParams &p, unsigned item)
+__device__ __forceinline__ void copy_item(const FwdParams &p, Ctx &ctx, unsigned item)
 {
-    const unsigned n = item / p.copy_chunks;
-    const size_t chunk = (size_t)(item - n * p.copy_chunks);
+    const unsigned n = fdiv(item, p.div_chunks);
+    const size_t chunk = (size_t)(item - n * p.div_chunks.d);
     const char *src = (const char *)p.x + (size_t)n * p.img_bytes + p.idt_off;
     char *dst = (char *)p.out + (size_t)n * p.img_bytes + p.idt_off;
     const size_t len = p.idt_len;
@@ -406,6 +690,7 @@ __device__ __forceinline__ void copy_item(const FwdParams &p, unsigned item)
             const size_t o = begin + ((size_t)k * kThreads + threadIdx.x) * 16;
             if (o + 16 <= end) v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
         }
+        announce_leave(p, ctx);
 #pragma unroll
         for (int k = 0; k < kCopyVecPerThread; ++k) {
             const size_t o = begin + ((size_t)k * kThreads + threadIdx.x) * 16;
@@ -423,6 +708,7 @@ __device__ __forceinline__ void copy_item(const FwdParams &p, unsigned item)
             }
         }
     } else {
+        announce_leave(p, ctx);
         for (size_t o = begin + (size_t)threadIdx.x * eb; o < end; o += (size_t)kThreads * eb) {
             if (eb == 4)
                 *reinterpret_cast<uint32_t *>(dst + o) = *reinterpret_cast<const uint32_t *>(src + o);
@@ -437,54 +723,99 @@ __device__ __forceinline__ void copy_item(const FwdParams &p, unsigned item)
 // esc_dynkernel_gen and for C_a == 0).
 // ---------------------------------------------------------------------------
 template <int KS, int RY, typename T>
-__global__ __launch_bounds__(kThreads) void forward_kernel(const FwdParams p)
+__global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const FwdParams p)
 {
-    constexpr int kTileFloats = ConvGeom<(KS > 0 ? KS : 1), RY>::LDS_FLOATS;
-    __shared__ __align__(16) float tile[KS > 0 ? kTileFloats : 4];
+    using G = ConvGeom<(KS > 0 ? KS : 1), RY>;
+    __shared__ __align__(16) float tile[KS > 0 ? G::TILE_FLOATS : 4];
+    __shared__ __align__(16) float wl[KS > 0 ? G::W_FLOATS : 4];
+    __shared__ float s_part[kStage];
     __shared__ float s_g[kMaxCa];
     __shared__ float s_t[kMaxHidden];
     __shared__ float s_small[16];
-    __shared__ unsigned s_next;
 
     const unsigned first_mixed = p.n_pool + p.n_gen;
-    const unsigned n_mixed = p.n_conv + p.n_copy;
-    const unsigned total = first_mixed + n_mixed;
-    unsigned item = blockIdx.x;
-    while (item < total) {
-        // take the next item now so the atomic's round trip hides behind this item's work
-        unsigned next = 0;
-        if (threadIdx.x == 0) {
-            const u64 base = ((u64)p.tag << 32) | (u64)gridDim.x;
-            __hip_atomic_fetch_max(p.queue, base, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            next = (unsigned)__hip_atomic_fetch_add(p.queue, (u64)1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (item < p.n_pool) {
-            pool_item<T>(p, item, s_small);
-        } else if (item < first_mixed) {
-            gen_item(p, item - p.n_pool, s_g, s_t);
-        } else {
-            // conv and copy items alternate in proportion: mixed item j is a conv item
-            // when floor((j+1)*n_conv/n_mixed) steps past floor(j*n_conv/n_mixed)
-            const u64 j = item - first_mixed;
-            const unsigned cb = (unsigned)(j * p.n_conv / n_mixed);
-            const unsigned ca = (unsigned)((j + 1) * p.n_conv / n_mixed);
-            if (ca > cb) {
-                if constexpr (KS > 0) conv_item<KS, RY, T>(p, cb, tile, s_small);
-            } else {
-                copy_item(p, (unsigned)j - cb);
+    const unsigned total = first_mixed + p.n_conv + p.n_copy;
+    Ctx ctx;
+    ctx.tag = 0;
+    ctx.have_tag = false;
+    ctx.last_item = false;
+    ctx.announced = false;
+    ctx.left = 0;
+    for (unsigned item = blockIdx.x; item < total; item += gridDim.x) {
+        u64 *rec = nullptr;
+#ifdef ESC_TRACE
+        if (p.trace != nullptr) {
+            rec = p.trace + (size_t)item * 16;
+            if (threadIdx.x == 0) {
+                rec[0] = item;
+                rec[1] = ((u64)__builtin_amdgcn_s_getreg((31 << 11) | 4) << 32) | blockIdx.x;
+                rec[15] = __builtin_amdgcn_s_getreg((31 << 11) | 20);
+                rec[13] = clock64();
             }
         }
-        if (threadIdx.x == 0) s_next = next;
-        __syncthreads();
-        item = s_next;
-        __syncthreads();
+#endif
+        ESC_STAMP(rec, 2);
+        ctx.last_item = item + gridDim.x >= total;
+        if (item < p.n_pool) {
+            pool_item<T>(p, ctx, item, s_small);
+        } else if (item < first_mixed) {
+            gen_item(p, ctx, item - p.n_pool, s_part, s_g, s_t, rec);
+        } else {
+            const unsigned j = item - first_mixed;
+            const unsigned group = p.mix_a + p.mix_b;
+            bool is_conv;
+            unsigned idx;
+            if (j < p.mix_groups * group) {
+                const unsigned g = fdiv(j, p.div_mix), r = j - g * group;
+                is_conv = r < p.mix_a;
+                idx = is_conv ? g * p.mix_a + r : g * p.mix_b + (r - p.mix_a);
+            } else {
+                const unsigned jj = j - p.mix_groups * group;
+                const unsigned conv_left = p.n_conv - p.mix_groups * p.mix_a;
+                is_conv = jj < conv_left;
+                idx = is_conv ? p.mix_groups * p.mix_a + jj : p.mix_groups * p.mix_b + (jj - conv_left);
+            }
+            if (is_conv) {
+                if constexpr (KS > 0) conv_item<KS, RY, T>(p, ctx, idx, tile, wl, s_small, s_part, s_g, s_t, rec);
+            } else {
+                copy_item(p, ctx, idx);
+            }
+        }
+        ESC_STAMP(rec, 6);
+#ifdef ESC_TRACE
+        if (rec != nullptr && threadIdx.x == 0) rec[14] = clock64();
+#endif
+        __syncthreads();  // LDS is reused by the next item
+    }
+    // A block without items still belongs to its group.  The last block of a group to have
+    // announced its leave opens the next call for the group: leave counter back to zero, tag + 1.
+    ctx.last_item = true;
+    announce_leave(p, ctx);
+    if (threadIdx.x == kThreads - 1) {
+        const unsigned g = blockIdx.x % kGroups;
+        const unsigned members = (gridDim.x - g + kGroups - 1) / kGroups;
+        if (ctx.left == members - 1) {
+            __hip_atomic_store(p.done + g * kCtlStride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.epoch + g * kCtlStride, ctx.tag + 1u == 0u ? 1u : ctx.tag + 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
-__global__ void fill_zero_kernel(uint32_t *ptr, size_t words)
+// Control block at the start of the workspace, in 32-bit words: word 0 the error word, then
+// from kCtlEpochWord one call counter per group and from kCtlDoneWord one leave counter per
+// group, each kCtlStride words apart.  Preparation: everything zero, call counters 1 (tag 0
+// is what empty mailboxes carry).
+constexpr size_t kCtlErrWord = 0;
+constexpr size_t kCtlEpochWord = kCtlStride;
+constexpr size_t kCtlDoneWord = kCtlEpochWord + (size_t)kGroups * kCtlStride;
+constexpr size_t kCtlWords = kCtlDoneWord + (size_t)kGroups * kCtlStride;
+
+__global__ void ws_init_kernel(uint32_t *ptr, size_t words)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < words) ptr[i] = 0u;
+    const bool is_epoch = i >= kCtlEpochWord && i < kCtlDoneWord && (i - kCtlEpochWord) % kCtlStride == 0;
+    if (i < words) ptr[i] = is_epoch ? 1u : 0u;
 }
 
 // ---------------------------------------------------------------------------
@@ -504,14 +835,26 @@ bool ws_layout(int N, int Ca, int H, int W, WsLayout *l)
     if (hw >= ((size_t)1 << 31)) return false;
     l->nslab = (int)((hw + kPoolSlab - 1) / kPoolSlab);
     size_t off = 0;
-    l->ctl_off = off;  // [0] work counter, [1] error word
-    off = round_up(off + 2 * sizeof(u64), kWsAlign);
+    l->ctl_off = off;
+    off = round_up(off + kCtlWords * sizeof(uint32_t), kWsAlign);
     l->pool_off = off;
     off = round_up(off + (size_t)N * Ca * l->nslab * sizeof(u64), kWsAlign);
     l->dk_off = off;
     off = round_up(off + (size_t)N * Ca * 9 * sizeof(u64), kWsAlign);
     l->total = off;
     return true;
+}
+
+FastDiv make_div(uint32_t d)
+{
+    FastDiv f;
+    if (d == 0) d = 1;
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    f.d = d;
+    f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
+    f.shift = l;
+    return f;
 }
 
 esc_status check_common(const void *x, esc_dtype dt, int N, int C, int H, int W, int Ca)
@@ -537,20 +880,14 @@ esc_status check_gen(const esc_gen_params *gen, int Ca)
 
 esc_status check_ws(const void *ws, size_t ws_bytes, size_t need)
 {
+    if (need < kCtlWords * sizeof(uint32_t)) need = kCtlWords * sizeof(uint32_t);
     if (ws == nullptr || ((uintptr_t)ws % kWsAlign) != 0 || ws_bytes < need) return ESC_ERR_WORKSPACE;
     return ESC_OK;
 }
 
-// every call gets its own non-zero tag; a zeroed workspace never matches one
-uint32_t next_tag()
-{
-    static std::atomic<uint32_t> counter{0};
-    uint32_t t;
-    do {
-        t = counter.fetch_add(1, std::memory_order_relaxed) + 1;
-    } while (t == 0);
-    return t;
-}
+#ifdef ESC_TRACE
+u64 *g_trace = nullptr;
+#endif
 
 int conv_ry_override()
 {
@@ -573,25 +910,53 @@ int device_cus()
     return cus;
 }
 
+// conv and copy items alternate in small groups so that both kinds are in flight together
+void set_mix(FwdParams &p)
+{
+    unsigned a = 1, b = 1;
+    if (p.n_conv > 0 && p.n_copy > 0) {
+        if (p.n_conv >= p.n_copy) {
+            a = (p.n_conv + p.n_copy / 2) / p.n_copy;
+            if (a > 16) a = 16;
+        } else {
+            b = (p.n_copy + p.n_conv / 2) / p.n_conv;
+            if (b > 16) b = 16;
+        }
+        const unsigned ga = p.n_conv / a, gb = p.n_copy / b;
+        p.mix_groups = ga < gb ? ga : gb;
+    } else {
+        p.mix_groups = 0;
+    }
+    p.mix_a = a;
+    p.mix_b = b;
+    p.div_mix = make_div(a + b);
+}
+
 template <int KS, int RY, typename T>
 esc_status launch_variant(FwdParams &p, hipStream_t s)
 {
-    // blocks that can be resident at once: occupancy of this instantiation x compute units
-    static int per_cu = 0;
-    if (per_cu == 0) {
-        int v = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, forward_kernel<KS, RY, T>, kThreads, 0) !=
-                hipSuccess ||
-            v < 1)
-            return ESC_ERR_HIP;
-        per_cu = v;
-    }
+    // the kernel is compiled for kBlocksPerCu resident blocks per compute unit (register
+    // budget via __launch_bounds__, LDS <= 40 KiB of 160 KiB), so this grid is co-resident
     const int cus = device_cus();
     if (cus < 1) return ESC_ERR_HIP;
     const u64 total = (u64)p.n_pool + p.n_gen + p.n_conv + p.n_copy;
     if (total == 0) return ESC_OK;
-    const u64 cap = (u64)per_cu * (u64)cus;
-    const unsigned grid = (unsigned)(total < cap ? total : cap);
+    if (total >= ((u64)1 << 30)) return ESC_ERR_UNSUPPORTED;  // item + grid must not wrap
+    set_mix(p);
+    const u64 cap = (u64)kBlocksPerCu * (u64)cus;
+    unsigned grid = (unsigned)(total < cap ? total : cap);
+    if (grid < (unsigned)kGroups) grid = kGroups;  // every group of blocks needs a member
+    // a block's items are grid apart: keep that stride coprime with the conv/copy pattern
+    const unsigned pattern = p.mix_a + p.mix_b;
+    auto gcd = [](unsigned a, unsigned b) {
+        while (b) {
+            const unsigned t = a % b;
+            a = b;
+            b = t;
+        }
+        return a;
+    };
+    while (total > grid && grid > (unsigned)kGroups && gcd(grid, pattern) != 1) --grid;
     hipLaunchKernelGGL((forward_kernel<KS, RY, T>), dim3(grid), dim3(kThreads), 0, s, p);
     return hipGetLastError() == hipSuccess ? ESC_OK : ESC_ERR_HIP;
 }
@@ -607,9 +972,11 @@ esc_status launch_ks(FwdParams &p, hipStream_t s)
         int ry = (tiles4 >= 2048 && KS <= 17) ? 4 : 2;
         if (conv_ry_override() == 2 || (conv_ry_override() == 4 && KS <= 17)) ry = conv_ry_override();
         const int th = 16 * ry;
-        p.tiles_x = (p.W + kTileW - 1) / kTileW;
-        p.tiles_y = (p.H + th - 1) / th;
-        const size_t n_conv = (size_t)p.tiles_x * p.tiles_y * p.N * p.Ca;
+        const int tiles_x = (p.W + kTileW - 1) / kTileW;
+        const int tiles_y = (p.H + th - 1) / th;
+        p.div_tiles_x = make_div((uint32_t)tiles_x);
+        p.div_tiles_y = make_div((uint32_t)tiles_y);
+        const size_t n_conv = (size_t)tiles_x * tiles_y * p.N * p.Ca;
         if (n_conv >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
         p.n_conv = (unsigned)n_conv;
         if constexpr (KS <= 17) {
@@ -661,9 +1028,11 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
     p.nslab = l.nslab;
     p.hw = (float)((double)H * (double)W);
     p.elem_bytes = dt == ESC_F32 ? 4 : 2;
-    p.tag = next_tag();
+    p.div_nslab = make_div((uint32_t)l.nslab);
+    p.div_ca = make_div((uint32_t)(Ca > 0 ? Ca : 1));
+    p.div_tiles_x = p.div_tiles_y = p.div_chunks = p.div_mix = make_div(1);
     if (gen != nullptr && Ca > 0) {
-        p.has_gen = 1;
+        p.dk_mode = ((size_t)Ca * l.nslab <= (size_t)kDirectMaxBoxes) ? kDkDirect : kDkBoxes;
         p.hidden = gen->hidden;
         p.w_down = gen->w_down;
         p.b_down = gen->b_down;
@@ -672,13 +1041,17 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
         const size_t n_pool = (size_t)N * Ca * l.nslab;
         if (n_pool >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
         p.n_pool = (unsigned)n_pool;
-        p.n_gen = (unsigned)N;
+        p.n_gen = p.dk_mode == kDkBoxes ? (unsigned)N : 0u;
         const size_t plane_bytes = (size_t)H * W * p.elem_bytes;
         p.pool_vec_ok = ((uintptr_t)x % 16 == 0) && (plane_bytes % 16 == 0);
     }
     char *w = (char *)workspace;
-    p.queue = (u64 *)(w + l.ctl_off);
-    p.err = (unsigned *)(w + l.ctl_off + sizeof(u64));
+    p.err = (unsigned *)(w + l.ctl_off) + kCtlErrWord;
+    p.epoch = (unsigned *)(w + l.ctl_off) + kCtlEpochWord;
+    p.done = (unsigned *)(w + l.ctl_off) + kCtlDoneWord;
+#ifdef ESC_TRACE
+    p.trace = g_trace;
+#endif
     p.pool_box = (u64 *)(w + l.pool_off);
     p.dk_box = (u64 *)(w + l.dk_off);
     return ESC_OK;
@@ -702,7 +1075,7 @@ esc_status esc_workspace_init(void *workspace, size_t workspace_bytes, void *str
     const size_t words = workspace_bytes / 4;
     const size_t blocks = (words + kThreads - 1) / kThreads;
     if (blocks >= ((size_t)1 << 31)) return ESC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(ws_init_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
                        (uint32_t *)workspace, words);
     return hipGetLastError() == hipSuccess ? ESC_OK : ESC_ERR_HIP;
 }
@@ -714,7 +1087,7 @@ esc_status esc_workspace_errors(const void *workspace, size_t workspace_bytes, v
     esc_status st = check_ws(workspace, workspace_bytes, kWsAlign);
     if (st != ESC_OK) return st;
     unsigned v = 0;
-    if (hipMemcpyAsync(&v, (const char *)workspace + sizeof(u64), sizeof v, hipMemcpyDeviceToHost,
+    if (hipMemcpyAsync(&v, (const uint32_t *)workspace + kCtlErrWord, sizeof v, hipMemcpyDeviceToHost,
                        (hipStream_t)stream) != hipSuccess)
         return ESC_ERR_HIP;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ESC_ERR_HIP;
@@ -738,6 +1111,8 @@ esc_status esc_dynkernel_gen(const void *x, esc_dtype dt, int N, int C, int H, i
     FwdParams p;
     if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
     p.dk_out = dk_out;
+    p.dk_mode = kDkBoxes;  // no conv items here: gen items write dk_out
+    p.n_gen = (unsigned)N;
     return dt == ESC_F32 ? launch_typed<float>(p, 0, (hipStream_t)stream)
                          : launch_typed<bf16_t>(p, 0, (hipStream_t)stream);
 }
@@ -770,8 +1145,11 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
     p.lk = lk;
     p.lk_cstride = lk_channel_stride;
     p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
+    if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
+    // aligned 4-element chunk loads of the halo tile need W % 4 == 0 and an aligned base
+    p.conv_ld_vec = (W % 4 == 0) && (xa % (4 * es) == 0);
     // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
-    p.conv_vec_ok = (W % 4 == 0) && ((uintptr_t)out % (4 * es) == 0);
+    p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
     if (C_a < C) {
         const size_t plane = (size_t)H * W * es;
         p.img_bytes = plane * C;
@@ -779,7 +1157,7 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
         p.idt_len = plane * (C - C_a);
         const size_t chunks = (p.idt_len + kCopyChunk - 1) / kCopyChunk;
         if (chunks * (size_t)N >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
-        p.copy_chunks = (unsigned)chunks;
+        p.div_chunks = make_div((uint32_t)chunks);
         p.n_copy = (unsigned)(chunks * N);
         p.copy_vec_ok = (xa % 16 == 0) && (oa % 16 == 0) && (p.img_bytes % 16 == 0) && (p.idt_off % 16 == 0);
     }
@@ -787,6 +1165,10 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
     return dt == ESC_F32 ? launch_typed<float>(p, ks_variant, (hipStream_t)stream)
                          : launch_typed<bf16_t>(p, ks_variant, (hipStream_t)stream);
 }
+
+#ifdef ESC_TRACE
+void esc_debug_set_trace(void *buf) { g_trace = (u64 *)buf; }
+#endif
 
 const char *esc_status_string(esc_status s)
 {

@@ -46,7 +46,7 @@ def run_dk(wl):
     x = to_dev_x(wl.x, wl.dtype)
     ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
     dk = binding.dynkernel_gen(x, wl.Ca, gen_params(wl), ws)
-    torch.cuda.synchronize()
+    assert binding.workspace_errors(ws) == 0
     return dk.cpu().numpy()
 
 
