@@ -9,22 +9,25 @@
 // One launch does the whole forward.  The work is cut into items that blocks take
 // from a queue in this order:
 //
-//   pool items   GAP partial sums of the attention slice, one 4096-element slab each
-//   gen items    one per image, only when an image has many slabs: finish the GAP,
-//                run the kernel estimator, publish DK
+//   pool items   GAP partial sums of the attention slice, one 64 x 32 pixel tile each;
+//                left out when every conv item is resident at once - then each conv
+//                item publishes the sums of its own tile from LDS
+//   gen items    one per image, only when an image has many pool tiles: finish the
+//                GAP, run the kernel estimator, publish DK
 //   conv items   one 64 x (16*RY) output tile of one (image, channel) plane: LK taps
 //                from an LDS halo tile with the channel's weights staged in LDS, then
 //                DK's nine taps once DK is known
-//   copy items   16 KiB of the identity channels, interleaved with the conv items so
+//   copy items   a chunk of the identity channels, interleaved with the conv items so
 //                streaming and arithmetic overlap on every compute unit
 //
-// Block b takes items b, b + grid, b + 2*grid, ...  An item only ever waits for
-// items with smaller indices (conv -> gen -> pool), pool items wait for nothing and
-// come first in every block's list, so every wait ends as long as the blocks of the
-// grid are co-resident (the host sizes the grid to what the kernel is compiled to
-// fit) - and each wait is bounded anyway: on expiry the block raises the error word
-// of the workspace and goes on.  The grid size is kept coprime with the length of
-// the conv/copy pattern so that every block meets both kinds of item.
+// Every die of the chip gets a contiguous eighth of each kind of item, and block number
+// s of a die takes entries s, s + S, s + 2S, ... of the die's list.  An item only ever
+// waits for items earlier in the lists (conv -> gen -> pool; with fused pooling, conv
+// items of the first round for one another, after having published their own sums),
+// pool items wait for nothing and come first in every block's list, so every wait ends
+// as long as the blocks of the grid are co-resident (the host sizes the grid to what
+// the kernel is compiled to fit) - and each wait is bounded anyway: on expiry the block
+// raises the error word of the workspace and goes on.
 //
 // Blocks talk through 64-bit mailboxes {fp32 value, 32-bit call tag} written and
 // read with relaxed device-scope atomics.  A mailbox is valid when its tag equals
@@ -56,7 +59,6 @@ namespace {
 
 constexpr int kThreads = 256;      // 4 wavefronts per block
 constexpr int kTileW = 64;         // conv tile width: 16 lanes x 4 outputs
-constexpr int kPoolSlab = 4096;    // elements per GAP partial sum
 constexpr int kMaxCa = 256;
 constexpr int kMaxHidden = 256;
 constexpr int kMaxKs = 31;
@@ -64,7 +66,7 @@ constexpr size_t kWsAlign = 256;
 constexpr unsigned kSpinLimit = 1u << 20;  // bounded wait: about a second, far beyond any real wait
 constexpr int kBlocksPerCu = 4;    // resident blocks per compute unit the kernel is compiled for (<= 128 VGPRs)
 constexpr int kCopyVecPerThread = 4;
-constexpr size_t kCopyChunk = (size_t)kThreads * 16 * kCopyVecPerThread;  // bytes per copy item
+constexpr size_t kCopyPiece = (size_t)kThreads * 16 * kCopyVecPerThread;  // bytes a block has in flight
 constexpr int kStage = 1024;       // pool mailboxes staged in LDS per round (multiple of 64)
 constexpr int kPollThreads = 192;  // wavefronts 0-2 poll mailboxes; wavefront 3 carries the leave atomic
 constexpr int kStagePerThread = (kStage + kPollThreads - 1) / kPollThreads;
@@ -77,15 +79,27 @@ struct bf16_t {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
-// Optional per-item timeline (development builds only, -DESC_TRACE): 16 words per item.
+// Optional per-item timeline (development builds only, -DESC_TRACE): 16 words per item,
+// kept in registers while the item runs and written out when it ends.
 #ifdef ESC_TRACE
-#define ESC_STAMP(rec, k)                                                    \
-    do {                                                                     \
-        if ((rec) != nullptr && threadIdx.x == 0) (rec)[k] = wall_clock64(); \
+struct Trace {
+    u64 t[16];
+};
+#define ESC_STAMP(rec, k) ((rec).t[k] = wall_clock64())
+#define ESC_TRACE_INIT(rec)                          \
+    do {                                             \
+        for (int k_ = 0; k_ < 16; ++k_) (rec).t[k_] = 0; \
+        (rec).t[13] = clock64();                     \
+        (rec).t[2] = wall_clock64();                 \
     } while (0)
 #else
+struct Trace {
+};
 #define ESC_STAMP(rec, k) \
     do {                  \
+    } while (0)
+#define ESC_TRACE_INIT(rec) \
+    do {                    \
     } while (0)
 #endif
 
@@ -141,9 +155,9 @@ __device__ __forceinline__ void load4(const bf16_t *p, float *v)
 struct FastDiv {
     uint32_t d, mul, shift;
 };
-__device__ __forceinline__ uint32_t fdiv(uint32_t x, const FastDiv &f)
+__device__ __forceinline__ uint32_t fdiv(uint32_t x, uint32_t mul, uint32_t shift)
 {
-    return (__umulhi(x, f.mul) + x) >> f.shift;
+    return (__umulhi(x, mul) + x) >> shift;
 }
 
 // ---------------------------------------------------------------------------
@@ -167,25 +181,29 @@ __device__ __forceinline__ float box_get(const u64 *box, uint32_t tag, unsigned 
     return 0.f;
 }
 
-// Whole block: waits for cnt (<= kStage) consecutive mailboxes and copies their values to
-// dst[0..cnt).  A thread's polls are issued together so their round trips overlap.
-__device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *dst, uint32_t tag, unsigned *err)
+// Whole block: waits for cnt (<= PER * kPollThreads) consecutive mailboxes and copies their
+// values to dst[0..cnt).  A thread's polls are issued together so their round trips overlap.
+// With `have_first` the caller has already issued the first round into v.
+template <int PER>
+__device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *dst, uint32_t tag, unsigned *err,
+                                             u64 (&v)[PER], bool have_first)
 {
-    bool pend[kStagePerThread];
+    bool pend[PER];
 #pragma unroll
-    for (int u = 0; u < kStagePerThread; ++u)
+    for (int u = 0; u < PER; ++u)
         pend[u] = threadIdx.x < kPollThreads && (int)threadIdx.x + u * kPollThreads < cnt;
     bool any = false;
     for (unsigned spin = 0; spin < kSpinLimit; ++spin) {
-        u64 v[kStagePerThread];
+        if (spin > 0 || !have_first) {
 #pragma unroll
-        for (int u = 0; u < kStagePerThread; ++u)
-            if (pend[u])
-                v[u] = __hip_atomic_load(boxes + threadIdx.x + u * kPollThreads, __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
+            for (int u = 0; u < PER; ++u)
+                if (pend[u])
+                    v[u] = __hip_atomic_load(boxes + threadIdx.x + u * kPollThreads, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+        }
         any = false;
 #pragma unroll
-        for (int u = 0; u < kStagePerThread; ++u)
+        for (int u = 0; u < PER; ++u)
             if (pend[u]) {
                 if ((uint32_t)(v[u] >> 32) == tag) {
                     dst[threadIdx.x + u * kPollThreads] = __uint_as_float((uint32_t)v[u]);
@@ -216,7 +234,13 @@ enum : int {
     kDkBoxes = 2,   // published by a gen item
     kDkDirect = 3   // each conv item finishes the GAP and runs its nine estimator outputs itself
 };
-constexpr int kDirectMaxBoxes = 512;  // direct mode while C_a * nslab mailboxes stay this few
+enum : int {
+    kPoolNone = 0,   // no estimator in this call
+    kPoolItems = 1,  // pool items read the attention slice and publish the partial sums
+    kPoolFused = 2   // every conv item is resident at once: each publishes the sum of its own tile
+};
+constexpr int kDirectMaxBoxes = 512;  // direct mode while C_a * (pool tiles) mailboxes stay this few
+constexpr int kPoolTileW = 64, kPoolTileH = 32;  // the GAP is cut into 64 x 32 pixel tiles
 
 struct FwdParams {
     const void *x;
@@ -228,23 +252,51 @@ struct FwdParams {
     const float *w_down, *b_down, *w_up, *b_up;
     int hidden;
     int dk_mode;         // where conv items take DK from (kDk*)
+    int pool_mode;       // who computes the GAP partial sums (kPool*)
     int N, C, Ca, H, W;
-    int nslab;           // pool slabs per (image, channel) plane
+    int ptiles_x, ptiles;  // pool tiles per row of tiles / per (image, channel) plane
     float hw;            // H*W as a float, the GAP divisor
     unsigned n_pool, n_gen, n_conv, n_copy;  // item counts
     // conv and copy items alternate in groups of mix_a conv + mix_b copy items while both
-    // last (mix_groups groups); the rest of the conv items follow, then the rest of the copy items
-    unsigned mix_a, mix_b, mix_groups;
-    FastDiv div_nslab, div_ca, div_tiles_x, div_tiles_y, div_chunks, div_mix;
+    // last; the rest of the conv items follow, then the rest of the copy items
+    unsigned mix_a, mix_b;
+    FastDiv div_ptiles, div_ptiles_x, div_ca, div_tiles_x, div_tiles_y, div_chunks, div_mix, div_mix_a, div_mix_b;
     size_t img_bytes, idt_off, idt_len;      // pass-through range of one image, in bytes
-    int conv_vec_ok, conv_ld_vec, copy_vec_ok, pool_vec_ok, elem_bytes;
-    u64 *pool_box;       // [N*Ca*nslab] partial sums
+    size_t copy_chunk;                       // bytes per copy item (a multiple of kCopyPiece)
+    int conv_vec_ok, conv_ld_vec, copy_vec_ok, elem_bytes;
+    u64 *pool_box;       // [N*Ca*ptiles] partial sums
     u64 *dk_box;         // [N*Ca*9]
     unsigned *err;       // raised when a bounded wait expires
     unsigned *epoch;     // [kGroups] call counters (kCtlStride words apart) = tag of the current call
     unsigned *done;      // [kGroups] blocks of the group that have announced their leave
     u64 *trace;          // development builds only
 };
+
+// The kernel's parameter block as the item functions see it: a pointer into the kernel
+// argument segment (constant address space), read with scalar loads where needed instead
+// of being held in registers across a whole item.
+typedef const __attribute__((address_space(4))) FwdParams *ParamsPtr;
+
+constexpr unsigned kXcds = 8;
+
+// die `die`'s contiguous share of n items: [base, base + cnt)
+__device__ __forceinline__ void die_share(unsigned n, unsigned die, unsigned &base, unsigned &cnt)
+{
+    const unsigned q = n / kXcds, r = n % kXcds;
+    cnt = q + (die < r ? 1u : 0u);
+    base = die * q + (die < r ? die : r);
+}
+
+// LDS of a block, shared by all item kinds: the conv tile and weights are sized for the
+// largest variant (Ks = 17 with 4-row register blocks; Ks = 31 with 2-row blocks).
+constexpr int kLdsTileFloats = 6400;
+constexpr int kLdsWeightFloats = 31 * 32;
+__shared__ __align__(16) float g_tile[kLdsTileFloats];
+__shared__ __align__(16) float g_wl[kLdsWeightFloats];
+__shared__ float g_part[kStage];
+__shared__ float g_g[kMaxCa];
+__shared__ float g_t[kMaxHidden];
+__shared__ float g_small[16];
 
 // Per-block state that item code touches.
 struct Ctx {
@@ -255,21 +307,28 @@ struct Ctx {
     unsigned left;    // thread kThreads-1 only: blocks of the group that had announced before this one
 };
 
+// What an item function hands back: the updated block state (and, in development builds,
+// its timeline).
+struct ItemOut {
+    Ctx ctx;
+    Trace rec;
+};
+
 // Reads the call tag once per block, at a point where the caller's own loads are already
 // in flight (it must not sit in front of them: results return in order).  A plain cached
 // load: the value was written by the previous launch and only changes once this block's
 // whole group has announced its leave.
-__device__ __forceinline__ void need_tag(const FwdParams &p, Ctx &ctx)
+__device__ __forceinline__ void need_tag(ParamsPtr p, Ctx &ctx)
 {
     if (!ctx.have_tag) {
-        ctx.tag = *(const volatile unsigned *)(p.epoch + (blockIdx.x % kGroups) * kCtlStride);
+        ctx.tag = *(const volatile unsigned *)(p->epoch + (blockIdx.x % kGroups) * kCtlStride);
         ctx.have_tag = true;
     }
 }
 
 // Called once the loads of the block's last item are in flight: announce the leave, so the
 // atomic's round trip is over long before the block ends.
-__device__ __forceinline__ void announce_leave(const FwdParams &p, Ctx &ctx)
+__device__ __forceinline__ void announce_leave(ParamsPtr p, Ctx &ctx)
 {
     if (ctx.last_item && !ctx.announced) {
         need_tag(p, ctx);
@@ -278,62 +337,23 @@ __device__ __forceinline__ void announce_leave(const FwdParams &p, Ctx &ctx)
         asm volatile("" ::"v"(ctx.tag) : "memory");
         __syncthreads();
         if (threadIdx.x == kThreads - 1)
-            ctx.left = __hip_atomic_fetch_add(p.done + (blockIdx.x % kGroups) * kCtlStride, 1u,
+            ctx.left = __hip_atomic_fetch_add(p->done + (blockIdx.x % kGroups) * kCtlStride, 1u,
                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ctx.announced = true;
     }
 }
 
 // ---------------------------------------------------------------------------
-// pool item (Eq. 4 line 2, first half).  Thread t adds elements
-// base + (k*256 + t)*V + q for k, then q, ascending - the same order whether the
-// 16-byte loads are usable or not - then a fixed tree over the block.  The
-// decomposition depends on H*W only, so a batch reproduces its images run alone.
+// GAP partial sums (Eq. 4 line 2, first half).  A plane is cut into 64 x 32 pixel
+// tiles.  Thread (tx, ty) = (t & 15, t >> 4) adds pixels (2*ty + a, 4*tx + q) of the
+// tile for a, then q, ascending (pixels outside the image count as 0), then the
+// wavefront tree adds the lanes and thread 0 the four wavefronts in order.  The order
+// is the same whether the pixels come from global memory (pool item) or from a conv
+// item's LDS tile, and depends on H and W only - so a batch reproduces its images run
+// alone, and esc_dynkernel_gen reproduces the DK of the forward bit for bit.
 // ---------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ void pool_item(const FwdParams &p, Ctx &ctx, unsigned item, float *s_red)
+__device__ __forceinline__ void pool_finish(ParamsPtr p, float s, unsigned box, uint32_t tag, float *s_red)
 {
-    constexpr int V = 16 / (int)sizeof(T);  // elements per 16-byte load
-    constexpr int K = kPoolSlab / (kThreads * V);
-    const int HW = p.H * p.W;
-    const unsigned nc = fdiv(item, p.div_nslab);
-    const int slab = (int)(item - nc * (unsigned)p.nslab);
-    const unsigned n = fdiv(nc, p.div_ca);
-    const unsigned c = nc - n * (unsigned)p.Ca;
-    const T *plane = (const T *)p.x + ((size_t)n * p.C + c) * (size_t)HW;
-    const int base = slab * kPoolSlab;
-    float s = 0.f;
-    if (p.pool_vec_ok && base + kPoolSlab <= HW) {
-        u32x4 raw[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k)
-            raw[k] = *reinterpret_cast<const u32x4 *>(plane + base + (k * kThreads + (int)threadIdx.x) * V);
-        need_tag(p, ctx);
-        announce_leave(p, ctx);
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            if (sizeof(T) == 4) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) s += __uint_as_float(raw[k][q]);
-            } else {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    s += __uint_as_float(raw[k][q] << 16);
-                    s += __uint_as_float(raw[k][q] & 0xffff0000u);
-                }
-            }
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < K; ++k)
-#pragma unroll
-            for (int q = 0; q < V; ++q) {
-                const int idx = base + (k * kThreads + (int)threadIdx.x) * V + q;
-                if (idx < HW) s += to_f32(plane[idx]);
-            }
-        need_tag(p, ctx);
-        announce_leave(p, ctx);
-    }
     s = wave_sum(s);
     if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = s;
     __syncthreads();
@@ -341,17 +361,59 @@ __device__ __forceinline__ void pool_item(const FwdParams &p, Ctx &ctx, unsigned
         float t = s_red[0];
 #pragma unroll
         for (int w = 1; w < kThreads / 64; ++w) t += s_red[w];
-        box_put(p.pool_box + item, t, ctx.tag);
+        box_put(p->pool_box + box, t, tag);
     }
+}
+
+template <typename T>
+__device__ __forceinline__ ItemOut pool_item(ParamsPtr p, Ctx ctx, unsigned item)
+{
+    float *s_red = g_small;
+    Trace rec;
+    ESC_TRACE_INIT(rec);
+    const int H = p->H, W = p->W;
+    const unsigned nc = fdiv(item, p->div_ptiles.mul, p->div_ptiles.shift);
+    const unsigned t = item - nc * (unsigned)p->ptiles;
+    const unsigned pty = fdiv(t, p->div_ptiles_x.mul, p->div_ptiles_x.shift), ptx = t - pty * (unsigned)p->ptiles_x;
+    const unsigned n = fdiv(nc, p->div_ca.mul, p->div_ca.shift);
+    const unsigned c = nc - n * (unsigned)p->Ca;
+    const T *plane = (const T *)p->x + ((size_t)n * p->C + c) * (size_t)H * (size_t)W;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int gx = (int)ptx * kPoolTileW + 4 * tx, gy = (int)pty * kPoolTileH + 2 * ty;
+    float v[2][4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[a][q] = 0.f;
+        if (gy + a < H) {
+            if (p->conv_ld_vec) {  // W % 4 == 0 and an aligned base: the four pixels are in or out together
+                if (gx < W) load4(plane + (size_t)(gy + a) * W + gx, v[a]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (gx + q < W) v[a][q] = to_f32(plane[(size_t)(gy + a) * W + gx + q]);
+            }
+        }
+    }
+    need_tag(p, ctx);
+    announce_leave(p, ctx);
+    float s = 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s += v[a][q];
+    pool_finish(p, s, item, ctx.tag, s_red);
+    ESC_STAMP(rec, 6);
+    return ItemOut{ctx, rec};
 }
 
 // ---------------------------------------------------------------------------
 // The kernel estimator (Eq. 4 line 2, second half) of image n.  The GAP of a
 // channel is finished in one fixed order everywhere: lane l of a wavefront adds
-// slabs l, l+64, ... ascending, then the wavefront tree adds the lanes.  Then the
-// estimator, one output per thread.  A gen item publishes all 9*C_a outputs; when
-// an image has few slabs the conv items skip that hop and derive their own nine
-// values with the same arithmetic.
+// pool tiles l, l+64, ... ascending, then the wavefront tree adds the lanes.  Then
+// the estimator, one output per thread.  A gen item publishes all 9*C_a outputs;
+// when an image has few pool tiles the conv items skip that hop and derive their
+// own nine values with the same arithmetic.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float gelu_erf(float v)
 {
@@ -374,37 +436,46 @@ __device__ __forceinline__ float dot_row(const float *w, const float *in, int K,
     return s;
 }
 
+// Wavefront w adds the staged partial sums of channels w, w+4, ... < gc of a round that
+// starts at channel c0: lane l adds tiles l, l+64, ... ascending, then the wavefront tree.
+__device__ __forceinline__ void sum_staged(const float *s_part, int ntile, int gc, int c0, float hw, float *s_g)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int cg = wave; cg < gc; cg += kThreads / 64) {
+        float s = 0.f;
+        for (int k = lane; k < ntile; k += 64) s += s_part[cg * ntile + k];
+        s = wave_sum(s);
+        if (lane == 0) s_g[c0 + cg] = s / hw;
+    }
+}
+
 // Whole block: waits for image n's pool mailboxes (staged through s_part), leaves the
 // pooled means in s_g and (two-layer estimator) the hidden activations in s_t.  Ends
 // with a barrier.
-__device__ __forceinline__ void estimator_front(const FwdParams &p, uint32_t tag, unsigned n, float *s_part,
+__device__ __forceinline__ void estimator_front(ParamsPtr p, uint32_t tag, unsigned n, float *s_part,
                                                 float *s_g, float *s_t)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int nslab = p.nslab, Ca = p.Ca;
-    const u64 *img_boxes = p.pool_box + (size_t)n * Ca * nslab;
-    if (nslab <= kStage) {
-        const int G = kStage / nslab;  // whole channels per round
+    const int ntile = p->ptiles, Ca = p->Ca;
+    const u64 *img_boxes = p->pool_box + (size_t)n * Ca * ntile;
+    u64 polled[kStagePerThread];
+    if (ntile <= kStage) {
+        const int G = kStage / ntile;  // whole channels per round
         for (int c0 = 0; c0 < Ca; c0 += G) {
             const int gc = Ca - c0 < G ? Ca - c0 : G;
-            boxes_to_lds(img_boxes + (size_t)c0 * nslab, gc * nslab, s_part, tag, p.err);
+            boxes_to_lds(img_boxes + (size_t)c0 * ntile, gc * ntile, s_part, tag, p->err, polled, false);
             __syncthreads();
-            for (int cg = wave; cg < gc; cg += kThreads / 64) {
-                float s = 0.f;
-                for (int k = lane; k < nslab; k += 64) s += s_part[cg * nslab + k];
-                s = wave_sum(s);
-                if (lane == 0) s_g[c0 + cg] = s / p.hw;
-            }
+            sum_staged(s_part, ntile, gc, c0, p->hw, s_g);
             __syncthreads();
         }
     } else {
-        // a channel has more slabs than fit: kStage at a time; kStage % 64 == 0 keeps every
-        // slab on the lane its index selects
+        // a channel has more tiles than fit: kStage at a time; kStage % 64 == 0 keeps every
+        // tile on the lane its index selects
         for (int c = 0; c < Ca; ++c) {
             float s = 0.f;
-            for (int k0 = 0; k0 < nslab; k0 += kStage) {
-                const int cnt = nslab - k0 < kStage ? nslab - k0 : kStage;
-                boxes_to_lds(img_boxes + (size_t)c * nslab + k0, cnt, s_part, tag, p.err);
+            for (int k0 = 0; k0 < ntile; k0 += kStage) {
+                const int cnt = ntile - k0 < kStage ? ntile - k0 : kStage;
+                boxes_to_lds(img_boxes + (size_t)c * ntile + k0, cnt, s_part, tag, p->err, polled, false);
                 __syncthreads();
                 if (wave == 0)
                     for (int k = lane; k < cnt; k += 64) s += s_part[k];
@@ -412,39 +483,43 @@ __device__ __forceinline__ void estimator_front(const FwdParams &p, uint32_t tag
             }
             if (wave == 0) {
                 s = wave_sum(s);
-                if (lane == 0) s_g[c] = s / p.hw;
+                if (lane == 0) s_g[c] = s / p->hw;
             }
         }
         __syncthreads();
     }
-    if (p.hidden > 0) {
-        for (int m = threadIdx.x; m < p.hidden; m += kThreads)
-            s_t[m] = gelu_erf(dot_row(p.w_down + (size_t)m * Ca, s_g, Ca, p.b_down ? p.b_down[m] : 0.f));
+    if (p->hidden > 0) {
+        for (int m = threadIdx.x; m < p->hidden; m += kThreads)
+            s_t[m] = gelu_erf(dot_row(p->w_down + (size_t)m * Ca, s_g, Ca, p->b_down ? p->b_down[m] : 0.f));
         __syncthreads();
     }
 }
 
 // One thread: estimator output o (= DK entry c*9 + i*3 + j) from what estimator_front left.
-__device__ __forceinline__ float estimator_out(const FwdParams &p, int o, const float *s_g, const float *s_t)
+__device__ __forceinline__ float estimator_out(ParamsPtr p, int o, const float *s_g, const float *s_t)
 {
-    const float *in = p.hidden > 0 ? s_t : s_g;
-    const int K = p.hidden > 0 ? p.hidden : p.Ca;
-    return dot_row(p.w_up + (size_t)o * K, in, K, p.b_up ? p.b_up[o] : 0.f);
+    const float *in = p->hidden > 0 ? s_t : s_g;
+    const int K = p->hidden > 0 ? p->hidden : p->Ca;
+    return dot_row(p->w_up + (size_t)o * K, in, K, p->b_up ? p->b_up[o] : 0.f);
 }
 
-__device__ __forceinline__ void gen_item(const FwdParams &p, Ctx &ctx, unsigned n, float *s_part, float *s_g,
-                                         float *s_t, u64 *rec)
+__device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
 {
+    float *s_part = g_part, *s_g = g_g, *s_t = g_t;
+    Trace rec;
+    ESC_TRACE_INIT(rec);
     need_tag(p, ctx);
     announce_leave(p, ctx);
     estimator_front(p, ctx.tag, n, s_part, s_g, s_t);
     ESC_STAMP(rec, 3);
-    for (int o = threadIdx.x; o < 9 * p.Ca; o += kThreads) {
+    for (int o = threadIdx.x; o < 9 * p->Ca; o += kThreads) {
         const float s = estimator_out(p, o, s_g, s_t);
-        const size_t idx = (size_t)n * 9 * p.Ca + o;
-        box_put(p.dk_box + idx, s, ctx.tag);
-        if (p.dk_out) p.dk_out[idx] = s;
+        const size_t idx = (size_t)n * 9 * p->Ca + o;
+        box_put(p->dk_box + idx, s, ctx.tag);
+        if (p->dk_out) p->dk_out[idx] = s;
     }
+    ESC_STAMP(rec, 6);
+    return ItemOut{ctx, rec};
 }
 
 // ---------------------------------------------------------------------------
@@ -468,31 +543,69 @@ struct ConvGeom {
     static constexpr int WP = (KS + 3) & ~3;      // pitch of a weight row in LDS
     static constexpr int TILE_FLOATS = HR * PITCH;
     static constexpr int W_FLOATS = KS * WP;
+    static constexpr int ROWS = RY + KS - 1;      // tile rows a thread walks through
+    static constexpr bool UNROLL = KS * KS * RY <= 13 * 13 * 4;
 };
 
+// Values hidden from the optimiser: what is computed from them cannot be moved above the
+// point where they are made, which keeps a later phase's addresses out of the registers of
+// an earlier one.
+__device__ __forceinline__ unsigned opaque_u(unsigned v)
+{
+    asm volatile("" : "+s"(v));
+    return v;
+}
+__device__ __forceinline__ int opaque_tid()
+{
+    int t = (int)threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
+// where a conv item lies
+struct ConvWhere {
+    unsigned n, nc;
+    int c, txi, tyi, x0, y0;
+    size_t plane_off;
+};
+template <int TH>
+__device__ __forceinline__ ConvWhere conv_where(ParamsPtr p, unsigned item)
+{
+    ConvWhere w;
+    const unsigned b1 = fdiv(item, p->div_tiles_x.mul, p->div_tiles_x.shift);
+    w.txi = (int)(item - b1 * p->div_tiles_x.d);
+    w.nc = fdiv(b1, p->div_tiles_y.mul, p->div_tiles_y.shift);
+    w.tyi = (int)(b1 - w.nc * p->div_tiles_y.d);
+    w.n = fdiv(w.nc, p->div_ca.mul, p->div_ca.shift);
+    w.c = (int)(w.nc - w.n * (unsigned)p->Ca);
+    w.plane_off = ((size_t)w.n * p->C + w.c) * (size_t)p->H * (size_t)p->W;
+    w.x0 = w.txi * kTileW;
+    w.y0 = w.tyi * TH;
+    return w;
+}
+
 template <int KS, int RY, typename T>
-__device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned item, float *tile, float *wl,
-                                          float *s_dk, float *s_part, float *s_g, float *s_t, u64 *rec)
+__device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
 {
     using G = ConvGeom<KS, RY>;
+    static_assert(G::TILE_FLOATS <= kLdsTileFloats && G::W_FLOATS <= kLdsWeightFloats, "LDS pool too small");
+    float *tile = g_tile, *wl = g_wl, *s_dk = g_small, *s_part = g_part, *s_g = g_g, *s_t = g_t;
+    Trace rec;
+    ESC_TRACE_INIT(rec);
     constexpr int PH = G::PH, OFF = G::OFF, TH = G::TH, HR = G::HR, HC = G::HC, PITCH = G::PITCH,
                   NV = G::NV, WP = G::WP;
-    const int H = p.H, W = p.W;
+    const int H = p->H, W = p->W;
 
-    const unsigned b1 = fdiv(item, p.div_tiles_x);
-    const int txi = (int)(item - b1 * p.div_tiles_x.d);
-    const unsigned nc = fdiv(b1, p.div_tiles_y);
-    const int tyi = (int)(b1 - nc * p.div_tiles_y.d);
-    const unsigned n = fdiv(nc, p.div_ca);
-    const int c = (int)(nc - n * (unsigned)p.Ca);
-    const size_t plane_off = ((size_t)n * p.C + c) * (size_t)H * (size_t)W;
-    const T *xp = (const T *)p.x + plane_off;
-    T *op = (T *)p.out + plane_off;
-    const int x0 = txi * kTileW, y0 = tyi * TH;
+    // ---- phase 1: fetch the halo tile and the channel's weights into LDS ----
+    const unsigned item = opaque_u(item_in);
+    const ConvWhere wa = conv_where<TH>(p, item);
+    const unsigned n = wa.n, nc = wa.nc;
+    const int c = wa.c, txi = wa.txi, tyi = wa.tyi, x0 = wa.x0, y0 = wa.y0;
+    const T *xp = (const T *)p->x + wa.plane_off;
 
     // this channel's weights, fetched together with the tile
     constexpr int KW = (KS * KS + kThreads - 1) / kThreads;
-    const float *lkc = p.lk + (size_t)c * p.lk_cstride;
+    const float *lkc = p->lk + (size_t)c * p->lk_cstride;
     float wreg[KW];
 #pragma unroll
     for (int m = 0; m < KW; ++m) {
@@ -501,7 +614,7 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
     }
 
     // halo tile -> LDS, zero outside the image
-    if (p.conv_ld_vec) {
+    if (p->conv_ld_vec) {
         // W % 4 == 0 and an aligned base: fetch whole 4-element chunks aligned in global
         // memory (each lies entirely inside or outside the image), all loads in flight
         // before the first LDS write.  A chunk lands at LDS column 4j - A.
@@ -520,7 +633,7 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
             for (int e = 0; e < 4; ++e) v[k][e] = 0.f;
             if (q < TOT && gy >= 0 && gy < H && gx >= 0 && gx < W) load4(xp + (size_t)gy * W + gx, v[k]);
         }
-        if (p.dk_mode >= kDkBoxes) need_tag(p, ctx);
+        if (p->pool_mode != kPoolNone) need_tag(p, ctx);
         announce_leave(p, ctx);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
@@ -547,7 +660,7 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
             if (gy >= 0 && gy < H && gx >= 0 && gx < W) v = to_f32(xp[(size_t)gy * W + gx]);
             tile[r * PITCH + cc] = v;
         }
-        if (p.dk_mode >= kDkBoxes) need_tag(p, ctx);
+        if (p->pool_mode != kPoolNone) need_tag(p, ctx);
         announce_leave(p, ctx);
     }
 #pragma unroll
@@ -559,6 +672,58 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
     ESC_STAMP(rec, 3);
 
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+
+    // Every conv item is resident (the host checked): publish the GAP partial sums of the
+    // pool tiles this tile covers, straight from LDS, instead of reading the plane twice.
+    if (p->pool_mode == kPoolFused) {
+        constexpr int NPT = TH / kPoolTileH;  // pool tiles stacked in this conv tile
+#pragma unroll
+        for (int h = 0; h < NPT; ++h) {
+            const unsigned pty = (unsigned)tyi * NPT + h;
+            if ((int)pty * kPoolTileH < H) {  // block-uniform
+                float s = 0.f;
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    const float *src = tile + (h * kPoolTileH + 2 * ty + a + PH) * PITCH + 4 * tx + PH;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) s += src[q];
+                }
+                const unsigned box = (nc * (unsigned)p->ptiles) + pty * (unsigned)p->ptiles_x + (unsigned)txi;
+                pool_finish(p, s, box, ctx.tag, s_dk);
+                __syncthreads();  // s_dk is reused
+            }
+        }
+    }
+
+    // Direct mode: ask for the pool sums, and for the estimator weights this channel
+    // needs, before the tap loop; look at the answers after it, so that their round trips
+    // cost nothing.
+    constexpr int kPer = (kDirectMaxBoxes + kPollThreads - 1) / kPollThreads;
+    const bool direct = p->dk_mode == kDkDirect;
+    const int nbox = p->Ca * p->ptiles;
+    const u64 *img_boxes = p->pool_box + (size_t)n * nbox;
+    const int Kin = p->hidden > 0 ? p->hidden : p->Ca;
+    const bool pre_w = direct && 9 * Kin <= kThreads && p->hidden * p->Ca <= kThreads;
+    u64 early[kPer];
+    float wup_r = 0.f, wdn_r = 0.f, bup_r = 0.f, bdn_r = 0.f;
+    auto ask_early = [&]() {
+        if (direct) {
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int f = (int)threadIdx.x + u * kPollThreads;
+                early[u] = 0;
+                if (threadIdx.x < kPollThreads && f < nbox)
+                    early[u] = __hip_atomic_load(img_boxes + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (pre_w) {
+                if ((int)threadIdx.x < 9 * Kin) wup_r = p->w_up[(size_t)c * 9 * Kin + threadIdx.x];
+                if ((int)threadIdx.x < p->hidden * p->Ca) wdn_r = p->w_down[threadIdx.x];
+                if (threadIdx.x < 9 && p->b_up) bup_r = p->b_up[c * 9 + threadIdx.x];
+                if ((int)threadIdx.x < p->hidden && p->b_down) bdn_r = p->b_down[threadIdx.x];
+            }
+        }
+    };
+
     float acc[RY][4];
 #pragma unroll
     for (int oy = 0; oy < RY; ++oy)
@@ -567,9 +732,12 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
 
     const float *trow = tile + (ty * RY) * PITCH + 4 * tx;
 
-#pragma unroll 1
-    for (int r = 0; r < RY + KS - 1; ++r) {
-        float v[NV];
+    // The tap loop, software-pipelined by hand so that the register use is ours to decide:
+    // while row r is multiplied, tile row r+1 is already on its way from LDS (two buffers),
+    // and kernel row r - the only new one - arrives while the older kernel rows, held in
+    // registers from the steps before, are applied first.  A scheduling barrier ends every
+    // step so the compiler cannot pull later rows' loads up and run out of registers.
+    auto load_x = [&](int r, float *v) {
         if (OFF == 0) {
             const float4 *src = reinterpret_cast<const float4 *>(trow + r * PITCH);
 #pragma unroll
@@ -585,26 +753,62 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
 #pragma unroll
             for (int k = 0; k < NV; ++k) v[k] = k < KS + 3 ? src[k] : 0.f;
         }
+    };
+    auto load_w = [&](int i, float *w) {
+        const float *wsrc = wl + i * WP;
 #pragma unroll
-        for (int oy = 0; oy < RY; ++oy) {
-            const int i = r - oy;  // kernel row that maps tile row r to output row oy
-            if (i >= 0 && i < KS) {
-                float w[WP];
-                const float4 *wsrc = reinterpret_cast<const float4 *>(wl + i * WP);
-#pragma unroll
-                for (int k = 0; k < WP / 4; ++k) {
-                    const float4 f = wsrc[k];
-                    w[4 * k + 0] = f.x;
-                    w[4 * k + 1] = f.y;
-                    w[4 * k + 2] = f.z;
-                    w[4 * k + 3] = f.w;
-                }
-#pragma unroll
-                for (int j = 0; j < KS; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) acc[oy][q] = fmaf(w[j], v[j + q], acc[oy][q]);
-            }
+        for (int k = 0; k + 4 <= KS; k += 4) {
+            const float4 f = *reinterpret_cast<const float4 *>(wsrc + k);
+            w[k + 0] = f.x;
+            w[k + 1] = f.y;
+            w[k + 2] = f.z;
+            w[k + 3] = f.w;
         }
+#pragma unroll
+        for (int k = KS & ~3; k < KS; ++k) w[k] = wsrc[k];
+    };
+    auto fma_row = [&](float *a, const float *w, const float *v) {
+#pragma unroll
+        for (int j = 0; j < KS; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) a[q] = fmaf(w[j], v[j + q], a[q]);
+    };
+    // what may move across a step boundary: arithmetic and global memory, not LDS traffic
+    constexpr int kSchedNoLds = 0x1 | 0x2 | 0x4 | 0x10 | 0x20 | 0x40;
+    constexpr bool kTwoX = 2 * NV + RY * KS + 4 * RY <= 104;  // room for a second tile-row buffer
+    float X[kTwoX ? 2 : 1][NV];
+    float Wt[RY][KS];  // kernel row i lives in slot i % RY while it is in use
+    if (kTwoX) load_x(0, X[0]);
+    auto step = [&](int r, int u) {  // u == r % RY, and RY is even
+        float *xc = X[kTwoX ? (u & 1) : 0];
+        if (kTwoX) {
+            if (r + 1 < G::ROWS) load_x(r + 1, X[(u + 1) & 1]);
+        } else {
+            load_x(r, xc);
+        }
+        if (r < KS) load_w(r, Wt[u]);
+#pragma unroll
+        for (int k = RY - 1; k >= 0; --k) {  // output row k of this thread: kernel row r - k
+            const int i = r - k;
+            if (i >= 0 && i < KS) fma_row(acc[k], Wt[(u - k + RY) % RY], xc);
+        }
+        __builtin_amdgcn_sched_barrier(kSchedNoLds);
+    };
+    // The early requests go out before the loop (in its middle they cost the compiler so
+    // many registers that it spills); whatever has not arrived by the end is asked for again.
+    ask_early();
+    if (G::UNROLL) {
+#pragma unroll
+        for (int r0 = 0; r0 < G::ROWS; r0 += RY)
+#pragma unroll
+            for (int u = 0; u < RY; ++u)
+                if (r0 + u < G::ROWS) step(r0 + u, u);
+    } else {
+#pragma unroll 1
+        for (int r0 = 0; r0 < G::ROWS; r0 += RY)
+#pragma unroll
+            for (int u = 0; u < RY; ++u)
+                if (r0 + u < G::ROWS) step(r0 + u, u);
     }
 #ifdef ESC_TRACE
 #pragma unroll
@@ -614,19 +818,45 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
 #endif
     ESC_STAMP(rec, 4);
 
-    if (p.dk_mode != kDkNone) {
-        const size_t dk_idx = ((size_t)n * p.Ca + c) * 9;
-        if (p.dk_mode == kDkDirect) estimator_front(p, ctx.tag, n, s_part, s_g, s_t);
+    // ---- phase 3: DK and the stores, located afresh (see opaque_u) ----
+    const ConvWhere wd = conv_where<TH>(p, opaque_u(item_in));
+    const int tid_d = opaque_tid();
+    const int tx_d = tid_d & 15, ty_d = tid_d >> 4;
+    const float *trow_d = tile + (ty_d * RY) * PITCH + 4 * tx_d;
+    T *op = (T *)p->out + wd.plane_off;
+
+    if (p->dk_mode != kDkNone) {
+        const size_t dk_idx = ((size_t)wd.n * p->Ca + wd.c) * 9;
+        float *s_wup = s_part + kDirectMaxBoxes, *s_wdn = s_part + kDirectMaxBoxes + kThreads;
+        if (direct) {
+            // same arithmetic, in the same order, as estimator_front + estimator_out
+            boxes_to_lds(img_boxes, nbox, s_part, ctx.tag, p->err, early, true);
+            if (pre_w) {
+                s_wup[tid_d] = wup_r;
+                s_wdn[tid_d] = wdn_r;
+            }
+            __syncthreads();
+            sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
+            __syncthreads();
+            if (p->hidden > 0) {
+                for (int m = tid_d; m < p->hidden; m += kThreads)
+                    s_t[m] = gelu_erf(pre_w ? dot_row(s_wdn + m * p->Ca, s_g, p->Ca, bdn_r)
+                                            : dot_row(p->w_down + (size_t)m * p->Ca, s_g, p->Ca,
+                                                      p->b_down ? p->b_down[m] : 0.f));
+                __syncthreads();
+            }
+        }
         ESC_STAMP(rec, 12);
-        if (threadIdx.x < 9) {
+        if (tid_d < 9) {
             float d;
-            if (p.dk_mode == kDkDirect)
-                d = estimator_out(p, c * 9 + (int)threadIdx.x, s_g, s_t);
-            else if (p.dk_mode == kDkBoxes)
-                d = box_get(p.dk_box + dk_idx + threadIdx.x, ctx.tag, p.err);
+            if (direct)
+                d = pre_w ? dot_row(s_wup + tid_d * Kin, p->hidden > 0 ? s_t : s_g, Kin, bup_r)
+                          : estimator_out(p, wd.c * 9 + tid_d, s_g, s_t);
+            else if (p->dk_mode == kDkBoxes)
+                d = box_get(p->dk_box + dk_idx + tid_d, ctx.tag, p->err);
             else
-                d = p.dk_in[dk_idx + threadIdx.x];
-            s_dk[threadIdx.x] = d;
+                d = p->dk_in[dk_idx + tid_d];
+            s_dk[tid_d] = d;
         }
         __syncthreads();
         ESC_STAMP(rec, 5);
@@ -636,7 +866,7 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
 #pragma unroll
         for (int r = 0; r < RY + 2; ++r) {
             float v[6];
-            const float *src = trow + (r + PH - 1) * PITCH + (PH - 1);
+            const float *src = trow_d + (r + PH - 1) * PITCH + (PH - 1);
 #pragma unroll
             for (int k = 0; k < 6; ++k) v[k] = src[k];
 #pragma unroll
@@ -653,13 +883,13 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
         }
     }
 
-    const int gx = x0 + 4 * tx;
+    const int gx = wd.x0 + 4 * tx_d;
 #pragma unroll
     for (int oy = 0; oy < RY; ++oy) {
-        const int gy = y0 + ty * RY + oy;
+        const int gy = wd.y0 + ty_d * RY + oy;
         if (gy >= H) continue;
         T *dst = op + (size_t)gy * W + gx;
-        if (p.conv_vec_ok && gx + 3 < W) {
+        if (p->conv_vec_ok && gx + 3 < W) {
             store4(dst, acc[oy]);
         } else {
 #pragma unroll
@@ -667,34 +897,41 @@ __device__ __forceinline__ void conv_item(const FwdParams &p, Ctx &ctx, unsigned
                 if (gx + q < W) store1(dst + q, acc[oy][q]);
         }
     }
+    ESC_STAMP(rec, 6);
+    return ItemOut{ctx, rec};
 }
 
 // ---------------------------------------------------------------------------
-// copy item (Eq. 4 lines 1 and 4): 16 KiB of one image's identity channels,
-// streamed with 16-byte non-temporal accesses when both sides allow it.
+// copy item (Eq. 4 lines 1 and 4): copy_chunk bytes of one image's identity
+// channels, streamed 16 KiB at a time with 16-byte non-temporal accesses when both
+// sides allow it.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void copy_item(const FwdParams &p, Ctx &ctx, unsigned item)
+__device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item)
 {
-    const unsigned n = fdiv(item, p.div_chunks);
-    const size_t chunk = (size_t)(item - n * p.div_chunks.d);
-    const char *src = (const char *)p.x + (size_t)n * p.img_bytes + p.idt_off;
-    char *dst = (char *)p.out + (size_t)n * p.img_bytes + p.idt_off;
-    const size_t len = p.idt_len;
-    const size_t begin = chunk * kCopyChunk;
-    const size_t end = begin + kCopyChunk < len ? begin + kCopyChunk : len;
-    const int eb = p.elem_bytes;
-    if (p.copy_vec_ok) {
-        u32x4 v[kCopyVecPerThread];
+    Trace rec;
+    ESC_TRACE_INIT(rec);
+    const unsigned n = fdiv(item, p->div_chunks.mul, p->div_chunks.shift);
+    const size_t chunk = (size_t)(item - n * p->div_chunks.d);
+    const char *src = (const char *)p->x + (size_t)n * p->img_bytes + p->idt_off;
+    char *dst = (char *)p->out + (size_t)n * p->img_bytes + p->idt_off;
+    const size_t len = p->idt_len;
+    const size_t begin = chunk * p->copy_chunk;
+    const size_t end = begin + p->copy_chunk < len ? begin + p->copy_chunk : len;
+    const int eb = p->elem_bytes;
+    if (p->copy_vec_ok) {
+        for (size_t piece = begin; piece < end; piece += kCopyPiece) {
+            u32x4 v[kCopyVecPerThread];
 #pragma unroll
-        for (int k = 0; k < kCopyVecPerThread; ++k) {
-            const size_t o = begin + ((size_t)k * kThreads + threadIdx.x) * 16;
-            if (o + 16 <= end) v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
-        }
-        announce_leave(p, ctx);
+            for (int k = 0; k < kCopyVecPerThread; ++k) {
+                const size_t o = piece + ((size_t)k * kThreads + threadIdx.x) * 16;
+                if (o + 16 <= end) v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
+            }
+            if (piece + kCopyPiece >= end) announce_leave(p, ctx);
 #pragma unroll
-        for (int k = 0; k < kCopyVecPerThread; ++k) {
-            const size_t o = begin + ((size_t)k * kThreads + threadIdx.x) * 16;
-            if (o + 16 <= end) __builtin_nontemporal_store(v[k], reinterpret_cast<u32x4 *>(dst + o));
+            for (int k = 0; k < kCopyVecPerThread; ++k) {
+                const size_t o = piece + ((size_t)k * kThreads + threadIdx.x) * 16;
+                if (o + 16 <= end) __builtin_nontemporal_store(v[k], reinterpret_cast<u32x4 *>(dst + o));
+            }
         }
         // a range that is not a multiple of 16 bytes ends with whole elements
         const size_t tail = len & ~(size_t)15;
@@ -716,6 +953,8 @@ __device__ __forceinline__ void copy_item(const FwdParams &p, Ctx &ctx, unsigned
                 *reinterpret_cast<uint16_t *>(dst + o) = *reinterpret_cast<const uint16_t *>(src + o);
         }
     }
+    ESC_STAMP(rec, 6);
+    return ItemOut{ctx, rec};
 }
 
 // ---------------------------------------------------------------------------
@@ -723,67 +962,90 @@ __device__ __forceinline__ void copy_item(const FwdParams &p, Ctx &ctx, unsigned
 // esc_dynkernel_gen and for C_a == 0).
 // ---------------------------------------------------------------------------
 template <int KS, int RY, typename T>
-__global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const FwdParams p)
+__global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const FwdParams params)
 {
-    using G = ConvGeom<(KS > 0 ? KS : 1), RY>;
-    __shared__ __align__(16) float tile[KS > 0 ? G::TILE_FLOATS : 4];
-    __shared__ __align__(16) float wl[KS > 0 ? G::W_FLOATS : 4];
-    __shared__ float s_part[kStage];
-    __shared__ float s_g[kMaxCa];
-    __shared__ float s_t[kMaxHidden];
-    __shared__ float s_small[16];
+    // the item functions are real calls, each with its own register allocation; they read
+    // the parameters from the kernel argument segment, which starts with `params`
+    (void)params;
+    ParamsPtr p = (ParamsPtr)__builtin_amdgcn_kernarg_segment_ptr();
 
-    const unsigned first_mixed = p.n_pool + p.n_gen;
-    const unsigned total = first_mixed + p.n_conv + p.n_copy;
+    // Blocks are handed to the chip's eight dies (XCDs, each with its own L2) round robin
+    // by block index.  Each die gets one contiguous eighth of every kind of item, so that
+    // neighbouring tiles - and the pool tiles over the same pixels - meet in one L2; inside
+    // a die, block number `slot` takes entries slot, slot + S, ... of the die's list.
+    const unsigned die = blockIdx.x % kXcds, slot = blockIdx.x / kXcds, S = gridDim.x / kXcds;
+    unsigned pool_base, pool_cnt, gen_base, gen_cnt, conv_base, conv_cnt, copy_base, copy_cnt;
+    die_share(p->n_pool, die, pool_base, pool_cnt);
+    die_share(p->n_gen, die, gen_base, gen_cnt);
+    die_share(p->n_conv, die, conv_base, conv_cnt);
+    die_share(p->n_copy, die, copy_base, copy_cnt);
+    // conv and copy entries alternate in groups of mix_a + mix_b while both last
+    const unsigned group = p->mix_a + p->mix_b;
+    unsigned groups = 0;
+    if (conv_cnt > 0 && copy_cnt > 0) {
+        const unsigned ga = fdiv(conv_cnt, p->div_mix_a.mul, p->div_mix_a.shift), gb = fdiv(copy_cnt, p->div_mix_b.mul, p->div_mix_b.shift);
+        groups = ga < gb ? ga : gb;
+    }
+    const unsigned first_mixed = pool_cnt + gen_cnt;
+    const unsigned total = first_mixed + conv_cnt + copy_cnt;
     Ctx ctx;
     ctx.tag = 0;
     ctx.have_tag = false;
     ctx.last_item = false;
     ctx.announced = false;
     ctx.left = 0;
-    for (unsigned item = blockIdx.x; item < total; item += gridDim.x) {
-        u64 *rec = nullptr;
-#ifdef ESC_TRACE
-        if (p.trace != nullptr) {
-            rec = p.trace + (size_t)item * 16;
-            if (threadIdx.x == 0) {
-                rec[0] = item;
-                rec[1] = ((u64)__builtin_amdgcn_s_getreg((31 << 11) | 4) << 32) | blockIdx.x;
-                rec[15] = __builtin_amdgcn_s_getreg((31 << 11) | 20);
-                rec[13] = clock64();
-            }
-        }
-#endif
-        ESC_STAMP(rec, 2);
-        ctx.last_item = item + gridDim.x >= total;
-        if (item < p.n_pool) {
-            pool_item<T>(p, ctx, item, s_small);
-        } else if (item < first_mixed) {
-            gen_item(p, ctx, item - p.n_pool, s_part, s_g, s_t, rec);
+    for (unsigned li = slot; li < total; li += S) {
+        // kind and index of this entry
+        int kind;  // 0 pool, 1 gen, 2 conv, 3 copy
+        unsigned idx;
+        if (li < pool_cnt) {
+            kind = 0;
+            idx = pool_base + li;
+        } else if (li < first_mixed) {
+            kind = 1;
+            idx = gen_base + (li - pool_cnt);
         } else {
-            const unsigned j = item - first_mixed;
-            const unsigned group = p.mix_a + p.mix_b;
+            const unsigned j = li - first_mixed;
             bool is_conv;
-            unsigned idx;
-            if (j < p.mix_groups * group) {
-                const unsigned g = fdiv(j, p.div_mix), r = j - g * group;
-                is_conv = r < p.mix_a;
-                idx = is_conv ? g * p.mix_a + r : g * p.mix_b + (r - p.mix_a);
+            unsigned local;
+            if (j < groups * group) {
+                const unsigned g = fdiv(j, p->div_mix.mul, p->div_mix.shift), r = j - g * group;
+                is_conv = r < p->mix_a;
+                local = is_conv ? g * p->mix_a + r : g * p->mix_b + (r - p->mix_a);
             } else {
-                const unsigned jj = j - p.mix_groups * group;
-                const unsigned conv_left = p.n_conv - p.mix_groups * p.mix_a;
+                const unsigned jj = j - groups * group;
+                const unsigned conv_left = conv_cnt - groups * p->mix_a;
                 is_conv = jj < conv_left;
-                idx = is_conv ? p.mix_groups * p.mix_a + jj : p.mix_groups * p.mix_b + (jj - conv_left);
+                local = is_conv ? groups * p->mix_a + jj : groups * p->mix_b + (jj - conv_left);
             }
-            if (is_conv) {
-                if constexpr (KS > 0) conv_item<KS, RY, T>(p, ctx, idx, tile, wl, s_small, s_part, s_g, s_t, rec);
-            } else {
-                copy_item(p, ctx, idx);
-            }
+            kind = is_conv ? 2 : 3;
+            idx = (is_conv ? conv_base : copy_base) + local;
         }
-        ESC_STAMP(rec, 6);
+        ctx.last_item = li + S >= total;
+        ItemOut o;
+        if (kind == 0) {
+            o = pool_item<T>(p, ctx, idx);
+        } else if (kind == 1) {
+            o = gen_item(p, ctx, idx);
+        } else if (kind == 2) {
+            if constexpr (KS > 0)
+                o = conv_item<KS, RY, T>(p, ctx, idx);
+            else
+                o.ctx = ctx;
+        } else {
+            o = copy_item(p, ctx, idx);
+        }
+        ctx = o.ctx;
 #ifdef ESC_TRACE
-        if (rec != nullptr && threadIdx.x == 0) rec[14] = clock64();
+        Trace &rec = o.rec;
+        if (p->trace != nullptr && threadIdx.x == 0) {
+            const unsigned gid = idx + (kind > 0 ? p->n_pool : 0) + (kind > 1 ? p->n_gen : 0) + (kind > 2 ? p->n_conv : 0);
+            rec.t[0] = gid;
+            rec.t[1] = ((u64)__builtin_amdgcn_s_getreg((31 << 11) | 4) << 32) | blockIdx.x;
+            rec.t[15] = __builtin_amdgcn_s_getreg((31 << 11) | 20);
+            rec.t[14] = clock64();
+            for (int k = 0; k < 16; ++k) p->trace[(size_t)gid * 16 + k] = rec.t[k];
+        }
 #endif
         __syncthreads();  // LDS is reused by the next item
     }
@@ -795,8 +1057,8 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
         const unsigned g = blockIdx.x % kGroups;
         const unsigned members = (gridDim.x - g + kGroups - 1) / kGroups;
         if (ctx.left == members - 1) {
-            __hip_atomic_store(p.done + g * kCtlStride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(p.epoch + g * kCtlStride, ctx.tag + 1u == 0u ? 1u : ctx.tag + 1u, __ATOMIC_RELAXED,
+            __hip_atomic_store(p->done + g * kCtlStride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p->epoch + g * kCtlStride, ctx.tag + 1u == 0u ? 1u : ctx.tag + 1u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         }
     }
@@ -822,7 +1084,7 @@ __global__ void ws_init_kernel(uint32_t *ptr, size_t words)
 // Host side
 // ---------------------------------------------------------------------------
 struct WsLayout {
-    int nslab;
+    int ptiles_x, ptiles;
     size_t ctl_off, pool_off, dk_off, total;
 };
 
@@ -833,12 +1095,13 @@ bool ws_layout(int N, int Ca, int H, int W, WsLayout *l)
     if (N < 1 || Ca < 0 || H < 1 || W < 1) return false;
     const size_t hw = (size_t)H * (size_t)W;
     if (hw >= ((size_t)1 << 31)) return false;
-    l->nslab = (int)((hw + kPoolSlab - 1) / kPoolSlab);
+    l->ptiles_x = (W + kPoolTileW - 1) / kPoolTileW;
+    l->ptiles = l->ptiles_x * ((H + kPoolTileH - 1) / kPoolTileH);
     size_t off = 0;
     l->ctl_off = off;
     off = round_up(off + kCtlWords * sizeof(uint32_t), kWsAlign);
     l->pool_off = off;
-    off = round_up(off + (size_t)N * Ca * l->nslab * sizeof(u64), kWsAlign);
+    off = round_up(off + (size_t)N * Ca * l->ptiles * sizeof(u64), kWsAlign);
     l->dk_off = off;
     off = round_up(off + (size_t)N * Ca * 9 * sizeof(u64), kWsAlign);
     l->total = off;
@@ -910,26 +1173,77 @@ int device_cus()
     return cus;
 }
 
-// conv and copy items alternate in small groups so that both kinds are in flight together
-void set_mix(FwdParams &p)
+// Lays the items out for the grid: how many blocks per die, whether the conv items can
+// pool for themselves, how big a copy item is and how conv and copy items alternate.
+// n_conv, n_gen and the pass-through range are set; n_pool holds the pool-item count that
+// applies if pooling is not fused.
+struct Plan {
+    unsigned per_die;
+};
+
+Plan plan_items(FwdParams &p, int Ks)
 {
-    unsigned a = 1, b = 1;
-    if (p.n_conv > 0 && p.n_copy > 0) {
-        if (p.n_conv >= p.n_copy) {
-            a = (p.n_conv + p.n_copy / 2) / p.n_copy;
-            if (a > 16) a = 16;
-        } else {
-            b = (p.n_copy + p.n_conv / 2) / p.n_conv;
-            if (b > 16) b = 16;
-        }
-        const unsigned ga = p.n_conv / a, gb = p.n_copy / b;
-        p.mix_groups = ga < gb ? ga : gb;
-    } else {
-        p.mix_groups = 0;
+    const unsigned U = (unsigned)device_cus() / kXcds;          // compute units per die
+    const unsigned Smax = (unsigned)kBlocksPerCu * (U ? U : 1);  // resident blocks per die
+    auto per_die_of = [](u64 n) { return (unsigned)((n + kXcds - 1) / kXcds); };
+
+    // all conv items (and the gen items they wait for) in the first round => fused pooling
+    if (p.pool_mode == kPoolItems && p.n_conv > 0 && per_die_of(p.n_conv) + per_die_of(p.n_gen) <= Smax) {
+        p.pool_mode = kPoolFused;
+        p.n_pool = 0;
     }
-    p.mix_a = a;
-    p.mix_b = b;
-    p.div_mix = make_div(a + b);
+
+    // rough time shares of the arithmetic and of the pass-through traffic decide how many of
+    // a compute unit's blocks should be convolving at any time: 3:1, 1:1 or 1:3
+    const double pix = (double)p.N * p.Ca * p.H * p.W;
+    const double t_valu = 2.0 * Ks * Ks * pix / 100e12;
+    const double t_copy = 2.0 * (double)p.N * (double)p.idt_len / 4.5e12;
+    unsigned a = 1, b = 1;
+    if (t_valu > 0 && t_copy > 0) {
+        const double share = t_valu / (t_valu + t_copy);
+        if (share < 0.375) b = 3;
+        if (share > 0.625) a = 3;
+    }
+
+    // copy items: as many as the pattern pairs with the conv items; if the whole call fits
+    // into one round of resident blocks, as many as still fit
+    p.n_copy = 0;
+    p.copy_chunk = kCopyPiece;
+    if (p.idt_len > 0) {
+        u64 want = p.n_conv > 0 ? (u64)p.n_conv * b / a : (u64)kXcds * Smax * 4;
+        const u64 others = (u64)p.n_pool + p.n_gen + p.n_conv;
+        const u64 resident = (u64)kXcds * Smax;
+        if (others + kXcds * 4 < resident && others + want > resident && (resident - others) * 4 >= want)
+            want = resident - others - kXcds * 3;  // the lists are rounded up per kind and die
+        if (want < 1) want = 1;
+        u64 per_img = (want + p.N / 2) / p.N;
+        if (per_img < 1) per_img = 1;
+        size_t chunk = (p.idt_len + per_img - 1) / per_img;
+        chunk = (chunk + kCopyPiece - 1) / kCopyPiece * kCopyPiece;
+        const size_t chunks = (p.idt_len + chunk - 1) / chunk;
+        p.copy_chunk = chunk;
+        p.div_chunks = make_div((uint32_t)chunks);
+        p.n_copy = (unsigned)(chunks * p.N);
+    }
+
+    // Alternation in layers of U entries, so that consecutive blocks - which the dispatcher
+    // spreads over a die's compute units - are of one kind and every unit gets every kind.
+    // With 3 resident layers and a pattern of 2 or 4 layers a block changes kind every round.
+    if (p.pool_mode == kPoolFused) {
+        p.mix_a = p.mix_b = 1u << 30;  // all conv items first: they must all be in the first round
+    } else {
+        p.mix_a = a * (U ? U : 1);
+        p.mix_b = b * (U ? U : 1);
+    }
+    p.div_mix = make_div(p.mix_a + p.mix_b);
+    p.div_mix_a = make_div(p.mix_a);
+    p.div_mix_b = make_div(p.mix_b);
+
+    Plan plan;
+    unsigned need = per_die_of(p.n_pool) + per_die_of(p.n_gen) + per_die_of(p.n_conv) + per_die_of(p.n_copy);
+    plan.per_die = need < Smax ? need : Smax;
+    if (plan.per_die < (unsigned)kGroups / kXcds) plan.per_die = kGroups / kXcds;  // every block group needs a member
+    return plan;
 }
 
 template <int KS, int RY, typename T>
@@ -937,26 +1251,12 @@ esc_status launch_variant(FwdParams &p, hipStream_t s)
 {
     // the kernel is compiled for kBlocksPerCu resident blocks per compute unit (register
     // budget via __launch_bounds__, LDS <= 40 KiB of 160 KiB), so this grid is co-resident
-    const int cus = device_cus();
-    if (cus < 1) return ESC_ERR_HIP;
-    const u64 total = (u64)p.n_pool + p.n_gen + p.n_conv + p.n_copy;
+    if (device_cus() < (int)kXcds) return ESC_ERR_HIP;
+    const u64 total = (u64)p.n_pool + p.n_gen + p.n_conv + (p.idt_len > 0 ? 1 : 0);
     if (total == 0) return ESC_OK;
-    if (total >= ((u64)1 << 30)) return ESC_ERR_UNSUPPORTED;  // item + grid must not wrap
-    set_mix(p);
-    const u64 cap = (u64)kBlocksPerCu * (u64)cus;
-    unsigned grid = (unsigned)(total < cap ? total : cap);
-    if (grid < (unsigned)kGroups) grid = kGroups;  // every group of blocks needs a member
-    // a block's items are grid apart: keep that stride coprime with the conv/copy pattern
-    const unsigned pattern = p.mix_a + p.mix_b;
-    auto gcd = [](unsigned a, unsigned b) {
-        while (b) {
-            const unsigned t = a % b;
-            a = b;
-            b = t;
-        }
-        return a;
-    };
-    while (total > grid && grid > (unsigned)kGroups && gcd(grid, pattern) != 1) --grid;
+    const Plan plan = plan_items(p, KS);
+    if ((u64)p.n_pool + p.n_gen + p.n_conv + p.n_copy >= ((u64)1 << 30)) return ESC_ERR_UNSUPPORTED;
+    const unsigned grid = plan.per_die * kXcds;
     hipLaunchKernelGGL((forward_kernel<KS, RY, T>), dim3(grid), dim3(kThreads), 0, s, p);
     return hipGetLastError() == hipSuccess ? ESC_OK : ESC_ERR_HIP;
 }
@@ -969,7 +1269,7 @@ esc_status launch_ks(FwdParams &p, hipStream_t s)
     } else {
         // taller register blocks once there is enough work to fill the chip several times over
         const size_t tiles4 = (size_t)((p.W + kTileW - 1) / kTileW) * ((p.H + 63) / 64) * p.N * p.Ca;
-        int ry = (tiles4 >= 2048 && KS <= 17) ? 4 : 2;
+        int ry = (tiles4 >= 1536 && KS <= 17) ? 4 : 2;
         if (conv_ry_override() == 2 || (conv_ry_override() == 4 && KS <= 17)) ry = conv_ry_override();
         const int th = 16 * ry;
         const int tiles_x = (p.W + kTileW - 1) / kTileW;
@@ -1025,25 +1325,28 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
     p.Ca = Ca;
     p.H = H;
     p.W = W;
-    p.nslab = l.nslab;
+    p.ptiles_x = l.ptiles_x;
+    p.ptiles = l.ptiles;
     p.hw = (float)((double)H * (double)W);
     p.elem_bytes = dt == ESC_F32 ? 4 : 2;
-    p.div_nslab = make_div((uint32_t)l.nslab);
+    p.div_ptiles = make_div((uint32_t)l.ptiles);
+    p.div_ptiles_x = make_div((uint32_t)l.ptiles_x);
+    // aligned 4-element chunk loads (halo tile, pool tile) need W % 4 == 0 and an aligned base
+    p.conv_ld_vec = (W % 4 == 0) && ((uintptr_t)x % (4 * (size_t)p.elem_bytes) == 0);
     p.div_ca = make_div((uint32_t)(Ca > 0 ? Ca : 1));
-    p.div_tiles_x = p.div_tiles_y = p.div_chunks = p.div_mix = make_div(1);
+    p.div_tiles_x = p.div_tiles_y = p.div_chunks = p.div_mix = p.div_mix_a = p.div_mix_b = make_div(1);
     if (gen != nullptr && Ca > 0) {
-        p.dk_mode = ((size_t)Ca * l.nslab <= (size_t)kDirectMaxBoxes) ? kDkDirect : kDkBoxes;
+        p.dk_mode = ((size_t)Ca * l.ptiles <= (size_t)kDirectMaxBoxes) ? kDkDirect : kDkBoxes;
+        p.pool_mode = kPoolItems;
         p.hidden = gen->hidden;
         p.w_down = gen->w_down;
         p.b_down = gen->b_down;
         p.w_up = gen->w_up;
         p.b_up = gen->b_up;
-        const size_t n_pool = (size_t)N * Ca * l.nslab;
+        const size_t n_pool = (size_t)N * Ca * l.ptiles;
         if (n_pool >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
         p.n_pool = (unsigned)n_pool;
         p.n_gen = p.dk_mode == kDkBoxes ? (unsigned)N : 0u;
-        const size_t plane_bytes = (size_t)H * W * p.elem_bytes;
-        p.pool_vec_ok = ((uintptr_t)x % 16 == 0) && (plane_bytes % 16 == 0);
     }
     char *w = (char *)workspace;
     p.err = (unsigned *)(w + l.ctl_off) + kCtlErrWord;
@@ -1146,8 +1449,6 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
     p.lk_cstride = lk_channel_stride;
     p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
     if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
-    // aligned 4-element chunk loads of the halo tile need W % 4 == 0 and an aligned base
-    p.conv_ld_vec = (W % 4 == 0) && (xa % (4 * es) == 0);
     // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
     p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
     if (C_a < C) {
@@ -1155,10 +1456,6 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
         p.img_bytes = plane * C;
         p.idt_off = plane * C_a;
         p.idt_len = plane * (C - C_a);
-        const size_t chunks = (p.idt_len + kCopyChunk - 1) / kCopyChunk;
-        if (chunks * (size_t)N >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
-        p.div_chunks = make_div((uint32_t)chunks);
-        p.n_copy = (unsigned)(chunks * N);
         p.copy_vec_ok = (xa % 16 == 0) && (oa % 16 == 0) && (p.img_bytes % 16 == 0) && (p.idt_off % 16 == 0);
     }
     const int ks_variant = C_a > 0 ? Ks : 0;
