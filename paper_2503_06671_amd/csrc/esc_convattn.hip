@@ -53,6 +53,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "esc_convattn.h"
 
 namespace {
@@ -218,11 +220,26 @@ __device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *d
     if (any) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Sum over the 64 lanes of a wavefront, returned in every lane.  Data-parallel-primitive
+// moves inside the vector ALU (a handful of cycles each; the LDS-crossbar shuffles they
+// replace cost over a hundred): an inclusive scan inside each row of 16 lanes, then the
+// row totals are carried over with the two row-broadcast steps; lane 63 ends with the
+// total.  The order of the additions is fixed, which is all the callers rely on.
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-    return v;
+    constexpr int kRowShr = 0x110, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+    auto dpp = [](float x, auto ctrl, auto row_mask) {
+        return __builtin_bit_cast(
+            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value,
+                                               decltype(row_mask)::value, 0xf, false));
+    };
+    v += dpp(v, std::integral_constant<int, kRowShr + 1>{}, std::integral_constant<int, 0xf>{});
+    v += dpp(v, std::integral_constant<int, kRowShr + 2>{}, std::integral_constant<int, 0xf>{});
+    v += dpp(v, std::integral_constant<int, kRowShr + 4>{}, std::integral_constant<int, 0xf>{});
+    v += dpp(v, std::integral_constant<int, kRowShr + 8>{}, std::integral_constant<int, 0xf>{});
+    v += dpp(v, std::integral_constant<int, kRowBcast15>{}, std::integral_constant<int, 0xa>{});
+    v += dpp(v, std::integral_constant<int, kRowBcast31>{}, std::integral_constant<int, 0xc>{});
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // ---------------------------------------------------------------------------
@@ -433,6 +450,16 @@ __device__ __forceinline__ float dot_row(const float *w, const float *in, int K,
         for (int u = 0; u < 8; ++u)
             if (k0 + u < K) s = fmaf(wv[u], in[k0 + u], s);
     }
+    return s;
+}
+
+// The same for a weight row and an input vector that both sit in LDS.
+typedef const __attribute__((address_space(3))) float *LdsFloats;
+__device__ __forceinline__ float dot_row_lds(const float *w_, const float *in_, int K, float bias)
+{
+    LdsFloats w = (LdsFloats)w_, in = (LdsFloats)in_;
+    float s = bias;
+    for (int k = 0; k < K; ++k) s = fmaf(w[k], in[k], s);
     return s;
 }
 
@@ -787,10 +814,22 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             load_x(r, xc);
         }
         if (r < KS) load_w(r, Wt[u]);
+        if (r >= RY - 1 && r < KS) {
+            // every output row of the thread takes part: interleave them tap by tap, oldest
+            // kernel row first, so that 4*RY independent accumulators are in flight
 #pragma unroll
-        for (int k = RY - 1; k >= 0; --k) {  // output row k of this thread: kernel row r - k
-            const int i = r - k;
-            if (i >= 0 && i < KS) fma_row(acc[k], Wt[(u - k + RY) % RY], xc);
+            for (int j = 0; j < KS; ++j)
+#pragma unroll
+                for (int k = RY - 1; k >= 0; --k)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[k][q] = fmaf(Wt[(u - k + RY) % RY][j], xc[j + q], acc[k][q]);
+        } else {
+#pragma unroll
+            for (int k = RY - 1; k >= 0; --k) {  // output row k of this thread: kernel row r - k
+                const int i = r - k;
+                if (i >= 0 && i < KS) fma_row(acc[k], Wt[(u - k + RY) % RY], xc);
+            }
         }
         __builtin_amdgcn_sched_barrier(kSchedNoLds);
     };
@@ -804,11 +843,22 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             for (int u = 0; u < RY; ++u)
                 if (r0 + u < G::ROWS) step(r0 + u, u);
     } else {
-#pragma unroll 1
-        for (int r0 = 0; r0 < G::ROWS; r0 += RY)
+        // Large kernels: a loop, two rows per trip; the kernel rows are re-read from LDS for
+        // every output row instead of being held (they would not fit in the registers).
+#pragma unroll 2
+        for (int r = 0; r < G::ROWS; ++r) {
+            float xr[NV];
+            load_x(r, xr);
 #pragma unroll
-            for (int u = 0; u < RY; ++u)
-                if (r0 + u < G::ROWS) step(r0 + u, u);
+            for (int k = 0; k < RY; ++k) {
+                const int i = r - k;
+                if (i >= 0 && i < KS) {
+                    float wr[KS];
+                    load_w(i, wr);
+                    fma_row(acc[k], wr, xr);
+                }
+            }
+        }
     }
 #ifdef ESC_TRACE
 #pragma unroll
@@ -831,16 +881,19 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         if (direct) {
             // same arithmetic, in the same order, as estimator_front + estimator_out
             boxes_to_lds(img_boxes, nbox, s_part, ctx.tag, p->err, early, true);
+            ESC_STAMP(rec, 7);
             if (pre_w) {
                 s_wup[tid_d] = wup_r;
                 s_wdn[tid_d] = wdn_r;
             }
             __syncthreads();
+            ESC_STAMP(rec, 8);
             sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
             __syncthreads();
+            ESC_STAMP(rec, 9);
             if (p->hidden > 0) {
                 for (int m = tid_d; m < p->hidden; m += kThreads)
-                    s_t[m] = gelu_erf(pre_w ? dot_row(s_wdn + m * p->Ca, s_g, p->Ca, bdn_r)
+                    s_t[m] = gelu_erf(pre_w ? dot_row_lds(s_wdn + m * p->Ca, s_g, p->Ca, bdn_r)
                                             : dot_row(p->w_down + (size_t)m * p->Ca, s_g, p->Ca,
                                                       p->b_down ? p->b_down[m] : 0.f));
                 __syncthreads();
@@ -850,7 +903,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         if (tid_d < 9) {
             float d;
             if (direct)
-                d = pre_w ? dot_row(s_wup + tid_d * Kin, p->hidden > 0 ? s_t : s_g, Kin, bup_r)
+                d = pre_w ? dot_row_lds(s_wup + tid_d * Kin, p->hidden > 0 ? s_t : s_g, Kin, bup_r)
                           : estimator_out(p, wd.c * 9 + tid_d, s_g, s_t);
             else if (p->dk_mode == kDkBoxes)
                 d = box_get(p->dk_box + dk_idx + tid_d, ctx.tag, p->err);
