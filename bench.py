@@ -26,9 +26,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
-FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CU x 2.4 GHz x 256 flop/clk (needs packed fp32 issue)
-FP32_UNPACKED_PEAK_TFLOPS = 78.6  # what one v_fma_f32 per lane per clock can reach
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, vendor figure
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CU x 2.4 GHz x 256 flop/clk
+
+# HBM bytes per launch of the forward kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled against a plain copy of known size (see the summaries under profiles/).
+MEASURED_TRAFFIC_BYTES = {
+    "cfg1_hd_x4_180x320_f32": 30.07e6,  # profiles/forward_kernel_ks13_f32_cfg1_180x320.txt
+}
 
 
 def parse_args():
@@ -127,8 +132,10 @@ def main():
     ms_total = ev0.elapsed_time(ev1)
     ms_step = ms_total / args.steps
 
-    # spot check of the last buffers against the first (same input => same bits)
+    # spot check of the last buffers against the first (same input => same bits), and no
+    # bounded wait inside the kernel may have expired
     assert torch.equal(outs[0], outs[(args.steps - 1) % pairs]), "rotating buffers disagree"
+    assert binding.workspace_errors(ws, stream) == 0, "a wait inside the kernel expired"
 
     sec = ms_step * 1e-3
     res = {
@@ -149,16 +156,20 @@ def main():
                    "cache": "warm" if args.warm_cache else "rotating"},
         "hbm_gbps_algorithmic": b_alg / sec / 1e9,
         "valu_tflops": f_alg / sec / 1e12,
+        # one step is one launch of the single forward kernel, so the per-launch duration is
+        # the HIP-event time of the timed region divided by the number of launches
         "roofline": {
             "bound": "hbm",
-            "kernel": "esc_convattn_forward (all kernels of one step)",
+            "kernel": f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)",
             "achieved": b_alg / sec / 1e9,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": b_alg / sec / 1e9 / HBM_PEAK_GBS,
-            "traffic": None,
-            "alu_frac_packed_peak": f_alg / sec / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
-            "alu_frac_unpacked_peak": f_alg / sec / 1e12 / FP32_UNPACKED_PEAK_TFLOPS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if not args.warm_cache else None,
+            "algorithmic_bytes": b_alg,
+            "kernel_us": ms_step * 1e3,
+            "alu_tflops": f_alg / sec / 1e12,
+            "alu_frac_of_fp32_vector_peak": f_alg / sec / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
         },
     }
     if not args.no_cpu_baseline:
