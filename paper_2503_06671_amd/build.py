@@ -11,10 +11,13 @@ SRC = os.path.join(HERE, "csrc", "esc_convattn.hip")
 LIB = os.path.join(HERE, "csrc", "libesc_convattn.so")
 
 # packed-fp32 instructions are switched off on purpose: some of their forms have
-# produced silently wrong results on the target machines
+# produced silently wrong results on the target machines.  The compiler's wavefront-level
+# rewrite of atomics is switched off too: it reads the atomic's result back at once, and
+# the kernel issues its one returning atomic per block early precisely so as not to wait.
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-ffp-contract=off", "-Wall", "-Wno-unused-command-line-argument",
     "-I", os.path.join(ROOT, "include"),
 ]

@@ -162,6 +162,21 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t x, uint32_t mul, uint32_t shif
     return (__umulhi(x, mul) + x) >> shift;
 }
 
+// Values hidden from the optimiser: what is computed from them cannot be moved above the
+// point where they are made, which keeps a later phase's addresses out of the registers of
+// an earlier one.
+__device__ __forceinline__ unsigned opaque_u(unsigned v)
+{
+    asm volatile("" : "+s"(v));
+    return v;
+}
+__device__ __forceinline__ int opaque_tid()
+{
+    int t = (int)threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
 // ---------------------------------------------------------------------------
 // mailboxes
 // ---------------------------------------------------------------------------
@@ -190,17 +205,17 @@ template <int PER>
 __device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *dst, uint32_t tag, unsigned *err,
                                              u64 (&v)[PER], bool have_first)
 {
+    const int tid = opaque_tid();
     bool pend[PER];
 #pragma unroll
-    for (int u = 0; u < PER; ++u)
-        pend[u] = threadIdx.x < kPollThreads && (int)threadIdx.x + u * kPollThreads < cnt;
+    for (int u = 0; u < PER; ++u) pend[u] = tid < kPollThreads && tid + u * kPollThreads < cnt;
     bool any = false;
     for (unsigned spin = 0; spin < kSpinLimit; ++spin) {
         if (spin > 0 || !have_first) {
 #pragma unroll
             for (int u = 0; u < PER; ++u)
                 if (pend[u])
-                    v[u] = __hip_atomic_load(boxes + threadIdx.x + u * kPollThreads, __ATOMIC_RELAXED,
+                    v[u] = __hip_atomic_load(boxes + tid + u * kPollThreads, __ATOMIC_RELAXED,
                                              __HIP_MEMORY_SCOPE_AGENT);
         }
         any = false;
@@ -208,7 +223,7 @@ __device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *d
         for (int u = 0; u < PER; ++u)
             if (pend[u]) {
                 if ((uint32_t)(v[u] >> 32) == tag) {
-                    dst[threadIdx.x + u * kPollThreads] = __uint_as_float((uint32_t)v[u]);
+                    dst[tid + u * kPollThreads] = __uint_as_float((uint32_t)v[u]);
                     pend[u] = false;
                 } else {
                     any = true;
@@ -240,6 +255,21 @@ __device__ __forceinline__ float wave_sum(float v)
     v += dpp(v, std::integral_constant<int, kRowBcast15>{}, std::integral_constant<int, 0xa>{});
     v += dpp(v, std::integral_constant<int, kRowBcast31>{}, std::integral_constant<int, 0xc>{});
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// Running sum along each row of 16 lanes (lane 15 of a row ends with the row's total).
+__device__ __forceinline__ float row_sum(float v)
+{
+    constexpr int kRowShr = 0x110;
+    auto dpp = [](float x, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x),
+                                                                     decltype(ctrl)::value, 0xf, 0xf, false));
+    };
+    v += dpp(v, std::integral_constant<int, kRowShr + 1>{});
+    v += dpp(v, std::integral_constant<int, kRowShr + 2>{});
+    v += dpp(v, std::integral_constant<int, kRowShr + 4>{});
+    v += dpp(v, std::integral_constant<int, kRowShr + 8>{});
+    return v;
 }
 
 // ---------------------------------------------------------------------------
@@ -286,6 +316,7 @@ struct FwdParams {
     unsigned *err;       // raised when a bounded wait expires
     unsigned *epoch;     // [kGroups] call counters (kCtlStride words apart) = tag of the current call
     unsigned *done;      // [kGroups] blocks of the group that have announced their leave
+    int copy_delay;      // experiment
     u64 *trace;          // development builds only
 };
 
@@ -395,7 +426,8 @@ __device__ __forceinline__ ItemOut pool_item(ParamsPtr p, Ctx ctx, unsigned item
     const unsigned n = fdiv(nc, p->div_ca.mul, p->div_ca.shift);
     const unsigned c = nc - n * (unsigned)p->Ca;
     const T *plane = (const T *)p->x + ((size_t)n * p->C + c) * (size_t)H * (size_t)W;
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int tid = opaque_tid();
+    const int tx = tid & 15, ty = tid >> 4;
     const int gx = (int)ptx * kPoolTileW + 4 * tx, gy = (int)pty * kPoolTileH + 2 * ty;
     float v[2][4];
 #pragma unroll
@@ -459,14 +491,40 @@ __device__ __forceinline__ float dot_row_lds(const float *w_, const float *in_, 
 {
     LdsFloats w = (LdsFloats)w_, in = (LdsFloats)in_;
     float s = bias;
-    for (int k = 0; k < K; ++k) s = fmaf(w[k], in[k], s);
+    for (int k0 = 0; k0 < K; k0 += 4) {  // operands first, so that their latencies overlap
+        float wv[4], iv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = k0 + u < K ? k0 + u : K - 1;
+            wv[u] = w[k];
+            iv[u] = in[k];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s = k0 + u < K ? fmaf(wv[u], iv[u], s) : s;
+    }
     return s;
 }
 
-// Wavefront w adds the staged partial sums of channels w, w+4, ... < gc of a round that
-// starts at channel c0: lane l adds tiles l, l+64, ... ascending, then the wavefront tree.
+// Channel means from the staged partial sums of a round that starts at channel c0.  The
+// order of the additions depends on the tile count alone.  Many tiles: wavefront w takes
+// channels w, w+4, ... < gc; lane l adds tiles l, l+64, ... ascending, then the wavefront
+// tree.
 __device__ __forceinline__ void sum_staged(const float *s_part, int ntile, int gc, int c0, float hw, float *s_g)
 {
+    if (ntile <= 64) {
+        // few tiles: a row of 16 lanes per channel, sixteen channels of the block at once;
+        // lane r adds tiles r, r+16, ... ascending, then the row's running sum
+        LdsFloats part = (LdsFloats)s_part;
+        const int tid = opaque_tid();
+        const int r = tid & 15;
+        for (int cg = tid >> 4; cg < gc; cg += kThreads / 16) {
+            float s = 0.f;
+            for (int k = r; k < ntile; k += 16) s += part[cg * ntile + k];
+            s = row_sum(s);
+            if (r == 15) s_g[c0 + cg] = s / hw;
+        }
+        return;
+    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int cg = wave; cg < gc; cg += kThreads / 64) {
         float s = 0.f;
@@ -574,21 +632,6 @@ struct ConvGeom {
     static constexpr bool UNROLL = KS * KS * RY <= 13 * 13 * 4;
 };
 
-// Values hidden from the optimiser: what is computed from them cannot be moved above the
-// point where they are made, which keeps a later phase's addresses out of the registers of
-// an earlier one.
-__device__ __forceinline__ unsigned opaque_u(unsigned v)
-{
-    asm volatile("" : "+s"(v));
-    return v;
-}
-__device__ __forceinline__ int opaque_tid()
-{
-    int t = (int)threadIdx.x;
-    asm volatile("" : "+v"(t));
-    return t;
-}
-
 // where a conv item lies
 struct ConvWhere {
     unsigned n, nc;
@@ -633,10 +676,13 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // this channel's weights, fetched together with the tile
     constexpr int KW = (KS * KS + kThreads - 1) / kThreads;
     const float *lkc = p->lk + (size_t)c * p->lk_cstride;
+    // (thread indices are taken afresh in every phase, so that nothing derived from them
+    // is computed once per kernel and then held in registers through all items)
+    const int tid1 = opaque_tid();
     float wreg[KW];
 #pragma unroll
     for (int m = 0; m < KW; ++m) {
-        const int idx = m * kThreads + (int)threadIdx.x;
+        const int idx = m * kThreads + tid1;
         wreg[m] = idx < KS * KS ? lkc[idx] : 0.f;
     }
 
@@ -653,7 +699,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         float v[K][4];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            const int q = k * kThreads + (int)threadIdx.x;
+            const int q = k * kThreads + tid1;
             const int r = q / NCH, j = q - r * NCH;
             const int gy = y0 - PH + r, gx = g0 + 4 * j;
 #pragma unroll
@@ -661,10 +707,9 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             if (q < TOT && gy >= 0 && gy < H && gx >= 0 && gx < W) load4(xp + (size_t)gy * W + gx, v[k]);
         }
         if (p->pool_mode != kPoolNone) need_tag(p, ctx);
-        announce_leave(p, ctx);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            const int q = k * kThreads + (int)threadIdx.x;
+            const int q = k * kThreads + tid1;
             const int r = q / NCH, j = q - r * NCH;
             if (q < TOT) {
                 float *dst = tile + r * PITCH + 4 * j - A;
@@ -680,7 +725,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             }
         }
     } else {
-        for (int idx = threadIdx.x; idx < HR * HC; idx += kThreads) {
+        for (int idx = tid1; idx < HR * HC; idx += kThreads) {
             const int r = idx / HC, cc = idx - r * HC;
             const int gy = y0 - PH + r, gx = x0 - PH + cc;
             float v = 0.f;
@@ -688,17 +733,17 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             tile[r * PITCH + cc] = v;
         }
         if (p->pool_mode != kPoolNone) need_tag(p, ctx);
-        announce_leave(p, ctx);
     }
 #pragma unroll
     for (int m = 0; m < KW; ++m) {
-        const int idx = m * kThreads + (int)threadIdx.x;
+        const int idx = m * kThreads + tid1;
         if (idx < KS * KS) wl[(idx / KS) * WP + idx % KS] = wreg[m];
     }
     __syncthreads();
     ESC_STAMP(rec, 3);
 
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int tid2 = opaque_tid();
+    const int tx = tid2 & 15, ty = tid2 >> 4;
 
     // Every conv item is resident (the host checked): publish the GAP partial sums of the
     // pool tiles this tile covers, straight from LDS, instead of reading the plane twice.
@@ -737,17 +782,32 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         if (direct) {
 #pragma unroll
             for (int u = 0; u < kPer; ++u) {
-                const int f = (int)threadIdx.x + u * kPollThreads;
+                const int f = tid2 + u * kPollThreads;
                 early[u] = 0;
-                if (threadIdx.x < kPollThreads && f < nbox)
+                if (!G::UNROLL && tid2 < kPollThreads && f < nbox)
                     early[u] = __hip_atomic_load(img_boxes + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             if (pre_w) {
-                if ((int)threadIdx.x < 9 * Kin) wup_r = p->w_up[(size_t)c * 9 * Kin + threadIdx.x];
-                if ((int)threadIdx.x < p->hidden * p->Ca) wdn_r = p->w_down[threadIdx.x];
-                if (threadIdx.x < 9 && p->b_up) bup_r = p->b_up[c * 9 + threadIdx.x];
-                if ((int)threadIdx.x < p->hidden && p->b_down) bdn_r = p->b_down[threadIdx.x];
+                if (tid2 < 9 * Kin) wup_r = p->w_up[(size_t)c * 9 * Kin + tid2];
+                if (tid2 < p->hidden * p->Ca) wdn_r = p->w_down[tid2];
+                if (tid2 < 9 && p->b_up) bup_r = p->b_up[c * 9 + tid2];
+                if (tid2 < p->hidden && p->b_down) bdn_r = p->b_down[tid2];
             }
+        }
+    };
+
+    // Asked again part-way through the tap loop: by then the other blocks have published,
+    // so the answers are back when the loop ends.  Addresses are made on the spot.
+    auto ask_again = [&]() {
+        // no branch here (one would split the loop body and cost registers): every thread
+        // reads some mailbox of the image, whichever mode the call is in
+        const int t = opaque_tid();
+        const u64 *bx = p->pool_box + (size_t)opaque_u(n) * nbox;
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            int f = t + u * kPollThreads;
+            f = f < nbox ? f : nbox - 1;
+            early[u] = __hip_atomic_load(bx + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     };
 
@@ -833,6 +893,10 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         }
         __builtin_amdgcn_sched_barrier(kSchedNoLds);
     };
+    // The leave is announced here: the announcing wavefront's atomic is then in flight
+    // during the tap loop, which waits for no memory access (anywhere earlier, the next
+    // wait for a load would wait for the atomic as well - results return in order).
+    announce_leave(p, ctx);
     // The early requests go out before the loop (in its middle they cost the compiler so
     // many registers that it spills); whatever has not arrived by the end is asked for again.
     ask_early();
@@ -841,7 +905,10 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         for (int r0 = 0; r0 < G::ROWS; r0 += RY)
 #pragma unroll
             for (int u = 0; u < RY; ++u)
-                if (r0 + u < G::ROWS) step(r0 + u, u);
+                if (r0 + u < G::ROWS) {
+                    if (r0 + u == (G::ROWS * 5) / 8) ask_again();
+                    step(r0 + u, u);
+                }
     } else {
         // Large kernels: a loop, two rows per trip; the kernel rows are re-read from LDS for
         // every output row instead of being held (they would not fit in the registers).
@@ -972,17 +1039,55 @@ __device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item
     const size_t end = begin + p->copy_chunk < len ? begin + p->copy_chunk : len;
     const int eb = p->elem_bytes;
     if (p->copy_vec_ok) {
-        for (size_t piece = begin; piece < end; piece += kCopyPiece) {
+        // Whole pieces move without a condition per access (a guarded load ends up in a basic
+        // block of its own and the compiler then waits for each before the next is issued),
+        // the next piece's loads going out before this piece's stores.
+        const size_t nfull = (end - begin) / kCopyPiece;
+        const size_t rest = begin + nfull * kCopyPiece;  // start of the partial piece, if any
+        const size_t lane_off = (size_t)opaque_tid() * 16;
+        if (nfull > 0) {
+            u32x4 v[kCopyVecPerThread], w[kCopyVecPerThread];
+            auto fetch = [&](u32x4 *r, size_t i) {
+#pragma unroll
+                for (int k = 0; k < kCopyVecPerThread; ++k)
+                    r[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(
+                        src + begin + i * kCopyPiece + (size_t)k * kThreads * 16 + lane_off));
+            };
+            auto put = [&](const u32x4 *r, size_t i) {
+#pragma unroll
+                for (int k = 0; k < kCopyVecPerThread; ++k)
+                    __builtin_nontemporal_store(r[k], reinterpret_cast<u32x4 *>(
+                        dst + begin + i * kCopyPiece + (size_t)k * kThreads * 16 + lane_off));
+            };
+            // two pieces per trip, the register sets swapping roles (copying one set into the
+            // other would wait for its loads on the spot)
+            fetch(v, 0);
+            for (size_t i = 0;; i += 2) {
+                if (i + 1 < nfull)
+                    fetch(w, i + 1);
+                else if (rest >= end)
+                    announce_leave(p, ctx);  // the item's last loads are out
+                put(v, i);
+                if (i + 1 >= nfull) break;
+                if (i + 2 < nfull)
+                    fetch(v, i + 2);
+                else if (rest >= end)
+                    announce_leave(p, ctx);
+                put(w, i + 1);
+                if (i + 2 >= nfull) break;
+            }
+        }
+        if (rest < end) {  // at most one partial piece per call and image
             u32x4 v[kCopyVecPerThread];
 #pragma unroll
             for (int k = 0; k < kCopyVecPerThread; ++k) {
-                const size_t o = piece + ((size_t)k * kThreads + threadIdx.x) * 16;
+                const size_t o = rest + (size_t)k * kThreads * 16 + lane_off;
                 if (o + 16 <= end) v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
             }
-            if (piece + kCopyPiece >= end) announce_leave(p, ctx);
+            announce_leave(p, ctx);
 #pragma unroll
             for (int k = 0; k < kCopyVecPerThread; ++k) {
-                const size_t o = piece + ((size_t)k * kThreads + threadIdx.x) * 16;
+                const size_t o = rest + (size_t)k * kThreads * 16 + lane_off;
                 if (o + 16 <= end) __builtin_nontemporal_store(v[k], reinterpret_cast<u32x4 *>(dst + o));
             }
         }
@@ -1086,6 +1191,8 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
             else
                 o.ctx = ctx;
         } else {
+            if (li == slot)
+                for (int i = 0; i < p->copy_delay; ++i) __builtin_amdgcn_s_sleep(8);
             o = copy_item(p, ctx, idx);
         }
         ctx = o.ctx;
@@ -1214,6 +1321,12 @@ int conv_ry_override()
     return v;
 }
 
+int copy_delay_override()
+{
+    const char *e = getenv("ESC_COPY_DELAY");  // read every call (experiment)
+    return e ? atoi(e) : 0;
+}
+
 int device_cus()
 {
     static int cus = [] {
@@ -1249,7 +1362,7 @@ Plan plan_items(FwdParams &p, int Ks)
     // rough time shares of the arithmetic and of the pass-through traffic decide how many of
     // a compute unit's blocks should be convolving at any time: 3:1, 1:1 or 1:3
     const double pix = (double)p.N * p.Ca * p.H * p.W;
-    const double t_valu = 2.0 * Ks * Ks * pix / 100e12;
+    const double t_valu = 2.0 * Ks * Ks * pix / 50e12;  // what a conv item sustains, its loads included
     const double t_copy = 2.0 * (double)p.N * (double)p.idt_len / 4.5e12;
     unsigned a = 1, b = 1;
     if (t_valu > 0 && t_copy > 0) {
@@ -1261,6 +1374,7 @@ Plan plan_items(FwdParams &p, int Ks)
     // copy items: as many as the pattern pairs with the conv items; if the whole call fits
     // into one round of resident blocks, as many as still fit
     p.n_copy = 0;
+    p.copy_delay = copy_delay_override();
     p.copy_chunk = kCopyPiece;
     if (p.idt_len > 0) {
         u64 want = p.n_conv > 0 ? (u64)p.n_conv * b / a : (u64)kXcds * Smax * 4;
