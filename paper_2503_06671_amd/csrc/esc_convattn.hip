@@ -316,7 +316,12 @@ struct FwdParams {
     unsigned *err;       // raised when a bounded wait expires
     unsigned *epoch;     // [kGroups] call counters (kCtlStride words apart) = tag of the current call
     unsigned *done;      // [kGroups] blocks of the group that have announced their leave
-    int copy_delay;      // experiment
+    // Every conv item is resident from the start (fused pooling) and the call is so short
+    // that the conv items' chain of load, taps, estimator and store is what it lasts: the
+    // copy items then keep little in flight, so that the conv items' few accesses (tile,
+    // mailboxes) come back quickly; measured, a full-rate copy beside them costs more than
+    // it saves.
+    int copy_gentle;
     u64 *trace;          // development builds only
 };
 
@@ -491,16 +496,16 @@ __device__ __forceinline__ float dot_row_lds(const float *w_, const float *in_, 
 {
     LdsFloats w = (LdsFloats)w_, in = (LdsFloats)in_;
     float s = bias;
-    for (int k0 = 0; k0 < K; k0 += 4) {  // operands first, so that their latencies overlap
-        float wv[4], iv[4];
+    for (int k0 = 0; k0 < K; k0 += 16) {  // operands first, so that their latencies overlap
+        float wv[16], iv[16];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 16; ++u) {
             const int k = k0 + u < K ? k0 + u : K - 1;
             wv[u] = w[k];
             iv[u] = in[k];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) s = k0 + u < K ? fmaf(wv[u], iv[u], s) : s;
+        for (int u = 0; u < 16; ++u) s = k0 + u < K ? fmaf(wv[u], iv[u], s) : s;
     }
     return s;
 }
@@ -1045,7 +1050,23 @@ __device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item
         const size_t nfull = (end - begin) / kCopyPiece;
         const size_t rest = begin + nfull * kCopyPiece;  // start of the partial piece, if any
         const size_t lane_off = (size_t)opaque_tid() * 16;
-        if (nfull > 0) {
+        if (p->copy_gentle) {
+            // one access per thread in flight
+            const size_t nvec = (end - begin) / (kThreads * 16);
+            for (size_t i = 0; i < nvec; ++i) {
+                const size_t o = begin + i * kThreads * 16 + lane_off;
+                const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
+                if (i + 1 == nvec && begin + nvec * kThreads * 16 >= end) announce_leave(p, ctx);
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(dst + o));
+            }
+            const size_t o = begin + nvec * kThreads * 16 + lane_off;
+            if (begin + nvec * kThreads * 16 < end) {
+                u32x4 v = {};
+                if (o + 16 <= end) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + o));
+                announce_leave(p, ctx);
+                if (o + 16 <= end) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(dst + o));
+            }
+        } else if (nfull > 0) {
             u32x4 v[kCopyVecPerThread], w[kCopyVecPerThread];
             auto fetch = [&](u32x4 *r, size_t i) {
 #pragma unroll
@@ -1077,7 +1098,7 @@ __device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item
                 if (i + 2 >= nfull) break;
             }
         }
-        if (rest < end) {  // at most one partial piece per call and image
+        if (!p->copy_gentle && rest < end) {  // at most one partial piece per call and image
             u32x4 v[kCopyVecPerThread];
 #pragma unroll
             for (int k = 0; k < kCopyVecPerThread; ++k) {
@@ -1191,8 +1212,6 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
             else
                 o.ctx = ctx;
         } else {
-            if (li == slot)
-                for (int i = 0; i < p->copy_delay; ++i) __builtin_amdgcn_s_sleep(8);
             o = copy_item(p, ctx, idx);
         }
         ctx = o.ctx;
@@ -1321,12 +1340,6 @@ int conv_ry_override()
     return v;
 }
 
-int copy_delay_override()
-{
-    const char *e = getenv("ESC_COPY_DELAY");  // read every call (experiment)
-    return e ? atoi(e) : 0;
-}
-
 int device_cus()
 {
     static int cus = [] {
@@ -1371,10 +1384,12 @@ Plan plan_items(FwdParams &p, int Ks)
         if (share > 0.625) a = 3;
     }
 
+    // short calls (the conv items' own chain is most of them): gentle, gated copying
+    p.copy_gentle = p.pool_mode == kPoolFused && p.dk_mode == kDkDirect;
+
     // copy items: as many as the pattern pairs with the conv items; if the whole call fits
     // into one round of resident blocks, as many as still fit
     p.n_copy = 0;
-    p.copy_delay = copy_delay_override();
     p.copy_chunk = kCopyPiece;
     if (p.idt_len > 0) {
         u64 want = p.n_conv > 0 ? (u64)p.n_conv * b / a : (u64)kXcds * Smax * 4;
@@ -1382,11 +1397,14 @@ Plan plan_items(FwdParams &p, int Ks)
         const u64 resident = (u64)kXcds * Smax;
         if (others + kXcds * 4 < resident && others + want > resident && (resident - others) * 4 >= want)
             want = resident - others - kXcds * 3;  // the lists are rounded up per kind and die
+        // gentle copying moves one access per thread at a time: as many items as fit, cut finely
+        const size_t grain = p.copy_gentle ? (size_t)kThreads * 16 : kCopyPiece;
+        if (p.copy_gentle && others + kXcds * 4 < resident) want = resident - others - kXcds * 3;
         if (want < 1) want = 1;
         u64 per_img = (want + p.N / 2) / p.N;
         if (per_img < 1) per_img = 1;
         size_t chunk = (p.idt_len + per_img - 1) / per_img;
-        chunk = (chunk + kCopyPiece - 1) / kCopyPiece * kCopyPiece;
+        chunk = (chunk + grain - 1) / grain * grain;
         const size_t chunks = (p.idt_len + chunk - 1) / chunk;
         p.copy_chunk = chunk;
         p.div_chunks = make_div((uint32_t)chunks);
