@@ -316,6 +316,8 @@ struct FwdParams {
     unsigned *err;       // raised when a bounded wait expires
     unsigned *epoch;     // [kGroups] call counters (kCtlStride words apart) = tag of the current call
     unsigned *done;      // [kGroups] blocks of the group that have announced their leave
+    unsigned *queue;     // [kGroups] entries of the group's list handed out beyond the first per block
+    int dynamic;         // blocks take their further entries from the group's queue
     // Every conv item is resident from the start (fused pooling) and the call is so short
     // that the conv items' chain of load, taps, estimator and store is what it lasts: the
     // copy items then keep little in flight, so that the conv items' few accesses (tile,
@@ -350,6 +352,7 @@ __shared__ float g_part[kStage];
 __shared__ float g_g[kMaxCa];
 __shared__ float g_t[kMaxHidden];
 __shared__ float g_small[16];
+__shared__ unsigned g_next[2];
 
 // Per-block state that item code touches.
 struct Ctx {
@@ -1173,7 +1176,20 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
     ctx.last_item = false;
     ctx.announced = false;
     ctx.left = 0;
-    for (unsigned li = slot; li < total; li += S) {
+    // Which entries a block processes.  A call that fits into one round of resident blocks:
+    // entry `slot` (and slot + S, ... if any).  Longer calls: the items differ too much in
+    // duration for a fixed deal, so the die's list is dealt to its eight block groups
+    // (entries k, k + 8, ... to group k = slot % 8) and inside a group each block starts
+    // with the entry of its rank and takes every further one from the group's queue - one
+    // atomic per item, asked for when the item starts, looked at when it ends.
+    const bool dynamic = p->dynamic != 0;
+    const unsigned k8 = slot % kXcds, rank = slot / kXcds, members8 = (S - k8 + kXcds - 1) / kXcds;
+    unsigned turn = 0;
+    for (unsigned li = dynamic ? k8 + kXcds * rank : slot; li < total;) {
+        unsigned claim = 0;
+        if (dynamic && threadIdx.x == kThreads - 1)
+            claim = __hip_atomic_fetch_add(p->queue + (blockIdx.x % kGroups) * kCtlStride, 1u, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
         // kind and index of this entry
         int kind;  // 0 pool, 1 gen, 2 conv, 3 copy
         unsigned idx;
@@ -1200,7 +1216,7 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
             kind = is_conv ? 2 : 3;
             idx = (is_conv ? conv_base : copy_base) + local;
         }
-        ctx.last_item = li + S >= total;
+        ctx.last_item = !dynamic && li + S >= total;
         ItemOut o;
         if (kind == 0) {
             o = pool_item<T>(p, ctx, idx);
@@ -1226,7 +1242,15 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
             for (int k = 0; k < 16; ++k) p->trace[(size_t)gid * 16 + k] = rec.t[k];
         }
 #endif
-        __syncthreads();  // LDS is reused by the next item
+        if (dynamic) {
+            if (threadIdx.x == kThreads - 1) g_next[turn & 1] = k8 + kXcds * (members8 + claim);
+            __syncthreads();  // also: LDS is reused by the next item
+            li = g_next[turn & 1];
+            ++turn;
+        } else {
+            __syncthreads();  // LDS is reused by the next item
+            li += S;
+        }
     }
     // A block without items still belongs to its group.  The last block of a group to have
     // announced its leave opens the next call for the group: leave counter back to zero, tag + 1.
@@ -1236,6 +1260,7 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
         const unsigned g = blockIdx.x % kGroups;
         const unsigned members = (gridDim.x - g + kGroups - 1) / kGroups;
         if (ctx.left == members - 1) {
+            __hip_atomic_store(p->queue + g * kCtlStride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(p->done + g * kCtlStride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(p->epoch + g * kCtlStride, ctx.tag + 1u == 0u ? 1u : ctx.tag + 1u, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
@@ -1244,13 +1269,14 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
 }
 
 // Control block at the start of the workspace, in 32-bit words: word 0 the error word, then
-// from kCtlEpochWord one call counter per group and from kCtlDoneWord one leave counter per
-// group, each kCtlStride words apart.  Preparation: everything zero, call counters 1 (tag 0
-// is what empty mailboxes carry).
+// from kCtlEpochWord one call counter per group, from kCtlDoneWord one leave counter per
+// group and from kCtlQueueWord one queue counter per group, each kCtlStride words apart.
+// Preparation: everything zero, call counters 1 (tag 0 is what empty mailboxes carry).
 constexpr size_t kCtlErrWord = 0;
 constexpr size_t kCtlEpochWord = kCtlStride;
 constexpr size_t kCtlDoneWord = kCtlEpochWord + (size_t)kGroups * kCtlStride;
-constexpr size_t kCtlWords = kCtlDoneWord + (size_t)kGroups * kCtlStride;
+constexpr size_t kCtlQueueWord = kCtlDoneWord + (size_t)kGroups * kCtlStride;
+constexpr size_t kCtlWords = kCtlQueueWord + (size_t)kGroups * kCtlStride;
 
 __global__ void ws_init_kernel(uint32_t *ptr, size_t words)
 {
@@ -1384,8 +1410,15 @@ Plan plan_items(FwdParams &p, int Ks)
         if (share > 0.625) a = 3;
     }
 
-    // short calls (the conv items' own chain is most of them): gentle, gated copying
-    p.copy_gentle = p.pool_mode == kPoolFused && p.dk_mode == kDkDirect;
+    // short calls (the conv items' own chain is most of them): gentle copying, if the blocks
+    // left over beside the conv items get through the pass-through range in about a dozen
+    // accesses per thread
+    {
+        const u64 others0 = (u64)p.n_pool + p.n_gen + p.n_conv, resident0 = (u64)kXcds * Smax;
+        const u64 spare = resident0 > others0 + kXcds * 4 ? resident0 - others0 - kXcds * 3 : 0;
+        p.copy_gentle = p.pool_mode == kPoolFused && p.dk_mode == kDkDirect &&
+                        (u64)p.N * p.idt_len <= spare * 12 * (u64)kThreads * 16;
+    }
 
     // copy items: as many as the pattern pairs with the conv items; if the whole call fits
     // into one round of resident blocks, as many as still fit
@@ -1427,6 +1460,7 @@ Plan plan_items(FwdParams &p, int Ks)
     Plan plan;
     unsigned need = per_die_of(p.n_pool) + per_die_of(p.n_gen) + per_die_of(p.n_conv) + per_die_of(p.n_copy);
     plan.per_die = need < Smax ? need : Smax;
+    p.dynamic = need > Smax;
     if (plan.per_die < (unsigned)kGroups / kXcds) plan.per_die = kGroups / kXcds;  // every block group needs a member
     return plan;
 }
@@ -1452,9 +1486,10 @@ esc_status launch_ks(FwdParams &p, hipStream_t s)
     if constexpr (KS == 0) {
         return launch_variant<0, 2, T>(p, s);
     } else {
-        // taller register blocks once there is enough work to fill the chip several times over
+        // taller register blocks (fewer halo rows, more arithmetic per item's fixed latencies)
+        // once they still give every compute unit two tiles
         const size_t tiles4 = (size_t)((p.W + kTileW - 1) / kTileW) * ((p.H + 63) / 64) * p.N * p.Ca;
-        int ry = (tiles4 >= 1536 && KS <= 17) ? 4 : 2;
+        int ry = (tiles4 >= 2 * (size_t)device_cus() && KS <= 17) ? 4 : 2;
         if (conv_ry_override() == 2 || (conv_ry_override() == 4 && KS <= 17)) ry = conv_ry_override();
         const int th = 16 * ry;
         const int tiles_x = (p.W + kTileW - 1) / kTileW;
@@ -1537,6 +1572,7 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
     p.err = (unsigned *)(w + l.ctl_off) + kCtlErrWord;
     p.epoch = (unsigned *)(w + l.ctl_off) + kCtlEpochWord;
     p.done = (unsigned *)(w + l.ctl_off) + kCtlDoneWord;
+    p.queue = (unsigned *)(w + l.ctl_off) + kCtlQueueWord;
 #ifdef ESC_TRACE
     p.trace = g_trace;
 #endif

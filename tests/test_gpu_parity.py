@@ -59,6 +59,13 @@ def test_edge_shapes(oracle, N, C, H, W, Ca, Ks, dtype):
     check_forward(wl, oracle)
 
 
+def test_plane_with_more_pool_tiles_than_one_polling_round(oracle):
+    # 66 x 66 = 4356 pool tiles per plane: the gen item has to stage a channel's partial
+    # sums in more than one round; a second channel and a ragged tail on both axes
+    wl = wk.make_random(21, 1, 2, 2100, 4200 - 6, 2, 3, dtype=F32, x_mean=0.25)
+    check_forward(wl, oracle)
+
+
 def test_no_attention_channels_is_a_pure_copy(oracle):
     wl = wk.make_random(7, 2, 5, 17, 19, 0, 13)
     out = gu.run_forward(wl)
