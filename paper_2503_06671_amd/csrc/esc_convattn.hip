@@ -278,8 +278,10 @@ __device__ __forceinline__ float row_sum(float v)
 enum : int {
     kDkNone = 0,    // DK = 0
     kDkGiven = 1,   // caller's dk_in
-    kDkBoxes = 2,   // published by a gen item
-    kDkDirect = 3   // each conv item finishes the GAP and runs its nine estimator outputs itself
+    kDkBoxes = 2,   // published by a gen item (esc_dynkernel_gen: the gen items also write dk_out)
+    kDkDirect = 3,  // each conv item finishes the GAP and runs its nine estimator outputs itself
+    kDkFromG = 4    // one gsum item per (image, channel) publishes the channel's mean; each conv
+                    // item collects its image's means and runs its nine estimator outputs
 };
 enum : int {
     kPoolNone = 0,   // no estimator in this call
@@ -333,6 +335,7 @@ struct FwdParams {
 typedef const __attribute__((address_space(4))) FwdParams *ParamsPtr;
 
 constexpr unsigned kXcds = 8;
+constexpr int kPrioHigh = 3;  // wavefront priority outside the tap loop
 
 // die `die`'s contiguous share of n items: [base, base + cnt)
 __device__ __forceinline__ void die_share(unsigned n, unsigned die, unsigned &base, unsigned &cnt)
@@ -545,8 +548,8 @@ __device__ __forceinline__ void sum_staged(const float *s_part, int ntile, int g
 // Whole block: waits for image n's pool mailboxes (staged through s_part), leaves the
 // pooled means in s_g and (two-layer estimator) the hidden activations in s_t.  Ends
 // with a barrier.
-__device__ __forceinline__ void estimator_front(ParamsPtr p, uint32_t tag, unsigned n, float *s_part,
-                                                float *s_g, float *s_t)
+__device__ __forceinline__ void estimator_front(ParamsPtr p, uint32_t tag, unsigned n, int c_first, int c_end,
+                                                bool with_hidden, float *s_part, float *s_g, float *s_t)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ntile = p->ptiles, Ca = p->Ca;
@@ -554,8 +557,8 @@ __device__ __forceinline__ void estimator_front(ParamsPtr p, uint32_t tag, unsig
     u64 polled[kStagePerThread];
     if (ntile <= kStage) {
         const int G = kStage / ntile;  // whole channels per round
-        for (int c0 = 0; c0 < Ca; c0 += G) {
-            const int gc = Ca - c0 < G ? Ca - c0 : G;
+        for (int c0 = c_first; c0 < c_end; c0 += G) {
+            const int gc = c_end - c0 < G ? c_end - c0 : G;
             boxes_to_lds(img_boxes + (size_t)c0 * ntile, gc * ntile, s_part, tag, p->err, polled, false);
             __syncthreads();
             sum_staged(s_part, ntile, gc, c0, p->hw, s_g);
@@ -564,7 +567,7 @@ __device__ __forceinline__ void estimator_front(ParamsPtr p, uint32_t tag, unsig
     } else {
         // a channel has more tiles than fit: kStage at a time; kStage % 64 == 0 keeps every
         // tile on the lane its index selects
-        for (int c = 0; c < Ca; ++c) {
+        for (int c = c_first; c < c_end; ++c) {
             float s = 0.f;
             for (int k0 = 0; k0 < ntile; k0 += kStage) {
                 const int cnt = ntile - k0 < kStage ? ntile - k0 : kStage;
@@ -581,7 +584,7 @@ __device__ __forceinline__ void estimator_front(ParamsPtr p, uint32_t tag, unsig
         }
         __syncthreads();
     }
-    if (p->hidden > 0) {
+    if (with_hidden && p->hidden > 0) {
         for (int m = threadIdx.x; m < p->hidden; m += kThreads)
             s_t[m] = gelu_erf(dot_row(p->w_down + (size_t)m * Ca, s_g, Ca, p->b_down ? p->b_down[m] : 0.f));
         __syncthreads();
@@ -603,7 +606,7 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
     ESC_TRACE_INIT(rec);
     need_tag(p, ctx);
     announce_leave(p, ctx);
-    estimator_front(p, ctx.tag, n, s_part, s_g, s_t);
+    estimator_front(p, ctx.tag, n, 0, p->Ca, true, s_part, s_g, s_t);
     ESC_STAMP(rec, 3);
     for (int o = threadIdx.x; o < 9 * p->Ca; o += kThreads) {
         const float s = estimator_out(p, o, s_g, s_t);
@@ -611,6 +614,25 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
         box_put(p->dk_box + idx, s, ctx.tag);
         if (p->dk_out) p->dk_out[idx] = s;
     }
+    ESC_STAMP(rec, 6);
+    return ItemOut{ctx, rec};
+}
+
+// gsum item: the mean of one (image, channel) plane from its pool mailboxes, with the
+// additions in the order every other path uses, published in the channel's mean mailbox
+// (these share the DK mailboxes' memory: a call uses one kind or the other).
+__device__ __forceinline__ ItemOut gsum_item(ParamsPtr p, Ctx ctx, unsigned nc)
+{
+    float *s_part = g_part, *s_g = g_g, *s_t = g_t;
+    Trace rec;
+    ESC_TRACE_INIT(rec);
+    need_tag(p, ctx);
+    announce_leave(p, ctx);
+    const unsigned n = fdiv(nc, p->div_ca.mul, p->div_ca.shift);
+    const int c = (int)(nc - n * (unsigned)p->Ca);
+    estimator_front(p, ctx.tag, n, c, c + 1, false, s_part, s_g, s_t);
+    ESC_STAMP(rec, 3);
+    if (threadIdx.x == 0) box_put(p->dk_box + nc, s_g[c], ctx.tag);
     ESC_STAMP(rec, 6);
     return ItemOut{ctx, rec};
 }
@@ -779,9 +801,10 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // needs, before the tap loop; look at the answers after it, so that their round trips
     // cost nothing.
     constexpr int kPer = (kDirectMaxBoxes + kPollThreads - 1) / kPollThreads;
-    const bool direct = p->dk_mode == kDkDirect;
-    const int nbox = p->Ca * p->ptiles;
-    const u64 *img_boxes = p->pool_box + (size_t)n * nbox;
+    const bool from_g = p->dk_mode == kDkFromG;  // the mailboxes hold channel means, not partial sums
+    const bool direct = p->dk_mode == kDkDirect || from_g;
+    const int nbox = from_g ? p->Ca : p->Ca * p->ptiles;
+    const u64 *img_boxes = from_g ? p->dk_box + (size_t)n * nbox : p->pool_box + (size_t)n * nbox;
     const int Kin = p->hidden > 0 ? p->hidden : p->Ca;
     const bool pre_w = direct && 9 * Kin <= kThreads && p->hidden * p->Ca <= kThreads;
     u64 early[kPer];
@@ -810,7 +833,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         // no branch here (one would split the loop body and cost registers): every thread
         // reads some mailbox of the image, whichever mode the call is in
         const int t = opaque_tid();
-        const u64 *bx = p->pool_box + (size_t)opaque_u(n) * nbox;
+        const u64 *bx = (p->dk_mode == kDkFromG ? p->dk_box : p->pool_box) + (size_t)opaque_u(n) * nbox;
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
             int f = t + u * kPollThreads;
@@ -905,6 +928,11 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // during the tap loop, which waits for no memory access (anywhere earlier, the next
     // wait for a load would wait for the atomic as well - results return in order).
     announce_leave(p, ctx);
+    // The tap loop is the one long stretch of pure arithmetic: it runs at the lowest
+    // wavefront priority, everything else (issuing loads, the serial estimator code, the
+    // stores) above it, so that the short latency-bound phases of one block are not starved
+    // by the tap loops of the other blocks on the compute unit.
+    __builtin_amdgcn_s_setprio(0);
     // The early requests go out before the loop (in its middle they cost the compiler so
     // many registers that it spills); whatever has not arrived by the end is asked for again.
     ask_early();
@@ -941,6 +969,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
 #pragma unroll
         for (int q = 0; q < 4; ++q) asm volatile("" ::"v"(acc[oy][q]));
 #endif
+    __builtin_amdgcn_s_setprio(kPrioHigh);
     ESC_STAMP(rec, 4);
 
     // ---- phase 3: DK and the stores, located afresh (see opaque_u) ----
@@ -963,7 +992,11 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             }
             __syncthreads();
             ESC_STAMP(rec, 8);
-            sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
+            if (from_g) {
+                for (int k = tid_d; k < p->Ca; k += kThreads) s_g[k] = s_part[k];
+            } else {
+                sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
+            }
             __syncthreads();
             ESC_STAMP(rec, 9);
             if (p->hidden > 0) {
@@ -1150,6 +1183,7 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
     // the parameters from the kernel argument segment, which starts with `params`
     (void)params;
     ParamsPtr p = (ParamsPtr)__builtin_amdgcn_kernarg_segment_ptr();
+    __builtin_amdgcn_s_setprio(kPrioHigh);
 
     // Blocks are handed to the chip's eight dies (XCDs, each with its own L2) round robin
     // by block index.  Each die gets one contiguous eighth of every kind of item, so that
@@ -1221,7 +1255,7 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
         if (kind == 0) {
             o = pool_item<T>(p, ctx, idx);
         } else if (kind == 1) {
-            o = gen_item(p, ctx, idx);
+            o = p->dk_mode == kDkFromG ? gsum_item(p, ctx, idx) : gen_item(p, ctx, idx);
         } else if (kind == 2) {
             if constexpr (KS > 0)
                 o = conv_item<KS, RY, T>(p, ctx, idx);
@@ -1556,7 +1590,7 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
     p.div_ca = make_div((uint32_t)(Ca > 0 ? Ca : 1));
     p.div_tiles_x = p.div_tiles_y = p.div_chunks = p.div_mix = p.div_mix_a = p.div_mix_b = make_div(1);
     if (gen != nullptr && Ca > 0) {
-        p.dk_mode = ((size_t)Ca * l.ptiles <= (size_t)kDirectMaxBoxes) ? kDkDirect : kDkBoxes;
+        p.dk_mode = ((size_t)Ca * l.ptiles <= (size_t)kDirectMaxBoxes) ? kDkDirect : kDkFromG;
         p.pool_mode = kPoolItems;
         p.hidden = gen->hidden;
         p.w_down = gen->w_down;
@@ -1566,7 +1600,7 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
         const size_t n_pool = (size_t)N * Ca * l.ptiles;
         if (n_pool >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
         p.n_pool = (unsigned)n_pool;
-        p.n_gen = p.dk_mode == kDkBoxes ? (unsigned)N : 0u;
+        p.n_gen = p.dk_mode == kDkFromG ? (unsigned)((size_t)N * Ca) : 0u;  // gsum items
     }
     char *w = (char *)workspace;
     p.err = (unsigned *)(w + l.ctl_off) + kCtlErrWord;
