@@ -364,6 +364,7 @@ struct Ctx {
     bool last_item;   // the item being processed is the block's last
     bool announced;   // leave already announced
     unsigned left;    // thread kThreads-1 only: blocks of the group that had announced before this one
+    unsigned claim;   // thread kThreads-1 only: what the group's queue returned for the block's next entry
 };
 
 // What an item function hands back: the updated block state (and, in development builds,
@@ -383,6 +384,18 @@ __device__ __forceinline__ void need_tag(ParamsPtr p, Ctx &ctx)
         ctx.tag = *(const volatile unsigned *)(p->epoch + (blockIdx.x % kGroups) * kCtlStride);
         ctx.have_tag = true;
     }
+}
+
+// Takes the block's next entry from its group's queue (calls longer than one round only).
+// Items that never wait for other items ask when they start, so that the answer is there
+// when they end.  Items that wait (conv items for the estimator, gen and gsum items for the
+// pool sums) ask only after their wait: an entry reserved by a waiting block could be the
+// very item it is waiting for.
+__device__ __forceinline__ void claim_next(ParamsPtr p, Ctx &ctx)
+{
+    if (p->dynamic && opaque_tid() == kThreads - 1)
+        ctx.claim = __hip_atomic_fetch_add(p->queue + (blockIdx.x % kGroups) * kCtlStride, 1u, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Called once the loads of the block's last item are in flight: announce the leave, so the
@@ -614,6 +627,7 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
         box_put(p->dk_box + idx, s, ctx.tag);
         if (p->dk_out) p->dk_out[idx] = s;
     }
+    claim_next(p, ctx);
     ESC_STAMP(rec, 6);
     return ItemOut{ctx, rec};
 }
@@ -633,6 +647,7 @@ __device__ __forceinline__ ItemOut gsum_item(ParamsPtr p, Ctx ctx, unsigned nc)
     estimator_front(p, ctx.tag, n, c, c + 1, false, s_part, s_g, s_t);
     ESC_STAMP(rec, 3);
     if (threadIdx.x == 0) box_put(p->dk_box + nc, s_g[c], ctx.tag);
+    claim_next(p, ctx);
     ESC_STAMP(rec, 6);
     return ItemOut{ctx, rec};
 }
@@ -893,7 +908,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     };
     // what may move across a step boundary: arithmetic and global memory, not LDS traffic
     constexpr int kSchedNoLds = 0x1 | 0x2 | 0x4 | 0x10 | 0x20 | 0x40;
-    constexpr bool kTwoX = 2 * NV + RY * KS + 4 * RY <= 104;  // room for a second tile-row buffer
+    constexpr bool kTwoX = 2 * NV + RY * KS + 4 * RY <= 96;  // room for a second tile-row buffer
     float X[kTwoX ? 2 : 1][NV];
     float Wt[RY][KS];  // kernel row i lives in slot i % RY while it is in use
     if (kTwoX) load_x(0, X[0]);
@@ -961,6 +976,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
                     fma_row(acc[k], wr, xr);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);  // one row's loads at a time: the registers are few
         }
     }
 #ifdef ESC_TRACE
@@ -1020,6 +1036,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             s_dk[tid_d] = d;
         }
         __syncthreads();
+        claim_next(p, ctx);  // the wait for the estimator is over
         ESC_STAMP(rec, 5);
         float d[9];
 #pragma unroll
@@ -1044,6 +1061,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         }
     }
 
+    if (p->dk_mode == kDkNone) claim_next(p, ctx);
     const int gx = wd.x0 + 4 * tx_d;
 #pragma unroll
     for (int oy = 0; oy < RY; ++oy) {
@@ -1210,20 +1228,17 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
     ctx.last_item = false;
     ctx.announced = false;
     ctx.left = 0;
+    ctx.claim = 0;
     // Which entries a block processes.  A call that fits into one round of resident blocks:
     // entry `slot` (and slot + S, ... if any).  Longer calls: the items differ too much in
     // duration for a fixed deal, so the die's list is dealt to its eight block groups
     // (entries k, k + 8, ... to group k = slot % 8) and inside a group each block starts
     // with the entry of its rank and takes every further one from the group's queue - one
-    // atomic per item, asked for when the item starts, looked at when it ends.
+    // atomic per item (see claim_next), looked at when the item ends.
     const bool dynamic = p->dynamic != 0;
     const unsigned k8 = slot % kXcds, rank = slot / kXcds, members8 = (S - k8 + kXcds - 1) / kXcds;
     unsigned turn = 0;
     for (unsigned li = dynamic ? k8 + kXcds * rank : slot; li < total;) {
-        unsigned claim = 0;
-        if (dynamic && threadIdx.x == kThreads - 1)
-            claim = __hip_atomic_fetch_add(p->queue + (blockIdx.x % kGroups) * kCtlStride, 1u, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
         // kind and index of this entry
         int kind;  // 0 pool, 1 gen, 2 conv, 3 copy
         unsigned idx;
@@ -1251,6 +1266,7 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
             idx = (is_conv ? conv_base : copy_base) + local;
         }
         ctx.last_item = !dynamic && li + S >= total;
+        if (kind == 0 || kind == 3) claim_next(p, ctx);
         ItemOut o;
         if (kind == 0) {
             o = pool_item<T>(p, ctx, idx);
@@ -1277,7 +1293,7 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
         }
 #endif
         if (dynamic) {
-            if (threadIdx.x == kThreads - 1) g_next[turn & 1] = k8 + kXcds * (members8 + claim);
+            if (threadIdx.x == kThreads - 1) g_next[turn & 1] = k8 + kXcds * (members8 + ctx.claim);
             __syncthreads();  // also: LDS is reused by the next item
             li = g_next[turn & 1];
             ++turn;
