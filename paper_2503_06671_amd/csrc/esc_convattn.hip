@@ -619,13 +619,53 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
     ESC_TRACE_INIT(rec);
     need_tag(p, ctx);
     announce_leave(p, ctx);
-    estimator_front(p, ctx.tag, n, 0, p->Ca, true, s_part, s_g, s_t);
+    // Small estimators (one output per thread, rows of at most 16 weights): the weights are
+    // fetched now, while the pool sums are still being waited for, so that what follows the
+    // wait is arithmetic only.  Same products in the same order as dot_row.
+    constexpr int kRow = 16;
+    const int Ca = p->Ca, hidden = p->hidden, K = hidden > 0 ? hidden : Ca;
+    const bool pre = K <= kRow && Ca <= kRow && 9 * Ca <= kThreads && hidden <= kThreads;
+    const int o1 = (int)threadIdx.x;
+    float wu[kRow], wd[kRow], bu = 0.f, bd = 0.f;
+    if (pre) {
+#pragma unroll
+        for (int k = 0; k < kRow; ++k) {
+            wu[k] = (o1 < 9 * Ca && k < K) ? p->w_up[(size_t)o1 * K + k] : 0.f;
+            wd[k] = (o1 < hidden && k < Ca) ? p->w_down[(size_t)o1 * Ca + k] : 0.f;
+        }
+        if (o1 < 9 * Ca && p->b_up) bu = p->b_up[o1];
+        if (o1 < hidden && p->b_down) bd = p->b_down[o1];
+    }
+    estimator_front(p, ctx.tag, n, 0, Ca, !pre, s_part, s_g, s_t);
     ESC_STAMP(rec, 3);
-    for (int o = threadIdx.x; o < 9 * p->Ca; o += kThreads) {
-        const float s = estimator_out(p, o, s_g, s_t);
-        const size_t idx = (size_t)n * 9 * p->Ca + o;
-        box_put(p->dk_box + idx, s, ctx.tag);
-        if (p->dk_out) p->dk_out[idx] = s;
+    if (pre) {
+        if (hidden > 0) {
+            if (o1 < hidden) {
+                float s = bd;
+#pragma unroll
+                for (int k = 0; k < kRow; ++k)
+                    if (k < Ca) s = fmaf(wd[k], s_g[k], s);
+                s_t[o1] = gelu_erf(s);
+            }
+            __syncthreads();
+        }
+        if (o1 < 9 * Ca) {
+            const float *in = hidden > 0 ? s_t : s_g;
+            float s = bu;
+#pragma unroll
+            for (int k = 0; k < kRow; ++k)
+                if (k < K) s = fmaf(wu[k], in[k], s);
+            const size_t idx = (size_t)n * 9 * Ca + o1;
+            box_put(p->dk_box + idx, s, ctx.tag);
+            if (p->dk_out) p->dk_out[idx] = s;
+        }
+    } else {
+        for (int o = threadIdx.x; o < 9 * Ca; o += kThreads) {
+            const float s = estimator_out(p, o, s_g, s_t);
+            const size_t idx = (size_t)n * 9 * Ca + o;
+            box_put(p->dk_box + idx, s, ctx.tag);
+            if (p->dk_out) p->dk_out[idx] = s;
+        }
     }
     claim_next(p, ctx);
     ESC_STAMP(rec, 6);
@@ -817,9 +857,12 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // cost nothing.
     constexpr int kPer = (kDirectMaxBoxes + kPollThreads - 1) / kPollThreads;
     const bool from_g = p->dk_mode == kDkFromG;  // the mailboxes hold channel means, not partial sums
+    const bool from_boxes = p->dk_mode == kDkBoxes;  // a gen item publishes DK itself
     const bool direct = p->dk_mode == kDkDirect || from_g;
-    const int nbox = from_g ? p->Ca : p->Ca * p->ptiles;
-    const u64 *img_boxes = from_g ? p->dk_box + (size_t)n * nbox : p->pool_box + (size_t)n * nbox;
+    const int nbox = from_boxes ? 9 : from_g ? p->Ca : p->Ca * p->ptiles;
+    const u64 *img_boxes = from_boxes ? p->dk_box + (size_t)nc * 9
+                           : from_g   ? p->dk_box + (size_t)n * nbox
+                                      : p->pool_box + (size_t)n * nbox;
     const int Kin = p->hidden > 0 ? p->hidden : p->Ca;
     const bool pre_w = direct && 9 * Kin <= kThreads && p->hidden * p->Ca <= kThreads;
     u64 early[kPer];
@@ -843,12 +886,15 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     };
 
     // Asked again part-way through the tap loop: by then the other blocks have published,
-    // so the answers are back when the loop ends.  Addresses are made on the spot.
+    // so the answers are back when the loop ends.  The mailboxes' base is block-uniform and
+    // waits in scalar registers; the per-thread addresses are made on the spot.
+    const u64 *boxes_s = img_boxes;
+    asm volatile("" : "+s"(boxes_s));
     auto ask_again = [&]() {
         // no branch here (one would split the loop body and cost registers): every thread
         // reads some mailbox of the image, whichever mode the call is in
         const int t = opaque_tid();
-        const u64 *bx = (p->dk_mode == kDkFromG ? p->dk_box : p->pool_box) + (size_t)opaque_u(n) * nbox;
+        const u64 *bx = boxes_s;
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
             int f = t + u * kPollThreads;
@@ -1029,8 +1075,10 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             if (direct)
                 d = pre_w ? dot_row_lds(s_wup + tid_d * Kin, p->hidden > 0 ? s_t : s_g, Kin, bup_r)
                           : estimator_out(p, wd.c * 9 + tid_d, s_g, s_t);
-            else if (p->dk_mode == kDkBoxes)
-                d = box_get(p->dk_box + dk_idx + tid_d, ctx.tag, p->err);
+            else if (from_boxes)  // asked for part-way through the tap loop; otherwise wait now
+                d = G::UNROLL && (uint32_t)(early[0] >> 32) == ctx.tag
+                        ? __uint_as_float((uint32_t)early[0])
+                        : box_get(p->dk_box + dk_idx + tid_d, ctx.tag, p->err);
             else
                 d = p->dk_in[dk_idx + tid_d];
             s_dk[tid_d] = d;
@@ -1442,6 +1490,16 @@ Plan plan_items(FwdParams &p, int Ks)
     const unsigned Smax = (unsigned)kBlocksPerCu * (U ? U : 1);  // resident blocks per die
     auto per_die_of = [](u64 n) { return (unsigned)((n + kXcds - 1) / kXcds); };
 
+    // Few pool tiles per image and a long tap loop: one gen item per image runs the estimator
+    // while the conv items multiply, and they pick DK up on the way (asked for inside the
+    // loop); with short loops the conv items run the estimator themselves (direct mode), one
+    // hop fewer.  Only if the gen items still fit beside all conv items (fused pooling).
+    if (p.pool_mode == kPoolItems && p.dk_mode == kDkDirect && Ks >= 9 && p.n_conv > 0 &&
+        per_die_of(p.n_conv) + per_die_of((u64)p.N) <= Smax) {
+        p.dk_mode = kDkBoxes;
+        p.n_gen = (unsigned)p.N;
+    }
+
     // all conv items (and the gen items they wait for) in the first round => fused pooling
     if (p.pool_mode == kPoolItems && p.n_conv > 0 && per_die_of(p.n_conv) + per_die_of(p.n_gen) <= Smax) {
         p.pool_mode = kPoolFused;
@@ -1466,7 +1524,7 @@ Plan plan_items(FwdParams &p, int Ks)
     {
         const u64 others0 = (u64)p.n_pool + p.n_gen + p.n_conv, resident0 = (u64)kXcds * Smax;
         const u64 spare = resident0 > others0 + kXcds * 4 ? resident0 - others0 - kXcds * 3 : 0;
-        p.copy_gentle = p.pool_mode == kPoolFused && p.dk_mode == kDkDirect &&
+        p.copy_gentle = p.pool_mode == kPoolFused && (p.dk_mode == kDkDirect || p.dk_mode == kDkBoxes) &&
                         (u64)p.N * p.idt_len <= spare * 12 * (u64)kThreads * 16;
     }
 
