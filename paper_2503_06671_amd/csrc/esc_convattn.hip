@@ -1003,7 +1003,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
 #pragma unroll
             for (int u = 0; u < RY; ++u)
                 if (r0 + u < G::ROWS) {
-                    if (r0 + u == (G::ROWS * 5) / 8) ask_again();
+                    if (r0 + u == (G::ROWS * 3) / 4) ask_again();
                     step(r0 + u, u);
                 }
     } else {
