@@ -112,3 +112,47 @@ def test_binding_refuses_cpu_tensors(lib):
     x = torch.zeros(1, 4, 8, 8)
     with pytest.raises(TypeError):
         binding.convattn_forward(x, 2, torch.zeros(2, 3, 3), torch.zeros(1024, dtype=torch.uint8))
+
+
+# ---------------------------------------------------------------- compiled kernel variants
+
+def kernel_metadata():
+    """(Ks, RY, type letter) -> (private segment bytes, VGPRs) of every forward_kernel
+    variant in the built library, read from the code object's notes."""
+    import subprocess
+    import tempfile
+    tools = "/opt/rocm/llvm/bin"
+    need = [os.path.join(tools, t) for t in ("llvm-objcopy", "clang-offload-bundler", "llvm-readelf")]
+    if not all(os.path.exists(t) for t in need):
+        pytest.skip("LLVM binary tools not found")
+    with tempfile.TemporaryDirectory() as tmp:
+        fat, dev = os.path.join(tmp, "fat.bin"), os.path.join(tmp, "dev.co")
+        subprocess.run([need[0], f"--dump-section=.hip_fatbin={fat}", binding.LIB_PATH, os.path.join(tmp, "copy.so")],
+                       check=True)
+        subprocess.run([need[1], "--unbundle", "--type=o", f"--input={fat}",
+                        "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={dev}"], check=True)
+        notes = subprocess.run([need[2], "--notes", dev], check=True, capture_output=True, text=True).stdout
+    out = {}
+    for block in notes.split(".name:")[1:]:
+        name = block.split()[0]
+        m = re.search(r"forward_kernelILi(\d+)ELi(\d+)E(\w)", name)
+        if not m:
+            continue
+        scratch = int(re.search(r"\.private_segment_fixed_size:\s*(\d+)", block).group(1))
+        vgprs = int(re.search(r"\.vgpr_count:\s*(\d+)", block).group(1))
+        out[(int(m.group(1)), int(m.group(2)), m.group(3))] = (scratch, vgprs)
+    return out
+
+
+def test_kernel_variants_fit_four_blocks_per_cu_without_scratch(lib):
+    # Four resident blocks per compute unit is what the grid is sized for (<= 128 VGPRs),
+    # and any private-segment use costs every launch a fixed microsecond or more: the
+    # variants the workloads use (Ks <= 15, both register blockings) must have none.
+    meta = kernel_metadata()
+    assert len(meta) >= 2 * 26, "every (Ks, RY, type) variant should be in the library"
+    for (ks, ry, t), (scratch, vgprs) in sorted(meta.items()):
+        assert vgprs <= 128, (ks, ry, t, vgprs)
+        if ks <= 15:
+            assert scratch == 0, (ks, ry, t, scratch)
+        else:
+            assert scratch <= 64, (ks, ry, t, scratch)

@@ -88,6 +88,30 @@ def test_two_layer_estimator(oracle, Ca, hidden, bias, dtype):
     check_forward(wl, oracle)
 
 
+@pytest.mark.parametrize("Ca,hidden,bias,dtype", [(16, 8, True, F32), (48, 24, True, BF16)])
+def test_two_layer_estimator_short_tap_loop(oracle, Ca, hidden, bias, dtype):
+    # Ks < 9: the conv items run the estimator themselves (weights staged in LDS for the
+    # small estimator, read from memory for the wide one)
+    wl = wk.make_random(520 + hidden, 2, Ca + 4, 40, 72, Ca, 5, dtype=dtype, hidden=hidden, bias=bias,
+                        x_mean=0.7)
+    check_forward(wl, oracle)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_two_layer_estimator_large_planes(oracle, dtype):
+    # 11 x 7 pool tiles x 8 channels > 512 mailboxes per image: channel-mean items, and the
+    # conv items run the two-layer estimator from the collected means
+    wl = wk.make_random(530, 2, 10, 200, 704, 8, 13, dtype=dtype, hidden=4, bias=True, x_mean=0.4)
+    check_forward(wl, oracle)
+
+
+def test_many_small_images_beyond_one_round(oracle):
+    # 3200 conv items of short tap loops: pool items, queue-dealt blocks, and conv items that
+    # collect the pool sums themselves
+    wl = wk.make_random(540, 200, 8, 40, 40, 8, 3, dtype=F32, x_mean=0.3)
+    check_forward(wl, oracle)
+
+
 def test_shared_single_filter(oracle):
     wl = wk.make_random(11, 2, 6, 30, 70, 4, 13)
     one = wl.lk[2].copy()
