@@ -290,6 +290,7 @@ enum : int {
 };
 constexpr int kDirectMaxBoxes = 512;  // direct mode while C_a * (pool tiles) mailboxes stay this few
 constexpr int kPoolTileW = 64, kPoolTileH = 32;  // the GAP is cut into 64 x 32 pixel tiles
+constexpr int kPoolBatch = 4;                    // pool tiles per pool item
 
 struct FwdParams {
     const void *x;
@@ -306,6 +307,7 @@ struct FwdParams {
     int ptiles_x, ptiles;  // pool tiles per row of tiles / per (image, channel) plane
     float hw;            // H*W as a float, the GAP divisor
     unsigned n_pool, n_gen, n_conv, n_copy;  // item counts
+    unsigned n_pool_tiles;                   // N * C_a * ptiles (a pool item covers kPoolBatch of them)
     // conv and copy items alternate in groups of mix_a conv + mix_b copy items while both
     // last; the rest of the conv items follow, then the rest of the copy items
     unsigned mix_a, mix_b;
@@ -437,6 +439,10 @@ __device__ __forceinline__ void pool_finish(ParamsPtr p, float s, unsigned box, 
     }
 }
 
+// A pool item covers kPoolBatch consecutive pool tiles: all their loads go out together
+// (no condition around a load - the compiler would wait for each guarded load before the
+// next; addresses are clamped into the plane and what lies outside is zeroed afterwards),
+// then each tile's sum is formed and published as if it were alone.
 template <typename T>
 __device__ __forceinline__ ItemOut pool_item(ParamsPtr p, Ctx ctx, unsigned item)
 {
@@ -444,38 +450,52 @@ __device__ __forceinline__ ItemOut pool_item(ParamsPtr p, Ctx ctx, unsigned item
     Trace rec;
     ESC_TRACE_INIT(rec);
     const int H = p->H, W = p->W;
-    const unsigned nc = fdiv(item, p->div_ptiles.mul, p->div_ptiles.shift);
-    const unsigned t = item - nc * (unsigned)p->ptiles;
-    const unsigned pty = fdiv(t, p->div_ptiles_x.mul, p->div_ptiles_x.shift), ptx = t - pty * (unsigned)p->ptiles_x;
-    const unsigned n = fdiv(nc, p->div_ca.mul, p->div_ca.shift);
-    const unsigned c = nc - n * (unsigned)p->Ca;
-    const T *plane = (const T *)p->x + ((size_t)n * p->C + c) * (size_t)H * (size_t)W;
     const int tid = opaque_tid();
     const int tx = tid & 15, ty = tid >> 4;
-    const int gx = (int)ptx * kPoolTileW + 4 * tx, gy = (int)pty * kPoolTileH + 2 * ty;
-    float v[2][4];
+    const unsigned first = item * kPoolBatch, ntiles = p->n_pool_tiles;
+    float v[kPoolBatch][2][4];
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    for (int b = 0; b < kPoolBatch; ++b) {
+        const bool have = first + b < ntiles;
+        const unsigned tile = have ? first + b : ntiles - 1;
+        const unsigned nc = fdiv(tile, p->div_ptiles.mul, p->div_ptiles.shift);
+        const unsigned t = tile - nc * (unsigned)p->ptiles;
+        const unsigned pty = fdiv(t, p->div_ptiles_x.mul, p->div_ptiles_x.shift), ptx = t - pty * (unsigned)p->ptiles_x;
+        const unsigned n = fdiv(nc, p->div_ca.mul, p->div_ca.shift);
+        const unsigned c = nc - n * (unsigned)p->Ca;
+        const T *plane = (const T *)p->x + ((size_t)n * p->C + c) * (size_t)H * (size_t)W;
+        const int gx = (int)ptx * kPoolTileW + 4 * tx, gy = (int)pty * kPoolTileH + 2 * ty;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[a][q] = 0.f;
-        if (gy + a < H) {
+        for (int a = 0; a < 2; ++a) {
             if (p->conv_ld_vec) {  // W % 4 == 0 and an aligned base: the four pixels are in or out together
-                if (gx < W) load4(plane + (size_t)(gy + a) * W + gx, v[a]);
+                const int ry = gy + a < H ? gy + a : H - 1, cx = gx < W ? gx : W - 4;
+                load4(plane + (size_t)ry * W + cx, v[b][a]);
+                const bool in = gy + a < H && gx < W;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[b][a][q] = in ? v[b][a][q] : 0.f;
             } else {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (gx + q < W) v[a][q] = to_f32(plane[(size_t)(gy + a) * W + gx + q]);
+                for (int q = 0; q < 4; ++q) {
+                    v[b][a][q] = 0.f;
+                    if (gy + a < H && gx + q < W) v[b][a][q] = to_f32(plane[(size_t)(gy + a) * W + gx + q]);
+                }
             }
         }
     }
     need_tag(p, ctx);
     announce_leave(p, ctx);
-    float s = 0.f;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int b = 0; b < kPoolBatch; ++b) {
+        if (first + b < ntiles) {  // block-uniform
+            float s = 0.f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) s += v[a][q];
-    pool_finish(p, s, item, ctx.tag, s_red);
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) s += v[b][a][q];
+            pool_finish(p, s, first + b, ctx.tag, s_red);
+            __syncthreads();  // s_red is reused
+        }
+    }
     ESC_STAMP(rec, 6);
     return ItemOut{ctx, rec};
 }
@@ -1673,7 +1693,8 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
         p.b_up = gen->b_up;
         const size_t n_pool = (size_t)N * Ca * l.ptiles;
         if (n_pool >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
-        p.n_pool = (unsigned)n_pool;
+        p.n_pool_tiles = (unsigned)n_pool;
+        p.n_pool = (unsigned)((n_pool + kPoolBatch - 1) / kPoolBatch);
         p.n_gen = p.dk_mode == kDkFromG ? (unsigned)((size_t)N * Ca) : 0u;  // gsum items
     }
     char *w = (char *)workspace;
