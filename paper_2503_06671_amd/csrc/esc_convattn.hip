@@ -1561,6 +1561,9 @@ Plan plan_items(FwdParams &p, int Ks)
         // gentle copying moves one access per thread at a time: as many items as fit, cut finely
         const size_t grain = p.copy_gentle ? (size_t)kThreads * 16 : kCopyPiece;
         if (p.copy_gentle && others + kXcds * 4 < resident) want = resident - others - kXcds * 3;
+        // fused pooling without room beside the conv items: the copy comes after them, and
+        // every block should get a share of it
+        if (p.pool_mode == kPoolFused && !p.copy_gentle && want < 2 * resident) want = 2 * resident;
         if (want < 1) want = 1;
         u64 per_img = (want + p.N / 2) / p.N;
         if (per_img < 1) per_img = 1;
