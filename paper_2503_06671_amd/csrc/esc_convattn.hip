@@ -123,16 +123,21 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 __device__ __forceinline__ void store1(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store1(bf16_t *p, float v) { p->bits = f32_to_bf16_bits(v); }
 
+// Output stores are non-temporal: nothing in the call reads them back, and lines that do
+// not linger in the L2 shorten the write-back at the end of the kernel (measured).
 __device__ __forceinline__ void store4(float *p, const float *v)
 {
-    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 t = {v[0], v[1], v[2], v[3]};
+    __builtin_nontemporal_store(t, reinterpret_cast<f32x4 *>(p));
 }
 __device__ __forceinline__ void store4(bf16_t *p, const float *v)
 {
-    uint2 w;
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 w;
     w.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
     w.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-    *reinterpret_cast<uint2 *>(p) = w;
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x2 *>(p));
 }
 
 // four consecutive elements from an address aligned to all four
@@ -1475,6 +1480,7 @@ esc_status check_ws(const void *ws, size_t ws_bytes, size_t need)
 u64 *g_trace = nullptr;
 #endif
 
+// development knob: ESC_CONV_RY=2 or 4 forces the conv items' register blocking
 int conv_ry_override()
 {
     static int v = [] {
