@@ -32,8 +32,12 @@
  *     esc_workspace_bytes gives the size for a shape; it never shrinks when N,
  *     C_a or H*W grow, so a workspace sized for the largest shape fits all.
  *   - The forward is one persistent kernel whose blocks wait for one another
- *     (bounded).  Should a wait ever expire, the result is undefined and the
- *     workspace's error word is raised; esc_workspace_errors reads it.
+ *     (bounded, about a second).  Its grid is sized so that all of its blocks are
+ *     resident at once on an otherwise idle device; work that other streams or
+ *     processes keep running on the same device at the same time can hold blocks
+ *     back and stretch those waits.  Should a wait ever expire, the result is
+ *     undefined and the workspace's error word is raised; esc_workspace_errors
+ *     reads it.
  *   - Limits: 0 <= C_a <= min(C, 256); estimator hidden width <= 256; Ks odd,
  *     1 <= Ks <= 31; H*W < 2^31; N, C, H, W >= 1.  No lower bound on H or W
  *     relative to Ks.
