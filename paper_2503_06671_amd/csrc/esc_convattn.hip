@@ -739,7 +739,7 @@ struct ConvGeom {
     static constexpr int TILE_FLOATS = HR * PITCH;
     static constexpr int W_FLOATS = KS * WP;
     static constexpr int ROWS = RY + KS - 1;      // tile rows a thread walks through
-    static constexpr bool UNROLL = KS * KS * RY <= 13 * 13 * 4;
+    static constexpr bool UNROLL = KS <= 17;
 };
 
 // where a conv item lies
