@@ -1532,16 +1532,17 @@ Plan plan_items(FwdParams &p, int Ks)
         p.n_pool = 0;
     }
 
-    // rough time shares of the arithmetic and of the pass-through traffic decide how many of
-    // a compute unit's blocks should be convolving at any time: 3:1, 1:1 or 1:3
+    // rough time shares of the arithmetic and of the pass-through traffic decide how conv
+    // and copy entries alternate (and with that how small the copy items are): 1:1, 1:2 or
+    // 1:3, thresholds from sweeps at 540 x 960 with Ks = 7 ... 31
     const double pix = (double)p.N * p.Ca * p.H * p.W;
     const double t_valu = 2.0 * Ks * Ks * pix / 50e12;  // what a conv item sustains, its loads included
     const double t_copy = 2.0 * (double)p.N * (double)p.idt_len / 4.5e12;
     unsigned a = 1, b = 1;
     if (t_valu > 0 && t_copy > 0) {
         const double share = t_valu / (t_valu + t_copy);
-        if (share < 0.375) b = 3;
-        if (share > 0.625) a = 3;
+        if (share < 0.6) b = 2;
+        if (share < 0.3) b = 3;
     }
 
     // short calls (the conv items' own chain is most of them): gentle copying, if the blocks
