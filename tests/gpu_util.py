@@ -28,11 +28,13 @@ def gen_params(wl):
     return binding.GenParams(dev(wl.w_up), dev(wl.b_up), wl.hidden, dev(wl.w_down), dev(wl.b_down))
 
 
-def run_forward(wl, use_gen=True, dk_in=None, lk=None):
-    """Full forward on the GPU.  Returns (out as numpy in storage dtype, dk float32 numpy or None)."""
+def run_forward(wl, use_gen=True, dk_in=None, lk=None, ws=None):
+    """Full forward on the GPU (in a fresh workspace unless one is given).  Returns out as
+    numpy in the storage dtype."""
     x = to_dev_x(wl.x, wl.dtype)
     lk_d = dev(wl.lk if lk is None else lk)
-    ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
+    if ws is None:
+        ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
     gen = gen_params(wl) if use_gen else None
     dk_d = dev(dk_in) if dk_in is not None else None
     out = torch.full_like(x, float("nan"))
@@ -42,9 +44,10 @@ def run_forward(wl, use_gen=True, dk_in=None, lk=None):
     return out_to_np(out, wl.dtype)
 
 
-def run_dk(wl):
+def run_dk(wl, ws=None):
     x = to_dev_x(wl.x, wl.dtype)
-    ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
+    if ws is None:
+        ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
     dk = binding.dynkernel_gen(x, wl.Ca, gen_params(wl), ws)
     assert binding.workspace_errors(ws) == 0
     return dk.cpu().numpy()

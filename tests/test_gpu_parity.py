@@ -181,6 +181,32 @@ def test_batch_equals_single_images_bit_for_bit():
         assert np.array_equal(gu.run_dk(one)[0], dk[n])
 
 
+def test_one_workspace_serves_a_sequence_of_different_calls():
+    # One workspace, sized for the largest shape, through calls that take every estimator
+    # form, both dealing schemes and both entry points, twice over: each result must equal,
+    # bit for bit, what the same call gives in a workspace of its own.
+    cases = [
+        wk.make_random(601, 2, 6, 40, 72, 4, 5, dtype=F32, x_mean=0.4),                 # conv items run the estimator
+        wk.make_random(602, 2, 6, 40, 72, 4, 13, dtype=BF16, x_mean=0.4),               # gen items, DK picked up in the loop
+        wk.make_random(603, 1, 10, 200, 704, 8, 13, dtype=F32, hidden=4, x_mean=0.4),   # channel means, one round
+        wk.make_random(604, 3, 12, 150, 400, 8, 7, dtype=BF16, x_mean=0.4),             # pool items, queue-dealt blocks
+        wk.make_random(605, 2, 5, 17, 19, 0, 13, dtype=F32),                            # copy only
+        wk.make_random(606, 40, 6, 30, 30, 4, 3, dtype=F32, x_mean=0.4),                # many small images
+    ]
+    size = max(binding.workspace_bytes(w.N, w.Ca, w.H, w.W) for w in cases)
+    ws = torch.empty(size, dtype=torch.uint8, device="cuda")
+    binding.workspace_init(ws)
+    alone = [(gu.run_forward(w), gu.run_dk(w) if w.Ca > 0 else None) for w in cases]
+    for rnd in range(2):
+        for w, (out_alone, dk_alone) in zip(cases, alone):
+            print(f"[case] shared workspace, round {rnd}, {w.name}", flush=True)
+            assert np.array_equal(gu.run_forward(w, ws=ws).view(np.uint8), out_alone.view(np.uint8))
+            if w.Ca > 0:
+                assert np.array_equal(gu.run_dk(w, ws=ws), dk_alone)
+                two_step = gu.run_forward(w, use_gen=False, dk_in=dk_alone, ws=ws)
+                assert np.array_equal(two_step.view(np.uint8), out_alone.view(np.uint8))
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_planted_non_finite_values_in_identity_channels(oracle, dtype):
     wl = wk.make_random(17, 2, 6, 20, 36, 2, 7, dtype=dtype)
