@@ -207,6 +207,54 @@ def test_one_workspace_serves_a_sequence_of_different_calls():
                 assert np.array_equal(two_step.view(np.uint8), out_alone.view(np.uint8))
 
 
+def test_captured_graph_replays_like_plain_calls():
+    # Three different calls on one workspace captured into one graph; the graph is replayed
+    # several times with plain calls and synchronisations in between, and every replay must
+    # reproduce the plain calls' outputs bit for bit (the call tag lives on the device, so a
+    # replay is a new call).
+    cases = [
+        wk.make_random(611, 2, 6, 40, 72, 4, 13, dtype=F32, x_mean=0.4),
+        wk.make_random(612, 1, 10, 200, 704, 8, 13, dtype=BF16, x_mean=0.4),
+        wk.make_random(613, 3, 12, 150, 400, 8, 7, dtype=F32, x_mean=0.4),
+    ]
+    size = max(binding.workspace_bytes(w.N, w.Ca, w.H, w.W) for w in cases)
+    ws = torch.empty(size, dtype=torch.uint8, device="cuda")
+    binding.workspace_init(ws)
+    xs = [gu.to_dev_x(w.x, w.dtype) for w in cases]
+    lks = [gu.dev(w.lk) for w in cases]
+    gens = [gu.gen_params(w) for w in cases]
+    want = [gu.run_forward(w) for w in cases]
+    outs = [torch.empty_like(x) for x in xs]
+    stream = torch.cuda.Stream()
+
+    def enqueue():
+        for w, x, lk, gen, out in zip(cases, xs, lks, gens, outs):
+            binding.convattn_forward(x, w.Ca, lk, ws, gen=gen, out=out, stream=stream)
+
+    with torch.cuda.stream(stream):
+        enqueue()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        enqueue()
+    for rep in range(4):
+        for out in outs:
+            out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            graph.replay()
+        torch.cuda.synchronize()
+        assert binding.workspace_errors(ws, stream) == 0
+        for w, out, ref in zip(cases, outs, want):
+            print(f"[case] graph replay {rep}, {w.name}", flush=True)
+            assert np.array_equal(gu.out_to_np(out, w.dtype).view(np.uint8), ref.view(np.uint8))
+        # plain work on the same workspace between replays
+        with torch.cuda.stream(stream):
+            binding.convattn_forward(xs[rep % 3], cases[rep % 3].Ca, lks[rep % 3], ws, gen=gens[rep % 3],
+                                     out=outs[rep % 3], stream=stream)
+        torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_planted_non_finite_values_in_identity_channels(oracle, dtype):
     wl = wk.make_random(17, 2, 6, 20, 36, 2, 7, dtype=dtype)
