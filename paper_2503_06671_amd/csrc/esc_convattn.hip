@@ -1516,11 +1516,12 @@ Plan plan_items(FwdParams &p, int Ks)
     const unsigned Smax = (unsigned)kBlocksPerCu * (U ? U : 1);  // resident blocks per die
     auto per_die_of = [](u64 n) { return (unsigned)((n + kXcds - 1) / kXcds); };
 
-    // Few pool tiles per image and a long tap loop: one gen item per image runs the estimator
-    // while the conv items multiply, and they pick DK up on the way (asked for inside the
-    // loop); with short loops the conv items run the estimator themselves (direct mode), one
-    // hop fewer.  Only if the gen items still fit beside all conv items (fused pooling).
-    if (p.pool_mode == kPoolItems && p.dk_mode == kDkDirect && Ks >= 9 && p.n_conv > 0 &&
+    // Few pool tiles per image: one gen item per image runs the estimator while the conv
+    // items multiply, and they pick DK up on the way (asked for inside the tap loop) - if the
+    // gen items still fit beside all conv items (fused pooling).  Otherwise the conv items
+    // run the estimator themselves (direct mode).  Measured at 180 x 320, the hop is the
+    // faster of the two for every Ks.
+    if (p.pool_mode == kPoolItems && p.dk_mode == kDkDirect && p.n_conv > 0 &&
         per_die_of(p.n_conv) + per_die_of((u64)p.N) <= Smax) {
         p.dk_mode = kDkBoxes;
         p.n_gen = (unsigned)p.N;

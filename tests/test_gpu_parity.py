@@ -88,11 +88,12 @@ def test_two_layer_estimator(oracle, Ca, hidden, bias, dtype):
     check_forward(wl, oracle)
 
 
-@pytest.mark.parametrize("Ca,hidden,bias,dtype", [(16, 8, True, F32), (48, 24, True, BF16)])
-def test_two_layer_estimator_short_tap_loop(oracle, Ca, hidden, bias, dtype):
-    # Ks < 9: the conv items run the estimator themselves (weights staged in LDS for the
-    # small estimator, read from memory for the wide one)
-    wl = wk.make_random(520 + hidden, 2, Ca + 4, 40, 72, Ca, 5, dtype=dtype, hidden=hidden, bias=bias,
+@pytest.mark.parametrize("N,Ca,hidden,bias,dtype", [(40, 16, 8, True, F32), (12, 48, 24, True, BF16)])
+def test_two_layer_estimator_run_by_the_conv_items(oracle, N, Ca, hidden, bias, dtype):
+    # more conv items than resident blocks and few pool tiles per image: pool items, and the
+    # conv items run the estimator themselves (weights staged in LDS for the small
+    # estimator, read from memory for the wide one)
+    wl = wk.make_random(520 + hidden, N, Ca + 4, 40, 72, Ca, 5, dtype=dtype, hidden=hidden, bias=bias,
                         x_mean=0.7)
     check_forward(wl, oracle)
 
