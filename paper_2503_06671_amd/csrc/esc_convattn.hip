@@ -293,7 +293,10 @@ enum : int {
     kPoolItems = 1,  // pool items read the attention slice and publish the partial sums
     kPoolFused = 2   // every conv item is resident at once: each publishes the sum of its own tile
 };
-constexpr int kDirectMaxBoxes = 512;  // direct mode while C_a * (pool tiles) mailboxes stay this few
+// an image with at most this many pool mailboxes (C_a * pool tiles) has them read in one
+// round by whoever finishes its GAP (a gen item, or each conv item); larger ones go
+// through channel-mean items
+constexpr int kDirectMaxBoxes = 512;
 constexpr int kPoolTileW = 64, kPoolTileH = 32;  // the GAP is cut into 64 x 32 pixel tiles
 constexpr int kPoolBatch = 4;                    // pool tiles per pool item
 
@@ -877,9 +880,10 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         }
     }
 
-    // Direct mode: ask for the pool sums, and for the estimator weights this channel
-    // needs, before the tap loop; look at the answers after it, so that their round trips
-    // cost nothing.
+    // What the DK phase will need is asked for ahead of it: the estimator weights this
+    // channel needs (conv items that run the estimator themselves) before the tap loop, the
+    // mailboxes (pool sums, channel means or DK itself) from inside it; the answers are
+    // looked at after the loop, so that their round trips cost nothing.
     constexpr int kPer = (kDirectMaxBoxes + kPollThreads - 1) / kPollThreads;
     const bool from_g = p->dk_mode == kDkFromG;  // the mailboxes hold channel means, not partial sums
     const bool from_boxes = p->dk_mode == kDkBoxes;  // a gen item publishes DK itself
@@ -1155,8 +1159,8 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
 
 // ---------------------------------------------------------------------------
 // copy item (Eq. 4 lines 1 and 4): copy_chunk bytes of one image's identity
-// channels, streamed 16 KiB at a time with 16-byte non-temporal accesses when both
-// sides allow it.
+// channels with 16-byte non-temporal accesses when both sides allow it: 16 KiB pieces,
+// two in flight - or, in the gentle mode, one access per thread at a time.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item)
 {
