@@ -40,8 +40,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=2000)
     ap.add_argument("--config", type=int, default=1, help="workload index 0..4")
     ap.add_argument("--ks", type=int, default=None, help="kernel size for workload 4")
     ap.add_argument("--rotate-bytes", type=float, default=1.0e9)
