@@ -6,28 +6,31 @@
 // depth-wise convolution has no reduction shared between outputs, so there is
 // nothing to feed a matrix core with).
 //
-// One launch does the whole forward.  The work is cut into items that blocks take
-// from a queue in this order:
+// One launch does the whole forward.  The work is cut into items, in this order in
+// every die's list:
 //
-//   pool items   GAP partial sums of the attention slice, one 64 x 32 pixel tile each;
+//   pool items   GAP partial sums of the attention slice, four 64 x 32 pixel tiles each;
 //                left out when every conv item is resident at once - then each conv
-//                item publishes the sums of its own tile from LDS
-//   gen items    one per image, only when an image has many pool tiles: finish the
-//                GAP, run the kernel estimator, publish DK
+//                item publishes the sums of its own tile from LDS ("fused pooling")
+//   gen items    one per image with few pool tiles: finish the GAP, run the kernel
+//                estimator, publish DK (esc_dynkernel_gen: also write it out)
+//   gsum items   instead, for images with many pool tiles: one per (image, channel),
+//                publish the channel's mean; the conv items run the estimator themselves
 //   conv items   one 64 x (16*RY) output tile of one (image, channel) plane: LK taps
 //                from an LDS halo tile with the channel's weights staged in LDS, then
-//                DK's nine taps once DK is known
+//                DK's nine taps once DK is known (asked for from inside the tap loop)
 //   copy items   a chunk of the identity channels, interleaved with the conv items so
 //                streaming and arithmetic overlap on every compute unit
 //
-// Every die of the chip gets a contiguous eighth of each kind of item, and block number
-// s of a die takes entries s, s + S, s + 2S, ... of the die's list.  An item only ever
-// waits for items earlier in the lists (conv -> gen -> pool; with fused pooling, conv
-// items of the first round for one another, after having published their own sums),
-// pool items wait for nothing and come first in every block's list, so every wait ends
-// as long as the blocks of the grid are co-resident (the host sizes the grid to what
-// the kernel is compiled to fit) - and each wait is bounded anyway: on expiry the block
-// raises the error word of the workspace and goes on.
+// Every die of the chip gets a contiguous eighth of each kind of item.  A call that fits
+// in one round of resident blocks is dealt statically; a longer one deals each die's list
+// to its eight block groups, whose blocks take entry after entry from a queue counter.
+// An item only ever waits for items that are earlier in the lists or dealt in the first
+// round, a waiting block holds no reservation on later entries, and pool items wait for
+// nothing and come first, so every wait ends as long as the blocks of the grid are
+// co-resident (the host sizes the grid to what the kernel is compiled to fit) - and each
+// wait is bounded anyway: on expiry the block raises the error word of the workspace and
+// goes on.
 //
 // Blocks talk through 64-bit mailboxes {fp32 value, 32-bit call tag} written and
 // read with relaxed device-scope atomics.  A mailbox is valid when its tag equals
@@ -39,15 +42,21 @@
 // per call, so all agree at every launch, no address is hot, and a captured launch
 // can be replayed any number of times.
 //
-// Three facts about the machine shape the code (measured, not assumed):
+// Facts about the machine that shape the code (measured, not assumed):
 //   - an FMA whose multiplier sits in a scalar register issues at half the rate of
 //     one with both operands in vector registers, so the tap weights are read from
 //     LDS (a broadcast read) into vector registers;
 //   - vector-memory results return in order, so an atomic with a slow answer delays
-//     every later load of its wavefront: the leave announcement is issued after an
-//     item's loads, by a wavefront that polls no mailbox afterwards;
+//     every later load of its wavefront: the leave announcement is issued where no
+//     wait on memory follows soon (for conv items: right before the tap loop);
 //   - a thousand atomics on one address take tens of microseconds: nothing here
-//     has more than a handful of blocks on the same word.
+//     has more than a handful of blocks on the same word;
+//   - a load behind a condition lands in a basic block of its own and the compiler then
+//     waits for it before issuing the next: loads that should overlap are unconditional
+//     (clamped addresses, results masked afterwards);
+//   - any private-segment (scratch) use costs a launch a fixed microsecond or more, and the
+//     compiler spills as soon as thread-index arithmetic is hoisted out of the item loop
+//     and held through every item: each phase takes the thread index afresh (opaque_tid).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
