@@ -21,7 +21,10 @@
  *     return; they never synchronise and never allocate.
  *   - x and out are contiguous [N, C, H, W] in the storage type `dt`; out must
  *     not overlap x.  lk, the estimator weights, dk and the workspace are fp32
- *     in both storage modes.
+ *     in both storage modes.  With bf16 storage and Ks <= 17 the large-kernel
+ *     weights are rounded to bf16 on the device before use (products are exact,
+ *     accumulation stays fp32); a pixel of the attention slice that is not
+ *     finite may then also spoil the output one column beyond the kernel's reach.
  *   - All arguments are validated on the host before the first launch; a call
  *     that returns an error has enqueued nothing.
  *   - Every compute call needs a workspace (work queue and the mailboxes blocks

@@ -167,6 +167,19 @@ __device__ __forceinline__ void load4(const bf16_t *p, float *v)
     v[3] = __uint_as_float(w.y & 0xffff0000u);
 }
 
+// the same four bf16 elements, left as they are (two per 32-bit word, lower address low)
+__device__ __forceinline__ uint2 load4_raw(const bf16_t *p) { return *reinterpret_cast<const uint2 *>(p); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// c + a.lo * b.lo + a.hi * b.hi on pairs of bf16, accumulated in fp32: one instruction,
+// two taps
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
 // x / d for x < 2^31 by multiply-high and shift (host fills mul and shift)
 struct FastDiv {
     uint32_t d, mul, shift;
@@ -754,6 +767,28 @@ struct ConvGeom {
     static constexpr bool UNROLL = KS <= 17;
 };
 
+// bf16 storage with an unrolled tap loop: the halo tile stays bf16 in LDS, two pixels per
+// 32-bit word exactly as they lie in memory (word w of a row holds the pixels at global
+// x = g0 + 2w, g0 + 2w + 1 with g0 a multiple of four), and a kernel row is staged as
+// pairs of bf16 weights in two phases: (w0,w1),(w2,w3),... for outputs whose first tap
+// falls on an even tile column, (0,w0),(w1,w2),... for the others.  One dot2 then applies
+// two taps, on words that are always aligned pairs.
+template <int KS, int RY>
+struct PackedGeom {
+    using G = ConvGeom<KS, RY>;
+    static constexpr int A = (4 - G::PH % 4) % 4;     // tile columns before the halo's first, so chunks stay aligned
+    static constexpr int NCH = (G::HC + A + 3) / 4;   // 4-pixel chunks per tile row
+    static constexpr int PITCH_E = 4 * NCH, PITCH_D = 2 * NCH;
+    static constexpr int S0 = A + G::OFF;             // tile column of tap 0 for output 0 of thread column 0
+    static constexpr int NP = (KS + 1) / 2;           // weight pairs per kernel row and phase
+    static constexpr int DSTART = (S0 >> 1) & ~1;     // first word a thread reads of a row (relative to 2*tx), even
+    static constexpr int DLAST = ((3 + S0) >> 1) + NP - 1;
+    static constexpr int NVD = ((DLAST - DSTART + 1) + 1) & ~1;  // words per row and thread, even
+    static constexpr int WPD = (2 * NP + 3) & ~3;     // words per staged kernel row
+    static_assert(30 + DSTART + NVD <= PITCH_D, "a thread would read past its tile row");
+    static_assert(G::HR * PITCH_D <= kLdsTileFloats && KS * WPD <= kLdsWeightFloats, "LDS pool too small");
+};
+
 // where a conv item lies
 struct ConvWhere {
     unsigned n, nc;
@@ -786,6 +821,11 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     ESC_TRACE_INIT(rec);
     constexpr int PH = G::PH, OFF = G::OFF, TH = G::TH, HR = G::HR, HC = G::HC, PITCH = G::PITCH,
                   NV = G::NV, WP = G::WP;
+    // bf16 storage and an unrolled loop: packed tile, two taps per instruction (PackedGeom)
+    constexpr bool kPacked = std::is_same<T, bf16_t>::value && G::UNROLL;
+    using PG = PackedGeom<KS, RY>;
+    uint32_t *tile_d = reinterpret_cast<uint32_t *>(g_tile), *wl_d = reinterpret_cast<uint32_t *>(g_wl);
+    uint16_t *tile_h = reinterpret_cast<uint16_t *>(g_tile);
     const int H = p->H, W = p->W;
 
     // ---- phase 1: fetch the halo tile and the channel's weights into LDS ----
@@ -802,10 +842,25 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // is computed once per kernel and then held in registers through all items)
     const int tid1 = opaque_tid();
     float wreg[KW];
+    constexpr int KWP = (KS * 2 * PG::NP + kThreads - 1) / kThreads;  // packed: one weight pair per thread and round
+    float wpa[KWP], wpb[KWP];
+    if constexpr (kPacked) {
 #pragma unroll
-    for (int m = 0; m < KW; ++m) {
-        const int idx = m * kThreads + tid1;
-        wreg[m] = idx < KS * KS ? lkc[idx] : 0.f;
+        for (int m = 0; m < KWP; ++m) {
+            const int idx = m * kThreads + tid1;
+            const int i = idx / (2 * PG::NP), rem = idx - i * (2 * PG::NP);
+            const int ph = rem / PG::NP, mm = rem - ph * PG::NP;
+            const int ja = 2 * mm - ph, jb = ja + 1;  // the two taps of this pair
+            const bool in = idx < KS * 2 * PG::NP;
+            wpa[m] = (in && ja >= 0 && ja < KS) ? lkc[i * KS + ja] : 0.f;
+            wpb[m] = (in && jb < KS) ? lkc[i * KS + jb] : 0.f;
+        }
+    } else {
+#pragma unroll
+        for (int m = 0; m < KW; ++m) {
+            const int idx = m * kThreads + tid1;
+            wreg[m] = idx < KS * KS ? lkc[idx] : 0.f;
+        }
     }
 
     // halo tile -> LDS, zero outside the image
@@ -819,21 +874,31 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         constexpr int K = (TOT + kThreads - 1) / kThreads;
         const int g0 = x0 - PH - A;
         float v[K][4];
+        uint2 raw[K];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int q = k * kThreads + tid1;
             const int r = q / NCH, j = q - r * NCH;
             const int gy = y0 - PH + r, gx = g0 + 4 * j;
+            const bool in = q < TOT && gy >= 0 && gy < H && gx >= 0 && gx < W;
+            if constexpr (kPacked) {
+                raw[k] = make_uint2(0u, 0u);
+                if constexpr (std::is_same<T, bf16_t>::value)
+                    if (in) raw[k] = load4_raw(xp + (size_t)gy * W + gx);
+            } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[k][e] = 0.f;
-            if (q < TOT && gy >= 0 && gy < H && gx >= 0 && gx < W) load4(xp + (size_t)gy * W + gx, v[k]);
+                for (int e = 0; e < 4; ++e) v[k][e] = 0.f;
+                if (in) load4(xp + (size_t)gy * W + gx, v[k]);
+            }
         }
         if (p->pool_mode != kPoolNone) need_tag(p, ctx);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int q = k * kThreads + tid1;
             const int r = q / NCH, j = q - r * NCH;
-            if (q < TOT) {
+            if constexpr (kPacked) {  // the chunk goes where it lies: word 2j of row r
+                if (q < TOT) *reinterpret_cast<uint2 *>(tile_d + r * PG::PITCH_D + 2 * j) = raw[k];
+            } else if (q < TOT) {
                 float *dst = tile + r * PITCH + 4 * j - A;
                 if (A == 0) {
                     *reinterpret_cast<float4 *>(dst) = make_float4(v[k][0], v[k][1], v[k][2], v[k][3]);
@@ -846,6 +911,19 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
                 }
             }
         }
+    } else if constexpr (kPacked) {
+        // element by element, the whole pitch of every row (what lies beyond the halo is
+        // multiplied by the zero half of a weight pair and must not be stale LDS)
+        if constexpr (std::is_same<T, bf16_t>::value) {
+            for (int idx = tid1; idx < HR * PG::PITCH_E; idx += kThreads) {
+                const int r = idx / PG::PITCH_E, cc = idx - r * PG::PITCH_E;
+                const int gy = y0 - PH + r, gx = x0 - PH - PG::A + cc;
+                uint16_t v = 0;
+                if (gy >= 0 && gy < H && gx >= 0 && gx < W) v = xp[(size_t)gy * W + gx].bits;
+                tile_h[idx] = v;
+            }
+        }
+        if (p->pool_mode != kPoolNone) need_tag(p, ctx);
     } else {
         for (int idx = tid1; idx < HR * HC; idx += kThreads) {
             const int r = idx / HC, cc = idx - r * HC;
@@ -856,10 +934,20 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         }
         if (p->pool_mode != kPoolNone) need_tag(p, ctx);
     }
+    if constexpr (kPacked) {
 #pragma unroll
-    for (int m = 0; m < KW; ++m) {
-        const int idx = m * kThreads + tid1;
-        if (idx < KS * KS) wl[(idx / KS) * WP + idx % KS] = wreg[m];
+        for (int m = 0; m < KWP; ++m) {
+            const int idx = m * kThreads + tid1;
+            const int i = idx / (2 * PG::NP), rem = idx - i * (2 * PG::NP);
+            if (idx < KS * 2 * PG::NP)
+                wl_d[i * PG::WPD + rem] = (uint32_t)f32_to_bf16_bits(wpa[m]) | ((uint32_t)f32_to_bf16_bits(wpb[m]) << 16);
+        }
+    } else {
+#pragma unroll
+        for (int m = 0; m < KW; ++m) {
+            const int idx = m * kThreads + tid1;
+            if (idx < KS * KS) wl[(idx / KS) * WP + idx % KS] = wreg[m];
+        }
     }
     __syncthreads();
     ESC_STAMP(rec, 3);
@@ -878,9 +966,18 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
                 float s = 0.f;
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
-                    const float *src = tile + (h * kPoolTileH + 2 * ty + a + PH) * PITCH + 4 * tx + PH;
+                    if constexpr (kPacked) {  // the same four pixels, in the same order
+                        const uint2 w2 = *reinterpret_cast<const uint2 *>(
+                            tile_d + (h * kPoolTileH + 2 * ty + a + PH) * PG::PITCH_D + 2 * tx + (PH + PG::A) / 2);
+                        s += bf16_lo(w2.x);
+                        s += bf16_hi(w2.x);
+                        s += bf16_lo(w2.y);
+                        s += bf16_hi(w2.y);
+                    } else {
+                        const float *src = tile + (h * kPoolTileH + 2 * ty + a + PH) * PITCH + 4 * tx + PH;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) s += src[q];
+                        for (int q = 0; q < 4; ++q) s += src[q];
+                    }
                 }
                 const unsigned box = (nc * (unsigned)p->ptiles) + pty * (unsigned)p->ptiles_x + (unsigned)txi;
                 pool_finish(p, s, box, ctx.tag, s_dk);
@@ -948,14 +1045,27 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         for (int q = 0; q < 4; ++q) acc[oy][q] = 0.f;
 
     const float *trow = tile + (ty * RY) * PITCH + 4 * tx;
+    const uint32_t *trow_p = tile_d + (ty * RY + OFF) * PG::PITCH_D + 2 * tx + PG::DSTART;  // packed tile
 
     // The tap loop, software-pipelined by hand so that the register use is ours to decide:
     // while row r is multiplied, tile row r+1 is already on its way from LDS (two buffers),
     // and kernel row r - the only new one - arrives while the older kernel rows, held in
     // registers from the steps before, are applied first.  A scheduling barrier ends every
     // step so the compiler cannot pull later rows' loads up and run out of registers.
-    auto load_x = [&](int r, float *v) {
-        if (OFF == 0) {
+    // XT is what a tile row and a kernel row are held as: floats, or words of two bf16.
+    using XT = typename std::conditional<kPacked, uint32_t, float>::type;
+    constexpr int NX = kPacked ? PG::NVD : NV;       // values of a tile row per thread
+    constexpr int NWT = kPacked ? 2 * PG::NP : KS;   // values of a kernel row
+    auto load_x = [&](int r, XT *v) {
+        if constexpr (kPacked) {
+            const uint2 *src = reinterpret_cast<const uint2 *>(trow_p + r * PG::PITCH_D);
+#pragma unroll
+            for (int k = 0; k < NX / 2; ++k) {
+                const uint2 f = src[k];
+                v[2 * k + 0] = f.x;
+                v[2 * k + 1] = f.y;
+            }
+        } else if (OFF == 0) {
             const float4 *src = reinterpret_cast<const float4 *>(trow + r * PITCH);
 #pragma unroll
             for (int k = 0; k < NV / 4; ++k) {
@@ -971,33 +1081,57 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             for (int k = 0; k < NV; ++k) v[k] = k < KS + 3 ? src[k] : 0.f;
         }
     };
-    auto load_w = [&](int i, float *w) {
-        const float *wsrc = wl + i * WP;
+    auto load_w = [&](int i, XT *w) {
+        if constexpr (kPacked) {
+            const uint32_t *wsrc = wl_d + i * PG::WPD;
 #pragma unroll
-        for (int k = 0; k + 4 <= KS; k += 4) {
-            const float4 f = *reinterpret_cast<const float4 *>(wsrc + k);
-            w[k + 0] = f.x;
-            w[k + 1] = f.y;
-            w[k + 2] = f.z;
-            w[k + 3] = f.w;
+            for (int k = 0; k + 4 <= NWT; k += 4) {
+                const uint4 f = *reinterpret_cast<const uint4 *>(wsrc + k);
+                w[k + 0] = f.x;
+                w[k + 1] = f.y;
+                w[k + 2] = f.z;
+                w[k + 3] = f.w;
+            }
+#pragma unroll
+            for (int k = NWT & ~3; k < NWT; ++k) w[k] = wsrc[k];
+        } else {
+            const float *wsrc = wl + i * WP;
+#pragma unroll
+            for (int k = 0; k + 4 <= KS; k += 4) {
+                const float4 f = *reinterpret_cast<const float4 *>(wsrc + k);
+                w[k + 0] = f.x;
+                w[k + 1] = f.y;
+                w[k + 2] = f.z;
+                w[k + 3] = f.w;
+            }
+#pragma unroll
+            for (int k = KS & ~3; k < KS; ++k) w[k] = wsrc[k];
         }
-#pragma unroll
-        for (int k = KS & ~3; k < KS; ++k) w[k] = wsrc[k];
     };
-    auto fma_row = [&](float *a, const float *w, const float *v) {
+    // packed: output q of the thread starts at tile column 4*tx + q + S0; its pairs are the
+    // row's words from ((q + S0) >> 1) on, with the weight pairs of that column's parity
+    auto fma_row = [&](float *a, const XT *w, const XT *v) {
+        if constexpr (kPacked) {
 #pragma unroll
-        for (int j = 0; j < KS; ++j)
+            for (int m = 0; m < PG::NP; ++m)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) a[q] = fmaf(w[j], v[j + q], a[q]);
+                for (int q = 0; q < 4; ++q)
+                    a[q] = dot2_bf16(w[((q + PG::S0) & 1) * PG::NP + m], v[((q + PG::S0) >> 1) - PG::DSTART + m], a[q]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < KS; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a[q] = fmaf(w[j], v[j + q], a[q]);
+        }
     };
     // what may move across a step boundary: arithmetic and global memory, not LDS traffic
     constexpr int kSchedNoLds = 0x1 | 0x2 | 0x4 | 0x10 | 0x20 | 0x40;
-    constexpr bool kTwoX = 2 * NV + RY * KS + 4 * RY <= 96;  // room for a second tile-row buffer
-    float X[kTwoX ? 2 : 1][NV];
-    float Wt[RY][KS];  // kernel row i lives in slot i % RY while it is in use
+    constexpr bool kTwoX = 2 * NX + RY * NWT + 4 * RY <= 96;  // room for a second tile-row buffer
+    XT X[kTwoX ? 2 : 1][NX];
+    XT Wt[RY][NWT];  // kernel row i lives in slot i % RY while it is in use
     if (kTwoX) load_x(0, X[0]);
     auto step = [&](int r, int u) {  // u == r % RY, and RY is even
-        float *xc = X[kTwoX ? (u & 1) : 0];
+        XT *xc = X[kTwoX ? (u & 1) : 0];
         if (kTwoX) {
             if (r + 1 < G::ROWS) load_x(r + 1, X[(u + 1) & 1]);
         } else {
@@ -1007,13 +1141,24 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         if (r >= RY - 1 && r < KS) {
             // every output row of the thread takes part: interleave them tap by tap, oldest
             // kernel row first, so that 4*RY independent accumulators are in flight
+            if constexpr (kPacked) {
 #pragma unroll
-            for (int j = 0; j < KS; ++j)
+                for (int m = 0; m < PG::NP; ++m)
 #pragma unroll
-                for (int k = RY - 1; k >= 0; --k)
+                    for (int k = RY - 1; k >= 0; --k)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        acc[k][q] = fmaf(Wt[(u - k + RY) % RY][j], xc[j + q], acc[k][q]);
+                        for (int q = 0; q < 4; ++q)
+                            acc[k][q] = dot2_bf16(Wt[(u - k + RY) % RY][((q + PG::S0) & 1) * PG::NP + m],
+                                                  xc[((q + PG::S0) >> 1) - PG::DSTART + m], acc[k][q]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < KS; ++j)
+#pragma unroll
+                    for (int k = RY - 1; k >= 0; --k)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            acc[k][q] = fmaf(Wt[(u - k + RY) % RY][j], xc[j + q], acc[k][q]);
+            }
         } else {
 #pragma unroll
             for (int k = RY - 1; k >= 0; --k) {  // output row k of this thread: kernel row r - k
@@ -1049,13 +1194,13 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         // every output row instead of being held (they would not fit in the registers).
 #pragma unroll 2
         for (int r = 0; r < G::ROWS; ++r) {
-            float xr[NV];
+            XT xr[NX];
             load_x(r, xr);
 #pragma unroll
             for (int k = 0; k < RY; ++k) {
                 const int i = r - k;
                 if (i >= 0 && i < KS) {
-                    float wr[KS];
+                    XT wr[NWT];
                     load_w(i, wr);
                     fma_row(acc[k], wr, xr);
                 }
@@ -1130,9 +1275,22 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
 #pragma unroll
         for (int r = 0; r < RY + 2; ++r) {
             float v[6];
-            const float *src = trow_d + (r + PH - 1) * PITCH + (PH - 1);
+            if constexpr (kPacked) {
+                // tile columns 4*tx + PH + A - 1 ... + 4: the four words from one before the
+                // thread's first interior pixel, of which the first and the last halves are unused
+                const uint32_t *src = tile_d + (ty_d * RY + r + PH - 1) * PG::PITCH_D + 2 * tx_d + (PH + PG::A) / 2 - 1;
+                const uint32_t w0 = src[0], w1 = src[1], w2 = src[2], w3 = src[3];
+                v[0] = bf16_hi(w0);
+                v[1] = bf16_lo(w1);
+                v[2] = bf16_hi(w1);
+                v[3] = bf16_lo(w2);
+                v[4] = bf16_hi(w2);
+                v[5] = bf16_lo(w3);
+            } else {
+                const float *src = trow_d + (r + PH - 1) * PITCH + (PH - 1);
 #pragma unroll
-            for (int k = 0; k < 6; ++k) v[k] = src[k];
+                for (int k = 0; k < 6; ++k) v[k] = src[k];
+            }
 #pragma unroll
             for (int oy = 0; oy < RY; ++oy) {
                 const int i = r - oy;
