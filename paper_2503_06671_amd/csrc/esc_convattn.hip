@@ -96,6 +96,7 @@ typedef unsigned long long u64;
 struct Trace {
     u64 t[16];
 };
+__shared__ u64 g_dbg[4];
 #define ESC_STAMP(rec, k) ((rec).t[k] = wall_clock64())
 #define ESC_TRACE_INIT(rec)                          \
     do {                                             \
@@ -237,6 +238,9 @@ __device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *d
 #pragma unroll
     for (int u = 0; u < PER; ++u) pend[u] = tid < kPollThreads && tid + u * kPollThreads < cnt;
     bool any = false;
+#ifdef ESC_TRACE
+    if (threadIdx.x == 0) g_dbg[1] = wall_clock64();
+#endif
     for (unsigned spin = 0; spin < kSpinLimit; ++spin) {
         if (spin > 0 || !have_first) {
 #pragma unroll
@@ -256,6 +260,12 @@ __device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *d
                     any = true;
                 }
             }
+#ifdef ESC_TRACE
+        if (threadIdx.x == 0) {
+            if (spin < 1) g_dbg[spin] = wall_clock64();
+            g_dbg[3] = spin + 1;
+        }
+#endif
         if (!any) break;
         __builtin_amdgcn_s_sleep(2);
     }
@@ -388,6 +398,9 @@ __shared__ float g_g[kMaxCa];
 __shared__ float g_t[kMaxHidden];
 __shared__ float g_small[16];
 __shared__ unsigned g_next[2];
+#ifdef ESC_TRACE
+__shared__ u64 g_wave_end[4];
+#endif
 
 // Per-block state that item code touches.
 struct Ctx {
@@ -623,7 +636,13 @@ __device__ __forceinline__ void estimator_front(ParamsPtr p, uint32_t tag, unsig
         for (int c0 = c_first; c0 < c_end; c0 += G) {
             const int gc = c_end - c0 < G ? c_end - c0 : G;
             boxes_to_lds(img_boxes + (size_t)c0 * ntile, gc * ntile, s_part, tag, p->err, polled, false);
+#ifdef ESC_TRACE
+            if (threadIdx.x == 0) g_wave_end[0] = wall_clock64();  // thread 0 has its mailboxes
+#endif
             __syncthreads();
+#ifdef ESC_TRACE
+            if (threadIdx.x == 0) g_wave_end[1] = wall_clock64();  // every thread has
+#endif
             sum_staged(s_part, ntile, gc, c0, p->hw, s_g);
             __syncthreads();
         }
@@ -709,6 +728,15 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
             box_put(p->dk_box + idx, s, ctx.tag);
             if (p->dk_out) p->dk_out[idx] = s;
         }
+        ESC_STAMP(rec, 4);
+#ifdef ESC_TRACE
+        rec.t[7] = g_wave_end[0];
+        rec.t[8] = g_wave_end[1];
+        rec.t[9] = g_dbg[0];
+        rec.t[10] = g_dbg[1];
+        rec.t[11] = g_dbg[2];
+        rec.t[12] = g_dbg[3];
+#endif
     } else {
         for (int o = threadIdx.x; o < 9 * Ca; o += kThreads) {
             const float s = estimator_out(p, o, s_g, s_t);
@@ -951,6 +979,13 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     }
     __syncthreads();
     ESC_STAMP(rec, 3);
+    // The leave is announced here: everything the block has loaded so far has arrived, and
+    // the announcing wavefront's atomic is then in flight during the tap loop, which waits
+    // for no memory access (anywhere earlier, the next wait for a load would wait for the
+    // atomic as well - results return in order; any later, behind the pool mailbox's store,
+    // the wait for the call tag in front of the announcement would wait for that store's
+    // round trip too).
+    announce_leave(p, ctx);
 
     const int tid2 = opaque_tid();
     const int tx = tid2 & 15, ty = tid2 >> 4;
@@ -981,6 +1016,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
                 }
                 const unsigned box = (nc * (unsigned)p->ptiles) + pty * (unsigned)p->ptiles_x + (unsigned)txi;
                 pool_finish(p, s, box, ctx.tag, s_dk);
+                ESC_STAMP(rec, 10);
                 __syncthreads();  // s_dk is reused
             }
         }
@@ -1168,15 +1204,12 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         }
         __builtin_amdgcn_sched_barrier(kSchedNoLds);
     };
-    // The leave is announced here: the announcing wavefront's atomic is then in flight
-    // during the tap loop, which waits for no memory access (anywhere earlier, the next
-    // wait for a load would wait for the atomic as well - results return in order).
-    announce_leave(p, ctx);
     // The tap loop is the one long stretch of pure arithmetic: it runs at the lowest
     // wavefront priority, everything else (issuing loads, the serial estimator code, the
     // stores) above it, so that the short latency-bound phases of one block are not starved
     // by the tap loops of the other blocks on the compute unit.
     __builtin_amdgcn_s_setprio(0);
+    ESC_STAMP(rec, 11);
     // The early requests go out before the loop (in its middle they cost the compiler so
     // many registers that it spills); whatever has not arrived by the end is asked for again.
     ask_early();
@@ -1216,6 +1249,9 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
 #endif
     __builtin_amdgcn_s_setprio(kPrioHigh);
     ESC_STAMP(rec, 4);
+#ifdef ESC_TRACE
+    if ((threadIdx.x & 63) == 0) g_wave_end[threadIdx.x >> 6] = wall_clock64();  // when each wavefront left the loop
+#endif
 
     // ---- phase 3: DK and the stores, located afresh (see opaque_u) ----
     const ConvWhere wd = conv_where<TH>(p, opaque_u(item_in));
@@ -1269,6 +1305,13 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         __syncthreads();
         claim_next(p, ctx);  // the wait for the estimator is over
         ESC_STAMP(rec, 5);
+#ifdef ESC_TRACE
+        if (from_boxes) {
+            rec.t[7] = g_wave_end[1];
+            rec.t[8] = g_wave_end[2];
+            rec.t[9] = g_wave_end[3];
+        }
+#endif
         float d[9];
 #pragma unroll
         for (int k = 0; k < 9; ++k) d[k] = s_dk[k];
