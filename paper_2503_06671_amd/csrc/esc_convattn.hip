@@ -397,6 +397,7 @@ __shared__ float g_part[kStage];
 __shared__ float g_g[kMaxCa];
 __shared__ float g_t[kMaxHidden];
 __shared__ float g_small[16];
+__shared__ float g_red[4 * kPoolBatch];  // wavefront totals of the pool tiles being finished
 __shared__ unsigned g_next[2];
 #ifdef ESC_TRACE
 __shared__ u64 g_wave_end[4];
@@ -460,6 +461,17 @@ __device__ __forceinline__ void announce_leave(ParamsPtr p, Ctx &ctx)
     }
 }
 
+// The same, for a caller that has just passed a block barrier behind which every wavefront
+// holds its copy of the call tag (need_tag called, and its load waited for, before it).
+__device__ __forceinline__ void announce_leave_synced(unsigned *group_done, Ctx &ctx)
+{
+    if (ctx.last_item && !ctx.announced) {
+        if (threadIdx.x == kThreads - 1)
+            ctx.left = __hip_atomic_fetch_add(group_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ctx.announced = true;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // GAP partial sums (Eq. 4 line 2, first half).  A plane is cut into 64 x 32 pixel
 // tiles.  Thread (tx, ty) = (t & 15, t >> 4) adds pixels (2*ty + a, 4*tx + q) of the
@@ -469,16 +481,27 @@ __device__ __forceinline__ void announce_leave(ParamsPtr p, Ctx &ctx)
 // item's LDS tile, and depends on H and W only - so a batch reproduces its images run
 // alone, and esc_dynkernel_gen reproduces the DK of the forward bit for bit.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void pool_finish(ParamsPtr p, float s, unsigned box, uint32_t tag, float *s_red)
+template <int NB>
+__device__ __forceinline__ void pool_finish(u64 *pool_box, const float (&s)[NB], const unsigned (&box)[NB],
+                                            const bool (&have)[NB], uint32_t tag, float *s_red)
 {
-    s = wave_sum(s);
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float t = s_red[0];
+    // NB tiles at once (s_red holds 4 * NB floats): every tile's four wavefront totals, one
+    // barrier, then thread b adds tile b's totals in ascending order and publishes the sum.
+    // The caller keeps s_red untouched until the block's next barrier.
 #pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) t += s_red[w];
-        box_put(p->pool_box + box, t, tag);
+    for (int b = 0; b < NB; ++b) {
+        const float w = wave_sum(s[b]);
+        if ((threadIdx.x & 63) == 0) s_red[b * (kThreads / 64) + (threadIdx.x >> 6)] = w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if ((int)threadIdx.x == b && have[b]) {
+            float t = s_red[b * (kThreads / 64)];
+#pragma unroll
+            for (int w = 1; w < kThreads / 64; ++w) t += s_red[b * (kThreads / 64) + w];
+            box_put(pool_box + box[b], t, tag);
+        }
     }
 }
 
@@ -489,7 +512,7 @@ __device__ __forceinline__ void pool_finish(ParamsPtr p, float s, unsigned box, 
 template <typename T>
 __device__ __forceinline__ ItemOut pool_item(ParamsPtr p, Ctx ctx, unsigned item)
 {
-    float *s_red = g_small;
+    float *s_red = g_red;
     Trace rec;
     ESC_TRACE_INIT(rec);
     const int H = p->H, W = p->W;
@@ -527,18 +550,21 @@ __device__ __forceinline__ ItemOut pool_item(ParamsPtr p, Ctx ctx, unsigned item
     }
     need_tag(p, ctx);
     announce_leave(p, ctx);
+    float sums[kPoolBatch];
+    unsigned box[kPoolBatch];
+    bool have[kPoolBatch];
 #pragma unroll
     for (int b = 0; b < kPoolBatch; ++b) {
-        if (first + b < ntiles) {  // block-uniform
-            float s = 0.f;
+        float s = 0.f;
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) s += v[b][a][q];
-            pool_finish(p, s, first + b, ctx.tag, s_red);
-            __syncthreads();  // s_red is reused
-        }
+            for (int q = 0; q < 4; ++q) s += v[b][a][q];
+        sums[b] = s;
+        box[b] = first + b;
+        have[b] = first + b < ntiles;
     }
+    pool_finish<kPoolBatch>(p->pool_box, sums, box, have, ctx.tag, s_red);
     ESC_STAMP(rec, 6);
     return ItemOut{ctx, rec};
 }
@@ -919,7 +945,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
                 if (in) load4(xp + (size_t)gy * W + gx, v[k]);
             }
         }
-        if (p->pool_mode != kPoolNone) need_tag(p, ctx);
+        if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int q = k * kThreads + tid1;
@@ -951,7 +977,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
                 tile_h[idx] = v;
             }
         }
-        if (p->pool_mode != kPoolNone) need_tag(p, ctx);
+        if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
     } else {
         for (int idx = tid1; idx < HR * HC; idx += kThreads) {
             const int r = idx / HC, cc = idx - r * HC;
@@ -960,7 +986,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             if (gy >= 0 && gy < H && gx >= 0 && gx < W) v = to_f32(xp[(size_t)gy * W + gx]);
             tile[r * PITCH + cc] = v;
         }
-        if (p->pool_mode != kPoolNone) need_tag(p, ctx);
+        if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
     }
     if constexpr (kPacked) {
 #pragma unroll
@@ -977,15 +1003,17 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             if (idx < KS * KS) wl[(idx / KS) * WP + idx % KS] = wreg[m];
         }
     }
+    // (the call tag, asked for behind the tile, has arrived in this wavefront too)
+    asm volatile("" ::"v"(ctx.tag));
     __syncthreads();
     ESC_STAMP(rec, 3);
-    // The leave is announced here: everything the block has loaded so far has arrived, and
-    // the announcing wavefront's atomic is then in flight during the tap loop, which waits
-    // for no memory access (anywhere earlier, the next wait for a load would wait for the
-    // atomic as well - results return in order; any later, behind the pool mailbox's store,
-    // the wait for the call tag in front of the announcement would wait for that store's
-    // round trip too).
-    announce_leave(p, ctx);
+    // The leave is announced here: every wavefront of the block has its tile and its copy of
+    // the call tag (the barrier above), and the announcing wavefront's atomic is then in
+    // flight during the tap loop, which waits for no memory access.  Anywhere earlier, the
+    // next wait for a load would wait for the atomic as well - results return in order; any
+    // later, behind the pool mailbox's store, a wait for the tag would wait for that store's
+    // round trip too.
+    announce_leave_synced(p->done + (blockIdx.x % kGroups) * kCtlStride, ctx);
 
     const int tid2 = opaque_tid();
     const int tx = tid2 & 15, ty = tid2 >> 4;
@@ -994,32 +1022,35 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // pool tiles this tile covers, straight from LDS, instead of reading the plane twice.
     if (p->pool_mode == kPoolFused) {
         constexpr int NPT = TH / kPoolTileH;  // pool tiles stacked in this conv tile
+        static_assert(NPT <= kPoolBatch, "g_red holds kPoolBatch tiles");
+        float sums[NPT];
+        unsigned box[NPT];
+        bool have[NPT];
 #pragma unroll
         for (int h = 0; h < NPT; ++h) {
             const unsigned pty = (unsigned)tyi * NPT + h;
-            if ((int)pty * kPoolTileH < H) {  // block-uniform
-                float s = 0.f;
+            float s = 0.f;
 #pragma unroll
-                for (int a = 0; a < 2; ++a) {
-                    if constexpr (kPacked) {  // the same four pixels, in the same order
-                        const uint2 w2 = *reinterpret_cast<const uint2 *>(
-                            tile_d + (h * kPoolTileH + 2 * ty + a + PH) * PG::PITCH_D + 2 * tx + (PH + PG::A) / 2);
-                        s += bf16_lo(w2.x);
-                        s += bf16_hi(w2.x);
-                        s += bf16_lo(w2.y);
-                        s += bf16_hi(w2.y);
-                    } else {
-                        const float *src = tile + (h * kPoolTileH + 2 * ty + a + PH) * PITCH + 4 * tx + PH;
+            for (int a = 0; a < 2; ++a) {
+                if constexpr (kPacked) {  // the same four pixels, in the same order
+                    const uint2 w2 = *reinterpret_cast<const uint2 *>(
+                        tile_d + (h * kPoolTileH + 2 * ty + a + PH) * PG::PITCH_D + 2 * tx + (PH + PG::A) / 2);
+                    s += bf16_lo(w2.x);
+                    s += bf16_hi(w2.x);
+                    s += bf16_lo(w2.y);
+                    s += bf16_hi(w2.y);
+                } else {
+                    const float *src = tile + (h * kPoolTileH + 2 * ty + a + PH) * PITCH + 4 * tx + PH;
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) s += src[q];
-                    }
+                    for (int q = 0; q < 4; ++q) s += src[q];
                 }
-                const unsigned box = (nc * (unsigned)p->ptiles) + pty * (unsigned)p->ptiles_x + (unsigned)txi;
-                pool_finish(p, s, box, ctx.tag, s_dk);
-                ESC_STAMP(rec, 10);
-                __syncthreads();  // s_dk is reused
             }
+            sums[h] = s;
+            box[h] = (nc * (unsigned)p->ptiles) + pty * (unsigned)p->ptiles_x + (unsigned)txi;
+            have[h] = (int)pty * kPoolTileH < H;  // block-uniform
         }
+        pool_finish<NPT>(p->pool_box, sums, box, have, ctx.tag, g_red);
+        ESC_STAMP(rec, 10);
     }
 
     // What the DK phase will need is asked for ahead of it: the estimator weights this
