@@ -1515,8 +1515,8 @@ __device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item
 template <int KS, int RY, typename T>
 __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const FwdParams params)
 {
-    // the item functions are real calls, each with its own register allocation; they read
-    // the parameters from the kernel argument segment, which starts with `params`
+    // the item functions (all inlined here) read the parameters from the kernel argument
+    // segment, which starts with `params`, where they need them
     (void)params;
     ParamsPtr p = (ParamsPtr)__builtin_amdgcn_kernarg_segment_ptr();
     __builtin_amdgcn_s_setprio(kPrioHigh);
@@ -1778,9 +1778,9 @@ Plan plan_items(FwdParams &p, int Ks)
         p.n_pool = 0;
     }
 
-    // rough time shares of the arithmetic and of the pass-through traffic decide how conv
-    // and copy entries alternate (and with that how small the copy items are): 1:1, 1:2 or
-    // 1:3, thresholds from sweeps at 540 x 960 with Ks = 7 ... 31
+    // rough time shares of the arithmetic and of the pass-through traffic decide how many
+    // copy items there are to a conv item (and with that how small they are): 1, 2 or 3,
+    // thresholds from sweeps at 540 x 960 with Ks = 7 ... 31
     const double pix = (double)p.N * p.Ca * p.H * p.W;
     const double t_valu = 2.0 * Ks * Ks * pix / 50e12;  // what a conv item sustains, its loads included
     const double t_copy = 2.0 * (double)p.N * (double)p.idt_len / 4.5e12;
@@ -1828,14 +1828,23 @@ Plan plan_items(FwdParams &p, int Ks)
         p.n_copy = (unsigned)(chunks * p.N);
     }
 
-    // Alternation in layers of U entries, so that consecutive blocks - which the dispatcher
-    // spreads over a die's compute units - are of one kind and every unit gets every kind.
-    // With 3 resident layers and a pattern of 2 or 4 layers a block changes kind every round.
+    // Alternation in layers, so that consecutive blocks - which the dispatcher spreads over a
+    // die's compute units - are of one kind and every unit gets every kind: U conv entries,
+    // then copy entries in proportion to what there is of each kind - times 3/4, so that the
+    // conv entries (the long ones) run out first and the list ends with copy entries, which
+    // even out the end of the call (measured at 540 x 960: 2 - 3 % over plain proportion for
+    // Ks = 7 ... 17, and over the fixed 1:1 / 1:2 / 1:3 patterns before it).
     if (p.pool_mode == kPoolFused) {
         p.mix_a = p.mix_b = 1u << 30;  // all conv items first: they must all be in the first round
     } else {
-        p.mix_a = a * (U ? U : 1);
-        p.mix_b = b * (U ? U : 1);
+        const unsigned Ul = U ? U : 1;
+        p.mix_a = Ul;
+        p.mix_b = Ul;
+        if (p.n_conv > 0 && p.n_copy > 0) {
+            const double share = 0.75 * (double)p.n_copy / (double)p.n_conv;
+            const double mb = share * Ul + 0.5;
+            p.mix_b = mb < 1.0 ? 1u : mb > 64.0 * Ul ? 64u * Ul : (unsigned)mb;
+        }
     }
     p.div_mix = make_div(p.mix_a + p.mix_b);
     p.div_mix_a = make_div(p.mix_a);
