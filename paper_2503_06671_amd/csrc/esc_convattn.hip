@@ -43,12 +43,18 @@
 // can be replayed any number of times.
 //
 // Facts about the machine that shape the code (measured, not assumed):
-//   - an FMA whose multiplier sits in a scalar register issues at half the rate of
-//     one with both operands in vector registers, so the tap weights are read from
-//     LDS (a broadcast read) into vector registers;
+//   - an FMA whose multiplier sits in a scalar register issues at about 0.27 per clock
+//     and SIMD, one with both operands in vector registers at up to 0.375 (four
+//     wavefronts; 0.34 with two, 0.20 with one), so the tap weights are read from LDS
+//     (a broadcast read) into vector registers; the bf16 dot instruction saturates at
+//     0.236, so two taps per instruction pay most when few wavefronts convolve;
 //   - vector-memory results return in order, so an atomic with a slow answer delays
-//     every later load of its wavefront: the leave announcement is issued where no
-//     wait on memory follows soon (for conv items: right before the tap loop);
+//     every later load of its wavefront, and a wait for a load is also a wait for every
+//     store issued before it: the leave announcement is issued where no wait on memory
+//     follows soon and no mailbox store precedes (for conv items: behind the barrier
+//     that ends the tile fill);
+//   - a mailbox hop takes 0.4 us on an idle chip and about 2 us beside streaming
+//     traffic, whichever dies the two blocks are on;
 //   - a thousand atomics on one address take tens of microseconds: nothing here
 //     has more than a handful of blocks on the same word;
 //   - a load behind a condition lands in a basic block of its own and the compiler then
