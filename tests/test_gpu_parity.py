@@ -113,6 +113,14 @@ def test_many_small_images_beyond_one_round(oracle):
     check_forward(wl, oracle)
 
 
+@pytest.mark.parametrize("C", [40, 10])
+def test_queue_dealt_call_with_lopsided_conv_and_copy_shares(oracle, C):
+    # 1280 conv items (more than fit at once) beside many copy items (C = 40) or few (C = 10):
+    # the layers in which the two kinds alternate follow their counts
+    wl = wk.make_random(541, 160, C, 40, 40, 8, 5, dtype=F32, x_mean=0.2)
+    check_forward(wl, oracle)
+
+
 def test_shared_single_filter(oracle):
     wl = wk.make_random(11, 2, 6, 30, 70, 4, 13)
     one = wl.lk[2].copy()
