@@ -1093,8 +1093,8 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         }
     };
 
-    // Asked again part-way through the tap loop: by then the other blocks have published,
-    // so the answers are back when the loop ends.  The mailboxes' base is block-uniform and
+    // Asked again in one of the last steps of the tap loop (any earlier, and in a call of one
+    // round the other blocks have not published yet): the answers travel while the loop ends.  The mailboxes' base is block-uniform and
     // waits in scalar registers; the per-thread addresses are made on the spot.
     const u64 *boxes_s = img_boxes;
     asm volatile("" : "+s"(boxes_s));
@@ -1256,7 +1256,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
 #pragma unroll
             for (int u = 0; u < RY; ++u)
                 if (r0 + u < G::ROWS) {
-                    if (r0 + u == (G::ROWS * 3) / 4) ask_again();
+                    if (r0 + u == (G::ROWS * 15) / 16) ask_again();
                     step(r0 + u, u);
                 }
     } else {
@@ -1331,7 +1331,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             if (direct)
                 d = pre_w ? dot_row_lds(s_wup + tid_d * Kin, p->hidden > 0 ? s_t : s_g, Kin, bup_r)
                           : estimator_out(p, wd.c * 9 + tid_d, s_g, s_t);
-            else if (from_boxes)  // asked for part-way through the tap loop; otherwise wait now
+            else if (from_boxes)  // asked for near the end of the tap loop; otherwise wait now
                 d = G::UNROLL && (uint32_t)(early[0] >> 32) == ctx.tag
                         ? __uint_as_float((uint32_t)early[0])
                         : box_get(p->dk_box + dk_idx + tid_d, ctx.tag, p->err);
