@@ -42,7 +42,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=2000)
-    ap.add_argument("--config", type=int, default=1, help="workload index 0..4")
+    ap.add_argument("--config", type=int, default=1, help="workload index 0..4; 5 = the large-model point (C = 192, C_a = 48, h = 24)")
     ap.add_argument("--ks", type=int, default=None, help="kernel size for workload 4")
     ap.add_argument("--rotate-bytes", type=float, default=1.0e9)
     ap.add_argument("--warm-cache", action="store_true", help="one buffer pair (cache-resident)")
@@ -81,7 +81,10 @@ def main():
 
     binding.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    wl = wk.make_config(args.config, args.ks) if args.config == 4 else wk.make_config(args.config)
+    if args.config == 5:
+        wl = wk.make_large_model()
+    else:
+        wl = wk.make_config(args.config, args.ks) if args.config == 4 else wk.make_config(args.config)
     es = wl.elem_bytes
     b_alg = 2.0 * wl.N * wl.C * wl.H * wl.W * es            # read x once, write out once
     f_alg = 2.0 * wl.Ks * wl.Ks * wl.N * wl.Ca * wl.H * wl.W  # merged-kernel tap count
@@ -94,7 +97,10 @@ def main():
     xs = [x0] + [x0.clone() for _ in range(pairs - 1)]
     outs = [torch.empty_like(x0) for _ in range(pairs)]
     lk = torch.from_numpy(wl.lk).cuda()
-    gen = binding.GenParams(torch.from_numpy(wl.w_up).cuda())
+    def dev(a):
+        return None if a is None else torch.from_numpy(a).cuda()
+
+    gen = binding.GenParams(dev(wl.w_up), dev(wl.b_up), wl.hidden, dev(wl.w_down), dev(wl.b_down))
     ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
     stream = torch.cuda.Stream()
 

@@ -129,6 +129,16 @@ def make_config(idx: int, Ks: Optional[int] = None) -> Workload:
                     x=np.ascontiguousarray(x), lk=np.ascontiguousarray(lk), w_up=w_up)
 
 
+def make_large_model() -> Workload:
+    """The ConvAttn call of the paper's scaled-up model (appendix "Classic SR Results on
+    Larger Model Size": C = 192, 48 attention channels, two-layer estimator with h = 24) on
+    the 320x180 map of the x4 HD protocol.  Not one of the five benchmark workloads: a
+    second measured point for the two-layer estimator.  x_mean = 0.25 keeps DK visible."""
+    wl = make_random(5, 1, 192, 180, 320, 48, 13, dtype=F32, hidden=24, bias=True, x_mean=0.25)
+    wl.name = "large_model_c192_ca48_h24_180x320_f32"
+    return wl
+
+
 def make_random(seed: int, N: int, C: int, H: int, W: int, Ca: int, Ks: int, dtype: int = F32,
                 hidden: int = 0, bias: bool = False, x_mean: float = 0.0,
                 x_scale: float = 1.0) -> Workload:

@@ -316,3 +316,10 @@ def test_benchmark_workload_4_full_size(oracle, Ks):
     if Ks == 13:
         for v in visible_dk_variants(wl):
             check_forward(v, oracle)
+
+
+def test_large_model_workload_full_size(oracle):
+    # C = 192, 48 attention channels, estimator with a hidden layer of 24: 1440 conv items
+    # (queue-dealt), channel-mean items, the two-layer estimator run by every conv item
+    check_forward(wk.make_large_model(), oracle)
+
