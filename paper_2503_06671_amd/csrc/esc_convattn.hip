@@ -363,11 +363,15 @@ struct FwdParams {
     int conv_vec_ok, conv_ld_vec, copy_vec_ok, elem_bytes;
     u64 *pool_box;       // [N*Ca*ptiles] partial sums
     u64 *dk_box;         // [N*Ca*9]
+    u64 *g_box;          // [N*Ca] channel means (calls with gsum items)
+    unsigned n_gsum;     // channel-mean calls: the first n_gsum gen entries are gsum items, one per
+                         // (image, channel); the N gen items behind them turn the means into DK
     unsigned *err;       // raised when a bounded wait expires
     unsigned *epoch;     // [kGroups] call counters (kCtlStride words apart) = tag of the current call
     unsigned *done;      // [kGroups] blocks of the group that have announced their leave
     unsigned *queue;     // [kGroups] entries of the group's list handed out beyond the first per block
     int dynamic;         // blocks take their further entries from the group's queue
+    int staged;          // host only: launch the kernel flavour with the staged estimator items
     // Every conv item is resident from the start (fused pooling) and the call is so short
     // that the conv items' chain of load, taps, estimator and store is what it lasts: the
     // copy items then keep little in flight, so that the conv items' few accesses (tile,
@@ -797,6 +801,121 @@ __device__ __forceinline__ ItemOut gsum_item(ParamsPtr p, Ctx ctx, unsigned nc)
     estimator_front(p, ctx.tag, n, c, c + 1, false, s_part, s_g, s_t);
     ESC_STAMP(rec, 3);
     if (threadIdx.x == 0) box_put(p->dk_box + nc, s_g[c], ctx.tag);
+    claim_next(p, ctx);
+    ESC_STAMP(rec, 6);
+    return ItemOut{ctx, rec};
+}
+
+// ---------------------------------------------------------------------------
+// The estimator items of the kernel flavour for channel-mean calls and for estimators
+// beyond the small ones (forward_kernel<..., true>).  Kept apart from the items above so
+// that the code of the other flavour - the one the short calls use - stays what it is.
+// ---------------------------------------------------------------------------
+
+// gsum item of a channel-mean call: as gsum_item, published among the mean mailboxes.
+__device__ __forceinline__ ItemOut gsum_item_means(ParamsPtr p, Ctx ctx, unsigned nc)
+{
+    float *s_part = g_part, *s_g = g_g, *s_t = g_t;
+    Trace rec;
+    ESC_TRACE_INIT(rec);
+    need_tag(p, ctx);
+    announce_leave(p, ctx);
+    const unsigned n = fdiv(nc, p->div_ca.mul, p->div_ca.shift);
+    const int c = (int)(nc - n * (unsigned)p->Ca);
+    estimator_front(p, ctx.tag, n, c, c + 1, false, s_part, s_g, s_t);
+    ESC_STAMP(rec, 3);
+    if (threadIdx.x == 0) box_put(p->g_box + nc, s_g[c], ctx.tag);
+    claim_next(p, ctx);
+    ESC_STAMP(rec, 6);
+    return ItemOut{ctx, rec};
+}
+
+// gen item of image n: the means come from the pool mailboxes (as in gen_item) or, in a
+// channel-mean call, from the gsum items' mailboxes.  All threads together stage the
+// estimator's weights in the tile's LDS (no conv item is running in this block): the first
+// layer's before the wait, afterwards the output rows, as many at a time as fit.  Read row
+// after row from memory by the few threads that use them, these weights cost the block ten
+// microseconds and more (measured with C_a = 48 and a hidden layer of 24).  Same products
+// in the same order as dot_row, so DK has the same bits whichever item computes it.
+__device__ __forceinline__ ItemOut gen_item_staged(ParamsPtr p, Ctx ctx, unsigned n, bool from_means)
+{
+    float *s_part = g_part, *s_g = g_g, *s_t = g_t, *s_w = g_tile;
+    Trace rec;
+    ESC_TRACE_INIT(rec);
+    need_tag(p, ctx);
+    announce_leave(p, ctx);
+    const int Ca = p->Ca, hidden = p->hidden, K = hidden > 0 ? hidden : Ca;
+    const int o1 = (int)threadIdx.x;
+    // the staging area holds the whole first layer and, behind it, at least 64 output rows
+    const int n_dn = hidden * Ca;
+    const bool staged = n_dn + 64 * K <= kLdsTileFloats;
+    constexpr int kFlight = 24;  // loads a thread has in flight
+    auto stage = [&](const float *src, int count, float *dst) {
+        for (int i0 = 0; i0 < count; i0 += kFlight * kThreads) {
+            float t[kFlight];
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {
+                const int i = i0 + u * kThreads + o1;
+                t[u] = src[i < count ? i : count - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {
+                const int i = i0 + u * kThreads + o1;
+                if (i < count) dst[i] = t[u];
+            }
+        }
+    };
+    float *s_rows = s_w + n_dn;
+    const int rows = !staged ? 0 : (kLdsTileFloats - n_dn) / K < kThreads ? (kLdsTileFloats - n_dn) / K : kThreads;
+    float bd = 0.f;
+    if (staged) {  // first layer and the first round of output rows, before the wait
+        if (hidden > 0) {
+            if (p->b_down) bd = p->b_down[o1 < hidden ? o1 : 0];
+            stage(p->w_down, n_dn, s_w);
+        }
+        stage(p->w_up, (9 * Ca < rows ? 9 * Ca : rows) * K, s_rows);
+    }
+    if (from_means) {
+        // the gsum items have finished the channels' means: collect them (C_a <= kStage)
+        u64 polled[kStagePerThread];
+        boxes_to_lds(p->g_box + (size_t)n * Ca, Ca, s_part, ctx.tag, p->err, polled, false);
+        __syncthreads();
+        for (int k = o1; k < Ca; k += kThreads) s_g[k] = s_part[k];
+        __syncthreads();
+    } else {
+        estimator_front(p, ctx.tag, n, 0, Ca, false, s_part, s_g, s_t);
+    }
+    ESC_STAMP(rec, 3);
+    if (hidden > 0) {
+        for (int m = o1; m < hidden; m += kThreads)
+            s_t[m] = gelu_erf(staged ? dot_row_lds(s_w + m * Ca, s_g, Ca, bd)
+                                     : dot_row(p->w_down + (size_t)m * Ca, s_g, Ca, p->b_down ? p->b_down[m] : 0.f));
+        __syncthreads();
+    }
+    if (staged) {
+        const float *in = hidden > 0 ? s_t : s_g;
+        for (int r0 = 0; r0 < 9 * Ca; r0 += rows) {  // block-uniform
+            const int nr = 9 * Ca - r0 < rows ? 9 * Ca - r0 : rows;
+            if (r0 > 0) {
+                stage(p->w_up + (size_t)r0 * K, nr * K, s_rows);
+                __syncthreads();
+            }
+            if (o1 < nr) {
+                const float sacc = dot_row_lds(s_rows + o1 * K, in, K, p->b_up ? p->b_up[r0 + o1] : 0.f);
+                const size_t idx = (size_t)n * 9 * Ca + r0 + o1;
+                box_put(p->dk_box + idx, sacc, ctx.tag);
+                if (p->dk_out) p->dk_out[idx] = sacc;
+            }
+            __syncthreads();  // the rows' area is reused
+        }
+    } else {
+        for (int o = o1; o < 9 * Ca; o += kThreads) {
+            const float sacc = estimator_out(p, o, s_g, s_t);
+            const size_t idx = (size_t)n * 9 * Ca + o;
+            box_put(p->dk_box + idx, sacc, ctx.tag);
+            if (p->dk_out) p->dk_out[idx] = sacc;
+        }
+    }
     claim_next(p, ctx);
     ESC_STAMP(rec, 6);
     return ItemOut{ctx, rec};
@@ -1518,7 +1637,7 @@ __device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item
 // the one kernel.  KS == 0 builds the variant without conv items (used by
 // esc_dynkernel_gen and for C_a == 0).
 // ---------------------------------------------------------------------------
-template <int KS, int RY, typename T>
+template <int KS, int RY, typename T, bool STAGED = false>
 __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const FwdParams params)
 {
     // the item functions (all inlined here) read the parameters from the kernel argument
@@ -1595,7 +1714,16 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
         if (kind == 0) {
             o = pool_item<T>(p, ctx, idx);
         } else if (kind == 1) {
-            o = p->dk_mode == kDkFromG ? gsum_item(p, ctx, idx) : gen_item(p, ctx, idx);
+            if constexpr (STAGED) {
+                // the gsum items of every (image, channel), then one gen item per image
+                const unsigned n_gsum = p->n_gsum;
+                if (idx < n_gsum)
+                    o = gsum_item_means(p, ctx, idx);
+                else
+                    o = gen_item_staged(p, ctx, idx - n_gsum, n_gsum > 0);
+            } else {
+                o = p->dk_mode == kDkFromG ? gsum_item(p, ctx, idx) : gen_item(p, ctx, idx);
+            }
         } else if (kind == 2) {
             if constexpr (KS > 0)
                 o = conv_item<KS, RY, T>(p, ctx, idx);
@@ -1664,7 +1792,7 @@ __global__ void ws_init_kernel(uint32_t *ptr, size_t words)
 // ---------------------------------------------------------------------------
 struct WsLayout {
     int ptiles_x, ptiles;
-    size_t ctl_off, pool_off, dk_off, total;
+    size_t ctl_off, pool_off, dk_off, g_off, total;
 };
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -1683,6 +1811,8 @@ bool ws_layout(int N, int Ca, int H, int W, WsLayout *l)
     off = round_up(off + (size_t)N * Ca * l->ptiles * sizeof(u64), kWsAlign);
     l->dk_off = off;
     off = round_up(off + (size_t)N * Ca * 9 * sizeof(u64), kWsAlign);
+    l->g_off = off;
+    off = round_up(off + (size_t)N * Ca * sizeof(u64), kWsAlign);
     l->total = off;
     return true;
 }
@@ -1803,7 +1933,7 @@ Plan plan_items(FwdParams &p, int Ks)
     {
         const u64 others0 = (u64)p.n_pool + p.n_gen + p.n_conv, resident0 = (u64)kXcds * Smax;
         const u64 spare = resident0 > others0 + kXcds * 4 ? resident0 - others0 - kXcds * 3 : 0;
-        p.copy_gentle = p.pool_mode == kPoolFused && (p.dk_mode == kDkDirect || p.dk_mode == kDkBoxes) &&
+        p.copy_gentle = p.pool_mode == kPoolFused && p.n_gsum == 0 && (p.dk_mode == kDkDirect || p.dk_mode == kDkBoxes) &&
                         (u64)p.N * p.idt_len <= spare * 12 * (u64)kThreads * 16;
     }
 
@@ -1875,7 +2005,10 @@ esc_status launch_variant(FwdParams &p, hipStream_t s)
     const Plan plan = plan_items(p, KS);
     if ((u64)p.n_pool + p.n_gen + p.n_conv + p.n_copy >= ((u64)1 << 30)) return ESC_ERR_UNSUPPORTED;
     const unsigned grid = plan.per_die * kXcds;
-    hipLaunchKernelGGL((forward_kernel<KS, RY, T>), dim3(grid), dim3(kThreads), 0, s, p);
+    if (p.staged)
+        hipLaunchKernelGGL((forward_kernel<KS, RY, T, true>), dim3(grid), dim3(kThreads), 0, s, p);
+    else
+        hipLaunchKernelGGL((forward_kernel<KS, RY, T, false>), dim3(grid), dim3(kThreads), 0, s, p);
     return hipGetLastError() == hipSuccess ? ESC_OK : ESC_ERR_HIP;
 }
 
@@ -1966,7 +2099,18 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
         if (n_pool >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
         p.n_pool_tiles = (unsigned)n_pool;
         p.n_pool = (unsigned)((n_pool + kPoolBatch - 1) / kPoolBatch);
-        p.n_gen = p.dk_mode == kDkFromG ? (unsigned)((size_t)N * Ca) : 0u;  // gsum items
+        // Larger planes: a gsum item per (image, channel), then a gen item per image that turns
+        // the means into DK; the conv items pick DK up as from any gen item.  These calls, and
+        // calls whose estimator is beyond the small ones that gen_item prefetches, run the
+        // kernel flavour with the staged estimator items.
+        const int K = gen->hidden > 0 ? gen->hidden : Ca;
+        const bool small_est = K <= 16 && Ca <= 16 && gen->hidden <= kThreads;
+        p.staged = p.dk_mode == kDkFromG || !small_est;
+        if (p.dk_mode == kDkFromG) {
+            p.n_gsum = (unsigned)((size_t)N * Ca);
+            p.n_gen = p.n_gsum + (unsigned)N;
+            p.dk_mode = kDkBoxes;
+        }
     }
     char *w = (char *)workspace;
     p.err = (unsigned *)(w + l.ctl_off) + kCtlErrWord;
@@ -1978,6 +2122,7 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
 #endif
     p.pool_box = (u64 *)(w + l.pool_off);
     p.dk_box = (u64 *)(w + l.dk_off);
+    p.g_box = (u64 *)(w + l.g_off);
     return ESC_OK;
 }
 
@@ -2035,8 +2180,9 @@ esc_status esc_dynkernel_gen(const void *x, esc_dtype dt, int N, int C, int H, i
     FwdParams p;
     if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
     p.dk_out = dk_out;
-    p.dk_mode = kDkBoxes;  // no conv items here: gen items write dk_out
+    p.dk_mode = kDkBoxes;  // no conv items here: gen items write dk_out, each from its image's pool sums
     p.n_gen = (unsigned)N;
+    p.n_gsum = 0;
     return dt == ESC_F32 ? launch_typed<float>(p, 0, (hipStream_t)stream)
                          : launch_typed<bf16_t>(p, 0, (hipStream_t)stream);
 }
