@@ -14,8 +14,8 @@
 //                item publishes the sums of its own tile from LDS ("fused pooling")
 //   gen items    one per image with few pool tiles: finish the GAP, run the kernel
 //                estimator, publish DK (esc_dynkernel_gen: also write it out)
-//   gsum items   instead, for images with many pool tiles: one per (image, channel),
-//                publish the channel's mean; the conv items run the estimator themselves
+//   gsum items   for images with many pool tiles: one per (image, channel), publish the
+//                channel's mean; one gen item per image behind them turns the means into DK
 //   conv items   one 64 x (16*RY) output tile of one (image, channel) plane: LK taps
 //                from an LDS halo tile with the channel's weights staged in LDS, then
 //                DK's nine taps once DK is known (asked for from inside the tap loop)
@@ -323,8 +323,8 @@ enum : int {
     kDkGiven = 1,   // caller's dk_in
     kDkBoxes = 2,   // published by a gen item (esc_dynkernel_gen: the gen items also write dk_out)
     kDkDirect = 3,  // each conv item finishes the GAP and runs its nine estimator outputs itself
-    kDkFromG = 4    // one gsum item per (image, channel) publishes the channel's mean; each conv
-                    // item collects its image's means and runs its nine estimator outputs
+    kDkFromG = 4    // host only, while a call is set up: larger planes, whose means come from gsum
+                    // items (n_gsum > 0); the call then runs as kDkBoxes
 };
 enum : int {
     kPoolNone = 0,   // no estimator in this call
@@ -786,34 +786,15 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
     return ItemOut{ctx, rec};
 }
 
-// gsum item: the mean of one (image, channel) plane from its pool mailboxes, with the
-// additions in the order every other path uses, published in the channel's mean mailbox
-// (these share the DK mailboxes' memory: a call uses one kind or the other).
-__device__ __forceinline__ ItemOut gsum_item(ParamsPtr p, Ctx ctx, unsigned nc)
-{
-    float *s_part = g_part, *s_g = g_g, *s_t = g_t;
-    Trace rec;
-    ESC_TRACE_INIT(rec);
-    need_tag(p, ctx);
-    announce_leave(p, ctx);
-    const unsigned n = fdiv(nc, p->div_ca.mul, p->div_ca.shift);
-    const int c = (int)(nc - n * (unsigned)p->Ca);
-    estimator_front(p, ctx.tag, n, c, c + 1, false, s_part, s_g, s_t);
-    ESC_STAMP(rec, 3);
-    if (threadIdx.x == 0) box_put(p->dk_box + nc, s_g[c], ctx.tag);
-    claim_next(p, ctx);
-    ESC_STAMP(rec, 6);
-    return ItemOut{ctx, rec};
-}
-
 // ---------------------------------------------------------------------------
 // The estimator items of the kernel flavour for channel-mean calls and for estimators
 // beyond the small ones (forward_kernel<..., true>).  Kept apart from the items above so
 // that the code of the other flavour - the one the short calls use - stays what it is.
 // ---------------------------------------------------------------------------
 
-// gsum item of a channel-mean call: as gsum_item, published among the mean mailboxes.
-__device__ __forceinline__ ItemOut gsum_item_means(ParamsPtr p, Ctx ctx, unsigned nc)
+// gsum item: the mean of one (image, channel) plane from its pool mailboxes, with the
+// additions in the order every other path uses, published in the channel's mean mailbox.
+__device__ __forceinline__ ItemOut gsum_item(ParamsPtr p, Ctx ctx, unsigned nc)
 {
     float *s_part = g_part, *s_g = g_g, *s_t = g_t;
     Trace rec;
@@ -1183,13 +1164,10 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // mailboxes (pool sums, channel means or DK itself) from inside it; the answers are
     // looked at after the loop, so that their round trips cost nothing.
     constexpr int kPer = (kDirectMaxBoxes + kPollThreads - 1) / kPollThreads;
-    const bool from_g = p->dk_mode == kDkFromG;  // the mailboxes hold channel means, not partial sums
     const bool from_boxes = p->dk_mode == kDkBoxes;  // a gen item publishes DK itself
-    const bool direct = p->dk_mode == kDkDirect || from_g;
-    const int nbox = from_boxes ? 9 : from_g ? p->Ca : p->Ca * p->ptiles;
-    const u64 *img_boxes = from_boxes ? p->dk_box + (size_t)nc * 9
-                           : from_g   ? p->dk_box + (size_t)n * nbox
-                                      : p->pool_box + (size_t)n * nbox;
+    const bool direct = p->dk_mode == kDkDirect;
+    const int nbox = from_boxes ? 9 : p->Ca * p->ptiles;
+    const u64 *img_boxes = from_boxes ? p->dk_box + (size_t)nc * 9 : p->pool_box + (size_t)n * nbox;
     const int Kin = p->hidden > 0 ? p->hidden : p->Ca;
     const bool pre_w = direct && 9 * Kin <= kThreads && p->hidden * p->Ca <= kThreads;
     u64 early[kPer];
@@ -1429,11 +1407,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             }
             __syncthreads();
             ESC_STAMP(rec, 8);
-            if (from_g) {
-                for (int k = tid_d; k < p->Ca; k += kThreads) s_g[k] = s_part[k];
-            } else {
-                sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
-            }
+            sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
             __syncthreads();
             ESC_STAMP(rec, 9);
             if (p->hidden > 0) {
@@ -1718,11 +1692,11 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
                 // the gsum items of every (image, channel), then one gen item per image
                 const unsigned n_gsum = p->n_gsum;
                 if (idx < n_gsum)
-                    o = gsum_item_means(p, ctx, idx);
+                    o = gsum_item(p, ctx, idx);
                 else
                     o = gen_item_staged(p, ctx, idx - n_gsum, n_gsum > 0);
             } else {
-                o = p->dk_mode == kDkFromG ? gsum_item(p, ctx, idx) : gen_item(p, ctx, idx);
+                o = gen_item(p, ctx, idx);
             }
         } else if (kind == 2) {
             if constexpr (KS > 0)
