@@ -32,8 +32,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CU x 2.4 GHz x 256 flop/clk
 # HBM bytes per launch of the forward kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled against a plain copy of known size (see the summaries under profiles/).
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_hd_x4_180x320_f32": 29.93e6,  # profiles/forward_kernel_ks13_f32_cfg1_180x320.txt
-    "cfg4_1080p_x2_540x960_f32_ks13": 284.9e6,  # profiles/forward_kernel_ks13_f32_cfg4_540x960.txt
+    "cfg1_hd_x4_180x320_f32": 29.92e6,  # profiles/forward_kernel_ks13_f32_cfg1_180x320.txt
+    "cfg4_1080p_x2_540x960_f32_ks13": 288.0e6,  # profiles/forward_kernel_ks13_f32_cfg4_540x960.txt
 }
 
 
