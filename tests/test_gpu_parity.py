@@ -323,3 +323,15 @@ def test_large_model_workload_full_size(oracle):
     # (queue-dealt), channel-mean items, the two-layer estimator run by every conv item
     check_forward(wk.make_large_model(), oracle)
 
+
+@pytest.mark.parametrize("N,C,H,W,Ca,hidden", [
+    (1, 100, 20, 20, 100, 0),     # one wide linear layer: 900 output rows staged 64 at a time
+    (1, 104, 96, 128, 100, 0),    # the same behind channel-mean items (600 pool mailboxes per image)
+    (2, 60, 96, 128, 56, 32),     # two layers, channel means, two rounds of output rows
+    (1, 200, 16, 16, 200, 200),   # too large to stage: weights read from memory
+    (1, 200, 96, 128, 200, 64),   # the same behind channel-mean items, more means than polling threads
+])
+def test_estimators_beyond_the_small_ones(oracle, N, C, H, W, Ca, hidden):
+    wl = wk.make_random(560 + Ca + hidden, N, C, H, W, Ca, 3, dtype=F32, hidden=hidden, bias=True, x_mean=0.5)
+    check_forward(wl, oracle)
+
