@@ -9,16 +9,26 @@ synthetic workload (paper_2503_06671_amd/workloads.py).  Default workload: the
 Inputs are resident in HBM before timing.  Steps rotate over enough distinct
 (x, out) buffer pairs to exceed the on-chip caches (--rotate-bytes), so the
 figure is an HBM figure, not a cache figure; --warm-cache times a single pair.
-The K timed steps are captured into one HIP graph and replayed (so the host's
-launch rate does not bound a few-microsecond step); --eager times plain calls.
+After W untimed warm-up steps the K timed steps are captured into one HIP graph
+(so the host's launch rate does not bound a few-microsecond step) and the graph
+is replayed `config.replays` times, each replay bracketed by HIP events on the
+launch stream; `ms_per_step` is the median over the replays (clocks need a few
+milliseconds of work to settle, which a single short replay does not give them).
+--eager times plain calls instead.  Also reported: the latency of one call after a
+device synchronisation, the same timing for the other benchmark workloads
+(`all_workloads`), and two floors measured in the same process with the library's
+own calls: a pure copy of the same tensors (C_a = 0) and a call with nothing to do.
 
 Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -26,15 +36,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, vendor figure
-FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CU x 2.4 GHz x 256 flop/clk
-
-# HBM bytes per launch of the forward kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# scaled against a plain copy of known size (see the summaries under profiles/).
-MEASURED_TRAFFIC_BYTES = {
-    "cfg1_hd_x4_180x320_f32": 29.92e6,  # profiles/forward_kernel_ks13_f32_cfg1_180x320.txt
-    "cfg4_1080p_x2_540x960_f32_ks13": 288.0e6,  # profiles/forward_kernel_ks13_f32_cfg4_540x960.txt
-}
+HBM_PEAK_GBS = 8000.0                 # MI355X HBM3E, vendor figure
+FP32_VECTOR_PEAK_TFLOPS = 157.3       # 256 CU x 2.4 GHz x 256 flop/clk (counts the packed fp32 forms)
+FP32_VECTOR_UNPACKED_TFLOPS = 78.6    # the same without them (they are switched off in this build)
+FP32_FMA_MEASURED_TFLOPS = 118.0      # 0.375 plain FMAs per clock and SIMD, the best rate measured on this chip
 
 
 def parse_args():
@@ -42,19 +47,61 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=2000)
-    ap.add_argument("--config", type=int, default=1, help="workload index 0..4; 5 = the large-model point (C = 192, C_a = 48, h = 24)")
+    ap.add_argument("--config", type=int, default=1,
+                    help="workload index 0..4; 5 = the large-model point (C = 192, C_a = 48, h = 24)")
     ap.add_argument("--ks", type=int, default=None, help="kernel size for workload 4")
     ap.add_argument("--rotate-bytes", type=float, default=1.0e9)
+    ap.add_argument("--replays", type=int, default=0, help="timed graph replays (0 = at least 50 and 20000 launches)")
     ap.add_argument("--warm-cache", action="store_true", help="one buffer pair (cache-resident)")
-    ap.add_argument("--eager", action="store_true", help="time plain calls instead of a graph replay")
+    ap.add_argument("--eager", action="store_true", help="time plain calls instead of graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-all-workloads", action="store_true", help="skip the other benchmark workloads")
+    ap.add_argument("--no-floors", action="store_true", help="skip the copy-only and empty-call floors")
     return ap.parse_args()
 
 
+def source_hash() -> str:
+    """Hash of the kernel sources: a profile summary applies to the build it was taken from."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2503_06671_amd", "csrc")
+    for f in sorted(glob.glob(os.path.join(csrc, "*.hip")) + glob.glob(os.path.join(csrc, "*.hpp"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profiled_traffic(workload_name: str):
+    """HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary under
+    profiles/ for this workload - if that summary was taken from the current kernel sources
+    (the summaries carry the source hash), else None."""
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        text = open(path).read()
+        m_w = re.search(r"^workload:\s*(\S+)", text, re.M)
+        m_t = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
+        m_h = re.search(r"^kernel_source_sha16:\s*([0-9a-f]+)", text, re.M)
+        if m_w and m_t and m_h and m_w.group(1) == workload_name:
+            if m_h.group(1) == source_hash():
+                return float(m_t.group(1)), os.path.relpath(path, ROOT)
+            return None, os.path.relpath(path, ROOT) + " (taken from other kernel sources: not used)"
+    return None, None
+
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(wl):
-    """The oracle as it stands, whole forward on the same workload, best of 3."""
+    """The oracle as it stands (float64 accumulators, never tuned), whole forward on the same
+    workload: best of several runs on all threads, and best of 3 on one thread."""
     from oracle import esc_oracle
     esc_oracle.build()
+    nthreads = esc_oracle.threads()
     best = float("inf")
     reps = 0
     t_all = time.perf_counter()
@@ -63,9 +110,131 @@ def cpu_baseline(wl):
         esc_oracle.forward_workload(wl, want_out=True)
         best = min(best, time.perf_counter() - t0)
         reps += 1
-    return {"value": wl.pixels / best / 1e6, "unit": "Mpixel/s", "cores": esc_oracle.threads(),
-            "kind": "oracle", "ms_per_step": best * 1e3,
-            "sample": f"whole workload {wl.name}, full forward, best of {reps} runs"}
+    esc_oracle.set_threads(1)
+    best1 = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        esc_oracle.forward_workload(wl, want_out=True)
+        best1 = min(best1, time.perf_counter() - t0)
+    esc_oracle.set_threads(nthreads)
+    return {"value": wl.pixels / best / 1e6, "unit": "Mpixel/s", "cores": nthreads,
+            "kind": "oracle", "ms_per_step": best * 1e3, "ms_per_step_1thread": best1 * 1e3,
+            "cpu_model": cpu_model(), "host_cpus": os.cpu_count(),
+            "sample": f"whole workload {wl.name}, full forward, best of {reps} runs on {nthreads} threads "
+                      f"and best of 3 on one thread"}
+
+
+def roofline_of(wl, sec):
+    """Which roof bounds this workload (HBM at 8 TB/s or the fp32 vector units at 157.3
+    TFLOP/s) and the fraction of it reached; the fractions against the other ceilings ride along."""
+    b_alg = 2.0 * wl.N * wl.C * wl.H * wl.W * wl.elem_bytes   # read x once, write out once
+    f_alg = 2.0 * wl.Ks * wl.Ks * wl.N * wl.Ca * wl.H * wl.W  # merged-kernel tap count
+    t_hbm = b_alg / (HBM_PEAK_GBS * 1e9)
+    t_alu = f_alg / (FP32_VECTOR_PEAK_TFLOPS * 1e12)
+    gbs, tfl = b_alg / sec / 1e9, f_alg / sec / 1e12
+    if t_hbm >= t_alu:
+        r = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+    else:
+        r = {"bound": "alu", "achieved": tfl, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+             "frac": tfl / FP32_VECTOR_PEAK_TFLOPS}
+    r.update({
+        "algorithmic_bytes": b_alg, "algorithmic_flops": f_alg,
+        "hbm_gbps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
+        "alu_tflops": tfl, "frac_of_fp32_vector_peak": tfl / FP32_VECTOR_PEAK_TFLOPS,
+        "frac_of_fp32_vector_peak_unpacked": tfl / FP32_VECTOR_UNPACKED_TFLOPS,
+        "frac_of_fp32_fma_rate_measured": tfl / FP32_FMA_MEASURED_TFLOPS,
+        # the roof itself with the unpacked ceiling: max(HBM time, ALU time at 78.6 TFLOP/s) / measured
+        "frac_of_roof_unpacked": max(t_hbm, f_alg / (FP32_VECTOR_UNPACKED_TFLOPS * 1e12)) / sec,
+    })
+    return r
+
+
+class Runner:
+    """Device buffers of one workload and the timing protocol."""
+
+    def __init__(self, wl, rotate_bytes, warm_cache, ca=None):
+        import numpy as np
+        import torch
+        from paper_2503_06671_amd import binding, workloads as wk
+        self.torch, self.binding, self.wl = torch, binding, wl
+        self.ca = wl.Ca if ca is None else ca
+        b_alg = 2.0 * wl.N * wl.C * wl.H * wl.W * wl.elem_bytes
+        self.pairs = 1 if warm_cache else max(2, int(np.ceil(rotate_bytes / b_alg)))
+        if wl.dtype == wk.F32:
+            x0 = torch.from_numpy(wl.x).cuda()
+        else:
+            x0 = torch.from_numpy(wl.x.view(np.int16)).cuda().view(torch.bfloat16)
+        self.xs = [x0] + [x0.clone() for _ in range(self.pairs - 1)]
+        self.outs = [torch.empty_like(x0) for _ in range(self.pairs)]
+        self.lk = torch.from_numpy(wl.lk).cuda()
+
+        def dev(a):
+            return None if a is None else torch.from_numpy(a).cuda()
+
+        self.gen = None
+        if self.ca > 0:
+            self.gen = binding.GenParams(dev(wl.w_up), dev(wl.b_up), wl.hidden, dev(wl.w_down), dev(wl.b_down))
+        self.ws = binding.new_workspace(wl.N, self.ca, wl.H, wl.W)
+        self.stream = torch.cuda.Stream()
+
+    def step(self, i):
+        k = i % self.pairs
+        self.binding.convattn_forward(self.xs[k], self.ca, self.lk, self.ws, gen=self.gen, out=self.outs[k],
+                                      stream=self.stream)
+
+    def time(self, steps, warmup, replays, eager=False):
+        """Median (and spread) of the per-step time over `replays` timed regions of `steps` launches."""
+        torch = self.torch
+        with torch.cuda.stream(self.stream):
+            for i in range(warmup):
+                self.step(i)
+        torch.cuda.synchronize()
+        graph = None
+        if not eager:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=self.stream):
+                for i in range(steps):
+                    self.step(i)
+            with torch.cuda.stream(self.stream):
+                graph.replay()                  # untimed: the first replay uploads the graph
+            torch.cuda.synchronize()
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(replays)]
+        with torch.cuda.stream(self.stream):
+            for e0, e1 in pairs:
+                e0.record(self.stream)
+                if graph is not None:
+                    graph.replay()
+                else:
+                    for i in range(steps):
+                        self.step(i)
+                e1.record(self.stream)
+        torch.cuda.synchronize()
+        per = sorted(e0.elapsed_time(e1) / steps for e0, e1 in pairs)
+        first = pairs[0][0].elapsed_time(pairs[0][1]) / steps
+        assert self.binding.workspace_errors(self.ws, self.stream) == 0, "a wait inside the kernel expired"
+        return {"median": per[len(per) // 2], "min": per[0], "max": per[-1], "first": first}
+
+    def single_call_latency_us(self, reps=25):
+        """One call after a device synchronisation, event to event; median of `reps`."""
+        torch = self.torch
+        lat = []
+        for i in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            with torch.cuda.stream(self.stream):
+                e0.record(self.stream)
+                self.step(i)
+                e1.record(self.stream)
+            torch.cuda.synchronize()
+            lat.append(e0.elapsed_time(e1) * 1e3)
+        lat.sort()
+        return lat[len(lat) // 2]
+
+
+def replays_for(steps, asked):
+    if asked > 0:
+        return asked
+    return max(50, -(-20000 // steps))
 
 
 def main():
@@ -75,7 +244,6 @@ def main():
               "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     from paper_2503_06671_amd import binding, workloads as wk
 
@@ -85,66 +253,38 @@ def main():
         wl = wk.make_large_model()
     else:
         wl = wk.make_config(args.config, args.ks) if args.config == 4 else wk.make_config(args.config)
-    es = wl.elem_bytes
-    b_alg = 2.0 * wl.N * wl.C * wl.H * wl.W * es            # read x once, write out once
-    f_alg = 2.0 * wl.Ks * wl.Ks * wl.N * wl.Ca * wl.H * wl.W  # merged-kernel tap count
-    pairs = 1 if args.warm_cache else max(2, int(np.ceil(args.rotate_bytes / b_alg)))
+    replays = replays_for(args.steps, args.replays)
 
-    if wl.dtype == wk.F32:
-        x0 = torch.from_numpy(wl.x).cuda()
-    else:
-        x0 = torch.from_numpy(wl.x.view(np.int16)).cuda().view(torch.bfloat16)
-    xs = [x0] + [x0.clone() for _ in range(pairs - 1)]
-    outs = [torch.empty_like(x0) for _ in range(pairs)]
-    lk = torch.from_numpy(wl.lk).cuda()
-    def dev(a):
-        return None if a is None else torch.from_numpy(a).cuda()
+    run = Runner(wl, args.rotate_bytes, args.warm_cache)
+    t = run.time(args.steps, args.warmup, replays, eager=args.eager)
+    ms_step = t["median"]
+    # spot check of the last buffers against the first (same input => same bits)
+    assert torch.equal(run.outs[0], run.outs[(args.steps - 1) % run.pairs]), "rotating buffers disagree"
+    latency_us = run.single_call_latency_us()
 
-    gen = binding.GenParams(dev(wl.w_up), dev(wl.b_up), wl.hidden, dev(wl.w_down), dev(wl.b_down))
-    ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
-    stream = torch.cuda.Stream()
-
-    def step(i):
-        binding.convattn_forward(xs[i % pairs], wl.Ca, lk, ws, gen=gen, out=outs[i % pairs], stream=stream)
-
-    with torch.cuda.stream(stream):
-        for i in range(args.warmup):
-            step(i)
-    torch.cuda.synchronize()
-
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    mode = "eager"
-    if not args.eager:
-        mode = "hipgraph"
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=stream):
-            for i in range(args.steps):
-                step(i)
-        with torch.cuda.stream(stream):
-            graph.replay()                      # untimed: first replay uploads the graph
-        torch.cuda.synchronize()
-        with torch.cuda.stream(stream):
-            ev0.record(stream)
-            graph.replay()
-            ev1.record(stream)
-        torch.cuda.synchronize()
-    else:
-        torch.cuda.synchronize()
-        with torch.cuda.stream(stream):
-            ev0.record(stream)
-            for i in range(args.steps):
-                step(i)
-            ev1.record(stream)
-        torch.cuda.synchronize()
-    ms_total = ev0.elapsed_time(ev1)
-    ms_step = ms_total / args.steps
-
-    # spot check of the last buffers against the first (same input => same bits), and no
-    # bounded wait inside the kernel may have expired
-    assert torch.equal(outs[0], outs[(args.steps - 1) % pairs]), "rotating buffers disagree"
-    assert binding.workspace_errors(ws, stream) == 0, "a wait inside the kernel expired"
+    floors = None
+    if not args.no_floors:
+        # the library's own pure copy (C_a = 0) on the same tensors and rotation, and a call
+        # with nothing to do (1 x 1 x 1 x 1, C_a = 0): what is left above them is the method's
+        copy_t = Runner(wl, args.rotate_bytes, args.warm_cache, ca=0).time(args.steps, min(args.warmup, 200), replays,
+                                                                          eager=args.eager)
+        tiny = wk.make_random(0, 1, 1, 1, 1, 0, 1)
+        empty_t = Runner(tiny, 1.0, True).time(args.steps, min(args.warmup, 200), replays, eager=args.eager)
+        floors = {"copy_only_us": copy_t["median"] * 1e3, "empty_call_us": empty_t["median"] * 1e3,
+                  "what": "esc_convattn_forward with C_a = 0 on the same tensors and rotation; the same on a "
+                          "1x1x1x1 tensor; medians over the same number of replays"}
+    del run
 
     sec = ms_step * 1e-3
+    roof = roofline_of(wl, sec)
+    traffic, traffic_src = (None, None) if args.warm_cache else profiled_traffic(wl.name)
+    roof.update({
+        "kernel": f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)",
+        "traffic": traffic, "traffic_source": traffic_src,
+        # one step is one launch of the single forward kernel, so the per-launch duration is
+        # the HIP-event time of a timed region divided by the number of launches in it
+        "kernel_us": ms_step * 1e3,
+    })
     res = {
         "metric": "convattn_fwd_mpixel_per_s",
         "value": wl.pixels / sec / 1e6,
@@ -159,26 +299,41 @@ def main():
         "dtype": wk.DTYPE_NAMES[wl.dtype],
         "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "C": wl.C, "C_a": wl.Ca, "H": wl.H, "W": wl.W,
-                   "Ks": wl.Ks, "launch": mode, "buffer_pairs": pairs,
-                   "cache": "warm" if args.warm_cache else "rotating"},
-        "hbm_gbps_algorithmic": b_alg / sec / 1e9,
-        "valu_tflops": f_alg / sec / 1e12,
-        # one step is one launch of the single forward kernel, so the per-launch duration is
-        # the HIP-event time of the timed region divided by the number of launches
-        "roofline": {
-            "bound": "hbm",
-            "kernel": f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)",
-            "achieved": b_alg / sec / 1e9,
-            "peak": HBM_PEAK_GBS,
-            "unit": "GB/s",
-            "frac": b_alg / sec / 1e9 / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if not args.warm_cache else None,
-            "algorithmic_bytes": b_alg,
-            "kernel_us": ms_step * 1e3,
-            "alu_tflops": f_alg / sec / 1e12,
-            "alu_frac_of_fp32_vector_peak": f_alg / sec / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
-        },
+                   "Ks": wl.Ks, "launch": "eager" if args.eager else "hipgraph",
+                   "buffer_pairs": max(2, int(-(-args.rotate_bytes // (2.0 * wl.N * wl.C * wl.H * wl.W * wl.elem_bytes))))
+                   if not args.warm_cache else 1,
+                   "cache": "warm" if args.warm_cache else "rotating", "replays": replays,
+                   "statistic": "median over the replays of (replay time / steps)"},
+        "ms_per_step_min": t["min"], "ms_per_step_max": t["max"], "ms_per_step_first_replay": t["first"],
+        "single_call_latency_us": latency_us,
+        "hbm_gbps_algorithmic": roof["hbm_gbps"],
+        "valu_tflops": roof["alu_tflops"],
+        "roofline": roof,
     }
+    if floors is not None:
+        res["floor"] = floors
+
+    if not args.no_all_workloads:
+        # every other benchmark workload, 200 launches per replay, no CPU leg
+        others = []
+        todo = [(i, None) for i in (0, 1, 2, 3)] + [(4, k) for k in wk.CFG4_KS]
+        for idx, ks in todo:
+            w2 = wk.make_config(idx, ks) if idx == 4 else wk.make_config(idx)
+            if w2.name == wl.name:
+                continue
+            r2 = Runner(w2, args.rotate_bytes, args.warm_cache)
+            t2 = r2.time(200, 200, 25, eager=args.eager)
+            s2 = t2["median"] * 1e-3
+            rf = roofline_of(w2, s2)
+            others.append({"workload": w2.name, "dtype": wk.DTYPE_NAMES[w2.dtype], "us_per_step": t2["median"] * 1e3,
+                           "mpixel_per_s": w2.pixels / s2 / 1e6, "bound": rf["bound"], "frac": rf["frac"],
+                           "hbm_gbps": rf["hbm_gbps"], "alu_tflops": rf["alu_tflops"],
+                           "frac_of_roof_unpacked": rf["frac_of_roof_unpacked"],
+                           "steps": 200, "warmup": 200, "replays": 25})
+            del r2
+            torch.cuda.empty_cache()
+        res["all_workloads"] = others
+
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res), flush=True)

@@ -20,27 +20,36 @@
  *     (NULL = the default stream).  Calls only enqueue work on `stream` and
  *     return; they never synchronise and never allocate.
  *   - x and out are contiguous [N, C, H, W] in the storage type `dt`; out must
- *     not overlap x.  lk, the estimator weights, dk and the workspace are fp32
- *     in both storage modes.  With bf16 storage and Ks <= 17 the large-kernel
- *     weights are rounded to bf16 on the device before use (products are exact,
- *     accumulation stays fp32); a pixel of the attention slice that is not
- *     finite may then also spoil the output one column beyond the kernel's reach.
+ *     not overlap x, the workspace, lk, dk_in or dk_out (ESC_ERR_ALIAS for the
+ *     ranges the library can see).  lk, the estimator weights, dk and the
+ *     workspace are fp32 in both storage modes.  With bf16 storage and Ks <= 17
+ *     the large-kernel weights are rounded to bf16 on the device before use
+ *     (products are exact, accumulation stays fp32), and two taps share one
+ *     instruction: a pixel of the attention slice that is not finite then also
+ *     turns the outputs one column beyond the kernel's reach, on either side,
+ *     into NaN.  fp32 storage, and bf16 storage with Ks >= 19, give NaN/Inf
+ *     exactly where the definition does.
  *   - All arguments are validated on the host before the first launch; a call
  *     that returns an error has enqueued nothing.
  *   - Every compute call needs a workspace (work queue and the mailboxes blocks
  *     use to hand over the GAP sums and DK).  It must have been prepared once with
  *     esc_workspace_init on a stream ordered before its first use; calls leave it
- *     ready for the next call, whatever its shape.  Two calls that share a
- *     workspace must be ordered (same stream, or synchronised).
+ *     ready for the next call, whatever its shape, so it carries state from call
+ *     to call and must not be cleared or reused for anything else in between.
  *     esc_workspace_bytes gives the size for a shape; it never shrinks when N,
- *     C_a or H*W grow, so a workspace sized for the largest shape fits all.
+ *     C_a, H or W grow (each taken by itself - not H*W), so a workspace sized
+ *     for the largest N, C_a, H and W fits every smaller shape.
  *   - The forward is one persistent kernel whose blocks wait for one another
- *     (bounded, about a second).  Its grid is sized so that all of its blocks are
- *     resident at once on an otherwise idle device; work that other streams or
- *     processes keep running on the same device at the same time can hold blocks
- *     back and stretch those waits.  Should a wait ever expire, the result is
- *     undefined and the workspace's error word is raised; esc_workspace_errors
- *     reads it.
+ *     (bounded, about a second).  Its grid is sized, per device and kernel
+ *     variant, from the runtime's occupancy answer so that all of its blocks are
+ *     resident at once on an otherwise idle device (ESC_ERR_UNSUPPORTED if the
+ *     device cannot hold one block).  Calls of this library on DIFFERENT streams
+ *     must be serialised by the caller (two half-resident grids could wait for
+ *     each other), and other work that keeps running on the same device at the
+ *     same time can hold blocks back and stretch the waits.  Should a wait ever
+ *     expire, the values that never came are taken as NaN - the affected outputs
+ *     are NaN, never silently wrong numbers - and the workspace's error word is
+ *     raised; esc_workspace_errors reads it.
  *   - Limits: 0 <= C_a <= min(C, 256); estimator hidden width <= 256; Ks odd,
  *     1 <= Ks <= 31; H*W < 2^31; N, C, H, W >= 1.  No lower bound on H or W
  *     relative to Ks.
@@ -61,7 +70,7 @@ typedef enum {
     ESC_ERR_DTYPE = 3,       /* dt is not a member of esc_dtype                    */
     ESC_ERR_UNSUPPORTED = 4, /* valid for the method, outside the library's limits */
     ESC_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or too small         */
-    ESC_ERR_ALIAS = 6,       /* out overlaps x                                     */
+    ESC_ERR_ALIAS = 6,       /* out overlaps x, the workspace, lk, dk_in or dk_out  */
     ESC_ERR_HIP = 7          /* the HIP runtime refused a launch                   */
 } esc_status;
 

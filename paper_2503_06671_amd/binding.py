@@ -110,6 +110,21 @@ class GenParams:
         self.hidden = int(hidden)
         self.c = _GenParams(self.hidden, *[_ptr(t) for t in self.tensors])
 
+    def check(self, Ca: int) -> None:
+        """The library reads these buffers by the sizes C_a and hidden imply: refuse others."""
+        w_down, b_down, w_up, b_up = self.tensors
+        K = self.hidden if self.hidden > 0 else Ca
+        want = {"w_up": (w_up, 9 * Ca * K), "b_up": (b_up, 9 * Ca)}
+        if self.hidden > 0:
+            want["w_down"] = (w_down, self.hidden * Ca)
+            want["b_down"] = (b_down, self.hidden)
+            if w_down is None:
+                raise ValueError("hidden > 0 needs w_down")
+        for name, (tensor, numel) in want.items():
+            if tensor is not None and tensor.numel() != numel:
+                raise ValueError(f"{name} has {tensor.numel()} elements, C_a = {Ca} and hidden = {self.hidden} "
+                                 f"need {numel}")
+
 
 def workspace_bytes(N: int, Ca: int, H: int, W: int) -> int:
     return int(load_library().esc_workspace_bytes(N, Ca, H, W))
@@ -147,30 +162,54 @@ def dynkernel_gen(x: torch.Tensor, Ca: int, gen: GenParams, workspace: torch.Ten
                   dk_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """esc_dynkernel_gen: DK [N,Ca,3,3] float32 from GAP of the attention slice."""
     dt, (N, C, H, W) = _x_checked(x)
+    gen.check(int(Ca))
     if dk_out is None:
         dk_out = torch.empty((N, Ca, 3, 3), dtype=torch.float32, device=x.device)
     _dev_f32(dk_out, "dk_out")
+    if dk_out.numel() != N * Ca * 9:
+        raise ValueError("dk_out must hold [N, Ca, 3, 3] values")
     _check(load_library().esc_dynkernel_gen(
         _ptr(x), dt, N, C, H, W, int(Ca), ctypes.byref(gen.c), _ptr(dk_out),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
     return dk_out
 
 
+def _lk_checked(lk: torch.Tensor, Ca: int, ks: Optional[int], lk_channel_stride: Optional[int]):
+    """(Ks, channel stride) of the large kernel: [Ca,Ks,Ks] (one filter per channel), [Ks,Ks]
+    (one for all), or a flat buffer read with an explicit Ks and channel stride."""
+    _dev_f32(lk, "lk")
+    if ks is not None or lk_channel_stride is not None:
+        if ks is None or lk_channel_stride is None:
+            raise ValueError("give ks and lk_channel_stride together")
+        ks, stride = int(ks), int(lk_channel_stride)
+        need = (Ca - 1) * stride + ks * ks if (stride and Ca > 0) else ks * ks
+        if lk.numel() < need:
+            raise ValueError(f"lk holds {lk.numel()} values, Ks = {ks} with channel stride {stride} reads {need}")
+        return ks, stride
+    if lk.dim() == 2 and lk.shape[0] == lk.shape[1]:
+        return int(lk.shape[0]), 0
+    if lk.dim() == 3 and lk.shape[1] == lk.shape[2] and (lk.shape[0] == Ca or Ca == 0):
+        return int(lk.shape[1]), int(lk.shape[1] * lk.shape[2])
+    raise ValueError(f"lk must be [Ca,Ks,Ks] with Ca = {Ca}, or [Ks,Ks]; got {tuple(lk.shape)}")
+
+
 def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, workspace: torch.Tensor,
                      gen: Optional[GenParams] = None, dk_in: Optional[torch.Tensor] = None,
-                     out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """esc_convattn_forward.  lk is [Ca,Ks,Ks] (one filter per channel) or [Ks,Ks] (shared)."""
+                     out: Optional[torch.Tensor] = None, stream=None, ks: Optional[int] = None,
+                     lk_channel_stride: Optional[int] = None) -> torch.Tensor:
+    """esc_convattn_forward.  lk is [Ca,Ks,Ks] (one filter per channel) or [Ks,Ks] (shared);
+    with ks and lk_channel_stride given it is a flat buffer with channel c at c * stride."""
     dt, (N, C, H, W) = _x_checked(x)
-    _dev_f32(lk, "lk")
-    if lk.dim() == 2:
-        Ks, stride = int(lk.shape[0]), 0
-    else:
-        Ks, stride = int(lk.shape[1]), int(lk.shape[1] * lk.shape[2])
+    Ks, stride = _lk_checked(lk, int(Ca), ks, lk_channel_stride)
+    if gen is not None:
+        gen.check(int(Ca))
     if out is None:
         out = torch.empty_like(x)
     if out.dtype != x.dtype or out.shape != x.shape or not out.is_contiguous():
         raise TypeError("out must match x in dtype and shape and be contiguous")
     _dev_f32(dk_in, "dk_in")
+    if dk_in is not None and dk_in.numel() != N * Ca * 9:
+        raise ValueError("dk_in must hold [N, Ca, 3, 3] values")
     ws_ptr, ws_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
     _check(load_library().esc_convattn_forward(
         _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk), Ks, stride,

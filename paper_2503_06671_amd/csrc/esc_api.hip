@@ -1,0 +1,495 @@
+// Host side of the ConvAttn forward library for gfx950 (MI355X): argument checks, the
+// layout of the workspace, the plan that cuts a call into work items, and the C ABI
+// declared in include/esc_convattn.h.  The kernels live in esc_kernels.hpp and are
+// instantiated per kernel size in esc_variants.hip.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include "esc_kernels.hpp"
+
+namespace esc {
+
+// one pair per kernel size, defined in esc_variants.hip (-DESC_KS=<Ks>)
+#define ESC_DECL_KS(K)                                                                                    \
+    hipError_t launch_ks_##K(int ry, bool bf16, bool staged, unsigned grid, hipStream_t s, const FwdParams &p); \
+    hipError_t occupancy_ks_##K(int ry, bool bf16, bool staged, int *blocks_per_cu);
+#define ESC_FOR_EACH_KS(X) X(0) X(1) X(3) X(5) X(7) X(9) X(11) X(13) X(15) X(17) X(19) X(21) X(23) X(25) X(27) X(29) X(31)
+ESC_FOR_EACH_KS(ESC_DECL_KS)
+#undef ESC_DECL_KS
+
+}  // namespace esc
+
+namespace {
+
+using namespace esc;
+
+__global__ void ws_init_kernel(uint32_t *ptr, size_t words)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool is_epoch = i >= kCtlEpochWord && i < kCtlDoneWord && (i - kCtlEpochWord) % kCtlStride == 0;
+    if (i < words) ptr[i] = is_epoch ? 1u : 0u;
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+struct WsLayout {
+    int ptiles_x, ptiles;
+    size_t ctl_off, pool_off, dk_off, g_off, total;
+};
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool ws_layout(int N, int Ca, int H, int W, WsLayout *l)
+{
+    if (N < 1 || Ca < 0 || H < 1 || W < 1) return false;
+    const size_t hw = (size_t)H * (size_t)W;
+    if (hw >= ((size_t)1 << 31)) return false;
+    l->ptiles_x = (W + kPoolTileW - 1) / kPoolTileW;
+    l->ptiles = l->ptiles_x * ((H + kPoolTileH - 1) / kPoolTileH);
+    size_t off = 0;
+    l->ctl_off = off;
+    off = round_up(off + kCtlWords * sizeof(uint32_t), kWsAlign);
+    l->pool_off = off;
+    off = round_up(off + (size_t)N * Ca * l->ptiles * sizeof(u64), kWsAlign);
+    l->dk_off = off;
+    off = round_up(off + (size_t)N * Ca * 9 * sizeof(u64), kWsAlign);
+    l->g_off = off;
+    off = round_up(off + (size_t)N * Ca * sizeof(u64), kWsAlign);
+    l->total = off;
+    return true;
+}
+
+FastDiv make_div(uint32_t d)
+{
+    FastDiv f;
+    if (d == 0) d = 1;
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    f.d = d;
+    f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
+    f.shift = l;
+    return f;
+}
+
+esc_status check_common(const void *x, esc_dtype dt, int N, int C, int H, int W, int Ca)
+{
+    if (dt != ESC_F32 && dt != ESC_BF16) return ESC_ERR_DTYPE;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || Ca < 0 || Ca > C) return ESC_ERR_SHAPE;
+    if (x == nullptr) return ESC_ERR_NULL;
+    if ((size_t)H * (size_t)W >= ((size_t)1 << 31)) return ESC_ERR_UNSUPPORTED;
+    if (Ca > kMaxCa) return ESC_ERR_UNSUPPORTED;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    if (((uintptr_t)x % es) != 0) return ESC_ERR_SHAPE;
+    return ESC_OK;
+}
+
+// do the byte ranges [a, a + na) and [b, b + nb) share a byte?
+bool overlaps(const void *a, size_t na, const void *b, size_t nb)
+{
+    const uintptr_t ua = (uintptr_t)a, ub = (uintptr_t)b;
+    return na > 0 && nb > 0 && ua < ub + nb && ub < ua + na;
+}
+
+esc_status check_gen(const esc_gen_params *gen, int Ca)
+{
+    if (gen->hidden < 0) return ESC_ERR_SHAPE;
+    if (gen->hidden > kMaxHidden) return ESC_ERR_UNSUPPORTED;
+    if (Ca > 0 && gen->w_up == nullptr) return ESC_ERR_NULL;
+    if (Ca > 0 && gen->hidden > 0 && gen->w_down == nullptr) return ESC_ERR_NULL;
+    return ESC_OK;
+}
+
+esc_status check_ws(const void *ws, size_t ws_bytes, size_t need)
+{
+    if (need < kCtlWords * sizeof(uint32_t)) need = kCtlWords * sizeof(uint32_t);
+    if (ws == nullptr || ((uintptr_t)ws % kWsAlign) != 0 || ws_bytes < need) return ESC_ERR_WORKSPACE;
+    return ESC_OK;
+}
+
+
+// compute units of the current device (asked once per device)
+int device_cus()
+{
+    constexpr int kMaxDev = 64;
+    static int cus[kMaxDev];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return 0;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+        cus[dev] = n;
+    }
+    return cus[dev];
+}
+
+// Lays the items out for the grid: how many blocks per die, whether the conv items can
+// pool for themselves, how big a copy item is and how conv and copy items alternate.
+// n_conv, n_gen and the pass-through range are set; n_pool holds the pool-item count that
+// applies if pooling is not fused.
+struct Plan {
+    unsigned per_die;
+};
+
+Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu)
+{
+    const unsigned U = (unsigned)device_cus() / kXcds;          // compute units per die
+    const unsigned Smax = (unsigned)blocks_per_cu * (U ? U : 1);  // resident blocks per die
+    auto per_die_of = [](u64 n) { return (unsigned)((n + kXcds - 1) / kXcds); };
+
+    // Few pool tiles per image: one gen item per image runs the estimator while the conv
+    // items multiply, and they pick DK up on the way (asked for inside the tap loop) - if the
+    // gen items still fit beside all conv items (fused pooling).  Otherwise the conv items
+    // run the estimator themselves (direct mode).  Measured at 180 x 320, the hop is the
+    // faster of the two for every Ks.
+    if (p.pool_mode == kPoolItems && p.dk_mode == kDkDirect && p.n_conv > 0 &&
+        per_die_of(p.n_conv) + per_die_of((u64)p.N) <= Smax) {
+        p.dk_mode = kDkBoxes;
+        p.n_gen = (unsigned)p.N;
+    }
+
+    // all conv items (and the gen items they wait for) in the first round => fused pooling
+    if (p.pool_mode == kPoolItems && p.n_conv > 0 && per_die_of(p.n_conv) + per_die_of(p.n_gen) <= Smax) {
+        p.pool_mode = kPoolFused;
+        p.n_pool = 0;
+    }
+
+    // rough time shares of the arithmetic and of the pass-through traffic decide how many
+    // copy items there are to a conv item (and with that how small they are): 1, 2 or 3,
+    // thresholds from sweeps at 540 x 960 with Ks = 7 ... 31
+    const double pix = (double)p.N * p.Ca * p.H * p.W;
+    const double t_valu = 2.0 * Ks * Ks * pix / 50e12;  // what a conv item sustains, its loads included
+    const double t_copy = 2.0 * (double)p.N * (double)p.idt_len / 4.5e12;
+    unsigned a = 1, b = 1;
+    if (t_valu > 0 && t_copy > 0) {
+        const double share = t_valu / (t_valu + t_copy);
+        if (share < 0.6) b = 2;
+        if (share < 0.3) b = 3;
+    }
+
+    // short calls (the conv items' own chain is most of them): gentle copying, if the blocks
+    // left over beside the conv items get through the pass-through range in about a dozen
+    // accesses per thread
+    {
+        const u64 others0 = (u64)p.n_pool + p.n_gen + p.n_conv, resident0 = (u64)kXcds * Smax;
+        const u64 spare = resident0 > others0 + kXcds * 4 ? resident0 - others0 - kXcds * 3 : 0;
+        p.copy_gentle = p.pool_mode == kPoolFused && p.n_gsum == 0 && (p.dk_mode == kDkDirect || p.dk_mode == kDkBoxes) &&
+                        (u64)p.N * p.idt_len <= spare * 12 * (u64)kThreads * 16;
+    }
+
+    // copy items: as many as the pattern pairs with the conv items; if the whole call fits
+    // into one round of resident blocks, as many as still fit
+    p.n_copy = 0;
+    p.copy_chunk = kCopyPiece;
+    if (p.idt_len > 0) {
+        u64 want = p.n_conv > 0 ? (u64)p.n_conv * b / a : (u64)kXcds * Smax * 4;
+        const u64 others = (u64)p.n_pool + p.n_gen + p.n_conv;
+        const u64 resident = (u64)kXcds * Smax;
+        if (others + kXcds * 4 < resident && others + want > resident && (resident - others) * 4 >= want)
+            want = resident - others - kXcds * 3;  // the lists are rounded up per kind and die
+        // gentle copying moves one access per thread at a time: as many items as fit, cut finely
+        const size_t grain = p.copy_gentle ? (size_t)kThreads * 16 : kCopyPiece;
+        if (p.copy_gentle && others + kXcds * 4 < resident) want = resident - others - kXcds * 3;
+        // fused pooling without room beside the conv items: the copy comes after them, and
+        // every block should get a share of it
+        if (p.pool_mode == kPoolFused && !p.copy_gentle && want < 2 * resident) want = 2 * resident;
+        if (want < 1) want = 1;
+        u64 per_img = (want + p.N / 2) / p.N;
+        if (per_img < 1) per_img = 1;
+        size_t chunk = (p.idt_len + per_img - 1) / per_img;
+        chunk = (chunk + grain - 1) / grain * grain;
+        const size_t chunks = (p.idt_len + chunk - 1) / chunk;
+        p.copy_chunk = chunk;
+        p.div_chunks = make_div((uint32_t)chunks);
+        p.n_copy = (unsigned)(chunks * p.N);
+    }
+
+    // Alternation in layers, so that consecutive blocks - which the dispatcher spreads over a
+    // die's compute units - are of one kind and every unit gets every kind: U conv entries,
+    // then copy entries in proportion to what there is of each kind - times 3/4, so that the
+    // conv entries (the long ones) run out first and the list ends with copy entries, which
+    // even out the end of the call (measured at 540 x 960: 2 - 3 % over plain proportion for
+    // Ks = 7 ... 17, and over the fixed 1:1 / 1:2 / 1:3 patterns before it).
+    if (p.pool_mode == kPoolFused) {
+        p.mix_a = p.mix_b = 1u << 30;  // all conv items first: they must all be in the first round
+    } else {
+        const unsigned Ul = U ? U : 1;
+        p.mix_a = Ul;
+        p.mix_b = Ul;
+        if (p.n_conv > 0 && p.n_copy > 0) {
+            const double share = 0.75 * (double)p.n_copy / (double)p.n_conv;
+            const double mb = share * Ul + 0.5;
+            p.mix_b = mb < 1.0 ? 1u : mb > 64.0 * Ul ? 64u * Ul : (unsigned)mb;
+        }
+    }
+    p.div_mix = make_div(p.mix_a + p.mix_b);
+    p.div_mix_a = make_div(p.mix_a);
+    p.div_mix_b = make_div(p.mix_b);
+
+    Plan plan;
+    unsigned need = per_die_of(p.n_pool) + per_die_of(p.n_gen) + per_die_of(p.n_conv) + per_die_of(p.n_copy);
+    plan.per_die = need < Smax ? need : Smax;
+    p.dynamic = need > Smax;
+    if (plan.per_die < (unsigned)kGroups / kXcds) plan.per_die = kGroups / kXcds;  // every block group needs a member
+    return plan;
+}
+
+// index of a kernel size in the variant tables: 0 for the variant without conv items,
+// (Ks + 1) / 2 for odd Ks
+typedef hipError_t (*LaunchFn)(int, bool, bool, unsigned, hipStream_t, const FwdParams &);
+typedef hipError_t (*OccupancyFn)(int, bool, bool, int *);
+constexpr int kKsSlots = 17;
+#define ESC_LAUNCH_ENTRY(K) launch_ks_##K,
+#define ESC_OCC_ENTRY(K) occupancy_ks_##K,
+const LaunchFn kLaunch[kKsSlots] = {ESC_FOR_EACH_KS(ESC_LAUNCH_ENTRY)};
+const OccupancyFn kOccupancy[kKsSlots] = {ESC_FOR_EACH_KS(ESC_OCC_ENTRY)};
+#undef ESC_LAUNCH_ENTRY
+#undef ESC_OCC_ENTRY
+
+// Resident blocks per compute unit the grid of a variant may count on: what the runtime's
+// occupancy query grants on the device in hand, asked once per device and variant, capped
+// at what the kernel is compiled for.  0 = the variant cannot run here.
+int resident_blocks_per_cu(int ks_slot, int ry, bool bf16, bool staged)
+{
+    constexpr int kMaxDev = 64;
+    static signed char cache[kMaxDev][kKsSlots][2][2][2];  // 0 = not asked yet, else answer + 1
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return 0;
+    signed char &slot = cache[dev][ks_slot][ry == 4][bf16][staged];
+    if (slot == 0) {
+        int n = 0;
+        if (kOccupancy[ks_slot](ry, bf16, staged, &n) != hipSuccess) n = 0;
+        if (n > kBlocksPerCu) n = kBlocksPerCu;
+        if (n < 0) n = 0;
+        slot = (signed char)(n + 1);
+    }
+    return slot - 1;
+}
+
+// Picks the register blocking, plans the items and launches the one kernel of a call.
+esc_status launch_forward(FwdParams &p, int Ks, bool bf16, hipStream_t s)
+{
+    const int cus = device_cus();
+    if (cus < (int)kXcds) return ESC_ERR_HIP;
+    int ry = 2;
+    if (Ks > 0) {
+        // taller register blocks (fewer halo rows, more arithmetic per item's fixed latencies)
+        // once they still give every compute unit two tiles
+        const size_t tiles4 = (size_t)((p.W + kTileW - 1) / kTileW) * ((p.H + 63) / 64) * p.N * p.Ca;
+        ry = (tiles4 >= 2 * (size_t)cus && Ks <= 17) ? 4 : 2;
+        const int th = 16 * ry;
+        const int tiles_x = (p.W + kTileW - 1) / kTileW;
+        const int tiles_y = (p.H + th - 1) / th;
+        p.div_tiles_x = make_div((uint32_t)tiles_x);
+        p.div_tiles_y = make_div((uint32_t)tiles_y);
+        const size_t n_conv = (size_t)tiles_x * tiles_y * p.N * p.Ca;
+        if (n_conv >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
+        p.n_conv = (unsigned)n_conv;
+    }
+    const u64 total = (u64)p.n_pool + p.n_gen + p.n_conv + (p.idt_len > 0 ? 1 : 0);
+    if (total == 0) return ESC_OK;
+    // the blocks of the grid wait for one another, so all of them must be resident at once:
+    // the grid is sized by what the runtime says fits on this device
+    const int ks_slot = (Ks + 1) / 2;
+    const int bpc = resident_blocks_per_cu(ks_slot, ry, bf16, p.staged != 0);
+    if (bpc < 1) return ESC_ERR_UNSUPPORTED;
+    const Plan plan = plan_items(p, Ks, bpc);
+    if ((u64)p.n_pool + p.n_gen + p.n_conv + p.n_copy >= ((u64)1 << 30)) return ESC_ERR_UNSUPPORTED;
+    const unsigned grid = plan.per_die * kXcds;
+    return kLaunch[ks_slot](ry, bf16, p.staged != 0, grid, s, p) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
+}
+
+// fills the parts of FwdParams every entry point shares
+esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C, int H, int W, int Ca,
+                        const esc_gen_params *gen, void *workspace, const WsLayout &l)
+{
+    p = FwdParams{};
+    p.x = x;
+    p.N = N;
+    p.C = C;
+    p.Ca = Ca;
+    p.H = H;
+    p.W = W;
+    p.ptiles_x = l.ptiles_x;
+    p.ptiles = l.ptiles;
+    p.hw = (float)((double)H * (double)W);
+    p.elem_bytes = dt == ESC_F32 ? 4 : 2;
+    p.div_ptiles = make_div((uint32_t)l.ptiles);
+    p.div_ptiles_x = make_div((uint32_t)l.ptiles_x);
+    // aligned 4-element chunk loads (halo tile, pool tile) need W % 4 == 0 and an aligned base
+    p.conv_ld_vec = (W % 4 == 0) && ((uintptr_t)x % (4 * (size_t)p.elem_bytes) == 0);
+    p.div_ca = make_div((uint32_t)(Ca > 0 ? Ca : 1));
+    p.div_tiles_x = p.div_tiles_y = p.div_chunks = p.div_mix = p.div_mix_a = p.div_mix_b = make_div(1);
+    if (gen != nullptr && Ca > 0) {
+        p.dk_mode = ((size_t)Ca * l.ptiles <= (size_t)kDirectMaxBoxes) ? kDkDirect : kDkFromG;
+        p.pool_mode = kPoolItems;
+        p.hidden = gen->hidden;
+        p.w_down = gen->w_down;
+        p.b_down = gen->b_down;
+        p.w_up = gen->w_up;
+        p.b_up = gen->b_up;
+        const size_t n_pool = (size_t)N * Ca * l.ptiles;
+        if (n_pool >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
+        p.n_pool_tiles = (unsigned)n_pool;
+        p.n_pool = (unsigned)((n_pool + kPoolBatch - 1) / kPoolBatch);
+        // Larger planes: a gsum item per (image, channel), then a gen item per image that turns
+        // the means into DK; the conv items pick DK up as from any gen item.  These calls, and
+        // calls whose estimator is beyond the small ones that gen_item prefetches, run the
+        // kernel flavour with the staged estimator items.
+        const int K = gen->hidden > 0 ? gen->hidden : Ca;
+        const bool small_est = K <= 16 && Ca <= 16 && gen->hidden <= kThreads;
+        p.staged = p.dk_mode == kDkFromG || !small_est;
+        if (p.dk_mode == kDkFromG) {
+            p.n_gsum = (unsigned)((size_t)N * Ca);
+            p.n_gen = p.n_gsum + (unsigned)N;
+            p.dk_mode = kDkBoxes;
+        }
+    }
+    char *w = (char *)workspace;
+    p.err = (unsigned *)(w + l.ctl_off) + kCtlErrWord;
+    p.epoch = (unsigned *)(w + l.ctl_off) + kCtlEpochWord;
+    p.done = (unsigned *)(w + l.ctl_off) + kCtlDoneWord;
+    p.queue = (unsigned *)(w + l.ctl_off) + kCtlQueueWord;
+    p.pool_box = (u64 *)(w + l.pool_off);
+    p.dk_box = (u64 *)(w + l.dk_off);
+    p.g_box = (u64 *)(w + l.g_off);
+    return ESC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t esc_workspace_bytes(int N, int C_a, int H, int W)
+{
+    WsLayout l;
+    if (!ws_layout(N, C_a, H, W, &l)) return 0;
+    return l.total;
+}
+
+esc_status esc_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    esc_status st = check_ws(workspace, workspace_bytes, kWsAlign);
+    if (st != ESC_OK) return st;
+    const size_t words = workspace_bytes / 4;
+    const size_t blocks = (words + kThreads - 1) / kThreads;
+    if (blocks >= ((size_t)1 << 31)) return ESC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(ws_init_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
+                       (uint32_t *)workspace, words);
+    return hipGetLastError() == hipSuccess ? ESC_OK : ESC_ERR_HIP;
+}
+
+esc_status esc_workspace_errors(const void *workspace, size_t workspace_bytes, void *stream,
+                                unsigned *errors_out)
+{
+    if (errors_out == nullptr) return ESC_ERR_NULL;
+    esc_status st = check_ws(workspace, workspace_bytes, kWsAlign);
+    if (st != ESC_OK) return st;
+    unsigned v = 0;
+    if (hipMemcpyAsync(&v, (const uint32_t *)workspace + kCtlErrWord, sizeof v, hipMemcpyDeviceToHost,
+                       (hipStream_t)stream) != hipSuccess)
+        return ESC_ERR_HIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ESC_ERR_HIP;
+    *errors_out = v;
+    return ESC_OK;
+}
+
+esc_status esc_dynkernel_gen(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                             const esc_gen_params *gen, float *dk_out, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    esc_status st = check_common(x, dt, N, C, H, W, C_a);
+    if (st != ESC_OK) return st;
+    if (gen == nullptr) return ESC_ERR_NULL;
+    if ((st = check_gen(gen, C_a)) != ESC_OK) return st;
+    if (C_a > 0 && dk_out == nullptr) return ESC_ERR_NULL;
+    WsLayout l;
+    if (!ws_layout(N, C_a, H, W, &l)) return ESC_ERR_SHAPE;
+    if ((st = check_ws(workspace, workspace_bytes, l.total)) != ESC_OK) return st;
+    if (C_a == 0) return ESC_OK;
+    {
+        const size_t x_bytes = (size_t)N * C * H * W * (dt == ESC_F32 ? 4 : 2);
+        const size_t dk_bytes = (size_t)N * C_a * 9 * sizeof(float);
+        if (overlaps(dk_out, dk_bytes, x, x_bytes) || overlaps(dk_out, dk_bytes, workspace, workspace_bytes) ||
+            overlaps(workspace, workspace_bytes, x, x_bytes))
+            return ESC_ERR_ALIAS;
+    }
+    FwdParams p;
+    if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
+    p.dk_out = dk_out;
+    p.dk_mode = kDkBoxes;  // no conv items here: gen items write dk_out, each from its image's pool sums
+    p.n_gen = (unsigned)N;
+    p.n_gsum = 0;
+    return launch_forward(p, 0, dt == ESC_BF16, (hipStream_t)stream);
+}
+
+esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                const float *lk, int Ks, long lk_channel_stride,
+                                const esc_gen_params *gen, const float *dk_in, void *out,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    esc_status st = check_common(x, dt, N, C, H, W, C_a);
+    if (st != ESC_OK) return st;
+    if (out == nullptr) return ESC_ERR_NULL;
+    if (Ks < 1 || (Ks % 2) == 0) return Ks < 1 ? ESC_ERR_SHAPE : ESC_ERR_UNSUPPORTED;
+    if (Ks > kMaxKs) return ESC_ERR_UNSUPPORTED;
+    if (C_a > 0 && lk == nullptr) return ESC_ERR_NULL;
+    if (lk_channel_stride != 0 && lk_channel_stride < (long)Ks * Ks) return ESC_ERR_SHAPE;
+    if (gen != nullptr && (st = check_gen(gen, C_a)) != ESC_OK) return st;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    if (((uintptr_t)out % es) != 0) return ESC_ERR_SHAPE;
+    const size_t bytes = (size_t)N * C * H * W * es;
+    const uintptr_t xa = (uintptr_t)x, oa = (uintptr_t)out;
+    if (overlaps(x, bytes, out, bytes)) return ESC_ERR_ALIAS;
+    WsLayout l;
+    if (!ws_layout(N, C_a, H, W, &l)) return ESC_ERR_SHAPE;
+    if ((st = check_ws(workspace, workspace_bytes, l.total)) != ESC_OK) return st;
+    if (overlaps(workspace, workspace_bytes, out, bytes) || overlaps(workspace, workspace_bytes, x, bytes))
+        return ESC_ERR_ALIAS;
+    if (C_a > 0) {
+        const size_t lk_bytes = ((size_t)(lk_channel_stride != 0 ? C_a - 1 : 0) * (size_t)lk_channel_stride +
+                                 (size_t)Ks * Ks) * sizeof(float);
+        if (overlaps(lk, lk_bytes, out, bytes)) return ESC_ERR_ALIAS;
+        if (gen == nullptr && dk_in != nullptr && overlaps(dk_in, (size_t)N * C_a * 9 * sizeof(float), out, bytes))
+            return ESC_ERR_ALIAS;
+    }
+
+    FwdParams p;
+    if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
+    p.out = out;
+    p.lk = lk;
+    p.lk_cstride = lk_channel_stride;
+    p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
+    if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
+    // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
+    p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
+    if (C_a < C) {
+        const size_t plane = (size_t)H * W * es;
+        p.img_bytes = plane * C;
+        p.idt_off = plane * C_a;
+        p.idt_len = plane * (C - C_a);
+        p.copy_vec_ok = (xa % 16 == 0) && (oa % 16 == 0) && (p.img_bytes % 16 == 0) && (p.idt_off % 16 == 0);
+    }
+    const int ks_variant = C_a > 0 ? Ks : 0;
+    return launch_forward(p, ks_variant, dt == ESC_BF16, (hipStream_t)stream);
+}
+
+
+const char *esc_status_string(esc_status s)
+{
+    switch (s) {
+    case ESC_OK: return "ok";
+    case ESC_ERR_NULL: return "a required pointer is NULL";
+    case ESC_ERR_SHAPE: return "a size or stride is out of its domain";
+    case ESC_ERR_DTYPE: return "unknown storage type";
+    case ESC_ERR_UNSUPPORTED: return "outside the library's limits (Ks odd <= 31, C_a <= 256, hidden <= 256)";
+    case ESC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ESC_ERR_ALIAS: return "out overlaps x, the workspace, lk or dk";
+    case ESC_ERR_HIP: return "the HIP runtime refused a launch";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

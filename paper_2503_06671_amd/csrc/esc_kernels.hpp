@@ -1,5 +1,6 @@
-// ConvAttn forward for gfx950 (MI355X): hand-written HIP kernels and the C ABI
-// declared in include/esc_convattn.h.
+// Device code of the ConvAttn forward for gfx950 (MI355X): the work items and the one
+// persistent kernel that runs them.  Included by esc_variants.hip (which instantiates the
+// kernel for one kernel size per translation unit) and by esc_api.hip (host side, C ABI).
 //
 // The operation is Eq. 4 of the ESC paper with the depth-wise large kernel of
 // the paragraph around Eq. 5.  Everything is plain fp32 vector arithmetic (a
@@ -63,16 +64,15 @@
 //   - any private-segment (scratch) use costs a launch a fixed microsecond or more, and the
 //     compiler spills as soon as thread-index arithmetic is hoisted out of the item loop
 //     and held through every item: each phase takes the thread index afresh (opaque_tid).
+#pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdio.h>
-#include <stdlib.h>
 
 #include <type_traits>
 
 #include "esc_convattn.h"
 
-namespace {
+namespace esc {
 
 constexpr int kThreads = 256;      // 4 wavefronts per block
 constexpr int kTileW = 64;         // conv tile width: 16 lanes x 4 outputs
@@ -96,30 +96,98 @@ struct bf16_t {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 
-// Optional per-item timeline (development builds only, -DESC_TRACE): 16 words per item,
-// kept in registers while the item runs and written out when it ends.
-#ifdef ESC_TRACE
-struct Trace {
-    u64 t[16];
+struct FastDiv {
+    uint32_t d, mul, shift;
 };
-__shared__ u64 g_dbg[4];
-#define ESC_STAMP(rec, k) ((rec).t[k] = wall_clock64())
-#define ESC_TRACE_INIT(rec)                          \
-    do {                                             \
-        for (int k_ = 0; k_ < 16; ++k_) (rec).t[k_] = 0; \
-        (rec).t[13] = clock64();                     \
-        (rec).t[2] = wall_clock64();                 \
-    } while (0)
-#else
-struct Trace {
+
+// ---------------------------------------------------------------------------
+// kernel arguments
+// ---------------------------------------------------------------------------
+enum : int {
+    kDkNone = 0,    // DK = 0
+    kDkGiven = 1,   // caller's dk_in
+    kDkBoxes = 2,   // published by a gen item (esc_dynkernel_gen: the gen items also write dk_out)
+    kDkDirect = 3,  // each conv item finishes the GAP and runs its nine estimator outputs itself
+    kDkFromG = 4    // host only, while a call is set up: larger planes, whose means come from gsum
+                    // items (n_gsum > 0); the call then runs as kDkBoxes
 };
-#define ESC_STAMP(rec, k) \
-    do {                  \
-    } while (0)
-#define ESC_TRACE_INIT(rec) \
-    do {                    \
-    } while (0)
-#endif
+enum : int {
+    kPoolNone = 0,   // no estimator in this call
+    kPoolItems = 1,  // pool items read the attention slice and publish the partial sums
+    kPoolFused = 2   // every conv item is resident at once: each publishes the sum of its own tile
+};
+// an image with at most this many pool mailboxes (C_a * pool tiles) has them read in one
+// round by whoever finishes its GAP (a gen item, or each conv item); larger ones go
+// through channel-mean items
+constexpr int kDirectMaxBoxes = 512;
+constexpr int kPoolTileW = 64, kPoolTileH = 32;  // the GAP is cut into 64 x 32 pixel tiles
+constexpr int kPoolBatch = 4;                    // pool tiles per pool item
+
+struct FwdParams {
+    const void *x;
+    void *out;
+    const float *lk;
+    long lk_cstride;
+    const float *dk_in;  // DK given by the caller (no estimator), or NULL
+    float *dk_out;       // esc_dynkernel_gen: where the estimator's DK goes, else NULL
+    const float *w_down, *b_down, *w_up, *b_up;
+    int hidden;
+    int dk_mode;         // where conv items take DK from (kDk*)
+    int pool_mode;       // who computes the GAP partial sums (kPool*)
+    int N, C, Ca, H, W;
+    int ptiles_x, ptiles;  // pool tiles per row of tiles / per (image, channel) plane
+    float hw;            // H*W as a float, the GAP divisor
+    unsigned n_pool, n_gen, n_conv, n_copy;  // item counts
+    unsigned n_pool_tiles;                   // N * C_a * ptiles (a pool item covers kPoolBatch of them)
+    // conv and copy items alternate in groups of mix_a conv + mix_b copy items while both
+    // last; the rest of the conv items follow, then the rest of the copy items
+    unsigned mix_a, mix_b;
+    FastDiv div_ptiles, div_ptiles_x, div_ca, div_tiles_x, div_tiles_y, div_chunks, div_mix, div_mix_a, div_mix_b;
+    size_t img_bytes, idt_off, idt_len;      // pass-through range of one image, in bytes
+    size_t copy_chunk;                       // bytes per copy item (a multiple of kCopyPiece)
+    int conv_vec_ok, conv_ld_vec, copy_vec_ok, elem_bytes;
+    u64 *pool_box;       // [N*Ca*ptiles] partial sums
+    u64 *dk_box;         // [N*Ca*9]
+    u64 *g_box;          // [N*Ca] channel means (calls with gsum items)
+    unsigned n_gsum;     // channel-mean calls: the first n_gsum gen entries are gsum items, one per
+                         // (image, channel); the N gen items behind them turn the means into DK
+    unsigned *err;       // raised when a bounded wait expires
+    unsigned *epoch;     // [kGroups] call counters (kCtlStride words apart) = tag of the current call
+    unsigned *done;      // [kGroups] blocks of the group that have announced their leave
+    unsigned *queue;     // [kGroups] entries of the group's list handed out beyond the first per block
+    int dynamic;         // blocks take their further entries from the group's queue
+    int staged;          // host only: launch the kernel flavour with the staged estimator items
+    // Every conv item is resident from the start (fused pooling) and the call is so short
+    // that the conv items' chain of load, taps, estimator and store is what it lasts: the
+    // copy items then keep little in flight, so that the conv items' few accesses (tile,
+    // mailboxes) come back quickly; measured, a full-rate copy beside them costs more than
+    // it saves.
+    int copy_gentle;
+};
+
+// The kernel's parameter block as the item functions see it: a pointer into the kernel
+// argument segment (constant address space), read with scalar loads where needed instead
+// of being held in registers across a whole item.
+typedef const __attribute__((address_space(4))) FwdParams *ParamsPtr;
+
+constexpr unsigned kXcds = 8;
+constexpr int kPrioHigh = 3;  // wavefront priority outside the tap loop
+
+// Control block at the start of the workspace, in 32-bit words: word 0 the error word, then
+// from kCtlEpochWord one call counter per group, from kCtlDoneWord one leave counter per
+// group and from kCtlQueueWord one queue counter per group, each kCtlStride words apart.
+// Preparation: everything zero, call counters 1 (tag 0 is what empty mailboxes carry).
+constexpr size_t kCtlErrWord = 0;
+constexpr size_t kCtlEpochWord = kCtlStride;
+constexpr size_t kCtlDoneWord = kCtlEpochWord + (size_t)kGroups * kCtlStride;
+constexpr size_t kCtlQueueWord = kCtlDoneWord + (size_t)kGroups * kCtlStride;
+constexpr size_t kCtlWords = kCtlQueueWord + (size_t)kGroups * kCtlStride;
+
+
+}  // namespace esc
+
+namespace esc {
+namespace {
 
 // ---------------------------------------------------------------------------
 // storage helpers
@@ -188,9 +256,6 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
 }
 
 // x / d for x < 2^31 by multiply-high and shift (host fills mul and shift)
-struct FastDiv {
-    uint32_t d, mul, shift;
-};
 __device__ __forceinline__ uint32_t fdiv(uint32_t x, uint32_t mul, uint32_t shift)
 {
     return (__umulhi(x, mul) + x) >> shift;
@@ -220,7 +285,8 @@ __device__ __forceinline__ void box_put(u64 *box, float v, uint32_t tag)
                        __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Waits (bounded) until the mailbox carries this call's tag.  On expiry raises *err.
+// Waits (bounded) until the mailbox carries this call's tag.  On expiry raises *err and
+// hands back NaN, so that whatever is computed from the missing value shows in the output.
 __device__ __forceinline__ float box_get(const u64 *box, uint32_t tag, unsigned *err)
 {
     for (unsigned spin = 0; spin < kSpinLimit; ++spin) {
@@ -229,11 +295,11 @@ __device__ __forceinline__ float box_get(const u64 *box, uint32_t tag, unsigned 
         __builtin_amdgcn_s_sleep(2);
     }
     __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return 0.f;
+    return __uint_as_float(0x7fc00000u);
 }
 
-// Whole block: waits for cnt (<= PER * kPollThreads) consecutive mailboxes and copies their
-// values to dst[0..cnt).  A thread's polls are issued together so their round trips overlap.
+// Whole block: waits (bounded) for cnt (<= PER * kPollThreads) consecutive mailboxes and
+// copies their values to dst[0..cnt).  A thread's polls are issued together so their round trips overlap.
 // With `have_first` the caller has already issued the first round into v.
 template <int PER>
 __device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *dst, uint32_t tag, unsigned *err,
@@ -244,9 +310,6 @@ __device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *d
 #pragma unroll
     for (int u = 0; u < PER; ++u) pend[u] = tid < kPollThreads && tid + u * kPollThreads < cnt;
     bool any = false;
-#ifdef ESC_TRACE
-    if (threadIdx.x == 0) g_dbg[1] = wall_clock64();
-#endif
     for (unsigned spin = 0; spin < kSpinLimit; ++spin) {
         if (spin > 0 || !have_first) {
 #pragma unroll
@@ -266,16 +329,15 @@ __device__ __forceinline__ void boxes_to_lds(const u64 *boxes, int cnt, float *d
                     any = true;
                 }
             }
-#ifdef ESC_TRACE
-        if (threadIdx.x == 0) {
-            if (spin < 1) g_dbg[spin] = wall_clock64();
-            g_dbg[3] = spin + 1;
-        }
-#endif
         if (!any) break;
         __builtin_amdgcn_s_sleep(2);
     }
-    if (any) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (any) {  // expired: raise the error word; the values that never came read as NaN
+        __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int u = 0; u < PER; ++u)
+            if (pend[u]) dst[tid + u * kPollThreads] = __uint_as_float(0x7fc00000u);
+    }
 }
 
 // Sum over the 64 lanes of a wavefront, returned in every lane.  Data-parallel-primitive
@@ -315,80 +377,6 @@ __device__ __forceinline__ float row_sum(float v)
     return v;
 }
 
-// ---------------------------------------------------------------------------
-// kernel arguments
-// ---------------------------------------------------------------------------
-enum : int {
-    kDkNone = 0,    // DK = 0
-    kDkGiven = 1,   // caller's dk_in
-    kDkBoxes = 2,   // published by a gen item (esc_dynkernel_gen: the gen items also write dk_out)
-    kDkDirect = 3,  // each conv item finishes the GAP and runs its nine estimator outputs itself
-    kDkFromG = 4    // host only, while a call is set up: larger planes, whose means come from gsum
-                    // items (n_gsum > 0); the call then runs as kDkBoxes
-};
-enum : int {
-    kPoolNone = 0,   // no estimator in this call
-    kPoolItems = 1,  // pool items read the attention slice and publish the partial sums
-    kPoolFused = 2   // every conv item is resident at once: each publishes the sum of its own tile
-};
-// an image with at most this many pool mailboxes (C_a * pool tiles) has them read in one
-// round by whoever finishes its GAP (a gen item, or each conv item); larger ones go
-// through channel-mean items
-constexpr int kDirectMaxBoxes = 512;
-constexpr int kPoolTileW = 64, kPoolTileH = 32;  // the GAP is cut into 64 x 32 pixel tiles
-constexpr int kPoolBatch = 4;                    // pool tiles per pool item
-
-struct FwdParams {
-    const void *x;
-    void *out;
-    const float *lk;
-    long lk_cstride;
-    const float *dk_in;  // DK given by the caller (no estimator), or NULL
-    float *dk_out;       // esc_dynkernel_gen: where the estimator's DK goes, else NULL
-    const float *w_down, *b_down, *w_up, *b_up;
-    int hidden;
-    int dk_mode;         // where conv items take DK from (kDk*)
-    int pool_mode;       // who computes the GAP partial sums (kPool*)
-    int N, C, Ca, H, W;
-    int ptiles_x, ptiles;  // pool tiles per row of tiles / per (image, channel) plane
-    float hw;            // H*W as a float, the GAP divisor
-    unsigned n_pool, n_gen, n_conv, n_copy;  // item counts
-    unsigned n_pool_tiles;                   // N * C_a * ptiles (a pool item covers kPoolBatch of them)
-    // conv and copy items alternate in groups of mix_a conv + mix_b copy items while both
-    // last; the rest of the conv items follow, then the rest of the copy items
-    unsigned mix_a, mix_b;
-    FastDiv div_ptiles, div_ptiles_x, div_ca, div_tiles_x, div_tiles_y, div_chunks, div_mix, div_mix_a, div_mix_b;
-    size_t img_bytes, idt_off, idt_len;      // pass-through range of one image, in bytes
-    size_t copy_chunk;                       // bytes per copy item (a multiple of kCopyPiece)
-    int conv_vec_ok, conv_ld_vec, copy_vec_ok, elem_bytes;
-    u64 *pool_box;       // [N*Ca*ptiles] partial sums
-    u64 *dk_box;         // [N*Ca*9]
-    u64 *g_box;          // [N*Ca] channel means (calls with gsum items)
-    unsigned n_gsum;     // channel-mean calls: the first n_gsum gen entries are gsum items, one per
-                         // (image, channel); the N gen items behind them turn the means into DK
-    unsigned *err;       // raised when a bounded wait expires
-    unsigned *epoch;     // [kGroups] call counters (kCtlStride words apart) = tag of the current call
-    unsigned *done;      // [kGroups] blocks of the group that have announced their leave
-    unsigned *queue;     // [kGroups] entries of the group's list handed out beyond the first per block
-    int dynamic;         // blocks take their further entries from the group's queue
-    int staged;          // host only: launch the kernel flavour with the staged estimator items
-    // Every conv item is resident from the start (fused pooling) and the call is so short
-    // that the conv items' chain of load, taps, estimator and store is what it lasts: the
-    // copy items then keep little in flight, so that the conv items' few accesses (tile,
-    // mailboxes) come back quickly; measured, a full-rate copy beside them costs more than
-    // it saves.
-    int copy_gentle;
-    u64 *trace;          // development builds only
-};
-
-// The kernel's parameter block as the item functions see it: a pointer into the kernel
-// argument segment (constant address space), read with scalar loads where needed instead
-// of being held in registers across a whole item.
-typedef const __attribute__((address_space(4))) FwdParams *ParamsPtr;
-
-constexpr unsigned kXcds = 8;
-constexpr int kPrioHigh = 3;  // wavefront priority outside the tap loop
-
 // die `die`'s contiguous share of n items: [base, base + cnt)
 __device__ __forceinline__ void die_share(unsigned n, unsigned die, unsigned &base, unsigned &cnt)
 {
@@ -409,9 +397,6 @@ __shared__ __align__(16) float g_t[kMaxHidden];
 __shared__ float g_small[16];
 __shared__ float g_red[4 * kPoolBatch];  // wavefront totals of the pool tiles being finished
 __shared__ unsigned g_next[2];
-#ifdef ESC_TRACE
-__shared__ u64 g_wave_end[4];
-#endif
 
 // Per-block state that item code touches.
 struct Ctx {
@@ -421,13 +406,6 @@ struct Ctx {
     bool announced;   // leave already announced
     unsigned left;    // thread kThreads-1 only: blocks of the group that had announced before this one
     unsigned claim;   // thread kThreads-1 only: what the group's queue returned for the block's next entry
-};
-
-// What an item function hands back: the updated block state (and, in development builds,
-// its timeline).
-struct ItemOut {
-    Ctx ctx;
-    Trace rec;
 };
 
 // Reads the call tag once per block, at a point where the caller's own loads are already
@@ -520,11 +498,9 @@ __device__ __forceinline__ void pool_finish(u64 *pool_box, const float (&s)[NB],
 // next; addresses are clamped into the plane and what lies outside is zeroed afterwards),
 // then each tile's sum is formed and published as if it were alone.
 template <typename T>
-__device__ __forceinline__ ItemOut pool_item(ParamsPtr p, Ctx ctx, unsigned item)
+__device__ __forceinline__ Ctx pool_item(ParamsPtr p, Ctx ctx, unsigned item)
 {
     float *s_red = g_red;
-    Trace rec;
-    ESC_TRACE_INIT(rec);
     const int H = p->H, W = p->W;
     const int tid = opaque_tid();
     const int tx = tid & 15, ty = tid >> 4;
@@ -575,8 +551,7 @@ __device__ __forceinline__ ItemOut pool_item(ParamsPtr p, Ctx ctx, unsigned item
         have[b] = first + b < ntiles;
     }
     pool_finish<kPoolBatch>(p->pool_box, sums, box, have, ctx.tag, s_red);
-    ESC_STAMP(rec, 6);
-    return ItemOut{ctx, rec};
+    return ctx;
 }
 
 // ---------------------------------------------------------------------------
@@ -701,13 +676,7 @@ __device__ __forceinline__ void estimator_front(ParamsPtr p, uint32_t tag, unsig
         for (int c0 = c_first; c0 < c_end; c0 += G) {
             const int gc = c_end - c0 < G ? c_end - c0 : G;
             boxes_to_lds(img_boxes + (size_t)c0 * ntile, gc * ntile, s_part, tag, p->err, polled, false);
-#ifdef ESC_TRACE
-            if (threadIdx.x == 0) g_wave_end[0] = wall_clock64();  // thread 0 has its mailboxes
-#endif
             __syncthreads();
-#ifdef ESC_TRACE
-            if (threadIdx.x == 0) g_wave_end[1] = wall_clock64();  // every thread has
-#endif
             sum_staged(s_part, ntile, gc, c0, p->hw, s_g);
             __syncthreads();
         }
@@ -746,11 +715,9 @@ __device__ __forceinline__ float estimator_out(ParamsPtr p, int o, const float *
     return dot_row(p->w_up + (size_t)o * K, in, K, p->b_up ? p->b_up[o] : 0.f);
 }
 
-__device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
+__device__ __forceinline__ Ctx gen_item(ParamsPtr p, Ctx ctx, unsigned n)
 {
     float *s_part = g_part, *s_g = g_g, *s_t = g_t;
-    Trace rec;
-    ESC_TRACE_INIT(rec);
     need_tag(p, ctx);
     announce_leave(p, ctx);
     // Small estimators (one output per thread, rows of at most 16 weights): the weights are
@@ -771,7 +738,6 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
         if (o1 < hidden && p->b_down) bd = p->b_down[o1];
     }
     estimator_front(p, ctx.tag, n, 0, Ca, !pre, s_part, s_g, s_t);
-    ESC_STAMP(rec, 3);
     if (pre) {
         if (hidden > 0) {
             if (o1 < hidden) {
@@ -793,15 +759,6 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
             box_put(p->dk_box + idx, s, ctx.tag);
             if (p->dk_out) p->dk_out[idx] = s;
         }
-        ESC_STAMP(rec, 4);
-#ifdef ESC_TRACE
-        rec.t[7] = g_wave_end[0];
-        rec.t[8] = g_wave_end[1];
-        rec.t[9] = g_dbg[0];
-        rec.t[10] = g_dbg[1];
-        rec.t[11] = g_dbg[2];
-        rec.t[12] = g_dbg[3];
-#endif
     } else {
         for (int o = threadIdx.x; o < 9 * Ca; o += kThreads) {
             const float s = estimator_out(p, o, s_g, s_t);
@@ -811,8 +768,7 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
         }
     }
     claim_next(p, ctx);
-    ESC_STAMP(rec, 6);
-    return ItemOut{ctx, rec};
+    return ctx;
 }
 
 // ---------------------------------------------------------------------------
@@ -823,21 +779,17 @@ __device__ __forceinline__ ItemOut gen_item(ParamsPtr p, Ctx ctx, unsigned n)
 
 // gsum item: the mean of one (image, channel) plane from its pool mailboxes, with the
 // additions in the order every other path uses, published in the channel's mean mailbox.
-__device__ __forceinline__ ItemOut gsum_item(ParamsPtr p, Ctx ctx, unsigned nc)
+__device__ __forceinline__ Ctx gsum_item(ParamsPtr p, Ctx ctx, unsigned nc)
 {
     float *s_part = g_part, *s_g = g_g, *s_t = g_t;
-    Trace rec;
-    ESC_TRACE_INIT(rec);
     need_tag(p, ctx);
     announce_leave(p, ctx);
     const unsigned n = fdiv(nc, p->div_ca.mul, p->div_ca.shift);
     const int c = (int)(nc - n * (unsigned)p->Ca);
     estimator_front(p, ctx.tag, n, c, c + 1, false, s_part, s_g, s_t);
-    ESC_STAMP(rec, 3);
     if (threadIdx.x == 0) box_put(p->g_box + nc, s_g[c], ctx.tag);
     claim_next(p, ctx);
-    ESC_STAMP(rec, 6);
-    return ItemOut{ctx, rec};
+    return ctx;
 }
 
 // gen item of image n: the means come from the pool mailboxes (as in gen_item) or, in a
@@ -847,11 +799,9 @@ __device__ __forceinline__ ItemOut gsum_item(ParamsPtr p, Ctx ctx, unsigned nc)
 // after row from memory by the few threads that use them, these weights cost the block ten
 // microseconds and more (measured with C_a = 48 and a hidden layer of 24).  Same products
 // in the same order as dot_row, so DK has the same bits whichever item computes it.
-__device__ __forceinline__ ItemOut gen_item_staged(ParamsPtr p, Ctx ctx, unsigned n, bool from_means)
+__device__ __forceinline__ Ctx gen_item_staged(ParamsPtr p, Ctx ctx, unsigned n, bool from_means)
 {
     float *s_part = g_part, *s_g = g_g, *s_t = g_t, *s_w = g_tile;
-    Trace rec;
-    ESC_TRACE_INIT(rec);
     need_tag(p, ctx);
     announce_leave(p, ctx);
     const int Ca = p->Ca, hidden = p->hidden, K = hidden > 0 ? hidden : Ca;
@@ -896,7 +846,6 @@ __device__ __forceinline__ ItemOut gen_item_staged(ParamsPtr p, Ctx ctx, unsigne
     } else {
         estimator_front(p, ctx.tag, n, 0, Ca, false, s_part, s_g, s_t);
     }
-    ESC_STAMP(rec, 3);
     if (hidden > 0) {
         for (int m = o1; m < hidden; m += kThreads)
             s_t[m] = gelu_erf(staged ? dot_row_lds(s_w + m * Ca, s_g, Ca, bd)
@@ -930,8 +879,7 @@ __device__ __forceinline__ ItemOut gen_item_staged(ParamsPtr p, Ctx ctx, unsigne
         }
     }
     claim_next(p, ctx);
-    ESC_STAMP(rec, 6);
-    return ItemOut{ctx, rec};
+    return ctx;
 }
 
 // ---------------------------------------------------------------------------
@@ -1004,13 +952,11 @@ __device__ __forceinline__ ConvWhere conv_where(ParamsPtr p, unsigned item)
 }
 
 template <int KS, int RY, typename T>
-__device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
+__device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
 {
     using G = ConvGeom<KS, RY>;
     static_assert(G::TILE_FLOATS <= kLdsTileFloats && G::W_FLOATS <= kLdsWeightFloats, "LDS pool too small");
     float *tile = g_tile, *wl = g_wl, *s_dk = g_small, *s_part = g_part, *s_g = g_g, *s_t = g_t;
-    Trace rec;
-    ESC_TRACE_INIT(rec);
     constexpr int PH = G::PH, OFF = G::OFF, TH = G::TH, HR = G::HR, HC = G::HC, PITCH = G::PITCH,
                   NV = G::NV, WP = G::WP;
     // bf16 storage and an unrolled loop: packed tile, two taps per instruction (PackedGeom)
@@ -1144,7 +1090,6 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // (the call tag, asked for behind the tile, has arrived in this wavefront too)
     asm volatile("" ::"v"(ctx.tag));
     __syncthreads();
-    ESC_STAMP(rec, 3);
     // The leave is announced here: every wavefront of the block has its tile and its copy of
     // the call tag (the barrier above), and the announcing wavefront's atomic is then in
     // flight during the tap loop, which waits for no memory access.  Anywhere earlier, the
@@ -1188,7 +1133,6 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             have[h] = (int)pty * kPoolTileH < H;  // block-uniform
         }
         pool_finish<NPT>(p->pool_box, sums, box, have, ctx.tag, g_red);
-        ESC_STAMP(rec, 10);
     }
 
     // What the DK phase will need is asked for ahead of it: the estimator weights this
@@ -1375,7 +1319,6 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
     // stores) above it, so that the short latency-bound phases of one block are not starved
     // by the tap loops of the other blocks on the compute unit.
     __builtin_amdgcn_s_setprio(0);
-    ESC_STAMP(rec, 11);
     // The early requests go out before the loop (in its middle they cost the compiler so
     // many registers that it spills); whatever has not arrived by the end is asked for again.
     ask_early();
@@ -1407,17 +1350,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
             __builtin_amdgcn_sched_barrier(0);  // one row's loads at a time: the registers are few
         }
     }
-#ifdef ESC_TRACE
-#pragma unroll
-    for (int oy = 0; oy < RY; ++oy)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) asm volatile("" ::"v"(acc[oy][q]));
-#endif
     __builtin_amdgcn_s_setprio(kPrioHigh);
-    ESC_STAMP(rec, 4);
-#ifdef ESC_TRACE
-    if ((threadIdx.x & 63) == 0) g_wave_end[threadIdx.x >> 6] = wall_clock64();  // when each wavefront left the loop
-#endif
 
     // ---- phase 3: DK and the stores, located afresh (see opaque_u) ----
     const ConvWhere wd = conv_where<TH>(p, opaque_u(item_in));
@@ -1432,16 +1365,13 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         if (direct) {
             // same arithmetic, in the same order, as estimator_front + estimator_out
             boxes_to_lds(img_boxes, nbox, s_part, ctx.tag, p->err, early, true);
-            ESC_STAMP(rec, 7);
             if (pre_w) {
                 s_wup[tid_d] = wup_r;
                 s_wdn[tid_d] = wdn_r;
             }
             __syncthreads();
-            ESC_STAMP(rec, 8);
             sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
             __syncthreads();
-            ESC_STAMP(rec, 9);
             if (p->hidden > 0) {
                 for (int m = tid_d; m < p->hidden; m += kThreads)
                     s_t[m] = gelu_erf(pre_w ? dot_row_lds(s_wdn + m * p->Ca, s_g, p->Ca, bdn_r)
@@ -1450,7 +1380,6 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
                 __syncthreads();
             }
         }
-        ESC_STAMP(rec, 12);
         if (tid_d < 9) {
             float d;
             if (direct)
@@ -1466,14 +1395,6 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
         }
         __syncthreads();
         claim_next(p, ctx);  // the wait for the estimator is over
-        ESC_STAMP(rec, 5);
-#ifdef ESC_TRACE
-        if (from_boxes) {
-            rec.t[7] = g_wave_end[1];
-            rec.t[8] = g_wave_end[2];
-            rec.t[9] = g_wave_end[3];
-        }
-#endif
         float d[9];
 #pragma unroll
         for (int k = 0; k < 9; ++k) d[k] = s_dk[k];
@@ -1525,8 +1446,7 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
                 if (gx + q < W) store1(dst + q, acc[oy][q]);
         }
     }
-    ESC_STAMP(rec, 6);
-    return ItemOut{ctx, rec};
+    return ctx;
 }
 
 // ---------------------------------------------------------------------------
@@ -1534,10 +1454,8 @@ __device__ __forceinline__ ItemOut conv_item(ParamsPtr p, Ctx ctx, unsigned item
 // channels with 16-byte non-temporal accesses when both sides allow it: 16 KiB pieces,
 // two in flight - or, in the gentle mode, one access per thread at a time.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item)
+__device__ __forceinline__ Ctx copy_item(ParamsPtr p, Ctx ctx, unsigned item)
 {
-    Trace rec;
-    ESC_TRACE_INIT(rec);
     const unsigned n = fdiv(item, p->div_chunks.mul, p->div_chunks.shift);
     const size_t chunk = (size_t)(item - n * p->div_chunks.d);
     const char *src = (const char *)p->x + (size_t)n * p->img_bytes + p->idt_off;
@@ -1635,8 +1553,7 @@ __device__ __forceinline__ ItemOut copy_item(ParamsPtr p, Ctx ctx, unsigned item
                 *reinterpret_cast<uint16_t *>(dst + o) = *reinterpret_cast<const uint16_t *>(src + o);
         }
     }
-    ESC_STAMP(rec, 6);
-    return ItemOut{ctx, rec};
+    return ctx;
 }
 
 // ---------------------------------------------------------------------------
@@ -1716,40 +1633,25 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
         }
         ctx.last_item = !dynamic && li + S >= total;
         if (kind == 0 || kind == 3) claim_next(p, ctx);
-        ItemOut o;
         if (kind == 0) {
-            o = pool_item<T>(p, ctx, idx);
+            ctx = pool_item<T>(p, ctx, idx);
         } else if (kind == 1) {
             if constexpr (STAGED) {
                 // the gsum items of every (image, channel), then one gen item per image
                 const unsigned n_gsum = p->n_gsum;
                 if (idx < n_gsum)
-                    o = gsum_item(p, ctx, idx);
+                    ctx = gsum_item(p, ctx, idx);
                 else
-                    o = gen_item_staged(p, ctx, idx - n_gsum, n_gsum > 0);
+                    ctx = gen_item_staged(p, ctx, idx - n_gsum, n_gsum > 0);
             } else {
-                o = gen_item(p, ctx, idx);
+                ctx = gen_item(p, ctx, idx);
             }
         } else if (kind == 2) {
             if constexpr (KS > 0)
-                o = conv_item<KS, RY, T>(p, ctx, idx);
-            else
-                o.ctx = ctx;
+                ctx = conv_item<KS, RY, T>(p, ctx, idx);
         } else {
-            o = copy_item(p, ctx, idx);
+            ctx = copy_item(p, ctx, idx);
         }
-        ctx = o.ctx;
-#ifdef ESC_TRACE
-        Trace &rec = o.rec;
-        if (p->trace != nullptr && threadIdx.x == 0) {
-            const unsigned gid = idx + (kind > 0 ? p->n_pool : 0) + (kind > 1 ? p->n_gen : 0) + (kind > 2 ? p->n_conv : 0);
-            rec.t[0] = gid;
-            rec.t[1] = ((u64)__builtin_amdgcn_s_getreg((31 << 11) | 4) << 32) | blockIdx.x;
-            rec.t[15] = __builtin_amdgcn_s_getreg((31 << 11) | 20);
-            rec.t[14] = clock64();
-            for (int k = 0; k < 16; ++k) p->trace[(size_t)gid * 16 + k] = rec.t[k];
-        }
-#endif
         if (dynamic) {
             if (threadIdx.x == kThreads - 1) g_next[turn & 1] = k8 + kXcds * (members8 + ctx.claim);
             __syncthreads();  // also: LDS is reused by the next item
@@ -1776,483 +1678,6 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
     }
 }
 
-// Control block at the start of the workspace, in 32-bit words: word 0 the error word, then
-// from kCtlEpochWord one call counter per group, from kCtlDoneWord one leave counter per
-// group and from kCtlQueueWord one queue counter per group, each kCtlStride words apart.
-// Preparation: everything zero, call counters 1 (tag 0 is what empty mailboxes carry).
-constexpr size_t kCtlErrWord = 0;
-constexpr size_t kCtlEpochWord = kCtlStride;
-constexpr size_t kCtlDoneWord = kCtlEpochWord + (size_t)kGroups * kCtlStride;
-constexpr size_t kCtlQueueWord = kCtlDoneWord + (size_t)kGroups * kCtlStride;
-constexpr size_t kCtlWords = kCtlQueueWord + (size_t)kGroups * kCtlStride;
-
-__global__ void ws_init_kernel(uint32_t *ptr, size_t words)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool is_epoch = i >= kCtlEpochWord && i < kCtlDoneWord && (i - kCtlEpochWord) % kCtlStride == 0;
-    if (i < words) ptr[i] = is_epoch ? 1u : 0u;
-}
-
-// ---------------------------------------------------------------------------
-// Host side
-// ---------------------------------------------------------------------------
-struct WsLayout {
-    int ptiles_x, ptiles;
-    size_t ctl_off, pool_off, dk_off, g_off, total;
-};
-
-size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-bool ws_layout(int N, int Ca, int H, int W, WsLayout *l)
-{
-    if (N < 1 || Ca < 0 || H < 1 || W < 1) return false;
-    const size_t hw = (size_t)H * (size_t)W;
-    if (hw >= ((size_t)1 << 31)) return false;
-    l->ptiles_x = (W + kPoolTileW - 1) / kPoolTileW;
-    l->ptiles = l->ptiles_x * ((H + kPoolTileH - 1) / kPoolTileH);
-    size_t off = 0;
-    l->ctl_off = off;
-    off = round_up(off + kCtlWords * sizeof(uint32_t), kWsAlign);
-    l->pool_off = off;
-    off = round_up(off + (size_t)N * Ca * l->ptiles * sizeof(u64), kWsAlign);
-    l->dk_off = off;
-    off = round_up(off + (size_t)N * Ca * 9 * sizeof(u64), kWsAlign);
-    l->g_off = off;
-    off = round_up(off + (size_t)N * Ca * sizeof(u64), kWsAlign);
-    l->total = off;
-    return true;
-}
-
-FastDiv make_div(uint32_t d)
-{
-    FastDiv f;
-    if (d == 0) d = 1;
-    uint32_t l = 0;
-    while (((uint64_t)1 << l) < d) ++l;
-    f.d = d;
-    f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
-    f.shift = l;
-    return f;
-}
-
-esc_status check_common(const void *x, esc_dtype dt, int N, int C, int H, int W, int Ca)
-{
-    if (dt != ESC_F32 && dt != ESC_BF16) return ESC_ERR_DTYPE;
-    if (N < 1 || C < 1 || H < 1 || W < 1 || Ca < 0 || Ca > C) return ESC_ERR_SHAPE;
-    if (x == nullptr) return ESC_ERR_NULL;
-    if ((size_t)H * (size_t)W >= ((size_t)1 << 31)) return ESC_ERR_UNSUPPORTED;
-    if (Ca > kMaxCa) return ESC_ERR_UNSUPPORTED;
-    const size_t es = dt == ESC_F32 ? 4 : 2;
-    if (((uintptr_t)x % es) != 0) return ESC_ERR_SHAPE;
-    return ESC_OK;
-}
-
-esc_status check_gen(const esc_gen_params *gen, int Ca)
-{
-    if (gen->hidden < 0) return ESC_ERR_SHAPE;
-    if (gen->hidden > kMaxHidden) return ESC_ERR_UNSUPPORTED;
-    if (Ca > 0 && gen->w_up == nullptr) return ESC_ERR_NULL;
-    if (Ca > 0 && gen->hidden > 0 && gen->w_down == nullptr) return ESC_ERR_NULL;
-    return ESC_OK;
-}
-
-esc_status check_ws(const void *ws, size_t ws_bytes, size_t need)
-{
-    if (need < kCtlWords * sizeof(uint32_t)) need = kCtlWords * sizeof(uint32_t);
-    if (ws == nullptr || ((uintptr_t)ws % kWsAlign) != 0 || ws_bytes < need) return ESC_ERR_WORKSPACE;
-    return ESC_OK;
-}
-
-#ifdef ESC_TRACE
-u64 *g_trace = nullptr;
-#endif
-
-// development knob: ESC_CONV_RY=2 or 4 forces the conv items' register blocking
-int conv_ry_override()
-{
-    static int v = [] {
-        const char *e = getenv("ESC_CONV_RY");
-        return e ? atoi(e) : 0;
-    }();
-    return v;
-}
-
-int device_cus()
-{
-    static int cus = [] {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            return prop.multiProcessorCount;
-        return 0;
-    }();
-    return cus;
-}
-
-// Lays the items out for the grid: how many blocks per die, whether the conv items can
-// pool for themselves, how big a copy item is and how conv and copy items alternate.
-// n_conv, n_gen and the pass-through range are set; n_pool holds the pool-item count that
-// applies if pooling is not fused.
-struct Plan {
-    unsigned per_die;
-};
-
-Plan plan_items(FwdParams &p, int Ks)
-{
-    const unsigned U = (unsigned)device_cus() / kXcds;          // compute units per die
-    const unsigned Smax = (unsigned)kBlocksPerCu * (U ? U : 1);  // resident blocks per die
-    auto per_die_of = [](u64 n) { return (unsigned)((n + kXcds - 1) / kXcds); };
-
-    // Few pool tiles per image: one gen item per image runs the estimator while the conv
-    // items multiply, and they pick DK up on the way (asked for inside the tap loop) - if the
-    // gen items still fit beside all conv items (fused pooling).  Otherwise the conv items
-    // run the estimator themselves (direct mode).  Measured at 180 x 320, the hop is the
-    // faster of the two for every Ks.
-    if (p.pool_mode == kPoolItems && p.dk_mode == kDkDirect && p.n_conv > 0 &&
-        per_die_of(p.n_conv) + per_die_of((u64)p.N) <= Smax) {
-        p.dk_mode = kDkBoxes;
-        p.n_gen = (unsigned)p.N;
-    }
-
-    // all conv items (and the gen items they wait for) in the first round => fused pooling
-    if (p.pool_mode == kPoolItems && p.n_conv > 0 && per_die_of(p.n_conv) + per_die_of(p.n_gen) <= Smax) {
-        p.pool_mode = kPoolFused;
-        p.n_pool = 0;
-    }
-
-    // rough time shares of the arithmetic and of the pass-through traffic decide how many
-    // copy items there are to a conv item (and with that how small they are): 1, 2 or 3,
-    // thresholds from sweeps at 540 x 960 with Ks = 7 ... 31
-    const double pix = (double)p.N * p.Ca * p.H * p.W;
-    const double t_valu = 2.0 * Ks * Ks * pix / 50e12;  // what a conv item sustains, its loads included
-    const double t_copy = 2.0 * (double)p.N * (double)p.idt_len / 4.5e12;
-    unsigned a = 1, b = 1;
-    if (t_valu > 0 && t_copy > 0) {
-        const double share = t_valu / (t_valu + t_copy);
-        if (share < 0.6) b = 2;
-        if (share < 0.3) b = 3;
-    }
-
-    // short calls (the conv items' own chain is most of them): gentle copying, if the blocks
-    // left over beside the conv items get through the pass-through range in about a dozen
-    // accesses per thread
-    {
-        const u64 others0 = (u64)p.n_pool + p.n_gen + p.n_conv, resident0 = (u64)kXcds * Smax;
-        const u64 spare = resident0 > others0 + kXcds * 4 ? resident0 - others0 - kXcds * 3 : 0;
-        p.copy_gentle = p.pool_mode == kPoolFused && p.n_gsum == 0 && (p.dk_mode == kDkDirect || p.dk_mode == kDkBoxes) &&
-                        (u64)p.N * p.idt_len <= spare * 12 * (u64)kThreads * 16;
-    }
-
-    // copy items: as many as the pattern pairs with the conv items; if the whole call fits
-    // into one round of resident blocks, as many as still fit
-    p.n_copy = 0;
-    p.copy_chunk = kCopyPiece;
-    if (p.idt_len > 0) {
-        u64 want = p.n_conv > 0 ? (u64)p.n_conv * b / a : (u64)kXcds * Smax * 4;
-        const u64 others = (u64)p.n_pool + p.n_gen + p.n_conv;
-        const u64 resident = (u64)kXcds * Smax;
-        if (others + kXcds * 4 < resident && others + want > resident && (resident - others) * 4 >= want)
-            want = resident - others - kXcds * 3;  // the lists are rounded up per kind and die
-        // gentle copying moves one access per thread at a time: as many items as fit, cut finely
-        const size_t grain = p.copy_gentle ? (size_t)kThreads * 16 : kCopyPiece;
-        if (p.copy_gentle && others + kXcds * 4 < resident) want = resident - others - kXcds * 3;
-        // fused pooling without room beside the conv items: the copy comes after them, and
-        // every block should get a share of it
-        if (p.pool_mode == kPoolFused && !p.copy_gentle && want < 2 * resident) want = 2 * resident;
-        if (want < 1) want = 1;
-        u64 per_img = (want + p.N / 2) / p.N;
-        if (per_img < 1) per_img = 1;
-        size_t chunk = (p.idt_len + per_img - 1) / per_img;
-        chunk = (chunk + grain - 1) / grain * grain;
-        const size_t chunks = (p.idt_len + chunk - 1) / chunk;
-        p.copy_chunk = chunk;
-        p.div_chunks = make_div((uint32_t)chunks);
-        p.n_copy = (unsigned)(chunks * p.N);
-    }
-
-    // Alternation in layers, so that consecutive blocks - which the dispatcher spreads over a
-    // die's compute units - are of one kind and every unit gets every kind: U conv entries,
-    // then copy entries in proportion to what there is of each kind - times 3/4, so that the
-    // conv entries (the long ones) run out first and the list ends with copy entries, which
-    // even out the end of the call (measured at 540 x 960: 2 - 3 % over plain proportion for
-    // Ks = 7 ... 17, and over the fixed 1:1 / 1:2 / 1:3 patterns before it).
-    if (p.pool_mode == kPoolFused) {
-        p.mix_a = p.mix_b = 1u << 30;  // all conv items first: they must all be in the first round
-    } else {
-        const unsigned Ul = U ? U : 1;
-        p.mix_a = Ul;
-        p.mix_b = Ul;
-        if (p.n_conv > 0 && p.n_copy > 0) {
-            const double share = 0.75 * (double)p.n_copy / (double)p.n_conv;
-            const double mb = share * Ul + 0.5;
-            p.mix_b = mb < 1.0 ? 1u : mb > 64.0 * Ul ? 64u * Ul : (unsigned)mb;
-        }
-    }
-    p.div_mix = make_div(p.mix_a + p.mix_b);
-    p.div_mix_a = make_div(p.mix_a);
-    p.div_mix_b = make_div(p.mix_b);
-
-    Plan plan;
-    unsigned need = per_die_of(p.n_pool) + per_die_of(p.n_gen) + per_die_of(p.n_conv) + per_die_of(p.n_copy);
-    plan.per_die = need < Smax ? need : Smax;
-    p.dynamic = need > Smax;
-    if (plan.per_die < (unsigned)kGroups / kXcds) plan.per_die = kGroups / kXcds;  // every block group needs a member
-    return plan;
-}
-
-template <int KS, int RY, typename T>
-esc_status launch_variant(FwdParams &p, hipStream_t s)
-{
-    // the kernel is compiled for kBlocksPerCu resident blocks per compute unit (register
-    // budget via __launch_bounds__, LDS <= 40 KiB of 160 KiB), so this grid is co-resident
-    if (device_cus() < (int)kXcds) return ESC_ERR_HIP;
-    const u64 total = (u64)p.n_pool + p.n_gen + p.n_conv + (p.idt_len > 0 ? 1 : 0);
-    if (total == 0) return ESC_OK;
-    const Plan plan = plan_items(p, KS);
-    if ((u64)p.n_pool + p.n_gen + p.n_conv + p.n_copy >= ((u64)1 << 30)) return ESC_ERR_UNSUPPORTED;
-    const unsigned grid = plan.per_die * kXcds;
-    if (p.staged)
-        hipLaunchKernelGGL((forward_kernel<KS, RY, T, true>), dim3(grid), dim3(kThreads), 0, s, p);
-    else
-        hipLaunchKernelGGL((forward_kernel<KS, RY, T, false>), dim3(grid), dim3(kThreads), 0, s, p);
-    return hipGetLastError() == hipSuccess ? ESC_OK : ESC_ERR_HIP;
-}
-
-template <int KS, typename T>
-esc_status launch_ks(FwdParams &p, hipStream_t s)
-{
-    if constexpr (KS == 0) {
-        return launch_variant<0, 2, T>(p, s);
-    } else {
-        // taller register blocks (fewer halo rows, more arithmetic per item's fixed latencies)
-        // once they still give every compute unit two tiles
-        const size_t tiles4 = (size_t)((p.W + kTileW - 1) / kTileW) * ((p.H + 63) / 64) * p.N * p.Ca;
-        int ry = (tiles4 >= 2 * (size_t)device_cus() && KS <= 17) ? 4 : 2;
-        if (conv_ry_override() == 2 || (conv_ry_override() == 4 && KS <= 17)) ry = conv_ry_override();
-        const int th = 16 * ry;
-        const int tiles_x = (p.W + kTileW - 1) / kTileW;
-        const int tiles_y = (p.H + th - 1) / th;
-        p.div_tiles_x = make_div((uint32_t)tiles_x);
-        p.div_tiles_y = make_div((uint32_t)tiles_y);
-        const size_t n_conv = (size_t)tiles_x * tiles_y * p.N * p.Ca;
-        if (n_conv >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
-        p.n_conv = (unsigned)n_conv;
-        if constexpr (KS <= 17) {
-            if (ry == 4) return launch_variant<KS, 4, T>(p, s);
-        }
-        return launch_variant<KS, 2, T>(p, s);
-    }
-}
-
-template <typename T>
-esc_status launch_typed(FwdParams &p, int Ks, hipStream_t s)
-{
-    switch (Ks) {
-#define ESC_KS_CASE(K) \
-    case K: return launch_ks<K, T>(p, s);
-        ESC_KS_CASE(0)
-        ESC_KS_CASE(1)
-        ESC_KS_CASE(3)
-        ESC_KS_CASE(5)
-        ESC_KS_CASE(7)
-        ESC_KS_CASE(9)
-        ESC_KS_CASE(11)
-        ESC_KS_CASE(13)
-        ESC_KS_CASE(15)
-        ESC_KS_CASE(17)
-        ESC_KS_CASE(19)
-        ESC_KS_CASE(21)
-        ESC_KS_CASE(23)
-        ESC_KS_CASE(25)
-        ESC_KS_CASE(27)
-        ESC_KS_CASE(29)
-        ESC_KS_CASE(31)
-#undef ESC_KS_CASE
-    default: return ESC_ERR_UNSUPPORTED;
-    }
-}
-
-// fills the parts of FwdParams every entry point shares
-esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C, int H, int W, int Ca,
-                        const esc_gen_params *gen, void *workspace, const WsLayout &l)
-{
-    p = FwdParams{};
-    p.x = x;
-    p.N = N;
-    p.C = C;
-    p.Ca = Ca;
-    p.H = H;
-    p.W = W;
-    p.ptiles_x = l.ptiles_x;
-    p.ptiles = l.ptiles;
-    p.hw = (float)((double)H * (double)W);
-    p.elem_bytes = dt == ESC_F32 ? 4 : 2;
-    p.div_ptiles = make_div((uint32_t)l.ptiles);
-    p.div_ptiles_x = make_div((uint32_t)l.ptiles_x);
-    // aligned 4-element chunk loads (halo tile, pool tile) need W % 4 == 0 and an aligned base
-    p.conv_ld_vec = (W % 4 == 0) && ((uintptr_t)x % (4 * (size_t)p.elem_bytes) == 0);
-    p.div_ca = make_div((uint32_t)(Ca > 0 ? Ca : 1));
-    p.div_tiles_x = p.div_tiles_y = p.div_chunks = p.div_mix = p.div_mix_a = p.div_mix_b = make_div(1);
-    if (gen != nullptr && Ca > 0) {
-        p.dk_mode = ((size_t)Ca * l.ptiles <= (size_t)kDirectMaxBoxes) ? kDkDirect : kDkFromG;
-        p.pool_mode = kPoolItems;
-        p.hidden = gen->hidden;
-        p.w_down = gen->w_down;
-        p.b_down = gen->b_down;
-        p.w_up = gen->w_up;
-        p.b_up = gen->b_up;
-        const size_t n_pool = (size_t)N * Ca * l.ptiles;
-        if (n_pool >= ((size_t)1 << 30)) return ESC_ERR_UNSUPPORTED;
-        p.n_pool_tiles = (unsigned)n_pool;
-        p.n_pool = (unsigned)((n_pool + kPoolBatch - 1) / kPoolBatch);
-        // Larger planes: a gsum item per (image, channel), then a gen item per image that turns
-        // the means into DK; the conv items pick DK up as from any gen item.  These calls, and
-        // calls whose estimator is beyond the small ones that gen_item prefetches, run the
-        // kernel flavour with the staged estimator items.
-        const int K = gen->hidden > 0 ? gen->hidden : Ca;
-        const bool small_est = K <= 16 && Ca <= 16 && gen->hidden <= kThreads;
-        p.staged = p.dk_mode == kDkFromG || !small_est;
-        if (p.dk_mode == kDkFromG) {
-            p.n_gsum = (unsigned)((size_t)N * Ca);
-            p.n_gen = p.n_gsum + (unsigned)N;
-            p.dk_mode = kDkBoxes;
-        }
-    }
-    char *w = (char *)workspace;
-    p.err = (unsigned *)(w + l.ctl_off) + kCtlErrWord;
-    p.epoch = (unsigned *)(w + l.ctl_off) + kCtlEpochWord;
-    p.done = (unsigned *)(w + l.ctl_off) + kCtlDoneWord;
-    p.queue = (unsigned *)(w + l.ctl_off) + kCtlQueueWord;
-#ifdef ESC_TRACE
-    p.trace = g_trace;
-#endif
-    p.pool_box = (u64 *)(w + l.pool_off);
-    p.dk_box = (u64 *)(w + l.dk_off);
-    p.g_box = (u64 *)(w + l.g_off);
-    return ESC_OK;
-}
 
 }  // namespace
-
-extern "C" {
-
-size_t esc_workspace_bytes(int N, int C_a, int H, int W)
-{
-    WsLayout l;
-    if (!ws_layout(N, C_a, H, W, &l)) return 0;
-    return l.total;
-}
-
-esc_status esc_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
-{
-    esc_status st = check_ws(workspace, workspace_bytes, kWsAlign);
-    if (st != ESC_OK) return st;
-    const size_t words = workspace_bytes / 4;
-    const size_t blocks = (words + kThreads - 1) / kThreads;
-    if (blocks >= ((size_t)1 << 31)) return ESC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(ws_init_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
-                       (uint32_t *)workspace, words);
-    return hipGetLastError() == hipSuccess ? ESC_OK : ESC_ERR_HIP;
-}
-
-esc_status esc_workspace_errors(const void *workspace, size_t workspace_bytes, void *stream,
-                                unsigned *errors_out)
-{
-    if (errors_out == nullptr) return ESC_ERR_NULL;
-    esc_status st = check_ws(workspace, workspace_bytes, kWsAlign);
-    if (st != ESC_OK) return st;
-    unsigned v = 0;
-    if (hipMemcpyAsync(&v, (const uint32_t *)workspace + kCtlErrWord, sizeof v, hipMemcpyDeviceToHost,
-                       (hipStream_t)stream) != hipSuccess)
-        return ESC_ERR_HIP;
-    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ESC_ERR_HIP;
-    *errors_out = v;
-    return ESC_OK;
-}
-
-esc_status esc_dynkernel_gen(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
-                             const esc_gen_params *gen, float *dk_out, void *workspace,
-                             size_t workspace_bytes, void *stream)
-{
-    esc_status st = check_common(x, dt, N, C, H, W, C_a);
-    if (st != ESC_OK) return st;
-    if (gen == nullptr) return ESC_ERR_NULL;
-    if ((st = check_gen(gen, C_a)) != ESC_OK) return st;
-    if (C_a > 0 && dk_out == nullptr) return ESC_ERR_NULL;
-    WsLayout l;
-    if (!ws_layout(N, C_a, H, W, &l)) return ESC_ERR_SHAPE;
-    if ((st = check_ws(workspace, workspace_bytes, l.total)) != ESC_OK) return st;
-    if (C_a == 0) return ESC_OK;
-    FwdParams p;
-    if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
-    p.dk_out = dk_out;
-    p.dk_mode = kDkBoxes;  // no conv items here: gen items write dk_out, each from its image's pool sums
-    p.n_gen = (unsigned)N;
-    p.n_gsum = 0;
-    return dt == ESC_F32 ? launch_typed<float>(p, 0, (hipStream_t)stream)
-                         : launch_typed<bf16_t>(p, 0, (hipStream_t)stream);
-}
-
-esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
-                                const float *lk, int Ks, long lk_channel_stride,
-                                const esc_gen_params *gen, const float *dk_in, void *out,
-                                void *workspace, size_t workspace_bytes, void *stream)
-{
-    esc_status st = check_common(x, dt, N, C, H, W, C_a);
-    if (st != ESC_OK) return st;
-    if (out == nullptr) return ESC_ERR_NULL;
-    if (Ks < 1 || (Ks % 2) == 0) return Ks < 1 ? ESC_ERR_SHAPE : ESC_ERR_UNSUPPORTED;
-    if (Ks > kMaxKs) return ESC_ERR_UNSUPPORTED;
-    if (C_a > 0 && lk == nullptr) return ESC_ERR_NULL;
-    if (lk_channel_stride != 0 && lk_channel_stride < (long)Ks * Ks) return ESC_ERR_SHAPE;
-    if (gen != nullptr && (st = check_gen(gen, C_a)) != ESC_OK) return st;
-    const size_t es = dt == ESC_F32 ? 4 : 2;
-    if (((uintptr_t)out % es) != 0) return ESC_ERR_SHAPE;
-    const size_t bytes = (size_t)N * C * H * W * es;
-    const uintptr_t xa = (uintptr_t)x, oa = (uintptr_t)out;
-    if (xa < oa + bytes && oa < xa + bytes) return ESC_ERR_ALIAS;
-    WsLayout l;
-    if (!ws_layout(N, C_a, H, W, &l)) return ESC_ERR_SHAPE;
-    if ((st = check_ws(workspace, workspace_bytes, l.total)) != ESC_OK) return st;
-
-    FwdParams p;
-    if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
-    p.out = out;
-    p.lk = lk;
-    p.lk_cstride = lk_channel_stride;
-    p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
-    if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
-    // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
-    p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
-    if (C_a < C) {
-        const size_t plane = (size_t)H * W * es;
-        p.img_bytes = plane * C;
-        p.idt_off = plane * C_a;
-        p.idt_len = plane * (C - C_a);
-        p.copy_vec_ok = (xa % 16 == 0) && (oa % 16 == 0) && (p.img_bytes % 16 == 0) && (p.idt_off % 16 == 0);
-    }
-    const int ks_variant = C_a > 0 ? Ks : 0;
-    return dt == ESC_F32 ? launch_typed<float>(p, ks_variant, (hipStream_t)stream)
-                         : launch_typed<bf16_t>(p, ks_variant, (hipStream_t)stream);
-}
-
-#ifdef ESC_TRACE
-void esc_debug_set_trace(void *buf) { g_trace = (u64 *)buf; }
-#endif
-
-const char *esc_status_string(esc_status s)
-{
-    switch (s) {
-    case ESC_OK: return "ok";
-    case ESC_ERR_NULL: return "a required pointer is NULL";
-    case ESC_ERR_SHAPE: return "a size or stride is out of its domain";
-    case ESC_ERR_DTYPE: return "unknown storage type";
-    case ESC_ERR_UNSUPPORTED: return "outside the library's limits (Ks odd <= 31, C_a <= 256, hidden <= 256)";
-    case ESC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
-    case ESC_ERR_ALIAS: return "out overlaps x";
-    case ESC_ERR_HIP: return "the HIP runtime refused a launch";
-    }
-    return "unknown status";
-}
-
-}  // extern "C"
+}  // namespace esc

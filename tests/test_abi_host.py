@@ -117,43 +117,66 @@ def test_binding_refuses_cpu_tensors(lib):
 # ---------------------------------------------------------------- compiled kernel variants
 
 def kernel_metadata():
-    """(Ks, RY, type letter) -> (private segment bytes, VGPRs) of every forward_kernel
-    variant in the built library, read from the code object's notes."""
+    """(Ks, RY, type letter, staged flavour) -> (private segment bytes, VGPRs, static LDS bytes)
+    of every forward_kernel variant in the built library, read from the code objects' notes.
+    The library holds one offload bundle per translation unit."""
     import subprocess
     import tempfile
     tools = "/opt/rocm/llvm/bin"
     need = [os.path.join(tools, t) for t in ("llvm-objcopy", "clang-offload-bundler", "llvm-readelf")]
     if not all(os.path.exists(t) for t in need):
         pytest.skip("LLVM binary tools not found")
+    magic = b"__CLANG_OFFLOAD_BUNDLE__"
+    out = {}
     with tempfile.TemporaryDirectory() as tmp:
-        fat, dev = os.path.join(tmp, "fat.bin"), os.path.join(tmp, "dev.co")
+        fat = os.path.join(tmp, "fat.bin")
         subprocess.run([need[0], f"--dump-section=.hip_fatbin={fat}", binding.LIB_PATH, os.path.join(tmp, "copy.so")],
                        check=True)
-        subprocess.run([need[1], "--unbundle", "--type=o", f"--input={fat}",
-                        "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={dev}"], check=True)
-        notes = subprocess.run([need[2], "--notes", dev], check=True, capture_output=True, text=True).stdout
-    out = {}
-    for block in notes.split(".name:")[1:]:
-        name = block.split()[0]
-        m = re.search(r"forward_kernelILi(\d+)ELi(\d+)E(\w)", name)
-        if not m:
-            continue
-        scratch = int(re.search(r"\.private_segment_fixed_size:\s*(\d+)", block).group(1))
-        vgprs = int(re.search(r"\.vgpr_count:\s*(\d+)", block).group(1))
-        out[(int(m.group(1)), int(m.group(2)), m.group(3))] = (scratch, vgprs)
+        data = open(fat, "rb").read()
+        starts = []
+        i = data.find(magic)
+        while i >= 0:
+            starts.append(i)
+            i = data.find(magic, i + 1)
+        for k, s in enumerate(starts):
+            one, dev = os.path.join(tmp, f"b{k}.bin"), os.path.join(tmp, f"d{k}.co")
+            open(one, "wb").write(data[s:starts[k + 1] if k + 1 < len(starts) else len(data)])
+            subprocess.run([need[1], "--unbundle", "--type=o", f"--input={one}",
+                            "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={dev}"], check=True)
+            notes = subprocess.run([need[2], "--notes", dev], check=True, capture_output=True, text=True).stdout
+            for block in notes.split("- .agpr_count:")[1:]:
+                name = re.search(r"\.name:\s*(\S+)", block).group(1)
+                m = re.search(r"forward_kernelILi(\d+)ELi(\d+)E(\w+?)Lb([01])E", name)
+                if not m:
+                    continue
+                scratch = int(re.search(r"\.private_segment_fixed_size:\s*(\d+)", block).group(1))
+                vgprs = int(re.search(r"\.vgpr_count:\s*(\d+)", block).group(1))
+                lds = int(re.search(r"\.group_segment_fixed_size:\s*(\d+)", block).group(1))
+                key = (int(m.group(1)), int(m.group(2)), "f" if m.group(3) == "f" else "b", int(m.group(4)))
+                assert key not in out, key
+                out[key] = (scratch, vgprs, lds)
     return out
 
 
+# (Ks, RY) pairs the library is built with: both register blockings up to Ks = 17, the
+# two-row one beyond, and Ks = 0 for the variant without conv items
+VARIANT_SHAPES = [(0, 2)] + [(ks, ry) for ks in range(1, 32, 2) for ry in ((2, 4) if ks <= 17 else (2,))]
+LDS_PER_CU = 160 * 1024
+
+
 def test_kernel_variants_fit_four_blocks_per_cu_without_scratch(lib):
-    # Four resident blocks per compute unit is what the grid is sized for (<= 128 VGPRs),
-    # and any private-segment use costs every launch a fixed microsecond or more: the
-    # variants short calls can use (Ks <= 13, both register blockings; two-row blocks up
-    # to Ks = 15) must have none, the others next to none.
+    # Four resident blocks per compute unit is what the grid is sized for: <= 128 VGPRs and a
+    # quarter of the compute unit's LDS per block.  Any private-segment use costs every launch
+    # a fixed microsecond or more: the flavour short calls use (unstaged estimator; Ks <= 13,
+    # both register blockings; two-row blocks up to Ks = 15) must have none, the others next
+    # to none.  Both storage types and both estimator flavours of every variant are checked.
     meta = kernel_metadata()
-    assert len(meta) >= 2 * 26, "every (Ks, RY, type) variant should be in the library"
-    for (ks, ry, t), (scratch, vgprs) in sorted(meta.items()):
-        assert vgprs <= 128, (ks, ry, t, vgprs)
-        if ks <= 13 or (ks <= 15 and ry == 2):
-            assert scratch == 0, (ks, ry, t, scratch)
+    want = {(ks, ry, t, st) for ks, ry in VARIANT_SHAPES for t in "fb" for st in (0, 1)}
+    assert set(meta) == want, sorted(want ^ set(meta))
+    for (ks, ry, t, st), (scratch, vgprs, lds) in sorted(meta.items()):
+        assert vgprs <= 128, (ks, ry, t, st, vgprs)
+        assert 4 * lds <= LDS_PER_CU, (ks, ry, t, st, lds)
+        if st == 0 and (ks <= 13 or (ks <= 15 and ry == 2)):
+            assert scratch == 0, (ks, ry, t, st, scratch)
         else:
-            assert scratch <= 64, (ks, ry, t, scratch)
+            assert scratch <= 64, (ks, ry, t, st, scratch)

@@ -37,8 +37,10 @@ def test_every_kernel_size_ragged_multi_tile(oracle, Ks):
     check_forward(wl, oracle)
 
 
-@pytest.mark.parametrize("Ks", [3, 7, 13, 17, 31])
+@pytest.mark.parametrize("Ks", list(range(1, 32, 2)))
 def test_bf16_storage_ragged_multi_tile(oracle, Ks):
+    # every kernel size with bf16 storage: the packed two-taps-per-instruction path up to
+    # Ks = 17 (its alignment constants depend on Ks), the widened path beyond
     wl = wk.make_random(300 + Ks, 2, 5, 45, 136, 4, Ks, dtype=BF16, x_mean=0.5)
     check_forward(wl, oracle)
 
@@ -72,12 +74,62 @@ def test_no_attention_channels_is_a_pure_copy(oracle):
     assert np.array_equal(out.view(np.uint8), wl.x.view(np.uint8))
 
 
-def test_tall_register_block_variant_ragged(oracle):
-    # enough tiles that the library picks the 4-row register block; ragged in H and W
-    wl = wk.make_random(8, 40, 17, 70, 150, 16, 13, dtype=F32, x_mean=0.5)
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("Ks", list(range(1, 18, 2)))
+def test_tall_register_block_variant_ragged(oracle, Ks, dtype):
+    # 6 x 16 planes of 3 x 2 tall tiles = 576 tiles >= two per compute unit: the library picks
+    # the 4-row register block (64 x 64 tiles) by shape; ragged in H and W
+    wl = wk.make_random(800 + Ks, 6, 17, 70, 150, 16, Ks, dtype=dtype, x_mean=0.5)
     check_forward(wl, oracle)
-    wl = wk.make_random(9, 40, 17, 70, 150, 16, 7, dtype=BF16, x_mean=0.5)
-    check_forward(wl, oracle)
+
+
+@pytest.mark.parametrize("dtype,Ks,N", [(F32, 13, 2), (BF16, 13, 2), (BF16, 31, 2), (F32, 5, 40), (BF16, 7, 40)])
+def test_base_pointers_off_the_vector_alignment(oracle, dtype, Ks, N):
+    # W % 4 == 0, but x and out start one element past a 16-byte boundary (views into larger
+    # buffers): the tile loads, the row stores and the pass-through copy must all take their
+    # element-wise forms.  N = 40 reaches the 4-row register block and the queue-dealt deal.
+    wl = wk.make_random(820 + Ks, N, 7, 40, 72, 4, Ks, dtype=dtype, x_mean=0.4)
+    print(f"[case] unaligned base, {wl.name}", flush=True)
+    ref_att, _, _ = oracle.forward_workload(wl, want_out=False)
+    x_al = gu.to_dev_x(wl.x, wl.dtype)
+    numel = x_al.numel()
+    for x_shift, out_shift in ((1, 1), (1, 0), (0, 3)):
+        xb = torch.zeros(numel + 8, dtype=x_al.dtype, device="cuda")
+        ob = torch.full((numel + 8,), float("nan"), dtype=x_al.dtype, device="cuda")
+        x = xb[x_shift:x_shift + numel].view(x_al.shape)
+        x.copy_(x_al)
+        out = ob[out_shift:out_shift + numel].view(x_al.shape)
+        assert x.data_ptr() % 16 == (x_shift * x.element_size()) % 16
+        ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
+        binding.convattn_forward(x, wl.Ca, gu.dev(wl.lk), ws, gen=gu.gen_params(wl), out=out)
+        assert binding.workspace_errors(ws) == 0
+        got = gu.out_to_np(out, wl.dtype)
+        gu.assert_identity_bits(got, wl, "unaligned base")
+        gu.assert_att_close(gu.att_as_f64(got, wl), ref_att, wl.dtype, "unaligned base")
+        # nothing outside the view was written
+        edge = ob.view(torch.int16 if dtype == BF16 else torch.int32)
+        nan_bits = torch.full((1,), float("nan"), dtype=x_al.dtype).view(edge.dtype).item()
+        assert all(int(v) == nan_bits for v in edge[:out_shift].tolist() + edge[out_shift + numel:].tolist())
+
+
+@pytest.mark.parametrize("dtype,Ks", [(F32, 13), (BF16, 13), (F32, 3), (BF16, 31)])
+def test_large_kernel_channel_stride_wider_than_the_kernel(oracle, dtype, Ks):
+    # channel c's filter starts at lk + c * (Ks*Ks + 3): the gaps are filled with NaN and must
+    # never be read into the result
+    wl = wk.make_random(840 + Ks, 2, 6, 40, 72, 4, Ks, dtype=dtype, x_mean=0.3)
+    ref_att, _, _ = oracle.forward_workload(wl, want_out=False)
+    stride = Ks * Ks + 3
+    flat = np.full((wl.Ca, stride), np.nan, np.float32)
+    flat[:, :Ks * Ks] = wl.lk.reshape(wl.Ca, -1)
+    x = gu.to_dev_x(wl.x, wl.dtype)
+    out = torch.full_like(x, float("nan"))
+    ws = binding.new_workspace(wl.N, wl.Ca, wl.H, wl.W)
+    binding.convattn_forward(x, wl.Ca, gu.dev(flat), ws, gen=gu.gen_params(wl), out=out, ks=Ks,
+                             lk_channel_stride=stride)
+    assert binding.workspace_errors(ws) == 0
+    got = gu.out_to_np(out, wl.dtype)
+    gu.assert_identity_bits(got, wl, "wide channel stride")
+    gu.assert_att_close(gu.att_as_f64(got, wl), ref_att, wl.dtype, "wide channel stride")
 
 
 @pytest.mark.parametrize("Ca,hidden,bias,dtype", [(16, 8, False, F32), (16, 4, True, BF16), (48, 24, True, F32)])
@@ -274,6 +326,64 @@ def test_planted_non_finite_values_in_identity_channels(oracle, dtype):
     else:
         flat[0, 3, 0], flat[0, 4, 1], flat[1, 5, 2], flat[1, 2, 3] = 0x7FC1, 0xFF80, 0x0001, 0x7FA0
     check_forward(wl, oracle, "planted non-finite")
+
+
+@pytest.mark.parametrize("dtype,Ks", [(F32, 13), (F32, 31), (BF16, 21), (BF16, 13), (BF16, 5), (BF16, 17)])
+def test_non_finite_pixels_in_the_attention_slice(oracle, dtype, Ks):
+    # Where do NaN/Inf pixels of the attention slice show in the output?  The definition
+    # (and the oracle): at every output whose Ks x Ks window (or DK's 3 x 3) covers the pixel.
+    # fp32 storage, and bf16 storage with Ks >= 19, must give exactly that footprint.  The
+    # packed bf16 path (Ks <= 17) applies two taps per instruction, one of them possibly a
+    # zero weight on the pixel one column beyond the window: there the footprint may be wider
+    # by one column on either side, and no more.  Everything else stays within the usual bar.
+    wl = wk.make_random(860 + Ks, 2, 5, 50, 150, 3, Ks, dtype=dtype)
+    rng = np.random.default_rng(861)
+    dk = rng.standard_normal((2, 3, 3, 3)).astype(np.float32)
+    spots = [(0, 0, 0, 0, "inf"), (0, 1, 25, 70, "nan"), (1, 2, 49, 149, "-inf"), (1, 0, 13, 64, "nan"),
+             (0, 2, 31, 127, "inf")]
+    xf = wl.x_as_f32().copy()
+    for n, c, y, x_, kind in spots:
+        xf[n, c, y, x_] = {"inf": np.inf, "-inf": -np.inf, "nan": np.nan}[kind]
+    wl.x = wk.f32_to_bf16_bits(xf) if dtype == BF16 else xf
+    with np.errstate(invalid="ignore"):
+        ref_att, _, _ = oracle.convattn_forward(wl.x, wl.Ca, wl.lk, wl.dtype, dk_in=dk, want_out=False)
+    out = gu.run_forward(wl, use_gen=False, dk_in=dk)
+    gu.assert_identity_bits(out, wl, "non-finite attention pixels")
+    got = gu.att_as_f64(out, wl)
+    bad_ref, bad_got = ~np.isfinite(ref_att), ~np.isfinite(got)
+    p = (Ks - 1) // 2
+    assert bad_ref.sum() >= len(spots) * (p + 1) ** 2
+    packed = dtype == BF16 and Ks <= 17
+    if packed:
+        wider = bad_ref.copy()
+        wider[..., 1:] |= bad_ref[..., :-1]
+        wider[..., :-1] |= bad_ref[..., 1:]
+        assert not (bad_ref & ~bad_got).any(), "a non-finite result of the definition came out finite"
+        assert not (bad_got & ~wider).any(), "NaN beyond one column past the kernel's reach"
+    else:
+        assert np.array_equal(bad_ref, bad_got), "NaN/Inf footprint differs from the definition's"
+    ok = ~bad_got
+    tol = gu.TOL[dtype]
+    fin = ref_att[~bad_ref]
+    scale, rms = np.abs(fin).max(), float(np.sqrt(np.mean(fin ** 2)))
+    d = np.abs(got[ok] - ref_att[ok])
+    assert d.max() <= tol * scale
+    assert (d <= tol * (np.abs(ref_att[ok]) + rms)).all()
+
+
+def test_bf16_large_kernel_weight_rounding_error_bound(oracle):
+    # With bf16 storage and Ks <= 17 the fp32 large-kernel weights are rounded to bf16 on
+    # the device (two taps per dot instruction).  Bound asserted here: the normwise error
+    # against the float64 oracle stays below 6e-3 at Ks = 13 (the store's own rounding to
+    # bf16 alone is 2^-9 ~ 2e-3 relative per value; weights add an independent 2^-9 per tap),
+    # far inside the 2e-2 bar; with weights that are exactly representable in bf16 the
+    # error is that of the store rounding alone.
+    wl = wk.make_random(880, 2, 5, 96, 160, 4, 13, dtype=BF16, x_mean=0.0)
+    rel = check_forward(wl, oracle, "bf16, fp32 weights")
+    wl.lk = wk.bf16_bits_to_f32(wk.f32_to_bf16_bits(wl.lk))
+    rel_exact = check_forward(wl, oracle, "bf16, bf16-exact weights")
+    print(f"[bound] normwise error: fp32 weights {rel:.3e}, bf16-exact weights {rel_exact:.3e}", flush=True)
+    assert rel <= 6e-3 and rel_exact <= 4.5e-3
 
 
 def test_linearity_with_dk_fixed():
