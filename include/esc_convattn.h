@@ -129,6 +129,24 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
                                 const esc_gen_params *gen, const float *dk_in,
                                 void *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * For callers that cannot allocate or prepare device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): esc_convattn_forward
+ * without the workspace arguments.  The mailboxes and counters live in a scratch array
+ * inside the library, ESC_NOALLOC_SCRATCH_BYTES per device, which needs no
+ * esc_workspace_init.  The call allocates nothing and computes exactly what
+ * esc_convattn_forward computes, bit for bit.  Shapes whose esc_workspace_bytes exceeds
+ * ESC_NOALLOC_SCRATCH_BYTES are refused with ESC_ERR_WORKSPACE (all arguments are checked
+ * as in esc_convattn_forward, before anything is enqueued).  Every call on a device uses
+ * that device's one array, which carries state from call to call: calls that overlap on
+ * one device (different streams, different threads) race; order them.
+ */
+#define ESC_NOALLOC_SCRATCH_BYTES (1u << 20)
+esc_status esc_convattn_forward_noalloc(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                        const float *lk, int Ks, long lk_channel_stride,
+                                        const esc_gen_params *gen, const float *dk_in,
+                                        void *out, void *stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *esc_status_string(esc_status s);
 

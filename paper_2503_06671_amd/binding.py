@@ -19,7 +19,8 @@ ESC_F32 = 0
 ESC_BF16 = 1
 
 EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_workspace_errors", "esc_dynkernel_gen",
-           "esc_convattn_forward", "esc_status_string")
+           "esc_convattn_forward", "esc_convattn_forward_noalloc", "esc_status_string")
+NOALLOC_SCRATCH_BYTES = 1 << 20
 
 
 class EscError(RuntimeError):
@@ -59,6 +60,9 @@ def load_library():
         lib.esc_convattn_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, cl,
                                              ctypes.POINTER(_GenParams), vp, vp, vp, sz, vp]
         lib.esc_convattn_forward.restype = ci
+        lib.esc_convattn_forward_noalloc.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, cl,
+                                                     ctypes.POINTER(_GenParams), vp, vp, vp]
+        lib.esc_convattn_forward_noalloc.restype = ci
         lib.esc_status_string.argtypes = [ci]
         lib.esc_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -193,12 +197,13 @@ def _lk_checked(lk: torch.Tensor, Ca: int, ks: Optional[int], lk_channel_stride:
     raise ValueError(f"lk must be [Ca,Ks,Ks] with Ca = {Ca}, or [Ks,Ks]; got {tuple(lk.shape)}")
 
 
-def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, workspace: torch.Tensor,
+def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, workspace: Optional[torch.Tensor],
                      gen: Optional[GenParams] = None, dk_in: Optional[torch.Tensor] = None,
                      out: Optional[torch.Tensor] = None, stream=None, ks: Optional[int] = None,
                      lk_channel_stride: Optional[int] = None) -> torch.Tensor:
-    """esc_convattn_forward.  lk is [Ca,Ks,Ks] (one filter per channel) or [Ks,Ks] (shared);
-    with ks and lk_channel_stride given it is a flat buffer with channel c at c * stride."""
+    """esc_convattn_forward (workspace given) or esc_convattn_forward_noalloc (workspace None).
+    lk is [Ca,Ks,Ks] (one filter per channel) or [Ks,Ks] (shared); with ks and
+    lk_channel_stride given it is a flat buffer with channel c at c * stride."""
     dt, (N, C, H, W) = _x_checked(x)
     Ks, stride = _lk_checked(lk, int(Ca), ks, lk_channel_stride)
     if gen is not None:
@@ -210,9 +215,14 @@ def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, workspace: torc
     _dev_f32(dk_in, "dk_in")
     if dk_in is not None and dk_in.numel() != N * Ca * 9:
         raise ValueError("dk_in must hold [N, Ca, 3, 3] values")
+    gen_ref = ctypes.byref(gen.c) if gen is not None else None
+    if workspace is None:  # the entry point that allocates nothing: the library's own scratch
+        _check(load_library().esc_convattn_forward_noalloc(
+            _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk), Ks, stride, gen_ref, _ptr(dk_in), _ptr(out),
+            _stream(stream)))
+        return out
     ws_ptr, ws_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
     _check(load_library().esc_convattn_forward(
-        _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk), Ks, stride,
-        ctypes.byref(gen.c) if gen is not None else None, _ptr(dk_in), _ptr(out),
+        _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk), Ks, stride, gen_ref, _ptr(dk_in), _ptr(out),
         ws_ptr, ws_bytes, _stream(stream)))
     return out

@@ -358,6 +358,95 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
     return ESC_OK;
 }
 
+// The mailboxes and counters of esc_convattn_forward_noalloc: one copy per device, in the
+// code object's data segment, so that a call needs no allocation and no preparation.  It is
+// laid out like a caller's workspace and starts out as esc_workspace_init would leave it
+// (everything zero, the groups' call counters 1), by constant initialisation.
+struct Scratch {
+    uint32_t words[ESC_NOALLOC_SCRATCH_BYTES / sizeof(uint32_t)];
+    constexpr Scratch() : words{}
+    {
+        for (size_t g = 0; g < (size_t)kGroups; ++g) words[kCtlEpochWord + g * kCtlStride] = 1u;
+    }
+};
+static __device__ __align__(256) Scratch scratch;
+
+// Device address of this device's copy of `scratch` (the name is a host-side stand-in, not
+// an address a kernel could use): asked once per device, with that device current.
+esc_status scratch_address(void **out_ptr)
+{
+    constexpr int kMaxDev = 64;
+    static void *ptrs[kMaxDev];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return ESC_ERR_HIP;
+    if (ptrs[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return ESC_ERR_HIP;
+        ptrs[dev] = ptr;
+    }
+    *out_ptr = ptrs[dev];
+    return ESC_OK;
+}
+
+// esc_convattn_forward and esc_convattn_forward_noalloc: the same checks, plan and kernel;
+// they differ in where the workspace lives.
+esc_status forward_impl(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a, const float *lk, int Ks,
+                        long lk_channel_stride, const esc_gen_params *gen, const float *dk_in, void *out,
+                        void *workspace, size_t workspace_bytes, bool own_scratch, void *stream)
+{
+    esc_status st = check_common(x, dt, N, C, H, W, C_a);
+    if (st != ESC_OK) return st;
+    if (out == nullptr) return ESC_ERR_NULL;
+    if (Ks < 1 || (Ks % 2) == 0) return Ks < 1 ? ESC_ERR_SHAPE : ESC_ERR_UNSUPPORTED;
+    if (Ks > kMaxKs) return ESC_ERR_UNSUPPORTED;
+    if (C_a > 0 && lk == nullptr) return ESC_ERR_NULL;
+    if (lk_channel_stride != 0 && lk_channel_stride < (long)Ks * Ks) return ESC_ERR_SHAPE;
+    if (gen != nullptr && (st = check_gen(gen, C_a)) != ESC_OK) return st;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    if (((uintptr_t)out % es) != 0) return ESC_ERR_SHAPE;
+    const size_t bytes = (size_t)N * C * H * W * es;
+    const uintptr_t xa = (uintptr_t)x, oa = (uintptr_t)out;
+    if (overlaps(x, bytes, out, bytes)) return ESC_ERR_ALIAS;
+    WsLayout l;
+    if (!ws_layout(N, C_a, H, W, &l)) return ESC_ERR_SHAPE;
+    if (own_scratch) {
+        // the built-in scratch has a fixed size: larger shapes need a caller's workspace
+        if (l.total > sizeof(Scratch)) return ESC_ERR_WORKSPACE;
+        if ((st = scratch_address(&workspace)) != ESC_OK) return st;
+        workspace_bytes = sizeof(Scratch);
+    }
+    if ((st = check_ws(workspace, workspace_bytes, l.total)) != ESC_OK) return st;
+    if (overlaps(workspace, workspace_bytes, out, bytes) || overlaps(workspace, workspace_bytes, x, bytes))
+        return ESC_ERR_ALIAS;
+    if (C_a > 0) {
+        const size_t lk_bytes = ((size_t)(lk_channel_stride != 0 ? C_a - 1 : 0) * (size_t)lk_channel_stride +
+                                 (size_t)Ks * Ks) * sizeof(float);
+        if (overlaps(lk, lk_bytes, out, bytes)) return ESC_ERR_ALIAS;
+        if (gen == nullptr && dk_in != nullptr && overlaps(dk_in, (size_t)N * C_a * 9 * sizeof(float), out, bytes))
+            return ESC_ERR_ALIAS;
+    }
+
+    FwdParams p;
+    if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
+    p.out = out;
+    p.lk = lk;
+    p.lk_cstride = lk_channel_stride;
+    p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
+    if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
+    // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
+    p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
+    if (C_a < C) {
+        const size_t plane = (size_t)H * W * es;
+        p.img_bytes = plane * C;
+        p.idt_off = plane * C_a;
+        p.idt_len = plane * (C - C_a);
+        p.copy_vec_ok = (xa % 16 == 0) && (oa % 16 == 0) && (p.img_bytes % 16 == 0) && (p.idt_off % 16 == 0);
+    }
+    const int ks_variant = C_a > 0 ? Ks : 0;
+    return launch_forward(p, ks_variant, dt == ESC_BF16, (hipStream_t)stream);
+}
+
+
 }  // namespace
 
 extern "C" {
@@ -430,50 +519,16 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
                                 const esc_gen_params *gen, const float *dk_in, void *out,
                                 void *workspace, size_t workspace_bytes, void *stream)
 {
-    esc_status st = check_common(x, dt, N, C, H, W, C_a);
-    if (st != ESC_OK) return st;
-    if (out == nullptr) return ESC_ERR_NULL;
-    if (Ks < 1 || (Ks % 2) == 0) return Ks < 1 ? ESC_ERR_SHAPE : ESC_ERR_UNSUPPORTED;
-    if (Ks > kMaxKs) return ESC_ERR_UNSUPPORTED;
-    if (C_a > 0 && lk == nullptr) return ESC_ERR_NULL;
-    if (lk_channel_stride != 0 && lk_channel_stride < (long)Ks * Ks) return ESC_ERR_SHAPE;
-    if (gen != nullptr && (st = check_gen(gen, C_a)) != ESC_OK) return st;
-    const size_t es = dt == ESC_F32 ? 4 : 2;
-    if (((uintptr_t)out % es) != 0) return ESC_ERR_SHAPE;
-    const size_t bytes = (size_t)N * C * H * W * es;
-    const uintptr_t xa = (uintptr_t)x, oa = (uintptr_t)out;
-    if (overlaps(x, bytes, out, bytes)) return ESC_ERR_ALIAS;
-    WsLayout l;
-    if (!ws_layout(N, C_a, H, W, &l)) return ESC_ERR_SHAPE;
-    if ((st = check_ws(workspace, workspace_bytes, l.total)) != ESC_OK) return st;
-    if (overlaps(workspace, workspace_bytes, out, bytes) || overlaps(workspace, workspace_bytes, x, bytes))
-        return ESC_ERR_ALIAS;
-    if (C_a > 0) {
-        const size_t lk_bytes = ((size_t)(lk_channel_stride != 0 ? C_a - 1 : 0) * (size_t)lk_channel_stride +
-                                 (size_t)Ks * Ks) * sizeof(float);
-        if (overlaps(lk, lk_bytes, out, bytes)) return ESC_ERR_ALIAS;
-        if (gen == nullptr && dk_in != nullptr && overlaps(dk_in, (size_t)N * C_a * 9 * sizeof(float), out, bytes))
-            return ESC_ERR_ALIAS;
-    }
+    return forward_impl(x, dt, N, C, H, W, C_a, lk, Ks, lk_channel_stride, gen, dk_in, out, workspace,
+                        workspace_bytes, false, stream);
+}
 
-    FwdParams p;
-    if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
-    p.out = out;
-    p.lk = lk;
-    p.lk_cstride = lk_channel_stride;
-    p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
-    if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
-    // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
-    p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
-    if (C_a < C) {
-        const size_t plane = (size_t)H * W * es;
-        p.img_bytes = plane * C;
-        p.idt_off = plane * C_a;
-        p.idt_len = plane * (C - C_a);
-        p.copy_vec_ok = (xa % 16 == 0) && (oa % 16 == 0) && (p.img_bytes % 16 == 0) && (p.idt_off % 16 == 0);
-    }
-    const int ks_variant = C_a > 0 ? Ks : 0;
-    return launch_forward(p, ks_variant, dt == ESC_BF16, (hipStream_t)stream);
+esc_status esc_convattn_forward_noalloc(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                        const float *lk, int Ks, long lk_channel_stride,
+                                        const esc_gen_params *gen, const float *dk_in, void *out, void *stream)
+{
+    return forward_impl(x, dt, N, C, H, W, C_a, lk, Ks, lk_channel_stride, gen, dk_in, out, nullptr, 0, true,
+                        stream);
 }
 
 
@@ -485,7 +540,7 @@ const char *esc_status_string(esc_status s)
     case ESC_ERR_SHAPE: return "a size or stride is out of its domain";
     case ESC_ERR_DTYPE: return "unknown storage type";
     case ESC_ERR_UNSUPPORTED: return "outside the library's limits (Ks odd <= 31, C_a <= 256, hidden <= 256)";
-    case ESC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ESC_ERR_WORKSPACE: return "workspace missing, misaligned or too small (esc_convattn_forward_noalloc: shape beyond the built-in scratch)";
     case ESC_ERR_ALIAS: return "out overlaps x, the workspace, lk or dk";
     case ESC_ERR_HIP: return "the HIP runtime refused a launch";
     }

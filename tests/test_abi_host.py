@@ -107,6 +107,22 @@ def test_dynkernel_gen_rejects_bad_arguments_before_launch(lib):
     assert lib.esc_workspace_init(0x1001, 1024, None) == E_WS
 
 
+def test_noalloc_entry_point_validates_before_anything_else(lib):
+    def na(x=0x10000, dt=0, N=1, C=64, H=8, W=8, Ca=16, lk=0x20000, Ks=13, stride=169, gen=None, dk=None,
+           out=0x90000):
+        return lib.esc_convattn_forward_noalloc(x, dt, N, C, H, W, Ca, lk, Ks, stride, gen, dk, out, None)
+    assert na(x=None) == E_NULL
+    assert na(out=None) == E_NULL
+    assert na(Ks=12) == E_UNSUP
+    assert na(N=0) == E_SHAPE
+    assert na(out=0x10000) == E_ALIAS
+    # a shape whose mailboxes do not fit the built-in scratch is refused as a workspace error
+    assert lib.esc_workspace_bytes(4096, 64, 8, 8) > binding.NOALLOC_SCRATCH_BYTES
+    assert na(N=4096, Ca=64, out=0x20000000) == E_WS
+    text = open(os.path.join(ROOT, "include", "esc_convattn.h")).read()
+    assert re.search(r"#define\s+ESC_NOALLOC_SCRATCH_BYTES\s+\(1u << 20\)", text)
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(1, 4, 8, 8)
