@@ -133,7 +133,7 @@ struct Plan {
     unsigned per_die;
 };
 
-Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu)
+Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_steps)
 {
     const unsigned U = (unsigned)device_cus() / kXcds;          // compute units per die
     const unsigned Smax = (unsigned)blocks_per_cu * (U ? U : 1);  // resident blocks per die
@@ -156,22 +156,9 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu)
         p.n_pool = 0;
     }
 
-    // rough time shares of the arithmetic and of the pass-through traffic decide how many
-    // copy items there are to a conv item (and with that how small they are): 1, 2 or 3,
-    // thresholds from sweeps at 540 x 960 with Ks = 7 ... 31
-    const double pix = (double)p.N * p.Ca * p.H * p.W;
-    const double t_valu = 2.0 * Ks * Ks * pix / 50e12;  // what a conv item sustains, its loads included
-    const double t_copy = 2.0 * (double)p.N * (double)p.idt_len / 4.5e12;
-    unsigned a = 1, b = 1;
-    if (t_valu > 0 && t_copy > 0) {
-        const double share = t_valu / (t_valu + t_copy);
-        if (share < 0.6) b = 2;
-        if (share < 0.3) b = 3;
-    }
-
-    // short calls (the conv items' own chain is most of them): gentle copying, if the blocks
-    // left over beside the conv items get through the pass-through range in about a dozen
-    // accesses per thread
+    // Short calls (the conv items' own chain of tile load, taps, estimator and store is most of
+    // them) copy gently: the blocks left over beside the resident conv items get through the
+    // pass-through range in about a dozen accesses per thread, one in flight at a time.
     {
         const u64 others0 = (u64)p.n_pool + p.n_gen + p.n_conv, resident0 = (u64)kXcds * Smax;
         const u64 spare = resident0 > others0 + kXcds * 4 ? resident0 - others0 - kXcds * 3 : 0;
@@ -179,11 +166,40 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu)
                         (u64)p.N * p.idt_len <= spare * 12 * (u64)kThreads * 16;
     }
 
+    // Carried copy, everywhere else: every conv item moves an equal share of its image's
+    // pass-through range from inside its tap loop, one 4 KiB grain per step, as far as the
+    // steps go; copy items are left with what lies beyond.
+    p.carry_g = 0;
+    p.copy_off = 0;
+    if (carry_steps > 0 && !p.copy_gentle && p.n_conv > 0 && p.idt_len > 0 && p.copy_vec_ok) {
+        const size_t per_img = p.n_conv / (size_t)p.N;
+        const size_t grains = (p.idt_len + kGrain - 1) / kGrain;
+        size_t g = (grains + per_img - 1) / per_img;
+        if (g > (size_t)carry_steps) g = (size_t)carry_steps;
+        p.carry_g = (unsigned)g;
+        const size_t carried = per_img * g * kGrain;
+        p.copy_off = carried < p.idt_len ? carried : p.idt_len;
+    }
+    const size_t rest_len = p.idt_len - p.copy_off;  // pass-through bytes per image left to copy items
+
+    // rough time shares of the arithmetic and of the pass-through traffic decide how many
+    // copy items there are to a conv item (and with that how small they are): 1, 2 or 3,
+    // thresholds from sweeps at 540 x 960 with Ks = 7 ... 31
+    const double pix = (double)p.N * p.Ca * p.H * p.W;
+    const double t_valu = 2.0 * Ks * Ks * pix / 50e12;  // what a conv item sustains, its loads included
+    const double t_copy = 2.0 * (double)p.N * (double)rest_len / 4.5e12;
+    unsigned a = 1, b = 1;
+    if (t_valu > 0 && t_copy > 0) {
+        const double share = t_valu / (t_valu + t_copy);
+        if (share < 0.6) b = 2;
+        if (share < 0.3) b = 3;
+    }
+
     // copy items: as many as the pattern pairs with the conv items; if the whole call fits
     // into one round of resident blocks, as many as still fit
     p.n_copy = 0;
     p.copy_chunk = kCopyPiece;
-    if (p.idt_len > 0) {
+    if (rest_len > 0) {
         u64 want = p.n_conv > 0 ? (u64)p.n_conv * b / a : (u64)kXcds * Smax * 4;
         const u64 others = (u64)p.n_pool + p.n_gen + p.n_conv;
         const u64 resident = (u64)kXcds * Smax;
@@ -198,9 +214,9 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu)
         if (want < 1) want = 1;
         u64 per_img = (want + p.N / 2) / p.N;
         if (per_img < 1) per_img = 1;
-        size_t chunk = (p.idt_len + per_img - 1) / per_img;
+        size_t chunk = (rest_len + per_img - 1) / per_img;
         chunk = (chunk + grain - 1) / grain * grain;
-        const size_t chunks = (p.idt_len + chunk - 1) / chunk;
+        const size_t chunks = (rest_len + chunk - 1) / chunk;
         p.copy_chunk = chunk;
         p.div_chunks = make_div((uint32_t)chunks);
         p.n_copy = (unsigned)(chunks * p.N);
@@ -295,7 +311,7 @@ esc_status launch_forward(FwdParams &p, int Ks, bool bf16, hipStream_t s)
     const int ks_slot = (Ks + 1) / 2;
     const int bpc = resident_blocks_per_cu(ks_slot, ry, bf16, p.staged != 0);
     if (bpc < 1) return ESC_ERR_UNSUPPORTED;
-    const Plan plan = plan_items(p, Ks, bpc);
+    const Plan plan = plan_items(p, Ks, bpc, Ks > 0 && conv_carries(Ks, ry, bf16) ? ry + Ks - 1 : 0);
     if ((u64)p.n_pool + p.n_gen + p.n_conv + p.n_copy >= ((u64)1 << 30)) return ESC_ERR_UNSUPPORTED;
     const unsigned grid = plan.per_die * kXcds;
     return kLaunch[ks_slot](ry, bf16, p.staged != 0, grid, s, p) == hipSuccess ? ESC_OK : ESC_ERR_HIP;

@@ -84,6 +84,7 @@ constexpr unsigned kSpinLimit = 1u << 20;  // bounded wait: about a second, far 
 constexpr int kBlocksPerCu = 4;    // resident blocks per compute unit the kernel is compiled for (<= 128 VGPRs)
 constexpr int kCopyVecPerThread = 4;
 constexpr size_t kCopyPiece = (size_t)kThreads * 16 * kCopyVecPerThread;  // bytes a block has in flight
+constexpr size_t kGrain = (size_t)kThreads * 16;  // bytes a conv item moves per step of its tap loop (carried copy)
 constexpr int kStage = 1024;       // pool mailboxes staged in LDS per round (multiple of 64)
 constexpr int kPollThreads = 192;  // wavefronts 0-2 poll mailboxes; wavefront 3 carries the leave atomic
 constexpr int kStagePerThread = (kStage + kPollThreads - 1) / kPollThreads;
@@ -95,6 +96,20 @@ struct bf16_t {
 };
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
+// Which conv variants move a share of the pass-through copy from inside their tap loops
+// (carried copy): the four-row blocks with bf16 storage.  Their calls fill every block
+// slot with conv items whose tap loops are bound by the dot instruction's rate, so the
+// streaming finds idle memory pipes under the arithmetic and no block to run in beside it.
+// Measured, the other variants lose by it: short fp32 calls last as long as their chain of
+// tile load, taps, estimator and store, which extra traffic stretches, and long fp32 calls
+// already alternate conv and copy items.
+constexpr bool conv_carries(int ks, int ry, bool bf16) { return bf16 && ry == 4 && ks <= 17; }
+// grains a thread of such a variant has in flight: a step of the tap loop is far shorter
+// than a round trip to memory
+constexpr int conv_carry_depth(int ks, int ry, bool bf16) { return conv_carries(ks, ry, bf16) ? 3 : 0; }
+typedef __amdgpu_buffer_rsrc_t CarryRsrc;
+constexpr int kRawBufferFlags = 0x00020000;  // raw buffer (no stride, no swizzle), 32-bit data format
+constexpr int kBufferNt = 2;                 // non-temporal
 
 struct FastDiv {
     uint32_t d, mul, shift;
@@ -163,6 +178,12 @@ struct FwdParams {
     // mailboxes) come back quickly; measured, a full-rate copy beside them costs more than
     // it saves.
     int copy_gentle;
+    // Carried copy: conv item j of an image (j counts its tiles channel-major) moves bytes
+    // [j * carry_g * kGrain, (j + 1) * carry_g * kGrain) of the image's pass-through range
+    // from inside its tap loop, one grain per step; the copy items cover what lies beyond
+    // copy_off (bytes from the start of the range).  0 = nothing is carried.
+    unsigned carry_g;
+    size_t copy_off;
 };
 
 // The kernel's parameter block as the item functions see it: a pointer into the kernel
@@ -1270,13 +1291,65 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                 for (int q = 0; q < 4; ++q) a[q] = fmaf(w[j], v[j + q], a[q]);
         }
     };
-    // what may move across a step boundary: arithmetic and global memory, not LDS traffic
-    constexpr int kSchedNoLds = 0x1 | 0x2 | 0x4 | 0x10 | 0x20 | 0x40;
-    constexpr bool kTwoX = 2 * NX + RY * NWT + 4 * RY <= 96;  // room for a second tile-row buffer
+    // what may move across a step boundary: arithmetic only - not LDS traffic, and not the
+    // carried copy's loads and stores, each of which belongs to its step
+    constexpr int kSchedNoLds = 0x1 | 0x2 | 0x4;
+
+    // Carried copy (Eq. 4 lines 1 and 4): this item's share of the image's pass-through range
+    // moves from inside the tap loop - step r loads grain r (16 bytes per thread) and stores
+    // grain r - 1 - so the streaming runs under the arithmetic on the same compute unit, with
+    // no block of its own.  Buffer accesses: the resources' sizes end the share, so grains
+    // beyond it read as nothing and their stores are dropped, without a branch in the loop.
+    constexpr bool kCarry = conv_carries(KS, RY, std::is_same<T, bf16_t>::value);
+    constexpr int kCarrySteps = G::ROWS;
+    CarryRsrc carry_src, carry_dst;
+    if constexpr (!kCarry) {
+        carry_src = carry_dst = __builtin_amdgcn_make_buffer_rsrc(nullptr, 0, 0, kRawBufferFlags);  // unused
+    } else {
+        const unsigned per_plane = p->div_tiles_x.d * p->div_tiles_y.d;
+        const size_t j = (size_t)c * per_plane + (size_t)tyi * p->div_tiles_x.d + (size_t)txi;
+        const size_t share = (size_t)p->carry_g * kGrain;
+        const size_t begin = j * share;
+        const size_t lim = p->copy_off;  // what the conv items carry ends here
+        const size_t len = begin < lim ? (lim - begin < share ? lim - begin : share) : 0;
+        const size_t base = (size_t)n * p->img_bytes + p->idt_off + begin;
+        carry_src = __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)p->x + base), 0, (int)len, kRawBufferFlags);
+        carry_dst = __builtin_amdgcn_make_buffer_rsrc((void *)((char *)p->out + base), 0, (int)len, kRawBufferFlags);
+    }
+    // kCarryDepth grains are in flight per thread (a grain's store follows its load that
+    // many steps later): one step is far shorter than a round trip to memory.
+    constexpr int kCarryDepth = kCarry ? conv_carry_depth(KS, RY, std::is_same<T, bf16_t>::value) : 1;
+    static_assert(kCarryDepth >= 1, "a carrying variant has at least one grain in flight");
+    u32x4 carry_v[kCarryDepth] = {};
+    auto carry_step = [&](int r) {  // r is a compile-time constant in the unrolled loops
+        if constexpr (!kCarry) return;
+        const int voff = opaque_tid() * 16;
+        // (before the first loads have aged, the offset is negative, that is, far beyond the
+        // resource's size: the store is dropped)
+        if (!G::UNROLL || (r >= kCarryDepth && r < kCarrySteps + kCarryDepth))
+            __builtin_amdgcn_raw_buffer_store_b128(carry_v[r % kCarryDepth], carry_dst,
+                                                   voff + (r - kCarryDepth) * (int)kGrain, 0, kBufferNt);
+        if (r < kCarrySteps)
+            carry_v[r % kCarryDepth] =
+                __builtin_amdgcn_raw_buffer_load_b128(carry_src, voff + r * (int)kGrain, 0, kBufferNt);
+    };
+    auto carry_drain = [&]() {
+        if constexpr (kCarry) {
+#pragma unroll
+            for (int r = kCarrySteps; r < kCarrySteps + kCarryDepth; ++r) {
+                const int voff = opaque_tid() * 16;
+                __builtin_amdgcn_raw_buffer_store_b128(carry_v[r % kCarryDepth], carry_dst,
+                                                       voff + (r - kCarryDepth) * (int)kGrain, 0, kBufferNt);
+            }
+        }
+    };
+    // room for a second tile-row buffer?
+    constexpr bool kTwoX = 2 * NX + RY * NWT + 4 * RY + (kCarry ? 4 * kCarryDepth - 4 : 0) <= 96;
     XT X[kTwoX ? 2 : 1][NX];
     XT Wt[RY][NWT];  // kernel row i lives in slot i % RY while it is in use
     if (kTwoX) load_x(0, X[0]);
     auto step = [&](int r, int u) {  // u == r % RY, and RY is even
+        carry_step(r);
         XT *xc = X[kTwoX ? (u & 1) : 0];
         if (kTwoX) {
             if (r + 1 < G::ROWS) load_x(r + 1, X[(u + 1) & 1]);
@@ -1331,11 +1404,13 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                     if (r0 + u == (G::ROWS * 15) / 16) ask_again();
                     step(r0 + u, u);
                 }
+        carry_drain();
     } else {
         // Large kernels: a loop, two rows per trip; the kernel rows are re-read from LDS for
         // every output row instead of being held (they would not fit in the registers).
 #pragma unroll 2
         for (int r = 0; r < G::ROWS; ++r) {
+            carry_step(r);
             XT xr[NX];
             load_x(r, xr);
 #pragma unroll
@@ -1349,6 +1424,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             }
             __builtin_amdgcn_sched_barrier(0);  // one row's loads at a time: the registers are few
         }
+        carry_drain();
     }
     __builtin_amdgcn_s_setprio(kPrioHigh);
 
@@ -1458,9 +1534,10 @@ __device__ __forceinline__ Ctx copy_item(ParamsPtr p, Ctx ctx, unsigned item)
 {
     const unsigned n = fdiv(item, p->div_chunks.mul, p->div_chunks.shift);
     const size_t chunk = (size_t)(item - n * p->div_chunks.d);
-    const char *src = (const char *)p->x + (size_t)n * p->img_bytes + p->idt_off;
-    char *dst = (char *)p->out + (size_t)n * p->img_bytes + p->idt_off;
-    const size_t len = p->idt_len;
+    // (what the conv items carry inside their tap loops comes first in the range)
+    const char *src = (const char *)p->x + (size_t)n * p->img_bytes + p->idt_off + p->copy_off;
+    char *dst = (char *)p->out + (size_t)n * p->img_bytes + p->idt_off + p->copy_off;
+    const size_t len = p->idt_len - p->copy_off;
     const size_t begin = chunk * p->copy_chunk;
     const size_t end = begin + p->copy_chunk < len ? begin + p->copy_chunk : len;
     const int eb = p->elem_bytes;
