@@ -16,7 +16,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "esc_oracle.c")
+_SRCS = [os.path.join(_HERE, "esc_oracle.c"), os.path.join(_HERE, "esc_oracle_fuse.c")]
 _LIB = os.path.join(_HERE, "libesc_oracle.so")
 
 F32 = 0
@@ -25,9 +25,9 @@ BF16 = 1
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (a second or two).  Returns the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in _SRCS):
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+               "-ffp-contract=off", "-o", _LIB, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -52,6 +52,14 @@ def _load():
         lib.esc_oracle_convattn_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, cl,
                                                     ci, ci, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.esc_oracle_convattn_forward.restype = ci
+        lib.esc_oracle_pointwise_lkc.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp]
+        lib.esc_oracle_pointwise_lkc.restype = None
+        lib.esc_oracle_fuse_1x1.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp]
+        lib.esc_oracle_fuse_1x1.restype = None
+        lib.esc_oracle_convattn_fused_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, ci, cl,
+                                                          ci, ci, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                          vp, vp, vp]
+        lib.esc_oracle_convattn_fused_forward.restype = ci
         lib.esc_oracle_f32_to_bf16.argtypes = [ctypes.c_float]
         lib.esc_oracle_f32_to_bf16.restype = ctypes.c_uint16
         lib.esc_oracle_threads.restype = ci
@@ -183,3 +191,67 @@ def forward_workload(wl, want_out: bool = True):
     """Run the whole forward on a workloads.Workload-like object."""
     return convattn_forward(wl.x, wl.Ca, wl.lk, wl.dtype, hidden=wl.hidden, w_up=wl.w_up,
                             b_up=wl.b_up, w_down=wl.w_down, b_down=wl.b_down, want_out=want_out)
+
+
+# ---------------------------------------------------------------- point-wise steps (esc_oracle_fuse.c)
+
+def pointwise_lkc(x: np.ndarray, Ca: int, lkc: np.ndarray, dtype: int = F32) -> np.ndarray:
+    """F_att (*) LK^c, the first factor of Eq. 5 -> [N,Ca,H,W] float64."""
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    lkc = _f32(lkc)
+    assert lkc.shape == (Ca, Ca)
+    pw = np.empty((N, Ca, H, W), dtype=np.float64)
+    _load().esc_oracle_pointwise_lkc(_ptr(x), dtype, N, C, H, W, Ca, _ptr(lkc), _ptr(pw))
+    return pw
+
+
+def fuse_1x1(cat: np.ndarray, w: np.ndarray, b=None) -> np.ndarray:
+    """Conv_fuse 1x1 (Eq. 4 line 4) of a float64 [N,C,H,W] tensor -> float64 [N,C,H,W]."""
+    cat = np.ascontiguousarray(cat, dtype=np.float64)
+    N, C, H, W = cat.shape
+    w, b = _f32(w), _f32(b)
+    assert w.shape == (C, C) and (b is None or b.shape == (C,))
+    out = np.empty_like(cat)
+    _load().esc_oracle_fuse_1x1(_ptr(cat), N, C, H, W, _ptr(w), _ptr(b), _ptr(out))
+    return out
+
+
+def convattn_fused_forward(x: np.ndarray, Ca: int, lk: np.ndarray, w_fuse: np.ndarray, dtype: int = F32, *,
+                           b_fuse=None, lkc=None, residual=None, hidden: int = 0, w_up=None, b_up=None,
+                           w_down=None, b_down=None, dk_in=None):
+    """The module with Conv_fuse, optionally LK^c in front (Eq. 5) and the residual of Eq. 3.
+
+    Returns (out float64 [N,C,H,W], res_att float64 [N,Ca,H,W], dk float64 [N,Ca,3,3]).
+    """
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    lk, Ks, cs = _lk_stride(lk, Ca)
+    if w_up is not None and dk_in is not None:
+        raise ValueError("give either estimator weights or dk_in, not both")
+    mode = 1 if w_up is not None else (2 if dk_in is not None else 0)
+    w_up, b_up, w_down, b_down = _f32(w_up), _f32(b_up), _f32(w_down), _f32(b_down)
+    w_fuse, b_fuse, lkc = _f32(w_fuse), _f32(b_fuse), _f32(lkc)
+    assert w_fuse.shape == (C, C) and (b_fuse is None or b_fuse.shape == (C,))
+    assert lkc is None or lkc.shape == (Ca, Ca)
+    if mode == 1:
+        K = hidden if hidden > 0 else Ca
+        assert w_up.shape == (9 * Ca, K)
+        if hidden > 0:
+            assert w_down.shape == (hidden, Ca)
+    if dk_in is not None:
+        dk_in = np.ascontiguousarray(dk_in, dtype=np.float64)
+        assert dk_in.shape == (N, Ca, 3, 3)
+    if residual is not None:
+        residual = _x(residual, dtype)
+        assert residual.shape == x.shape
+    res = np.empty((N, Ca, H, W), dtype=np.float64)
+    dk = np.empty((N, Ca, 3, 3), dtype=np.float64)
+    out = np.empty((N, C, H, W), dtype=np.float64)
+    rc = _load().esc_oracle_convattn_fused_forward(
+        _ptr(x), dtype, N, C, H, W, Ca, _ptr(lkc), _ptr(lk), Ks, cs, mode, hidden,
+        _ptr(w_down), _ptr(b_down), _ptr(w_up), _ptr(b_up), _ptr(dk_in), _ptr(w_fuse), _ptr(b_fuse),
+        _ptr(residual), _ptr(res), _ptr(dk), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out, res, dk
