@@ -130,6 +130,34 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
                                 void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The module with its point-wise steps (Eq. 4 lines 1-4 in full; Eq. 5; Eq. 3 line 3):
+ *
+ *   F_pw  = F_att (*) LK^c                  lk_c [C_a, C_a] row-major [out, in], 1x1, no bias;
+ *                                            NULL = F_att itself (Eq. 4 line 3 as it stands)
+ *   DK    = Estimator(GAP(F_att))           from the UNFILTERED slice (Eq. 4 line 2)
+ *   F_res = F_pw (*) (ZP(DK) + LK^s)        depth-wise, as in esc_convattn_forward (Eq. 5)
+ *   out   = Conv_fuse(Concat(F_res, F_idt)) w_fuse [C, C] row-major [out, in], b_fuse [C] or NULL
+ *           + residual                      [N,C,H,W] in the storage type, or NULL (Eq. 3 line 3:
+ *                                            the tensor the module's result is added to)
+ *
+ * The concat is never written: Conv_fuse reads F_res from the workspace and the identity
+ * channels from x, on the matrix cores with fp32 products and fp32 accumulation (bf16
+ * storage is widened on load).  F_res (and F_pw) pass through the workspace in the storage
+ * type, so with bf16 storage they are rounded to bf16 on the way, as a network's tensors
+ * would be; out is rounded once more at its store.  out must not overlap x, residual or
+ * the workspace.  The workspace is larger than esc_convattn_forward's
+ * (esc_fused_workspace_bytes; with_lk_c != 0 when lk_c will be given), prepared with the
+ * same esc_workspace_init, and serves esc_convattn_forward / esc_dynkernel_gen calls of
+ * the same shape as well.  Limits as above, and C <= 240.  Two to four launches on `stream`.
+ */
+size_t esc_fused_workspace_bytes(int N, int C_a, int H, int W, esc_dtype dt, int with_lk_c);
+esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                      const float *lk_c, const float *lk, int Ks, long lk_channel_stride,
+                                      const esc_gen_params *gen, const float *dk_in,
+                                      const float *w_fuse, const float *b_fuse, const void *residual,
+                                      void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * For callers that cannot allocate or prepare device memory (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): esc_convattn_forward
  * without the workspace arguments.  The mailboxes and counters live in a scratch array

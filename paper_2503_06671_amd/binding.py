@@ -19,7 +19,8 @@ ESC_F32 = 0
 ESC_BF16 = 1
 
 EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_workspace_errors", "esc_dynkernel_gen",
-           "esc_convattn_forward", "esc_convattn_forward_noalloc", "esc_status_string")
+           "esc_convattn_forward", "esc_convattn_forward_noalloc", "esc_fused_workspace_bytes",
+           "esc_convattn_fused_forward", "esc_status_string")
 NOALLOC_SCRATCH_BYTES = 1 << 20
 
 
@@ -63,6 +64,11 @@ def load_library():
         lib.esc_convattn_forward_noalloc.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, cl,
                                                      ctypes.POINTER(_GenParams), vp, vp, vp]
         lib.esc_convattn_forward_noalloc.restype = ci
+        lib.esc_fused_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+        lib.esc_fused_workspace_bytes.restype = sz
+        lib.esc_convattn_fused_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, ci, cl,
+                                                   ctypes.POINTER(_GenParams), vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.esc_convattn_fused_forward.restype = ci
         lib.esc_status_string.argtypes = [ci]
         lib.esc_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -225,4 +231,51 @@ def convattn_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, workspace: Opti
     _check(load_library().esc_convattn_forward(
         _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk), Ks, stride, gen_ref, _ptr(dk_in), _ptr(out),
         ws_ptr, ws_bytes, _stream(stream)))
+    return out
+
+
+def fused_workspace_bytes(N: int, Ca: int, H: int, W: int, dtype: torch.dtype, with_lk_c: bool) -> int:
+    dt = ESC_F32 if dtype == torch.float32 else ESC_BF16
+    return int(load_library().esc_fused_workspace_bytes(N, Ca, H, W, dt, int(bool(with_lk_c))))
+
+
+def new_fused_workspace(N: int, Ca: int, H: int, W: int, dtype: torch.dtype, with_lk_c: bool, device="cuda",
+                        stream=None) -> torch.Tensor:
+    """Allocate (with torch) and prepare a workspace for esc_convattn_fused_forward."""
+    nbytes = fused_workspace_bytes(N, Ca, H, W, dtype, with_lk_c)
+    if nbytes == 0:
+        raise ValueError("bad shape for a workspace")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    workspace_init(ws, stream)
+    return ws
+
+
+def convattn_fused_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, w_fuse: torch.Tensor, workspace: torch.Tensor,
+                           b_fuse: Optional[torch.Tensor] = None, lk_c: Optional[torch.Tensor] = None,
+                           residual: Optional[torch.Tensor] = None, gen: Optional[GenParams] = None,
+                           dk_in: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                           stream=None) -> torch.Tensor:
+    """esc_convattn_fused_forward: the module with Conv_fuse, optionally LK^c and the residual."""
+    dt, (N, C, H, W) = _x_checked(x)
+    Ks, stride = _lk_checked(lk, int(Ca), None, None)
+    if gen is not None:
+        gen.check(int(Ca))
+    _dev_f32(w_fuse, "w_fuse"), _dev_f32(b_fuse, "b_fuse"), _dev_f32(lk_c, "lk_c"), _dev_f32(dk_in, "dk_in")
+    if w_fuse.numel() != C * C or (b_fuse is not None and b_fuse.numel() != C):
+        raise ValueError("w_fuse must be [C, C] and b_fuse [C]")
+    if lk_c is not None and lk_c.numel() != Ca * Ca:
+        raise ValueError("lk_c must be [Ca, Ca]")
+    if dk_in is not None and dk_in.numel() != N * Ca * 9:
+        raise ValueError("dk_in must hold [N, Ca, 3, 3] values")
+    if residual is not None and (residual.dtype != x.dtype or residual.shape != x.shape or not residual.is_contiguous()
+                                 or not residual.is_cuda):
+        raise TypeError("residual must match x in dtype and shape and be a contiguous device tensor")
+    if out is None:
+        out = torch.empty_like(x)
+    if out.dtype != x.dtype or out.shape != x.shape or not out.is_contiguous():
+        raise TypeError("out must match x in dtype and shape and be contiguous")
+    _check(load_library().esc_convattn_fused_forward(
+        _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk_c), _ptr(lk), Ks, stride,
+        ctypes.byref(gen.c) if gen is not None else None, _ptr(dk_in), _ptr(w_fuse), _ptr(b_fuse), _ptr(residual),
+        _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
     return out

@@ -8,6 +8,7 @@
 #include <stdlib.h>
 
 #include "esc_kernels.hpp"
+#include "esc_pointwise.hpp"
 
 namespace esc {
 
@@ -374,6 +375,78 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
     return ESC_OK;
 }
 
+// Eq. 4 line 2 alone on checked arguments: one launch of the variant without conv items.
+esc_status enqueue_dynkernel(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a, const esc_gen_params *gen,
+                             float *dk_out, void *workspace, const WsLayout &l, hipStream_t stream)
+{
+    FwdParams p;
+    esc_status st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l);
+    if (st != ESC_OK) return st;
+    p.dk_out = dk_out;
+    p.dk_mode = kDkBoxes;  // no conv items here: gen items write dk_out, each from its image's pool sums
+    p.n_gen = (unsigned)N;
+    p.n_gsum = 0;
+    return launch_forward(p, 0, dt == ESC_BF16, stream);
+}
+
+// The forward on checked arguments: one launch.  `out` holds out_c channels per image, of
+// which the first C_a are written by the conv items; with_copy adds the pass-through copy
+// of channels C_a .. C (then out_c == C).
+esc_status enqueue_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a, const float *lk, int Ks,
+                           long lk_channel_stride, const esc_gen_params *gen, const float *dk_in, void *out, int out_c,
+                           bool with_copy, void *workspace, const WsLayout &l, hipStream_t stream)
+{
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    const uintptr_t xa = (uintptr_t)x, oa = (uintptr_t)out;
+    FwdParams p;
+    esc_status st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l);
+    if (st != ESC_OK) return st;
+    p.out = out;
+    p.out_c = out_c;
+    p.lk = lk;
+    p.lk_cstride = lk_channel_stride;
+    p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
+    if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
+    // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
+    p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
+    if (with_copy && C_a < C) {
+        const size_t plane = (size_t)H * W * es;
+        p.img_bytes = plane * C;
+        p.idt_off = plane * C_a;
+        p.idt_len = plane * (C - C_a);
+        p.copy_vec_ok = (xa % 16 == 0) && (oa % 16 == 0) && (p.img_bytes % 16 == 0) && (p.idt_off % 16 == 0);
+    }
+    const int ks_variant = C_a > 0 ? Ks : 0;
+    return launch_forward(p, ks_variant, dt == ESC_BF16, stream);
+}
+
+// Workspace of esc_convattn_fused_forward: the forward's own workspace first, then F_res
+// [N,C_a,H,W] in the storage type and, with LK^c, F_att (*) LK^c (same shape) and DK.
+struct FusedLayout {
+    WsLayout ws;
+    size_t fres_off, pw_off, dk_off, total;
+};
+
+bool fused_layout(int N, int Ca, int H, int W, esc_dtype dt, bool with_lkc, FusedLayout *f)
+{
+    if (dt != ESC_F32 && dt != ESC_BF16) return false;
+    if (!ws_layout(N, Ca, H, W, &f->ws)) return false;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    const size_t slice = round_up((size_t)N * Ca * H * W * es, kWsAlign);
+    size_t off = f->ws.total;
+    f->fres_off = off;
+    off += slice;
+    f->pw_off = off;
+    f->dk_off = off;
+    if (with_lkc) {
+        off += slice;
+        f->dk_off = off;
+        off += round_up((size_t)N * Ca * 9 * sizeof(float), kWsAlign);
+    }
+    f->total = off;
+    return true;
+}
+
 // The mailboxes and counters of esc_convattn_forward_noalloc: one copy per device, in the
 // code object's data segment, so that a call needs no allocation and no preparation.  It is
 // laid out like a caller's workspace and starts out as esc_workspace_init would leave it
@@ -421,7 +494,6 @@ esc_status forward_impl(const void *x, esc_dtype dt, int N, int C, int H, int W,
     const size_t es = dt == ESC_F32 ? 4 : 2;
     if (((uintptr_t)out % es) != 0) return ESC_ERR_SHAPE;
     const size_t bytes = (size_t)N * C * H * W * es;
-    const uintptr_t xa = (uintptr_t)x, oa = (uintptr_t)out;
     if (overlaps(x, bytes, out, bytes)) return ESC_ERR_ALIAS;
     WsLayout l;
     if (!ws_layout(N, C_a, H, W, &l)) return ESC_ERR_SHAPE;
@@ -442,24 +514,8 @@ esc_status forward_impl(const void *x, esc_dtype dt, int N, int C, int H, int W,
             return ESC_ERR_ALIAS;
     }
 
-    FwdParams p;
-    if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
-    p.out = out;
-    p.lk = lk;
-    p.lk_cstride = lk_channel_stride;
-    p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
-    if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
-    // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
-    p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
-    if (C_a < C) {
-        const size_t plane = (size_t)H * W * es;
-        p.img_bytes = plane * C;
-        p.idt_off = plane * C_a;
-        p.idt_len = plane * (C - C_a);
-        p.copy_vec_ok = (xa % 16 == 0) && (oa % 16 == 0) && (p.img_bytes % 16 == 0) && (p.idt_off % 16 == 0);
-    }
-    const int ks_variant = C_a > 0 ? Ks : 0;
-    return launch_forward(p, ks_variant, dt == ESC_BF16, (hipStream_t)stream);
+    return enqueue_forward(x, dt, N, C, H, W, C_a, lk, Ks, lk_channel_stride, gen, dk_in, out, C, true, workspace, l,
+                           (hipStream_t)stream);
 }
 
 
@@ -521,13 +577,7 @@ esc_status esc_dynkernel_gen(const void *x, esc_dtype dt, int N, int C, int H, i
             overlaps(workspace, workspace_bytes, x, x_bytes))
             return ESC_ERR_ALIAS;
     }
-    FwdParams p;
-    if ((st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l)) != ESC_OK) return st;
-    p.dk_out = dk_out;
-    p.dk_mode = kDkBoxes;  // no conv items here: gen items write dk_out, each from its image's pool sums
-    p.n_gen = (unsigned)N;
-    p.n_gsum = 0;
-    return launch_forward(p, 0, dt == ESC_BF16, (hipStream_t)stream);
+    return enqueue_dynkernel(x, dt, N, C, H, W, C_a, gen, dk_out, workspace, l, (hipStream_t)stream);
 }
 
 esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
@@ -548,6 +598,101 @@ esc_status esc_convattn_forward_noalloc(const void *x, esc_dtype dt, int N, int 
 }
 
 
+size_t esc_fused_workspace_bytes(int N, int C_a, int H, int W, esc_dtype dt, int with_lk_c)
+{
+    FusedLayout f;
+    if (!fused_layout(N, C_a, H, W, dt, with_lk_c != 0, &f)) return 0;
+    return f.total;
+}
+
+esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                      const float *lk_c, const float *lk, int Ks, long lk_channel_stride,
+                                      const esc_gen_params *gen, const float *dk_in, const float *w_fuse,
+                                      const float *b_fuse, const void *residual, void *out, void *workspace,
+                                      size_t workspace_bytes, void *stream)
+{
+    esc_status st = check_common(x, dt, N, C, H, W, C_a);
+    if (st != ESC_OK) return st;
+    if (out == nullptr || w_fuse == nullptr) return ESC_ERR_NULL;
+    if (Ks < 1 || (Ks % 2) == 0) return Ks < 1 ? ESC_ERR_SHAPE : ESC_ERR_UNSUPPORTED;
+    if (Ks > kMaxKs || C > kPointwiseMaxK) return ESC_ERR_UNSUPPORTED;
+    if (C_a > 0 && lk == nullptr) return ESC_ERR_NULL;
+    if (lk_channel_stride != 0 && lk_channel_stride < (long)Ks * Ks) return ESC_ERR_SHAPE;
+    if (gen != nullptr && (st = check_gen(gen, C_a)) != ESC_OK) return st;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    if (((uintptr_t)out % es) != 0 || ((uintptr_t)residual % es) != 0) return ESC_ERR_SHAPE;
+    const size_t bytes = (size_t)N * C * H * W * es;
+    if (overlaps(x, bytes, out, bytes) || (residual != nullptr && overlaps(residual, bytes, out, bytes)))
+        return ESC_ERR_ALIAS;
+    const bool with_lkc = lk_c != nullptr && C_a > 0;
+    FusedLayout f;
+    if (!fused_layout(N, C_a, H, W, dt, with_lkc, &f)) return ESC_ERR_SHAPE;
+    if ((st = check_ws(workspace, workspace_bytes, f.total)) != ESC_OK) return st;
+    if (overlaps(workspace, workspace_bytes, out, bytes) || overlaps(workspace, workspace_bytes, x, bytes) ||
+        (residual != nullptr && overlaps(workspace, workspace_bytes, residual, bytes)))
+        return ESC_ERR_ALIAS;
+    if (overlaps(w_fuse, (size_t)C * C * sizeof(float), out, bytes)) return ESC_ERR_ALIAS;
+
+    hipStream_t s = (hipStream_t)stream;
+    const bool bf16 = dt == ESC_BF16;
+    const size_t plane = (size_t)H * W;
+    char *w = (char *)workspace;
+    void *fres = w + f.fres_off;
+    if (C_a > 0) {
+        const void *conv_in = x;
+        int conv_c = C;
+        const esc_gen_params *conv_gen = gen;
+        const float *conv_dk = dk_in;
+        if (with_lkc) {
+            // Eq. 5: DK from the unfiltered slice first (Eq. 4 line 2), then F_att (*) LK^c,
+            // on which both depth-wise kernels act
+            if (gen != nullptr) {
+                float *dk = (float *)(w + f.dk_off);
+                if ((st = enqueue_dynkernel(x, dt, N, C, H, W, C_a, gen, dk, workspace, f.ws, s)) != ESC_OK) return st;
+                conv_gen = nullptr;
+                conv_dk = dk;
+            }
+            PointwiseParams pp{};
+            pp.src1 = x;
+            pp.src1_img_stride = (size_t)C * plane;
+            pp.K1 = C_a;
+            pp.w = lk_c;
+            pp.w_ld = C_a;
+            pp.dst = w + f.pw_off;
+            pp.dst_img_stride = (size_t)C_a * plane;
+            pp.M = C_a;
+            pp.N = N;
+            pp.P = (long)plane;
+            if (launch_pointwise(pp, bf16, s) != hipSuccess) return ESC_ERR_HIP;
+            conv_in = w + f.pw_off;
+            conv_c = C_a;
+        }
+        // F_res = F_pw (*) LK^s + F_pw (*) DK into the workspace; no pass-through copy
+        if ((st = enqueue_forward(conv_in, dt, N, conv_c, H, W, C_a, lk, Ks, lk_channel_stride, conv_gen, conv_dk, fres,
+                                  C_a, false, workspace, f.ws, s)) != ESC_OK)
+            return st;
+    }
+    // Eq. 4 line 4 (and Eq. 3 line 3): Conv_fuse over F_res and the identity channels of x
+    PointwiseParams pp{};
+    pp.src1 = fres;
+    pp.src1_img_stride = (size_t)C_a * plane;
+    pp.K1 = C_a;
+    pp.src2 = (const char *)x + (size_t)C_a * plane * es;
+    pp.src2_img_stride = (size_t)C * plane;
+    pp.K2 = C - C_a;
+    pp.w = w_fuse;
+    pp.w_ld = C;
+    pp.bias = b_fuse;
+    pp.res = residual;
+    pp.res_img_stride = (size_t)C * plane;
+    pp.dst = out;
+    pp.dst_img_stride = (size_t)C * plane;
+    pp.M = C;
+    pp.N = N;
+    pp.P = (long)plane;
+    return launch_pointwise(pp, bf16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
+}
+
 const char *esc_status_string(esc_status s)
 {
     switch (s) {
@@ -555,7 +700,7 @@ const char *esc_status_string(esc_status s)
     case ESC_ERR_NULL: return "a required pointer is NULL";
     case ESC_ERR_SHAPE: return "a size or stride is out of its domain";
     case ESC_ERR_DTYPE: return "unknown storage type";
-    case ESC_ERR_UNSUPPORTED: return "outside the library's limits (Ks odd <= 31, C_a <= 256, hidden <= 256)";
+    case ESC_ERR_UNSUPPORTED: return "outside the library's limits (Ks odd <= 31, C_a <= 256, hidden <= 256; fused call: C <= 240)";
     case ESC_ERR_WORKSPACE: return "workspace missing, misaligned or too small (esc_convattn_forward_noalloc: shape beyond the built-in scratch)";
     case ESC_ERR_ALIAS: return "out overlaps x, the workspace, lk or dk";
     case ESC_ERR_HIP: return "the HIP runtime refused a launch";

@@ -150,6 +150,7 @@ struct FwdParams {
     int dk_mode;         // where conv items take DK from (kDk*)
     int pool_mode;       // who computes the GAP partial sums (kPool*)
     int N, C, Ca, H, W;
+    int out_c;           // channels per image of `out` (C; C_a when only F_res is written)
     int ptiles_x, ptiles;  // pool tiles per row of tiles / per (image, channel) plane
     float hw;            // H*W as a float, the GAP divisor
     unsigned n_pool, n_gen, n_conv, n_copy;  // item counts
@@ -1433,7 +1434,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     const int tid_d = opaque_tid();
     const int tx_d = tid_d & 15, ty_d = tid_d >> 4;
     const float *trow_d = tile + (ty_d * RY) * PITCH + 4 * tx_d;
-    T *op = (T *)p->out + wd.plane_off;
+    T *op = (T *)p->out + ((size_t)wd.n * p->out_c + wd.c) * (size_t)p->H * (size_t)p->W;  // out may have fewer channels than x
 
     if (p->dk_mode != kDkNone) {
         const size_t dk_idx = ((size_t)wd.n * p->Ca + wd.c) * 9;

@@ -123,6 +123,35 @@ def test_noalloc_entry_point_validates_before_anything_else(lib):
     assert re.search(r"#define\s+ESC_NOALLOC_SCRATCH_BYTES\s+\(1u << 20\)", text)
 
 
+def test_fused_forward_rejects_bad_arguments_before_launch(lib):
+    def fu(x=0x10000, dt=0, N=1, C=64, H=8, W=8, Ca=16, lkc=None, lk=0x20000, Ks=13, stride=169, gen=None, dk=None,
+           wf=0x50000, bf=None, res=None, out=0x90000, ws=0x30000 * 256, ws_bytes=1 << 22):
+        return lib.esc_convattn_fused_forward(x, dt, N, C, H, W, Ca, lkc, lk, Ks, stride, gen, dk, wf, bf, res, out,
+                                              ws, ws_bytes, None)
+    assert fu(x=None) == E_NULL
+    assert fu(out=None) == E_NULL
+    assert fu(wf=None) == E_NULL
+    assert fu(lk=None) == E_NULL
+    assert fu(dt=3) == E_DTYPE
+    assert fu(Ks=4) == E_UNSUP
+    assert fu(C=241, Ca=16) == E_UNSUP
+    assert fu(Ca=65) == E_SHAPE
+    assert fu(out=0x10000) == E_ALIAS
+    assert fu(res=0x90000) == E_ALIAS                     # residual overlaps out
+    assert fu(res=0x90002) == E_SHAPE                     # misaligned residual
+    assert fu(ws=None) == E_WS
+    # the fused call needs room for F_res (and F_pw, DK with LK^c) behind the forward's workspace
+    plain = lib.esc_workspace_bytes(1, 16, 8, 8)
+    need = lib.esc_fused_workspace_bytes(1, 16, 8, 8, 0, 0)
+    need_c = lib.esc_fused_workspace_bytes(1, 16, 8, 8, 0, 1)
+    assert plain < need < need_c and need % 256 == 0 and need_c % 256 == 0
+    assert need - plain >= 16 * 64 * 4 and need_c - need >= 16 * 64 * 4 + 16 * 9 * 4
+    assert lib.esc_fused_workspace_bytes(1, 16, 8, 8, 1, 0) < need          # bf16 slices are smaller
+    assert lib.esc_fused_workspace_bytes(1, 16, 8, 8, 5, 0) == 0
+    assert fu(ws_bytes=plain) == E_WS
+    assert fu(ws_bytes=need, lkc=0x60000) == E_WS
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(1, 4, 8, 8)
