@@ -57,6 +57,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-all-workloads", action="store_true", help="skip the other benchmark workloads")
     ap.add_argument("--no-floors", action="store_true", help="skip the copy-only and empty-call floors")
+    ap.add_argument("--fused", action="store_true",
+                    help="time esc_convattn_fused_forward (the module with Conv_fuse, Eq. 4 line 4) instead")
+    ap.add_argument("--lkc", action="store_true", help="with --fused: LK^c in front of the depth-wise kernels (Eq. 5)")
+    ap.add_argument("--residual", action="store_true", help="with --fused: add the residual of Eq. 3 line 3")
     return ap.parse_args()
 
 
@@ -149,10 +153,31 @@ def roofline_of(wl, sec):
     return r
 
 
+FP32_MFMA_PEAK_TFLOPS = 157.3         # dense fp32 matrix-core peak
+
+
+def fused_roofline_of(wl, sec, lkc, residual):
+    """The fused call: x read once (plus the residual), out written once; the depth-wise taps on
+    the vector units, Conv_fuse (and LK^c) on the matrix cores in fp32."""
+    P = wl.N * wl.H * wl.W
+    b_alg = (3.0 if residual else 2.0) * P * wl.C * wl.elem_bytes
+    f_vec = 2.0 * wl.Ks * wl.Ks * P * wl.Ca
+    f_mat = 2.0 * wl.C * wl.C * P + (2.0 * wl.Ca * wl.Ca * P if lkc else 0.0)
+    t = {"hbm": b_alg / (HBM_PEAK_GBS * 1e9), "alu": f_vec / (FP32_VECTOR_PEAK_TFLOPS * 1e12),
+         "mfma": f_mat / (FP32_MFMA_PEAK_TFLOPS * 1e12)}
+    bound = max(t, key=t.get)
+    ach = {"hbm": b_alg / sec / 1e9, "alu": f_vec / sec / 1e12, "mfma": f_mat / sec / 1e12}[bound]
+    peak = {"hbm": HBM_PEAK_GBS, "alu": FP32_VECTOR_PEAK_TFLOPS, "mfma": FP32_MFMA_PEAK_TFLOPS}[bound]
+    return {"bound": bound, "achieved": ach, "peak": peak, "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+            "frac": ach / peak, "algorithmic_bytes": b_alg, "algorithmic_flops_vector": f_vec,
+            "algorithmic_flops_matrix": f_mat, "hbm_gbps": b_alg / sec / 1e9, "alu_tflops": f_vec / sec / 1e12,
+            "mfma_tflops": f_mat / sec / 1e12}
+
+
 class Runner:
     """Device buffers of one workload and the timing protocol."""
 
-    def __init__(self, wl, rotate_bytes, warm_cache, ca=None):
+    def __init__(self, wl, rotate_bytes, warm_cache, ca=None, fused=None):
         import numpy as np
         import torch
         from paper_2503_06671_amd import binding, workloads as wk
@@ -174,11 +199,26 @@ class Runner:
         self.gen = None
         if self.ca > 0:
             self.gen = binding.GenParams(dev(wl.w_up), dev(wl.b_up), wl.hidden, dev(wl.w_down), dev(wl.b_down))
-        self.ws = binding.new_workspace(wl.N, self.ca, wl.H, wl.W)
+        self.fused = fused
+        if fused is None:
+            self.ws = binding.new_workspace(wl.N, self.ca, wl.H, wl.W)
+        else:
+            # seeded point-wise weights: Conv_fuse [C,C] ~ N(0, 1/C) with a small bias, LK^c [C_a,C_a] ~ N(0, 1/C_a)
+            rng = np.random.default_rng(1000 + wl.C)
+            self.w_fuse = dev((rng.standard_normal((wl.C, wl.C)) / np.sqrt(wl.C)).astype(np.float32))
+            self.b_fuse = dev((rng.standard_normal(wl.C) * 0.1).astype(np.float32))
+            self.lk_c = dev((rng.standard_normal((wl.Ca, wl.Ca)) / np.sqrt(wl.Ca)).astype(np.float32)) if fused["lkc"] else None
+            self.res = [torch.randn_like(x0) for _ in range(self.pairs)] if fused["residual"] else None
+            self.ws = binding.new_fused_workspace(wl.N, self.ca, wl.H, wl.W, x0.dtype, fused["lkc"])
         self.stream = torch.cuda.Stream()
 
     def step(self, i):
         k = i % self.pairs
+        if self.fused is not None:
+            self.binding.convattn_fused_forward(
+                self.xs[k], self.ca, self.lk, self.w_fuse, self.ws, b_fuse=self.b_fuse, lk_c=self.lk_c,
+                residual=None if self.res is None else self.res[k], gen=self.gen, out=self.outs[k], stream=self.stream)
+            return
         self.binding.convattn_forward(self.xs[k], self.ca, self.lk, self.ws, gen=self.gen, out=self.outs[k],
                                       stream=self.stream)
 
@@ -255,15 +295,17 @@ def main():
         wl = wk.make_config(args.config, args.ks) if args.config == 4 else wk.make_config(args.config)
     replays = replays_for(args.steps, args.replays)
 
-    run = Runner(wl, args.rotate_bytes, args.warm_cache)
+    fused = {"lkc": args.lkc, "residual": args.residual} if args.fused else None
+    run = Runner(wl, args.rotate_bytes, args.warm_cache, fused=fused)
     t = run.time(args.steps, args.warmup, replays, eager=args.eager)
     ms_step = t["median"]
     # spot check of the last buffers against the first (same input => same bits)
-    assert torch.equal(run.outs[0], run.outs[(args.steps - 1) % run.pairs]), "rotating buffers disagree"
+    if not args.residual:
+        assert torch.equal(run.outs[0], run.outs[(args.steps - 1) % run.pairs]), "rotating buffers disagree"
     latency_us = run.single_call_latency_us()
 
     floors = None
-    if not args.no_floors:
+    if not args.no_floors and fused is None:
         # the library's own pure copy (C_a = 0) on the same tensors and rotation, and a call
         # with nothing to do (1 x 1 x 1 x 1, C_a = 0): what is left above them is the method's
         copy_t = Runner(wl, args.rotate_bytes, args.warm_cache, ca=0).time(args.steps, min(args.warmup, 200), replays,
@@ -276,17 +318,25 @@ def main():
     del run
 
     sec = ms_step * 1e-3
-    roof = roofline_of(wl, sec)
-    traffic, traffic_src = (None, None) if args.warm_cache else profiled_traffic(wl.name)
+    wl_name = wl.name
+    if fused is not None:
+        wl_name += "_fused" + ("_lkc" if args.lkc else "") + ("_res" if args.residual else "")
+        roof = fused_roofline_of(wl, sec, args.lkc, args.residual)
+    else:
+        roof = roofline_of(wl, sec)
+    traffic, traffic_src = (None, None) if args.warm_cache else profiled_traffic(wl_name)
     roof.update({
-        "kernel": f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)",
+        "kernel": (f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)"
+                   if fused is None else
+                   "forward_kernel (F_res into the workspace) + pointwise_kernel (Conv_fuse on the matrix cores)"
+                   + ("; with LK^c also the estimator launch and a second pointwise_kernel" if args.lkc else "")),
         "traffic": traffic, "traffic_source": traffic_src,
         # one step is one launch of the single forward kernel, so the per-launch duration is
         # the HIP-event time of a timed region divided by the number of launches in it
         "kernel_us": ms_step * 1e3,
     })
     res = {
-        "metric": "convattn_fwd_mpixel_per_s",
+        "metric": "convattn_fwd_mpixel_per_s" if fused is None else "convattn_fused_fwd_mpixel_per_s",
         "value": wl.pixels / sec / 1e6,
         "unit": "Mpixel/s",
         "n_gpus": 1,
@@ -298,7 +348,7 @@ def main():
         "vs_baseline": None,
         "dtype": wk.DTYPE_NAMES[wl.dtype],
         "data": "synthetic",
-        "config": {"workload": wl.name, "N": wl.N, "C": wl.C, "C_a": wl.Ca, "H": wl.H, "W": wl.W,
+        "config": {"workload": wl_name, "N": wl.N, "C": wl.C, "C_a": wl.Ca, "H": wl.H, "W": wl.W,
                    "Ks": wl.Ks, "launch": "eager" if args.eager else "hipgraph",
                    "buffer_pairs": max(2, int(-(-args.rotate_bytes // (2.0 * wl.N * wl.C * wl.H * wl.W * wl.elem_bytes))))
                    if not args.warm_cache else 1,
@@ -333,6 +383,25 @@ def main():
             del r2
             torch.cuda.empty_cache()
         res["all_workloads"] = others
+        # the module with Conv_fuse (esc_convattn_fused_forward) on the benchmark shapes
+        fus = []
+        for idx, opts in ((1, {"lkc": False, "residual": False}), (1, {"lkc": True, "residual": True}),
+                          (2, {"lkc": False, "residual": False}), (3, {"lkc": False, "residual": False})):
+            w2 = wk.make_config(idx)
+            name2 = w2.name + "_fused" + ("_lkc" if opts["lkc"] else "") + ("_res" if opts["residual"] else "")
+            if fused is not None and name2 == wl_name:
+                continue
+            r2 = Runner(w2, args.rotate_bytes, args.warm_cache, fused=opts)
+            t2 = r2.time(200, 200, 25, eager=args.eager)
+            s2 = t2["median"] * 1e-3
+            rf = fused_roofline_of(w2, s2, opts["lkc"], opts["residual"])
+            fus.append({"workload": name2, "dtype": wk.DTYPE_NAMES[w2.dtype], "us_per_step": t2["median"] * 1e3,
+                        "mpixel_per_s": w2.pixels / s2 / 1e6, "bound": rf["bound"], "frac": rf["frac"],
+                        "hbm_gbps": rf["hbm_gbps"], "mfma_tflops": rf["mfma_tflops"], "alu_tflops": rf["alu_tflops"],
+                        "steps": 200, "warmup": 200, "replays": 25})
+            del r2
+            torch.cuda.empty_cache()
+        res["fused_workloads"] = fus
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
