@@ -72,7 +72,7 @@ extern __shared__ __align__(16) float pw_lds[];
 // uses a stage later): a value touched right after its load would make the compiler wait
 // for that load before it issues the next.
 template <typename T, bool VEC>
-__global__ __launch_bounds__(kPwThreads, 3) void pointwise_kernel(const PointwiseParams p)
+__global__ __launch_bounds__(kPwThreads, (VEC && sizeof(T) == 4) ? 3 : 2) void pointwise_kernel(const PointwiseParams p)
 {
     constexpr int kPer = 16 / (int)sizeof(T);               // pixels per 16-byte piece
     constexpr int kPieces = kPwTile / kPer;                  // pieces per channel row of a tile
