@@ -71,10 +71,13 @@ typedef enum {
     ESC_ERR_UNSUPPORTED = 4, /* valid for the method, outside the library's limits */
     ESC_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or too small         */
     ESC_ERR_ALIAS = 6,       /* out overlaps x, the workspace, lk, dk_in or dk_out  */
-    ESC_ERR_HIP = 7          /* the HIP runtime refused a launch                   */
+    ESC_ERR_HIP = 7,         /* the HIP runtime refused a launch                   */
+    ESC_STATUS_INT_RANGE = 0x7fffffff /* not a status: gives the type the range of int */
 } esc_status;
 
-typedef enum { ESC_F32 = 0, ESC_BF16 = 1 } esc_dtype; /* storage type of x and out */
+/* storage type of x and out (the last member is not a type: it gives the enum the range of
+ * int, so that a bad value is an argument to refuse, not undefined behaviour) */
+typedef enum { ESC_F32 = 0, ESC_BF16 = 1, ESC_DTYPE_INT_RANGE = 0x7fffffff } esc_dtype;
 
 /*
  * The kernel estimator of Eq. 4 line 2, applied to g = GAP(F_att) of one image:

@@ -704,6 +704,7 @@ const char *esc_status_string(esc_status s)
     case ESC_ERR_WORKSPACE: return "workspace missing, misaligned or too small (esc_convattn_forward_noalloc: shape beyond the built-in scratch)";
     case ESC_ERR_ALIAS: return "out overlaps x, the workspace, lk or dk";
     case ESC_ERR_HIP: return "the HIP runtime refused a launch";
+    case ESC_STATUS_INT_RANGE: break;
     }
     return "unknown status";
 }
