@@ -16,7 +16,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "esc_oracle.c"), os.path.join(_HERE, "esc_oracle_fuse.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("esc_oracle.c", "esc_oracle_fuse.c", "esc_oracle_dense.c")]
 _LIB = os.path.join(_HERE, "libesc_oracle.so")
 
 F32 = 0
@@ -60,6 +60,11 @@ def _load():
                                                           ci, ci, vp, vp, vp, vp, vp, vp, vp, vp,
                                                           vp, vp, vp]
         lib.esc_oracle_convattn_fused_forward.restype = ci
+        lib.esc_oracle_dense_lk_conv.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, vp]
+        lib.esc_oracle_dense_lk_conv.restype = None
+        lib.esc_oracle_convattn_dense_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, ci, ci,
+                                                          vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.esc_oracle_convattn_dense_forward.restype = ci
         lib.esc_oracle_f32_to_bf16.argtypes = [ctypes.c_float]
         lib.esc_oracle_f32_to_bf16.restype = ctypes.c_uint16
         lib.esc_oracle_threads.restype = ci
@@ -255,3 +260,48 @@ def convattn_fused_forward(x: np.ndarray, Ca: int, lk: np.ndarray, w_fuse: np.nd
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return out, res, dk
+
+
+# ---------------------------------------------------------------- dense large kernel (esc_oracle_dense.c)
+
+def dense_lk_conv(x: np.ndarray, Ca: int, lk: np.ndarray, dtype: int = F32) -> np.ndarray:
+    """F_att cross-correlated with a dense large kernel lk[Ca(out),Ca(in),Ks,Ks] -> [N,Ca,H,W] float64."""
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    lk = _f32(lk)
+    assert lk.ndim == 4 and lk.shape[0] == lk.shape[1] == Ca and lk.shape[2] == lk.shape[3]
+    res = np.empty((N, Ca, H, W), dtype=np.float64)
+    _load().esc_oracle_dense_lk_conv(_ptr(x), dtype, N, C, H, W, Ca, _ptr(lk), lk.shape[2], _ptr(res))
+    return res
+
+
+def convattn_dense_forward(x: np.ndarray, Ca: int, lk: np.ndarray, dtype: int = F32, *, hidden: int = 0,
+                           w_up=None, b_up=None, w_down=None, b_down=None, dk_in=None, want_out: bool = True):
+    """The module with the dense large kernel of the paper's main variants (Eq. 4 lines 1-4
+    without Conv_fuse).  Returns (res_att float64, dk float64, out in the storage dtype or None)."""
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    lk = _f32(lk)
+    assert lk.ndim == 4 and lk.shape[0] == lk.shape[1] == Ca and lk.shape[2] == lk.shape[3]
+    if w_up is not None and dk_in is not None:
+        raise ValueError("give either estimator weights or dk_in, not both")
+    mode = 1 if w_up is not None else (2 if dk_in is not None else 0)
+    w_up, b_up, w_down, b_down = _f32(w_up), _f32(b_up), _f32(w_down), _f32(b_down)
+    if mode == 1:
+        K = hidden if hidden > 0 else Ca
+        assert w_up.shape == (9 * Ca, K)
+        if hidden > 0:
+            assert w_down.shape == (hidden, Ca)
+    if dk_in is not None:
+        dk_in = np.ascontiguousarray(dk_in, dtype=np.float64)
+        assert dk_in.shape == (N, Ca, 3, 3)
+    res = np.empty((N, Ca, H, W), dtype=np.float64)
+    tmp = np.empty((N, Ca, H, W), dtype=np.float64)
+    dk = np.empty((N, Ca, 3, 3), dtype=np.float64)
+    out = np.empty_like(x) if want_out else None
+    rc = _load().esc_oracle_convattn_dense_forward(
+        _ptr(x), dtype, N, C, H, W, Ca, _ptr(lk), lk.shape[2], mode, hidden, _ptr(w_down), _ptr(b_down),
+        _ptr(w_up), _ptr(b_up), _ptr(dk_in), _ptr(tmp), _ptr(res), _ptr(dk), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return res, dk, out
