@@ -161,6 +161,25 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
                                       void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Eq. 4 lines 1-4 (without Conv_fuse) with the DENSE large kernel of the paper's main
+ * variants (Sec. 3: LK in R^{Ks x Ks x C_a x C_a}, shared by the whole model):
+ *
+ *   F_res[co] = sum_ci F_att[ci] (*) LK[co, ci]  +  F_att[co] (*) DK[co]
+ *
+ *   lk_dense [C_a, C_a, Ks, Ks] fp32, output channel first; cross-correlation, zero padding.
+ * DK stays a separate depth-wise term, as in the paper.  Everything else (gen, dk_in, out,
+ * the identity channels, rounding) is as in esc_convattn_forward.  The contraction runs on
+ * the matrix cores with fp32 products and accumulation.  Limits: C_a <= 64, Ks odd <= 17.
+ * The workspace is esc_dense_workspace_bytes large (the forward's workspace, DK and the
+ * rearranged weights), prepared with esc_workspace_init.  Two or three launches on `stream`.
+ */
+size_t esc_dense_workspace_bytes(int N, int C_a, int H, int W, int Ks);
+esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                      const float *lk_dense, int Ks,
+                                      const esc_gen_params *gen, const float *dk_in,
+                                      void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * For callers that cannot allocate or prepare device memory (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): esc_convattn_forward
  * without the workspace arguments.  The mailboxes and counters live in a scratch array

@@ -20,7 +20,8 @@ ESC_BF16 = 1
 
 EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_workspace_errors", "esc_dynkernel_gen",
            "esc_convattn_forward", "esc_convattn_forward_noalloc", "esc_fused_workspace_bytes",
-           "esc_convattn_fused_forward", "esc_status_string")
+           "esc_convattn_fused_forward", "esc_dense_workspace_bytes", "esc_convattn_dense_forward",
+           "esc_status_string")
 NOALLOC_SCRATCH_BYTES = 1 << 20
 
 
@@ -69,6 +70,11 @@ def load_library():
         lib.esc_convattn_fused_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, ci, cl,
                                                    ctypes.POINTER(_GenParams), vp, vp, vp, vp, vp, vp, sz, vp]
         lib.esc_convattn_fused_forward.restype = ci
+        lib.esc_dense_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        lib.esc_dense_workspace_bytes.restype = sz
+        lib.esc_convattn_dense_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci,
+                                                   ctypes.POINTER(_GenParams), vp, vp, vp, sz, vp]
+        lib.esc_convattn_dense_forward.restype = ci
         lib.esc_status_string.argtypes = [ci]
         lib.esc_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -278,4 +284,38 @@ def convattn_fused_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, w_fuse: t
         _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk_c), _ptr(lk), Ks, stride,
         ctypes.byref(gen.c) if gen is not None else None, _ptr(dk_in), _ptr(w_fuse), _ptr(b_fuse), _ptr(residual),
         _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out
+
+
+def new_dense_workspace(N: int, Ca: int, H: int, W: int, Ks: int, device="cuda", stream=None) -> torch.Tensor:
+    """Allocate (with torch) and prepare a workspace for esc_convattn_dense_forward."""
+    nbytes = int(load_library().esc_dense_workspace_bytes(N, Ca, H, W, Ks))
+    if nbytes == 0:
+        raise ValueError("bad shape for a workspace")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    workspace_init(ws, stream)
+    return ws
+
+
+def convattn_dense_forward(x: torch.Tensor, Ca: int, lk_dense: torch.Tensor, workspace: torch.Tensor,
+                           gen: Optional[GenParams] = None, dk_in: Optional[torch.Tensor] = None,
+                           out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """esc_convattn_dense_forward.  lk_dense is [Ca, Ca, Ks, Ks], output channel first."""
+    dt, (N, C, H, W) = _x_checked(x)
+    _dev_f32(lk_dense, "lk_dense")
+    if lk_dense.dim() != 4 or lk_dense.shape[0] != Ca or lk_dense.shape[1] != Ca or lk_dense.shape[2] != lk_dense.shape[3]:
+        raise ValueError(f"lk_dense must be [Ca, Ca, Ks, Ks] with Ca = {Ca}; got {tuple(lk_dense.shape)}")
+    Ks = int(lk_dense.shape[2])
+    if gen is not None:
+        gen.check(int(Ca))
+    _dev_f32(dk_in, "dk_in")
+    if dk_in is not None and dk_in.numel() != N * Ca * 9:
+        raise ValueError("dk_in must hold [N, Ca, 3, 3] values")
+    if out is None:
+        out = torch.empty_like(x)
+    if out.dtype != x.dtype or out.shape != x.shape or not out.is_contiguous():
+        raise TypeError("out must match x in dtype and shape and be contiguous")
+    _check(load_library().esc_convattn_dense_forward(
+        _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk_dense), Ks, ctypes.byref(gen.c) if gen is not None else None,
+        _ptr(dk_in), _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
     return out

@@ -8,6 +8,7 @@
 #include <stdlib.h>
 
 #include "esc_kernels.hpp"
+#include "esc_dense.hpp"
 #include "esc_pointwise.hpp"
 
 namespace esc {
@@ -447,6 +448,25 @@ bool fused_layout(int N, int Ca, int H, int W, esc_dtype dt, bool with_lkc, Fuse
     return true;
 }
 
+// Workspace of esc_convattn_dense_forward: the forward's own workspace (the estimator
+// launch uses its mailboxes), then DK [N,C_a,3,3] fp32 and the rearranged dense weights.
+struct DenseLayout {
+    WsLayout ws;
+    size_t dk_off, wt_off, total;
+};
+
+bool dense_layout(int N, int Ca, int H, int W, int Ks, DenseLayout *d)
+{
+    if (Ks < 1 || !ws_layout(N, Ca, H, W, &d->ws)) return false;
+    size_t off = d->ws.total;
+    d->dk_off = off;
+    off += round_up((size_t)N * Ca * 9 * sizeof(float), kWsAlign);
+    d->wt_off = off;
+    off += round_up(dense_weight_floats(Ca, Ks) * sizeof(float), kWsAlign);
+    d->total = off;
+    return true;
+}
+
 // The mailboxes and counters of esc_convattn_forward_noalloc: one copy per device, in the
 // code object's data segment, so that a call needs no allocation and no preparation.  It is
 // laid out like a caller's workspace and starts out as esc_workspace_init would leave it
@@ -693,6 +713,73 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
     return launch_pointwise(pp, bf16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
 }
 
+size_t esc_dense_workspace_bytes(int N, int C_a, int H, int W, int Ks)
+{
+    DenseLayout d;
+    if (!dense_layout(N, C_a, H, W, Ks, &d)) return 0;
+    return d.total;
+}
+
+esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                      const float *lk_dense, int Ks, const esc_gen_params *gen, const float *dk_in,
+                                      void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    esc_status st = check_common(x, dt, N, C, H, W, C_a);
+    if (st != ESC_OK) return st;
+    if (out == nullptr) return ESC_ERR_NULL;
+    if (Ks < 1 || (Ks % 2) == 0) return Ks < 1 ? ESC_ERR_SHAPE : ESC_ERR_UNSUPPORTED;
+    if (Ks > kDenseMaxKs || C_a > kDenseMaxCa) return ESC_ERR_UNSUPPORTED;
+    if (C_a > 0 && lk_dense == nullptr) return ESC_ERR_NULL;
+    if (gen != nullptr && (st = check_gen(gen, C_a)) != ESC_OK) return st;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    if (((uintptr_t)out % es) != 0) return ESC_ERR_SHAPE;
+    const size_t bytes = (size_t)N * C * H * W * es;
+    if (overlaps(x, bytes, out, bytes)) return ESC_ERR_ALIAS;
+    DenseLayout d;
+    if (!dense_layout(N, C_a, H, W, Ks, &d)) return ESC_ERR_SHAPE;
+    if ((st = check_ws(workspace, workspace_bytes, d.total)) != ESC_OK) return st;
+    if (overlaps(workspace, workspace_bytes, out, bytes) || overlaps(workspace, workspace_bytes, x, bytes))
+        return ESC_ERR_ALIAS;
+    if (C_a > 0) {
+        if (overlaps(lk_dense, (size_t)C_a * C_a * Ks * Ks * sizeof(float), out, bytes)) return ESC_ERR_ALIAS;
+        if (gen == nullptr && dk_in != nullptr && overlaps(dk_in, (size_t)N * C_a * 9 * sizeof(float), out, bytes))
+            return ESC_ERR_ALIAS;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (C_a == 0)  // nothing but the pass-through copy: the plain forward does that
+        return enqueue_forward(x, dt, N, C, H, W, 0, nullptr, Ks, 0, nullptr, nullptr, out, C, true, workspace, d.ws, s);
+    char *w = (char *)workspace;
+    const float *dk = dk_in;
+    if (gen != nullptr) {  // Eq. 4 line 2: one launch of the variant without conv items
+        float *dk_ws = (float *)(w + d.dk_off);
+        if ((st = enqueue_dynkernel(x, dt, N, C, H, W, C_a, gen, dk_ws, workspace, d.ws, s)) != ESC_OK) return st;
+        dk = dk_ws;
+    }
+    float *wt = (float *)(w + d.wt_off);
+    if (launch_dense_weights(lk_dense, C_a, Ks, wt, s) != hipSuccess) return ESC_ERR_HIP;
+    DenseParams p{};
+    p.x = x;
+    p.out = out;
+    p.wt = wt;
+    p.dk = dk;
+    p.N = N;
+    p.C = C;
+    p.Ca = C_a;
+    p.H = H;
+    p.W = W;
+    p.Ks = Ks;
+    p.elem_bytes = (int)es;
+    if (C_a < C) {
+        const size_t plane = (size_t)H * W * es;
+        p.img_bytes = plane * C;
+        p.idt_off = plane * C_a;
+        p.idt_len = plane * (C - C_a);
+        p.copy_vec = ((uintptr_t)x % 16 == 0) && ((uintptr_t)out % 16 == 0) && (p.img_bytes % 16 == 0) &&
+                     (p.idt_off % 16 == 0);
+    }
+    return launch_dense(p, dt == ESC_BF16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
+}
+
 const char *esc_status_string(esc_status s)
 {
     switch (s) {
@@ -700,7 +787,7 @@ const char *esc_status_string(esc_status s)
     case ESC_ERR_NULL: return "a required pointer is NULL";
     case ESC_ERR_SHAPE: return "a size or stride is out of its domain";
     case ESC_ERR_DTYPE: return "unknown storage type";
-    case ESC_ERR_UNSUPPORTED: return "outside the library's limits (Ks odd <= 31, C_a <= 256, hidden <= 256; fused call: C <= 240)";
+    case ESC_ERR_UNSUPPORTED: return "outside the library's limits (Ks odd <= 31, C_a <= 256, hidden <= 256; fused call: C <= 240; dense call: C_a <= 64, Ks <= 17)";
     case ESC_ERR_WORKSPACE: return "workspace missing, misaligned or too small (esc_convattn_forward_noalloc: shape beyond the built-in scratch)";
     case ESC_ERR_ALIAS: return "out overlaps x, the workspace, lk or dk";
     case ESC_ERR_HIP: return "the HIP runtime refused a launch";

@@ -1,0 +1,319 @@
+// The ConvAttn module with the DENSE large kernel of the ESC paper's main variants
+// (Sec. 3: LK in R^{Ks x Ks x C_a x C_a}, shared by the whole model; Eq. 4 line 3
+//   F_res = F_att (*) DK + F_att (*) LK,  DK depth-wise, kept unmerged as the paper does)
+// for gfx950 (MI355X).
+//
+// A full C_a -> C_a convolution is a dense contraction over K = C_a * Ks * Ks (2704 for the
+// paper's 13 x 13 x 16 x 16), sixteen times the depth-wise form's arithmetic on the same
+// bytes: it is bound by the matrix cores, so it runs as an implicit GEMM on
+// v_mfma_f32_16x16x4_f32 (fp32 products and accumulation; bf16 storage is widened exactly
+// when a tile is staged and rounded once at the store).  Per block: an 8 x 32 pixel output
+// tile of one image, all output channels.  Sixteen input channels at a time, their
+// zero-extended halo tile sits in LDS; per kernel row the weights of its Ks taps
+// ([tap][16 co][16 ci], rearranged once per call by a small kernel so that a row is one run
+// of memory) are staged beside it, the next row's already in flight in registers.  Per tap
+// and group of four input channels a wavefront reads one A operand per 16 output channels
+// (lane l: W[co = l % 16][ci = l / 16]) and four B operands (lane l: pixel l % 16 of input
+// channel l / 16, shifted by the tap - the im2col happens in the LDS address), for its four
+// runs of 16 pixels.  DK's nine depth-wise taps are added from the same tile on the vector
+// units; the block also moves its share of the pass-through channels (Eq. 4 lines 1 and 4).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "esc_dense.hpp"
+
+namespace esc {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDnThreads = 256;
+constexpr int kDnTh = 8, kDnTw = 32;  // output tile
+constexpr unsigned kXcds = 8;
+
+struct bf16d {
+    uint16_t bits;
+};
+__device__ __forceinline__ float dn_load(const float *p) { return *p; }
+__device__ __forceinline__ float dn_load(const bf16d *p) { return __uint_as_float((uint32_t)p->bits << 16); }
+__device__ __forceinline__ uint16_t dn_f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ void dn_store(float *p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void dn_store(bf16d *p, float v) { __builtin_nontemporal_store(dn_f32_to_bf16(v), &p->bits); }
+
+// halo tile geometry for a kernel size: rows, pitch and floats per channel plane (the plane
+// stride is 16 modulo 32 banks, so the four channels of a B operand fall on both bank halves)
+__host__ __device__ inline void dense_geom(int Ks, int &hr, int &pitch, int &plane)
+{
+    const int p = (Ks - 1) / 2;
+    hr = kDnTh + 2 * p;
+    pitch = kDnTw + 2 * p;
+    plane = hr * pitch;
+    plane += (16 - plane % 32 + 32) % 32;
+}
+
+// wt[chunk][i][j][ct][ci][co] = lk[16 ct + co][16 chunk + ci][i - off][j - off], zero beyond C_a
+// and outside the Ks x Ks kernel: the kernel is embedded, centred, in a Kse x Kse one (Kse =
+// max(Ks, 3): the halo tile must also hold DK's 3 x 3 neighbourhood)
+__global__ void dense_weights_kernel(const float *lk, int Ca, int Ks, int Kse, float *wt, size_t total)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int CT = (Ca + 15) / 16, off = (Kse - Ks) / 2;
+    size_t r = idx;
+    const int co = (int)(r % 16); r /= 16;
+    const int ci = (int)(r % 16); r /= 16;
+    const int ct = (int)(r % CT); r /= CT;
+    const int j = (int)(r % Kse) - off; r /= Kse;
+    const int i = (int)(r % Kse) - off; r /= Kse;
+    const int chunk = (int)r;
+    const int o = 16 * ct + co, c = 16 * chunk + ci;
+    const bool in = o < Ca && c < Ca && i >= 0 && i < Ks && j >= 0 && j < Ks;
+    wt[idx] = in ? lk[(((size_t)o * Ca + c) * Ks + i) * Ks + j] : 0.f;
+}
+
+extern __shared__ __align__(16) float dn_lds[];
+
+template <typename T, int CT>
+__global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(const DenseParams p)
+{
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kq = lane >> 4;  // pixel (or output channel) within a run; input channel within a group of four
+    const int Ks = p.Ks, pad = (Ks - 1) / 2, H = p.H, W = p.W;
+    int HR, PITCH, PLANE;
+    dense_geom(Ks, HR, PITCH, PLANE);
+    float *s_tile = dn_lds;                 // [16][PLANE]
+    float *s_w = dn_lds + 16 * PLANE;       // [Ks][CT][16 ci][16 co]
+    const int row_floats = Ks * CT * 256;
+
+    // Blocks go to the chip's eight dies round robin; each die gets a contiguous eighth of the
+    // tiles, so that neighbouring tiles (shared halos) meet in one L2.
+    const unsigned nblk = gridDim.x, die = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const unsigned q = nblk / kXcds, rem = nblk % kXcds;
+    const unsigned tile_id = die * q + (die < rem ? die : rem) + slot;
+    const unsigned per_img = (unsigned)(p.tiles_x * p.tiles_y);
+    const unsigned n = tile_id / per_img, t_in = tile_id - n * per_img;
+    const int tyi = (int)(t_in / (unsigned)p.tiles_x), txi = (int)(t_in - (unsigned)tyi * p.tiles_x);
+    const int y0 = tyi * kDnTh, x0 = txi * kDnTw;
+    const size_t plane_px = (size_t)H * W;
+    const T *xn = (const T *)p.x + (size_t)n * p.C * plane_px;
+
+    // ---- the block's share of the pass-through copy (Eq. 4 lines 1 and 4): issued first, it
+    // streams while the first tile and weights arrive ----
+    if (p.idt_len > 0) {
+        const char *src = (const char *)p.x + (size_t)n * p.img_bytes + p.idt_off;
+        char *dst = (char *)p.out + (size_t)n * p.img_bytes + p.idt_off;
+        const size_t begin = (size_t)t_in * p.copy_share;
+        const size_t end = begin + p.copy_share < p.idt_len ? begin + p.copy_share : p.idt_len;
+        if (p.copy_vec) {
+            for (size_t o0 = begin; o0 < end; o0 += (size_t)4 * kDnThreads * 16) {
+                u32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const size_t o = o0 + ((size_t)u * kDnThreads + tid) * 16;
+                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (o + 16 <= end ? o : begin)));
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const size_t o = o0 + ((size_t)u * kDnThreads + tid) * 16;
+                    if (o + 16 <= end) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4 *>(dst + o));
+                }
+            }
+        } else {
+            const size_t eb = (size_t)p.elem_bytes;
+            for (size_t o = begin + (size_t)tid * eb; o < end; o += (size_t)kDnThreads * eb) {
+                if (eb == 4)
+                    *reinterpret_cast<uint32_t *>(dst + o) = *reinterpret_cast<const uint32_t *>(src + o);
+                else
+                    *reinterpret_cast<uint16_t *>(dst + o) = *reinterpret_cast<const uint16_t *>(src + o);
+            }
+        }
+    }
+
+    // this wavefront's four runs of 16 pixels: rows 2*wave and 2*wave + 1 of the tile, two halves each
+    f32x4 acc[CT][4];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[ct][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    constexpr int kWPer = (kDenseMaxKs * CT * 256 + kDnThreads * 4 - 1) / (kDnThreads * 4);  // 16-byte pieces of a weight row per thread, at most
+    for (int chunk = 0; chunk < CT; ++chunk) {
+        // ---- the zero-extended halo tile of input channels 16*chunk .. +15 ----
+        __syncthreads();  // the previous chunk's tile and weights are no longer read
+        {
+            const int hc = kDnTw + 2 * pad;
+            const int total = 16 * HR * hc;
+            for (int i0 = 0; i0 < total; i0 += 8 * kDnThreads) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = i0 + u * kDnThreads + tid;
+                    const int ci = idx / (HR * hc), r2 = idx - ci * (HR * hc), r = r2 / hc, c = r2 - r * hc;
+                    const int gy = y0 - pad + r, gx = x0 - pad + c, ch = 16 * chunk + ci;
+                    const bool in = idx < total && ch < p.Ca && gy >= 0 && gy < H && gx >= 0 && gx < W;
+                    v[u] = dn_load(xn + (in ? (size_t)ch * plane_px + (size_t)gy * W + gx : 0));
+                    v[u] = in ? v[u] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = i0 + u * kDnThreads + tid;
+                    const int ci = idx / (HR * hc), r2 = idx - ci * (HR * hc), r = r2 / hc, c = r2 - r * hc;
+                    if (idx < total) s_tile[ci * PLANE + r * PITCH + c] = v[u];
+                }
+            }
+        }
+        // ---- kernel rows: row i's weights in LDS while row i + 1's are in flight in registers ----
+        const float *wt_chunk = p.wt + (size_t)chunk * Ks * row_floats;
+        const int pieces = row_floats / 4;  // 16-byte pieces per row
+        f32x4 wreg[kWPer];
+        auto fetch_row = [&](int i) {
+#pragma unroll
+            for (int u = 0; u < kWPer; ++u) {
+                const int pc = u * kDnThreads + tid;
+                wreg[u] = *reinterpret_cast<const f32x4 *>(wt_chunk + (size_t)i * row_floats + 4 * (pc < pieces ? pc : 0));
+            }
+        };
+        fetch_row(0);
+        for (int i = 0; i < Ks; ++i) {
+            __syncthreads();  // row i - 1's taps are done with the weight area (and, for i == 0, the tile is written)
+#pragma unroll
+            for (int u = 0; u < kWPer; ++u) {
+                const int pc = u * kDnThreads + tid;
+                if (pc < pieces) *reinterpret_cast<f32x4 *>(s_w + 4 * pc) = wreg[u];
+            }
+            __syncthreads();
+            if (i + 1 < Ks) fetch_row(i + 1);
+            for (int j = 0; j < Ks; ++j) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float b[4];
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) {
+                        const int r = 2 * wave + (nt >> 1), c = 16 * (nt & 1);
+                        b[nt] = s_tile[(4 * g + kq) * PLANE + (r + i) * PITCH + c + j + l16];
+                    }
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const float a = s_w[((j * CT + ct) * 16 + 4 * g + kq) * 16 + l16];
+#pragma unroll
+                        for (int nt = 0; nt < 4; ++nt)
+                            acc[ct][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[nt], acc[ct][nt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        // ---- DK's nine depth-wise taps for the output channels of this chunk, from the same
+        // tile: lane l holds output channels 16*chunk + 4*(l / 16) + r, r < 4, of pixel l % 16 ----
+        if (p.dk != nullptr) {
+            float d[4][9];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int co = 16 * chunk + 4 * kq + r;
+#pragma unroll
+                for (int k = 0; k < 9; ++k) d[r][k] = p.dk[((size_t)n * p.Ca + (co < p.Ca ? co : p.Ca - 1)) * 9 + k];
+            }
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                const int rr = 2 * wave + (nt >> 1), c = 16 * (nt & 1);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float *src = s_tile + (4 * kq + r) * PLANE + (rr + pad - 1) * PITCH + c + pad - 1 + l16;
+                    float s = 0.f;
+#pragma unroll
+                    for (int di = 0; di < 3; ++di)
+#pragma unroll
+                        for (int dj = 0; dj < 3; ++dj) s = fmaf(d[r][di * 3 + dj], src[di * PITCH + dj], s);
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct)  // (a constant index: the accumulators stay in registers)
+                        if (ct == chunk) acc[ct][nt][r] += s;
+                }
+            }
+        }
+    }
+
+    // ---- store: one rounding to the storage type ----
+    T *on = (T *)p.out + (size_t)n * p.C * plane_px;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const int gy = y0 + 2 * wave + (nt >> 1), gx = x0 + 16 * (nt & 1) + l16;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int co = 16 * ct + 4 * kq + r;
+                if (co < p.Ca && gy < H && gx < W) dn_store(on + (size_t)co * plane_px + (size_t)gy * W + gx, acc[ct][nt][r]);
+            }
+        }
+}
+
+template <typename T, int CT>
+hipError_t launch_ct(const DenseParams &p, unsigned grid, size_t lds, hipStream_t s)
+{
+    static size_t granted = 48 * 1024;
+    if (lds > granted) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dense_kernel<T, CT>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        granted = lds;
+    }
+    hipLaunchKernelGGL((dense_kernel<T, CT>), dim3(grid), dim3(kDnThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_t(const DenseParams &p, int ct, unsigned grid, size_t lds, hipStream_t s)
+{
+    switch (ct) {
+    case 1: return launch_ct<T, 1>(p, grid, lds, s);
+    case 2: return launch_ct<T, 2>(p, grid, lds, s);
+    case 3: return launch_ct<T, 3>(p, grid, lds, s);
+    case 4: return launch_ct<T, 4>(p, grid, lds, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+__attribute__((visibility("hidden"))) hipError_t launch_dense_weights(const float *lk, int Ca, int Ks, float *wt, hipStream_t s)
+{
+    const int Kse = dense_effective_ks(Ks);
+    const size_t total = dense_weight_floats(Ca, Ks);
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(dense_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, lk, Ca, Ks, Kse, wt, total);
+    return hipGetLastError();
+}
+
+__attribute__((visibility("hidden"))) hipError_t launch_dense(const DenseParams &p_in, bool bf16, hipStream_t s)
+{
+    DenseParams p = p_in;
+    p.Ks = dense_effective_ks(p.Ks);  // the kernel walks the embedding kernel (launch_dense_weights)
+    if (p.Ca < 1 || p.Ca > kDenseMaxCa || p.Ks < 1 || p.Ks > kDenseMaxKs) return hipErrorInvalidValue;
+    const int ct = (p.Ca + 15) / 16;
+    p.tiles_x = (p.W + kDnTw - 1) / kDnTw;
+    p.tiles_y = (p.H + kDnTh - 1) / kDnTh;
+    const size_t per_img = (size_t)p.tiles_x * p.tiles_y;
+    const size_t grid = per_img * p.N;
+    if (grid >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    if (p.idt_len > 0) {
+        // every block of an image moves an equal share, in whole 16 KiB rounds when vector accesses apply
+        const size_t grain = p.copy_vec ? (size_t)4 * kDnThreads * 16 : (size_t)p.elem_bytes;
+        size_t share = (p.idt_len + per_img - 1) / per_img;
+        share = (share + grain - 1) / grain * grain;
+        p.copy_share = share;
+    }
+    int hr, pitch, plane;
+    dense_geom(p.Ks, hr, pitch, plane);
+    const size_t lds = ((size_t)16 * plane + (size_t)p.Ks * ct * 256) * sizeof(float);
+    return bf16 ? launch_t<bf16d>(p, ct, (unsigned)grid, lds, s) : launch_t<float>(p, ct, (unsigned)grid, lds, s);
+}
+
+}  // namespace esc

@@ -1,0 +1,38 @@
+// Interface between the host side (esc_api.hip) and the dense large-kernel convolution
+// kernels (esc_dense.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace esc {
+
+constexpr int kDenseMaxCa = 64;   // attention channels the dense form handles (four tiles of 16)
+constexpr int kDenseMaxKs = 17;   // largest dense kernel (its halo tile and weight rows must fit in LDS)
+
+struct DenseParams {
+    const void *x;      // [N,C,H,W] storage type
+    void *out;          // [N,C,H,W] storage type
+    const float *wt;    // weights rearranged by launch_dense_weights (workspace)
+    const float *dk;    // [N,Ca,3,3] fp32 or nullptr (DK = 0)
+    int N, C, Ca, H, W, Ks;
+    int tiles_x, tiles_y;
+    // pass-through copy: every block moves `copy_share` bytes (a multiple of 4096, or the whole
+    // range by elements when copy_vec is 0) of its image's identity range [idt_off, idt_off + idt_len)
+    size_t img_bytes, idt_off, idt_len, copy_share;
+    int copy_vec, elem_bytes;
+};
+
+// the kernel size the device code walks: a 1 x 1 kernel is embedded in a 3 x 3 one
+inline int dense_effective_ks(int Ks) { return Ks < 3 ? 3 : Ks; }
+
+// floats the rearranged weights take: [CT chunks][Kse rows][Kse taps][CT][16 ci][16 co]
+inline size_t dense_weight_floats(int Ca, int Ks)
+{
+    const size_t ct = (size_t)(Ca + 15) / 16, kse = (size_t)dense_effective_ks(Ks);
+    return ct * kse * kse * ct * 256;
+}
+
+hipError_t launch_dense_weights(const float *lk, int Ca, int Ks, float *wt, hipStream_t s);
+hipError_t launch_dense(const DenseParams &p, bool bf16, hipStream_t s);
+
+}  // namespace esc
