@@ -59,6 +59,8 @@ def parse_args():
     ap.add_argument("--no-floors", action="store_true", help="skip the copy-only and empty-call floors")
     ap.add_argument("--fused", action="store_true",
                     help="time esc_convattn_fused_forward (the module with Conv_fuse, Eq. 4 line 4) instead")
+    ap.add_argument("--dense", action="store_true",
+                    help="time esc_convattn_dense_forward (dense Ks x Ks x C_a x C_a large kernel of the paper's main variants) instead")
     ap.add_argument("--lkc", action="store_true", help="with --fused: LK^c in front of the depth-wise kernels (Eq. 5)")
     ap.add_argument("--residual", action="store_true", help="with --fused: add the residual of Eq. 3 line 3")
     return ap.parse_args()
@@ -174,10 +176,27 @@ def fused_roofline_of(wl, sec, lkc, residual):
             "mfma_tflops": f_mat / sec / 1e12}
 
 
+def dense_roofline_of(wl, sec):
+    """The dense-LK call: same bytes as the depth-wise forward; the C_a x C_a x Ks x Ks contraction on the
+    matrix cores in fp32, DK's nine taps on the vector units."""
+    P = wl.N * wl.H * wl.W
+    b_alg = 2.0 * P * wl.C * wl.elem_bytes
+    f_mat = 2.0 * wl.Ks * wl.Ks * wl.Ca * wl.Ca * P
+    t_hbm, t_mat = b_alg / (HBM_PEAK_GBS * 1e9), f_mat / (FP32_MFMA_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mat:
+        r = {"bound": "hbm", "achieved": b_alg / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        r = {"bound": "mfma", "achieved": f_mat / sec / 1e12, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    r["frac"] = r["achieved"] / r["peak"]
+    r.update({"algorithmic_bytes": b_alg, "algorithmic_flops_matrix": f_mat, "hbm_gbps": b_alg / sec / 1e9,
+              "mfma_tflops": f_mat / sec / 1e12, "alu_tflops": 0.0})
+    return r
+
+
 class Runner:
     """Device buffers of one workload and the timing protocol."""
 
-    def __init__(self, wl, rotate_bytes, warm_cache, ca=None, fused=None):
+    def __init__(self, wl, rotate_bytes, warm_cache, ca=None, fused=None, dense=False):
         import numpy as np
         import torch
         from paper_2503_06671_amd import binding, workloads as wk
@@ -200,7 +219,13 @@ class Runner:
         if self.ca > 0:
             self.gen = binding.GenParams(dev(wl.w_up), dev(wl.b_up), wl.hidden, dev(wl.w_down), dev(wl.b_down))
         self.fused = fused
-        if fused is None:
+        self.dense = dense
+        if dense:
+            # seeded dense large kernel [C_a, C_a, Ks, Ks] ~ N(0, 1 / (Ks^2 C_a))
+            rng = np.random.default_rng(2000 + wl.Ks)
+            self.lk_dense = dev((rng.standard_normal((wl.Ca, wl.Ca, wl.Ks, wl.Ks)) / (wl.Ks * np.sqrt(wl.Ca))).astype(np.float32))
+            self.ws = binding.new_dense_workspace(wl.N, self.ca, wl.H, wl.W, wl.Ks)
+        elif fused is None:
             self.ws = binding.new_workspace(wl.N, self.ca, wl.H, wl.W)
         else:
             # seeded point-wise weights: Conv_fuse [C,C] ~ N(0, 1/C) with a small bias, LK^c [C_a,C_a] ~ N(0, 1/C_a)
@@ -214,6 +239,10 @@ class Runner:
 
     def step(self, i):
         k = i % self.pairs
+        if self.dense:
+            self.binding.convattn_dense_forward(self.xs[k], self.ca, self.lk_dense, self.ws, gen=self.gen, out=self.outs[k],
+                                                stream=self.stream)
+            return
         if self.fused is not None:
             self.binding.convattn_fused_forward(
                 self.xs[k], self.ca, self.lk, self.w_fuse, self.ws, b_fuse=self.b_fuse, lk_c=self.lk_c,
@@ -296,7 +325,7 @@ def main():
     replays = replays_for(args.steps, args.replays)
 
     fused = {"lkc": args.lkc, "residual": args.residual} if args.fused else None
-    run = Runner(wl, args.rotate_bytes, args.warm_cache, fused=fused)
+    run = Runner(wl, args.rotate_bytes, args.warm_cache, fused=fused, dense=args.dense)
     t = run.time(args.steps, args.warmup, replays, eager=args.eager)
     ms_step = t["median"]
     # spot check of the last buffers against the first (same input => same bits)
@@ -305,7 +334,7 @@ def main():
     latency_us = run.single_call_latency_us()
 
     floors = None
-    if not args.no_floors and fused is None:
+    if not args.no_floors and fused is None and not args.dense:
         # the library's own pure copy (C_a = 0) on the same tensors and rotation, and a call
         # with nothing to do (1 x 1 x 1 x 1, C_a = 0): what is left above them is the method's
         copy_t = Runner(wl, args.rotate_bytes, args.warm_cache, ca=0).time(args.steps, min(args.warmup, 200), replays,
@@ -322,12 +351,17 @@ def main():
     if fused is not None:
         wl_name += "_fused" + ("_lkc" if args.lkc else "") + ("_res" if args.residual else "")
         roof = fused_roofline_of(wl, sec, args.lkc, args.residual)
+    elif args.dense:
+        wl_name += "_dense"
+        roof = dense_roofline_of(wl, sec)
     else:
         roof = roofline_of(wl, sec)
     traffic, traffic_src = (None, None) if args.warm_cache else profiled_traffic(wl_name)
     roof.update({
         "kernel": (f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)"
-                   if fused is None else
+                   if fused is None and not args.dense else
+                   "dense_kernel (implicit GEMM on the matrix cores, DK taps, pass-through share) after the estimator launch and the weight rearrangement"
+                   if args.dense else
                    "forward_kernel (F_res into the workspace) + pointwise_kernel (Conv_fuse on the matrix cores)"
                    + ("; with LK^c also the estimator launch and a second pointwise_kernel" if args.lkc else "")),
         "traffic": traffic, "traffic_source": traffic_src,
@@ -336,7 +370,8 @@ def main():
         "kernel_us": ms_step * 1e3,
     })
     res = {
-        "metric": "convattn_fwd_mpixel_per_s" if fused is None else "convattn_fused_fwd_mpixel_per_s",
+        "metric": ("convattn_dense_fwd_mpixel_per_s" if args.dense else
+                   "convattn_fwd_mpixel_per_s" if fused is None else "convattn_fused_fwd_mpixel_per_s"),
         "value": wl.pixels / sec / 1e6,
         "unit": "Mpixel/s",
         "n_gpus": 1,
@@ -402,6 +437,22 @@ def main():
             del r2
             torch.cuda.empty_cache()
         res["fused_workloads"] = fus
+        # the module with the dense 13 x 13 x 16 x 16 large kernel of the paper's main variants
+        den = []
+        for idx in (1, 2):
+            w2 = wk.make_config(idx)
+            if args.dense and w2.name + "_dense" == wl_name:
+                continue
+            r2 = Runner(w2, args.rotate_bytes, args.warm_cache, dense=True)
+            t2 = r2.time(100, 100, 15, eager=args.eager)
+            s2 = t2["median"] * 1e-3
+            rf = dense_roofline_of(w2, s2)
+            den.append({"workload": w2.name + "_dense", "dtype": wk.DTYPE_NAMES[w2.dtype], "us_per_step": t2["median"] * 1e3,
+                        "mpixel_per_s": w2.pixels / s2 / 1e6, "bound": rf["bound"], "frac": rf["frac"],
+                        "hbm_gbps": rf["hbm_gbps"], "mfma_tflops": rf["mfma_tflops"], "steps": 100, "warmup": 100, "replays": 15})
+            del r2
+            torch.cuda.empty_cache()
+        res["dense_workloads"] = den
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
