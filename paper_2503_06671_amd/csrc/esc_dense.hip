@@ -7,8 +7,8 @@
 // paper's 13 x 13 x 16 x 16), sixteen times the depth-wise form's arithmetic on the same
 // bytes: it is bound by the matrix cores, so it runs as an implicit GEMM on
 // v_mfma_f32_16x16x4_f32 (fp32 products and accumulation; bf16 storage is widened exactly
-// when a tile is staged and rounded once at the store).  Per block: an 8 x 32 pixel output
-// tile of one image, all output channels.  Sixteen input channels at a time, their
+// when a tile is staged and rounded once at the store).  Per block: an 8 x 32 (small calls:
+// 4 x 32) pixel output tile of one image, all output channels.  Sixteen input channels at a time, their
 // zero-extended halo tile sits in LDS; per kernel row the weights of its Ks taps
 // ([tap][16 co][16 ci], rearranged once per call by a small kernel so that a row is one run
 // of memory) are staged beside it, the next row's already in flight in registers.  Per tap
@@ -31,7 +31,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kDnThreads = 256;
-constexpr int kDnTh = 8, kDnTw = 32;  // output tile
+constexpr int kDnTw = 32;  // output tile width; its height TH is 8, or 4 when that is needed to fill the chip
 constexpr unsigned kXcds = 8;
 
 struct bf16d {
@@ -51,10 +51,10 @@ __device__ __forceinline__ void dn_store(bf16d *p, float v) { __builtin_nontempo
 
 // halo tile geometry for a kernel size: rows, pitch and floats per channel plane (the plane
 // stride is 16 modulo 32 banks, so the four channels of a B operand fall on both bank halves)
-__host__ __device__ inline void dense_geom(int Ks, int &hr, int &pitch, int &plane)
+__host__ __device__ inline void dense_geom(int Ks, int th, int &hr, int &pitch, int &plane)
 {
     const int p = (Ks - 1) / 2;
-    hr = kDnTh + 2 * p;
+    hr = th + 2 * p;
     pitch = kDnTw + 2 * p;
     plane = hr * pitch;
     plane += (16 - plane % 32 + 32) % 32;
@@ -82,14 +82,16 @@ __global__ void dense_weights_kernel(const float *lk, int Ca, int Ks, int Kse, f
 
 extern __shared__ __align__(16) float dn_lds[];
 
-template <typename T, int CT>
+template <typename T, int CT, int TH>
 __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(const DenseParams p)
 {
+    constexpr int NT = TH / 2;  // runs of 16 pixels per wavefront: rows (TH/4)*wave .., two halves each
+    constexpr int RW = TH / 4;
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kq = lane >> 4;  // pixel (or output channel) within a run; input channel within a group of four
     const int Ks = p.Ks, pad = (Ks - 1) / 2, H = p.H, W = p.W;
     int HR, PITCH, PLANE;
-    dense_geom(Ks, HR, PITCH, PLANE);
+    dense_geom(Ks, TH, HR, PITCH, PLANE);
     float *s_tile = dn_lds;                 // [16][PLANE]
     float *s_w = dn_lds + 16 * PLANE;       // [Ks][CT][16 ci][16 co]
     const int row_floats = Ks * CT * 256;
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
     const unsigned per_img = (unsigned)(p.tiles_x * p.tiles_y);
     const unsigned n = tile_id / per_img, t_in = tile_id - n * per_img;
     const int tyi = (int)(t_in / (unsigned)p.tiles_x), txi = (int)(t_in - (unsigned)tyi * p.tiles_x);
-    const int y0 = tyi * kDnTh, x0 = txi * kDnTw;
+    const int y0 = tyi * TH, x0 = txi * kDnTw;
     const size_t plane_px = (size_t)H * W;
     const T *xn = (const T *)p.x + (size_t)n * p.C * plane_px;
 
@@ -138,12 +140,11 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
         }
     }
 
-    // this wavefront's four runs of 16 pixels: rows 2*wave and 2*wave + 1 of the tile, two halves each
-    f32x4 acc[CT][4];
+    f32x4 acc[CT][NT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) acc[ct][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int nt = 0; nt < NT; ++nt) acc[ct][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     constexpr int kWPer = (kDenseMaxKs * CT * 256 + kDnThreads * 4 - 1) / (kDnThreads * 4);  // 16-byte pieces of a weight row per thread, at most
     for (int chunk = 0; chunk < CT; ++chunk) {
@@ -195,17 +196,17 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
             for (int j = 0; j < Ks; ++j) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    float b[4];
+                    float b[NT];
 #pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) {
-                        const int r = 2 * wave + (nt >> 1), c = 16 * (nt & 1);
+                    for (int nt = 0; nt < NT; ++nt) {
+                        const int r = RW * wave + (nt >> 1), c = 16 * (nt & 1);
                         b[nt] = s_tile[(4 * g + kq) * PLANE + (r + i) * PITCH + c + j + l16];
                     }
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
                         const float a = s_w[((j * CT + ct) * 16 + 4 * g + kq) * 16 + l16];
 #pragma unroll
-                        for (int nt = 0; nt < 4; ++nt)
+                        for (int nt = 0; nt < NT; ++nt)
                             acc[ct][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[nt], acc[ct][nt], 0, 0, 0);
                     }
                 }
@@ -222,8 +223,8 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
                 for (int k = 0; k < 9; ++k) d[r][k] = p.dk[((size_t)n * p.Ca + (co < p.Ca ? co : p.Ca - 1)) * 9 + k];
             }
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                const int rr = 2 * wave + (nt >> 1), c = 16 * (nt & 1);
+            for (int nt = 0; nt < NT; ++nt) {
+                const int rr = RW * wave + (nt >> 1), c = 16 * (nt & 1);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float *src = s_tile + (4 * kq + r) * PLANE + (rr + pad - 1) * PITCH + c + pad - 1 + l16;
@@ -245,8 +246,8 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const int gy = y0 + 2 * wave + (nt >> 1), gx = x0 + 16 * (nt & 1) + l16;
+        for (int nt = 0; nt < NT; ++nt) {
+            const int gy = y0 + RW * wave + (nt >> 1), gx = x0 + 16 * (nt & 1) + l16;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int co = 16 * ct + 4 * kq + r;
@@ -255,28 +256,28 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
         }
 }
 
-template <typename T, int CT>
+template <typename T, int CT, int TH>
 hipError_t launch_ct(const DenseParams &p, unsigned grid, size_t lds, hipStream_t s)
 {
     static size_t granted = 48 * 1024;
     if (lds > granted) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dense_kernel<T, CT>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dense_kernel<T, CT, TH>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         granted = lds;
     }
-    hipLaunchKernelGGL((dense_kernel<T, CT>), dim3(grid), dim3(kDnThreads), lds, s, p);
+    hipLaunchKernelGGL((dense_kernel<T, CT, TH>), dim3(grid), dim3(kDnThreads), lds, s, p);
     return hipGetLastError();
 }
 
-template <typename T>
+template <typename T, int TH>
 hipError_t launch_t(const DenseParams &p, int ct, unsigned grid, size_t lds, hipStream_t s)
 {
     switch (ct) {
-    case 1: return launch_ct<T, 1>(p, grid, lds, s);
-    case 2: return launch_ct<T, 2>(p, grid, lds, s);
-    case 3: return launch_ct<T, 3>(p, grid, lds, s);
-    case 4: return launch_ct<T, 4>(p, grid, lds, s);
+    case 1: return launch_ct<T, 1, TH>(p, grid, lds, s);
+    case 2: return launch_ct<T, 2, TH>(p, grid, lds, s);
+    case 3: return launch_ct<T, 3, TH>(p, grid, lds, s);
+    case 4: return launch_ct<T, 4, TH>(p, grid, lds, s);
     }
     return hipErrorInvalidValue;
 }
@@ -298,8 +299,18 @@ __attribute__((visibility("hidden"))) hipError_t launch_dense(const DenseParams 
     p.Ks = dense_effective_ks(p.Ks);  // the kernel walks the embedding kernel (launch_dense_weights)
     if (p.Ca < 1 || p.Ca > kDenseMaxCa || p.Ks < 1 || p.Ks > kDenseMaxKs) return hipErrorInvalidValue;
     const int ct = (p.Ca + 15) / 16;
+    // 8-row tiles, or 4-row ones while those are needed to give every compute unit two blocks
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return hipErrorInvalidDevice;
+        cus = n > 0 ? n : 1;
+    }
     p.tiles_x = (p.W + kDnTw - 1) / kDnTw;
-    p.tiles_y = (p.H + kDnTh - 1) / kDnTh;
+    const size_t blocks8 = (size_t)p.tiles_x * ((p.H + 7) / 8) * p.N;
+    const int th = blocks8 >= 2 * (size_t)cus ? 8 : 4;
+    p.tiles_y = (p.H + th - 1) / th;
     const size_t per_img = (size_t)p.tiles_x * p.tiles_y;
     const size_t grid = per_img * p.N;
     if (grid >= ((size_t)1 << 31)) return hipErrorInvalidValue;
@@ -311,9 +322,11 @@ __attribute__((visibility("hidden"))) hipError_t launch_dense(const DenseParams 
         p.copy_share = share;
     }
     int hr, pitch, plane;
-    dense_geom(p.Ks, hr, pitch, plane);
+    dense_geom(p.Ks, th, hr, pitch, plane);
     const size_t lds = ((size_t)16 * plane + (size_t)p.Ks * ct * 256) * sizeof(float);
-    return bf16 ? launch_t<bf16d>(p, ct, (unsigned)grid, lds, s) : launch_t<float>(p, ct, (unsigned)grid, lds, s);
+    if (th == 8)
+        return bf16 ? launch_t<bf16d, 8>(p, ct, (unsigned)grid, lds, s) : launch_t<float, 8>(p, ct, (unsigned)grid, lds, s);
+    return bf16 ? launch_t<bf16d, 4>(p, ct, (unsigned)grid, lds, s) : launch_t<float, 4>(p, ct, (unsigned)grid, lds, s);
 }
 
 }  // namespace esc
