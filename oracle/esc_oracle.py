@@ -16,7 +16,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, f) for f in ("esc_oracle.c", "esc_oracle_fuse.c", "esc_oracle_dense.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("esc_oracle.c", "esc_oracle_fuse.c", "esc_oracle_dense.c", "esc_oracle_backward.c")]
 _LIB = os.path.join(_HERE, "libesc_oracle.so")
 
 F32 = 0
@@ -65,6 +65,9 @@ def _load():
         lib.esc_oracle_convattn_dense_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci, ci, ci,
                                                           vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.esc_oracle_convattn_dense_forward.restype = ci
+        lib.esc_oracle_convattn_backward.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, cl, ci, ci, vp, vp, vp, vp,
+                                                     vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.esc_oracle_convattn_backward.restype = ci
         lib.esc_oracle_f32_to_bf16.argtypes = [ctypes.c_float]
         lib.esc_oracle_f32_to_bf16.restype = ctypes.c_uint16
         lib.esc_oracle_threads.restype = ci
@@ -305,3 +308,42 @@ def convattn_dense_forward(x: np.ndarray, Ca: int, lk: np.ndarray, dtype: int = 
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return res, dk, out
+
+
+# ---------------------------------------------------------------- backward (esc_oracle_backward.c)
+
+def convattn_backward(x: np.ndarray, go: np.ndarray, Ca: int, lk: np.ndarray, dtype: int = F32, *, hidden: int = 0,
+                      w_up=None, b_up=None, w_down=None, b_down=None, dk_in=None):
+    """Gradients of the depth-wise ConvAttn forward (Eq. 4 lines 1-4 without Conv_fuse) for an upstream
+    gradient go = dL/dout.  Returns a dict of float64 arrays: dx [N,C,H,W], dlk (shape of lk), ddk [N,Ca,3,3],
+    dg [N,Ca] and, when estimator weights are given, dw_up, db_up (and dw_down, db_down when hidden > 0)."""
+    x, go = _x(x, dtype), _x(go, dtype)
+    assert go.shape == x.shape
+    N, C, H, W = x.shape
+    lk, Ks, cs = _lk_stride(lk, Ca)
+    if w_up is not None and dk_in is not None:
+        raise ValueError("give either estimator weights or dk_in, not both")
+    mode = 1 if w_up is not None else (2 if dk_in is not None else 0)
+    w_up, b_up, w_down, b_down = _f32(w_up), _f32(b_up), _f32(w_down), _f32(b_down)
+    K = hidden if hidden > 0 else Ca
+    if mode == 1:
+        assert w_up.shape == (9 * Ca, K)
+        if hidden > 0:
+            assert w_down.shape == (hidden, Ca)
+    if dk_in is not None:
+        dk_in = np.ascontiguousarray(dk_in, dtype=np.float64)
+        assert dk_in.shape == (N, Ca, 3, 3)
+    res = {"dx": np.empty((N, C, H, W)), "dlk": np.empty(lk.shape), "ddk": np.empty((N, Ca, 3, 3)),
+           "dg": np.empty((N, Ca))}
+    if mode == 1:
+        res["dw_up"], res["db_up"] = np.empty((9 * Ca, K)), np.empty(9 * Ca)
+        if hidden > 0:
+            res["dw_down"], res["db_down"] = np.empty((hidden, Ca)), np.empty(hidden)
+    rc = _load().esc_oracle_convattn_backward(
+        _ptr(x), _ptr(go), dtype, N, C, H, W, Ca, _ptr(lk), Ks, cs, mode, hidden, _ptr(w_down), _ptr(b_down),
+        _ptr(w_up), _ptr(b_up), _ptr(dk_in), _ptr(res["dx"]), _ptr(res["dlk"]), _ptr(res["ddk"]),
+        _ptr(res.get("dw_up")), _ptr(res.get("db_up")), _ptr(res.get("dw_down")), _ptr(res.get("db_down")),
+        _ptr(res["dg"]))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return res
