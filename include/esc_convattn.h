@@ -180,6 +180,38 @@ esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C,
                                       void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Backward of esc_convattn_forward (the paper trains its shared LK end to end, Sec. 3; it
+ * prints no gradient formulae - these are the derivatives of Eq. 4 lines 1-4 as defined
+ * above).  Given grad_out = dL/dout [N,C,H,W] in the storage type:
+ *
+ *   grad_x   [N,C,H,W] storage type (written, every element): identity channels = grad_out;
+ *            attention channels = grad_out (*) flipped (LK + ZP(DK)) + the GAP path's
+ *            dL/dg / (H W)
+ *   grad_lk  fp32, laid out like lk (same channel stride; ONE Ks x Ks filter, summed over
+ *            the channels, when lk_channel_stride == 0), summed over the batch; or NULL
+ *   grad_gen gradients of the estimator's weights (each member fp32, shaped like the
+ *            weight, or NULL); ignored when gen is NULL
+ *   grad_dk  [N,C_a,3,3] fp32, dL/dDK (what a caller who supplied dk_in needs); or NULL
+ *   accumulate != 0: the parameter gradients (grad_lk, grad_gen) are ADDED to the buffers'
+ *            contents - the way a kernel shared by many modules collects its gradient
+ * x, lk, gen and dk_in are the forward's inputs.  fp32 accumulation throughout; every sum
+ * has a fixed order.  The workspace is esc_backward_workspace_bytes large, prepared with
+ * esc_workspace_init.  Seven small and large launches on `stream`.
+ */
+typedef struct esc_gen_grads {
+    float *w_down; /* [hidden, C_a] or NULL */
+    float *b_down; /* [hidden] or NULL      */
+    float *w_up;   /* [9*C_a, hidden ? hidden : C_a] or NULL */
+    float *b_up;   /* [9*C_a] or NULL       */
+} esc_gen_grads;
+size_t esc_backward_workspace_bytes(int N, int C_a, int H, int W, int Ks, int hidden);
+esc_status esc_convattn_backward(const void *x, const void *grad_out, esc_dtype dt, int N, int C, int H, int W,
+                                 int C_a, const float *lk, int Ks, long lk_channel_stride,
+                                 const esc_gen_params *gen, const float *dk_in,
+                                 void *grad_x, float *grad_lk, const esc_gen_grads *grad_gen, float *grad_dk,
+                                 int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * For callers that cannot allocate or prepare device memory (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): esc_convattn_forward
  * without the workspace arguments.  The mailboxes and counters live in a scratch array

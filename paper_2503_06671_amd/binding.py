@@ -21,7 +21,7 @@ ESC_BF16 = 1
 EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_workspace_errors", "esc_dynkernel_gen",
            "esc_convattn_forward", "esc_convattn_forward_noalloc", "esc_fused_workspace_bytes",
            "esc_convattn_fused_forward", "esc_dense_workspace_bytes", "esc_convattn_dense_forward",
-           "esc_status_string")
+           "esc_backward_workspace_bytes", "esc_convattn_backward", "esc_status_string")
 NOALLOC_SCRATCH_BYTES = 1 << 20
 
 
@@ -34,6 +34,11 @@ class EscError(RuntimeError):
 class _GenParams(ctypes.Structure):
     _fields_ = [("hidden", ctypes.c_int),
                 ("w_down", ctypes.c_void_p), ("b_down", ctypes.c_void_p),
+                ("w_up", ctypes.c_void_p), ("b_up", ctypes.c_void_p)]
+
+
+class _GenGrads(ctypes.Structure):
+    _fields_ = [("w_down", ctypes.c_void_p), ("b_down", ctypes.c_void_p),
                 ("w_up", ctypes.c_void_p), ("b_up", ctypes.c_void_p)]
 
 
@@ -75,6 +80,11 @@ def load_library():
         lib.esc_convattn_dense_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, ci,
                                                    ctypes.POINTER(_GenParams), vp, vp, vp, sz, vp]
         lib.esc_convattn_dense_forward.restype = ci
+        lib.esc_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+        lib.esc_backward_workspace_bytes.restype = sz
+        lib.esc_convattn_backward.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, cl, ctypes.POINTER(_GenParams), vp,
+                                              vp, vp, ctypes.POINTER(_GenGrads), vp, ci, vp, sz, vp]
+        lib.esc_convattn_backward.restype = ci
         lib.esc_status_string.argtypes = [ci]
         lib.esc_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -319,3 +329,56 @@ def convattn_dense_forward(x: torch.Tensor, Ca: int, lk_dense: torch.Tensor, wor
         _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk_dense), Ks, ctypes.byref(gen.c) if gen is not None else None,
         _ptr(dk_in), _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
     return out
+
+
+def new_backward_workspace(N: int, Ca: int, H: int, W: int, Ks: int, hidden: int, device="cuda", stream=None) -> torch.Tensor:
+    """Allocate (with torch) and prepare a workspace for esc_convattn_backward."""
+    nbytes = int(load_library().esc_backward_workspace_bytes(N, Ca, H, W, Ks, hidden))
+    if nbytes == 0:
+        raise ValueError("bad shape for a workspace")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    workspace_init(ws, stream)
+    return ws
+
+
+def convattn_backward(x: torch.Tensor, grad_out: torch.Tensor, Ca: int, lk: torch.Tensor, workspace: torch.Tensor,
+                      gen: Optional[GenParams] = None, dk_in: Optional[torch.Tensor] = None, accumulate: bool = False,
+                      grads: Optional[dict] = None, stream=None) -> dict:
+    """esc_convattn_backward.  Returns a dict of device tensors: grad_x, grad_lk, grad_dk and, with an
+    estimator, grad_w_up, grad_b_up (and grad_w_down, grad_b_down when hidden > 0).  `grads` may carry
+    buffers to write into (required to make sense of accumulate=True)."""
+    dt, (N, C, H, W) = _x_checked(x)
+    if grad_out.dtype != x.dtype or grad_out.shape != x.shape or not grad_out.is_contiguous() or not grad_out.is_cuda:
+        raise TypeError("grad_out must match x in dtype and shape and be a contiguous device tensor")
+    Ks, stride = _lk_checked(lk, int(Ca), None, None)
+    if gen is not None:
+        gen.check(int(Ca))
+    _dev_f32(dk_in, "dk_in")
+    if dk_in is not None and dk_in.numel() != N * Ca * 9:
+        raise ValueError("dk_in must hold [N, Ca, 3, 3] values")
+    g = dict(grads or {})
+    f32 = dict(dtype=torch.float32, device=x.device)
+    g.setdefault("grad_x", torch.empty_like(x))
+    g.setdefault("grad_lk", torch.zeros_like(lk))
+    g.setdefault("grad_dk", torch.empty((N, Ca, 3, 3), **f32))
+    gg = None
+    if gen is not None:
+        w_down, b_down, w_up, b_up = gen.tensors
+        g.setdefault("grad_w_up", torch.zeros_like(w_up))
+        if b_up is not None:
+            g.setdefault("grad_b_up", torch.zeros_like(b_up))
+        if gen.hidden > 0:
+            g.setdefault("grad_w_down", torch.zeros_like(w_down))
+            if b_down is not None:
+                g.setdefault("grad_b_down", torch.zeros_like(b_down))
+        gg = _GenGrads(_ptr(g.get("grad_w_down")), _ptr(g.get("grad_b_down")), _ptr(g.get("grad_w_up")),
+                       _ptr(g.get("grad_b_up")))
+    for k, v in g.items():
+        if k != "grad_x":
+            _dev_f32(v, k)
+    _check(load_library().esc_convattn_backward(
+        _ptr(x), _ptr(grad_out), dt, N, C, H, W, int(Ca), _ptr(lk), Ks, stride,
+        ctypes.byref(gen.c) if gen is not None else None, _ptr(dk_in), _ptr(g["grad_x"]), _ptr(g["grad_lk"]),
+        ctypes.byref(gg) if gg is not None else None, _ptr(g["grad_dk"]), int(bool(accumulate)),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    return g

@@ -8,6 +8,7 @@
 #include <stdlib.h>
 
 #include "esc_kernels.hpp"
+#include "esc_backward.hpp"
 #include "esc_dense.hpp"
 #include "esc_pointwise.hpp"
 
@@ -467,6 +468,35 @@ bool dense_layout(int N, int Ca, int H, int W, int Ks, DenseLayout *d)
     return true;
 }
 
+// Workspace of esc_convattn_backward: the forward's own workspace (the input gradient is a
+// forward launch), then the fp32 pieces BackwardParams names.
+struct BackwardLayout {
+    WsLayout ws;
+    size_t partial_off, ddk_off, g_off, t_off, du_off, dgc_off, dkf_off, lkf_off, total;
+};
+
+bool backward_layout(int N, int Ca, int H, int W, int Ks, int hidden, BackwardLayout *b)
+{
+    if (Ks < 1 || hidden < 0 || !ws_layout(N, Ca, H, W, &b->ws)) return false;
+    size_t off = b->ws.total;
+    auto take = [&](size_t floats) {
+        const size_t at = off;
+        off += round_up((floats > 0 ? floats : 1) * sizeof(float), kWsAlign);
+        return at;
+    };
+    const size_t K = hidden > 0 ? (size_t)hidden : (size_t)Ca;
+    b->partial_off = take(corr_partial_floats(N, Ca, H, W, Ks));
+    b->ddk_off = take((size_t)N * Ca * 9);
+    b->g_off = take((size_t)N * Ca);
+    b->t_off = take((size_t)N * K);
+    b->du_off = take((size_t)N * hidden);
+    b->dgc_off = take((size_t)N * Ca);
+    b->dkf_off = take((size_t)N * Ca * 9);
+    b->lkf_off = take((size_t)Ca * Ks * Ks);
+    b->total = off;
+    return true;
+}
+
 // The mailboxes and counters of esc_convattn_forward_noalloc: one copy per device, in the
 // code object's data segment, so that a call needs no allocation and no preparation.  It is
 // laid out like a caller's workspace and starts out as esc_workspace_init would leave it
@@ -778,6 +808,94 @@ esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C,
                      (p.idt_off % 16 == 0);
     }
     return launch_dense(p, dt == ESC_BF16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
+}
+
+size_t esc_backward_workspace_bytes(int N, int C_a, int H, int W, int Ks, int hidden)
+{
+    BackwardLayout b;
+    if (!backward_layout(N, C_a, H, W, Ks, hidden, &b)) return 0;
+    return b.total;
+}
+
+esc_status esc_convattn_backward(const void *x, const void *grad_out, esc_dtype dt, int N, int C, int H, int W, int C_a,
+                                 const float *lk, int Ks, long lk_channel_stride, const esc_gen_params *gen,
+                                 const float *dk_in, void *grad_x, float *grad_lk, const esc_gen_grads *grad_gen,
+                                 float *grad_dk, int accumulate, void *workspace, size_t workspace_bytes, void *stream)
+{
+    esc_status st = check_common(x, dt, N, C, H, W, C_a);
+    if (st != ESC_OK) return st;
+    if (grad_out == nullptr || grad_x == nullptr) return ESC_ERR_NULL;
+    if (Ks < 1 || (Ks % 2) == 0) return Ks < 1 ? ESC_ERR_SHAPE : ESC_ERR_UNSUPPORTED;
+    if (Ks > kMaxKs) return ESC_ERR_UNSUPPORTED;
+    if (C_a > 0 && lk == nullptr) return ESC_ERR_NULL;
+    if (lk_channel_stride != 0 && lk_channel_stride < (long)Ks * Ks) return ESC_ERR_SHAPE;
+    if (gen != nullptr && (st = check_gen(gen, C_a)) != ESC_OK) return st;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    if (((uintptr_t)grad_out % es) != 0 || ((uintptr_t)grad_x % es) != 0) return ESC_ERR_SHAPE;
+    const size_t bytes = (size_t)N * C * H * W * es;
+    if (overlaps(x, bytes, grad_x, bytes) || overlaps(grad_out, bytes, grad_x, bytes)) return ESC_ERR_ALIAS;
+    const int hidden = gen != nullptr ? gen->hidden : 0;
+    BackwardLayout b;
+    if (!backward_layout(N, C_a, H, W, Ks, hidden, &b)) return ESC_ERR_SHAPE;
+    if ((st = check_ws(workspace, workspace_bytes, b.total)) != ESC_OK) return st;
+    if (overlaps(workspace, workspace_bytes, grad_x, bytes) || overlaps(workspace, workspace_bytes, x, bytes) ||
+        overlaps(workspace, workspace_bytes, grad_out, bytes))
+        return ESC_ERR_ALIAS;
+    hipStream_t s = (hipStream_t)stream;
+    const bool bf16 = dt == ESC_BF16;
+    char *w = (char *)workspace;
+    if (C_a == 0)  // no attention channels: the input gradient is the upstream one
+        return enqueue_forward(grad_out, dt, N, C, H, W, 0, nullptr, Ks, 0, nullptr, nullptr, grad_x, C, true, workspace,
+                               b.ws, s);
+    BackwardParams p{};
+    p.x = x;
+    p.go = grad_out;
+    p.N = N;
+    p.C = C;
+    p.Ca = C_a;
+    p.H = H;
+    p.W = W;
+    p.Ks = Ks;
+    p.lk = lk;
+    p.lk_cstride = lk_channel_stride;
+    p.has_gen = gen != nullptr;
+    if (gen != nullptr) {
+        p.hidden = gen->hidden;
+        p.w_down = gen->w_down;
+        p.b_down = gen->b_down;
+        p.w_up = gen->w_up;
+        p.b_up = gen->b_up;
+    } else {
+        p.dk_in = dk_in;
+    }
+    p.partial = (float *)(w + b.partial_off);
+    p.ddk = (float *)(w + b.ddk_off);
+    p.g = (float *)(w + b.g_off);
+    p.t = (float *)(w + b.t_off);
+    p.du = (float *)(w + b.du_off);
+    p.dgc = (float *)(w + b.dgc_off);
+    p.dkf = (float *)(w + b.dkf_off);
+    p.lkf = (float *)(w + b.lkf_off);
+    p.grad_lk = grad_lk;
+    p.grad_dk = grad_dk;
+    if (grad_gen != nullptr && gen != nullptr) {
+        p.grad_w_down = grad_gen->w_down;
+        p.grad_b_down = grad_gen->b_down;
+        p.grad_w_up = grad_gen->w_up;
+        p.grad_b_up = grad_gen->b_up;
+    }
+    p.accumulate = accumulate != 0;
+    // 1. S = correlation of grad_out with x: grad_lk, dL/dDK, and the GAP means on the way
+    if (launch_backward_sums(p, bf16, s) != hipSuccess) return ESC_ERR_HIP;
+    // 2. the estimator forwards (DK) and backwards; the flipped kernels
+    if (launch_backward_estimator(p, s) != hipSuccess) return ESC_ERR_HIP;
+    // 3. the input gradient's convolution is the forward on grad_out with the flipped kernels
+    //    (identity channels: grad_x = grad_out, the forward's pass-through copy)
+    if ((st = enqueue_forward(grad_out, dt, N, C, H, W, C_a, p.lkf, Ks, lk_channel_stride != 0 ? (long)Ks * Ks : 0,
+                              nullptr, p.dkf, grad_x, C, true, workspace, b.ws, s)) != ESC_OK)
+        return st;
+    // 4. the GAP's share: dL/dg / (H W) on every pixel of the attention planes
+    return launch_backward_add_gap_term(p, grad_x, bf16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
 }
 
 const char *esc_status_string(esc_status s)

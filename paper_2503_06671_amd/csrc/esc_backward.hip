@@ -1,0 +1,432 @@
+// Backward pass of the ConvAttn module (depth-wise form; Eq. 4 lines 1-4 of the ESC paper
+// without Conv_fuse) for gfx950 (MI355X).  The paper trains its shared LK end to end
+// (Sec. 3) but prints no gradient formulae; these are the derivatives of the definition:
+//
+//   S[n,c,i,j]  = sum_{y,x} go[n,c,y,x] xz[n,c,y+i-p,x+j-p]      correlation of grad_out with x
+//   dLK[c]      = sum_n S[n,c]           dDK[n,c] = centre 3 x 3 of S[n,c]
+//   estimator   : dd = dDK;  db_up = sum_n dd;  dw_up = sum_n dd (x) t;  dt = w_up^T dd;
+//                 du = dt * gelu'(u);  db_down = sum_n du;  dw_down = sum_n du (x) g;  dg = w_down^T du
+//   dx[n,c]     = go[n,c] (*) flip(LK[c] + ZP(DK[n,c])) + dg[n,c] / (H W)     (c < C_a; dx = go elsewhere)
+//
+// The input gradient's convolution is the forward kernel itself, run on grad_out with the
+// flipped kernels (esc_api.hip); this file holds what is new: the correlation S (the same
+// arithmetic as the forward's tap loop, turned round: 2 Ks^2 flops per pixel into Ks^2
+// sums), the small estimator kernels, and the GAP term of dx.  Every sum has a fixed order
+// (per-tile partial sums in the workspace, then one thread per result), so results do not
+// depend on scheduling.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "esc_backward.hpp"
+
+namespace esc {
+namespace {
+
+constexpr int kBwThreads = 256;
+
+struct bf16b {
+    uint16_t bits;
+};
+__device__ __forceinline__ float bw_load(const float *p) { return *p; }
+__device__ __forceinline__ float bw_load(const bf16b *p) { return __uint_as_float((uint32_t)p->bits << 16); }
+__device__ __forceinline__ uint16_t bw_f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// running sum along each row of 16 lanes (data-parallel moves inside the vector unit):
+// lane 15 of a row ends with the row's total, in a fixed order
+__device__ __forceinline__ float row16_sum(float v)
+{
+    auto dpp = [](float x, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value,
+                                                                     0xf, 0xf, false));
+    };
+    v += dpp(v, std::integral_constant<int, 0x111>{});
+    v += dpp(v, std::integral_constant<int, 0x112>{});
+    v += dpp(v, std::integral_constant<int, 0x114>{});
+    v += dpp(v, std::integral_constant<int, 0x118>{});
+    return v;
+}
+
+extern __shared__ __align__(16) float bw_lds[];
+
+// ---------------------------------------------------------------------------
+// S per tile.  A block takes a 64 x 32 pixel tile of one (image, channel) plane: grad_out's
+// tile and x's zero-extended halo tile go to LDS.  Thread (tx, tg) = (t & 15, t >> 4) owns the
+// 4-pixel column strip tx and two rows (2*ip, 2*ip + 1) of the correlation window; with at
+// most eight row pairs the sixteen groups also split the tile's rows in two halves.  Walking
+// down its rows it reads one grad_out segment and one new x segment per row (the x segment
+// of window row 2*ip + 1 at tile row y is that of window row 2*ip at y + 1) and applies
+// 2 * KC * 4 multiply-adds to its 2 * KC sums - the forward tap loop's ratio of arithmetic
+// to LDS traffic.  The strip sums are added along each row of 16 lanes, then over the row
+// halves, and written as the tile's partial sums; the last entry is the tile's sum of x
+// (for the GAP).
+// ---------------------------------------------------------------------------
+template <typename T, int KC>
+__global__ __launch_bounds__(kBwThreads) void corr_kernel(const BackwardParams p)
+{
+    constexpr int P = (KC - 1) / 2;
+    constexpr int NP = (KC + 1) / 2;             // row pairs of the window
+    constexpr int YS = NP <= 8 ? 2 : 1;           // halves the tile's rows are split in
+    constexpr int ROWS = kCorrTileH / YS;
+    constexpr int NXV = (KC + 3 + 3) & ~3;        // x values a thread reads per row
+    constexpr int HC = kCorrTileW + KC - 1;
+    constexpr int PITCH = ((60 + NXV > HC ? 60 + NXV : HC) + 3) & ~3;
+    constexpr int HR = kCorrTileH + KC - 1 + 1;   // one spare row of zeros (an odd window's last pair reads it)
+    float *xs = bw_lds;                            // [HR][PITCH]
+    float *gs = xs + HR * PITCH;                   // [32][64]
+    float *red = gs + kCorrTileH * kCorrTileW;     // [16][2*KC + 1]
+
+    const int tid = (int)threadIdx.x;
+    const int H = p.H, W = p.W;
+    const int tiles_x = (W + kCorrTileW - 1) / kCorrTileW;
+    const int tiles = corr_tiles(H, W);
+    const unsigned nc = blockIdx.x / (unsigned)tiles, tile = blockIdx.x - nc * (unsigned)tiles;
+    const unsigned n = nc / (unsigned)p.Ca, c = nc - n * (unsigned)p.Ca;
+    const int ty0 = (int)(tile / (unsigned)tiles_x) * kCorrTileH, tx0 = (int)(tile % (unsigned)tiles_x) * kCorrTileW;
+    const size_t plane = ((size_t)n * p.C + c) * (size_t)H * W;
+    const T *xp = (const T *)p.x + plane, *gp = (const T *)p.go + plane;
+
+    // ---- tiles to LDS (all of a batch's loads before their uses) ----
+    for (int i0 = 0; i0 < HR * PITCH; i0 += 8 * kBwThreads) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = i0 + u * kBwThreads + tid;
+            const int r = idx / PITCH, cc = idx - r * PITCH;
+            const int gy = ty0 - P + r, gx = tx0 - P + cc;
+            const bool in = idx < HR * PITCH && gy >= 0 && gy < H && gx >= 0 && gx < W;
+            v[u] = bw_load(xp + (in ? (size_t)gy * W + gx : 0));
+            v[u] = in ? v[u] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = i0 + u * kBwThreads + tid;
+            if (idx < HR * PITCH) xs[idx] = v[u];
+        }
+    }
+    {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = u * kBwThreads + tid;
+            const int r = idx >> 6, cc = idx & 63;
+            const int gy = ty0 + r, gx = tx0 + cc;
+            const bool in = gy < H && gx < W;
+            v[u] = bw_load(gp + (in ? (size_t)gy * W + gx : 0));
+            v[u] = in ? v[u] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) gs[u * kBwThreads + tid] = v[u];
+    }
+    __syncthreads();
+
+    const int tx = tid & 15, tg = tid >> 4;
+    const int ip = YS == 2 ? (tg & 7) : tg, yh = YS == 2 ? (tg >> 3) : 0;
+    const int i_first = 2 * ip;
+    float acc0[KC], acc1[KC];
+#pragma unroll
+    for (int j = 0; j < KC; ++j) acc0[j] = acc1[j] = 0.f;
+    float sx = 0.f;
+    if (i_first < KC) {  // (uniform per row of 16 lanes)
+        const int ya = yh * ROWS;
+        float xa[NXV], xb[NXV];
+        {
+            const float4 *src = reinterpret_cast<const float4 *>(xs + (ya + i_first) * PITCH + 4 * tx);
+#pragma unroll
+            for (int k = 0; k < NXV / 4; ++k) {
+                const float4 f = src[k];
+                xa[4 * k] = f.x, xa[4 * k + 1] = f.y, xa[4 * k + 2] = f.z, xa[4 * k + 3] = f.w;
+            }
+        }
+        for (int y = ya; y < ya + ROWS; ++y) {
+            const float4 g4 = *reinterpret_cast<const float4 *>(gs + y * kCorrTileW + 4 * tx);
+            const float4 *src = reinterpret_cast<const float4 *>(xs + (y + i_first + 1) * PITCH + 4 * tx);
+#pragma unroll
+            for (int k = 0; k < NXV / 4; ++k) {
+                const float4 f = src[k];
+                xb[4 * k] = f.x, xb[4 * k + 1] = f.y, xb[4 * k + 2] = f.z, xb[4 * k + 3] = f.w;
+            }
+            const float g[4] = {g4.x, g4.y, g4.z, g4.w};
+#pragma unroll
+            for (int j = 0; j < KC; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc0[j] = fmaf(g[q], xa[q + j], acc0[j]);
+                    acc1[j] = fmaf(g[q], xb[q + j], acc1[j]);
+                }
+            if (ip == 0) {  // the tile's own pixels, for the GAP: the window's centre row of this tile row
+                const float *ctr = xs + (y + P) * PITCH + 4 * tx + P;
+                sx += (ctr[0] + ctr[1]) + (ctr[2] + ctr[3]);
+            }
+#pragma unroll
+            for (int k = 0; k < NXV; ++k) xa[k] = xb[k];
+        }
+    }
+    // ---- strips -> rows of 16 lanes -> row halves -> the tile's partial sums ----
+#pragma unroll
+    for (int j = 0; j < KC; ++j) {
+        const float a = row16_sum(acc0[j]), b = row16_sum(acc1[j]);
+        if (tx == 15) {
+            red[tg * (2 * KC + 1) + j] = a;
+            red[tg * (2 * KC + 1) + KC + j] = b;
+        }
+    }
+    {
+        const float a = row16_sum(sx);
+        if (tx == 15) red[tg * (2 * KC + 1) + 2 * KC] = a;
+    }
+    __syncthreads();
+    float *dst = p.partial + ((size_t)nc * tiles + tile) * (KC * KC + 1);
+    for (int o = tid; o < KC * KC + 1; o += kBwThreads) {
+        float s;
+        if (o == KC * KC) {
+            s = red[2 * KC];
+            if (YS == 2) s += red[8 * (2 * KC + 1) + 2 * KC];
+        } else {
+            const int i = o / KC, j = o - i * KC;
+            const int g0 = i >> 1, off = (i & 1) * KC + j;
+            s = red[g0 * (2 * KC + 1) + off];
+            if (YS == 2) s += red[(g0 + 8) * (2 * KC + 1) + off];
+        }
+        dst[o] = s;
+    }
+}
+
+// One thread per result: grad_lk (sums over images and tiles; over channels too for a single
+// shared filter), ddk (sums over tiles), g (the GAP mean).
+__global__ void sums_kernel(const BackwardParams p, int KC, int tiles)
+{
+    const int Ks = p.Ks, Ca = p.Ca, off = (KC - Ks) / 2;
+    const size_t per = (size_t)KC * KC + 1;
+    const size_t n_lk = (size_t)(p.lk_cstride != 0 ? Ca : 1) * Ks * Ks;
+    const size_t n_dk = (size_t)p.N * Ca * 9, n_g = (size_t)p.N * Ca;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < n_lk) {
+        if (p.grad_lk == nullptr) return;
+        const int c0 = (int)(idx / ((size_t)Ks * Ks)), r = (int)(idx % ((size_t)Ks * Ks));
+        const int i = r / Ks + off, j = r % Ks + off;
+        float s = 0.f;
+        const int c_lo = p.lk_cstride != 0 ? c0 : 0, c_hi = p.lk_cstride != 0 ? c0 + 1 : Ca;
+        for (int c = c_lo; c < c_hi; ++c)
+            for (int n = 0; n < p.N; ++n)
+                for (int t = 0; t < tiles; ++t) s += p.partial[(((size_t)n * Ca + c) * tiles + t) * per + (size_t)i * KC + j];
+        float *dst = p.grad_lk + (p.lk_cstride != 0 ? (size_t)c0 * p.lk_cstride : 0) + r;
+        *dst = p.accumulate ? *dst + s : s;
+    } else if (idx < n_lk + n_dk) {
+        const size_t q = idx - n_lk;
+        const size_t nc = q / 9;
+        const int r = (int)(q % 9), i = r / 3 + (KC - 3) / 2, j = r % 3 + (KC - 3) / 2;
+        float s = 0.f;
+        for (int t = 0; t < tiles; ++t) s += p.partial[(nc * tiles + t) * per + (size_t)i * KC + j];
+        p.ddk[q] = s;
+        if (p.grad_dk != nullptr) p.grad_dk[q] = s;
+    } else if (idx < n_lk + n_dk + n_g) {
+        const size_t nc = idx - n_lk - n_dk;
+        float s = 0.f;
+        for (int t = 0; t < tiles; ++t) s += p.partial[(nc * tiles + t) * per + (size_t)KC * KC];
+        p.g[nc] = s / (float)((double)p.H * (double)p.W);
+    }
+}
+
+__device__ __forceinline__ float gelu_f(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f)); }
+__device__ __forceinline__ float gelu_grad_f(float v)
+{
+    return 0.5f * (1.f + erff(v * 0.70710678118654752440f)) + v * expf(-0.5f * v * v) * 0.39894228040143267794f;
+}
+
+// One block per image: the estimator forwards from g (DK, stored flipped for the input
+// gradient) and backwards from dDK (dL/dt, dL/du, dL/dg).  Plain loops: a few thousand
+// multiply-adds per image.
+__global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const BackwardParams p)
+{
+    __shared__ float s_g[256], s_u[256], s_t[256], s_dt[256], s_du[256];
+    const int n = (int)blockIdx.x, tid = (int)threadIdx.x;
+    const int Ca = p.Ca, hidden = p.hidden, K = hidden > 0 ? hidden : Ca;
+    const float hw = (float)((double)p.H * (double)p.W);
+    if (!p.has_gen) {  // DK as given (or zero): only its flipped copy is needed
+        for (int o = tid; o < 9 * Ca; o += kBwThreads) {
+            const int c = o / 9, r = o - 9 * c;
+            p.dkf[((size_t)n * Ca + c) * 9 + (8 - r)] = p.dk_in != nullptr ? p.dk_in[(size_t)n * 9 * Ca + o] : 0.f;
+        }
+        for (int k = tid; k < Ca; k += kBwThreads) p.dgc[(size_t)n * Ca + k] = 0.f;
+        return;
+    }
+    for (int k = tid; k < Ca; k += kBwThreads) s_g[k] = p.g[(size_t)n * Ca + k];
+    __syncthreads();
+    if (hidden > 0) {
+        for (int m = tid; m < hidden; m += kBwThreads) {
+            float s = p.b_down != nullptr ? p.b_down[m] : 0.f;
+            for (int k = 0; k < Ca; ++k) s = fmaf(p.w_down[(size_t)m * Ca + k], s_g[k], s);
+            s_u[m] = s;
+            s_t[m] = gelu_f(s);
+        }
+    } else {
+        for (int k = tid; k < Ca; k += kBwThreads) s_t[k] = s_g[k];
+    }
+    __syncthreads();
+    for (int k = tid; k < K; k += kBwThreads) p.t[(size_t)n * K + k] = s_t[k];
+    for (int o = tid; o < 9 * Ca; o += kBwThreads) {
+        float s = p.b_up != nullptr ? p.b_up[o] : 0.f;
+        for (int k = 0; k < K; ++k) s = fmaf(p.w_up[(size_t)o * K + k], s_t[k], s);
+        const int c = o / 9, r = o - 9 * c;
+        p.dkf[((size_t)n * Ca + c) * 9 + (8 - r)] = s;
+    }
+    for (int k = tid; k < K; k += kBwThreads) {  // dL/dt = w_up^T dd
+        float s = 0.f;
+        for (int o = 0; o < 9 * Ca; ++o) s = fmaf(p.w_up[(size_t)o * K + k], p.ddk[(size_t)n * 9 * Ca + o], s);
+        s_dt[k] = s;
+    }
+    __syncthreads();
+    if (hidden > 0) {
+        for (int m = tid; m < hidden; m += kBwThreads) {
+            const float v = s_dt[m] * gelu_grad_f(s_u[m]);
+            s_du[m] = v;
+            p.du[(size_t)n * hidden + m] = v;
+        }
+        __syncthreads();
+        for (int k = tid; k < Ca; k += kBwThreads) {
+            float s = 0.f;
+            for (int m = 0; m < hidden; ++m) s = fmaf(p.w_down[(size_t)m * Ca + k], s_du[m], s);
+            p.dgc[(size_t)n * Ca + k] = s / hw;
+        }
+    } else {
+        for (int k = tid; k < Ca; k += kBwThreads) p.dgc[(size_t)n * Ca + k] = s_dt[k] / hw;
+    }
+}
+
+// One thread per parameter: the sums over the images, in image order; and the flipped LK.
+__global__ void estimator_param_kernel(const BackwardParams p)
+{
+    const int Ca = p.Ca, hidden = p.hidden, K = hidden > 0 ? hidden : Ca, Ks = p.Ks;
+    const size_t n_wu = p.has_gen ? (size_t)9 * Ca * K : 0, n_bu = p.has_gen ? (size_t)9 * Ca : 0;
+    const size_t n_wd = p.has_gen ? (size_t)hidden * Ca : 0, n_bd = p.has_gen ? (size_t)hidden : 0;
+    const size_t n_lkf = (size_t)(p.lk_cstride != 0 ? Ca : 1) * Ks * Ks;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    auto put = [&](float *dst, float s) {
+        if (dst != nullptr) *dst = p.accumulate ? *dst + s : s;
+    };
+    if (idx < n_wu) {
+        const size_t o = idx / K, k = idx % K;
+        float s = 0.f;
+        for (int n = 0; n < p.N; ++n) s = fmaf(p.ddk[(size_t)n * 9 * Ca + o], p.t[(size_t)n * K + k], s);
+        put(p.grad_w_up ? p.grad_w_up + idx : nullptr, s);
+        return;
+    }
+    idx -= n_wu;
+    if (idx < n_bu) {
+        float s = 0.f;
+        for (int n = 0; n < p.N; ++n) s += p.ddk[(size_t)n * 9 * Ca + idx];
+        put(p.grad_b_up ? p.grad_b_up + idx : nullptr, s);
+        return;
+    }
+    idx -= n_bu;
+    if (idx < n_wd) {
+        const size_t m = idx / Ca, k = idx % Ca;
+        float s = 0.f;
+        for (int n = 0; n < p.N; ++n) s = fmaf(p.du[(size_t)n * hidden + m], p.g[(size_t)n * Ca + k], s);
+        put(p.grad_w_down ? p.grad_w_down + idx : nullptr, s);
+        return;
+    }
+    idx -= n_wd;
+    if (idx < n_bd) {
+        float s = 0.f;
+        for (int n = 0; n < p.N; ++n) s += p.du[(size_t)n * hidden + idx];
+        put(p.grad_b_down ? p.grad_b_down + idx : nullptr, s);
+        return;
+    }
+    idx -= n_bd;
+    if (idx < n_lkf) {
+        const size_t c = idx / ((size_t)Ks * Ks), r = idx % ((size_t)Ks * Ks);
+        p.lkf[idx] = p.lk[c * (size_t)p.lk_cstride + ((size_t)Ks * Ks - 1 - r)];
+    }
+}
+
+template <typename T>
+__global__ void add_gap_term_kernel(T *dx, const float *dgc, int N, int C, int Ca, size_t plane)
+{
+    const size_t total = (size_t)N * Ca * plane;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t nc = i / plane, q = i - nc * plane;
+        const size_t n = nc / Ca, c = nc - n * Ca;
+        T *dst = dx + (n * C + c) * plane + q;
+        const float v = bw_load(dst) + dgc[nc];
+        if constexpr (std::is_same<T, float>::value)
+            *dst = v;
+        else
+            dst->bits = bw_f32_to_bf16(v);
+    }
+}
+
+template <typename T, int KC>
+hipError_t launch_corr(const BackwardParams &p, unsigned grid, hipStream_t s)
+{
+    constexpr int NXV = (KC + 3 + 3) & ~3, HC = kCorrTileW + KC - 1;
+    constexpr int PITCH = ((60 + NXV > HC ? 60 + NXV : HC) + 3) & ~3, HR = kCorrTileH + KC;
+    constexpr size_t lds = ((size_t)HR * PITCH + kCorrTileH * kCorrTileW + 16 * (2 * KC + 1)) * sizeof(float);
+    static_assert(lds <= 64 * 1024, "the correlation kernel's tiles must fit the default LDS limit");
+    hipLaunchKernelGGL((corr_kernel<T, KC>), dim3(grid), dim3(kBwThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_corr_kc(const BackwardParams &p, int kc, unsigned grid, hipStream_t s)
+{
+    switch (kc) {
+#define ESC_KC(K) case K: return launch_corr<T, K>(p, grid, s);
+        ESC_KC(3) ESC_KC(5) ESC_KC(7) ESC_KC(9) ESC_KC(11) ESC_KC(13) ESC_KC(15) ESC_KC(17)
+        ESC_KC(19) ESC_KC(21) ESC_KC(23) ESC_KC(25) ESC_KC(27) ESC_KC(29) ESC_KC(31)
+#undef ESC_KC
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+__attribute__((visibility("hidden"))) hipError_t launch_backward_sums(const BackwardParams &p, bool bf16, hipStream_t s)
+{
+    if (p.Ca < 1) return hipSuccess;
+    const int kc = corr_window(p.Ks), tiles = corr_tiles(p.H, p.W);
+    const size_t grid = (size_t)p.N * p.Ca * tiles;
+    if (grid >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    hipError_t e = bf16 ? launch_corr_kc<bf16b>(p, kc, (unsigned)grid, s) : launch_corr_kc<float>(p, kc, (unsigned)grid, s);
+    if (e != hipSuccess) return e;
+    const size_t results = (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks + (size_t)p.N * p.Ca * 10;
+    hipLaunchKernelGGL(sums_kernel, dim3((unsigned)((results + 255) / 256)), dim3(256), 0, s, p, kc, tiles);
+    return hipGetLastError();
+}
+
+__attribute__((visibility("hidden"))) hipError_t launch_backward_estimator(const BackwardParams &p, hipStream_t s)
+{
+    if (p.Ca < 1) return hipSuccess;
+    hipLaunchKernelGGL(estimator_image_kernel, dim3((unsigned)p.N), dim3(kBwThreads), 0, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int K = p.hidden > 0 ? p.hidden : p.Ca;
+    const size_t params = (p.has_gen ? (size_t)9 * p.Ca * K + 9 * p.Ca + (size_t)p.hidden * p.Ca + p.hidden : 0) +
+                          (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks;
+    hipLaunchKernelGGL(estimator_param_kernel, dim3((unsigned)((params + 255) / 256)), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+__attribute__((visibility("hidden"))) hipError_t launch_backward_add_gap_term(const BackwardParams &p, void *dx, bool bf16,
+                                                                              hipStream_t s)
+{
+    if (p.Ca < 1 || !p.has_gen) return hipSuccess;
+    const size_t plane = (size_t)p.H * p.W, total = (size_t)p.N * p.Ca * plane;
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (bf16)
+        hipLaunchKernelGGL(add_gap_term_kernel<bf16b>, dim3((unsigned)blocks), dim3(256), 0, s, (bf16b *)dx, p.dgc, p.N, p.C, p.Ca, plane);
+    else
+        hipLaunchKernelGGL(add_gap_term_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (float *)dx, p.dgc, p.N, p.C, p.Ca, plane);
+    return hipGetLastError();
+}
+
+}  // namespace esc
