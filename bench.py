@@ -61,6 +61,8 @@ def parse_args():
                     help="time esc_convattn_fused_forward (the module with Conv_fuse, Eq. 4 line 4) instead")
     ap.add_argument("--dense", action="store_true",
                     help="time esc_convattn_dense_forward (dense Ks x Ks x C_a x C_a large kernel of the paper's main variants) instead")
+    ap.add_argument("--backward", action="store_true",
+                    help="time esc_convattn_backward (gradients of the depth-wise forward) instead")
     ap.add_argument("--lkc", action="store_true", help="with --fused: LK^c in front of the depth-wise kernels (Eq. 5)")
     ap.add_argument("--residual", action="store_true", help="with --fused: add the residual of Eq. 3 line 3")
     return ap.parse_args()
@@ -193,10 +195,28 @@ def dense_roofline_of(wl, sec):
     return r
 
 
+def backward_roofline_of(wl, sec):
+    """The backward call: x and grad_out read once, grad_x written once (3 tensors); two passes of
+    2 Ks^2 flops per attention pixel on the vector units (the correlation and the input gradient)."""
+    P = wl.N * wl.H * wl.W
+    b_alg = 3.0 * P * wl.C * wl.elem_bytes
+    f_alg = 4.0 * wl.Ks * wl.Ks * P * wl.Ca
+    r = roofline_of(wl, sec)
+    t_hbm, t_alu = b_alg / (HBM_PEAK_GBS * 1e9), f_alg / (FP32_VECTOR_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_alu:
+        out = {"bound": "hbm", "achieved": b_alg / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        out = {"bound": "alu", "achieved": f_alg / sec / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    out["frac"] = out["achieved"] / out["peak"]
+    out.update({"algorithmic_bytes": b_alg, "algorithmic_flops": f_alg, "hbm_gbps": b_alg / sec / 1e9,
+                "alu_tflops": f_alg / sec / 1e12})
+    return out
+
+
 class Runner:
     """Device buffers of one workload and the timing protocol."""
 
-    def __init__(self, wl, rotate_bytes, warm_cache, ca=None, fused=None, dense=False):
+    def __init__(self, wl, rotate_bytes, warm_cache, ca=None, fused=None, dense=False, backward=False):
         import numpy as np
         import torch
         from paper_2503_06671_amd import binding, workloads as wk
@@ -220,7 +240,12 @@ class Runner:
             self.gen = binding.GenParams(dev(wl.w_up), dev(wl.b_up), wl.hidden, dev(wl.w_down), dev(wl.b_down))
         self.fused = fused
         self.dense = dense
-        if dense:
+        self.backward = backward
+        if backward:
+            self.gos = [torch.randn_like(x0) for _ in range(self.pairs)]   # seeded by torch's default generator below
+            self.ws = binding.new_backward_workspace(wl.N, self.ca, wl.H, wl.W, wl.Ks, wl.hidden)
+            self.grads = {"grad_x": None}
+        elif dense:
             # seeded dense large kernel [C_a, C_a, Ks, Ks] ~ N(0, 1 / (Ks^2 C_a))
             rng = np.random.default_rng(2000 + wl.Ks)
             self.lk_dense = dev((rng.standard_normal((wl.Ca, wl.Ca, wl.Ks, wl.Ks)) / (wl.Ks * np.sqrt(wl.Ca))).astype(np.float32))
@@ -239,6 +264,12 @@ class Runner:
 
     def step(self, i):
         k = i % self.pairs
+        if self.backward:
+            g = dict(self.grads)
+            g["grad_x"] = self.outs[k]
+            self.grads = self.binding.convattn_backward(self.xs[k], self.gos[k], self.ca, self.lk, self.ws, gen=self.gen,
+                                                        grads=g, stream=self.stream)
+            return
         if self.dense:
             self.binding.convattn_dense_forward(self.xs[k], self.ca, self.lk_dense, self.ws, gen=self.gen, out=self.outs[k],
                                                 stream=self.stream)
@@ -325,16 +356,17 @@ def main():
     replays = replays_for(args.steps, args.replays)
 
     fused = {"lkc": args.lkc, "residual": args.residual} if args.fused else None
-    run = Runner(wl, args.rotate_bytes, args.warm_cache, fused=fused, dense=args.dense)
+    torch.manual_seed(7)
+    run = Runner(wl, args.rotate_bytes, args.warm_cache, fused=fused, dense=args.dense, backward=args.backward)
     t = run.time(args.steps, args.warmup, replays, eager=args.eager)
     ms_step = t["median"]
     # spot check of the last buffers against the first (same input => same bits)
-    if not args.residual:
+    if not args.residual and not args.backward:
         assert torch.equal(run.outs[0], run.outs[(args.steps - 1) % run.pairs]), "rotating buffers disagree"
     latency_us = run.single_call_latency_us()
 
     floors = None
-    if not args.no_floors and fused is None and not args.dense:
+    if not args.no_floors and fused is None and not args.dense and not args.backward:
         # the library's own pure copy (C_a = 0) on the same tensors and rotation, and a call
         # with nothing to do (1 x 1 x 1 x 1, C_a = 0): what is left above them is the method's
         copy_t = Runner(wl, args.rotate_bytes, args.warm_cache, ca=0).time(args.steps, min(args.warmup, 200), replays,
@@ -354,12 +386,17 @@ def main():
     elif args.dense:
         wl_name += "_dense"
         roof = dense_roofline_of(wl, sec)
+    elif args.backward:
+        wl_name += "_backward"
+        roof = backward_roofline_of(wl, sec)
     else:
         roof = roofline_of(wl, sec)
     traffic, traffic_src = (None, None) if args.warm_cache else profiled_traffic(wl_name)
     roof.update({
         "kernel": (f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)"
-                   if fused is None and not args.dense else
+                   if fused is None and not args.dense and not args.backward else
+                   "corr_kernel (grad_out x correlation), sums, estimator kernels, forward_kernel on grad_out with flipped kernels, GAP term"
+                   if args.backward else
                    "dense_kernel (implicit GEMM on the matrix cores, DK taps, pass-through share) after the estimator launch and the weight rearrangement"
                    if args.dense else
                    "forward_kernel (F_res into the workspace) + pointwise_kernel (Conv_fuse on the matrix cores)"
@@ -370,7 +407,7 @@ def main():
         "kernel_us": ms_step * 1e3,
     })
     res = {
-        "metric": ("convattn_dense_fwd_mpixel_per_s" if args.dense else
+        "metric": ("convattn_dense_fwd_mpixel_per_s" if args.dense else "convattn_bwd_mpixel_per_s" if args.backward else
                    "convattn_fwd_mpixel_per_s" if fused is None else "convattn_fused_fwd_mpixel_per_s"),
         "value": wl.pixels / sec / 1e6,
         "unit": "Mpixel/s",
@@ -453,6 +490,22 @@ def main():
             del r2
             torch.cuda.empty_cache()
         res["dense_workloads"] = den
+        # the backward of the depth-wise module
+        bwd = []
+        for idx in (1, 3):
+            w2 = wk.make_config(idx)
+            if args.backward and w2.name + "_backward" == wl_name:
+                continue
+            r2 = Runner(w2, args.rotate_bytes, args.warm_cache, backward=True)
+            t2 = r2.time(100, 100, 15, eager=args.eager)
+            s2 = t2["median"] * 1e-3
+            rf = backward_roofline_of(w2, s2)
+            bwd.append({"workload": w2.name + "_backward", "dtype": wk.DTYPE_NAMES[w2.dtype], "us_per_step": t2["median"] * 1e3,
+                        "mpixel_per_s": w2.pixels / s2 / 1e6, "bound": rf["bound"], "frac": rf["frac"],
+                        "hbm_gbps": rf["hbm_gbps"], "alu_tflops": rf["alu_tflops"], "steps": 100, "warmup": 100, "replays": 15})
+            del r2
+            torch.cuda.empty_cache()
+        res["backward_workloads"] = bwd
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
