@@ -244,7 +244,7 @@ class Runner:
         if backward:
             self.gos = [torch.randn_like(x0) for _ in range(self.pairs)]   # seeded by torch's default generator below
             self.ws = binding.new_backward_workspace(wl.N, self.ca, wl.H, wl.W, wl.Ks, wl.hidden)
-            self.grads = {"grad_x": None}
+            self.grads = None   # the first call allocates the parameter-gradient buffers, later calls reuse them
         elif dense:
             # seeded dense large kernel [C_a, C_a, Ks, Ks] ~ N(0, 1 / (Ks^2 C_a))
             rng = np.random.default_rng(2000 + wl.Ks)
@@ -265,7 +265,7 @@ class Runner:
     def step(self, i):
         k = i % self.pairs
         if self.backward:
-            g = dict(self.grads)
+            g = dict(self.grads or {})
             g["grad_x"] = self.outs[k]
             self.grads = self.binding.convattn_backward(self.xs[k], self.gos[k], self.ca, self.lk, self.ws, gen=self.gen,
                                                         grads=g, stream=self.stream)

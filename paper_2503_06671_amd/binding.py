@@ -357,20 +357,24 @@ def convattn_backward(x: torch.Tensor, grad_out: torch.Tensor, Ca: int, lk: torc
     if dk_in is not None and dk_in.numel() != N * Ca * 9:
         raise ValueError("dk_in must hold [N, Ca, 3, 3] values")
     g = dict(grads or {})
-    f32 = dict(dtype=torch.float32, device=x.device)
-    g.setdefault("grad_x", torch.empty_like(x))
-    g.setdefault("grad_lk", torch.zeros_like(lk))
-    g.setdefault("grad_dk", torch.empty((N, Ca, 3, 3), **f32))
+
+    def need(name, make):  # (allocate only what the caller did not bring)
+        if g.get(name) is None:
+            g[name] = make()
+
+    need("grad_x", lambda: torch.empty_like(x))
+    need("grad_lk", lambda: torch.zeros_like(lk))
+    need("grad_dk", lambda: torch.empty((N, Ca, 3, 3), dtype=torch.float32, device=x.device))
     gg = None
     if gen is not None:
         w_down, b_down, w_up, b_up = gen.tensors
-        g.setdefault("grad_w_up", torch.zeros_like(w_up))
+        need("grad_w_up", lambda: torch.zeros_like(w_up))
         if b_up is not None:
-            g.setdefault("grad_b_up", torch.zeros_like(b_up))
+            need("grad_b_up", lambda: torch.zeros_like(b_up))
         if gen.hidden > 0:
-            g.setdefault("grad_w_down", torch.zeros_like(w_down))
+            need("grad_w_down", lambda: torch.zeros_like(w_down))
             if b_down is not None:
-                g.setdefault("grad_b_down", torch.zeros_like(b_down))
+                need("grad_b_down", lambda: torch.zeros_like(b_down))
         gg = _GenGrads(_ptr(g.get("grad_w_down")), _ptr(g.get("grad_b_down")), _ptr(g.get("grad_w_up")),
                        _ptr(g.get("grad_b_up")))
     for k, v in g.items():

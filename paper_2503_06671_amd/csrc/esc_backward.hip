@@ -199,39 +199,74 @@ __global__ __launch_bounds__(kBwThreads) void corr_kernel(const BackwardParams p
     }
 }
 
-// One thread per result: grad_lk (sums over images and tiles; over channels too for a single
-// shared filter), ddk (sums over tiles), g (the GAP mean).
-__global__ void sums_kernel(const BackwardParams p, int KC, int tiles)
+// One row of 16 lanes per result: grad_lk (sums over images and tiles; over channels too for
+// a single shared filter), ddk (sums over tiles), g (the GAP mean).  Lane l adds terms l,
+// l + 16, ... in ascending order, then the row's lanes are added in lane order: a fixed
+// order, and sixteen loads in flight instead of a chain of dependent ones.
+__global__ __launch_bounds__(256) void sums_kernel(const BackwardParams p, int KC, int tiles)
 {
     const int Ks = p.Ks, Ca = p.Ca, off = (KC - Ks) / 2;
     const size_t per = (size_t)KC * KC + 1;
     const size_t n_lk = (size_t)(p.lk_cstride != 0 ? Ca : 1) * Ks * Ks;
     const size_t n_dk = (size_t)p.N * Ca * 9, n_g = (size_t)p.N * Ca;
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;  // uniform per row of 16 lanes
+    const int l = (int)(threadIdx.x & 15);
+    if (idx >= n_lk + n_dk + n_g) return;
+    // the result's terms: `count` of them, term k at partial[base(k)]
+    size_t elem, nc0;
+    int count, terms_per_plane = tiles, planes, plane_step;  // planes of (image, channel) walked, and the step between them
+    if (idx < n_lk) {
+        const int c0 = (int)(idx / ((size_t)Ks * Ks)), r = (int)(idx % ((size_t)Ks * Ks));
+        elem = (size_t)(r / Ks + off) * KC + (size_t)(r % Ks + off);
+        if (p.lk_cstride != 0) {  // channel c0 of every image
+            nc0 = (size_t)c0;
+            planes = p.N;
+            plane_step = Ca;
+        } else {                  // every channel of every image
+            nc0 = 0;
+            planes = p.N * Ca;
+            plane_step = 1;
+        }
+    } else if (idx < n_lk + n_dk) {
+        const size_t q = idx - n_lk;
+        const int r = (int)(q % 9);
+        elem = (size_t)(r / 3 + (KC - 3) / 2) * KC + (size_t)(r % 3 + (KC - 3) / 2);
+        nc0 = q / 9;
+        planes = 1;
+        plane_step = 0;
+    } else {
+        elem = (size_t)KC * KC;
+        nc0 = idx - n_lk - n_dk;
+        planes = 1;
+        plane_step = 0;
+    }
+    count = planes * terms_per_plane;
+    float s = 0.f;
+    for (int k0 = l; k0 < count; k0 += 64) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = k0 + 16 * u;
+            const int kk = k < count ? k : count - 1;
+            const int pl = kk / terms_per_plane, tl = kk - pl * terms_per_plane;
+            v[u] = p.partial[((nc0 + (size_t)pl * plane_step) * tiles + tl) * per + elem];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += k0 + 16 * u < count ? v[u] : 0.f;
+    }
+    s = row16_sum(s);
+    if (l != 15) return;
     if (idx < n_lk) {
         if (p.grad_lk == nullptr) return;
         const int c0 = (int)(idx / ((size_t)Ks * Ks)), r = (int)(idx % ((size_t)Ks * Ks));
-        const int i = r / Ks + off, j = r % Ks + off;
-        float s = 0.f;
-        const int c_lo = p.lk_cstride != 0 ? c0 : 0, c_hi = p.lk_cstride != 0 ? c0 + 1 : Ca;
-        for (int c = c_lo; c < c_hi; ++c)
-            for (int n = 0; n < p.N; ++n)
-                for (int t = 0; t < tiles; ++t) s += p.partial[(((size_t)n * Ca + c) * tiles + t) * per + (size_t)i * KC + j];
         float *dst = p.grad_lk + (p.lk_cstride != 0 ? (size_t)c0 * p.lk_cstride : 0) + r;
         *dst = p.accumulate ? *dst + s : s;
     } else if (idx < n_lk + n_dk) {
         const size_t q = idx - n_lk;
-        const size_t nc = q / 9;
-        const int r = (int)(q % 9), i = r / 3 + (KC - 3) / 2, j = r % 3 + (KC - 3) / 2;
-        float s = 0.f;
-        for (int t = 0; t < tiles; ++t) s += p.partial[(nc * tiles + t) * per + (size_t)i * KC + j];
         p.ddk[q] = s;
         if (p.grad_dk != nullptr) p.grad_dk[q] = s;
-    } else if (idx < n_lk + n_dk + n_g) {
-        const size_t nc = idx - n_lk - n_dk;
-        float s = 0.f;
-        for (int t = 0; t < tiles; ++t) s += p.partial[(nc * tiles + t) * per + (size_t)KC * KC];
-        p.g[nc] = s / (float)((double)p.H * (double)p.W);
+    } else {
+        p.g[idx - n_lk - n_dk] = s / (float)((double)p.H * (double)p.W);
     }
 }
 
@@ -246,7 +281,7 @@ __device__ __forceinline__ float gelu_grad_f(float v)
 // multiply-adds per image.
 __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const BackwardParams p)
 {
-    __shared__ float s_g[256], s_u[256], s_t[256], s_dt[256], s_du[256];
+    __shared__ float s_g[256], s_u[256], s_t[256], s_dt[256], s_du[256], s_dd[9 * 256];
     const int n = (int)blockIdx.x, tid = (int)threadIdx.x;
     const int Ca = p.Ca, hidden = p.hidden, K = hidden > 0 ? hidden : Ca;
     const float hw = (float)((double)p.H * (double)p.W);
@@ -259,10 +294,12 @@ __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const Backw
         return;
     }
     for (int k = tid; k < Ca; k += kBwThreads) s_g[k] = p.g[(size_t)n * Ca + k];
+    for (int o = tid; o < 9 * Ca; o += kBwThreads) s_dd[o] = p.ddk[(size_t)n * 9 * Ca + o];
     __syncthreads();
     if (hidden > 0) {
         for (int m = tid; m < hidden; m += kBwThreads) {
             float s = p.b_down != nullptr ? p.b_down[m] : 0.f;
+#pragma unroll 8
             for (int k = 0; k < Ca; ++k) s = fmaf(p.w_down[(size_t)m * Ca + k], s_g[k], s);
             s_u[m] = s;
             s_t[m] = gelu_f(s);
@@ -274,13 +311,15 @@ __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const Backw
     for (int k = tid; k < K; k += kBwThreads) p.t[(size_t)n * K + k] = s_t[k];
     for (int o = tid; o < 9 * Ca; o += kBwThreads) {
         float s = p.b_up != nullptr ? p.b_up[o] : 0.f;
+#pragma unroll 8
         for (int k = 0; k < K; ++k) s = fmaf(p.w_up[(size_t)o * K + k], s_t[k], s);
         const int c = o / 9, r = o - 9 * c;
         p.dkf[((size_t)n * Ca + c) * 9 + (8 - r)] = s;
     }
     for (int k = tid; k < K; k += kBwThreads) {  // dL/dt = w_up^T dd
         float s = 0.f;
-        for (int o = 0; o < 9 * Ca; ++o) s = fmaf(p.w_up[(size_t)o * K + k], p.ddk[(size_t)n * 9 * Ca + o], s);
+#pragma unroll 8
+        for (int o = 0; o < 9 * Ca; ++o) s = fmaf(p.w_up[(size_t)o * K + k], s_dd[o], s);
         s_dt[k] = s;
     }
     __syncthreads();
@@ -293,6 +332,7 @@ __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const Backw
         __syncthreads();
         for (int k = tid; k < Ca; k += kBwThreads) {
             float s = 0.f;
+#pragma unroll 8
             for (int m = 0; m < hidden; ++m) s = fmaf(p.w_down[(size_t)m * Ca + k], s_du[m], s);
             p.dgc[(size_t)n * Ca + k] = s / hw;
         }
@@ -301,66 +341,80 @@ __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const Backw
     }
 }
 
-// One thread per parameter: the sums over the images, in image order; and the flipped LK.
-__global__ void estimator_param_kernel(const BackwardParams p)
+// One row of 16 lanes per parameter: the sums over the images (lane l adds images l, l + 16,
+// ... in ascending order, then the row's lanes in lane order); and the flipped LK.
+__global__ __launch_bounds__(256) void estimator_param_kernel(const BackwardParams p)
 {
     const int Ca = p.Ca, hidden = p.hidden, K = hidden > 0 ? hidden : Ca, Ks = p.Ks;
     const size_t n_wu = p.has_gen ? (size_t)9 * Ca * K : 0, n_bu = p.has_gen ? (size_t)9 * Ca : 0;
     const size_t n_wd = p.has_gen ? (size_t)hidden * Ca : 0, n_bd = p.has_gen ? (size_t)hidden : 0;
     const size_t n_lkf = (size_t)(p.lk_cstride != 0 ? Ca : 1) * Ks * Ks;
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    auto put = [&](float *dst, float s) {
-        if (dst != nullptr) *dst = p.accumulate ? *dst + s : s;
-    };
+    size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;  // uniform per row of 16 lanes
+    const int l = (int)(threadIdx.x & 15);
+    if (idx >= n_wu + n_bu + n_wd + n_bd) {  // the flipped large kernel: one element per lane of the rows left over
+        const size_t e = (idx - (n_wu + n_bu + n_wd + n_bd)) * 16 + l;
+        if (e < n_lkf) {
+            const size_t c = e / ((size_t)Ks * Ks), r = e % ((size_t)Ks * Ks);
+            p.lkf[e] = p.lk[c * (size_t)p.lk_cstride + ((size_t)Ks * Ks - 1 - r)];
+        }
+        return;
+    }
+    // result = sum_n a[n * sa + ia] * b[n * sb + ib]   (b == nullptr: the plain sum of a)
+    const float *a, *b = nullptr;
+    size_t sa, ia, sb = 0, ib = 0;
+    float *dst;
     if (idx < n_wu) {
-        const size_t o = idx / K, k = idx % K;
-        float s = 0.f;
-        for (int n = 0; n < p.N; ++n) s = fmaf(p.ddk[(size_t)n * 9 * Ca + o], p.t[(size_t)n * K + k], s);
-        put(p.grad_w_up ? p.grad_w_up + idx : nullptr, s);
-        return;
+        a = p.ddk, sa = (size_t)9 * Ca, ia = idx / K;
+        b = p.t, sb = (size_t)K, ib = idx % K;
+        dst = p.grad_w_up ? p.grad_w_up + idx : nullptr;
+    } else if ((idx -= n_wu) < n_bu) {
+        a = p.ddk, sa = (size_t)9 * Ca, ia = idx;
+        dst = p.grad_b_up ? p.grad_b_up + idx : nullptr;
+    } else if ((idx -= n_bu) < n_wd) {
+        a = p.du, sa = (size_t)hidden, ia = idx / Ca;
+        b = p.g, sb = (size_t)Ca, ib = idx % Ca;
+        dst = p.grad_w_down ? p.grad_w_down + idx : nullptr;
+    } else {
+        idx -= n_wd;
+        a = p.du, sa = (size_t)hidden, ia = idx;
+        dst = p.grad_b_down ? p.grad_b_down + idx : nullptr;
     }
-    idx -= n_wu;
-    if (idx < n_bu) {
-        float s = 0.f;
-        for (int n = 0; n < p.N; ++n) s += p.ddk[(size_t)n * 9 * Ca + idx];
-        put(p.grad_b_up ? p.grad_b_up + idx : nullptr, s);
-        return;
-    }
-    idx -= n_bu;
-    if (idx < n_wd) {
-        const size_t m = idx / Ca, k = idx % Ca;
-        float s = 0.f;
-        for (int n = 0; n < p.N; ++n) s = fmaf(p.du[(size_t)n * hidden + m], p.g[(size_t)n * Ca + k], s);
-        put(p.grad_w_down ? p.grad_w_down + idx : nullptr, s);
-        return;
-    }
-    idx -= n_wd;
-    if (idx < n_bd) {
-        float s = 0.f;
-        for (int n = 0; n < p.N; ++n) s += p.du[(size_t)n * hidden + idx];
-        put(p.grad_b_down ? p.grad_b_down + idx : nullptr, s);
-        return;
-    }
-    idx -= n_bd;
-    if (idx < n_lkf) {
-        const size_t c = idx / ((size_t)Ks * Ks), r = idx % ((size_t)Ks * Ks);
-        p.lkf[idx] = p.lk[c * (size_t)p.lk_cstride + ((size_t)Ks * Ks - 1 - r)];
-    }
+    float s = 0.f;
+    for (int n = l; n < p.N; n += 16) s = b != nullptr ? fmaf(a[(size_t)n * sa + ia], b[(size_t)n * sb + ib], s) : s + a[(size_t)n * sa + ia];
+    s = row16_sum(s);
+    if (l == 15 && dst != nullptr) *dst = p.accumulate ? *dst + s : s;
 }
 
-template <typename T>
+// dx[n,c,:] += dgc[n,c] on the attention planes, 16 bytes per access when the planes allow it
+template <typename T, bool VEC>
 __global__ void add_gap_term_kernel(T *dx, const float *dgc, int N, int C, int Ca, size_t plane)
 {
-    const size_t total = (size_t)N * Ca * plane;
+    constexpr int PER = VEC ? 16 / (int)sizeof(T) : 1;
+    const size_t groups = plane / PER, total = (size_t)N * Ca * groups;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const size_t nc = i / plane, q = i - nc * plane;
+        const size_t nc = i / groups, q = (i - nc * groups) * PER;
         const size_t n = nc / Ca, c = nc - n * Ca;
         T *dst = dx + (n * C + c) * plane + q;
-        const float v = bw_load(dst) + dgc[nc];
-        if constexpr (std::is_same<T, float>::value)
-            *dst = v;
-        else
-            dst->bits = bw_f32_to_bf16(v);
+        const float add = dgc[nc];
+        if constexpr (!VEC) {
+            const float v = bw_load(dst) + add;
+            if constexpr (std::is_same<T, float>::value)
+                *dst = v;
+            else
+                dst->bits = bw_f32_to_bf16(v);
+        } else if constexpr (std::is_same<T, float>::value) {
+            float4 v = *reinterpret_cast<float4 *>(dst);
+            v.x += add, v.y += add, v.z += add, v.w += add;
+            *reinterpret_cast<float4 *>(dst) = v;
+        } else {
+            uint4 w = *reinterpret_cast<uint4 *>(dst);
+            auto both = [&](uint32_t u) {
+                const float lo = __uint_as_float(u << 16) + add, hi = __uint_as_float(u & 0xffff0000u) + add;
+                return (uint32_t)bw_f32_to_bf16(lo) | ((uint32_t)bw_f32_to_bf16(hi) << 16);
+            };
+            w.x = both(w.x), w.y = both(w.y), w.z = both(w.z), w.w = both(w.w);
+            *reinterpret_cast<uint4 *>(dst) = w;
+        }
     }
 }
 
@@ -398,7 +452,7 @@ __attribute__((visibility("hidden"))) hipError_t launch_backward_sums(const Back
     hipError_t e = bf16 ? launch_corr_kc<bf16b>(p, kc, (unsigned)grid, s) : launch_corr_kc<float>(p, kc, (unsigned)grid, s);
     if (e != hipSuccess) return e;
     const size_t results = (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks + (size_t)p.N * p.Ca * 10;
-    hipLaunchKernelGGL(sums_kernel, dim3((unsigned)((results + 255) / 256)), dim3(256), 0, s, p, kc, tiles);
+    hipLaunchKernelGGL(sums_kernel, dim3((unsigned)((results * 16 + 255) / 256)), dim3(256), 0, s, p, kc, tiles);
     return hipGetLastError();
 }
 
@@ -411,7 +465,12 @@ __attribute__((visibility("hidden"))) hipError_t launch_backward_estimator(const
     const int K = p.hidden > 0 ? p.hidden : p.Ca;
     const size_t params = (p.has_gen ? (size_t)9 * p.Ca * K + 9 * p.Ca + (size_t)p.hidden * p.Ca + p.hidden : 0) +
                           (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks;
-    hipLaunchKernelGGL(estimator_param_kernel, dim3((unsigned)((params + 255) / 256)), dim3(256), 0, s, p);
+    // a row of 16 lanes per estimator parameter; the flipped LK takes one lane per element behind them
+    const size_t n_est = p.has_gen ? (size_t)9 * p.Ca * K + 9 * p.Ca + (size_t)p.hidden * p.Ca + p.hidden : 0;
+    const size_t n_lkf = (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks;
+    const size_t threads = n_est * 16 + (n_lkf + 15) / 16 * 16;
+    (void)params;
+    hipLaunchKernelGGL(estimator_param_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -419,13 +478,20 @@ __attribute__((visibility("hidden"))) hipError_t launch_backward_add_gap_term(co
                                                                               hipStream_t s)
 {
     if (p.Ca < 1 || !p.has_gen) return hipSuccess;
-    const size_t plane = (size_t)p.H * p.W, total = (size_t)p.N * p.Ca * plane;
+    const size_t plane = (size_t)p.H * p.W, es = bf16 ? 2 : 4, per = 16 / es;
+    const bool vec = plane % per == 0 && (uintptr_t)dx % 16 == 0;
+    const size_t total = (size_t)p.N * p.Ca * (vec ? plane / per : plane);
     size_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    if (bf16)
-        hipLaunchKernelGGL(add_gap_term_kernel<bf16b>, dim3((unsigned)blocks), dim3(256), 0, s, (bf16b *)dx, p.dgc, p.N, p.C, p.Ca, plane);
+    const dim3 grid((unsigned)blocks), block(256);
+    if (bf16 && vec)
+        hipLaunchKernelGGL((add_gap_term_kernel<bf16b, true>), grid, block, 0, s, (bf16b *)dx, p.dgc, p.N, p.C, p.Ca, plane);
+    else if (bf16)
+        hipLaunchKernelGGL((add_gap_term_kernel<bf16b, false>), grid, block, 0, s, (bf16b *)dx, p.dgc, p.N, p.C, p.Ca, plane);
+    else if (vec)
+        hipLaunchKernelGGL((add_gap_term_kernel<float, true>), grid, block, 0, s, (float *)dx, p.dgc, p.N, p.C, p.Ca, plane);
     else
-        hipLaunchKernelGGL(add_gap_term_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (float *)dx, p.dgc, p.N, p.C, p.Ca, plane);
+        hipLaunchKernelGGL((add_gap_term_kernel<float, false>), grid, block, 0, s, (float *)dx, p.dgc, p.N, p.C, p.Ca, plane);
     return hipGetLastError();
 }
 
