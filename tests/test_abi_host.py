@@ -152,6 +152,65 @@ def test_fused_forward_rejects_bad_arguments_before_launch(lib):
     assert fu(ws_bytes=need, lkc=0x60000) == E_WS
 
 
+def test_dense_forward_rejects_bad_arguments_before_launch(lib):
+    def de(x=0x10000, dt=0, N=1, C=64, H=8, W=8, Ca=16, lk=0x20000, Ks=13, gen=None, dk=None, out=0x90000,
+           ws=0x30000 * 256, ws_bytes=1 << 22):
+        return lib.esc_convattn_dense_forward(x, dt, N, C, H, W, Ca, lk, Ks, gen, dk, out, ws, ws_bytes, None)
+    assert de(x=None) == E_NULL
+    assert de(out=None) == E_NULL
+    assert de(lk=None) == E_NULL
+    assert de(dt=2) == E_DTYPE
+    assert de(Ks=0) == E_SHAPE
+    assert de(Ks=6) == E_UNSUP
+    assert de(Ks=19) == E_UNSUP                           # dense kernels stop at 17 x 17
+    assert de(C=80, Ca=65) == E_UNSUP                     # and at 64 attention channels
+    assert de(Ca=65) == E_SHAPE                           # C_a > C
+    assert de(out=0x10000) == E_ALIAS
+    assert de(out=0x90001, dt=1) == E_SHAPE               # misaligned for the storage type
+    assert de(lk=0x90000 + 64) == E_ALIAS                 # weights inside out
+    assert de(dk=0x90000 + 128) == E_ALIAS
+    assert de(gen=gen_struct(w_up=None)) == E_NULL
+    assert de(ws=None) == E_WS
+    plain = lib.esc_workspace_bytes(1, 16, 8, 8)
+    need = lib.esc_dense_workspace_bytes(1, 16, 8, 8, 13)
+    # room for DK and for the rearranged weights behind the forward's workspace
+    assert need % 256 == 0 and need - plain >= 16 * 9 * 4 + 16 * 16 * 169 * 4
+    assert lib.esc_dense_workspace_bytes(1, 16, 8, 8, 3) < need
+    assert lib.esc_dense_workspace_bytes(1, 16, 8, 8, 0) == 0
+    assert de(ws_bytes=need - 256) == E_WS
+    assert de(ws=0x90000 - 256, ws_bytes=need) == E_ALIAS  # workspace runs into out
+
+
+def test_backward_rejects_bad_arguments_before_launch(lib):
+    def bw(x=0x10000, go=0x50000, dt=0, N=1, C=64, H=8, W=8, Ca=16, lk=0x20000, Ks=13, stride=169, gen=None, dk=None,
+           gx=0x90000, glk=0x28000, ggen=None, gdk=None, acc=0, ws=0x30000 * 256, ws_bytes=1 << 22):
+        return lib.esc_convattn_backward(x, go, dt, N, C, H, W, Ca, lk, Ks, stride, gen, dk, gx, glk, ggen, gdk, acc,
+                                         ws, ws_bytes, None)
+    assert bw(x=None) == E_NULL
+    assert bw(go=None) == E_NULL
+    assert bw(gx=None) == E_NULL
+    assert bw(lk=None) == E_NULL
+    assert bw(dt=7) == E_DTYPE
+    assert bw(Ks=-1) == E_SHAPE
+    assert bw(Ks=8) == E_UNSUP
+    assert bw(Ks=33) == E_UNSUP
+    assert bw(stride=100) == E_SHAPE                      # channel stride shorter than one kernel
+    assert bw(Ca=65) == E_SHAPE
+    assert bw(gx=0x10000) == E_ALIAS                      # grad_x over x
+    assert bw(gx=0x50000) == E_ALIAS                      # grad_x over grad_out
+    assert bw(gx=0x90002) == E_SHAPE
+    assert bw(gen=gen_struct(w_up=None)) == E_NULL
+    assert bw(ws=None) == E_WS
+    plain = lib.esc_workspace_bytes(1, 16, 8, 8)
+    need = lib.esc_backward_workspace_bytes(1, 16, 8, 8, 13, 0)
+    assert need % 256 == 0 and need > plain
+    assert lib.esc_backward_workspace_bytes(1, 16, 8, 8, 13, 8) >= need       # a hidden layer keeps more
+    assert lib.esc_backward_workspace_bytes(1, 16, 8, 8, 13, -1) == 0
+    assert lib.esc_backward_workspace_bytes(1, 16, 8, 8, 0, 0) == 0
+    assert bw(ws_bytes=need - 256) == E_WS
+    assert bw(ws=0x90000 - 256, ws_bytes=need) == E_ALIAS
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(1, 4, 8, 8)
