@@ -136,7 +136,7 @@ struct Plan {
     unsigned per_die;
 };
 
-Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_steps)
+Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_grains)
 {
     const unsigned U = (unsigned)device_cus() / kXcds;          // compute units per die
     const unsigned Smax = (unsigned)blocks_per_cu * (U ? U : 1);  // resident blocks per die
@@ -157,6 +157,12 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_steps)
     if (p.pool_mode == kPoolItems && p.n_conv > 0 && per_die_of(p.n_conv) + per_die_of(p.n_gen) <= Smax) {
         p.pool_mode = kPoolFused;
         p.n_pool = 0;
+    } else if (p.dk_mode == kDkMeans) {
+        // Longer calls: a conv item that runs the estimator itself pays for it (mailboxes,
+        // barriers) in every one of a block's items, while the hop it saves is waited for once
+        // per call: one gen item per image publishes DK instead (measured at 540 x 960).
+        p.n_gen = p.n_gsum + (unsigned)p.N;
+        p.dk_mode = kDkBoxes;
     }
 
     // Short calls (the conv items' own chain of tile load, taps, estimator and store is most of
@@ -170,15 +176,15 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_steps)
     }
 
     // Carried copy, everywhere else: every conv item moves an equal share of its image's
-    // pass-through range from inside its tap loop, one 4 KiB grain per step, as far as the
-    // steps go; copy items are left with what lies beyond.
+    // pass-through range, in 4 KiB grains, as many as its registers hold; copy items are left
+    // with what lies beyond.
     p.carry_g = 0;
     p.copy_off = 0;
-    if (carry_steps > 0 && !p.copy_gentle && p.n_conv > 0 && p.idt_len > 0 && p.copy_vec_ok) {
+    if (carry_grains > 0 && !p.copy_gentle && p.n_conv > 0 && p.idt_len > 0 && p.copy_vec_ok) {
         const size_t per_img = p.n_conv / (size_t)p.N;
         const size_t grains = (p.idt_len + kGrain - 1) / kGrain;
         size_t g = (grains + per_img - 1) / per_img;
-        if (g > (size_t)carry_steps) g = (size_t)carry_steps;
+        if (g > (size_t)carry_grains) g = (size_t)carry_grains;
         p.carry_g = (unsigned)g;
         const size_t carried = per_img * g * kGrain;
         p.copy_off = carried < p.idt_len ? carried : p.idt_len;
@@ -314,7 +320,7 @@ esc_status launch_forward(FwdParams &p, int Ks, bool bf16, hipStream_t s)
     const int ks_slot = (Ks + 1) / 2;
     const int bpc = resident_blocks_per_cu(ks_slot, ry, bf16, p.staged != 0);
     if (bpc < 1) return ESC_ERR_UNSUPPORTED;
-    const Plan plan = plan_items(p, Ks, bpc, Ks > 0 && conv_carries(Ks, ry, bf16) ? ry + Ks - 1 : 0);
+    const Plan plan = plan_items(p, Ks, bpc, Ks > 0 ? conv_carry_grains(Ks, ry, bf16) : 0);
     if ((u64)p.n_pool + p.n_gen + p.n_conv + p.n_copy >= ((u64)1 << 30)) return ESC_ERR_UNSUPPORTED;
     const unsigned grid = plan.per_die * kXcds;
     return kLaunch[ks_slot](ry, bf16, p.staged != 0, grid, s, p) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
@@ -339,6 +345,8 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
     p.div_ptiles_x = make_div((uint32_t)l.ptiles_x);
     // aligned 4-element chunk loads (halo tile, pool tile) need W % 4 == 0 and an aligned base
     p.conv_ld_vec = (W % 4 == 0) && ((uintptr_t)x % (4 * (size_t)p.elem_bytes) == 0);
+    // bf16: 16-byte pieces of 8 elements where the width and the base allow them
+    if (p.conv_ld_vec && dt == ESC_BF16 && W % 8 == 0 && (uintptr_t)x % 16 == 0) p.conv_ld_vec = 2;
     p.div_ca = make_div((uint32_t)(Ca > 0 ? Ca : 1));
     p.div_tiles_x = p.div_tiles_y = p.div_chunks = p.div_mix = p.div_mix_a = p.div_mix_b = make_div(1);
     if (gen != nullptr && Ca > 0) {
@@ -362,8 +370,13 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
         p.staged = p.dk_mode == kDkFromG || !small_est;
         if (p.dk_mode == kDkFromG) {
             p.n_gsum = (unsigned)((size_t)N * Ca);
-            p.n_gen = p.n_gsum + (unsigned)N;
-            p.dk_mode = kDkBoxes;
+            if (small_est) {  // the conv items run the estimator themselves, from the means
+                p.n_gen = p.n_gsum;
+                p.dk_mode = kDkMeans;
+            } else {
+                p.n_gen = p.n_gsum + (unsigned)N;
+                p.dk_mode = kDkBoxes;
+            }
         }
     }
     char *w = (char *)workspace;

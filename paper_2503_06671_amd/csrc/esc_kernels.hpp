@@ -3,9 +3,10 @@
 // kernel for one kernel size per translation unit) and by esc_api.hip (host side, C ABI).
 //
 // The operation is Eq. 4 of the ESC paper with the depth-wise large kernel of
-// the paragraph around Eq. 5.  Everything is plain fp32 vector arithmetic (a
-// depth-wise convolution has no reduction shared between outputs, so there is
-// nothing to feed a matrix core with).
+// the paragraph around Eq. 5.  With fp32 storage everything is plain fp32 vector
+// arithmetic (a depth-wise convolution has no reduction shared between outputs); with
+// bf16 storage and Ks <= 17 the tap loop multiplies bf16 tile rows with the kernel rows'
+// Toeplitz matrices on the matrix cores, fp32 accumulation (MatrixGeom).
 //
 // One launch does the whole forward.  The work is cut into items, in this order in
 // every die's list:
@@ -48,7 +49,8 @@
 //     and SIMD, one with both operands in vector registers at up to 0.375 (four
 //     wavefronts; 0.34 with two, 0.20 with one), so the tap weights are read from LDS
 //     (a broadcast read) into vector registers; the bf16 dot instruction saturates at
-//     0.236, so two taps per instruction pay most when few wavefronts convolve;
+//     0.236, so two taps per instruction gain little on a full compute unit - the bf16
+//     tap loop therefore runs on the matrix cores;
 //   - vector-memory results return in order, so an atomic with a slow answer delays
 //     every later load of its wavefront, and a wait for a load is also a wait for every
 //     store issued before it: the leave announcement is issued where no wait on memory
@@ -84,7 +86,7 @@ constexpr unsigned kSpinLimit = 1u << 20;  // bounded wait: about a second, far 
 constexpr int kBlocksPerCu = 4;    // resident blocks per compute unit the kernel is compiled for (<= 128 VGPRs)
 constexpr int kCopyVecPerThread = 4;
 constexpr size_t kCopyPiece = (size_t)kThreads * 16 * kCopyVecPerThread;  // bytes a block has in flight
-constexpr size_t kGrain = (size_t)kThreads * 16;  // bytes a conv item moves per step of its tap loop (carried copy)
+constexpr size_t kGrain = (size_t)kThreads * 16;  // a grain of the carried copy: 16 bytes per thread of a conv item
 constexpr int kStage = 1024;       // pool mailboxes staged in LDS per round (multiple of 64)
 constexpr int kPollThreads = 192;  // wavefronts 0-2 poll mailboxes; wavefront 3 carries the leave atomic
 constexpr int kStagePerThread = (kStage + kPollThreads - 1) / kPollThreads;
@@ -98,15 +100,15 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 // Which conv variants move a share of the pass-through copy from inside their tap loops
 // (carried copy): the four-row blocks with bf16 storage.  Their calls fill every block
-// slot with conv items whose tap loops are bound by the dot instruction's rate, so the
-// streaming finds idle memory pipes under the arithmetic and no block to run in beside it.
+// slot with conv items, so the streaming finds no block to run in beside them, and idle
+// memory pipes under their tap loops.
 // Measured, the other variants lose by it: short fp32 calls last as long as their chain of
 // tile load, taps, estimator and store, which extra traffic stretches, and long fp32 calls
 // already alternate conv and copy items.
 constexpr bool conv_carries(int ks, int ry, bool bf16) { return bf16 && ry == 4 && ks <= 17; }
-// grains a thread of such a variant has in flight: a step of the tap loop is far shorter
-// than a round trip to memory
-constexpr int conv_carry_depth(int ks, int ry, bool bf16) { return conv_carries(ks, ry, bf16) ? 3 : 0; }
+// grains (16 bytes per thread, 4 KiB per block) such an item has room for in its registers
+constexpr int kCarryGrains = 6;
+constexpr int conv_carry_grains(int ks, int ry, bool bf16) { return conv_carries(ks, ry, bf16) ? kCarryGrains : 0; }
 typedef __amdgpu_buffer_rsrc_t CarryRsrc;
 constexpr int kRawBufferFlags = 0x00020000;  // raw buffer (no stride, no swizzle), 32-bit data format
 constexpr int kBufferNt = 2;                 // non-temporal
@@ -123,8 +125,11 @@ enum : int {
     kDkGiven = 1,   // caller's dk_in
     kDkBoxes = 2,   // published by a gen item (esc_dynkernel_gen: the gen items also write dk_out)
     kDkDirect = 3,  // each conv item finishes the GAP and runs its nine estimator outputs itself
-    kDkFromG = 4    // host only, while a call is set up: larger planes, whose means come from gsum
-                    // items (n_gsum > 0); the call then runs as kDkBoxes
+    kDkFromG = 4,   // host only, while a call is set up: larger planes, whose means come from gsum
+                    // items (n_gsum > 0); the call then runs as kDkBoxes or kDkMeans
+    kDkMeans = 5    // larger planes, small estimator: each conv item collects its image's channel
+                    // means from the gsum items' mailboxes and runs its nine estimator outputs itself
+                    // (one mailbox hop fewer than through a gen item)
 };
 enum : int {
     kPoolNone = 0,   // no estimator in this call
@@ -181,8 +186,8 @@ struct FwdParams {
     int copy_gentle;
     // Carried copy: conv item j of an image (j counts its tiles channel-major) moves bytes
     // [j * carry_g * kGrain, (j + 1) * carry_g * kGrain) of the image's pass-through range
-    // from inside its tap loop, one grain per step; the copy items cover what lies beyond
-    // copy_off (bytes from the start of the range).  0 = nothing is carried.
+    // (loaded behind its tile, stored behind its tap loop); the copy items cover what lies
+    // beyond copy_off (bytes from the start of the range).  0 = nothing is carried.
     unsigned carry_g;
     size_t copy_off;
 };
@@ -268,14 +273,6 @@ __device__ __forceinline__ void load4(const bf16_t *p, float *v)
 __device__ __forceinline__ uint2 load4_raw(const bf16_t *p) { return *reinterpret_cast<const uint2 *>(p); }
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-// c + a.lo * b.lo + a.hi * b.hi on pairs of bf16, accumulated in fp32: one instruction,
-// two taps
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
-{
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
-}
 
 // x / d for x < 2^31 by multiply-high and shift (host fills mul and shift)
 __device__ __forceinline__ uint32_t fdiv(uint32_t x, uint32_t mul, uint32_t shift)
@@ -929,26 +926,51 @@ struct ConvGeom {
     static constexpr bool UNROLL = KS <= 17;
 };
 
-// bf16 storage with an unrolled tap loop: the halo tile stays bf16 in LDS, two pixels per
-// 32-bit word exactly as they lie in memory (word w of a row holds the pixels at global
-// x = g0 + 2w, g0 + 2w + 1 with g0 a multiple of four), and a kernel row is staged as
-// pairs of bf16 weights in two phases: (w0,w1),(w2,w3),... for outputs whose first tap
-// falls on an even tile column, (0,w0),(w1,w2),... for the others.  One dot2 then applies
-// two taps, on words that are always aligned pairs.
+// bf16 storage with Ks <= 17: the tap loop runs on the matrix cores.  One row of the
+// depth-wise kernel applied to 16 neighbouring outputs of an image row is a product with a
+// banded (Toeplitz) matrix: out[x0 + m] += sum_k T_i[m][k] * x[row + i][t0 + k], with
+// T_i[m][k] = LK[i][k - m - S0] inside the band and 0 outside, and 16 + Ks - 1 <= 32 input
+// columns are exactly the K of one v_mfma_f32_16x16x32_bf16.  A = T_i (16 output columns x
+// 32 tile columns), B = 32 tile columns x 16 image rows, so the instruction yields a 16 x 16
+// block of outputs for kernel row i; Ks of them, the tile rows moving down by one each time,
+// finish the block.  (60 % of the products are with zeros of the band; the matrix cores
+// are 17 times faster than the dot instruction, which bounded these calls.)
+//
+// LDS layout: the tile is cut into pieces of 8 columns (16 bytes) and stored piece column
+// after piece column - element (r, t) at ((t / 8) * HRP + r) * 8 + t % 8 - so that the 16
+// lanes that read one B operand's rows at one piece column read 256 consecutive bytes (the
+// LDS delivers 16-byte reads at full rate only then; row-major with any pitch runs at half).
+// HRP is odd: pieces of neighbouring columns start on different banks.  Tile column t is
+// image column x0 - PH - A + t (A pads the halo to 8 columns, so that a piece is 16 aligned
+// bytes of memory where the image's width and base allow 16-byte fetches); all 80
+// columns of every row are written for every item, because what lies beyond the halo is
+// multiplied by the zeros of the band and must not be stale.  Lane (m, kg) = (l % 16, l / 16)
+// of an A operand holds T_i[m][8 kg ... 8 kg + 7], which depends on 8 kg - m alone: the 40
+// distinct operands per kernel row are staged behind the tile, 16 bytes each.
 template <int KS, int RY>
-struct PackedGeom {
+struct MatrixGeom {
     using G = ConvGeom<KS, RY>;
-    static constexpr int A = (4 - G::PH % 4) % 4;     // tile columns before the halo's first, so chunks stay aligned
-    static constexpr int NCH = (G::HC + A + 3) / 4;   // 4-pixel chunks per tile row
-    static constexpr int PITCH_E = 4 * NCH, PITCH_D = 2 * NCH;
-    static constexpr int S0 = A + G::OFF;             // tile column of tap 0 for output 0 of thread column 0
-    static constexpr int NP = (KS + 1) / 2;           // weight pairs per kernel row and phase
-    static constexpr int DSTART = (S0 >> 1) & ~1;     // first word a thread reads of a row (relative to 2*tx), even
-    static constexpr int DLAST = ((3 + S0) >> 1) + NP - 1;
-    static constexpr int NVD = ((DLAST - DSTART + 1) + 1) & ~1;  // words per row and thread, even
-    static constexpr int WPD = (2 * NP + 3) & ~3;     // words per staged kernel row
-    static_assert(30 + DSTART + NVD <= PITCH_D, "a thread would read past its tile row");
-    static_assert(G::HR * PITCH_D <= kLdsTileFloats && KS * WPD <= kLdsWeightFloats, "LDS pool too small");
+    static constexpr int A = (8 - G::PH % 8) % 8;  // the halo starts a multiple of 8 columns left of the tile's outputs
+    static constexpr int S0 = A + G::OFF;        // tile column of tap 0 for output column 0
+    static constexpr int COLS = kTileW + 16;     // 80 tile columns
+    static constexpr int NCH = COLS / 4;         // 4-element chunks per tile row
+    static constexpr int HRP = G::HR | 1;        // rows per piece column (odd)
+    static constexpr int TILE_WORDS = (COLS / 8) * HRP * 4;
+    static constexpr int ND = 40;                // 8 kg - m + 15 = 0 ... 39
+    static constexpr int TBL_WORDS = KS * ND * 4;
+    // After the tap loop the table's place takes the output tile on its way to memory: bf16,
+    // row-major, OP words per row (the results leave the matrix cores as 16 rows x 4 columns
+    // per lane group, which would be stored in 32-byte runs; passed through LDS, sixteen
+    // lanes store a whole 128-byte row segment).  The odd multiple of two words keeps the
+    // sixteen rows a wavefront writes at once on different banks.
+    static constexpr int OP = kTileW / 2 + 2;
+    static constexpr int OUT_WORDS = G::TH * OP;
+    static_assert(KS > 17 || G::HC + A <= COLS, "the halo does not fit in 80 tile columns");
+    static_assert(KS > 17 || 15 + (KS - 1) + S0 <= 31, "a block of 16 outputs needs more than 32 tile columns");
+    static_assert(KS > 17 || TILE_WORDS + (TBL_WORDS > OUT_WORDS ? TBL_WORDS : OUT_WORDS) <= kLdsTileFloats,
+                  "LDS pool too small");  // (larger kernels do not take this path)
+    // word (two bf16) `wi` of tile row r
+    __device__ static __forceinline__ int word(int r, int wi) { return ((wi >> 2) * HRP + r) * 4 + (wi & 3); }
 };
 
 // where a conv item lies
@@ -981,10 +1003,10 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     float *tile = g_tile, *wl = g_wl, *s_dk = g_small, *s_part = g_part, *s_g = g_g, *s_t = g_t;
     constexpr int PH = G::PH, OFF = G::OFF, TH = G::TH, HR = G::HR, HC = G::HC, PITCH = G::PITCH,
                   NV = G::NV, WP = G::WP;
-    // bf16 storage and an unrolled loop: packed tile, two taps per instruction (PackedGeom)
-    constexpr bool kPacked = std::is_same<T, bf16_t>::value && G::UNROLL;
-    using PG = PackedGeom<KS, RY>;
-    uint32_t *tile_d = reinterpret_cast<uint32_t *>(g_tile), *wl_d = reinterpret_cast<uint32_t *>(g_wl);
+    // bf16 storage and Ks <= 17: bf16 tile in pieces of 8 columns, tap loop on the matrix cores (MatrixGeom)
+    constexpr bool kMatrix = std::is_same<T, bf16_t>::value && G::UNROLL;
+    using MG = MatrixGeom<KS, RY>;
+    uint32_t *tile_d = reinterpret_cast<uint32_t *>(g_tile), *tbl_d = tile_d + MG::TILE_WORDS;
     uint16_t *tile_h = reinterpret_cast<uint16_t *>(g_tile);
     const int H = p->H, W = p->W;
 
@@ -1002,18 +1024,24 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     // is computed once per kernel and then held in registers through all items)
     const int tid1 = opaque_tid();
     float wreg[KW];
-    constexpr int KWP = (KS * 2 * PG::NP + kThreads - 1) / kThreads;  // packed: one weight pair per thread and round
+    // matrix path: word idx of the Toeplitz table holds the band's entries for two
+    // neighbouring tile columns: kernel row i = idx / 160, operand d = (idx % 160) / 4,
+    // columns k = 2 (idx % 4), + 1 of the operand's eight, i.e. taps j = d - 15 + k - S0
+    constexpr int KWP = (MG::TBL_WORDS + kThreads - 1) / kThreads;
     float wpa[KWP], wpb[KWP];
-    if constexpr (kPacked) {
+    if constexpr (kMatrix) {
 #pragma unroll
         for (int m = 0; m < KWP; ++m) {
             const int idx = m * kThreads + tid1;
-            const int i = idx / (2 * PG::NP), rem = idx - i * (2 * PG::NP);
-            const int ph = rem / PG::NP, mm = rem - ph * PG::NP;
-            const int ja = 2 * mm - ph, jb = ja + 1;  // the two taps of this pair
-            const bool in = idx < KS * 2 * PG::NP;
-            wpa[m] = (in && ja >= 0 && ja < KS) ? lkc[i * KS + ja] : 0.f;
-            wpb[m] = (in && jb < KS) ? lkc[i * KS + jb] : 0.f;
+            int i = idx / (MG::ND * 4);
+            const int rem = idx - i * (MG::ND * 4);
+            const int ja = (rem >> 2) - 15 + 2 * (rem & 3) - MG::S0, jb = ja + 1;
+            i = i < KS ? i : KS - 1;
+            // (unconditional loads from clamped addresses, masked afterwards)
+            const float va = lkc[i * KS + (ja < 0 ? 0 : ja >= KS ? KS - 1 : ja)];
+            const float vb = lkc[i * KS + (jb < 0 ? 0 : jb >= KS ? KS - 1 : jb)];
+            wpa[m] = (ja >= 0 && ja < KS) ? va : 0.f;
+            wpb[m] = (jb >= 0 && jb < KS) ? vb : 0.f;
         }
     } else {
 #pragma unroll
@@ -1023,13 +1051,81 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         }
     }
 
+    // Carried copy (Eq. 4 lines 1 and 4): this item's share of the image's pass-through range
+    // - up to kCarryGrains grains of 16 bytes per thread - is asked for right behind the tile
+    // (and behind the call tag: results return in order, and the tile and the tag are waited
+    // for first), travels while the tile is filled and multiplied, and is stored after the
+    // tap loop, where the item would otherwise only wait for the estimator.  Memory thus
+    // streams from the start of the item, with no block of its own.  (Measured against moving
+    // the share after the loop, before the tile in every other block, or loading it after the
+    // pool sums: this order is the fastest at 360 x 640 and 64 x 64 x 64.)  Buffer accesses:
+    // the resources end with the share, so grains beyond it read as nothing and their stores
+    // are dropped, without a branch.
+    constexpr bool kCarry = conv_carries(KS, RY, std::is_same<T, bf16_t>::value);
+    constexpr int kCarryN = kCarry ? kCarryGrains : 1;
+    CarryRsrc carry_dst = __builtin_amdgcn_make_buffer_rsrc(nullptr, 0, 0, kRawBufferFlags);
+    u32x4 carry_v[kCarryN] = {};
+    auto carry_load = [&]() {
+        if constexpr (kCarry) {
+            const unsigned per_plane = p->div_tiles_x.d * p->div_tiles_y.d;
+            const size_t j = (size_t)c * per_plane + (size_t)tyi * p->div_tiles_x.d + (size_t)txi;
+            const size_t share = (size_t)p->carry_g * kGrain;
+            const size_t begin = j * share;
+            const size_t lim = p->copy_off;  // what the conv items carry ends here
+            const size_t len = begin < lim ? (lim - begin < share ? lim - begin : share) : 0;
+            const size_t base = (size_t)n * p->img_bytes + p->idt_off + begin;
+            const CarryRsrc src =
+                __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)p->x + base), 0, (int)len, kRawBufferFlags);
+            carry_dst = __builtin_amdgcn_make_buffer_rsrc((void *)((char *)p->out + base), 0, (int)len, kRawBufferFlags);
+            const int voff = tid1 * 16;
+#pragma unroll
+            for (int r = 0; r < kCarryN; ++r)
+                carry_v[r] = __builtin_amdgcn_raw_buffer_load_b128(src, voff + r * (int)kGrain, 0, kBufferNt);
+        }
+    };
+    auto carry_store = [&]() {
+        if constexpr (kCarry) {
+            const int voff = opaque_tid() * 16;
+#pragma unroll
+            for (int r = 0; r < kCarryN; ++r)
+                __builtin_amdgcn_raw_buffer_store_b128(carry_v[r], carry_dst, voff + r * (int)kGrain, 0, kBufferNt);
+        }
+    };
+
     // halo tile -> LDS, zero outside the image
-    if (p->conv_ld_vec) {
+    if (kMatrix && p->conv_ld_vec == 2) {
+        // bf16, W % 8 == 0 and a 16-byte aligned base: whole pieces of 8 columns (each lies
+        // entirely inside or outside the image), all loads in flight before the first LDS write
+        if constexpr (kMatrix) {
+            constexpr int NP8 = MG::COLS / 8;
+            constexpr int TOT = HR * NP8;
+            constexpr int K = (TOT + kThreads - 1) / kThreads;
+            const int g0 = x0 - PH - MG::A;
+            u32x4 raw[K];
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const int q = k * kThreads + tid1;
+                const int r = q / NP8, j = q - r * NP8;
+                const int gy = y0 - PH + r, gx = g0 + 8 * j;
+                const bool in = q < TOT && gy >= 0 && gy < H && gx >= 0 && gx < W;
+                raw[k] = u32x4{0u, 0u, 0u, 0u};
+                if (in) raw[k] = *reinterpret_cast<const u32x4 *>(xp + (size_t)gy * W + gx);
+            }
+            if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
+            carry_load();
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const int q = k * kThreads + tid1;
+                const int r = q / NP8, j = q - r * NP8;
+                if (q < TOT) *reinterpret_cast<u32x4 *>(tile_d + MG::word(r, 4 * j)) = raw[k];
+            }
+        }
+    } else if (p->conv_ld_vec) {
         // W % 4 == 0 and an aligned base: fetch whole 4-element chunks aligned in global
         // memory (each lies entirely inside or outside the image), all loads in flight
         // before the first LDS write.  A chunk lands at LDS column 4j - A.
-        constexpr int A = (4 - PH % 4) % 4;
-        constexpr int NCH = (HC + A + 3) / 4;
+        constexpr int A = kMatrix ? MG::A : (4 - PH % 4) % 4;
+        constexpr int NCH = kMatrix ? MG::NCH : (HC + A + 3) / 4;
         constexpr int TOT = HR * NCH;
         constexpr int K = (TOT + kThreads - 1) / kThreads;
         const int g0 = x0 - PH - A;
@@ -1041,7 +1137,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             const int r = q / NCH, j = q - r * NCH;
             const int gy = y0 - PH + r, gx = g0 + 4 * j;
             const bool in = q < TOT && gy >= 0 && gy < H && gx >= 0 && gx < W;
-            if constexpr (kPacked) {
+            if constexpr (kMatrix) {
                 raw[k] = make_uint2(0u, 0u);
                 if constexpr (std::is_same<T, bf16_t>::value)
                     if (in) raw[k] = load4_raw(xp + (size_t)gy * W + gx);
@@ -1052,12 +1148,13 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             }
         }
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
+        carry_load();
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int q = k * kThreads + tid1;
             const int r = q / NCH, j = q - r * NCH;
-            if constexpr (kPacked) {  // the chunk goes where it lies: word 2j of row r
-                if (q < TOT) *reinterpret_cast<uint2 *>(tile_d + r * PG::PITCH_D + 2 * j) = raw[k];
+            if constexpr (kMatrix) {  // the chunk is words 2j, 2j + 1 of row r
+                if (q < TOT) *reinterpret_cast<uint2 *>(tile_d + MG::word(r, 2 * j)) = raw[k];
             } else if (q < TOT) {
                 float *dst = tile + r * PITCH + 4 * j - A;
                 if (A == 0) {
@@ -1071,19 +1168,20 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                 }
             }
         }
-    } else if constexpr (kPacked) {
-        // element by element, the whole pitch of every row (what lies beyond the halo is
-        // multiplied by the zero half of a weight pair and must not be stale LDS)
+    } else if constexpr (kMatrix) {
+        // element by element, all 80 columns of every row (what lies beyond the halo is
+        // multiplied by the zeros of the band and must not be stale LDS)
         if constexpr (std::is_same<T, bf16_t>::value) {
-            for (int idx = tid1; idx < HR * PG::PITCH_E; idx += kThreads) {
-                const int r = idx / PG::PITCH_E, cc = idx - r * PG::PITCH_E;
-                const int gy = y0 - PH + r, gx = x0 - PH - PG::A + cc;
+            for (int idx = tid1; idx < HR * MG::COLS; idx += kThreads) {
+                const int r = idx / MG::COLS, cc = idx - r * MG::COLS;
+                const int gy = y0 - PH + r, gx = x0 - PH - MG::A + cc;
                 uint16_t v = 0;
                 if (gy >= 0 && gy < H && gx >= 0 && gx < W) v = xp[(size_t)gy * W + gx].bits;
-                tile_h[idx] = v;
+                tile_h[2 * MG::word(r, cc >> 1) + (cc & 1)] = v;
             }
         }
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
+        carry_load();
     } else {
         for (int idx = tid1; idx < HR * HC; idx += kThreads) {
             const int r = idx / HC, cc = idx - r * HC;
@@ -1094,13 +1192,12 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         }
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
     }
-    if constexpr (kPacked) {
+    if constexpr (kMatrix) {
 #pragma unroll
         for (int m = 0; m < KWP; ++m) {
             const int idx = m * kThreads + tid1;
-            const int i = idx / (2 * PG::NP), rem = idx - i * (2 * PG::NP);
-            if (idx < KS * 2 * PG::NP)
-                wl_d[i * PG::WPD + rem] = (uint32_t)f32_to_bf16_bits(wpa[m]) | ((uint32_t)f32_to_bf16_bits(wpb[m]) << 16);
+            if (idx < MG::TBL_WORDS)
+                tbl_d[idx] = (uint32_t)f32_to_bf16_bits(wpa[m]) | ((uint32_t)f32_to_bf16_bits(wpb[m]) << 16);
         }
     } else {
 #pragma unroll
@@ -1137,9 +1234,9 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             float s = 0.f;
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
-                if constexpr (kPacked) {  // the same four pixels, in the same order
+                if constexpr (kMatrix) {  // the same four pixels, in the same order
                     const uint2 w2 = *reinterpret_cast<const uint2 *>(
-                        tile_d + (h * kPoolTileH + 2 * ty + a + PH) * PG::PITCH_D + 2 * tx + (PH + PG::A) / 2);
+                        tile_d + MG::word(h * kPoolTileH + 2 * ty + a + PH, 2 * tx + (PH + MG::A) / 2));
                     s += bf16_lo(w2.x);
                     s += bf16_hi(w2.x);
                     s += bf16_lo(w2.y);
@@ -1163,9 +1260,12 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     // looked at after the loop, so that their round trips cost nothing.
     constexpr int kPer = (kDirectMaxBoxes + kPollThreads - 1) / kPollThreads;
     const bool from_boxes = p->dk_mode == kDkBoxes;  // a gen item publishes DK itself
-    const bool direct = p->dk_mode == kDkDirect;
-    const int nbox = from_boxes ? 9 : p->Ca * p->ptiles;
-    const u64 *img_boxes = from_boxes ? p->dk_box + (size_t)nc * 9 : p->pool_box + (size_t)n * nbox;
+    const bool means = p->dk_mode == kDkMeans;
+    const bool direct = p->dk_mode == kDkDirect || means;  // this item runs the estimator
+    const int nbox = from_boxes ? 9 : means ? p->Ca : p->Ca * p->ptiles;
+    const u64 *img_boxes = from_boxes ? p->dk_box + (size_t)nc * 9
+                           : means    ? p->g_box + (size_t)n * nbox
+                                      : p->pool_box + (size_t)n * nbox;
     const int Kin = p->hidden > 0 ? p->hidden : p->Ca;
     const bool pre_w = direct && 9 * Kin <= kThreads && p->hidden * p->Ca <= kThreads;
     u64 early[kPer];
@@ -1213,27 +1313,18 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         for (int q = 0; q < 4; ++q) acc[oy][q] = 0.f;
 
     const float *trow = tile + (ty * RY) * PITCH + 4 * tx;
-    const uint32_t *trow_p = tile_d + (ty * RY + OFF) * PG::PITCH_D + 2 * tx + PG::DSTART;  // packed tile
 
     // The tap loop, software-pipelined by hand so that the register use is ours to decide:
     // while row r is multiplied, tile row r+1 is already on its way from LDS (two buffers),
     // and kernel row r - the only new one - arrives while the older kernel rows, held in
     // registers from the steps before, are applied first.  A scheduling barrier ends every
     // step so the compiler cannot pull later rows' loads up and run out of registers.
-    // XT is what a tile row and a kernel row are held as: floats, or words of two bf16.
-    using XT = typename std::conditional<kPacked, uint32_t, float>::type;
-    constexpr int NX = kPacked ? PG::NVD : NV;       // values of a tile row per thread
-    constexpr int NWT = kPacked ? 2 * PG::NP : KS;   // values of a kernel row
+    // (The matrix path has a loop of its own, further down.)
+    using XT = float;
+    constexpr int NX = NV;    // values of a tile row per thread
+    constexpr int NWT = KS;   // values of a kernel row
     auto load_x = [&](int r, XT *v) {
-        if constexpr (kPacked) {
-            const uint2 *src = reinterpret_cast<const uint2 *>(trow_p + r * PG::PITCH_D);
-#pragma unroll
-            for (int k = 0; k < NX / 2; ++k) {
-                const uint2 f = src[k];
-                v[2 * k + 0] = f.x;
-                v[2 * k + 1] = f.y;
-            }
-        } else if (OFF == 0) {
+        if (OFF == 0) {
             const float4 *src = reinterpret_cast<const float4 *>(trow + r * PITCH);
 #pragma unroll
             for (int k = 0; k < NV / 4; ++k) {
@@ -1250,19 +1341,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         }
     };
     auto load_w = [&](int i, XT *w) {
-        if constexpr (kPacked) {
-            const uint32_t *wsrc = wl_d + i * PG::WPD;
-#pragma unroll
-            for (int k = 0; k + 4 <= NWT; k += 4) {
-                const uint4 f = *reinterpret_cast<const uint4 *>(wsrc + k);
-                w[k + 0] = f.x;
-                w[k + 1] = f.y;
-                w[k + 2] = f.z;
-                w[k + 3] = f.w;
-            }
-#pragma unroll
-            for (int k = NWT & ~3; k < NWT; ++k) w[k] = wsrc[k];
-        } else {
+        {
             const float *wsrc = wl + i * WP;
 #pragma unroll
             for (int k = 0; k + 4 <= KS; k += 4) {
@@ -1276,81 +1355,21 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             for (int k = KS & ~3; k < KS; ++k) w[k] = wsrc[k];
         }
     };
-    // packed: output q of the thread starts at tile column 4*tx + q + S0; its pairs are the
-    // row's words from ((q + S0) >> 1) on, with the weight pairs of that column's parity
     auto fma_row = [&](float *a, const XT *w, const XT *v) {
-        if constexpr (kPacked) {
 #pragma unroll
-            for (int m = 0; m < PG::NP; ++m)
+        for (int j = 0; j < KS; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    a[q] = dot2_bf16(w[((q + PG::S0) & 1) * PG::NP + m], v[((q + PG::S0) >> 1) - PG::DSTART + m], a[q]);
-        } else {
-#pragma unroll
-            for (int j = 0; j < KS; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) a[q] = fmaf(w[j], v[j + q], a[q]);
-        }
+            for (int q = 0; q < 4; ++q) a[q] = fmaf(w[j], v[j + q], a[q]);
     };
-    // what may move across a step boundary: arithmetic only - not LDS traffic, and not the
-    // carried copy's loads and stores, each of which belongs to its step
+    // what may move across a step boundary: arithmetic only, not LDS traffic
     constexpr int kSchedNoLds = 0x1 | 0x2 | 0x4;
 
-    // Carried copy (Eq. 4 lines 1 and 4): this item's share of the image's pass-through range
-    // moves from inside the tap loop - step r loads grain r (16 bytes per thread) and stores
-    // grain r - 1 - so the streaming runs under the arithmetic on the same compute unit, with
-    // no block of its own.  Buffer accesses: the resources' sizes end the share, so grains
-    // beyond it read as nothing and their stores are dropped, without a branch in the loop.
-    constexpr bool kCarry = conv_carries(KS, RY, std::is_same<T, bf16_t>::value);
-    constexpr int kCarrySteps = G::ROWS;
-    CarryRsrc carry_src, carry_dst;
-    if constexpr (!kCarry) {
-        carry_src = carry_dst = __builtin_amdgcn_make_buffer_rsrc(nullptr, 0, 0, kRawBufferFlags);  // unused
-    } else {
-        const unsigned per_plane = p->div_tiles_x.d * p->div_tiles_y.d;
-        const size_t j = (size_t)c * per_plane + (size_t)tyi * p->div_tiles_x.d + (size_t)txi;
-        const size_t share = (size_t)p->carry_g * kGrain;
-        const size_t begin = j * share;
-        const size_t lim = p->copy_off;  // what the conv items carry ends here
-        const size_t len = begin < lim ? (lim - begin < share ? lim - begin : share) : 0;
-        const size_t base = (size_t)n * p->img_bytes + p->idt_off + begin;
-        carry_src = __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)p->x + base), 0, (int)len, kRawBufferFlags);
-        carry_dst = __builtin_amdgcn_make_buffer_rsrc((void *)((char *)p->out + base), 0, (int)len, kRawBufferFlags);
-    }
-    // kCarryDepth grains are in flight per thread (a grain's store follows its load that
-    // many steps later): one step is far shorter than a round trip to memory.
-    constexpr int kCarryDepth = kCarry ? conv_carry_depth(KS, RY, std::is_same<T, bf16_t>::value) : 1;
-    static_assert(kCarryDepth >= 1, "a carrying variant has at least one grain in flight");
-    u32x4 carry_v[kCarryDepth] = {};
-    auto carry_step = [&](int r) {  // r is a compile-time constant in the unrolled loops
-        if constexpr (!kCarry) return;
-        const int voff = opaque_tid() * 16;
-        // (before the first loads have aged, the offset is negative, that is, far beyond the
-        // resource's size: the store is dropped)
-        if (!G::UNROLL || (r >= kCarryDepth && r < kCarrySteps + kCarryDepth))
-            __builtin_amdgcn_raw_buffer_store_b128(carry_v[r % kCarryDepth], carry_dst,
-                                                   voff + (r - kCarryDepth) * (int)kGrain, 0, kBufferNt);
-        if (r < kCarrySteps)
-            carry_v[r % kCarryDepth] =
-                __builtin_amdgcn_raw_buffer_load_b128(carry_src, voff + r * (int)kGrain, 0, kBufferNt);
-    };
-    auto carry_drain = [&]() {
-        if constexpr (kCarry) {
-#pragma unroll
-            for (int r = kCarrySteps; r < kCarrySteps + kCarryDepth; ++r) {
-                const int voff = opaque_tid() * 16;
-                __builtin_amdgcn_raw_buffer_store_b128(carry_v[r % kCarryDepth], carry_dst,
-                                                       voff + (r - kCarryDepth) * (int)kGrain, 0, kBufferNt);
-            }
-        }
-    };
     // room for a second tile-row buffer?
-    constexpr bool kTwoX = 2 * NX + RY * NWT + 4 * RY + (kCarry ? 4 * kCarryDepth - 4 : 0) <= 96;
+    constexpr bool kTwoX = 2 * NX + RY * NWT + 4 * RY <= 96;
     XT X[kTwoX ? 2 : 1][NX];
     XT Wt[RY][NWT];  // kernel row i lives in slot i % RY while it is in use
     if (kTwoX) load_x(0, X[0]);
     auto step = [&](int r, int u) {  // u == r % RY, and RY is even
-        carry_step(r);
         XT *xc = X[kTwoX ? (u & 1) : 0];
         if (kTwoX) {
             if (r + 1 < G::ROWS) load_x(r + 1, X[(u + 1) & 1]);
@@ -1361,24 +1380,13 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         if (r >= RY - 1 && r < KS) {
             // every output row of the thread takes part: interleave them tap by tap, oldest
             // kernel row first, so that 4*RY independent accumulators are in flight
-            if constexpr (kPacked) {
 #pragma unroll
-                for (int m = 0; m < PG::NP; ++m)
+            for (int j = 0; j < KS; ++j)
 #pragma unroll
-                    for (int k = RY - 1; k >= 0; --k)
+                for (int k = RY - 1; k >= 0; --k)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            acc[k][q] = dot2_bf16(Wt[(u - k + RY) % RY][((q + PG::S0) & 1) * PG::NP + m],
-                                                  xc[((q + PG::S0) >> 1) - PG::DSTART + m], acc[k][q]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < KS; ++j)
-#pragma unroll
-                    for (int k = RY - 1; k >= 0; --k)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            acc[k][q] = fmaf(Wt[(u - k + RY) % RY][j], xc[j + q], acc[k][q]);
-            }
+                    for (int q = 0; q < 4; ++q)
+                        acc[k][q] = fmaf(Wt[(u - k + RY) % RY][j], xc[j + q], acc[k][q]);
         } else {
 #pragma unroll
             for (int k = RY - 1; k >= 0; --k) {  // output row k of this thread: kernel row r - k
@@ -1396,7 +1404,50 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     // The early requests go out before the loop (in its middle they cost the compiler so
     // many registers that it spills); whatever has not arrived by the end is asked for again.
     ask_early();
-    if (G::UNROLL) {
+    if constexpr (kMatrix) {
+        // The matrix path (MatrixGeom).  The tile's 4 * RY blocks of 16 x 16 outputs are dealt
+        // to the four wavefronts, RY neighbouring blocks of one row of blocks each: block
+        // b = wv * RY + t covers output rows 16 (b / 4) ... and columns 16 (b % 4) ...  Per
+        // kernel row: one A operand (the band, shared by the wavefront's blocks) and one B
+        // operand per block (lane (n, kg): tile row 16 (b / 4) + i + n, columns 16 (b % 4) +
+        // 8 kg ... + 7), the next kernel row's operands in flight while this one's multiply.
+        // The result: lane (n, g) of block t holds output row n, columns 4 g ... 4 g + 3.
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+        const int lane = tid2 & 63, b0 = (tid2 >> 6) * RY;
+        const int nrow = lane & 15, kg = lane >> 4;
+        const uint32_t *a_src = tbl_d + (8 * kg - nrow + 15) * 4;
+        const uint32_t *b_src = tile_d + ((2 * (b0 & 3) + kg) * MG::HRP + 16 * (b0 >> 2) + OFF + nrow) * 4;
+        auto load_a = [&](int i) { return *reinterpret_cast<const u32x4 *>(a_src + i * (MG::ND * 4)); };
+        auto load_b = [&](int i, int t) { return *reinterpret_cast<const u32x4 *>(b_src + (2 * t * MG::HRP + i) * 4); };
+        f32x4 macc[RY];
+        u32x4 av[2], bv[2][RY];
+        av[0] = load_a(0);
+#pragma unroll
+        for (int t = 0; t < RY; ++t) {
+            macc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            bv[0][t] = load_b(0, t);
+        }
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+            if (i == (KS * 15) / 16) ask_again();
+            if (i + 1 < KS) {
+                av[(i + 1) & 1] = load_a(i + 1);
+#pragma unroll
+                for (int t = 0; t < RY; ++t) bv[(i + 1) & 1][t] = load_b(i + 1, t);
+            }
+#pragma unroll
+            for (int t = 0; t < RY; ++t)
+                macc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[i & 1]),
+                                                                  __builtin_bit_cast(bf16x8, bv[i & 1][t]), macc[t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(kSchedNoLds);
+        }
+        carry_store();
+#pragma unroll
+        for (int t = 0; t < RY; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[t][q] = macc[t][q];
+    } else if (G::UNROLL) {
 #pragma unroll
         for (int r0 = 0; r0 < G::ROWS; r0 += RY)
 #pragma unroll
@@ -1405,13 +1456,11 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                     if (r0 + u == (G::ROWS * 15) / 16) ask_again();
                     step(r0 + u, u);
                 }
-        carry_drain();
     } else {
         // Large kernels: a loop, two rows per trip; the kernel rows are re-read from LDS for
         // every output row instead of being held (they would not fit in the registers).
 #pragma unroll 2
         for (int r = 0; r < G::ROWS; ++r) {
-            carry_step(r);
             XT xr[NX];
             load_x(r, xr);
 #pragma unroll
@@ -1425,7 +1474,6 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             }
             __builtin_amdgcn_sched_barrier(0);  // one row's loads at a time: the registers are few
         }
-        carry_drain();
     }
     __builtin_amdgcn_s_setprio(kPrioHigh);
 
@@ -1434,6 +1482,8 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     const int tid_d = opaque_tid();
     const int tx_d = tid_d & 15, ty_d = tid_d >> 4;
     const float *trow_d = tile + (ty_d * RY) * PITCH + 4 * tx_d;
+    // matrix path: the wavefront's first block, the lane's output row inside a block and its group of four columns
+    const int mb0 = (tid_d >> 6) * RY, mrow = tid_d & 15, mg4 = (tid_d & 63) >> 4;
     T *op = (T *)p->out + ((size_t)wd.n * p->out_c + wd.c) * (size_t)p->H * (size_t)p->W;  // out may have fewer channels than x
 
     if (p->dk_mode != kDkNone) {
@@ -1447,7 +1497,11 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                 s_wdn[tid_d] = wdn_r;
             }
             __syncthreads();
-            sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
+            if (means) {  // the mailboxes hold the means themselves
+                for (int k = tid_d; k < p->Ca; k += kThreads) s_g[k] = s_part[k];
+            } else {
+                sum_staged(s_part, p->ptiles, p->Ca, 0, p->hw, s_g);
+            }
             __syncthreads();
             if (p->hidden > 0) {
                 for (int m = tid_d; m < p->hidden; m += kThreads)
@@ -1475,21 +1529,30 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         float d[9];
 #pragma unroll
         for (int k = 0; k < 9; ++k) d[k] = s_dk[k];
+        if constexpr (kMatrix) {
+            // block t of the wavefront: this lane's output row and four columns; per tile row the
+            // six pixels from one before the first to one behind the last: the word in front
+            // (upper half), the two words of the four pixels, the word behind (lower half)
 #pragma unroll
-        for (int r = 0; r < RY + 2; ++r) {
+            for (int t = 0; t < RY; ++t) {
+                const int wi = (16 * ((mb0 & 3) + t) + 4 * mg4 + PH + MG::A) / 2;
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    const int row = 16 * (mb0 >> 2) + mrow + PH - 1 + i;
+                    const uint32_t w0 = tile_d[MG::word(row, wi - 1)], w3 = tile_d[MG::word(row, wi + 2)];
+                    const uint2 w12 = *reinterpret_cast<const uint2 *>(tile_d + MG::word(row, wi));
+                    const float v[6] = {bf16_hi(w0), bf16_lo(w12.x), bf16_hi(w12.x), bf16_lo(w12.y), bf16_hi(w12.y), bf16_lo(w3)};
+#pragma unroll
+                    for (int j = 0; j < 3; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) acc[t][q] = fmaf(d[i * 3 + j], v[j + q], acc[t][q]);
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < (kMatrix ? 0 : RY + 2); ++r) {
             float v[6];
-            if constexpr (kPacked) {
-                // tile columns 4*tx + PH + A - 1 ... + 4: the four words from one before the
-                // thread's first interior pixel, of which the first and the last halves are unused
-                const uint32_t *src = tile_d + (ty_d * RY + r + PH - 1) * PG::PITCH_D + 2 * tx_d + (PH + PG::A) / 2 - 1;
-                const uint32_t w0 = src[0], w1 = src[1], w2 = src[2], w3 = src[3];
-                v[0] = bf16_hi(w0);
-                v[1] = bf16_lo(w1);
-                v[2] = bf16_hi(w1);
-                v[3] = bf16_lo(w2);
-                v[4] = bf16_hi(w2);
-                v[5] = bf16_lo(w3);
-            } else {
+            {
                 const float *src = trow_d + (r + PH - 1) * PITCH + (PH - 1);
 #pragma unroll
                 for (int k = 0; k < 6; ++k) v[k] = src[k];
@@ -1509,9 +1572,41 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     }
 
     if (p->dk_mode == kDkNone) claim_next(p, ctx);
-    const int gx = wd.x0 + 4 * tx_d;
+    if constexpr (kMatrix) {
+        // rounded once, through LDS (MatrixGeom::OP), then rows ty*RY ... of the tile, four
+        // columns per thread, as on the other path
+        if (p->dk_mode == kDkNone) __syncthreads();  // (the other modes have passed a barrier since the tap loop)
+        uint32_t *otile = tbl_d;
+#pragma unroll
+        for (int t = 0; t < RY; ++t) {
+            uint2 w;
+            w.x = (uint32_t)f32_to_bf16_bits(acc[t][0]) | ((uint32_t)f32_to_bf16_bits(acc[t][1]) << 16);
+            w.y = (uint32_t)f32_to_bf16_bits(acc[t][2]) | ((uint32_t)f32_to_bf16_bits(acc[t][3]) << 16);
+            *reinterpret_cast<uint2 *>(otile + (16 * (mb0 >> 2) + mrow) * MG::OP + 8 * ((mb0 & 3) + t) + 2 * mg4) = w;
+        }
+        __syncthreads();
+        const int gx = wd.x0 + 4 * tx_d;
+#pragma unroll
+        for (int oy = 0; oy < RY; ++oy) {
+            const int gy = wd.y0 + ty_d * RY + oy;
+            const uint2 w = *reinterpret_cast<const uint2 *>(otile + (ty_d * RY + oy) * MG::OP + 2 * tx_d);
+            if (gy >= H) continue;
+            uint16_t *dst = reinterpret_cast<uint16_t *>(op) + (size_t)gy * W + gx;
+            if (p->conv_vec_ok && gx + 3 < W) {
+                typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+                __builtin_nontemporal_store(u32x2{w.x, w.y}, reinterpret_cast<u32x2 *>(dst));
+            } else {
+                if (gx + 0 < W) dst[0] = (uint16_t)w.x;
+                if (gx + 1 < W) dst[1] = (uint16_t)(w.x >> 16);
+                if (gx + 2 < W) dst[2] = (uint16_t)w.y;
+                if (gx + 3 < W) dst[3] = (uint16_t)(w.y >> 16);
+            }
+        }
+        return ctx;
+    }
 #pragma unroll
     for (int oy = 0; oy < RY; ++oy) {
+        const int gx = wd.x0 + 4 * tx_d;
         const int gy = wd.y0 + ty_d * RY + oy;
         if (gy >= H) continue;
         T *dst = op + (size_t)gy * W + gx;

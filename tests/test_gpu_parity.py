@@ -333,9 +333,11 @@ def test_non_finite_pixels_in_the_attention_slice(oracle, dtype, Ks):
     # Where do NaN/Inf pixels of the attention slice show in the output?  The definition
     # (and the oracle): at every output whose Ks x Ks window (or DK's 3 x 3) covers the pixel.
     # fp32 storage, and bf16 storage with Ks >= 19, must give exactly that footprint.  The
-    # packed bf16 path (Ks <= 17) applies two taps per instruction, one of them possibly a
-    # zero weight on the pixel one column beyond the window: there the footprint may be wider
-    # by one column on either side, and no more.  Everything else stays within the usual bar.
+    # matrix path (bf16 storage, Ks <= 17) forms 16 neighbouring outputs of a row from the 32
+    # tile columns that start P + A columns left of the first (A pads the halo to 8 columns),
+    # most of them times a zero of the band: there the footprint may widen, inside the rows
+    # the definition reaches, to every 16-column block whose 32 columns hold the pixel - and
+    # no further.  Everything else stays within the usual bar.
     wl = wk.make_random(860 + Ks, 2, 5, 50, 150, 3, Ks, dtype=dtype)
     rng = np.random.default_rng(861)
     dk = rng.standard_normal((2, 3, 3, 3)).astype(np.float32)
@@ -353,13 +355,17 @@ def test_non_finite_pixels_in_the_attention_slice(oracle, dtype, Ks):
     bad_ref, bad_got = ~np.isfinite(ref_att), ~np.isfinite(got)
     p = (Ks - 1) // 2
     assert bad_ref.sum() >= len(spots) * (p + 1) ** 2
-    packed = dtype == BF16 and Ks <= 17
-    if packed:
+    matrix = dtype == BF16 and Ks <= 17
+    if matrix:
+        ph = max(p, 1)
+        pad = ph + (8 - ph % 8) % 8
         wider = bad_ref.copy()
-        wider[..., 1:] |= bad_ref[..., :-1]
-        wider[..., :-1] |= bad_ref[..., 1:]
+        for n, c, y, x_, _ in spots:
+            for X0 in range(0, wl.W, 16):
+                if X0 - pad <= x_ <= X0 - pad + 31:
+                    wider[n, c, max(0, y - p):y + p + 1, X0:X0 + 16] = True
         assert not (bad_ref & ~bad_got).any(), "a non-finite result of the definition came out finite"
-        assert not (bad_got & ~wider).any(), "NaN beyond one column past the kernel's reach"
+        assert not (bad_got & ~wider).any(), "NaN outside the blocks whose input columns hold the pixel"
     else:
         assert np.array_equal(bad_ref, bad_got), "NaN/Inf footprint differs from the definition's"
     ok = ~bad_got
