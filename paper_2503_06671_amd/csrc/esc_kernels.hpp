@@ -1024,31 +1024,10 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     // is computed once per kernel and then held in registers through all items)
     const int tid1 = opaque_tid();
     float wreg[KW];
-    // matrix path: word idx of the Toeplitz table holds the band's entries for two
-    // neighbouring tile columns: kernel row i = idx / 160, operand d = (idx % 160) / 4,
-    // columns k = 2 (idx % 4), + 1 of the operand's eight, i.e. taps j = d - 15 + k - S0
-    constexpr int KWP = (MG::TBL_WORDS + kThreads - 1) / kThreads;
-    float wpa[KWP], wpb[KWP];
-    if constexpr (kMatrix) {
 #pragma unroll
-        for (int m = 0; m < KWP; ++m) {
-            const int idx = m * kThreads + tid1;
-            int i = idx / (MG::ND * 4);
-            const int rem = idx - i * (MG::ND * 4);
-            const int ja = (rem >> 2) - 15 + 2 * (rem & 3) - MG::S0, jb = ja + 1;
-            i = i < KS ? i : KS - 1;
-            // (unconditional loads from clamped addresses, masked afterwards)
-            const float va = lkc[i * KS + (ja < 0 ? 0 : ja >= KS ? KS - 1 : ja)];
-            const float vb = lkc[i * KS + (jb < 0 ? 0 : jb >= KS ? KS - 1 : jb)];
-            wpa[m] = (ja >= 0 && ja < KS) ? va : 0.f;
-            wpb[m] = (jb >= 0 && jb < KS) ? vb : 0.f;
-        }
-    } else {
-#pragma unroll
-        for (int m = 0; m < KW; ++m) {
-            const int idx = m * kThreads + tid1;
-            wreg[m] = idx < KS * KS ? lkc[idx] : 0.f;
-        }
+    for (int m = 0; m < KW; ++m) {
+        const int idx = m * kThreads + tid1;
+        wreg[m] = idx < KS * KS ? lkc[idx] : 0.f;
     }
 
     // Carried copy (Eq. 4 lines 1 and 4): this item's share of the image's pass-through range
@@ -1192,19 +1171,11 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         }
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
     }
-    if constexpr (kMatrix) {
 #pragma unroll
-        for (int m = 0; m < KWP; ++m) {
-            const int idx = m * kThreads + tid1;
-            if (idx < MG::TBL_WORDS)
-                tbl_d[idx] = (uint32_t)f32_to_bf16_bits(wpa[m]) | ((uint32_t)f32_to_bf16_bits(wpb[m]) << 16);
-        }
-    } else {
-#pragma unroll
-        for (int m = 0; m < KW; ++m) {
-            const int idx = m * kThreads + tid1;
-            if (idx < KS * KS) wl[(idx / KS) * WP + idx % KS] = wreg[m];
-        }
+    for (int m = 0; m < KW; ++m) {
+        const int idx = m * kThreads + tid1;
+        // (matrix path: the Ks x Ks weights as they lie in memory; the band table is made from them further down)
+        if (idx < KS * KS) wl[kMatrix ? idx : (idx / KS) * WP + idx % KS] = wreg[m];
     }
     // (the call tag, asked for behind the tile, has arrived in this wavefront too)
     asm volatile("" ::"v"(ctx.tag));
@@ -1252,6 +1223,27 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             have[h] = (int)pty * kPoolTileH < H;  // block-uniform
         }
         pool_finish<NPT>(p->pool_box, sums, box, have, ctx.tag, g_red);
+    }
+    if constexpr (kMatrix) {
+        // The band table (MatrixGeom), made from the weights in LDS once the pool sums are
+        // out (they are what the other blocks wait for): word idx holds the band's entries for
+        // two neighbouring tile columns - kernel row i = idx / 160, operand d = (idx % 160) / 4,
+        // columns k = 2 (idx % 4), + 1 of the operand's eight, i.e. taps j = d - 15 + k - S0.
+        constexpr int KWP = (MG::TBL_WORDS + kThreads - 1) / kThreads;
+#pragma unroll
+        for (int m = 0; m < KWP; ++m) {
+            const int idx = m * kThreads + tid2;
+            int i = idx / (MG::ND * 4);
+            const int rem = idx - i * (MG::ND * 4);
+            const int ja = (rem >> 2) - 15 + 2 * (rem & 3) - MG::S0, jb = ja + 1;
+            i = i < KS ? i : KS - 1;
+            const float va = wl[i * KS + (ja < 0 ? 0 : ja >= KS ? KS - 1 : ja)];
+            const float vb = wl[i * KS + (jb < 0 ? 0 : jb >= KS ? KS - 1 : jb)];
+            const uint32_t ha = (ja >= 0 && ja < KS) ? f32_to_bf16_bits(va) : 0u;
+            const uint32_t hb = (jb >= 0 && jb < KS) ? f32_to_bf16_bits(vb) : 0u;
+            if (idx < MG::TBL_WORDS) tbl_d[idx] = ha | (hb << 16);
+        }
+        __syncthreads();
     }
 
     // What the DK phase will need is asked for ahead of it: the estimator weights this
