@@ -4,8 +4,12 @@
 //
 // A 1x1 convolution in NCHW is the dense contraction  D[M x P] = W[M x K] . B[K x P]
 // per image, with P = H*W pixels contiguous in memory for every channel of B and D, so
-// it runs on the matrix cores: v_mfma_f32_32x32x2_f32, fp32 products and fp32
-// accumulation (bf16 storage is widened exactly on load and rounded once at the store).
+// it runs on the matrix cores.  fp32 storage: v_mfma_f32_32x32x2_f32, fp32 products and
+// fp32 accumulation.  bf16 storage: v_mfma_f32_32x32x16_bf16 on the stored bf16 values, with
+// every fp32 weight split into two bf16 terms (w = hi + lo to 16 mantissa bits, two
+// instructions per operand pair: the products are exact in fp32, the accumulation is fp32,
+// the result is rounded once at the store) - sixteen times the fp32 form's rate, which
+// with bf16 storage was all such a call lasted.
 // The input channels come from two tensors (the first K1 from `src1`, the other K2 from
 // `src2`): that is the concat, which is never materialised.
 //
@@ -57,6 +61,87 @@ constexpr unsigned kBeyond = 0x80000000u;  // an offset beyond every resource (a
 
 extern __shared__ __align__(16) float pw_lds[];
 
+// Residual (Eq. 3 line 3) and store of a wavefront's two 32 x 32 accumulator tiles: lane l
+// of tile t holds output channels m0 + 32 mt + 8*(r/4) + 4*(l/32) + r%4 of pixel
+// 64 ph + 32 t + l%32 of the block's tile.  Buffer accesses on resources that end with the
+// image: rows beyond M and (their offset pushed beyond every resource) pixels beyond the
+// plane read as zero and are not written; without a residual its resource is empty.
+template <typename T>
+__device__ __forceinline__ void store_tile(const PointwiseParams &p, const f32x16 (&acc)[2], unsigned tile,
+                                           unsigned tiles_per_img, int m0, int mt, int ph, int l32, int half)
+{
+    const long P = p.P;
+    const unsigned n = tile / tiles_per_img;
+    const unsigned px0 = (tile - n * tiles_per_img) * kPwTile + 64 * ph + l32;
+    const unsigned plane_bytes = (unsigned)P * (unsigned)sizeof(T);
+    const Rsrc rdst = __builtin_amdgcn_make_buffer_rsrc((void *)((T *)p.dst + (size_t)n * p.dst_img_stride), 0,
+                                                        (int)((unsigned)p.M * plane_bytes), kRawBuffer);
+    const Rsrc rres = __builtin_amdgcn_make_buffer_rsrc((void *)((const T *)p.res + (size_t)n * p.res_img_stride), 0,
+                                                        p.res != nullptr ? (int)((unsigned)p.M * plane_bytes) : 0, kRawBuffer);
+    if (m0 + 32 * mt < p.M) {  // wavefront-uniform
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+            const unsigned px = px0 + 32 * t2;
+            const unsigned px_off = px < (unsigned)P ? px * (unsigned)sizeof(T) : kBeyond;
+            float rv[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const unsigned co = (unsigned)(m0 + 32 * mt + 8 * (r >> 2) + 4 * half + (r & 3));
+                if constexpr (sizeof(T) == 4)
+                    rv[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, (int)(co * plane_bytes + px_off), 0, kNt));
+                else
+                    rv[r] = __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b16(rres, (int)(co * plane_bytes + px_off), 0, kNt) << 16);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const unsigned co = (unsigned)(m0 + 32 * mt + 8 * (r >> 2) + 4 * half + (r & 3));
+                const float v = acc[t2][r] + rv[r];
+                if constexpr (sizeof(T) == 4)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rdst, (int)(co * plane_bytes + px_off), 0, kNt);
+                else
+                    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)pw_f32_to_bf16(v), rdst, (int)(co * plane_bytes + px_off), 0, kNt);
+            }
+        }
+    }
+}
+
+// Fetch of a thread's pieces of stage `st` of tile `tile` into registers (raw storage bits):
+// channel rows my_row + u * rows_per_sweep of the stage, pixels my_px ... of the tile.
+template <typename T, bool VEC, int LOADS>
+__device__ __forceinline__ void fetch_stage(const PointwiseParams &p, unsigned tile, unsigned tiles_per_img, int st,
+                                            int my_row, int my_px, int rows_per_sweep, u32x4 (&r)[LOADS])
+{
+    constexpr int kPer = 16 / (int)sizeof(T);
+    const long P = p.P;
+    const int K = p.K1 + p.K2;
+    const unsigned n = tile / tiles_per_img;
+    const long px0 = (long)(tile - n * tiles_per_img) * kPwTile + my_px;
+    const T *s1 = (const T *)p.src1 + (size_t)n * p.src1_img_stride;
+    const T *s2 = (const T *)p.src2 + (size_t)n * p.src2_img_stride;
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) {
+        int k = st * kPwKc + my_row + u * rows_per_sweep;
+        k = k < K ? k : K - 1;  // (rows beyond K are zeroed when they are staged)
+        const T *plane = k < p.K1 ? s1 + (size_t)k * P : s2 + (size_t)(k - p.K1) * P;
+        if constexpr (VEC) {
+            const long e = px0 < P ? px0 : P - kPer;  // P % kPer == 0: a piece is inside or outside as a whole
+            r[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(plane + e));
+        } else {
+            float v[kPer];
+#pragma unroll
+            for (int e = 0; e < kPer; ++e) v[e] = pw_load1(plane + (px0 + e < P ? px0 + e : P - 1));
+            if constexpr (sizeof(T) == 4) {
+                r[u] = u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+            } else {
+                r[u] = u32x4{(__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xffff0000u),
+                             (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xffff0000u),
+                             (__float_as_uint(v[4]) >> 16) | (__float_as_uint(v[5]) & 0xffff0000u),
+                             (__float_as_uint(v[6]) >> 16) | (__float_as_uint(v[7]) & 0xffff0000u)};
+            }
+        }
+    }
+}
+
 // The kernel: D[M x P] = W[M x K] . B[K x P] + bias (+ residual) per image, B's channels
 // coming from two tensors.  A block owns tiles of 128 pixels (tile b, b + grid, ...); per
 // tile the K input channels pass through LDS in stages of 32: every thread fetches 16-byte
@@ -96,34 +181,8 @@ __global__ __launch_bounds__(kPwThreads, (VEC && sizeof(T) == 4) ? 3 : 2) void p
     // this thread's pieces of a stage: channel row my_row + u * kRowsPerSweep, pixels my_px ..
     const int my_row = tid / kPieces, my_px = (tid - my_row * kPieces) * kPer;
 
-    // fetch: stage `st` of tile `tile` into registers (raw storage bits)
     auto fetch = [&](unsigned tile, int st, u32x4 (&r)[kLoads]) {
-        const unsigned n = tile / tiles_per_img;
-        const long px0 = (long)(tile - n * tiles_per_img) * kPwTile + my_px;
-        const T *s1 = (const T *)p.src1 + (size_t)n * p.src1_img_stride;
-        const T *s2 = (const T *)p.src2 + (size_t)n * p.src2_img_stride;
-#pragma unroll
-        for (int u = 0; u < kLoads; ++u) {
-            int k = st * kPwKc + my_row + u * kRowsPerSweep;
-            k = k < K ? k : K - 1;  // (rows beyond K are zeroed when they are staged)
-            const T *plane = k < p.K1 ? s1 + (size_t)k * P : s2 + (size_t)(k - p.K1) * P;
-            if constexpr (VEC) {
-                const long e = px0 < P ? px0 : P - kPer;  // P % kPer == 0: a piece is inside or outside as a whole
-                r[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(plane + e));
-            } else {
-                float v[kPer];
-#pragma unroll
-                for (int e = 0; e < kPer; ++e) v[e] = pw_load1(plane + (px0 + e < P ? px0 + e : P - 1));
-                if constexpr (sizeof(T) == 4) {
-                    r[u] = u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
-                } else {
-                    r[u] = u32x4{(__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xffff0000u),
-                                 (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xffff0000u),
-                                 (__float_as_uint(v[4]) >> 16) | (__float_as_uint(v[5]) & 0xffff0000u),
-                                 (__float_as_uint(v[6]) >> 16) | (__float_as_uint(v[7]) & 0xffff0000u)};
-                }
-            }
-        }
+        fetch_stage<T, VEC, kLoads>(p, tile, tiles_per_img, st, my_row, my_px, kRowsPerSweep, r);
     };
     // stage: the fetched pieces, widened to fp32, into buffer `buf`; rows beyond K as zeros
     // (their weights are zero too, but zero times a stray Inf would not be)
@@ -205,59 +264,238 @@ __global__ __launch_bounds__(kPwThreads, (VEC && sizeof(T) == 4) ? 3 : 2) void p
                     acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc[1], 0, 0, 0);
                 }
             }
-            // ---- residual (Eq. 3 line 3) and store: lane l of accumulator tile t holds output
-            // channels 8*(r/4) + 4*(l/32) + r%4 of pixel 64*ph + 32*t + l%32.  Buffer accesses on
-            // resources that end with the image: rows beyond M and (their offset pushed beyond
-            // every resource) pixels beyond the plane read as zero and are not written; without
-            // a residual its resource is empty ----
-            const unsigned n = tile / tiles_per_img;
-            const unsigned px0 = (tile - n * tiles_per_img) * kPwTile + 64 * ph + l32;
-            const unsigned plane_bytes = (unsigned)P * (unsigned)sizeof(T);
-            const Rsrc rdst = __builtin_amdgcn_make_buffer_rsrc((void *)((T *)p.dst + (size_t)n * p.dst_img_stride), 0,
-                                                                (int)((unsigned)p.M * plane_bytes), kRawBuffer);
-            const Rsrc rres = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)((const T *)p.res + (size_t)n * p.res_img_stride), 0,
-                p.res != nullptr ? (int)((unsigned)p.M * plane_bytes) : 0, kRawBuffer);
-            if (m0 + 32 * mt < p.M) {  // wavefront-uniform
-#pragma unroll
-                for (int t2 = 0; t2 < 2; ++t2) {
-                    const unsigned px = px0 + 32 * t2;
-                    const unsigned px_off = px < (unsigned)P ? px * (unsigned)sizeof(T) : kBeyond;
-                    float rv[16];
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const unsigned co = (unsigned)(m0 + 32 * mt + 8 * (r >> 2) + 4 * half + (r & 3));
-                        if constexpr (sizeof(T) == 4)
-                            rv[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rres, (int)(co * plane_bytes + px_off), 0, kNt));
-                        else
-                            rv[r] = __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b16(rres, (int)(co * plane_bytes + px_off), 0, kNt) << 16);
-                    }
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const unsigned co = (unsigned)(m0 + 32 * mt + 8 * (r >> 2) + 4 * half + (r & 3));
-                        const float v = acc[t2][r] + rv[r];
-                        if constexpr (sizeof(T) == 4)
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rdst, (int)(co * plane_bytes + px_off), 0, kNt);
-                        else
-                            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)pw_f32_to_bf16(v), rdst, (int)(co * plane_bytes + px_off), 0, kNt);
-                    }
-                }
-            }
+            store_tile<T>(p, acc, tile, tiles_per_img, m0, mt, ph, l32, half);
         }
     }
 }
 
-template <typename T, bool VEC>
+// The same contraction for bf16 storage, on v_mfma_f32_32x32x16_bf16.  The inputs stay
+// bf16 in LDS, [channel][pixel] as they are fetched (16-byte pieces, no widening); an
+// operand wants eight consecutive channels of one pixel per lane, so the B operands are
+// gathered with 16-bit LDS reads (lanes read consecutive pixels: no bank conflicts).  The
+// weights of a pass are staged as two bf16 arrays [64][K], hi = bf16(w) and
+// lo = bf16(w - hi): A operands are 16-byte reads, and each B operand is multiplied by
+// both.  Same tiles, stages and buffers as the fp32 kernel.  With 16-byte accesses (VEC)
+// the operands swap roles - pixels are the rows of the product, output channels its columns
+// - so that a lane ends up with runs of four neighbouring pixels of one channel: residual
+// added, rounded and packed, they pass through a per-wavefront LDS tile [32 channels][64
+// pixels] and leave as 16-byte pieces, eight lanes to a 128-byte run of a channel (stored
+// straight from the matrix cores' layout they would be 2-byte elements in 64-byte runs).
+constexpr int kPwBfBPitch = kPwTile + 8;  // bf16 elements between two channel rows of a staged input tile
+constexpr int kPwBfOPitch = 64;           // bf16 elements of a channel row of a wavefront's output tile (no padding:
+                                          // the 16-byte piece q of row ch lies at piece q ^ (ch & 7), which spreads the
+                                          // rows over the banks; padded rows would cost the third block per compute unit)
+
+template <bool VEC>
+__global__ __launch_bounds__(kPwThreads, VEC ? 3 : 2) void pointwise_bf16_kernel(const PointwiseParams p)
+{
+    typedef bf16s T;
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    constexpr int kPer = 8;                                  // pixels per 16-byte piece
+    constexpr int kPieces = kPwTile / kPer;                  // 16 pieces per channel row of a tile
+    constexpr int kRowsPerSweep = kPwThreads / kPieces;      // 16 channel rows at once
+    constexpr int kLoads = kPwKc / kRowsPerSweep;            // 2 pieces per thread and stage
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int mt = wave & 1, ph = wave >> 1;
+    const int K = p.K1 + p.K2;
+    const int stages = (K + kPwKc - 1) / kPwKc;
+    const int Kr = stages * kPwKc;
+    const int wp = Kr + 8;                                   // bf16 elements between two rows of the staged weights
+    const unsigned tiles_per_img = (unsigned)((p.P + kPwTile - 1) / kPwTile);
+    const unsigned n_tiles = tiles_per_img * (unsigned)p.N;
+
+    float *s_bias = pw_lds;                                                   // [kPwM]
+    uint16_t *s_wh = reinterpret_cast<uint16_t *>(pw_lds + kPwM);             // [kPwM][wp]
+    uint16_t *s_wl = s_wh + kPwM * wp;                                        // [kPwM][wp]
+    uint16_t *s_b = s_wl + kPwM * wp;                                         // [2][kPwKc][kPwBfBPitch]
+    uint16_t *s_o = s_b + 2 * kPwKc * kPwBfBPitch + wave * (32 * kPwBfOPitch);  // VEC: [32][kPwBfOPitch] per wavefront
+
+    const int my_row = tid / kPieces, my_px = (tid - my_row * kPieces) * kPer;
+    auto fetch = [&](unsigned tile, int st, u32x4 (&r)[kLoads]) {
+        fetch_stage<T, VEC, kLoads>(p, tile, tiles_per_img, st, my_row, my_px, kRowsPerSweep, r);
+    };
+    // the fetched pieces as they are; rows beyond K as zeros (zero weights times a stray Inf would not be zero)
+    auto stage = [&](int st, const u32x4 (&r)[kLoads], int buf) {
+        uint16_t *dst = s_b + buf * (kPwKc * kPwBfBPitch);
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            const int row = my_row + u * kRowsPerSweep;
+            const bool live = st * kPwKc + row < K;
+            *reinterpret_cast<u32x4 *>(dst + row * kPwBfBPitch + my_px) = live ? r[u] : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+
+    // Two stages are in flight per thread (two register sets taking turns): with the matrix
+    // time gone, what such a call lasts is how many bytes the chip has asked for at a time.
+    struct Pos {
+        unsigned tile;
+        int st;
+    };
+    auto next = [&](Pos q) { return q.st + 1 < stages ? Pos{q.tile, q.st + 1} : Pos{q.tile + gridDim.x, 0}; };
+    u32x4 regs_a[kLoads], regs_b[kLoads];
+    auto prologue = [&]() {
+        const Pos q0{blockIdx.x, 0}, q1 = next(q0);
+        if (q0.tile < n_tiles) fetch(q0.tile, q0.st, regs_a);
+        if (q1.tile < n_tiles) fetch(q1.tile, q1.st, regs_b);
+    };
+    prologue();
+
+    for (int m0 = 0; m0 < p.M; m0 += kPwM) {
+        __syncthreads();  // every wavefront has finished the previous pass
+        for (int i0 = 0; i0 < Kr * kPwM; i0 += kPwStageW * kPwThreads) {
+            float wv[kPwStageW];
+            bool in[kPwStageW];
+#pragma unroll
+            for (int u = 0; u < kPwStageW; ++u) {
+                const int idx = i0 + u * kPwThreads + tid;
+                const int m = (idx >> 4) & (kPwM - 1), k = ((idx >> 10) << 4) + (idx & 15);
+                in[u] = m0 + m < p.M && k < K;
+                wv[u] = p.w[in[u] ? (size_t)(m0 + m) * p.w_ld + k : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < kPwStageW; ++u) {
+                const int idx = i0 + u * kPwThreads + tid;
+                const int m = (idx >> 4) & (kPwM - 1), k = ((idx >> 10) << 4) + (idx & 15);
+                const float w = in[u] ? wv[u] : 0.f;
+                const uint16_t hi = pw_f32_to_bf16(w);
+                const uint16_t lo = pw_f32_to_bf16(w - __uint_as_float((uint32_t)hi << 16));
+                if (idx < Kr * kPwM) {
+                    s_wh[m * wp + k] = hi;
+                    s_wl[m * wp + k] = lo;
+                }
+            }
+        }
+        if (tid < kPwM) s_bias[tid] = (p.bias != nullptr && m0 + tid < p.M) ? p.bias[m0 + tid] : 0.f;
+        if (m0 > 0) prologue();
+
+        f32x16 acc[2];
+        int step = 0;  // stages done by this block in this pass: picks the LDS buffer and the register set
+        Pos cur{blockIdx.x, 0}, ahead = next(next(cur));
+        // one stage: its pieces into LDS, the stage after next asked for into the registers
+        // they came from, the products, and behind a tile's last stage its results
+        auto body = [&](u32x4 (&regs)[kLoads]) {
+            const unsigned tile = cur.tile;
+            const int st = cur.st;
+            {
+                stage(st, regs, step & 1);
+                __syncthreads();
+                if (ahead.tile < n_tiles) fetch(ahead.tile, ahead.st, regs);
+                if (st == 0) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float b = s_bias[VEC ? 32 * mt + l32 : 32 * mt + 8 * (r >> 2) + 4 * half + (r & 3)];
+                        acc[0][r] = b;
+                        acc[1][r] = b;
+                    }
+                }
+                // weights: lane l holds W[m = l % 32][k = 8 (l / 32) ... + 7] of the 16 channels of a chunk;
+                // inputs: lane l holds the same eight channels of pixel l % 32
+                const uint16_t *wh = s_wh + (32 * mt + l32) * wp + st * kPwKc + 8 * half;
+                const uint16_t *wl = s_wl + (32 * mt + l32) * wp + st * kPwKc + 8 * half;
+                const uint16_t *bk = s_b + (step & 1) * (kPwKc * kPwBfBPitch) + (8 * half) * kPwBfBPitch + 64 * ph + l32;
+#pragma unroll
+                for (int c = 0; c < kPwKc / 16; ++c) {
+                    const u32x4 ah = *reinterpret_cast<const u32x4 *>(wh + 16 * c);
+                    const u32x4 al = *reinterpret_cast<const u32x4 *>(wl + 16 * c);
+                    u32x4 b[2];
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                        for (int w2 = 0; w2 < 4; ++w2) {
+                            const uint32_t e0 = bk[(16 * c + 2 * w2) * kPwBfBPitch + 32 * t2];
+                            const uint32_t e1 = bk[(16 * c + 2 * w2 + 1) * kPwBfBPitch + 32 * t2];
+                            b[t2][w2] = e0 | (e1 << 16);
+                        }
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2) {
+                        if constexpr (VEC) {  // rows = pixels, columns = output channels
+                            acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b[t2]),
+                                                                              __builtin_bit_cast(bf16x8, ah), acc[t2], 0, 0, 0);
+                            acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b[t2]),
+                                                                              __builtin_bit_cast(bf16x8, al), acc[t2], 0, 0, 0);
+                        } else {
+                            acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ah),
+                                                                              __builtin_bit_cast(bf16x8, b[t2]), acc[t2], 0, 0, 0);
+                            acc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, al),
+                                                                              __builtin_bit_cast(bf16x8, b[t2]), acc[t2], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+            if (st + 1 < stages) {
+                // (more stages of this tile to come)
+            } else if constexpr (!VEC) {
+                store_tile<T>(p, acc, tile, tiles_per_img, m0, mt, ph, l32, half);
+            } else if (m0 + 32 * mt < p.M) {  // wavefront-uniform
+                // lane l of accumulator tile t holds output channel m0 + 32 mt + l % 32, pixels
+                // 64 ph + 32 t + 8 q + 4 (l / 32) + (0 ... 3) in registers 4 q ... 4 q + 3
+                typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+                const unsigned n = tile / tiles_per_img;
+                const unsigned tpx = (tile - n * tiles_per_img) * kPwTile + 64 * ph;  // first pixel of the wavefront's 64
+                const unsigned plane_bytes = (unsigned)p.P * 2u;
+                const Rsrc rdst = __builtin_amdgcn_make_buffer_rsrc((void *)((T *)p.dst + (size_t)n * p.dst_img_stride), 0,
+                                                                    (int)((unsigned)p.M * plane_bytes), kRawBuffer);
+                const Rsrc rres = __builtin_amdgcn_make_buffer_rsrc(
+                    (void *)((const T *)p.res + (size_t)n * p.res_img_stride), 0,
+                    p.res != nullptr ? (int)((unsigned)p.M * plane_bytes) : 0, kRawBuffer);
+                const unsigned co = (unsigned)(m0 + 32 * mt + l32);
+                u32x2 rv[2][4];
+#pragma unroll
+                for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const unsigned px = tpx + 32 * t2 + 8 * q + 4 * half;  // P % 8 == 0: four pixels are inside or outside together
+                        const unsigned off = px < (unsigned)p.P ? co * plane_bytes + px * 2u : kBeyond;
+                        rv[t2][q] = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rres, (int)off, 0, kNt));
+                    }
+#pragma unroll
+                for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float v0 = acc[t2][4 * q + 0] + __uint_as_float(rv[t2][q].x << 16);
+                        const float v1 = acc[t2][4 * q + 1] + __uint_as_float(rv[t2][q].x & 0xffff0000u);
+                        const float v2 = acc[t2][4 * q + 2] + __uint_as_float(rv[t2][q].y << 16);
+                        const float v3 = acc[t2][4 * q + 3] + __uint_as_float(rv[t2][q].y & 0xffff0000u);
+                        const u32x2 w = {(uint32_t)pw_f32_to_bf16(v0) | ((uint32_t)pw_f32_to_bf16(v1) << 16),
+                                         (uint32_t)pw_f32_to_bf16(v2) | ((uint32_t)pw_f32_to_bf16(v3) << 16)};
+                        *reinterpret_cast<u32x2 *>(s_o + l32 * kPwBfOPitch + 8 * ((4 * t2 + q) ^ (l32 & 7)) + 4 * half) = w;
+                    }
+                __builtin_amdgcn_wave_barrier();  // (the wavefront's LDS accesses are carried out in order)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int ch = 8 * i + (lane >> 3), piece = lane & 7;
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(s_o + ch * kPwBfOPitch + 8 * (piece ^ (ch & 7)));
+                    const unsigned px = tpx + 8 * piece;
+                    const unsigned off = px < (unsigned)p.P ? (unsigned)(m0 + 32 * mt + ch) * plane_bytes + px * 2u : kBeyond;
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rdst, (int)off, 0, kNt);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+            cur = next(cur);
+            ahead = next(ahead);
+            ++step;
+        };
+        while (cur.tile < n_tiles) {
+            body(regs_a);
+            if (cur.tile >= n_tiles) break;
+            body(regs_b);
+        }
+    }
+}
+
+template <void (*KERNEL)(const PointwiseParams)>
 hipError_t launch_one(const PointwiseParams &p, unsigned grid, size_t lds, hipStream_t s)
 {
-    static size_t granted = 48 * 1024;  // dynamic LDS a launch may ask for without asking first
+    static size_t granted = 48 * 1024;  // dynamic LDS a launch of this kernel may ask for without asking first
     if (lds > granted) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pointwise_kernel<T, VEC>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(KERNEL),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         granted = lds;
     }
-    hipLaunchKernelGGL((pointwise_kernel<T, VEC>), dim3(grid), dim3(kPwThreads), lds, s, p);
+    hipLaunchKernelGGL(KERNEL, dim3(grid), dim3(kPwThreads), lds, s, p);
     return hipGetLastError();
 }
 
@@ -274,7 +512,9 @@ __attribute__((visibility("hidden"))) hipError_t launch_pointwise(const Pointwis
     // the stores address an image of a tensor with 32-bit byte offsets below 2 GiB
     if ((size_t)p.M * (size_t)p.P * es >= ((size_t)1 << 31)) return hipErrorInvalidValue;
     const int Kr = (K + kPwKc - 1) / kPwKc * kPwKc;
-    const size_t lds = ((size_t)Kr * kPwWPitch + kPwM + 2 * (size_t)kPwKc * kPwBPitch) * sizeof(float);
+    const size_t lds = bf16 ? kPwM * sizeof(float) + (2 * (size_t)kPwM * (Kr + 8) + 2 * (size_t)kPwKc * kPwBfBPitch +
+                                                      4 * 32 * (size_t)kPwBfOPitch) * sizeof(uint16_t)
+                            : ((size_t)Kr * kPwWPitch + kPwM + 2 * (size_t)kPwKc * kPwBPitch) * sizeof(float);
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, n = 0;
@@ -289,8 +529,11 @@ __attribute__((visibility("hidden"))) hipError_t launch_pointwise(const Pointwis
     auto aligned = [&](const void *ptr, size_t img_stride) { return (uintptr_t)ptr % 16 == 0 && img_stride % per == 0; };
     const bool vec = (size_t)p.P % per == 0 && (p.K1 == 0 || aligned(p.src1, p.src1_img_stride)) &&
                      (p.K2 == 0 || aligned(p.src2, p.src2_img_stride));
-    if (vec) return bf16 ? launch_one<bf16s, true>(p, (unsigned)grid, lds, s) : launch_one<float, true>(p, (unsigned)grid, lds, s);
-    return bf16 ? launch_one<bf16s, false>(p, (unsigned)grid, lds, s) : launch_one<float, false>(p, (unsigned)grid, lds, s);
+    if (vec)
+        return bf16 ? launch_one<pointwise_bf16_kernel<true>>(p, (unsigned)grid, lds, s)
+                    : launch_one<pointwise_kernel<float, true>>(p, (unsigned)grid, lds, s);
+    return bf16 ? launch_one<pointwise_bf16_kernel<false>>(p, (unsigned)grid, lds, s)
+                : launch_one<pointwise_kernel<float, false>>(p, (unsigned)grid, lds, s);
 }
 
 }  // namespace esc
