@@ -1290,11 +1290,13 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         // reads some mailbox of the image, whichever mode the call is in
         const int t = opaque_tid();
         const u64 *bx = boxes_s;
+        // (threads beyond the image's mailboxes read their block group's counter line instead:
+        // aimed at the last mailbox, a thousand blocks' idle lanes would queue on a few lines)
+        const u64 *idle = reinterpret_cast<const u64 *>(p->epoch + (blockIdx.x % kGroups) * kCtlStride);
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
-            int f = t + u * kPollThreads;
-            f = f < nbox ? f : nbox - 1;
-            early[u] = __hip_atomic_load(bx + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int f = t + u * kPollThreads;
+            early[u] = __hip_atomic_load(f < nbox ? bx + f : idle, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     };
 
