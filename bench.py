@@ -132,19 +132,31 @@ def cpu_baseline(wl):
                       f"and best of 3 on one thread"}
 
 
+BF16_MFMA_PEAK_TFLOPS = 2500.0        # dense bf16 matrix-core peak
+
+
+def taps_on_matrix_cores(wl) -> bool:
+    """bf16 storage with Ks <= 17: the library runs the depth-wise taps as bf16 matrix
+    instructions (fp32 accumulation), so their roof is the bf16 matrix peak."""
+    return wl.elem_bytes == 2 and wl.Ks <= 17
+
+
 def roofline_of(wl, sec):
-    """Which roof bounds this workload (HBM at 8 TB/s or the fp32 vector units at 157.3
-    TFLOP/s) and the fraction of it reached; the fractions against the other ceilings ride along."""
+    """Which roof bounds this workload (HBM at 8 TB/s, or the units the taps run on: the fp32
+    vector units at 157.3 TFLOP/s, for bf16 storage with Ks <= 17 the bf16 matrix cores at
+    2.5 PFLOP/s) and the fraction of it reached; the fractions against the other ceilings ride along."""
     b_alg = 2.0 * wl.N * wl.C * wl.H * wl.W * wl.elem_bytes   # read x once, write out once
     f_alg = 2.0 * wl.Ks * wl.Ks * wl.N * wl.Ca * wl.H * wl.W  # merged-kernel tap count
     t_hbm = b_alg / (HBM_PEAK_GBS * 1e9)
-    t_alu = f_alg / (FP32_VECTOR_PEAK_TFLOPS * 1e12)
+    on_mfma = taps_on_matrix_cores(wl)
+    alu_peak = BF16_MFMA_PEAK_TFLOPS if on_mfma else FP32_VECTOR_PEAK_TFLOPS
+    t_alu = f_alg / (alu_peak * 1e12)
     gbs, tfl = b_alg / sec / 1e9, f_alg / sec / 1e12
     if t_hbm >= t_alu:
         r = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
     else:
-        r = {"bound": "alu", "achieved": tfl, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-             "frac": tfl / FP32_VECTOR_PEAK_TFLOPS}
+        r = {"bound": "mfma" if on_mfma else "alu", "achieved": tfl, "peak": alu_peak, "unit": "TFLOP/s",
+             "frac": tfl / alu_peak}
     r.update({
         "algorithmic_bytes": b_alg, "algorithmic_flops": f_alg,
         "hbm_gbps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
@@ -162,16 +174,18 @@ FP32_MFMA_PEAK_TFLOPS = 157.3         # dense fp32 matrix-core peak
 
 def fused_roofline_of(wl, sec, lkc, residual):
     """The fused call: x read once (plus the residual), out written once; the depth-wise taps on
-    the vector units, Conv_fuse (and LK^c) on the matrix cores in fp32."""
+    the vector units, Conv_fuse (and LK^c) on the matrix cores in fp32 - with bf16 storage both
+    on the bf16 matrix cores (taps: Ks <= 17), whose peak is then the one that counts."""
     P = wl.N * wl.H * wl.W
     b_alg = (3.0 if residual else 2.0) * P * wl.C * wl.elem_bytes
     f_vec = 2.0 * wl.Ks * wl.Ks * P * wl.Ca
     f_mat = 2.0 * wl.C * wl.C * P + (2.0 * wl.Ca * wl.Ca * P if lkc else 0.0)
-    t = {"hbm": b_alg / (HBM_PEAK_GBS * 1e9), "alu": f_vec / (FP32_VECTOR_PEAK_TFLOPS * 1e12),
-         "mfma": f_mat / (FP32_MFMA_PEAK_TFLOPS * 1e12)}
+    taps_peak = BF16_MFMA_PEAK_TFLOPS if taps_on_matrix_cores(wl) else FP32_VECTOR_PEAK_TFLOPS
+    mat_peak = BF16_MFMA_PEAK_TFLOPS if wl.elem_bytes == 2 else FP32_MFMA_PEAK_TFLOPS
+    t = {"hbm": b_alg / (HBM_PEAK_GBS * 1e9), "alu": f_vec / (taps_peak * 1e12), "mfma": f_mat / (mat_peak * 1e12)}
     bound = max(t, key=t.get)
     ach = {"hbm": b_alg / sec / 1e9, "alu": f_vec / sec / 1e12, "mfma": f_mat / sec / 1e12}[bound]
-    peak = {"hbm": HBM_PEAK_GBS, "alu": FP32_VECTOR_PEAK_TFLOPS, "mfma": FP32_MFMA_PEAK_TFLOPS}[bound]
+    peak = {"hbm": HBM_PEAK_GBS, "alu": taps_peak, "mfma": mat_peak}[bound]
     return {"bound": bound, "achieved": ach, "peak": peak, "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
             "frac": ach / peak, "algorithmic_bytes": b_alg, "algorithmic_flops_vector": f_vec,
             "algorithmic_flops_matrix": f_mat, "hbm_gbps": b_alg / sec / 1e9, "alu_tflops": f_vec / sec / 1e12,
@@ -202,11 +216,14 @@ def backward_roofline_of(wl, sec):
     b_alg = 3.0 * P * wl.C * wl.elem_bytes
     f_alg = 4.0 * wl.Ks * wl.Ks * P * wl.Ca
     r = roofline_of(wl, sec)
-    t_hbm, t_alu = b_alg / (HBM_PEAK_GBS * 1e9), f_alg / (FP32_VECTOR_PEAK_TFLOPS * 1e12)
+    # (the input gradient's half runs on the bf16 matrix cores where the forward's taps do: its time
+    # at that peak is negligible, and the correlation's half stays on the fp32 vector units)
+    f_vec = f_alg / 2.0 if taps_on_matrix_cores(wl) else f_alg
+    t_hbm, t_alu = b_alg / (HBM_PEAK_GBS * 1e9), f_vec / (FP32_VECTOR_PEAK_TFLOPS * 1e12)
     if t_hbm >= t_alu:
         out = {"bound": "hbm", "achieved": b_alg / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        out = {"bound": "alu", "achieved": f_alg / sec / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
+        out = {"bound": "alu", "achieved": f_vec / sec / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
     out["frac"] = out["achieved"] / out["peak"]
     out.update({"algorithmic_bytes": b_alg, "algorithmic_flops": f_alg, "hbm_gbps": b_alg / sec / 1e9,
                 "alu_tflops": f_alg / sec / 1e12})

@@ -24,11 +24,13 @@
  *     ranges the library can see).  lk, the estimator weights, dk and the
  *     workspace are fp32 in both storage modes.  With bf16 storage and Ks <= 17
  *     the large-kernel weights are rounded to bf16 on the device before use
- *     (products are exact, accumulation stays fp32), and two taps share one
- *     instruction: a pixel of the attention slice that is not finite then also
- *     turns the outputs one column beyond the kernel's reach, on either side,
- *     into NaN.  fp32 storage, and bf16 storage with Ks >= 19, give NaN/Inf
- *     exactly where the definition does.
+ *     (products are exact, accumulation stays fp32) and the taps run on the
+ *     matrix cores, 16 neighbouring outputs of a row from 32 input columns at a
+ *     time, most of them times a zero: a pixel of the attention slice that is
+ *     not finite then turns into NaN, in the rows its kernel window reaches,
+ *     every such run of 16 outputs (columns 16 b ... 16 b + 15) whose 32 input
+ *     columns hold it, and nothing else.  fp32 storage, and bf16 storage with
+ *     Ks >= 19, give NaN/Inf exactly where the definition does.
  *   - All arguments are validated on the host before the first launch; a call
  *     that returns an error has enqueued nothing.
  *   - Every compute call needs a workspace (work queue and the mailboxes blocks
@@ -144,8 +146,10 @@ esc_status esc_convattn_forward(const void *x, esc_dtype dt, int N, int C, int H
  *                                            the tensor the module's result is added to)
  *
  * The concat is never written: Conv_fuse reads F_res from the workspace and the identity
- * channels from x, on the matrix cores with fp32 products and fp32 accumulation (bf16
- * storage is widened on load).  F_res (and F_pw) pass through the workspace in the storage
+ * channels from x, on the matrix cores: with fp32 storage fp32 products and fp32
+ * accumulation; with bf16 storage bf16 matrix instructions on the stored values, each fp32
+ * weight applied as the sum of two bf16 terms (w = hi + lo to 16 mantissa bits; products
+ * exact, accumulation fp32).  F_res (and F_pw) pass through the workspace in the storage
  * type, so with bf16 storage they are rounded to bf16 on the way, as a network's tensors
  * would be; out is rounded once more at its store.  out must not overlap x, residual or
  * the workspace.  The workspace is larger than esc_convattn_forward's
@@ -196,7 +200,7 @@ esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C,
  *            contents - the way a kernel shared by many modules collects its gradient
  * x, lk, gen and dk_in are the forward's inputs.  fp32 accumulation throughout; every sum
  * has a fixed order.  The workspace is esc_backward_workspace_bytes large, prepared with
- * esc_workspace_init.  Seven small and large launches on `stream`.
+ * esc_workspace_init.  Six launches on `stream`.
  */
 typedef struct esc_gen_grads {
     float *w_down; /* [hidden, C_a] or NULL */

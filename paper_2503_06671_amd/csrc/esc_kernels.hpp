@@ -934,7 +934,8 @@ struct ConvGeom {
 // 32 tile columns), B = 32 tile columns x 16 image rows, so the instruction yields a 16 x 16
 // block of outputs for kernel row i; Ks of them, the tile rows moving down by one each time,
 // finish the block.  (60 % of the products are with zeros of the band; the matrix cores
-// are 17 times faster than the dot instruction, which bounded these calls.)
+// are 17 times faster than the two-tap dot instruction this loop used to run on, whose
+// rate bounded these calls.)
 //
 // LDS layout: the tile is cut into pieces of 8 columns (16 bytes) and stored piece column
 // after piece column - element (r, t) at ((t / 8) * HRP + r) * 8 + t % 8 - so that the 16

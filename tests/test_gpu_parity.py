@@ -39,8 +39,8 @@ def test_every_kernel_size_ragged_multi_tile(oracle, Ks):
 
 @pytest.mark.parametrize("Ks", list(range(1, 32, 2)))
 def test_bf16_storage_ragged_multi_tile(oracle, Ks):
-    # every kernel size with bf16 storage: the packed two-taps-per-instruction path up to
-    # Ks = 17 (its alignment constants depend on Ks), the widened path beyond
+    # every kernel size with bf16 storage: the matrix-core path up to Ks = 17 (its alignment
+    # constants depend on Ks), the widened path beyond
     wl = wk.make_random(300 + Ks, 2, 5, 45, 136, 4, Ks, dtype=BF16, x_mean=0.5)
     check_forward(wl, oracle)
 
@@ -379,7 +379,7 @@ def test_non_finite_pixels_in_the_attention_slice(oracle, dtype, Ks):
 
 def test_bf16_large_kernel_weight_rounding_error_bound(oracle):
     # With bf16 storage and Ks <= 17 the fp32 large-kernel weights are rounded to bf16 on
-    # the device (two taps per dot instruction).  Bound asserted here: the normwise error
+    # the device (operands of the bf16 matrix instructions).  Bound asserted here: the normwise error
     # against the float64 oracle stays below 6e-3 at Ks = 13 (the store's own rounding to
     # bf16 alone is 2^-9 ~ 2e-3 relative per value; weights add an independent 2^-9 per tap),
     # far inside the 2e-2 bar; with weights that are exactly representable in bf16 the
