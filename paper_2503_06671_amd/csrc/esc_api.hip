@@ -154,7 +154,8 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_grains)
     }
 
     // all conv items (and the gen items they wait for) in the first round => fused pooling
-    if (p.pool_mode == kPoolItems && p.n_conv > 0 && per_die_of(p.n_conv) + per_die_of(p.n_gen) <= Smax) {
+    const bool one_round = p.n_conv > 0 && per_die_of(p.n_conv) + per_die_of(p.n_gen) <= Smax;
+    if (p.pool_mode == kPoolItems && one_round) {
         p.pool_mode = kPoolFused;
         p.n_pool = 0;
     } else if (p.dk_mode == kDkMeans) {
@@ -171,7 +172,10 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_grains)
     {
         const u64 others0 = (u64)p.n_pool + p.n_gen + p.n_conv, resident0 = (u64)kXcds * Smax;
         const u64 spare = resident0 > others0 + kXcds * 4 ? resident0 - others0 - kXcds * 3 : 0;
-        p.copy_gentle = p.pool_mode == kPoolFused && p.n_gsum == 0 && (p.dk_mode == kDkDirect || p.dk_mode == kDkBoxes) &&
+        // (calls without an estimator - DK given, or none - take the same arrangement when their conv items fit)
+        const bool resident_convs = p.pool_mode == kPoolFused || (p.pool_mode == kPoolNone && one_round);
+        p.copy_gentle = resident_convs && p.n_gsum == 0 &&
+                        (p.dk_mode == kDkDirect || p.dk_mode == kDkBoxes || p.dk_mode == kDkGiven || p.dk_mode == kDkNone) &&
                         (u64)p.N * p.idt_len <= spare * 12 * (u64)kThreads * 16;
     }
 
@@ -237,7 +241,7 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_grains)
     // conv entries (the long ones) run out first and the list ends with copy entries, which
     // even out the end of the call (measured at 540 x 960: 2 - 3 % over plain proportion for
     // Ks = 7 ... 17, and over the fixed 1:1 / 1:2 / 1:3 patterns before it).
-    if (p.pool_mode == kPoolFused) {
+    if (p.pool_mode == kPoolFused || p.copy_gentle) {
         p.mix_a = p.mix_b = 1u << 30;  // all conv items first: they must all be in the first round
     } else {
         const unsigned Ul = U ? U : 1;
@@ -406,10 +410,12 @@ esc_status enqueue_dynkernel(const void *x, esc_dtype dt, int N, int C, int H, i
 
 // The forward on checked arguments: one launch.  `out` holds out_c channels per image, of
 // which the first C_a are written by the conv items; with_copy adds the pass-through copy
-// of channels C_a .. C (then out_c == C).
+// of channels C_a .. C (then out_c == C).  out_add: a constant per (image, channel) for the
+// conv items to add to their plane's outputs, or NULL.
 esc_status enqueue_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a, const float *lk, int Ks,
                            long lk_channel_stride, const esc_gen_params *gen, const float *dk_in, void *out, int out_c,
-                           bool with_copy, void *workspace, const WsLayout &l, hipStream_t stream)
+                           bool with_copy, void *workspace, const WsLayout &l, hipStream_t stream,
+                           const float *out_add = nullptr)
 {
     const size_t es = dt == ESC_F32 ? 4 : 2;
     const uintptr_t xa = (uintptr_t)x, oa = (uintptr_t)out;
@@ -422,6 +428,8 @@ esc_status enqueue_forward(const void *x, esc_dtype dt, int N, int C, int H, int
     p.lk_cstride = lk_channel_stride;
     p.dk_in = (gen == nullptr && C_a > 0) ? dk_in : nullptr;
     if (p.dk_in != nullptr) p.dk_mode = kDkGiven;
+    p.out_add = C_a > 0 ? out_add : nullptr;
+    if (p.out_add != nullptr) p.staged = 1;  // the kernel flavour whose conv items know of it
     // 16-byte (fp32) / 8-byte (bf16) row stores need W % 4 == 0 and an aligned base
     p.conv_vec_ok = (W % 4 == 0) && (oa % (4 * es) == 0);
     if (with_copy && C_a < C) {
@@ -903,12 +911,10 @@ esc_status esc_convattn_backward(const void *x, const void *grad_out, esc_dtype 
     // 2. the estimator forwards (DK) and backwards; the flipped kernels
     if (launch_backward_estimator(p, s) != hipSuccess) return ESC_ERR_HIP;
     // 3. the input gradient's convolution is the forward on grad_out with the flipped kernels
-    //    (identity channels: grad_x = grad_out, the forward's pass-through copy)
-    if ((st = enqueue_forward(grad_out, dt, N, C, H, W, C_a, p.lkf, Ks, lk_channel_stride != 0 ? (long)Ks * Ks : 0,
-                              nullptr, p.dkf, grad_x, C, true, workspace, b.ws, s)) != ESC_OK)
-        return st;
-    // 4. the GAP's share: dL/dg / (H W) on every pixel of the attention planes
-    return launch_backward_add_gap_term(p, grad_x, bf16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
+    //    (identity channels: grad_x = grad_out, the forward's pass-through copy); the GAP's
+    //    share, dL/dg / (H W) on every pixel of the attention planes, is added at its stores
+    return enqueue_forward(grad_out, dt, N, C, H, W, C_a, p.lkf, Ks, lk_channel_stride != 0 ? (long)Ks * Ks : 0, nullptr,
+                           p.dkf, grad_x, C, true, workspace, b.ws, s, p.has_gen ? p.dgc : nullptr);
 }
 
 const char *esc_status_string(esc_status s)

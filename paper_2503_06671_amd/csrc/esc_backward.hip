@@ -11,7 +11,8 @@
 // The input gradient's convolution is the forward kernel itself, run on grad_out with the
 // flipped kernels (esc_api.hip); this file holds what is new: the correlation S (the same
 // arithmetic as the forward's tap loop, turned round: 2 Ks^2 flops per pixel into Ks^2
-// sums), the small estimator kernels, and the GAP term of dx.  Every sum has a fixed order
+// sums) and the small estimator kernels; the GAP term of dx is a constant per plane that the
+// input gradient's launch adds at its stores.  Every sum has a fixed order
 // (per-tile partial sums in the workspace, then one thread per result), so results do not
 // depend on scheduling.
 #include <hip/hip_runtime.h>
@@ -385,38 +386,6 @@ __global__ __launch_bounds__(256) void estimator_param_kernel(const BackwardPara
     if (l == 15 && dst != nullptr) *dst = p.accumulate ? *dst + s : s;
 }
 
-// dx[n,c,:] += dgc[n,c] on the attention planes, 16 bytes per access when the planes allow it
-template <typename T, bool VEC>
-__global__ void add_gap_term_kernel(T *dx, const float *dgc, int N, int C, int Ca, size_t plane)
-{
-    constexpr int PER = VEC ? 16 / (int)sizeof(T) : 1;
-    const size_t groups = plane / PER, total = (size_t)N * Ca * groups;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const size_t nc = i / groups, q = (i - nc * groups) * PER;
-        const size_t n = nc / Ca, c = nc - n * Ca;
-        T *dst = dx + (n * C + c) * plane + q;
-        const float add = dgc[nc];
-        if constexpr (!VEC) {
-            const float v = bw_load(dst) + add;
-            if constexpr (std::is_same<T, float>::value)
-                *dst = v;
-            else
-                dst->bits = bw_f32_to_bf16(v);
-        } else if constexpr (std::is_same<T, float>::value) {
-            float4 v = *reinterpret_cast<float4 *>(dst);
-            v.x += add, v.y += add, v.z += add, v.w += add;
-            *reinterpret_cast<float4 *>(dst) = v;
-        } else {
-            uint4 w = *reinterpret_cast<uint4 *>(dst);
-            auto both = [&](uint32_t u) {
-                const float lo = __uint_as_float(u << 16) + add, hi = __uint_as_float(u & 0xffff0000u) + add;
-                return (uint32_t)bw_f32_to_bf16(lo) | ((uint32_t)bw_f32_to_bf16(hi) << 16);
-            };
-            w.x = both(w.x), w.y = both(w.y), w.z = both(w.z), w.w = both(w.w);
-            *reinterpret_cast<uint4 *>(dst) = w;
-        }
-    }
-}
 
 template <typename T, int KC>
 hipError_t launch_corr(const BackwardParams &p, unsigned grid, hipStream_t s)
@@ -471,27 +440,6 @@ __attribute__((visibility("hidden"))) hipError_t launch_backward_estimator(const
     const size_t threads = n_est * 16 + (n_lkf + 15) / 16 * 16;
     (void)params;
     hipLaunchKernelGGL(estimator_param_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
-    return hipGetLastError();
-}
-
-__attribute__((visibility("hidden"))) hipError_t launch_backward_add_gap_term(const BackwardParams &p, void *dx, bool bf16,
-                                                                              hipStream_t s)
-{
-    if (p.Ca < 1 || !p.has_gen) return hipSuccess;
-    const size_t plane = (size_t)p.H * p.W, es = bf16 ? 2 : 4, per = 16 / es;
-    const bool vec = plane % per == 0 && (uintptr_t)dx % 16 == 0;
-    const size_t total = (size_t)p.N * p.Ca * (vec ? plane / per : plane);
-    size_t blocks = (total + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    const dim3 grid((unsigned)blocks), block(256);
-    if (bf16 && vec)
-        hipLaunchKernelGGL((add_gap_term_kernel<bf16b, true>), grid, block, 0, s, (bf16b *)dx, p.dgc, p.N, p.C, p.Ca, plane);
-    else if (bf16)
-        hipLaunchKernelGGL((add_gap_term_kernel<bf16b, false>), grid, block, 0, s, (bf16b *)dx, p.dgc, p.N, p.C, p.Ca, plane);
-    else if (vec)
-        hipLaunchKernelGGL((add_gap_term_kernel<float, true>), grid, block, 0, s, (float *)dx, p.dgc, p.N, p.C, p.Ca, plane);
-    else
-        hipLaunchKernelGGL((add_gap_term_kernel<float, false>), grid, block, 0, s, (float *)dx, p.dgc, p.N, p.C, p.Ca, plane);
     return hipGetLastError();
 }
 

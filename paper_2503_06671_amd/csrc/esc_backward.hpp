@@ -47,7 +47,5 @@ struct BackwardParams {
 hipError_t launch_backward_sums(const BackwardParams &p, bool bf16, hipStream_t s);
 // the estimator forwards (DK) and backwards (its gradients, dL/dg), the flipped kernels
 hipError_t launch_backward_estimator(const BackwardParams &p, hipStream_t s);
-// dx[n,c] += dgc[n,c] on the attention planes
-hipError_t launch_backward_add_gap_term(const BackwardParams &p, void *dx, bool bf16, hipStream_t s);
 
 }  // namespace esc

@@ -150,6 +150,8 @@ struct FwdParams {
     long lk_cstride;
     const float *dk_in;  // DK given by the caller (no estimator), or NULL
     float *dk_out;       // esc_dynkernel_gen: where the estimator's DK goes, else NULL
+    const float *out_add;  // [N*Ca] a constant per (image, channel) added to every output of its plane before the
+                           // store's rounding (the backward's GAP term), or NULL
     const float *w_down, *b_down, *w_up, *b_up;
     int hidden;
     int dk_mode;         // where conv items take DK from (kDk*)
@@ -177,7 +179,7 @@ struct FwdParams {
     unsigned *done;      // [kGroups] blocks of the group that have announced their leave
     unsigned *queue;     // [kGroups] entries of the group's list handed out beyond the first per block
     int dynamic;         // blocks take their further entries from the group's queue
-    int staged;          // host only: launch the kernel flavour with the staged estimator items
+    int staged;          // host only: launch the kernel flavour with the staged estimator items (and out_add)
     // Every conv item is resident from the start (fused pooling) and the call is so short
     // that the conv items' chain of load, taps, estimator and store is what it lasts: the
     // copy items then keep little in flight, so that the conv items' few accesses (tile,
@@ -996,7 +998,7 @@ __device__ __forceinline__ ConvWhere conv_where(ParamsPtr p, unsigned item)
     return w;
 }
 
-template <int KS, int RY, typename T>
+template <int KS, int RY, typename T, bool ADD>
 __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
 {
     using G = ConvGeom<KS, RY>;
@@ -1567,6 +1569,15 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     }
 
     if (p->dk_mode == kDkNone) claim_next(p, ctx);
+    // (only in the kernel flavour that calls with such a constant are sent to: the flavour
+    // the short forward calls use stays free of it)
+    if (ADD && p->out_add != nullptr) {  // block-uniform
+        const float add = p->out_add[wd.nc];
+#pragma unroll
+        for (int oy = 0; oy < RY; ++oy)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[oy][q] += add;
+    }
     if constexpr (kMatrix) {
         // rounded once, through LDS (MatrixGeom::OP), then rows ty*RY ... of the tile, four
         // columns per thread, as on the other path
@@ -1816,7 +1827,7 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
             }
         } else if (kind == 2) {
             if constexpr (KS > 0)
-                ctx = conv_item<KS, RY, T>(p, ctx, idx);
+                ctx = conv_item<KS, RY, T, STAGED>(p, ctx, idx);
         } else {
             ctx = copy_item(p, ctx, idx);
         }
