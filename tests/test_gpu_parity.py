@@ -268,6 +268,27 @@ def test_one_workspace_serves_a_sequence_of_different_calls():
                 assert np.array_equal(two_step.view(np.uint8), out_alone.view(np.uint8))
 
 
+@pytest.mark.parametrize("N,C,H,W,Ca,Ks", [
+    (2, 6, 70, 132, 4, 3), (2, 6, 70, 132, 4, 9), (2, 6, 70, 132, 4, 13), (2, 6, 70, 132, 4, 17),   # two-row blocks
+    (8, 10, 130, 132, 8, 13), (8, 10, 130, 140, 8, 7),                                              # four-row blocks
+])
+def test_bf16_matrix_path_eight_byte_tile_fetch(oracle, N, C, H, W, Ca, Ks):
+    # W % 4 == 0 but W % 8 != 0: the matrix-core path fetches its tile in 4-element chunks
+    # (16-byte pieces need W % 8 == 0, single elements serve every other width)
+    wl = wk.make_random(900 + Ks + W, N, C, H, W, Ca, Ks, dtype=BF16, x_mean=0.4)
+    check_forward(wl, oracle)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("hidden,bias", [(0, True), (8, True), (16, False)])
+def test_large_planes_in_one_round_conv_items_run_the_estimator_from_the_channel_means(oracle, dtype, hidden, bias):
+    # more pool mailboxes per image than one item collects (8 channels x 77 tiles), a small
+    # estimator, and all conv items resident at once: gsum items publish the channel means and
+    # every conv item runs its nine estimator outputs itself
+    wl = wk.make_random(920 + hidden, 1, 10, 200, 704, 8, 13, dtype=dtype, hidden=hidden, bias=bias, x_mean=0.4)
+    check_forward(wl, oracle)
+
+
 def test_captured_graph_replays_like_plain_calls():
     # Three different calls on one workspace captured into one graph; the graph is replayed
     # several times with plain calls and synchronisations in between, and every replay must
