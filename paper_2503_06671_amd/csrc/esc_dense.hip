@@ -13,10 +13,15 @@
 // ([tap][16 co][16 ci], rearranged once per call by a small kernel so that a row is one run
 // of memory) are staged beside it, the next row's already in flight in registers.  Per tap
 // and group of four input channels a wavefront reads one A operand per 16 output channels
-// (lane l: W[co = l % 16][ci = l / 16]) and four B operands (lane l: pixel l % 16 of input
-// channel l / 16, shifted by the tap - the im2col happens in the LDS address), for its four
-// runs of 16 pixels.  DK's nine depth-wise taps are added from the same tile on the vector
-// units; the block also moves its share of the pass-through channels (Eq. 4 lines 1 and 4).
+// (lane l: W[co = l % 16][ci = l / 16]) and its B operands (lane l: pixel l % 16 of input
+// channel l / 16, shifted by the tap - the im2col happens in the LDS address).  With more
+// than 16 channels a wavefront owns a quarter of the tile's runs of 16 pixels and walks all
+// input channels; with up to 16 (the paper's C_a) it owns four input channels - the K of one
+// instruction - for all of the tile's runs, and the four partial results are added through
+// LDS: eight to sixteen independent accumulators per wavefront instead of two, operands of
+// the next tap in flight while this tap's instructions issue.  DK's nine depth-wise taps are
+// added from the same tile on the vector units; the block also moves its share of the
+// pass-through channels (Eq. 4 lines 1 and 4).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -82,6 +87,16 @@ __global__ void dense_weights_kernel(const float *lk, int Ca, int Ks, int Kse, f
 
 extern __shared__ __align__(16) float dn_lds[];
 
+// x / d for x < 2^31 by multiply-high and shift (dn_make_div fills mul and shift on the host)
+__device__ __forceinline__ unsigned dn_div(unsigned x, unsigned mul, unsigned shift) { return (__umulhi(x, mul) + x) >> shift; }
+void dn_make_div(unsigned d, unsigned &mul, unsigned &shift)
+{
+    unsigned l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    mul = (unsigned)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
+    shift = l;
+}
+
 template <typename T, int CT, int TH>
 __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(const DenseParams p)
 {
@@ -109,19 +124,30 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
     const T *xn = (const T *)p.x + (size_t)n * p.C * plane_px;
 
     // ---- the block's share of the pass-through copy (Eq. 4 lines 1 and 4): issued first, it
-    // streams while the first tile and weights arrive ----
+    // streams while the first tile and weights arrive; its last 16 KiB round is stored only
+    // behind the tile's loads (copy_last_store), so that the two round trips overlap ----
+    u32x4 copy_v[4] = {};
+    size_t copy_o0 = 0, copy_end = 0;
+    char *copy_dst = nullptr;
     if (p.idt_len > 0) {
         const char *src = (const char *)p.x + (size_t)n * p.img_bytes + p.idt_off;
         char *dst = (char *)p.out + (size_t)n * p.img_bytes + p.idt_off;
         const size_t begin = (size_t)t_in * p.copy_share;
         const size_t end = begin + p.copy_share < p.idt_len ? begin + p.copy_share : p.idt_len;
         if (p.copy_vec) {
-            for (size_t o0 = begin; o0 < end; o0 += (size_t)4 * kDnThreads * 16) {
+            constexpr size_t kRound = (size_t)4 * kDnThreads * 16;
+            for (size_t o0 = begin; o0 < end; o0 += kRound) {
                 u32x4 v[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const size_t o = o0 + ((size_t)u * kDnThreads + tid) * 16;
                     v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (o + 16 <= end ? o : begin)));
+                }
+                if (o0 + kRound >= end) {  // the last round (block-uniform)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) copy_v[u] = v[u];
+                    copy_o0 = o0, copy_end = end, copy_dst = dst;
+                    break;
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -140,11 +166,34 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
         }
     }
 
+    auto copy_last_store = [&]() {
+        if (copy_dst != nullptr) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const size_t o = copy_o0 + ((size_t)u * kDnThreads + tid) * 16;
+                if (o + 16 <= copy_end) __builtin_nontemporal_store(copy_v[u], reinterpret_cast<u32x4 *>(copy_dst + o));
+            }
+            copy_dst = nullptr;
+        }
+    };
+
     f32x4 acc[CT][NT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[ct][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // At most 16 channels (the paper's C_a): the contraction is split over the wavefronts by
+    // input channel - wavefront w takes channels 4w .. 4w + 3, exactly the K of one
+    // instruction, for ALL of the tile's runs of 16 pixels.  One A operand then serves 2 TH
+    // independent accumulators (with one tile row per wavefront it served two, and a
+    // compute unit with two blocks had four chains of dependent instructions per SIMD:
+    // 42 % of the matrix rate), and nobody reads the same weights twice.  The four partial
+    // results are added through LDS at the end.
+    constexpr bool kSplitK = CT == 1;
+    constexpr int NA = kSplitK ? 2 * TH : 1;
+    f32x4 part[NA];
+#pragma unroll
+    for (int nt = 0; nt < NA; ++nt) part[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     constexpr int kWPer = (kDenseMaxKs * CT * 256 + kDnThreads * 4 - 1) / (kDnThreads * 4);  // 16-byte pieces of a weight row per thread, at most
     for (int chunk = 0; chunk < CT; ++chunk) {
@@ -153,22 +202,27 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
         {
             const int hc = kDnTw + 2 * pad;
             const int total = 16 * HR * hc;
-            for (int i0 = 0; i0 < total; i0 += 8 * kDnThreads) {
-                float v[8];
+            constexpr int kFlight = 24;  // loads a thread has in flight: a round costs one trip to memory
+            for (int i0 = 0; i0 < total; i0 += kFlight * kDnThreads) {
+                float v[kFlight];
+                unsigned inside = 0;  // bit u: element u lies in the image (the loads are unconditional, from clamped addresses)
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < kFlight; ++u) {
                     const int idx = i0 + u * kDnThreads + tid;
-                    const int ci = idx / (HR * hc), r2 = idx - ci * (HR * hc), r = r2 / hc, c = r2 - r * hc;
+                    const int ci = (int)dn_div((unsigned)idx, p.hp_mul, p.hp_shift), r2 = idx - ci * (HR * hc);
+                    const int r = (int)dn_div((unsigned)r2, p.hc_mul, p.hc_shift), c = r2 - r * hc;
                     const int gy = y0 - pad + r, gx = x0 - pad + c, ch = 16 * chunk + ci;
                     const bool in = idx < total && ch < p.Ca && gy >= 0 && gy < H && gx >= 0 && gx < W;
                     v[u] = dn_load(xn + (in ? (size_t)ch * plane_px + (size_t)gy * W + gx : 0));
-                    v[u] = in ? v[u] : 0.f;
+                    inside |= (in ? 1u : 0u) << u;
                 }
+                copy_last_store();
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < kFlight; ++u) {
                     const int idx = i0 + u * kDnThreads + tid;
-                    const int ci = idx / (HR * hc), r2 = idx - ci * (HR * hc), r = r2 / hc, c = r2 - r * hc;
-                    if (idx < total) s_tile[ci * PLANE + r * PITCH + c] = v[u];
+                    const int ci = (int)dn_div((unsigned)idx, p.hp_mul, p.hp_shift), r2 = idx - ci * (HR * hc);
+                    const int r = (int)dn_div((unsigned)r2, p.hc_mul, p.hc_shift), c = r2 - r * hc;
+                    if (idx < total) s_tile[ci * PLANE + r * PITCH + c] = ((inside >> u) & 1u) != 0 ? v[u] : 0.f;
                 }
             }
         }
@@ -193,7 +247,36 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
             }
             __syncthreads();
             if (i + 1 < Ks) fetch_row(i + 1);
-            for (int j = 0; j < Ks; ++j) {
+            if constexpr (kSplitK) {
+                // two operand sets take turns: tap j + 1's LDS reads are issued before tap j's
+                // instructions (left to itself the compiler reads, waits and multiplies pair by pair)
+                const float *wj = s_w + (4 * wave + kq) * 16 + l16;
+                const float *tj = s_tile + (4 * wave + kq) * PLANE + i * PITCH + l16;
+                auto fetch = [&](int j, float &a, float (&b)[NA]) {
+                    a = wj[j * 256];
+#pragma unroll
+                    for (int nt = 0; nt < NA; ++nt) b[nt] = tj[(nt >> 1) * PITCH + 16 * (nt & 1) + j];
+                };
+                auto multiply = [&](float a, const float (&b)[NA]) {
+#pragma unroll
+                    for (int nt = 0; nt < NA; ++nt) part[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[nt], part[nt], 0, 0, 0);
+                };
+                // (the reads are unconditional - beyond the last tap they repeat it - because behind
+                // a branch the compiler no longer knows how many are in flight and waits for all)
+                float a0, a1, b0[NA], b1[NA];
+                fetch(0, a0, b0);
+                for (int j = 0; j < Ks; j += 2) {
+                    fetch(j + 1 < Ks ? j + 1 : Ks - 1, a1, b1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    multiply(a0, b0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch(j + 2 < Ks ? j + 2 : Ks - 1, a0, b0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (j + 1 < Ks) multiply(a1, b1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            for (int j = 0; j < (kSplitK ? 0 : Ks); ++j) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     float b[NT];
@@ -236,6 +319,33 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct)  // (a constant index: the accumulators stay in registers)
                         if (ct == chunk) acc[ct][nt][r] += s;
+                }
+            }
+        }
+    }
+
+    if constexpr (kSplitK) {
+        // run nt of the tile belongs to wavefront nt / NT (as accumulator nt % NT); lane l's four
+        // values of a run lie 16 bytes together, a wavefront's run 1 KiB, the four wavefronts'
+        // copies of a run side by side
+        constexpr int kPass = 8;  // runs per pass: 32 KiB of LDS
+        f32x4 *s_red = reinterpret_cast<f32x4 *>(s_tile);
+#pragma unroll
+        for (int p0 = 0; p0 < NA; p0 += kPass) {
+            __syncthreads();  // the tile (DK's taps) or the previous pass is no longer read
+#pragma unroll
+            for (int u = 0; u < kPass; ++u) s_red[((u * 4) + wave) * 64 + lane] = part[p0 + u];
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kPass; ++u) {
+                const int nt = p0 + u;
+                if (nt / NT == wave) {  // wavefront-uniform
+                    f32x4 sum = s_red[(u * 4 + 0) * 64 + lane];
+#pragma unroll
+                    for (int w = 1; w < 4; ++w) sum += s_red[(u * 4 + w) * 64 + lane];
+#pragma unroll
+                    for (int m = 0; m < NT; ++m)  // (a constant index: the accumulators stay in registers)
+                        if (m == nt % NT) acc[0][m] += sum;
                 }
             }
         }
@@ -323,7 +433,12 @@ __attribute__((visibility("hidden"))) hipError_t launch_dense(const DenseParams 
     }
     int hr, pitch, plane;
     dense_geom(p.Ks, th, hr, pitch, plane);
-    const size_t lds = ((size_t)16 * plane + (size_t)p.Ks * ct * 256) * sizeof(float);
+    const unsigned hc = (unsigned)(kDnTw + 2 * ((p.Ks - 1) / 2));
+    dn_make_div(hc, p.hc_mul, p.hc_shift);
+    dn_make_div((unsigned)hr * hc, p.hp_mul, p.hp_shift);
+    size_t lds = ((size_t)16 * plane + (size_t)p.Ks * ct * 256) * sizeof(float);
+    // (up to 16 channels: the wavefronts' partial results pass through the same LDS, 32 KiB at a time)
+    if (ct == 1 && lds < (size_t)8 * 4 * 64 * 16) lds = (size_t)8 * 4 * 64 * 16;
     if (th == 8)
         return bf16 ? launch_t<bf16d, 8>(p, ct, (unsigned)grid, lds, s) : launch_t<float, 8>(p, ct, (unsigned)grid, lds, s);
     return bf16 ? launch_t<bf16d, 4>(p, ct, (unsigned)grid, lds, s) : launch_t<float, 4>(p, ct, (unsigned)grid, lds, s);

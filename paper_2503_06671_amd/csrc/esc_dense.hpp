@@ -20,6 +20,9 @@ struct DenseParams {
     // range by elements when copy_vec is 0) of its image's identity range [idt_off, idt_off + idt_len)
     size_t img_bytes, idt_off, idt_len, copy_share;
     int copy_vec, elem_bytes;
+    // set by launch_dense: division by the halo tile's width and by its rows x width as a
+    // multiply-high and a shift (the tile fill locates every element with both)
+    unsigned hc_mul, hc_shift, hp_mul, hp_shift;
 };
 
 // the kernel size the device code walks: a 1 x 1 kernel is embedded in a 3 x 3 one
