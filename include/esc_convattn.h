@@ -200,7 +200,7 @@ esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C,
  *            contents - the way a kernel shared by many modules collects its gradient
  * x, lk, gen and dk_in are the forward's inputs.  fp32 accumulation throughout; every sum
  * has a fixed order.  The workspace is esc_backward_workspace_bytes large, prepared with
- * esc_workspace_init.  Six launches on `stream`.
+ * esc_workspace_init.  Five launches on `stream`.
  */
 typedef struct esc_gen_grads {
     float *w_down; /* [hidden, C_a] or NULL */
