@@ -1034,15 +1034,16 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     }
 
     // Carried copy (Eq. 4 lines 1 and 4): this item's share of the image's pass-through range
-    // - up to kCarryGrains grains of 16 bytes per thread - is asked for right behind the tile
-    // (and behind the call tag: results return in order, and the tile and the tag are waited
-    // for first), travels while the tile is filled and multiplied, and is stored after the
-    // tap loop, where the item would otherwise only wait for the estimator.  Memory thus
-    // streams from the start of the item, with no block of its own.  (Measured against moving
-    // the share after the loop, before the tile in every other block, or loading it after the
-    // pool sums: this order is the fastest at 360 x 640 and 64 x 64 x 64.)  Buffer accesses:
-    // the resources end with the share, so grains beyond it read as nothing and their stores
-    // are dropped, without a branch.
+    // - up to kCarryGrains grains of 16 bytes per thread - is asked for once the tile has
+    // landed and its pool sums are out, travels while the tile is multiplied, and is stored
+    // after the tap loop, where the item would otherwise only wait for the estimator.  The
+    // copy thus has no block of its own.  Earlier blocks' shares asked for ahead of the tile
+    // delay the tiles of later blocks, and with them the pool sums every estimator waits for;
+    // asked for after the band table they come back too late for the store.  (Measured at
+    // 360 x 640 and 64 x 64 x 64 against: right behind the tile loads, behind the fill
+    // barrier, after the band table, after the loop, before the tile in every other block.)
+    // Buffer accesses: the resources end with the share, so grains beyond it read as nothing
+    // and their stores are dropped, without a branch.
     constexpr bool kCarry = conv_carries(KS, RY, std::is_same<T, bf16_t>::value);
     constexpr int kCarryN = kCarry ? kCarryGrains : 1;
     CarryRsrc carry_dst = __builtin_amdgcn_make_buffer_rsrc(nullptr, 0, 0, kRawBufferFlags);
@@ -1059,7 +1060,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             const CarryRsrc src =
                 __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)p->x + base), 0, (int)len, kRawBufferFlags);
             carry_dst = __builtin_amdgcn_make_buffer_rsrc((void *)((char *)p->out + base), 0, (int)len, kRawBufferFlags);
-            const int voff = tid1 * 16;
+            const int voff = opaque_tid() * 16;
 #pragma unroll
             for (int r = 0; r < kCarryN; ++r)
                 carry_v[r] = __builtin_amdgcn_raw_buffer_load_b128(src, voff + r * (int)kGrain, 0, kBufferNt);
@@ -1094,7 +1095,6 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                 if (in) raw[k] = *reinterpret_cast<const u32x4 *>(xp + (size_t)gy * W + gx);
             }
             if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
-            carry_load();
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 const int q = k * kThreads + tid1;
@@ -1130,7 +1130,6 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             }
         }
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
-        carry_load();
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int q = k * kThreads + tid1;
@@ -1163,7 +1162,6 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             }
         }
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
-        carry_load();
     } else {
         for (int idx = tid1; idx < HR * HC; idx += kThreads) {
             const int r = idx / HC, cc = idx - r * HC;
@@ -1227,6 +1225,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
         }
         pool_finish<NPT>(p->pool_box, sums, box, have, ctx.tag, g_red);
     }
+    carry_load();
     if constexpr (kMatrix) {
         // The band table (MatrixGeom), made from the weights in LDS once the pool sums are
         // out (they are what the other blocks wait for): word idx holds the band's entries for
