@@ -194,15 +194,18 @@ def fused_roofline_of(wl, sec, lkc, residual):
 
 def dense_roofline_of(wl, sec):
     """The dense-LK call: same bytes as the depth-wise forward; the C_a x C_a x Ks x Ks contraction on the
-    matrix cores in fp32, DK's nine taps on the vector units."""
+    matrix cores - fp32 instructions for fp32 storage (and for more than 16 channels), bf16 instructions
+    for bf16 storage with up to 16 channels (each weight as two bf16 terms: twice the instructions, which
+    the algorithmic flop count does not include) - DK's nine taps on the vector units."""
     P = wl.N * wl.H * wl.W
     b_alg = 2.0 * P * wl.C * wl.elem_bytes
     f_mat = 2.0 * wl.Ks * wl.Ks * wl.Ca * wl.Ca * P
-    t_hbm, t_mat = b_alg / (HBM_PEAK_GBS * 1e9), f_mat / (FP32_MFMA_PEAK_TFLOPS * 1e12)
+    mat_peak = BF16_MFMA_PEAK_TFLOPS if (wl.elem_bytes == 2 and wl.Ca <= 16) else FP32_MFMA_PEAK_TFLOPS
+    t_hbm, t_mat = b_alg / (HBM_PEAK_GBS * 1e9), f_mat / (mat_peak * 1e12)
     if t_hbm >= t_mat:
         r = {"bound": "hbm", "achieved": b_alg / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        r = {"bound": "mfma", "achieved": f_mat / sec / 1e12, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s"}
+        r = {"bound": "mfma", "achieved": f_mat / sec / 1e12, "peak": mat_peak, "unit": "TFLOP/s"}
     r["frac"] = r["achieved"] / r["peak"]
     r.update({"algorithmic_bytes": b_alg, "algorithmic_flops_matrix": f_mat, "hbm_gbps": b_alg / sec / 1e9,
               "mfma_tflops": f_mat / sec / 1e12, "alu_tflops": 0.0})

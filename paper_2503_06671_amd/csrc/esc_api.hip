@@ -807,7 +807,7 @@ esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C,
         dk = dk_ws;
     }
     float *wt = (float *)(w + d.wt_off);
-    if (launch_dense_weights(lk_dense, C_a, Ks, wt, s) != hipSuccess) return ESC_ERR_HIP;
+    if (launch_dense_weights(lk_dense, C_a, Ks, dt == ESC_BF16, wt, s) != hipSuccess) return ESC_ERR_HIP;
     DenseParams p{};
     p.x = x;
     p.out = out;

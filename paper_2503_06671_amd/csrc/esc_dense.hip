@@ -5,7 +5,8 @@
 //
 // A full C_a -> C_a convolution is a dense contraction over K = C_a * Ks * Ks (2704 for the
 // paper's 13 x 13 x 16 x 16), sixteen times the depth-wise form's arithmetic on the same
-// bytes: it is bound by the matrix cores, so it runs as an implicit GEMM on
+// bytes: it is bound by the matrix cores, so it runs as an implicit GEMM - for bf16 storage
+// with up to 16 channels on the bf16 instructions (dense_bf16_kernel, further down), else on
 // v_mfma_f32_16x16x4_f32 (fp32 products and accumulation; bf16 storage is widened exactly
 // when a tile is staged and rounded once at the store).  Per block: an 8 x 32 (small calls:
 // 4 x 32) pixel output tile of one image, all output channels.  Sixteen input channels at a time, their
@@ -366,6 +367,426 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
         }
 }
 
+// ---------------------------------------------------------------------------------------
+// bf16 storage, up to 16 channels: the contraction on v_mfma_f32_16x16x32_bf16.
+//
+// K of one instruction = two neighbouring taps of a kernel row x 16 input channels.  The
+// stored values stay bf16 (exact operands); each fp32 weight enters as two bf16 terms,
+// w = hi + lo to 16 mantissa bits, so two instructions per operand pair, products exact,
+// accumulation fp32.  The halo tile sits in LDS pixel-major, as cells of 16 bytes = eight
+// channels of one pixel, in two half planes (channels 0-7, 8-15): the sixteen lanes that read
+// one B operand's pixels read 256 consecutive bytes, the only pattern in which 16-byte LDS
+// reads run at full rate.  The tile's columns start at x0 - 8, so that (W % 8 == 0, 16-byte
+// aligned base) a thread fetches whole 16-byte pieces - eight pixels of each of eight
+// channels - transposes them in registers and writes eight cells; the row pitch is odd in
+// cells, lanes take consecutive rows, and the writes spread over all banks.
+//
+// The contraction is split over the four wavefronts by KERNEL ROW, every wavefront
+// accumulating all runs of 16 pixels of the tile: for a pair of tap columns a wavefront
+// holds the A operands of its block of 3-5 neighbouring kernel rows and walks down the tile
+// rows once - a B operand (tile row R, half h) serves every kernel row i of the block with
+// an output row R - i in the tile, so one 1 KiB read feeds up to 2 x 5 instructions instead
+// of two (read once per tap pair and run, the same loop was bound by the LDS as much as by
+// the matrix cores).  Which wavefront takes the larger block rotates with the pair, so that
+// the four end together; the next pair's A operands (from the rearranged table in memory)
+// travel during the walk.  The four partial results meet in LDS as in the fp32 kernel.  An
+// odd kernel leaves the last pair's second column empty: those lanes read the first
+// column's pixels again, against zero weights.
+// ---------------------------------------------------------------------------------------
+constexpr int kBfCols = 48;   // cells per tile row: columns x0 - 8 .. x0 + 39, six aligned pieces of eight
+constexpr int kBfPitch = 49;  // row pitch in cells
+
+// cells in one half plane of the tile; first cell behind the tile and behind the 32 KiB (2048
+// cells) that the partial results pass through; the block's LDS bytes (DK sits at the end)
+__host__ __device__ constexpr int bf_half_cells(int Kse, int th) { return (th + Kse - 1) * kBfPitch; }
+__host__ __device__ constexpr int bf_aux_cell(int Kse, int th) { return 2 * bf_half_cells(Kse, th) < 2048 ? 2048 : 2 * bf_half_cells(Kse, th); }
+inline size_t bf_lds_bytes(int Kse, int th) { return (size_t)bf_aux_cell(Kse, th) * 16 + 16 * 9 * sizeof(float); }
+
+// wa[pair of columns jp][kernel row i][term: hi, lo][lane l][8 bf16]: lane l holds output channel
+// l % 16, tap (i, 2 jp + l / 32), input channels 8 ((l / 16) % 2) .. + 7 - the A operand of the
+// instruction; zero beyond the kernel (the last pair's second column) and beyond C_a
+__global__ void dense_weights_bf16_kernel(const float *lk, int Ca, int Ks, int Kse, uint32_t *wa)
+{
+    const int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    const int njp = (Kse + 1) / 2;
+    if (idx >= njp * Kse * 64) return;
+    const int q = idx >> 6, l = idx & 63, co = l & 15, kg = l >> 4, off = (Kse - Ks) / 2;
+    const int jp = q / Kse, i = q - jp * Kse - off, j = 2 * jp + (kg >> 1) - off;
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        uint32_t h2[2], l2[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int ci = 8 * (kg & 1) + 2 * w + s;
+            const bool in = co < Ca && ci < Ca && i >= 0 && i < Ks && j >= 0 && j < Ks;
+            const float v = in ? lk[(((size_t)co * Ca + ci) * Ks + i) * Ks + j] : 0.f;
+            const uint16_t h = dn_f32_to_bf16(v);
+            h2[s] = h;
+            l2[s] = dn_f32_to_bf16(v - __uint_as_float((uint32_t)h << 16));
+        }
+        hi[w] = h2[0] | (h2[1] << 16);
+        lo[w] = l2[0] | (l2[1] << 16);
+    }
+    u32x4 *dst = reinterpret_cast<u32x4 *>(wa) + (size_t)q * 128 + l;
+    dst[0] = u32x4{hi[0], hi[1], hi[2], hi[3]};
+    dst[64] = u32x4{lo[0], lo[1], lo[2], lo[3]};
+}
+
+template <int KS, int TH>
+__global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DenseParams p)
+{
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    constexpr int NA = 2 * TH;  // runs of 16 pixels in the tile: run nt = row nt / 2, columns 16 (nt % 2) ..
+    constexpr int NT = TH / 2;  // runs whose results a wavefront ends up with
+    constexpr int pad = (KS - 1) / 2, HR = TH + 2 * pad, HP = HR * kBfPitch;
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int H = p.H, W = p.W;
+    char *s_bytes = reinterpret_cast<char *>(dn_lds);
+    u32x4 *s_cells = reinterpret_cast<u32x4 *>(dn_lds);  // [2 halves][HR][kBfPitch] cells
+    float *s_dk = reinterpret_cast<float *>(s_cells + bf_aux_cell(KS, TH));
+    const size_t plane_px = (size_t)H * W;
+
+    // Blocks go to the chip's eight dies round robin; each die gets a contiguous eighth of the
+    // tiles, so that neighbouring tiles (shared halos) meet in one L2.
+    const unsigned nblk = gridDim.x, die = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const unsigned qd = nblk / kXcds, rem = nblk % kXcds;
+    const unsigned tile_id = die * qd + (die < rem ? die : rem) + slot;
+    const unsigned per_img = (unsigned)(p.tiles_x * p.tiles_y);
+    const unsigned n = tile_id / per_img, t_in = tile_id - n * per_img;
+    const int tyi = (int)(t_in / (unsigned)p.tiles_x), txi = (int)(t_in - (unsigned)tyi * p.tiles_x);
+    const int y0 = tyi * TH, x0 = txi * kDnTw;
+    const bf16d *xn = (const bf16d *)p.x + (size_t)n * p.C * plane_px;
+
+    // ---- the block's share of the pass-through copy (Eq. 4 lines 1 and 4): up to three rounds
+    // of 16 KiB are asked for at once, in front of the tile, and stored behind the tile's loads
+    // (copy_last_store): one trip to memory for both, while no other registers are live ----
+    constexpr int kCopyRounds = 3;
+    constexpr int kWalkGrains = 2;  // 16-byte accesses per thread and walk of the contraction
+    constexpr size_t kWalkCopy = (size_t)((KS + 1) / 2) * kWalkGrains * kDnThreads * 16;
+    const char *walk_src = reinterpret_cast<const char *>(p.wt);  // (a readable, aligned address for the clamped loads of a walk with nothing to copy)
+    char *walk_dst = nullptr;
+    size_t walk_len = 0;
+    u32x4 copy_v[4 * kCopyRounds] = {};
+    size_t copy_o0 = 0, copy_end = 0;
+    char *copy_dst = nullptr;
+    if (p.idt_len > 0) {
+        const char *src = (const char *)p.x + (size_t)n * p.img_bytes + p.idt_off;
+        char *dst = (char *)p.out + (size_t)n * p.img_bytes + p.idt_off;
+        const size_t begin0 = (size_t)t_in * p.copy_share < p.idt_len ? (size_t)t_in * p.copy_share : p.idt_len;
+        const size_t end = begin0 + p.copy_share < p.idt_len ? begin0 + p.copy_share : p.idt_len;
+        // (with vector accesses, the first kWalkCopy bytes of the share travel during the contraction, see there)
+        const size_t begin = p.copy_vec ? (begin0 + kWalkCopy < end ? begin0 + kWalkCopy : end) : begin0;
+        if (p.copy_vec && begin > begin0) walk_src = src + begin0, walk_dst = dst + begin0, walk_len = begin - begin0;
+        if (p.copy_vec) {
+            constexpr size_t kGroup = (size_t)4 * kCopyRounds * kDnThreads * 16;
+            for (size_t o0 = begin; o0 < end; o0 += kGroup) {
+                u32x4 v[4 * kCopyRounds];
+#pragma unroll
+                for (int u = 0; u < 4 * kCopyRounds; ++u) {
+                    const size_t o = o0 + ((size_t)u * kDnThreads + tid) * 16;
+                    v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (o + 16 <= end ? o : begin)));
+                }
+                if (o0 + kGroup >= end) {  // the last group (block-uniform)
+#pragma unroll
+                    for (int u = 0; u < 4 * kCopyRounds; ++u) copy_v[u] = v[u];
+                    copy_o0 = o0, copy_end = end, copy_dst = dst;
+                    break;
+                }
+#pragma unroll
+                for (int u = 0; u < 4 * kCopyRounds; ++u) {
+                    const size_t o = o0 + ((size_t)u * kDnThreads + tid) * 16;
+                    if (o + 16 <= end) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4 *>(dst + o));
+                }
+            }
+        } else {
+            for (size_t o = begin + (size_t)tid * 2; o < end; o += (size_t)kDnThreads * 2)
+                *reinterpret_cast<uint16_t *>(dst + o) = *reinterpret_cast<const uint16_t *>(src + o);
+        }
+    }
+    auto copy_last_store = [&]() {
+        if (copy_dst != nullptr) {
+#pragma unroll
+            for (int u = 0; u < 4 * kCopyRounds; ++u) {
+                const size_t o = copy_o0 + ((size_t)u * kDnThreads + tid) * 16;
+                if (o + 16 <= copy_end) __builtin_nontemporal_store(copy_v[u], reinterpret_cast<u32x4 *>(copy_dst + o));
+            }
+            copy_dst = nullptr;
+        }
+    };
+
+    // DK of this image goes to LDS beside the tile (asked for now, read after the contraction)
+    float dk_v = 0.f;
+    if (p.dk != nullptr && tid < 16 * 9) dk_v = p.dk[(size_t)n * p.Ca * 9 + (tid < p.Ca * 9 ? tid : 0)];
+
+    // ---- the zero-extended halo tile, pixel-major ----
+    if (p.fill_vec) {
+        // task = (half, piece of eight columns, row), lanes on consecutive rows; at most two per thread
+        constexpr int tasks = 2 * (kBfCols / 8) * HR;
+        u32x4 v[2][8];
+        bool in[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int task = k * kDnThreads + tid;
+            const int r = task % HR, rest = task / HR, pc = rest % (kBfCols / 8), h2 = rest / (kBfCols / 8);
+            const int gy = y0 - pad + r, gx = x0 - 8 + 8 * pc;
+            in[k] = task < tasks && gy >= 0 && gy < H && gx >= 0 && gx < W;
+            const size_t o = in[k] ? (size_t)gy * W + gx : 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int ch = 8 * h2 + e;
+                v[k][e] = *reinterpret_cast<const u32x4 *>(xn + (ch < p.Ca ? (size_t)ch * plane_px : 0) + o);
+            }
+        }
+        copy_last_store();
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int task = k * kDnThreads + tid;
+            const int r = task % HR, rest = task / HR, pc = rest % (kBfCols / 8), h2 = rest / (kBfCols / 8);
+            u32x4 *dst = s_cells + h2 * HP + r * kBfPitch + 8 * pc;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                u32x4 c0, c1;  // the cells of pixels 2 d and 2 d + 1
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const bool a_in = in[k] && 8 * h2 + 2 * w < p.Ca, b_in = in[k] && 8 * h2 + 2 * w + 1 < p.Ca;
+                    const uint32_t a = a_in ? v[k][2 * w][d] : 0u, b = b_in ? v[k][2 * w + 1][d] : 0u;
+                    c0[w] = (a & 0xffffu) | (b << 16);
+                    c1[w] = (a >> 16) | (b & 0xffff0000u);
+                }
+                if (task < tasks) {
+                    dst[2 * d] = c0;
+                    dst[2 * d + 1] = c1;
+                }
+            }
+        }
+    } else {
+        // any width and alignment: element by element
+        copy_last_store();
+        constexpr int total = 16 * HR * kBfCols;
+        for (int i0 = 0; i0 < total; i0 += 8 * kDnThreads) {
+            uint16_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = i0 + u * kDnThreads + tid;
+                const int ci = idx / (HR * kBfCols), r2 = idx - ci * (HR * kBfCols), r = r2 / kBfCols, c = r2 - r * kBfCols;
+                const int gy = y0 - pad + r, gx = x0 - 8 + c;
+                const bool ok = idx < total && ci < p.Ca && gy >= 0 && gy < H && gx >= 0 && gx < W;
+                const uint16_t raw = xn[ok ? (size_t)ci * plane_px + (size_t)gy * W + gx : 0].bits;
+                v[u] = ok ? raw : (uint16_t)0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = i0 + u * kDnThreads + tid;
+                const int ci = idx / (HR * kBfCols), r2 = idx - ci * (HR * kBfCols), r = r2 / kBfCols, c = r2 - r * kBfCols;
+                if (idx < total)
+                    *reinterpret_cast<uint16_t *>(s_bytes + (size_t)((ci >> 3) * HP + r * kBfPitch + c) * 16 + (ci & 7) * 2) = v[u];
+            }
+        }
+    }
+    if (tid < 16 * 9) s_dk[tid] = dk_v;
+    __syncthreads();
+
+    // ---- the contraction ----
+    f32x4 part[NA];
+#pragma unroll
+    for (int nt = 0; nt < NA; ++nt) part[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    {
+        constexpr int NJP = (KS + 1) / 2;                // pairs of tap columns
+        constexpr int kBase = KS / 4, kExtra = KS % 4;   // kernel rows per wavefront: kBase, one more for kExtra of the four
+        constexpr int MB = kBase + 1;                    // (KS is odd: kExtra > 0)
+        constexpr int NR = TH + MB - 1;                  // tile rows a block of MB kernel rows walks
+        const u32x4 *wa = reinterpret_cast<const u32x4 *>(p.wt) + lane;
+        // this wavefront's block of kernel rows for pair jp: rows i0 .. i0 + cnt - 1
+        auto rows_of = [&](int jp, int &i0, int &cnt) {
+            const int pos = (wave - jp) & 3;
+            i0 = pos * kBase + (pos < kExtra ? pos : kExtra);
+            cnt = kBase + (pos < kExtra ? 1 : 0);
+        };
+        auto fetch_a = [&](int jp, u32x4 (&a)[MB][2]) {
+            int i0, cnt;
+            rows_of(jp, i0, cnt);
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                int i = i0 + (m < cnt ? m : 0);
+                i = i < KS ? i : KS - 1;
+                a[m][0] = wa[(size_t)(jp * KS + i) * 128];
+                a[m][1] = wa[(size_t)(jp * KS + i) * 128 + 64];
+            }
+        };
+        auto mma = [&](const u32x4 &a, const u32x4 &b, f32x4 &c) {
+            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+        };
+        // a walk's piece of the pass-through copy: asked for at its start, behind the next
+        // pair's A operands (which are waited for first), stored at the end of the NEXT walk -
+        // a trip to memory takes longer than one walk
+        auto copy_ask = [&](int jp, u32x4 (&cv)[kWalkGrains]) {
+#pragma unroll
+            for (int g = 0; g < kWalkGrains; ++g) {
+                const size_t o = (((size_t)jp * kWalkGrains + g) * kDnThreads + tid) * 16;
+                cv[g] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(walk_src + (o + 16 <= walk_len ? o : 0)));
+            }
+        };
+        auto copy_put = [&](int jp, const u32x4 (&cv)[kWalkGrains]) {
+#pragma unroll
+            for (int g = 0; g < kWalkGrains; ++g) {
+                const size_t o = (((size_t)jp * kWalkGrains + g) * kDnThreads + tid) * 16;
+                if (jp >= 0 && o + 16 <= walk_len) __builtin_nontemporal_store(cv[g], reinterpret_cast<u32x4 *>(walk_dst + o));
+            }
+        };
+        auto walk = [&](int jp, const u32x4 (&a)[MB][2], u32x4 (&a_next)[MB][2], u32x4 (&cv)[kWalkGrains],
+                        const u32x4 (&cv_before)[kWalkGrains]) {
+            int i0, cnt;
+            rows_of(jp, i0, cnt);
+            fetch_a(jp + 1 < NJP ? jp + 1 : jp, a_next);
+            copy_ask(jp, cv);
+            const bool full = cnt == MB;  // wavefront-uniform
+            // this lane's B operand for tile row i0, half 0: its tap column's shift (the empty
+            // column reads the one before it), its half plane, its pixel
+            int j = 2 * jp + (kq >> 1);
+            j = j < KS ? j : KS - 1;
+            const char *bp = s_bytes + (size_t)((kq & 1) * HP + i0 * kBfPitch + j + 8 - pad + l16) * 16;
+            u32x4 b[2][2];
+            auto read_b = [&](int R, u32x4 (&bb)[2]) {
+                bb[0] = *reinterpret_cast<const u32x4 *>(bp + R * kBfPitch * 16);
+                bb[1] = *reinterpret_cast<const u32x4 *>(bp + R * kBfPitch * 16 + 256);
+            };
+            read_b(0, b[0]);
+#pragma unroll
+            for (int R = 0; R < NR; ++R) {
+                // tile row R + 1 (the last one serves the block's last kernel row only)
+                if (R + 1 < NR - 1) read_b(R + 1, b[(R + 1) & 1]);
+                if (R + 1 == NR - 1 && full) read_b(R + 1, b[(R + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int term = 0; term < 2; ++term)
+#pragma unroll
+                    for (int m = 0; m < MB - 1; ++m)
+                        if (R - m >= 0 && R - m < TH) {
+                            mma(a[m][term], b[R & 1][0], part[2 * (R - m)]);
+                            mma(a[m][term], b[R & 1][1], part[2 * (R - m) + 1]);
+                        }
+                if (R - (MB - 1) >= 0 && R - (MB - 1) < TH && full) {
+#pragma unroll
+                    for (int term = 0; term < 2; ++term) {
+                        mma(a[MB - 1][term], b[R & 1][0], part[2 * (R - (MB - 1))]);
+                        mma(a[MB - 1][term], b[R & 1][1], part[2 * (R - (MB - 1)) + 1]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            copy_put(jp - 1, cv_before);
+        };
+        u32x4 a0[MB][2], a1[MB][2], cv0[kWalkGrains] = {}, cv1[kWalkGrains] = {};
+        fetch_a(0, a0);
+#pragma unroll
+        for (int jp = 0; jp < NJP; jp += 2) {
+            walk(jp, a0, a1, cv0, cv1);
+            if (jp + 1 < NJP) walk(jp + 1, a1, a0, cv1, cv0);
+        }
+        copy_put(NJP - 1, (NJP - 1) % 2 == 0 ? cv0 : cv1);
+    }
+
+    // ---- DK's nine depth-wise taps for the runs this wavefront ends up with, from the same
+    // tile: lane l holds output channels 4 (l / 16) + r, r < 4, of pixel l % 16 ----
+    f32x4 acc[NT];
+#pragma unroll
+    for (int m = 0; m < NT; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (p.dk != nullptr) {
+        float d[4][9];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int k = 0; k < 9; ++k) d[r][k] = s_dk[(4 * kq + r) * 9 + k];
+#pragma unroll
+        for (int m = 0; m < NT; ++m) {
+            const int nt = wave * NT + m, rr = nt >> 1, c = 16 * (nt & 1);
+            const char *src = s_bytes + (size_t)((kq >> 1) * HP + (rr + pad - 1) * kBfPitch + c + l16 + 7) * 16 + 8 * (kq & 1);
+#pragma unroll
+            for (int di = 0; di < 3; ++di)
+#pragma unroll
+                for (int dj = 0; dj < 3; ++dj) {
+                    const u32x2 v = *reinterpret_cast<const u32x2 *>(src + (di * kBfPitch + dj) * 16);
+                    acc[m][0] = fmaf(d[0][di * 3 + dj], __uint_as_float(v[0] << 16), acc[m][0]);
+                    acc[m][1] = fmaf(d[1][di * 3 + dj], __uint_as_float(v[0] & 0xffff0000u), acc[m][1]);
+                    acc[m][2] = fmaf(d[2][di * 3 + dj], __uint_as_float(v[1] << 16), acc[m][2]);
+                    acc[m][3] = fmaf(d[3][di * 3 + dj], __uint_as_float(v[1] & 0xffff0000u), acc[m][3]);
+                }
+        }
+    }
+
+    // ---- the four wavefronts' partial results: run nt goes to wavefront nt / NT ----
+    {
+        constexpr int kPass = NA < 8 ? NA : 8;  // runs per pass: 32 KiB of LDS
+        f32x4 *s_red = reinterpret_cast<f32x4 *>(dn_lds);
+#pragma unroll
+        for (int p0 = 0; p0 < NA; p0 += kPass) {
+            __syncthreads();  // the tile (DK's taps) or the previous pass is no longer read
+#pragma unroll
+            for (int u = 0; u < kPass; ++u) s_red[((u * 4) + wave) * 64 + lane] = part[p0 + u];
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kPass; ++u) {
+                const int nt = p0 + u;
+                if (nt / NT == wave) {  // wavefront-uniform
+                    f32x4 sum = s_red[(u * 4 + 0) * 64 + lane];
+#pragma unroll
+                    for (int w = 1; w < 4; ++w) sum += s_red[(u * 4 + w) * 64 + lane];
+#pragma unroll
+                    for (int m = 0; m < NT; ++m)  // (a constant index: the accumulators stay in registers)
+                        if (m == nt % NT) acc[m] += sum;
+                }
+            }
+        }
+    }
+
+    // ---- store: one rounding to bf16 ----
+    bf16d *on = (bf16d *)p.out + (size_t)n * p.C * plane_px;
+#pragma unroll
+    for (int m = 0; m < NT; ++m) {
+        const int nt = wave * NT + m;
+        const int gy = y0 + (nt >> 1), gx = x0 + 16 * (nt & 1) + l16;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int co = 4 * kq + r;
+            if (co < p.Ca && gy < H && gx < W) dn_store(on + (size_t)co * plane_px + (size_t)gy * W + gx, acc[m][r]);
+        }
+    }
+}
+
+template <int KS, int TH>
+hipError_t launch_bf16_kt(const DenseParams &p, unsigned grid, hipStream_t s)
+{
+    const size_t lds = bf_lds_bytes(KS, TH);
+    static bool granted = false;
+    if (lds > 48 * 1024 && !granted) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dense_bf16_kernel<KS, TH>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        granted = true;
+    }
+    hipLaunchKernelGGL((dense_bf16_kernel<KS, TH>), dim3(grid), dim3(kDnThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+template <int TH>
+hipError_t launch_bf16(const DenseParams &p, unsigned grid, hipStream_t s)
+{
+    switch (p.Ks) {
+    case 3: return launch_bf16_kt<3, TH>(p, grid, s);
+    case 5: return launch_bf16_kt<5, TH>(p, grid, s);
+    case 7: return launch_bf16_kt<7, TH>(p, grid, s);
+    case 9: return launch_bf16_kt<9, TH>(p, grid, s);
+    case 11: return launch_bf16_kt<11, TH>(p, grid, s);
+    case 13: return launch_bf16_kt<13, TH>(p, grid, s);
+    case 15: return launch_bf16_kt<15, TH>(p, grid, s);
+    case 17: return launch_bf16_kt<17, TH>(p, grid, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 template <typename T, int CT, int TH>
 hipError_t launch_ct(const DenseParams &p, unsigned grid, size_t lds, hipStream_t s)
 {
@@ -394,9 +815,15 @@ hipError_t launch_t(const DenseParams &p, int ct, unsigned grid, size_t lds, hip
 
 }  // namespace
 
-__attribute__((visibility("hidden"))) hipError_t launch_dense_weights(const float *lk, int Ca, int Ks, float *wt, hipStream_t s)
+__attribute__((visibility("hidden"))) hipError_t launch_dense_weights(const float *lk, int Ca, int Ks, bool bf16, float *wt, hipStream_t s)
 {
     const int Kse = dense_effective_ks(Ks);
+    if (dense_on_bf16_mfma(Ca, bf16)) {
+        const int threads = (Kse + 1) / 2 * Kse * 64;
+        hipLaunchKernelGGL(dense_weights_bf16_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, lk, Ca, Ks, Kse,
+                           reinterpret_cast<uint32_t *>(wt));
+        return hipGetLastError();
+    }
     const size_t total = dense_weight_floats(Ca, Ks);
     if (total == 0) return hipSuccess;
     hipLaunchKernelGGL(dense_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, lk, Ca, Ks, Kse, wt, total);
@@ -430,6 +857,10 @@ __attribute__((visibility("hidden"))) hipError_t launch_dense(const DenseParams 
         size_t share = (p.idt_len + per_img - 1) / per_img;
         share = (share + grain - 1) / grain * grain;
         p.copy_share = share;
+    }
+    if (dense_on_bf16_mfma(p.Ca, bf16)) {
+        p.fill_vec = (p.W % 8 == 0) && ((uintptr_t)p.x % 16 == 0);
+        return th == 8 ? launch_bf16<8>(p, (unsigned)grid, s) : launch_bf16<4>(p, (unsigned)grid, s);
     }
     int hr, pitch, plane;
     dense_geom(p.Ks, th, hr, pitch, plane);

@@ -23,19 +23,26 @@ struct DenseParams {
     // set by launch_dense: division by the halo tile's width and by its rows x width as a
     // multiply-high and a shift (the tile fill locates every element with both)
     unsigned hc_mul, hc_shift, hp_mul, hp_shift;
+    // bf16 matrix path: whether the tile is fetched in 16-byte pieces
+    int fill_vec;
 };
 
 // the kernel size the device code walks: a 1 x 1 kernel is embedded in a 3 x 3 one
 inline int dense_effective_ks(int Ks) { return Ks < 3 ? 3 : Ks; }
 
-// floats the rearranged weights take: [CT chunks][Kse rows][Kse taps][CT][16 ci][16 co]
+// bf16 storage with up to 16 channels runs on the bf16 matrix instructions
+inline bool dense_on_bf16_mfma(int Ca, bool bf16) { return bf16 && Ca <= 16; }
+
+// floats the rearranged weights take: [CT chunks][Kse rows][Kse taps][CT][16 ci][16 co], or, for
+// the bf16 matrix path, [(Kse + 1) / 2 pairs of tap columns][Kse rows][hi, lo][64 lanes][8 bf16]
+// (the storage type is not known when a workspace is sized: the larger of the two)
 inline size_t dense_weight_floats(int Ca, int Ks)
 {
     const size_t ct = (size_t)(Ca + 15) / 16, kse = (size_t)dense_effective_ks(Ks);
-    return ct * kse * kse * ct * 256;
+    return ct == 1 ? kse * (kse + 1) * 256 : ct * kse * kse * ct * 256;
 }
 
-hipError_t launch_dense_weights(const float *lk, int Ca, int Ks, float *wt, hipStream_t s);
+hipError_t launch_dense_weights(const float *lk, int Ca, int Ks, bool bf16, float *wt, hipStream_t s);
 hipError_t launch_dense(const DenseParams &p, bool bf16, hipStream_t s);
 
 }  // namespace esc

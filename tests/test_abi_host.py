@@ -220,10 +220,10 @@ def test_binding_refuses_cpu_tensors(lib):
 
 # ---------------------------------------------------------------- compiled kernel variants
 
-def kernel_metadata():
-    """(Ks, RY, type letter, staged flavour) -> (private segment bytes, VGPRs, static LDS bytes)
-    of every forward_kernel variant in the built library, read from the code objects' notes.
-    The library holds one offload bundle per translation unit."""
+def kernel_notes():
+    """(mangled name, private segment bytes, VGPRs, static LDS bytes) of every kernel in the built
+    library, read from the code objects' notes.  The library holds one offload bundle per
+    translation unit."""
     import subprocess
     import tempfile
     tools = "/opt/rocm/llvm/bin"
@@ -231,7 +231,7 @@ def kernel_metadata():
     if not all(os.path.exists(t) for t in need):
         pytest.skip("LLVM binary tools not found")
     magic = b"__CLANG_OFFLOAD_BUNDLE__"
-    out = {}
+    out = []
     with tempfile.TemporaryDirectory() as tmp:
         fat = os.path.join(tmp, "fat.bin")
         subprocess.run([need[0], f"--dump-section=.hip_fatbin={fat}", binding.LIB_PATH, os.path.join(tmp, "copy.so")],
@@ -250,15 +250,24 @@ def kernel_metadata():
             notes = subprocess.run([need[2], "--notes", dev], check=True, capture_output=True, text=True).stdout
             for block in notes.split("- .agpr_count:")[1:]:
                 name = re.search(r"\.name:\s*(\S+)", block).group(1)
-                m = re.search(r"forward_kernelILi(\d+)ELi(\d+)E(\w+?)Lb([01])E", name)
-                if not m:
-                    continue
                 scratch = int(re.search(r"\.private_segment_fixed_size:\s*(\d+)", block).group(1))
                 vgprs = int(re.search(r"\.vgpr_count:\s*(\d+)", block).group(1))
                 lds = int(re.search(r"\.group_segment_fixed_size:\s*(\d+)", block).group(1))
-                key = (int(m.group(1)), int(m.group(2)), "f" if m.group(3) == "f" else "b", int(m.group(4)))
-                assert key not in out, key
-                out[key] = (scratch, vgprs, lds)
+                out.append((name, scratch, vgprs, lds))
+    return out
+
+
+def kernel_metadata():
+    """(Ks, RY, type letter, staged flavour) -> (private segment bytes, VGPRs, static LDS bytes)
+    of every forward_kernel variant in the built library."""
+    out = {}
+    for name, scratch, vgprs, lds in kernel_notes():
+        m = re.search(r"forward_kernelILi(\d+)ELi(\d+)E(\w+?)Lb([01])E", name)
+        if not m:
+            continue
+        key = (int(m.group(1)), int(m.group(2)), "f" if m.group(3) == "f" else "b", int(m.group(4)))
+        assert key not in out, key
+        out[key] = (scratch, vgprs, lds)
     return out
 
 
@@ -284,3 +293,16 @@ def test_kernel_variants_fit_four_blocks_per_cu_without_scratch(lib):
             assert scratch == 0, (ks, ry, t, st, scratch)
         else:
             assert scratch <= 64, (ks, ry, t, st, scratch)
+
+
+def test_dense_bf16_kernels_fit_two_blocks_per_cu_without_scratch(lib):
+    # dense_bf16_kernel<Ks, TH>: one instantiation per odd kernel size 3 ... 17 and tile height;
+    # two blocks per compute unit (256 registers a lane), nothing in the private segment
+    meta = {}
+    for name, scratch, vgprs, lds in kernel_notes():
+        m = re.search(r"dense_bf16_kernelILi(\d+)ELi(\d+)EE", name)
+        if m:
+            meta[(int(m.group(1)), int(m.group(2)))] = (scratch, vgprs)
+    assert set(meta) == {(ks, th) for ks in range(3, 18, 2) for th in (4, 8)}, sorted(meta)
+    for key, (scratch, vgprs) in sorted(meta.items()):
+        assert scratch == 0 and vgprs <= 256, (key, scratch, vgprs)

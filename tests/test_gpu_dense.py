@@ -88,6 +88,47 @@ def test_no_attention_channels_is_a_pure_copy():
     assert np.array_equal(got.view(np.uint8), wl.x.view(np.uint8))
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_dense_base_pointers_off_the_vector_alignment(oracle, dtype):
+    # W % 8 == 0, but x and out start one element past a 16-byte boundary (views into larger
+    # buffers): the tile fetch and the pass-through copy must take their element-wise forms,
+    # and nothing outside the view may be written.  Then the aligned call on the same data (the
+    # 16-byte tile fetch of the bf16 matrix path) must give the same attention slice bit for bit.
+    wl = wk.make_random(940, 2, 19, 21, 72, 16, 7, dtype=dtype, x_mean=0.4)
+    lk = dense_kernel(941, 16, 7)
+    print(f"[case] dense, unaligned base, {wl.name}", flush=True)
+    ref, _, _ = oracle.convattn_dense_forward(wl.x, wl.Ca, lk, wl.dtype, hidden=wl.hidden, w_up=wl.w_up, b_up=wl.b_up,
+                                              w_down=wl.w_down, b_down=wl.b_down, want_out=False)
+    aligned = run_dense(wl, lk)
+    x_al = gu.to_dev_x(wl.x, wl.dtype)
+    numel = x_al.numel()
+    for x_shift, out_shift in ((1, 1), (1, 0), (0, 3)):
+        xb = torch.zeros(numel + 8, dtype=x_al.dtype, device="cuda")
+        ob = torch.full((numel + 8,), float("nan"), dtype=x_al.dtype, device="cuda")
+        x = xb[x_shift:x_shift + numel].view(x_al.shape)
+        x.copy_(x_al)
+        out = ob[out_shift:out_shift + numel].view(x_al.shape)
+        ws = binding.new_dense_workspace(wl.N, wl.Ca, wl.H, wl.W, 7)
+        binding.convattn_dense_forward(x, wl.Ca, gu.dev(lk), ws, gen=gu.gen_params(wl), out=out)
+        assert binding.workspace_errors(ws) == 0
+        got = gu.out_to_np(out, wl.dtype)
+        gu.assert_identity_bits(got, wl, "dense, unaligned base")
+        gu.assert_att_close(gu.att_as_f64(got, wl), ref, wl.dtype, "dense, unaligned base")
+        assert np.array_equal(got.view(np.uint8), aligned.view(np.uint8))
+        edge = ob.view(torch.int16 if dtype == BF16 else torch.int32)
+        nan_bits = torch.full((1,), float("nan"), dtype=x_al.dtype).view(edge.dtype).item()
+        assert all(int(v) == nan_bits for v in edge[:out_shift].tolist() + edge[out_shift + numel:].tolist())
+
+
+@pytest.mark.parametrize("Ks", [1, 3, 5, 7, 9, 11, 15, 17])
+def test_dense_bf16_matrix_path_every_kernel_size_on_eight_row_tiles(oracle, Ks):
+    # bf16 storage with 16 channels runs one compiled kernel per kernel size and tile height:
+    # 44 images of 43 x 64 give 8-row tiles (enough blocks to fill the chip twice), ragged at the
+    # bottom edge; the small shapes above take the 4-row tiles, the benchmark shapes Ks = 13.
+    wl = wk.make_random(950 + Ks, 44, 17, 43, 64, 16, Ks, dtype=BF16, x_mean=0.2)
+    check_dense(wl, dense_kernel(951 + Ks, 16, Ks), oracle)
+
+
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
 def test_dense_benchmark_shapes_full_size(oracle, idx):
     wl = wk.make_config(idx)
