@@ -1020,18 +1020,21 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
     const int c = wa.c, txi = wa.txi, tyi = wa.tyi, x0 = wa.x0, y0 = wa.y0;
     const T *xp = (const T *)p->x + wa.plane_off;
 
-    // this channel's weights, fetched together with the tile
+    // this channel's weights, asked for right behind the tile's loads (results return in order:
+    // in front of them, the tile would wait for the weights as well)
     constexpr int KW = (KS * KS + kThreads - 1) / kThreads;
     const float *lkc = p->lk + (size_t)c * p->lk_cstride;
     // (thread indices are taken afresh in every phase, so that nothing derived from them
     // is computed once per kernel and then held in registers through all items)
     const int tid1 = opaque_tid();
     float wreg[KW];
+    auto load_weights = [&]() {
 #pragma unroll
-    for (int m = 0; m < KW; ++m) {
-        const int idx = m * kThreads + tid1;
-        wreg[m] = idx < KS * KS ? lkc[idx] : 0.f;
-    }
+        for (int m = 0; m < KW; ++m) {
+            const int idx = m * kThreads + tid1;
+            wreg[m] = idx < KS * KS ? lkc[idx] : 0.f;
+        }
+    };
 
     // Carried copy (Eq. 4 lines 1 and 4): this item's share of the image's pass-through range
     // - up to kCarryGrains grains of 16 bytes per thread - is asked for once the tile has
@@ -1094,7 +1097,8 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                 raw[k] = u32x4{0u, 0u, 0u, 0u};
                 if (in) raw[k] = *reinterpret_cast<const u32x4 *>(xp + (size_t)gy * W + gx);
             }
-            if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
+            load_weights();
+        if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
 #pragma unroll
             for (int k = 0; k < K; ++k) {
                 const int q = k * kThreads + tid1;
@@ -1129,6 +1133,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                 if (in) load4(xp + (size_t)gy * W + gx, v[k]);
             }
         }
+        load_weights();
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
@@ -1161,6 +1166,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
                 tile_h[2 * MG::word(r, cc >> 1) + (cc & 1)] = v;
             }
         }
+        load_weights();
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
     } else {
         for (int idx = tid1; idx < HR * HC; idx += kThreads) {
@@ -1170,6 +1176,7 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
             if (gy >= 0 && gy < H && gx >= 0 && gx < W) v = to_f32(xp[(size_t)gy * W + gx]);
             tile[r * PITCH + cc] = v;
         }
+        load_weights();
         if (p->pool_mode != kPoolNone || ctx.last_item) need_tag(p, ctx);
     }
 #pragma unroll
