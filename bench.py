@@ -214,23 +214,23 @@ def dense_roofline_of(wl, sec):
 
 def backward_roofline_of(wl, sec):
     """The backward call: x and grad_out read once, grad_x written once (3 tensors); two passes of
-    2 Ks^2 flops per attention pixel on the vector units (the correlation and the input gradient)."""
+    2 Ks^2 flops per attention pixel: the correlation (on the bf16 matrix cores for Ks <= 15 - fp32
+    values as three exact bf16 terms each, nine instructions per product block, which the algorithmic
+    count does not include - else on the vector units) and the input gradient (the forward kernel: the
+    vector units, or the bf16 matrix cores where the forward's taps run there)."""
     P = wl.N * wl.H * wl.W
     b_alg = 3.0 * P * wl.C * wl.elem_bytes
     f_alg = 4.0 * wl.Ks * wl.Ks * P * wl.Ca
-    r = roofline_of(wl, sec)
-    # (the input gradient's half runs on the bf16 matrix cores where the forward's taps do: its time
-    # at that peak is negligible, and the correlation's half stays on the fp32 vector units)
-    f_vec = f_alg / 2.0 if taps_on_matrix_cores(wl) else f_alg
-    t_hbm, t_alu = b_alg / (HBM_PEAK_GBS * 1e9), f_vec / (FP32_VECTOR_PEAK_TFLOPS * 1e12)
-    if t_hbm >= t_alu:
-        out = {"bound": "hbm", "achieved": b_alg / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    else:
-        out = {"bound": "alu", "achieved": f_vec / sec / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s"}
-    out["frac"] = out["achieved"] / out["peak"]
-    out.update({"algorithmic_bytes": b_alg, "algorithmic_flops": f_alg, "hbm_gbps": b_alg / sec / 1e9,
-                "alu_tflops": f_alg / sec / 1e12})
-    return out
+    f_vec = (0.0 if wl.Ks <= 15 else f_alg / 2.0) + (0.0 if taps_on_matrix_cores(wl) else f_alg / 2.0)
+    f_mat = f_alg - f_vec
+    t = {"hbm": b_alg / (HBM_PEAK_GBS * 1e9), "alu": f_vec / (FP32_VECTOR_PEAK_TFLOPS * 1e12),
+         "mfma": f_mat / (BF16_MFMA_PEAK_TFLOPS * 1e12)}
+    bound = max(t, key=t.get)
+    ach = {"hbm": b_alg / sec / 1e9, "alu": f_vec / sec / 1e12, "mfma": f_mat / sec / 1e12}[bound]
+    peak = {"hbm": HBM_PEAK_GBS, "alu": FP32_VECTOR_PEAK_TFLOPS, "mfma": BF16_MFMA_PEAK_TFLOPS}[bound]
+    return {"bound": bound, "achieved": ach, "peak": peak, "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+            "frac": ach / peak, "algorithmic_bytes": b_alg, "algorithmic_flops": f_alg, "hbm_gbps": b_alg / sec / 1e9,
+            "alu_tflops": f_vec / sec / 1e12, "mfma_tflops": f_mat / sec / 1e12}
 
 
 class Runner:
@@ -415,7 +415,7 @@ def main():
     roof.update({
         "kernel": (f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)"
                    if fused is None and not args.dense and not args.backward else
-                   "corr_kernel (grad_out x correlation), sums, estimator kernels, forward_kernel on grad_out with flipped kernels, GAP term"
+                   "corr_mfma_kernel (grad_out x correlation on the matrix cores), sums, estimator kernels, forward_kernel on grad_out with flipped kernels and the GAP term"
                    if args.backward else
                    "dense_kernel (implicit GEMM on the matrix cores, DK taps, pass-through share) after the estimator launch and the weight rearrangement"
                    if args.dense else

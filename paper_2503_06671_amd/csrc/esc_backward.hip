@@ -9,9 +9,10 @@
 //   dx[n,c]     = go[n,c] (*) flip(LK[c] + ZP(DK[n,c])) + dg[n,c] / (H W)     (c < C_a; dx = go elsewhere)
 //
 // The input gradient's convolution is the forward kernel itself, run on grad_out with the
-// flipped kernels (esc_api.hip); this file holds what is new: the correlation S (the same
-// arithmetic as the forward's tap loop, turned round: 2 Ks^2 flops per pixel into Ks^2
-// sums) and the small estimator kernels; the GAP term of dx is a constant per plane that the
+// flipped kernels (esc_api.hip); this file holds what is new: the correlation S - windows up
+// to 15 x 15 as Toeplitz products on the matrix cores (corr_mfma_kernel), larger ones with
+// the forward's vector tap loop turned round (corr_kernel: 2 Ks^2 flops per pixel into Ks^2
+// sums) - and the small estimator kernels; the GAP term of dx is a constant per plane that the
 // input gradient's launch adds at its stores.  Every sum has a fixed order
 // (per-tile partial sums in the workspace, then one thread per result), so results do not
 // depend on scheduling.
@@ -198,6 +199,264 @@ __global__ __launch_bounds__(kBwThreads) void corr_kernel(const BackwardParams p
         }
         dst[o] = s;
     }
+}
+
+// ---------------------------------------------------------------------------
+// S per tile for windows up to 15 x 15, on the matrix cores.  For one row y of grad_out's
+// tile the sums over x are a product of two 16 x K matrices:
+//   S[i][j] += sum_c  X_y[i][c] * G_y[c][j],   X_y[i][c] = xz[y + i][c]  (rows of x's halo tile),
+//                                              G_y[c][j] = go[y][c - j]  (a Toeplitz matrix of the row)
+// with K = the halo tile's columns, 32 per v_mfma_f32_16x16x32_bf16: 3 instructions per tile
+// row, 96 per tile, against 5400 vector multiply-adds per thread in corr_kernel.  With bf16
+// storage the stored values are the operands (products exact, fp32 accumulation).  fp32 values
+// are split exactly into three bf16 terms each (8 + 8 + 8 mantissa bits, by truncation), kept
+// as three tiles, and all nine products of terms are accumulated - every product is still
+// exact, and nine times 96 instructions are still a fifth of the vector loop's time.
+// A operand: lane (i, kg) reads 16 bytes of halo row y + i - the halo tile is laid out from the
+// aligned column x0 - 8, so every read is aligned.  B operand: lane (j, kg) wants eight
+// consecutive values of the row starting j elements to the left - a start that is odd for
+// every other lane.  grad_out's rows are therefore kept twice, zero-extended: as they are and
+// moved by one element; a lane reads four whole words from the copy of its parity.  The four
+// wavefronts take every fourth row and add their results through LDS; the sum of x (for the
+// GAP) comes from the halo tile's loads.  Same partial sums, same layout as corr_kernel.
+// ---------------------------------------------------------------------------
+constexpr int kCmXP = 104;  // halo tile: elements per row (96 columns are read; 13 x 16 bytes: rows fall on different banks)
+constexpr int kCmXR = 48;   // halo tile rows (rows up to 31 + 15 are read; those beyond the window feed discarded results)
+constexpr int kCmGP = 112;  // elements per zero-extended row of grad_out
+constexpr size_t kCmG0 = (size_t)kCmXR * kCmXP * 2, kCmG1 = kCmG0 + (size_t)kCorrTileH * kCmGP * 2 + 64;
+constexpr size_t kCmLds = kCmG1 + (size_t)kCorrTileH * kCmGP * 2;  // per term
+
+// eight consecutive bf16 values to row[q ...]: whole words where the parity of q allows
+template <bool EVEN>
+__device__ __forceinline__ void cm_put8(uint16_t *row, int q, const uint16_t (&v)[8])
+{
+    if (EVEN) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) *reinterpret_cast<uint32_t *>(row + q + 2 * d) = (uint32_t)v[2 * d] | ((uint32_t)v[2 * d + 1] << 16);
+    } else {
+        row[q] = v[0];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) *reinterpret_cast<uint32_t *>(row + q + 1 + 2 * d) = (uint32_t)v[2 * d + 1] | ((uint32_t)v[2 * d + 2] << 16);
+        row[q + 7] = v[7];
+    }
+}
+
+template <typename T, int KC>
+__global__ __launch_bounds__(kBwThreads) void corr_mfma_kernel(const BackwardParams p)
+{
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    static_assert(KC % 2 == 1 && KC >= 3 && KC <= 15, "one 16 x 16 block of sums");
+    constexpr bool kF32 = std::is_same<T, float>::value;
+    constexpr int NT = kF32 ? 3 : 1;          // bf16 terms per value
+    constexpr int P = (KC - 1) / 2;
+    constexpr int HRU = kCorrTileH + KC - 1;  // halo rows the window reaches
+    constexpr int GOFF = P + 8;               // element of a zero-extended row that holds the tile's column 0
+    char *lds = reinterpret_cast<char *>(bw_lds);
+    // term t: halo tile [kCmXR][kCmXP] (column c = image column x0 - 8 + c), then grad_out's rows
+    // [32][kCmGP] (element q = column q - GOFF) and the same moved by one (element q = column q + 1 - GOFF)
+    auto xs = [&](int t) { return reinterpret_cast<uint16_t *>(lds + t * kCmLds); };
+    auto g0 = [&](int t) { return reinterpret_cast<uint16_t *>(lds + t * kCmLds + kCmG0); };
+    auto g1 = [&](int t) { return reinterpret_cast<uint16_t *>(lds + t * kCmLds + kCmG1); };
+
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int H = p.H, W = p.W;
+    const int tiles_x = (W + kCorrTileW - 1) / kCorrTileW;
+    const int tiles = corr_tiles(H, W);
+    const unsigned nc = blockIdx.x / (unsigned)tiles, tile = blockIdx.x - nc * (unsigned)tiles;
+    const unsigned n = nc / (unsigned)p.Ca, c = nc - n * (unsigned)p.Ca;
+    const int ty0 = (int)(tile / (unsigned)tiles_x) * kCorrTileH, tx0 = (int)(tile % (unsigned)tiles_x) * kCorrTileW;
+    const size_t plane = ((size_t)n * p.C + c) * (size_t)H * W;
+    const T *xp = (const T *)p.x + plane, *gp = (const T *)p.go + plane;
+
+    // a value as NT bf16 terms (fp32: the top eight mantissa bits, the next eight, the rest - exact)
+    auto split = [](float v, uint16_t (&t)[3]) {
+        const uint32_t hb = __float_as_uint(v) & 0xffff0000u;
+        const float r1 = v - __uint_as_float(hb);
+        const uint32_t mb = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(mb);
+        t[0] = (uint16_t)(hb >> 16), t[1] = (uint16_t)(mb >> 16), t[2] = (uint16_t)(__float_as_uint(r2) >> 16);
+    };
+    // eight neighbouring values (16 or 32 bytes of memory) at e, or zeros; their sum for the GAP
+    auto fetch8 = [](const T *e, bool in, u32x4 (&raw)[kF32 ? 2 : 1]) {
+        raw[0] = *reinterpret_cast<const u32x4 *>(e);
+        if (kF32) raw[kF32 ? 1 : 0] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(e) + 16);
+        if (!in)
+            for (int k = 0; k < (kF32 ? 2 : 1); ++k) raw[k] = u32x4{0u, 0u, 0u, 0u};
+    };
+    auto terms8 = [&](const u32x4 (&raw)[kF32 ? 2 : 1], uint16_t (&v)[NT][8], float &sum) {
+        sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (kF32) {
+                uint16_t t3[3];
+                const float f = __uint_as_float(raw[kF32 ? e >> 2 : 0][e & 3]);
+                split(f, t3);
+#pragma unroll
+                for (int t = 0; t < NT; ++t) v[t][e] = t3[t];
+                sum += f;
+            } else {
+                v[0][e] = (uint16_t)(raw[0][e >> 1] >> (16 * (e & 1)));
+                sum += __uint_as_float((uint32_t)v[0][e] << 16);
+            }
+        }
+    };
+
+    float sx = 0.f;
+    if (p.corr_vec) {
+        // whole pieces of eight columns, each entirely inside or outside the image; the loads
+        // travel while the LDS is cleared
+        constexpr int XT = HRU * 10, XK = (XT + kBwThreads - 1) / kBwThreads;
+        u32x4 xv[XK][kF32 ? 2 : 1], gv[kF32 ? 2 : 1];
+#pragma unroll
+        for (int k = 0; k < XK; ++k) {
+            const int t = k * kBwThreads + tid, r = t / 10, pc = t - r * 10;
+            const int gy = ty0 - P + r, gx = tx0 - 8 + 8 * pc;
+            const bool in = t < XT && gy >= 0 && gy < H && gx >= 0 && gx < W;
+            fetch8(xp + (in ? (size_t)gy * W + gx : 0), in, xv[k]);
+        }
+        {
+            const int r = tid >> 3, pc = tid & 7;
+            const int gy = ty0 + r, gx = tx0 + 8 * pc;
+            const bool in = gy < H && gx < W;
+            fetch8(gp + (in ? (size_t)gy * W + gx : 0), in, gv);
+        }
+        for (int o = tid; o < (int)(NT * kCmLds / 16); o += kBwThreads) reinterpret_cast<u32x4 *>(lds)[o] = u32x4{0u, 0u, 0u, 0u};
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < XK; ++k) {
+            const int t = k * kBwThreads + tid, r = t / 10, pc = t - r * 10;
+            uint16_t v[NT][8];
+            float sum;
+            terms8(xv[k], v, sum);
+            if (t < XT) {
+#pragma unroll
+                for (int tt = 0; tt < NT; ++tt) cm_put8<true>(xs(tt) + r * kCmXP, 8 * pc, v[tt]);
+                // the tile's own pixels, for the GAP
+                if (r >= P && r < P + kCorrTileH && pc >= 1 && pc <= 8) sx += sum;
+            }
+        }
+        {
+            const int r = tid >> 3, pc = tid & 7;
+            uint16_t v[NT][8];
+            float sum;
+            terms8(gv, v, sum);
+#pragma unroll
+            for (int tt = 0; tt < NT; ++tt) {
+                cm_put8<GOFF % 2 == 0>(g0(tt) + r * kCmGP, GOFF + 8 * pc, v[tt]);
+                cm_put8<GOFF % 2 != 0>(g1(tt) + r * kCmGP, GOFF + 8 * pc - 1, v[tt]);
+            }
+        }
+    } else {
+        for (int o = tid; o < (int)(NT * kCmLds / 16); o += kBwThreads) reinterpret_cast<u32x4 *>(lds)[o] = u32x4{0u, 0u, 0u, 0u};
+        __syncthreads();
+        for (int t = tid; t < HRU * 80; t += kBwThreads) {
+            const int r = t / 80, cc = t - r * 80;
+            const int gy = ty0 - P + r, gx = tx0 - 8 + cc;
+            if (gy >= 0 && gy < H && gx >= 0 && gx < W) {
+                const float f = bw_load(xp + (size_t)gy * W + gx);
+                uint16_t t3[3];
+                split(f, t3);
+#pragma unroll
+                for (int tt = 0; tt < NT; ++tt) xs(tt)[r * kCmXP + cc] = t3[tt];
+                if (r >= P && r < P + kCorrTileH && cc >= 8 && cc < 8 + kCorrTileW) sx += f;
+            }
+        }
+        for (int t = tid; t < kCorrTileH * kCorrTileW; t += kBwThreads) {
+            const int r = t >> 6, cc = t & 63;
+            const int gy = ty0 + r, gx = tx0 + cc;
+            if (gy < H && gx < W) {
+                uint16_t t3[3];
+                split(bw_load(gp + (size_t)gy * W + gx), t3);
+#pragma unroll
+                for (int tt = 0; tt < NT; ++tt) {
+                    g0(tt)[r * kCmGP + GOFF + cc] = t3[tt];
+                    g1(tt)[r * kCmGP + GOFF + cc - 1] = t3[tt];
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- this wavefront's rows of the tile: y = wave, wave + 4, ... ----
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int jc = l16 < KC ? l16 : KC - 1;  // (columns beyond the window repeat its last one; their sums are dropped)
+    const size_t gsel = (jc & 1) ? kCmG1 : kCmG0;
+    const int o0 = 8 * kg - jc + 2 * P - (jc & 1);  // even: the lane's first element in its copy, for block 0
+    f32x4 acc[3];
+#pragma unroll
+    for (int b = 0; b < 3; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < kCorrTileH / 4; ++t) {
+        const int y = wave + 4 * t;
+        u32x4 a[NT][3], bv[NT][3];
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                a[tt][b] = *reinterpret_cast<const u32x4 *>(xs(tt) + (y + l16) * kCmXP + 32 * b + 8 * kg);
+                __builtin_memcpy(&bv[tt][b],
+                                 reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint16_t *>(lds + tt * kCmLds + gsel) + y * kCmGP + o0 + 32 * b),
+                                 16);
+            }
+        // (small terms first; the three column blocks' chains take turns)
+#pragma unroll
+        for (int ta = NT - 1; ta >= 0; --ta)
+#pragma unroll
+            for (int tb = NT - 1; tb >= 0; --tb)
+#pragma unroll
+                for (int b = 0; b < 3; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ta][b]),
+                                                                     __builtin_bit_cast(bf16x8, bv[tb][b]), acc[b], 0, 0, 0);
+    }
+    const f32x4 tot = (acc[0] + acc[1]) + acc[2];
+    const float sxr = row16_sum(sx);
+    __syncthreads();  // the tiles are no longer read: their LDS takes the wavefronts' results
+    float *red = bw_lds;              // [4 wavefronts][16 i][16 j]
+    float *sxs = bw_lds + 4 * 256;    // [16 rows of lanes]
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave * 256 + (4 * kg + r) * 16 + l16] = tot[r];
+    if (l16 == 15) sxs[tid >> 4] = sxr;
+    __syncthreads();
+    float *dst = p.partial + ((size_t)nc * tiles + tile) * (KC * KC + 1);
+    for (int o = tid; o < KC * KC + 1; o += kBwThreads) {
+        float s2 = 0.f;
+        if (o == KC * KC) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) s2 += sxs[k];
+        } else {
+            const int i = o / KC, j = o - i * KC;
+            s2 = ((red[i * 16 + j] + red[256 + i * 16 + j]) + red[512 + i * 16 + j]) + red[768 + i * 16 + j];
+        }
+        dst[o] = s2;
+    }
+}
+
+template <typename T, int KC>
+hipError_t launch_corr_mfma(const BackwardParams &p, unsigned grid, hipStream_t s)
+{
+    constexpr size_t lds = (std::is_same<T, float>::value ? 3 : 1) * kCmLds;
+    static bool granted = false;
+    if (lds > 48 * 1024 && !granted) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&corr_mfma_kernel<T, KC>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        granted = true;
+    }
+    hipLaunchKernelGGL((corr_mfma_kernel<T, KC>), dim3(grid), dim3(kBwThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_corr_mfma_kc(const BackwardParams &p, int kc, unsigned grid, hipStream_t s)
+{
+    switch (kc) {
+#define ESC_KC(K) case K: return launch_corr_mfma<T, K>(p, grid, s);
+        ESC_KC(3) ESC_KC(5) ESC_KC(7) ESC_KC(9) ESC_KC(11) ESC_KC(13) ESC_KC(15)
+#undef ESC_KC
+    }
+    return hipErrorInvalidValue;
 }
 
 // One row of 16 lanes per result: grad_lk (sums over images and tiles; over channels too for
@@ -418,7 +677,14 @@ __attribute__((visibility("hidden"))) hipError_t launch_backward_sums(const Back
     const int kc = corr_window(p.Ks), tiles = corr_tiles(p.H, p.W);
     const size_t grid = (size_t)p.N * p.Ca * tiles;
     if (grid >= ((size_t)1 << 31)) return hipErrorInvalidValue;
-    hipError_t e = bf16 ? launch_corr_kc<bf16b>(p, kc, (unsigned)grid, s) : launch_corr_kc<float>(p, kc, (unsigned)grid, s);
+    hipError_t e;
+    if (kc <= 15) {  // one 16 x 16 block of sums: the matrix cores
+        BackwardParams q = p;
+        q.corr_vec = (p.W % 8 == 0) && ((uintptr_t)p.x % 16 == 0) && ((uintptr_t)p.go % 16 == 0);
+        e = bf16 ? launch_corr_mfma_kc<bf16b>(q, kc, (unsigned)grid, s) : launch_corr_mfma_kc<float>(q, kc, (unsigned)grid, s);
+    } else {
+        e = bf16 ? launch_corr_kc<bf16b>(p, kc, (unsigned)grid, s) : launch_corr_kc<float>(p, kc, (unsigned)grid, s);
+    }
     if (e != hipSuccess) return e;
     const size_t results = (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks + (size_t)p.N * p.Ca * 10;
     hipLaunchKernelGGL(sums_kernel, dim3((unsigned)((results * 16 + 255) / 256)), dim3(256), 0, s, p, kc, tiles);

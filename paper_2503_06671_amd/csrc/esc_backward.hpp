@@ -41,6 +41,7 @@ struct BackwardParams {
     // caller's gradient buffers (any may be nullptr)
     float *grad_lk, *grad_dk, *grad_w_down, *grad_b_down, *grad_w_up, *grad_b_up;
     int accumulate;          // parameter gradients are added to what the buffers hold
+    int corr_vec;            // set by launch_backward_sums: the correlation fetches its tiles in 16-byte pieces
 };
 
 // correlation of grad_out with x per tile, then the sums over tiles (and images): grad_lk, ddk, g

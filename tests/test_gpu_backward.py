@@ -75,6 +75,14 @@ def test_backward_every_kernel_size(oracle, dtype, Ks):
     check_backward(wl, oracle, 1101 + Ks)
 
 
+@pytest.mark.parametrize("Ks", [1, 3, 5, 7, 9, 11, 13, 15, 17])
+def test_backward_bf16_rows_of_whole_pieces(oracle, Ks):
+    # bf16 storage, W % 8 == 0: the correlation on the matrix cores (windows up to 15 x 15) fetches
+    # its tiles in 16-byte pieces - three column tiles, two row tiles, ragged at both edges
+    wl = wk.make_random(1150 + Ks, 2, 6, 45, 136, 4, Ks, dtype=BF16, x_mean=0.4)
+    check_backward(wl, oracle, 1151 + Ks)
+
+
 @pytest.mark.parametrize("N,C,H,W,Ca,Ks,hidden,bias,dtype", [
     (2, 20, 40, 72, 16, 13, 8, True, F32),     # the paper's estimator (two layers, GELU)
     (3, 8, 9, 11, 4, 5, 4, False, BF16),       # odd planes
