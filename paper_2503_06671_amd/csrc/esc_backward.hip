@@ -541,7 +541,7 @@ __device__ __forceinline__ float gelu_grad_f(float v)
 // multiply-adds per image.
 __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const BackwardParams p)
 {
-    __shared__ float s_g[256], s_u[256], s_t[256], s_dt[256], s_du[256], s_dd[9 * 256];
+    __shared__ float s_g[256], s_u[256], s_t[256], s_dt[256], s_du[256], s_dd[9 * 256], s_part[kBwThreads];
     const int n = (int)blockIdx.x, tid = (int)threadIdx.x;
     const int Ca = p.Ca, hidden = p.hidden, K = hidden > 0 ? hidden : Ca;
     const float hw = (float)((double)p.H * (double)p.W);
@@ -576,11 +576,30 @@ __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const Backw
         const int c = o / 9, r = o - 9 * c;
         p.dkf[((size_t)n * Ca + c) * 9 + (8 - r)] = s;
     }
-    for (int k = tid; k < K; k += kBwThreads) {  // dL/dt = w_up^T dd
+    // dL/dt = w_up^T dd: the rows o are dealt to the block's groups of K threads (group g takes
+    // rows g, g + groups, ...), whose partial sums are then added in group order - a chain of
+    // 9 C_a dependent loads per thread otherwise
+    if (K <= kBwThreads / 2) {
+        const int groups = kBwThreads / K, g = tid / K, k = tid - g * K;
         float s = 0.f;
+        if (g < groups) {
+#pragma unroll 4
+            for (int o = g; o < 9 * Ca; o += groups) s = fmaf(p.w_up[(size_t)o * K + k], s_dd[o], s);
+            s_part[g * K + k] = s;
+        }
+        __syncthreads();
+        if (tid < K) {
+            float t = 0.f;
+            for (int q = 0; q < groups; ++q) t += s_part[q * K + tid];
+            s_dt[tid] = t;
+        }
+    } else {
+        for (int k = tid; k < K; k += kBwThreads) {
+            float s = 0.f;
 #pragma unroll 8
-        for (int o = 0; o < 9 * Ca; ++o) s = fmaf(p.w_up[(size_t)o * K + k], s_dd[o], s);
-        s_dt[k] = s;
+            for (int o = 0; o < 9 * Ca; ++o) s = fmaf(p.w_up[(size_t)o * K + k], s_dd[o], s);
+            s_dt[k] = s;
+        }
     }
     __syncthreads();
     if (hidden > 0) {
