@@ -206,7 +206,7 @@ esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C,
  * has a fixed order.  grad_lk's correlation of grad_out with x runs, for Ks <= 15, on the
  * bf16 matrix instructions with exact products: bf16 values as they are, fp32 values each
  * split exactly into three bf16 terms, all nine products of terms accumulated.  The workspace is esc_backward_workspace_bytes large, prepared with
- * esc_workspace_init.  Five launches on `stream`.
+ * esc_workspace_init.  Four launches on `stream`.
  */
 typedef struct esc_gen_grads {
     float *w_down; /* [hidden, C_a] or NULL */

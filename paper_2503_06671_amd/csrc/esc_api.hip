@@ -906,11 +906,13 @@ esc_status esc_convattn_backward(const void *x, const void *grad_out, esc_dtype 
         p.grad_b_up = grad_gen->b_up;
     }
     p.accumulate = accumulate != 0;
-    // 1. S = correlation of grad_out with x: grad_lk, dL/dDK, and the GAP means on the way
+    // 1. S = correlation of grad_out with x, per tile (and the tiles' sums of x for the GAP)
     if (launch_backward_sums(p, bf16, s) != hipSuccess) return ESC_ERR_HIP;
-    // 2. the estimator forwards (DK) and backwards; the flipped kernels
+    // 2. per image: dL/dDK and the GAP means, the estimator forwards (DK) and backwards; the flipped kernels
     if (launch_backward_estimator(p, s) != hipSuccess) return ESC_ERR_HIP;
-    // 3. the input gradient's convolution is the forward on grad_out with the flipped kernels
+    // 3. the sums over the batch: grad_lk and the estimator's parameter gradients
+    if (launch_backward_batch_sums(p, s) != hipSuccess) return ESC_ERR_HIP;
+    // 4. the input gradient's convolution is the forward on grad_out with the flipped kernels
     //    (identity channels: grad_x = grad_out, the forward's pass-through copy); the GAP's
     //    share, dL/dg / (H W) on every pixel of the attention planes, is added at its stores
     return enqueue_forward(grad_out, dt, N, C, H, W, C_a, p.lkf, Ks, lk_channel_stride != 0 ? (long)Ks * Ks : 0, nullptr,

@@ -459,48 +459,20 @@ hipError_t launch_corr_mfma_kc(const BackwardParams &p, int kc, unsigned grid, h
     return hipErrorInvalidValue;
 }
 
-// One row of 16 lanes per result: grad_lk (sums over images and tiles; over channels too for
-// a single shared filter), ddk (sums over tiles), g (the GAP mean).  Lane l adds terms l,
-// l + 16, ... in ascending order, then the row's lanes are added in lane order: a fixed
-// order, and sixteen loads in flight instead of a chain of dependent ones.
-__global__ __launch_bounds__(256) void sums_kernel(const BackwardParams p, int KC, int tiles)
+// grad_lk: one row of 16 lanes per element (element idx of the Ks x Ks filters; sums over images
+// and tiles, over channels too for a single shared filter).  Lane l adds terms l, l + 16, ...
+// in ascending order, then the row's lanes are added in lane order: a fixed order, and
+// sixteen loads in flight instead of a chain of dependent ones.
+__device__ __forceinline__ void sums_row(const BackwardParams &p, int KC, int tiles, size_t idx, int l)
 {
     const int Ks = p.Ks, Ca = p.Ca, off = (KC - Ks) / 2;
     const size_t per = (size_t)KC * KC + 1;
-    const size_t n_lk = (size_t)(p.lk_cstride != 0 ? Ca : 1) * Ks * Ks;
-    const size_t n_dk = (size_t)p.N * Ca * 9, n_g = (size_t)p.N * Ca;
-    const size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;  // uniform per row of 16 lanes
-    const int l = (int)(threadIdx.x & 15);
-    if (idx >= n_lk + n_dk + n_g) return;
-    // the result's terms: `count` of them, term k at partial[base(k)]
-    size_t elem, nc0;
-    int count, terms_per_plane = tiles, planes, plane_step;  // planes of (image, channel) walked, and the step between them
-    if (idx < n_lk) {
-        const int c0 = (int)(idx / ((size_t)Ks * Ks)), r = (int)(idx % ((size_t)Ks * Ks));
-        elem = (size_t)(r / Ks + off) * KC + (size_t)(r % Ks + off);
-        if (p.lk_cstride != 0) {  // channel c0 of every image
-            nc0 = (size_t)c0;
-            planes = p.N;
-            plane_step = Ca;
-        } else {                  // every channel of every image
-            nc0 = 0;
-            planes = p.N * Ca;
-            plane_step = 1;
-        }
-    } else if (idx < n_lk + n_dk) {
-        const size_t q = idx - n_lk;
-        const int r = (int)(q % 9);
-        elem = (size_t)(r / 3 + (KC - 3) / 2) * KC + (size_t)(r % 3 + (KC - 3) / 2);
-        nc0 = q / 9;
-        planes = 1;
-        plane_step = 0;
-    } else {
-        elem = (size_t)KC * KC;
-        nc0 = idx - n_lk - n_dk;
-        planes = 1;
-        plane_step = 0;
-    }
-    count = planes * terms_per_plane;
+    const int c0 = (int)(idx / ((size_t)Ks * Ks)), r = (int)(idx % ((size_t)Ks * Ks));
+    const size_t elem = (size_t)(r / Ks + off) * KC + (size_t)(r % Ks + off);
+    // channel c0 of every image, or (one shared filter) every channel of every image
+    const size_t nc0 = p.lk_cstride != 0 ? (size_t)c0 : 0;
+    const int planes = p.lk_cstride != 0 ? p.N : p.N * Ca, plane_step = p.lk_cstride != 0 ? Ca : 1;
+    const int count = planes * tiles;
     float s = 0.f;
     for (int k0 = l; k0 < count; k0 += 64) {
         float v[4];
@@ -508,26 +480,16 @@ __global__ __launch_bounds__(256) void sums_kernel(const BackwardParams p, int K
         for (int u = 0; u < 4; ++u) {
             const int k = k0 + 16 * u;
             const int kk = k < count ? k : count - 1;
-            const int pl = kk / terms_per_plane, tl = kk - pl * terms_per_plane;
+            const int pl = kk / tiles, tl = kk - pl * tiles;
             v[u] = p.partial[((nc0 + (size_t)pl * plane_step) * tiles + tl) * per + elem];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) s += k0 + 16 * u < count ? v[u] : 0.f;
     }
     s = row16_sum(s);
-    if (l != 15) return;
-    if (idx < n_lk) {
-        if (p.grad_lk == nullptr) return;
-        const int c0 = (int)(idx / ((size_t)Ks * Ks)), r = (int)(idx % ((size_t)Ks * Ks));
-        float *dst = p.grad_lk + (p.lk_cstride != 0 ? (size_t)c0 * p.lk_cstride : 0) + r;
-        *dst = p.accumulate ? *dst + s : s;
-    } else if (idx < n_lk + n_dk) {
-        const size_t q = idx - n_lk;
-        p.ddk[q] = s;
-        if (p.grad_dk != nullptr) p.grad_dk[q] = s;
-    } else {
-        p.g[idx - n_lk - n_dk] = s / (float)((double)p.H * (double)p.W);
-    }
+    if (l != 15 || p.grad_lk == nullptr) return;
+    float *dst = p.grad_lk + (p.lk_cstride != 0 ? (size_t)c0 * p.lk_cstride : 0) + r;
+    *dst = p.accumulate ? *dst + s : s;
 }
 
 __device__ __forceinline__ float gelu_f(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f)); }
@@ -536,15 +498,44 @@ __device__ __forceinline__ float gelu_grad_f(float v)
     return 0.5f * (1.f + erff(v * 0.70710678118654752440f)) + v * expf(-0.5f * v * v) * 0.39894228040143267794f;
 }
 
-// One block per image: the estimator forwards from g (DK, stored flipped for the input
-// gradient) and backwards from dDK (dL/dt, dL/du, dL/dg).  Plain loops: a few thousand
+// One block per image: its tiles' partial sums are added to dDK[n] and the GAP means g[n]
+// (a thread per result); then the estimator forwards from g (DK, stored flipped for the input
+// gradient) and backwards from dDK (dL/dt, dL/du, dL/dg) - plain loops, a few thousand
 // multiply-adds per image.
-__global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const BackwardParams p)
+__global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const BackwardParams p, int KC, int tiles)
 {
     __shared__ float s_g[256], s_u[256], s_t[256], s_dt[256], s_du[256], s_dd[9 * 256], s_part[kBwThreads];
     const int n = (int)blockIdx.x, tid = (int)threadIdx.x;
     const int Ca = p.Ca, hidden = p.hidden, K = hidden > 0 ? hidden : Ca;
     const float hw = (float)((double)p.H * (double)p.W);
+    {
+        // this image's sums over its tiles, one thread per result (9 C_a of dDK, C_a of g), the
+        // tiles in ascending order, eight loads in flight
+        const size_t per = (size_t)KC * KC + 1;
+        for (int o = tid; o < 10 * Ca; o += kBwThreads) {
+            const bool is_dd = o < 9 * Ca;
+            const int c = is_dd ? o / 9 : o - 9 * Ca, r = is_dd ? o - 9 * c : 0;
+            const size_t elem = is_dd ? (size_t)(r / 3 + (KC - 3) / 2) * KC + (size_t)(r % 3 + (KC - 3) / 2) : (size_t)KC * KC;
+            const float *src = p.partial + ((size_t)n * Ca + c) * tiles * per + elem;
+            float sum = 0.f;
+            for (int t0 = 0; t0 < tiles; t0 += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(t0 + u < tiles ? t0 + u : tiles - 1) * per];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += t0 + u < tiles ? v[u] : 0.f;
+            }
+            if (is_dd) {
+                s_dd[o] = sum;
+                p.ddk[(size_t)n * 9 * Ca + o] = sum;
+                if (p.grad_dk != nullptr) p.grad_dk[(size_t)n * 9 * Ca + o] = sum;
+            } else {
+                const float g = sum / hw;
+                s_g[c] = g;
+                p.g[(size_t)n * Ca + c] = g;
+            }
+        }
+    }
     if (!p.has_gen) {  // DK as given (or zero): only its flipped copy is needed
         for (int o = tid; o < 9 * Ca; o += kBwThreads) {
             const int c = o / 9, r = o - 9 * c;
@@ -553,9 +544,7 @@ __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const Backw
         for (int k = tid; k < Ca; k += kBwThreads) p.dgc[(size_t)n * Ca + k] = 0.f;
         return;
     }
-    for (int k = tid; k < Ca; k += kBwThreads) s_g[k] = p.g[(size_t)n * Ca + k];
-    for (int o = tid; o < 9 * Ca; o += kBwThreads) s_dd[o] = p.ddk[(size_t)n * 9 * Ca + o];
-    __syncthreads();
+    __syncthreads();  // s_g and s_dd are written
     if (hidden > 0) {
         for (int m = tid; m < hidden; m += kBwThreads) {
             float s = p.b_down != nullptr ? p.b_down[m] : 0.f;
@@ -620,19 +609,25 @@ __global__ __launch_bounds__(kBwThreads) void estimator_image_kernel(const Backw
     }
 }
 
-// One row of 16 lanes per parameter: the sums over the images (lane l adds images l, l + 16,
-// ... in ascending order, then the row's lanes in lane order); and the flipped LK.
-__global__ __launch_bounds__(256) void estimator_param_kernel(const BackwardParams p)
+// One row of 16 lanes per result of the sums over the batch: grad_lk (sums_row) and the
+// estimator's parameters (lane l adds images l, l + 16, ... in ascending order, then the
+// row's lanes in lane order); the flipped LK takes one lane per element behind them.
+__global__ __launch_bounds__(256) void batch_sums_kernel(const BackwardParams p, int KC, int tiles)
 {
     const int Ca = p.Ca, hidden = p.hidden, K = hidden > 0 ? hidden : Ca, Ks = p.Ks;
+    const size_t n_lk = (size_t)(p.lk_cstride != 0 ? Ca : 1) * Ks * Ks;
     const size_t n_wu = p.has_gen ? (size_t)9 * Ca * K : 0, n_bu = p.has_gen ? (size_t)9 * Ca : 0;
     const size_t n_wd = p.has_gen ? (size_t)hidden * Ca : 0, n_bd = p.has_gen ? (size_t)hidden : 0;
-    const size_t n_lkf = (size_t)(p.lk_cstride != 0 ? Ca : 1) * Ks * Ks;
     size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 4;  // uniform per row of 16 lanes
     const int l = (int)(threadIdx.x & 15);
+    if (idx < n_lk) {
+        sums_row(p, KC, tiles, idx, l);
+        return;
+    }
+    idx -= n_lk;
     if (idx >= n_wu + n_bu + n_wd + n_bd) {  // the flipped large kernel: one element per lane of the rows left over
         const size_t e = (idx - (n_wu + n_bu + n_wd + n_bd)) * 16 + l;
-        if (e < n_lkf) {
+        if (e < n_lk) {
             const size_t c = e / ((size_t)Ks * Ks), r = e % ((size_t)Ks * Ks);
             p.lkf[e] = p.lk[c * (size_t)p.lk_cstride + ((size_t)Ks * Ks - 1 - r)];
         }
@@ -690,41 +685,41 @@ hipError_t launch_corr_kc(const BackwardParams &p, int kc, unsigned grid, hipStr
 
 }  // namespace
 
+// the correlation of grad_out with x, tile by tile
 __attribute__((visibility("hidden"))) hipError_t launch_backward_sums(const BackwardParams &p, bool bf16, hipStream_t s)
 {
     if (p.Ca < 1) return hipSuccess;
     const int kc = corr_window(p.Ks), tiles = corr_tiles(p.H, p.W);
     const size_t grid = (size_t)p.N * p.Ca * tiles;
     if (grid >= ((size_t)1 << 31)) return hipErrorInvalidValue;
-    hipError_t e;
     if (kc <= 15) {  // one 16 x 16 block of sums: the matrix cores
         BackwardParams q = p;
         q.corr_vec = (p.W % 8 == 0) && ((uintptr_t)p.x % 16 == 0) && ((uintptr_t)p.go % 16 == 0);
-        e = bf16 ? launch_corr_mfma_kc<bf16b>(q, kc, (unsigned)grid, s) : launch_corr_mfma_kc<float>(q, kc, (unsigned)grid, s);
-    } else {
-        e = bf16 ? launch_corr_kc<bf16b>(p, kc, (unsigned)grid, s) : launch_corr_kc<float>(p, kc, (unsigned)grid, s);
+        return bf16 ? launch_corr_mfma_kc<bf16b>(q, kc, (unsigned)grid, s) : launch_corr_mfma_kc<float>(q, kc, (unsigned)grid, s);
     }
-    if (e != hipSuccess) return e;
-    const size_t results = (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks + (size_t)p.N * p.Ca * 10;
-    hipLaunchKernelGGL(sums_kernel, dim3((unsigned)((results * 16 + 255) / 256)), dim3(256), 0, s, p, kc, tiles);
-    return hipGetLastError();
+    return bf16 ? launch_corr_kc<bf16b>(p, kc, (unsigned)grid, s) : launch_corr_kc<float>(p, kc, (unsigned)grid, s);
 }
 
+// per image: dDK and g from the tiles' sums, the estimator forwards and backwards, the
+// flipped kernels (all that the input gradient's launch needs); then the sums over the
+// batch: grad_lk and the estimator's parameter gradients
 __attribute__((visibility("hidden"))) hipError_t launch_backward_estimator(const BackwardParams &p, hipStream_t s)
 {
     if (p.Ca < 1) return hipSuccess;
-    hipLaunchKernelGGL(estimator_image_kernel, dim3((unsigned)p.N), dim3(kBwThreads), 0, s, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const int K = p.hidden > 0 ? p.hidden : p.Ca;
-    const size_t params = (p.has_gen ? (size_t)9 * p.Ca * K + 9 * p.Ca + (size_t)p.hidden * p.Ca + p.hidden : 0) +
-                          (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks;
-    // a row of 16 lanes per estimator parameter; the flipped LK takes one lane per element behind them
-    const size_t n_est = p.has_gen ? (size_t)9 * p.Ca * K + 9 * p.Ca + (size_t)p.hidden * p.Ca + p.hidden : 0;
-    const size_t n_lkf = (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks;
-    const size_t threads = n_est * 16 + (n_lkf + 15) / 16 * 16;
-    (void)params;
-    hipLaunchKernelGGL(estimator_param_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, p);
+    const int kc = corr_window(p.Ks), tiles = corr_tiles(p.H, p.W);
+    hipLaunchKernelGGL(estimator_image_kernel, dim3((unsigned)p.N), dim3(kBwThreads), 0, s, p, kc, tiles);
+    return hipGetLastError();
+}
+
+__attribute__((visibility("hidden"))) hipError_t launch_backward_batch_sums(const BackwardParams &p, hipStream_t s)
+{
+    if (p.Ca < 1) return hipSuccess;
+    const int kc = corr_window(p.Ks), tiles = corr_tiles(p.H, p.W);
+    const size_t K = p.hidden > 0 ? (size_t)p.hidden : (size_t)p.Ca;
+    const size_t rows = (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks +
+                        (p.has_gen ? (size_t)9 * p.Ca * K + 9 * p.Ca + (size_t)p.hidden * p.Ca + p.hidden : 0);
+    const size_t n_lkf = (size_t)(p.lk_cstride != 0 ? p.Ca : 1) * p.Ks * p.Ks;  // one lane per element behind the rows
+    hipLaunchKernelGGL(batch_sums_kernel, dim3((unsigned)((rows * 16 + n_lkf + 255) / 256)), dim3(256), 0, s, p, kc, tiles);
     return hipGetLastError();
 }
 

@@ -44,9 +44,12 @@ struct BackwardParams {
     int corr_vec;            // set by launch_backward_sums: the correlation fetches its tiles in 16-byte pieces
 };
 
-// correlation of grad_out with x per tile, then the sums over tiles (and images): grad_lk, ddk, g
+// 1. correlation of grad_out with x per tile (partial sums in the workspace)
 hipError_t launch_backward_sums(const BackwardParams &p, bool bf16, hipStream_t s);
-// the estimator forwards (DK) and backwards (its gradients, dL/dg), the flipped kernels
+// 2. per image: dDK and g from the tiles' sums, the estimator forwards (DK) and backwards
+//    (dL/dg), the flipped kernels - all that the input gradient's launch needs
 hipError_t launch_backward_estimator(const BackwardParams &p, hipStream_t s);
+// 3. the sums over the batch: grad_lk and the estimator's parameter gradients
+hipError_t launch_backward_batch_sums(const BackwardParams &p, hipStream_t s);
 
 }  // namespace esc
