@@ -148,3 +148,54 @@ def test_delta_kernel_backward_is_exact():
 def test_backward_benchmark_workloads_full_size(oracle, idx):
     wl = wk.make_config(idx)
     check_backward(wl, oracle, 1600 + idx)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_backward_and_dense_calls_replay_from_a_captured_graph(dtype):
+    # The multi-launch calls captured into one graph: replays, with plain calls and
+    # synchronisations in between, must reproduce the plain calls bit for bit (every sum has a
+    # fixed order; nothing in the workspace may carry over from one call to the next).
+    wl = wk.make_random(1400, 3, 8, 45, 136, 4, 13, dtype=dtype, hidden=4, bias=True, x_mean=0.4)
+    go = grad_out_for(wl, 1401)
+    x, g = gu.to_dev_x(wl.x, wl.dtype), gu.to_dev_x(go, wl.dtype)
+    lk, gen = gu.dev(wl.lk), gu.gen_params(wl)
+    lkd = gu.dev((np.random.default_rng(1402).standard_normal((4, 4, 13, 13)) / 26.0).astype(np.float32))
+    ws_b = binding.new_backward_workspace(wl.N, wl.Ca, wl.H, wl.W, wl.Ks, wl.hidden)
+    ws_d = binding.new_dense_workspace(wl.N, wl.Ca, wl.H, wl.W, 13)
+    stream = torch.cuda.Stream()
+
+    def fresh():
+        w_down, b_down, w_up, b_up = gen.tensors
+        return {"grad_x": torch.full_like(x, float("nan")), "grad_lk": torch.full_like(lk, float("nan")),
+                "grad_dk": torch.full((wl.N, wl.Ca, 3, 3), float("nan"), device="cuda"),
+                "grad_w_up": torch.full_like(w_up, float("nan")), "grad_b_up": torch.full_like(b_up, float("nan")),
+                "grad_w_down": torch.full_like(w_down, float("nan")), "grad_b_down": torch.full_like(b_down, float("nan"))}
+
+    def enqueue(grads, out_d):
+        binding.convattn_backward(x, g, wl.Ca, lk, ws_b, gen=gen, grads=grads, stream=stream)
+        binding.convattn_dense_forward(x, wl.Ca, lkd, ws_d, gen=gen, out=out_d, stream=stream)
+
+    want, want_d = fresh(), torch.full_like(x, float("nan"))
+    with torch.cuda.stream(stream):
+        enqueue(want, want_d)
+    torch.cuda.synchronize()
+    got, got_d = fresh(), torch.full_like(x, float("nan"))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        enqueue(got, got_d)
+    scratch, scratch_d = fresh(), torch.empty_like(x)
+    for rep in range(3):
+        for t in list(got.values()) + [got_d]:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            graph.replay()
+        torch.cuda.synchronize()
+        assert binding.workspace_errors(ws_b, stream) == 0 and binding.workspace_errors(ws_d, stream) == 0
+        print(f"[case] backward + dense graph replay {rep}, {wl.name}", flush=True)
+        for k in want:
+            assert torch.equal(got[k].view(torch.uint8), want[k].view(torch.uint8)), k
+        assert torch.equal(got_d.view(torch.uint8), want_d.view(torch.uint8))
+        with torch.cuda.stream(stream):  # plain work on the same workspaces between replays
+            enqueue(scratch, scratch_d)
+        torch.cuda.synchronize()
