@@ -217,7 +217,8 @@ __global__ __launch_bounds__(kBwThreads) void corr_kernel(const BackwardParams p
 // consecutive values of the row starting j elements to the left - a start that is odd for
 // every other lane.  grad_out's rows are therefore kept twice, zero-extended: as they are and
 // moved by one element; a lane reads four whole words from the copy of its parity.  The four
-// wavefronts take every fourth row and add their results through LDS; the sum of x (for the
+// wavefronts take eight rows each (neighbouring rows share their A operands, see there) and add
+// their results through LDS; the sum of x (for the
 // GAP) comes from the halo tile's loads.  Same partial sums, same layout as corr_kernel.
 // ---------------------------------------------------------------------------
 constexpr int kCmXP = 104;  // halo tile: elements per row (96 columns are read; 13 x 16 bytes: rows fall on different banks)
@@ -379,44 +380,60 @@ __global__ __launch_bounds__(kBwThreads) void corr_mfma_kernel(const BackwardPar
     }
     __syncthreads();
 
-    // ---- this wavefront's rows of the tile: y = wave, wave + 4, ... ----
+    // ---- this wavefront's rows of the tile: 8 w .. 8 w + 7, in groups of SH neighbours that
+    // share their A operands: the halo rows R .. R + 15 serve tile row R + s as window rows
+    // i = i' - s (i' the row of the product), s < SH = 16 - KC + 1 (at most 4); every shift has
+    // accumulators of its own, and the shifted results are put together at the end ----
+    constexpr int SH = KC <= 13 ? 4 : 2;
     const int l16 = lane & 15, kg = lane >> 4;
     const int jc = l16 < KC ? l16 : KC - 1;  // (columns beyond the window repeat its last one; their sums are dropped)
     const size_t gsel = (jc & 1) ? kCmG1 : kCmG0;
     const int o0 = 8 * kg - jc + 2 * P - (jc & 1);  // even: the lane's first element in its copy, for block 0
-    f32x4 acc[3];
+    f32x4 acc[SH][3];
 #pragma unroll
-    for (int b = 0; b < 3; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int sft = 0; sft < SH; ++sft)
 #pragma unroll
-    for (int t = 0; t < kCorrTileH / 4; ++t) {
-        const int y = wave + 4 * t;
-        u32x4 a[NT][3], bv[NT][3];
+        for (int b = 0; b < 3; ++b) acc[sft][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 8 / SH; ++u) {
+        const int R = 8 * wave + SH * u;
+        u32x4 a[NT][3];
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
-            for (int b = 0; b < 3; ++b) {
-                a[tt][b] = *reinterpret_cast<const u32x4 *>(xs(tt) + (y + l16) * kCmXP + 32 * b + 8 * kg);
-                __builtin_memcpy(&bv[tt][b],
-                                 reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint16_t *>(lds + tt * kCmLds + gsel) + y * kCmGP + o0 + 32 * b),
-                                 16);
-            }
-        // (small terms first; the three column blocks' chains take turns)
+            for (int b = 0; b < 3; ++b) a[tt][b] = *reinterpret_cast<const u32x4 *>(xs(tt) + (R + l16) * kCmXP + 32 * b + 8 * kg);
 #pragma unroll
-        for (int ta = NT - 1; ta >= 0; --ta)
+        for (int sft = 0; sft < SH; ++sft) {
+            u32x4 bv[NT][3];
 #pragma unroll
-            for (int tb = NT - 1; tb >= 0; --tb)
+            for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
                 for (int b = 0; b < 3; ++b)
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ta][b]),
-                                                                     __builtin_bit_cast(bf16x8, bv[tb][b]), acc[b], 0, 0, 0);
+                    __builtin_memcpy(&bv[tt][b],
+                                     reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint16_t *>(lds + tt * kCmLds + gsel) +
+                                                                        (R + sft) * kCmGP + o0 + 32 * b),
+                                     16);
+            // (small terms first; the three column blocks' chains take turns)
+#pragma unroll
+            for (int ta = NT - 1; ta >= 0; --ta)
+#pragma unroll
+                for (int tb = NT - 1; tb >= 0; --tb)
+#pragma unroll
+                    for (int b = 0; b < 3; ++b)
+                        acc[sft][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ta][b]),
+                                                                              __builtin_bit_cast(bf16x8, bv[tb][b]), acc[sft][b], 0, 0, 0);
+        }
     }
-    const f32x4 tot = (acc[0] + acc[1]) + acc[2];
     const float sxr = row16_sum(sx);
     __syncthreads();  // the tiles are no longer read: their LDS takes the wavefronts' results
-    float *red = bw_lds;              // [4 wavefronts][16 i][16 j]
-    float *sxs = bw_lds + 4 * 256;    // [16 rows of lanes]
+    float *red = bw_lds;                   // [4 wavefronts][SH shifts][16 i'][16 j]
+    float *sxs = bw_lds + 4 * SH * 256;    // [16 rows of lanes]
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[wave * 256 + (4 * kg + r) * 16 + l16] = tot[r];
+    for (int sft = 0; sft < SH; ++sft) {
+        const f32x4 tot = (acc[sft][0] + acc[sft][1]) + acc[sft][2];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[(wave * SH + sft) * 256 + (4 * kg + r) * 16 + l16] = tot[r];
+    }
     if (l16 == 15) sxs[tid >> 4] = sxr;
     __syncthreads();
     float *dst = p.partial + ((size_t)nc * tiles + tile) * (KC * KC + 1);
@@ -427,7 +444,10 @@ __global__ __launch_bounds__(kBwThreads) void corr_mfma_kernel(const BackwardPar
             for (int k = 0; k < 16; ++k) s2 += sxs[k];
         } else {
             const int i = o / KC, j = o - i * KC;
-            s2 = ((red[i * 16 + j] + red[256 + i * 16 + j]) + red[512 + i * 16 + j]) + red[768 + i * 16 + j];
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                for (int sft = 0; sft < SH; ++sft) s2 += red[(w * SH + sft) * 256 + (i + sft) * 16 + j];
         }
         dst[o] = s2;
     }
