@@ -205,7 +205,8 @@ esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C,
  * x, lk, gen and dk_in are the forward's inputs.  fp32 accumulation throughout; every sum
  * has a fixed order.  grad_lk's correlation of grad_out with x runs, for Ks <= 15, on the
  * bf16 matrix instructions with exact products: bf16 values as they are, fp32 values each
- * split exactly into three bf16 terms, all nine products of terms accumulated.  The workspace is esc_backward_workspace_bytes large, prepared with
+ * split into three bf16 terms (exactly, but for values below 2^-102), all nine products of
+ * terms accumulated.  The workspace is esc_backward_workspace_bytes large, prepared with
  * esc_workspace_init.  Four launches on `stream`.
  */
 typedef struct esc_gen_grads {

@@ -209,7 +209,8 @@ __global__ __launch_bounds__(kBwThreads) void corr_kernel(const BackwardParams p
 // with K = the halo tile's columns, 32 per v_mfma_f32_16x16x32_bf16: 3 instructions per tile
 // row, 96 per tile, against 5400 vector multiply-adds per thread in corr_kernel.  With bf16
 // storage the stored values are the operands (products exact, fp32 accumulation).  fp32 values
-// are split exactly into three bf16 terms each (8 + 8 + 8 mantissa bits, by truncation), kept
+// are split into three bf16 terms each (8 + 8 + 8 mantissa bits, by truncation: exact but for
+// values within 2^24 of the smallest normal number, whose third term loses denormal bits), kept
 // as three tiles, and all nine products of terms are accumulated - every product is still
 // exact, and nine times 96 instructions are still a fifth of the vector loop's time.
 // A operand: lane (i, kg) reads 16 bytes of halo row y + i - the halo tile is laid out from the

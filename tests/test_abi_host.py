@@ -5,6 +5,8 @@ import ctypes
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 from paper_2503_06671_amd import binding
@@ -306,3 +308,36 @@ def test_dense_bf16_kernels_fit_two_blocks_per_cu_without_scratch(lib):
     assert set(meta) == {(ks, th) for ks in range(3, 18, 2) for th in (4, 8)}, sorted(meta)
     for key, (scratch, vgprs) in sorted(meta.items()):
         assert scratch == 0 and vgprs <= 256, (key, scratch, vgprs)
+
+
+def test_three_bf16_terms_hold_an_fp32_value_exactly():
+    # The backward's correlation feeds fp32 values to the bf16 matrix instructions as three terms
+    # taken by truncation (top 16 bits of the value, of the remainder, of what is left).  The
+    # claim the kernel rests on, checked here in numpy: every term is a bf16 value and the three
+    # add up to the fp32 value exactly, so that all nine products of two values' terms are exact
+    # (values within 2^24 of the smallest normal number lose denormal bits of the third term:
+    # an error below 2^-133, checked last).
+    rng = np.random.default_rng(77)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * np.float32(10.0) ** rng.integers(-6, 6, 20000),
+                        np.array([0.0, -0.0, 1.0, -1.0, 3.0e38, 1.0e-30, np.float32(1) + np.float32(2) ** -23], np.float32)])
+    x = x.astype(np.float32)
+
+    def top16(v):
+        return (v.view(np.uint32) & np.uint32(0xffff0000)).view(np.float32)
+
+    h = top16(x)
+    r1 = x - h
+    m = top16(r1)
+    r2 = r1 - m
+    lo = top16(r2)
+    assert np.array_equal(lo, r2)                       # the third term needs no truncation
+    s = (h.astype(np.float64) + m.astype(np.float64)) + lo.astype(np.float64)
+    assert np.array_equal(s, x.astype(np.float64))
+    for t in (h, m, lo):                                # each term is a bf16 value
+        assert not (t.view(np.uint32) & np.uint32(0xffff)).any()
+    tiny = np.array([1.2e-38, -2.0e-38, 1.0e-36], np.float32)
+    th = top16(tiny)
+    tm = top16(tiny - th)
+    tl = top16(tiny - th - tm)
+    err = np.abs(tiny.astype(np.float64) - (th.astype(np.float64) + tm.astype(np.float64) + tl.astype(np.float64)))
+    assert err.max() < 2.0 ** -133
