@@ -341,3 +341,15 @@ def test_three_bf16_terms_hold_an_fp32_value_exactly():
     tl = top16(tiny - th - tm)
     err = np.abs(tiny.astype(np.float64) - (th.astype(np.float64) + tm.astype(np.float64) + tl.astype(np.float64)))
     assert err.max() < 2.0 ** -133
+
+
+def test_two_bf16_terms_hold_a_weight_to_sixteen_mantissa_bits():
+    # Conv_fuse, LK^c and the dense large kernel with bf16 storage apply every fp32 weight as
+    # hi = bf16(w), lo = bf16(w - hi): the pair must miss w by no more than 2^-17 of |w|.
+    from paper_2503_06671_amd import workloads as wk
+    rng = np.random.default_rng(78)
+    w = (rng.standard_normal(50000) * 10.0 ** rng.integers(-4, 4, 50000)).astype(np.float32)
+    hi = wk.bf16_bits_to_f32(wk.f32_to_bf16_bits(w))
+    lo = wk.bf16_bits_to_f32(wk.f32_to_bf16_bits(w - hi))
+    err = np.abs(w.astype(np.float64) - (hi.astype(np.float64) + lo.astype(np.float64)))
+    assert (err <= np.abs(w.astype(np.float64)) * 2.0 ** -17).all()
