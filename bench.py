@@ -194,21 +194,30 @@ def fused_roofline_of(wl, sec, lkc, residual):
 
 def dense_roofline_of(wl, sec):
     """The dense-LK call: same bytes as the depth-wise forward; the C_a x C_a x Ks x Ks contraction on the
-    matrix cores - fp32 instructions for fp32 storage (and for more than 16 channels), bf16 instructions
-    for bf16 storage with up to 16 channels (each weight as two bf16 terms: twice the instructions, which
-    the algorithmic flop count does not include) - DK's nine taps on the vector units."""
+    matrix cores, DK's nine taps on the vector units.  With up to 16 channels the contraction runs on the
+    bf16 instructions: bf16 storage with every weight as two bf16 terms (two instructions per product
+    block), fp32 storage (Ks <= 13) with every value and weight as three exact bf16 terms (six
+    instructions per product block).  What bounds such a kernel is the instructions it issues at the
+    bf16 peak: `achieved` counts those (`terms_per_product` times the algorithmic flops, which hold
+    each product once and are reported beside it, also against the fp32 matrix peak).  Otherwise
+    fp32 instructions at the fp32 matrix peak."""
     P = wl.N * wl.H * wl.W
     b_alg = 2.0 * P * wl.C * wl.elem_bytes
     f_mat = 2.0 * wl.Ks * wl.Ks * wl.Ca * wl.Ca * P
-    mat_peak = BF16_MFMA_PEAK_TFLOPS if (wl.elem_bytes == 2 and wl.Ca <= 16) else FP32_MFMA_PEAK_TFLOPS
-    t_hbm, t_mat = b_alg / (HBM_PEAK_GBS * 1e9), f_mat / (mat_peak * 1e12)
+    on_bf16 = wl.Ca <= 16 and (wl.elem_bytes == 2 or wl.Ks <= 13)
+    mat_peak = BF16_MFMA_PEAK_TFLOPS if on_bf16 else FP32_MFMA_PEAK_TFLOPS
+    issued = (2.0 if wl.elem_bytes == 2 else 6.0) if on_bf16 else 1.0
+    t_hbm, t_mat = b_alg / (HBM_PEAK_GBS * 1e9), issued * f_mat / (mat_peak * 1e12)
     if t_hbm >= t_mat:
         r = {"bound": "hbm", "achieved": b_alg / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        r = {"bound": "mfma", "achieved": f_mat / sec / 1e12, "peak": mat_peak, "unit": "TFLOP/s"}
+        r = {"bound": "mfma", "achieved": issued * f_mat / sec / 1e12, "peak": mat_peak, "unit": "TFLOP/s"}
     r["frac"] = r["achieved"] / r["peak"]
-    r.update({"algorithmic_bytes": b_alg, "algorithmic_flops_matrix": f_mat, "hbm_gbps": b_alg / sec / 1e9,
-              "mfma_tflops": f_mat / sec / 1e12, "alu_tflops": 0.0})
+    r.update({"algorithmic_bytes": b_alg, "algorithmic_flops_matrix": f_mat, "terms_per_product": issued,
+              "matrix_instructions": "bf16" if on_bf16 else "fp32", "hbm_gbps": b_alg / sec / 1e9,
+              "mfma_tflops": f_mat / sec / 1e12, "mfma_issued_tflops": issued * f_mat / sec / 1e12,
+              "algorithmic_frac_of_fp32_mfma_peak": f_mat / sec / 1e12 / FP32_MFMA_PEAK_TFLOPS,
+              "algorithmic_frac_of_bf16_mfma_peak": f_mat / sec / 1e12 / BF16_MFMA_PEAK_TFLOPS, "alu_tflops": 0.0})
     return r
 
 
@@ -417,7 +426,7 @@ def main():
                    if fused is None and not args.dense and not args.backward else
                    "corr_mfma_kernel (grad_out x correlation on the matrix cores), sums, estimator kernels, forward_kernel on grad_out with flipped kernels and the GAP term"
                    if args.backward else
-                   "dense_kernel (implicit GEMM on the matrix cores, DK taps, pass-through share) after the estimator launch and the weight rearrangement"
+                   "dense_bf16_kernel / dense_kernel (implicit GEMM on the matrix cores, DK taps, pass-through share) after the estimator launch and the weight rearrangement"
                    if args.dense else
                    "forward_kernel (F_res into the workspace) + pointwise_kernel (Conv_fuse on the matrix cores)"
                    + ("; with LK^c also the estimator launch and a second pointwise_kernel" if args.lkc else "")),

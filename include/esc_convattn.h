@@ -173,10 +173,12 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
  *   lk_dense [C_a, C_a, Ks, Ks] fp32, output channel first; cross-correlation, zero padding.
  * DK stays a separate depth-wise term, as in the paper.  Everything else (gen, dk_in, out,
  * the identity channels, rounding) is as in esc_convattn_forward.  The contraction runs on
- * the matrix cores with fp32 accumulation: fp32 products for fp32 storage (and for bf16
- * storage with more than 16 channels, the stored values widened exactly); for bf16 storage
- * with C_a <= 16 bf16 matrix instructions on the stored values, each fp32 weight applied as
- * the sum of two bf16 terms (w = hi + lo to 16 mantissa bits; products exact).  Limits:
+ * the matrix cores with fp32 accumulation.  With C_a <= 16 on the bf16 matrix instructions:
+ * bf16 storage on the stored values, each fp32 weight applied as the sum of two bf16 terms
+ * (w = hi + lo to 16 mantissa bits; products exact); fp32 storage with Ks <= 13 on values and
+ * weights each split exactly into three bf16 terms, the six products of terms whose orders
+ * add up to at most two accumulated (what is left out lies below 2^-24 of a product: fp32
+ * accuracy).  Otherwise fp32 instructions (bf16 storage widened exactly).  Limits:
  * C_a <= 64, Ks odd <= 17.
  * The workspace is esc_dense_workspace_bytes large (the forward's workspace, DK and the
  * rearranged weights), prepared with esc_workspace_init.  Two or three launches on `stream`.

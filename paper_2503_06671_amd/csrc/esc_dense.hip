@@ -5,10 +5,11 @@
 //
 // A full C_a -> C_a convolution is a dense contraction over K = C_a * Ks * Ks (2704 for the
 // paper's 13 x 13 x 16 x 16), sixteen times the depth-wise form's arithmetic on the same
-// bytes: it is bound by the matrix cores, so it runs as an implicit GEMM - for bf16 storage
-// with up to 16 channels on the bf16 instructions (dense_bf16_kernel, further down), else on
+// bytes: it is bound by the matrix cores, so it runs as an implicit GEMM - with up to 16
+// channels on the bf16 instructions (dense_bf16_kernel, further down: bf16 storage, and fp32
+// storage up to 13 x 13 with values and weights as exact bf16 terms), else on
 // v_mfma_f32_16x16x4_f32 (fp32 products and accumulation; bf16 storage is widened exactly
-// when a tile is staged and rounded once at the store).  Per block: an 8 x 32 (small calls:
+// when a tile is staged and rounded once at the store).  That kernel: per block an 8 x 32 (small calls:
 // 4 x 32) pixel output tile of one image, all output channels.  Sixteen input channels at a time, their
 // zero-extended halo tile sits in LDS; per kernel row the weights of its Ks taps
 // ([tap][16 co][16 ci], rearranged once per call by a small kernel so that a row is one run
@@ -368,12 +369,16 @@ __global__ __launch_bounds__(kDnThreads, CT <= 2 ? 2 : 1) void dense_kernel(cons
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16 storage, up to 16 channels: the contraction on v_mfma_f32_16x16x32_bf16.
+// Up to 16 channels: the contraction on v_mfma_f32_16x16x32_bf16.
 //
-// K of one instruction = two neighbouring taps of a kernel row x 16 input channels.  The
-// stored values stay bf16 (exact operands); each fp32 weight enters as two bf16 terms,
+// K of one instruction = two neighbouring taps of a kernel row x 16 input channels.  bf16
+// storage: the stored values are the operands; each fp32 weight enters as two bf16 terms,
 // w = hi + lo to 16 mantissa bits, so two instructions per operand pair, products exact,
-// accumulation fp32.  The halo tile sits in LDS pixel-major, as cells of 16 bytes = eight
+// accumulation fp32.  fp32 storage (kernels up to 13 x 13): the bf16 instructions are sixteen
+// times as fast as the fp32 ones, so every value and every weight is split exactly into three
+// bf16 terms (dn_split3; one tile in LDS per term, three terms in the table) and the six
+// products of terms whose orders add up to at most two are accumulated - what is left out
+// lies below 2^-24 of a product, the size of fp32's own rounding.  The halo tile sits in LDS pixel-major, as cells of 16 bytes = eight
 // channels of one pixel, in two half planes (channels 0-7, 8-15): the sixteen lanes that read
 // one B operand's pixels read 256 consecutive bytes, the only pattern in which 16-byte LDS
 // reads run at full rate.  The tile's columns start at x0 - 8, so that (W % 8 == 0, 16-byte
@@ -399,45 +404,66 @@ constexpr int kBfPitch = 49;  // row pitch in cells
 // cells in one half plane of the tile; first cell behind the tile and behind the 32 KiB (2048
 // cells) that the partial results pass through; the block's LDS bytes (DK sits at the end)
 __host__ __device__ constexpr int bf_half_cells(int Kse, int th) { return (th + Kse - 1) * kBfPitch; }
-__host__ __device__ constexpr int bf_aux_cell(int Kse, int th) { return 2 * bf_half_cells(Kse, th) < 2048 ? 2048 : 2 * bf_half_cells(Kse, th); }
-inline size_t bf_lds_bytes(int Kse, int th) { return (size_t)bf_aux_cell(Kse, th) * 16 + 16 * 9 * sizeof(float); }
+__host__ __device__ constexpr int bf_aux_cell(int Kse, int th, int nx)
+{
+    return nx * 2 * bf_half_cells(Kse, th) < 2048 ? 2048 : nx * 2 * bf_half_cells(Kse, th);
+}
+inline size_t bf_lds_bytes(int Kse, int th, int nx) { return (size_t)bf_aux_cell(Kse, th, nx) * 16 + 16 * 9 * sizeof(float); }
 
-// wa[pair of columns jp][kernel row i][term: hi, lo][lane l][8 bf16]: lane l holds output channel
-// l % 16, tap (i, 2 jp + l / 32), input channels 8 ((l / 16) % 2) .. + 7 - the A operand of the
-// instruction; zero beyond the kernel (the last pair's second column) and beyond C_a
-__global__ void dense_weights_bf16_kernel(const float *lk, int Ca, int Ks, int Kse, uint32_t *wa)
+// a value as three bf16 terms by truncation (the top eight mantissa bits, the next eight, the
+// rest): exact (but for values within 2^24 of the smallest normal number)
+__device__ __forceinline__ void dn_split3(float v, uint16_t (&t)[3])
+{
+    const uint32_t hb = __float_as_uint(v) & 0xffff0000u;
+    const float r1 = v - __uint_as_float(hb);
+    const uint32_t mb = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(mb);
+    t[0] = (uint16_t)(hb >> 16), t[1] = (uint16_t)(mb >> 16), t[2] = (uint16_t)(__float_as_uint(r2) >> 16);
+}
+
+// wa[pair of columns jp][kernel row i][term][lane l][8 bf16]: lane l holds output channel l % 16,
+// tap (i, 2 jp + l / 32), input channels 8 ((l / 16) % 2) .. + 7 - the A operand of the
+// instruction; zero beyond the kernel (the last pair's second column) and beyond C_a.  Terms:
+// nw == 2: hi = bf16(w), lo = bf16(w - hi) (bf16 storage); nw == 3: the exact split (fp32 storage)
+__global__ void dense_weights_bf16_kernel(const float *lk, int Ca, int Ks, int Kse, int nw, uint32_t *wa)
 {
     const int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
     const int njp = (Kse + 1) / 2;
     if (idx >= njp * Kse * 64) return;
     const int q = idx >> 6, l = idx & 63, co = l & 15, kg = l >> 4, off = (Kse - Ks) / 2;
     const int jp = q / Kse, i = q - jp * Kse - off, j = 2 * jp + (kg >> 1) - off;
-    uint32_t hi[4], lo[4];
+    uint32_t term[3][4];
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-        uint32_t h2[2], l2[2];
+        uint16_t t2[2][3];
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const int ci = 8 * (kg & 1) + 2 * w + s;
             const bool in = co < Ca && ci < Ca && i >= 0 && i < Ks && j >= 0 && j < Ks;
             const float v = in ? lk[(((size_t)co * Ca + ci) * Ks + i) * Ks + j] : 0.f;
-            const uint16_t h = dn_f32_to_bf16(v);
-            h2[s] = h;
-            l2[s] = dn_f32_to_bf16(v - __uint_as_float((uint32_t)h << 16));
+            if (nw == 3) {
+                dn_split3(v, t2[s]);
+            } else {
+                t2[s][0] = dn_f32_to_bf16(v);
+                t2[s][1] = dn_f32_to_bf16(v - __uint_as_float((uint32_t)t2[s][0] << 16));
+                t2[s][2] = 0;
+            }
         }
-        hi[w] = h2[0] | (h2[1] << 16);
-        lo[w] = l2[0] | (l2[1] << 16);
+#pragma unroll
+        for (int t = 0; t < 3; ++t) term[t][w] = (uint32_t)t2[0][t] | ((uint32_t)t2[1][t] << 16);
     }
-    u32x4 *dst = reinterpret_cast<u32x4 *>(wa) + (size_t)q * 128 + l;
-    dst[0] = u32x4{hi[0], hi[1], hi[2], hi[3]};
-    dst[64] = u32x4{lo[0], lo[1], lo[2], lo[3]};
+    u32x4 *dst = reinterpret_cast<u32x4 *>(wa) + (size_t)q * nw * 64 + l;
+    for (int t = 0; t < nw; ++t) dst[t * 64] = u32x4{term[t][0], term[t][1], term[t][2], term[t][3]};
 }
 
-template <int KS, int TH>
+template <typename T, int KS, int TH>
 __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DenseParams p)
 {
     typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    constexpr bool kF32 = std::is_same<T, float>::value;
+    constexpr int NX = kF32 ? 3 : 1;  // bf16 terms of a stored value (one tile in LDS per term)
+    constexpr int NW = kF32 ? 3 : 2;  // bf16 terms of a weight
     constexpr int NA = 2 * TH;  // runs of 16 pixels in the tile: run nt = row nt / 2, columns 16 (nt % 2) ..
     constexpr int NT = TH / 2;  // runs whose results a wavefront ends up with
     constexpr int pad = (KS - 1) / 2, HR = TH + 2 * pad, HP = HR * kBfPitch;
@@ -445,8 +471,9 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
     const int l16 = lane & 15, kq = lane >> 4;
     const int H = p.H, W = p.W;
     char *s_bytes = reinterpret_cast<char *>(dn_lds);
-    u32x4 *s_cells = reinterpret_cast<u32x4 *>(dn_lds);  // [2 halves][HR][kBfPitch] cells
-    float *s_dk = reinterpret_cast<float *>(s_cells + bf_aux_cell(KS, TH));
+    u32x4 *s_cells = reinterpret_cast<u32x4 *>(dn_lds);  // [NX terms][2 halves][HR][kBfPitch] cells
+    constexpr int TILE = 2 * HP;                          // cells of one term's tile
+    float *s_dk = reinterpret_cast<float *>(s_cells + bf_aux_cell(KS, TH, NX));
     const size_t plane_px = (size_t)H * W;
 
     // Blocks go to the chip's eight dies round robin; each die gets a contiguous eighth of the
@@ -458,7 +485,7 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
     const unsigned n = tile_id / per_img, t_in = tile_id - n * per_img;
     const int tyi = (int)(t_in / (unsigned)p.tiles_x), txi = (int)(t_in - (unsigned)tyi * p.tiles_x);
     const int y0 = tyi * TH, x0 = txi * kDnTw;
-    const bf16d *xn = (const bf16d *)p.x + (size_t)n * p.C * plane_px;
+    const T *xn = (const T *)p.x + (size_t)n * p.C * plane_px;
 
     // ---- the block's share of the pass-through copy (Eq. 4 lines 1 and 4): up to three rounds
     // of 16 KiB are asked for at once, in front of the tile, and stored behind the tile's loads
@@ -502,8 +529,9 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
                 }
             }
         } else {
-            for (size_t o = begin + (size_t)tid * 2; o < end; o += (size_t)kDnThreads * 2)
-                *reinterpret_cast<uint16_t *>(dst + o) = *reinterpret_cast<const uint16_t *>(src + o);
+            typedef typename std::conditional<kF32, uint32_t, uint16_t>::type E;
+            for (size_t o = begin + (size_t)tid * sizeof(E); o < end; o += (size_t)kDnThreads * sizeof(E))
+                *reinterpret_cast<E *>(dst + o) = *reinterpret_cast<const E *>(src + o);
         }
     }
     auto copy_last_store = [&]() {
@@ -522,7 +550,54 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
     if (p.dk != nullptr && tid < 16 * 9) dk_v = p.dk[(size_t)n * p.Ca * 9 + (tid < p.Ca * 9 ? tid : 0)];
 
     // ---- the zero-extended halo tile, pixel-major ----
-    if (p.fill_vec) {
+    if (kF32 && p.fill_vec) {
+        // fp32 storage: the same tasks, 32 bytes (eight pixels) of each of eight channels per task,
+        // every value split into its three terms on the way to the three tiles
+        if constexpr (kF32) {
+            constexpr int tasks = 2 * (kBfCols / 8) * HR, KT = (tasks + kDnThreads - 1) / kDnThreads;
+            u32x4 v[KT][8][2];
+            bool in[KT];
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                const int task = k * kDnThreads + tid;
+                const int r = task % HR, rest = task / HR, pc = rest % (kBfCols / 8), h2 = rest / (kBfCols / 8);
+                const int gy = y0 - pad + r, gx = x0 - 8 + 8 * pc;
+                in[k] = task < tasks && gy >= 0 && gy < H && gx >= 0 && gx < W;
+                const size_t o = in[k] ? (size_t)gy * W + gx : 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int ch = 8 * h2 + e;
+                    const float *src = xn + (ch < p.Ca ? (size_t)ch * plane_px : 0) + o;
+                    v[k][e][0] = *reinterpret_cast<const u32x4 *>(src);
+                    v[k][e][1] = *reinterpret_cast<const u32x4 *>(src + 4);
+                }
+            }
+            copy_last_store();
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                const int task = k * kDnThreads + tid;
+                const int r = task % HR, rest = task / HR, pc = rest % (kBfCols / 8), h2 = rest / (kBfCols / 8);
+                u32x4 *dst = s_cells + h2 * HP + r * kBfPitch + 8 * pc;
+#pragma unroll
+                for (int d = 0; d < 8; ++d) {
+                    u32x4 cell[3];  // pixel d of the piece, one cell per term
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        uint16_t ta[3], tb[3];
+                        const bool a_in = in[k] && 8 * h2 + 2 * w < p.Ca, b_in = in[k] && 8 * h2 + 2 * w + 1 < p.Ca;
+                        dn_split3(a_in ? __uint_as_float(v[k][2 * w][d >> 2][d & 3]) : 0.f, ta);
+                        dn_split3(b_in ? __uint_as_float(v[k][2 * w + 1][d >> 2][d & 3]) : 0.f, tb);
+#pragma unroll
+                        for (int t = 0; t < 3; ++t) cell[t][w] = (uint32_t)ta[t] | ((uint32_t)tb[t] << 16);
+                    }
+                    if (task < tasks) {
+#pragma unroll
+                        for (int t = 0; t < 3; ++t) dst[t * TILE + d] = cell[t];
+                    }
+                }
+            }
+        }
+    } else if (p.fill_vec) {
         // task = (half, piece of eight columns, row), lanes on consecutive rows; at most two per thread
         constexpr int tasks = 2 * (kBfCols / 8) * HR;
         u32x4 v[2][8];
@@ -537,7 +612,8 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int ch = 8 * h2 + e;
-                v[k][e] = *reinterpret_cast<const u32x4 *>(xn + (ch < p.Ca ? (size_t)ch * plane_px : 0) + o);
+                v[k][e] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const bf16d *>(p.x) + (size_t)n * p.C * plane_px +
+                                                           (ch < p.Ca ? (size_t)ch * plane_px : 0) + o);
             }
         }
         copy_last_store();
@@ -567,22 +643,27 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
         copy_last_store();
         constexpr int total = 16 * HR * kBfCols;
         for (int i0 = 0; i0 < total; i0 += 8 * kDnThreads) {
-            uint16_t v[8];
+            float v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int idx = i0 + u * kDnThreads + tid;
                 const int ci = idx / (HR * kBfCols), r2 = idx - ci * (HR * kBfCols), r = r2 / kBfCols, c = r2 - r * kBfCols;
                 const int gy = y0 - pad + r, gx = x0 - 8 + c;
                 const bool ok = idx < total && ci < p.Ca && gy >= 0 && gy < H && gx >= 0 && gx < W;
-                const uint16_t raw = xn[ok ? (size_t)ci * plane_px + (size_t)gy * W + gx : 0].bits;
-                v[u] = ok ? raw : (uint16_t)0;
+                const float raw = dn_load(xn + (ok ? (size_t)ci * plane_px + (size_t)gy * W + gx : 0));
+                v[u] = ok ? raw : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int idx = i0 + u * kDnThreads + tid;
                 const int ci = idx / (HR * kBfCols), r2 = idx - ci * (HR * kBfCols), r = r2 / kBfCols, c = r2 - r * kBfCols;
-                if (idx < total)
-                    *reinterpret_cast<uint16_t *>(s_bytes + (size_t)((ci >> 3) * HP + r * kBfPitch + c) * 16 + (ci & 7) * 2) = v[u];
+                uint16_t t3[3];
+                dn_split3(v[u], t3);  // (bf16 storage: the value is its own first term)
+                if (idx < total) {
+#pragma unroll
+                    for (int t = 0; t < NX; ++t)
+                        *reinterpret_cast<uint16_t *>(s_bytes + (size_t)(t * TILE + (ci >> 3) * HP + r * kBfPitch + c) * 16 + (ci & 7) * 2) = t3[t];
+                }
             }
         }
     }
@@ -605,17 +686,24 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
             i0 = pos * kBase + (pos < kExtra ? pos : kExtra);
             cnt = kBase + (pos < kExtra ? 1 : 0);
         };
-        auto fetch_a = [&](int jp, u32x4 (&a)[MB][2]) {
+        auto fetch_a = [&](int jp, u32x4 (&a)[MB][NW]) {
             int i0, cnt;
             rows_of(jp, i0, cnt);
 #pragma unroll
             for (int m = 0; m < MB; ++m) {
                 int i = i0 + (m < cnt ? m : 0);
                 i = i < KS ? i : KS - 1;
-                a[m][0] = wa[(size_t)(jp * KS + i) * 128];
-                a[m][1] = wa[(size_t)(jp * KS + i) * 128 + 64];
+#pragma unroll
+                for (int t = 0; t < NW; ++t) a[m][t] = wa[((size_t)(jp * KS + i) * NW + t) * 64];
             }
         };
+        // the products of a value's and a weight's terms that are accumulated, small ones first:
+        // bf16 storage (value, lo) and (value, hi); fp32 storage the six products of terms whose
+        // orders add up to at most two - the three left out lie below 2^-24 of the product
+        constexpr int NP = kF32 ? 6 : 2;
+        constexpr int kPx[6] = {2, 0, 1, 1, 0, 0}, kPw[6] = {0, 2, 1, 0, 1, 0};
+        auto px = [&](int q) { return kF32 ? kPx[q] : 0; };
+        auto pw = [&](int q) { return kF32 ? kPw[q] : 1 - q; };
         auto mma = [&](const u32x4 &a, const u32x4 &b, f32x4 &c) {
             c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
         };
@@ -636,7 +724,7 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
                 if (jp >= 0 && o + 16 <= walk_len) __builtin_nontemporal_store(cv[g], reinterpret_cast<u32x4 *>(walk_dst + o));
             }
         };
-        auto walk = [&](int jp, const u32x4 (&a)[MB][2], u32x4 (&a_next)[MB][2], u32x4 (&cv)[kWalkGrains],
+        auto walk = [&](int jp, const u32x4 (&a)[MB][NW], u32x4 (&a_next)[MB][NW], u32x4 (&cv)[kWalkGrains],
                         const u32x4 (&cv_before)[kWalkGrains]) {
             int i0, cnt;
             rows_of(jp, i0, cnt);
@@ -648,10 +736,13 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
             int j = 2 * jp + (kq >> 1);
             j = j < KS ? j : KS - 1;
             const char *bp = s_bytes + (size_t)((kq & 1) * HP + i0 * kBfPitch + j + 8 - pad + l16) * 16;
-            u32x4 b[2][2];
-            auto read_b = [&](int R, u32x4 (&bb)[2]) {
-                bb[0] = *reinterpret_cast<const u32x4 *>(bp + R * kBfPitch * 16);
-                bb[1] = *reinterpret_cast<const u32x4 *>(bp + R * kBfPitch * 16 + 256);
+            u32x4 b[2][2][NX];
+            auto read_b = [&](int R, u32x4 (&bb)[2][NX]) {
+#pragma unroll
+                for (int t = 0; t < NX; ++t) {
+                    bb[0][t] = *reinterpret_cast<const u32x4 *>(bp + (t * TILE + R * kBfPitch) * 16);
+                    bb[1][t] = *reinterpret_cast<const u32x4 *>(bp + (t * TILE + R * kBfPitch) * 16 + 256);
+                }
             };
             read_b(0, b[0]);
 #pragma unroll
@@ -661,25 +752,25 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
                 if (R + 1 == NR - 1 && full) read_b(R + 1, b[(R + 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int term = 0; term < 2; ++term)
+                for (int q = 0; q < NP; ++q)
 #pragma unroll
                     for (int m = 0; m < MB - 1; ++m)
                         if (R - m >= 0 && R - m < TH) {
-                            mma(a[m][term], b[R & 1][0], part[2 * (R - m)]);
-                            mma(a[m][term], b[R & 1][1], part[2 * (R - m) + 1]);
+                            mma(a[m][pw(q)], b[R & 1][0][px(q)], part[2 * (R - m)]);
+                            mma(a[m][pw(q)], b[R & 1][1][px(q)], part[2 * (R - m) + 1]);
                         }
                 if (R - (MB - 1) >= 0 && R - (MB - 1) < TH && full) {
 #pragma unroll
-                    for (int term = 0; term < 2; ++term) {
-                        mma(a[MB - 1][term], b[R & 1][0], part[2 * (R - (MB - 1))]);
-                        mma(a[MB - 1][term], b[R & 1][1], part[2 * (R - (MB - 1)) + 1]);
+                    for (int q = 0; q < NP; ++q) {
+                        mma(a[MB - 1][pw(q)], b[R & 1][0][px(q)], part[2 * (R - (MB - 1))]);
+                        mma(a[MB - 1][pw(q)], b[R & 1][1][px(q)], part[2 * (R - (MB - 1)) + 1]);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
             copy_put(jp - 1, cv_before);
         };
-        u32x4 a0[MB][2], a1[MB][2], cv0[kWalkGrains] = {}, cv1[kWalkGrains] = {};
+        u32x4 a0[MB][NW], a1[MB][NW], cv0[kWalkGrains] = {}, cv1[kWalkGrains] = {};
         fetch_a(0, a0);
 #pragma unroll
         for (int jp = 0; jp < NJP; jp += 2) {
@@ -708,11 +799,17 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
             for (int di = 0; di < 3; ++di)
 #pragma unroll
                 for (int dj = 0; dj < 3; ++dj) {
-                    const u32x2 v = *reinterpret_cast<const u32x2 *>(src + (di * kBfPitch + dj) * 16);
-                    acc[m][0] = fmaf(d[0][di * 3 + dj], __uint_as_float(v[0] << 16), acc[m][0]);
-                    acc[m][1] = fmaf(d[1][di * 3 + dj], __uint_as_float(v[0] & 0xffff0000u), acc[m][1]);
-                    acc[m][2] = fmaf(d[2][di * 3 + dj], __uint_as_float(v[1] << 16), acc[m][2]);
-                    acc[m][3] = fmaf(d[3][di * 3 + dj], __uint_as_float(v[1] & 0xffff0000u), acc[m][3]);
+                    float xv[4] = {0.f, 0.f, 0.f, 0.f};  // the stored value: the sum of its terms, smallest first (exact)
+#pragma unroll
+                    for (int t = NX - 1; t >= 0; --t) {
+                        const u32x2 v = *reinterpret_cast<const u32x2 *>(src + (t * TILE + di * kBfPitch + dj) * 16);
+                        xv[0] += __uint_as_float(v[0] << 16);
+                        xv[1] += __uint_as_float(v[0] & 0xffff0000u);
+                        xv[2] += __uint_as_float(v[1] << 16);
+                        xv[3] += __uint_as_float(v[1] & 0xffff0000u);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[m][r] = fmaf(d[r][di * 3 + dj], xv[r], acc[m][r]);
                 }
         }
     }
@@ -742,8 +839,8 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
         }
     }
 
-    // ---- store: one rounding to bf16 ----
-    bf16d *on = (bf16d *)p.out + (size_t)n * p.C * plane_px;
+    // ---- store: one rounding to the storage type ----
+    T *on = (T *)p.out + (size_t)n * p.C * plane_px;
 #pragma unroll
     for (int m = 0; m < NT; ++m) {
         const int nt = wave * NT + m;
@@ -756,33 +853,35 @@ __global__ __launch_bounds__(kDnThreads, 2) void dense_bf16_kernel(const DensePa
     }
 }
 
-template <int KS, int TH>
+template <typename T, int KS, int TH>
 hipError_t launch_bf16_kt(const DenseParams &p, unsigned grid, hipStream_t s)
 {
-    const size_t lds = bf_lds_bytes(KS, TH);
+    const size_t lds = bf_lds_bytes(KS, TH, std::is_same<T, float>::value ? 3 : 1);
     static bool granted = false;
     if (lds > 48 * 1024 && !granted) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dense_bf16_kernel<KS, TH>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&dense_bf16_kernel<T, KS, TH>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         granted = true;
     }
-    hipLaunchKernelGGL((dense_bf16_kernel<KS, TH>), dim3(grid), dim3(kDnThreads), lds, s, p);
+    hipLaunchKernelGGL((dense_bf16_kernel<T, KS, TH>), dim3(grid), dim3(kDnThreads), lds, s, p);
     return hipGetLastError();
 }
 
-template <int TH>
+template <typename T, int TH>
 hipError_t launch_bf16(const DenseParams &p, unsigned grid, hipStream_t s)
 {
     switch (p.Ks) {
-    case 3: return launch_bf16_kt<3, TH>(p, grid, s);
-    case 5: return launch_bf16_kt<5, TH>(p, grid, s);
-    case 7: return launch_bf16_kt<7, TH>(p, grid, s);
-    case 9: return launch_bf16_kt<9, TH>(p, grid, s);
-    case 11: return launch_bf16_kt<11, TH>(p, grid, s);
-    case 13: return launch_bf16_kt<13, TH>(p, grid, s);
-    case 15: return launch_bf16_kt<15, TH>(p, grid, s);
-    case 17: return launch_bf16_kt<17, TH>(p, grid, s);
+    case 3: return launch_bf16_kt<T, 3, TH>(p, grid, s);
+    case 5: return launch_bf16_kt<T, 5, TH>(p, grid, s);
+    case 7: return launch_bf16_kt<T, 7, TH>(p, grid, s);
+    case 9: return launch_bf16_kt<T, 9, TH>(p, grid, s);
+    case 11: return launch_bf16_kt<T, 11, TH>(p, grid, s);
+    case 13: return launch_bf16_kt<T, 13, TH>(p, grid, s);
+    }
+    if constexpr (!std::is_same<T, float>::value) {  // (fp32 storage: three tiles in LDS, kernels up to 13 x 13)
+        if (p.Ks == 15) return launch_bf16_kt<T, 15, TH>(p, grid, s);
+        if (p.Ks == 17) return launch_bf16_kt<T, 17, TH>(p, grid, s);
     }
     return hipErrorInvalidValue;
 }
@@ -818,10 +917,10 @@ hipError_t launch_t(const DenseParams &p, int ct, unsigned grid, size_t lds, hip
 __attribute__((visibility("hidden"))) hipError_t launch_dense_weights(const float *lk, int Ca, int Ks, bool bf16, float *wt, hipStream_t s)
 {
     const int Kse = dense_effective_ks(Ks);
-    if (dense_on_bf16_mfma(Ca, bf16)) {
+    if (dense_on_bf16_mfma(Ca, Ks, bf16)) {
         const int threads = (Kse + 1) / 2 * Kse * 64;
         hipLaunchKernelGGL(dense_weights_bf16_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, lk, Ca, Ks, Kse,
-                           reinterpret_cast<uint32_t *>(wt));
+                           bf16 ? 2 : 3, reinterpret_cast<uint32_t *>(wt));
         return hipGetLastError();
     }
     const size_t total = dense_weight_floats(Ca, Ks);
@@ -846,7 +945,9 @@ __attribute__((visibility("hidden"))) hipError_t launch_dense(const DenseParams 
     }
     p.tiles_x = (p.W + kDnTw - 1) / kDnTw;
     const size_t blocks8 = (size_t)p.tiles_x * ((p.H + 7) / 8) * p.N;
-    const int th = blocks8 >= 2 * (size_t)cus ? 8 : 4;
+    const bool matrix_bf16 = dense_on_bf16_mfma(p.Ca, p.Ks, bf16);
+    // (fp32 storage on the bf16 instructions keeps three tiles in LDS: 4-row tiles, two blocks per compute unit)
+    const int th = (blocks8 >= 2 * (size_t)cus && !(matrix_bf16 && !bf16)) ? 8 : 4;
     p.tiles_y = (p.H + th - 1) / th;
     const size_t per_img = (size_t)p.tiles_x * p.tiles_y;
     const size_t grid = per_img * p.N;
@@ -858,9 +959,10 @@ __attribute__((visibility("hidden"))) hipError_t launch_dense(const DenseParams 
         share = (share + grain - 1) / grain * grain;
         p.copy_share = share;
     }
-    if (dense_on_bf16_mfma(p.Ca, bf16)) {
+    if (matrix_bf16) {
         p.fill_vec = (p.W % 8 == 0) && ((uintptr_t)p.x % 16 == 0);
-        return th == 8 ? launch_bf16<8>(p, (unsigned)grid, s) : launch_bf16<4>(p, (unsigned)grid, s);
+        if (!bf16) return launch_bf16<float, 4>(p, (unsigned)grid, s);
+        return th == 8 ? launch_bf16<bf16d, 8>(p, (unsigned)grid, s) : launch_bf16<bf16d, 4>(p, (unsigned)grid, s);
     }
     int hr, pitch, plane;
     dense_geom(p.Ks, th, hr, pitch, plane);

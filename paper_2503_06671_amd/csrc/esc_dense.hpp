@@ -30,16 +30,17 @@ struct DenseParams {
 // the kernel size the device code walks: a 1 x 1 kernel is embedded in a 3 x 3 one
 inline int dense_effective_ks(int Ks) { return Ks < 3 ? 3 : Ks; }
 
-// bf16 storage with up to 16 channels runs on the bf16 matrix instructions
-inline bool dense_on_bf16_mfma(int Ca, bool bf16) { return bf16 && Ca <= 16; }
+// up to 16 channels run on the bf16 matrix instructions: bf16 storage for every kernel size,
+// fp32 storage (every value and weight as three exact bf16 terms, three tiles in LDS) up to 13 x 13
+inline bool dense_on_bf16_mfma(int Ca, int Ks, bool bf16) { return Ca <= 16 && (bf16 || dense_effective_ks(Ks) <= 13); }
 
 // floats the rearranged weights take: [CT chunks][Kse rows][Kse taps][CT][16 ci][16 co], or, for
-// the bf16 matrix path, [(Kse + 1) / 2 pairs of tap columns][Kse rows][hi, lo][64 lanes][8 bf16]
-// (the storage type is not known when a workspace is sized: the larger of the two)
+// the bf16 matrix path, [(Kse + 1) / 2 pairs of tap columns][Kse rows][2 or 3 terms][64 lanes][8 bf16]
+// (the storage type is not known when a workspace is sized: room for three terms)
 inline size_t dense_weight_floats(int Ca, int Ks)
 {
     const size_t ct = (size_t)(Ca + 15) / 16, kse = (size_t)dense_effective_ks(Ks);
-    return ct == 1 ? kse * (kse + 1) * 256 : ct * kse * kse * ct * 256;
+    return ct == 1 ? kse * (kse + 1) * 384 : ct * kse * kse * ct * 256;
 }
 
 hipError_t launch_dense_weights(const float *lk, int Ca, int Ks, bool bf16, float *wt, hipStream_t s);

@@ -298,14 +298,16 @@ def test_kernel_variants_fit_four_blocks_per_cu_without_scratch(lib):
 
 
 def test_dense_bf16_kernels_fit_two_blocks_per_cu_without_scratch(lib):
-    # dense_bf16_kernel<Ks, TH>: one instantiation per odd kernel size 3 ... 17 and tile height;
-    # two blocks per compute unit (256 registers a lane), nothing in the private segment
+    # dense_bf16_kernel<T, Ks, TH>: bf16 storage one instantiation per odd kernel size 3 ... 17 and
+    # tile height, fp32 storage (three tiles in LDS) per odd kernel size 3 ... 13 at four rows; two
+    # blocks per compute unit (256 registers a lane), nothing in the private segment
     meta = {}
     for name, scratch, vgprs, lds in kernel_notes():
-        m = re.search(r"dense_bf16_kernelILi(\d+)ELi(\d+)EE", name)
+        m = re.search(r"dense_bf16_kernelI(f|NS\d_5bf16dE)Li(\d+)ELi(\d+)EE", name)
         if m:
-            meta[(int(m.group(1)), int(m.group(2)))] = (scratch, vgprs)
-    assert set(meta) == {(ks, th) for ks in range(3, 18, 2) for th in (4, 8)}, sorted(meta)
+            meta[("f" if m.group(1) == "f" else "b", int(m.group(2)), int(m.group(3)))] = (scratch, vgprs)
+    want = {("b", ks, th) for ks in range(3, 18, 2) for th in (4, 8)} | {("f", ks, 4) for ks in range(3, 14, 2)}
+    assert set(meta) == want, sorted(set(meta) ^ want)
     for key, (scratch, vgprs) in sorted(meta.items()):
         assert scratch == 0 and vgprs <= 256, (key, scratch, vgprs)
 
