@@ -129,6 +129,17 @@ def test_dense_bf16_matrix_path_every_kernel_size_on_eight_row_tiles(oracle, Ks)
     check_dense(wl, dense_kernel(951 + Ks, 16, Ks), oracle)
 
 
+@pytest.mark.parametrize("W", [72, 45])
+@pytest.mark.parametrize("Ks", [1, 3, 5, 7, 9, 11, 13, 15])
+def test_dense_fp32_on_bf16_terms_every_kernel_size(oracle, Ks, W):
+    # fp32 storage with up to 16 channels and Ks <= 13 runs the bf16 matrix instructions on three
+    # exact terms per value and weight (Ks = 15 stays on the fp32 instructions); W = 72 takes the
+    # 16-byte tile fetch, W = 45 the element-wise one; fewer channels than 16, ragged tiles.
+    wl = wk.make_random(960 + Ks + W, 2, 14, 21, W, 12, Ks, dtype=F32, x_mean=0.2)
+    rel = check_dense(wl, dense_kernel(961 + Ks, 12, Ks), oracle)
+    assert rel <= 2e-6, rel  # (six of the nine products of terms: fp32 accuracy, far inside the 1e-5 bar)
+
+
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
 def test_dense_benchmark_shapes_full_size(oracle, idx):
     wl = wk.make_config(idx)
