@@ -467,9 +467,10 @@ def main():
     if not args.no_all_workloads:
         # every other benchmark workload, 200 launches per replay, no CPU leg
         others = []
-        todo = [(i, None) for i in (0, 1, 2, 3)] + [(4, k) for k in wk.CFG4_KS]
+        todo = [(i, None) for i in (0, 1, 2, 3)] + [(4, k) for k in wk.CFG4_KS] + [(5, None)]
         for idx, ks in todo:
-            w2 = wk.make_config(idx, ks) if idx == 4 else wk.make_config(idx)
+            # (5: the larger model's shape, C = 192, C_a = 48, a hidden layer of 24)
+            w2 = wk.make_large_model() if idx == 5 else wk.make_config(idx, ks) if idx == 4 else wk.make_config(idx)
             if w2.name == wl.name:
                 continue
             r2 = Runner(w2, args.rotate_bytes, args.warm_cache)
