@@ -235,6 +235,9 @@ Plan plan_items(FwdParams &p, int Ks, int blocks_per_cu, int carry_grains)
         p.n_copy = (unsigned)(chunks * p.N);
     }
 
+    // (the estimator launch of a dense call: its copy entries build the dense kernel's table)
+    if (p.aux_n > 0 && p.n_conv == 0 && rest_len == 0) p.n_copy = (unsigned)((p.aux_n + kThreads - 1) / kThreads);
+
     // Alternation in layers, so that consecutive blocks - which the dispatcher spreads over a
     // die's compute units - are of one kind and every unit gets every kind: U conv entries,
     // then copy entries in proportion to what there is of each kind - times 3/4, so that the
@@ -395,12 +398,24 @@ esc_status setup_common(FwdParams &p, const void *x, esc_dtype dt, int N, int C,
 }
 
 // Eq. 4 line 2 alone on checked arguments: one launch of the variant without conv items.
+// dense_lk / dense_table: the dense kernel's A-operand table (dense_table_entry) is built by the
+// same launch, beside the pooling, from the Ks x Ks x C_a x C_a kernel dense_lk (nullptr: not)
 esc_status enqueue_dynkernel(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_a, const esc_gen_params *gen,
-                             float *dk_out, void *workspace, const WsLayout &l, hipStream_t stream)
+                             float *dk_out, void *workspace, const WsLayout &l, hipStream_t stream,
+                             const float *dense_lk = nullptr, int dense_ks = 0, uint32_t *dense_table = nullptr)
 {
     FwdParams p;
     esc_status st = setup_common(p, x, dt, N, C, H, W, C_a, gen, workspace, l);
     if (st != ESC_OK) return st;
+    if (dense_lk != nullptr) {
+        p.aux_lk = dense_lk;
+        p.aux_wa = dense_table;
+        p.aux_Ca = C_a;
+        p.aux_Ks = dense_ks;
+        p.aux_Kse = dense_effective_ks(dense_ks);
+        p.aux_nw = dt == ESC_BF16 ? 2 : 3;
+        p.aux_n = dense_table_entries(p.aux_Kse);
+    }
     p.dk_out = dk_out;
     p.dk_mode = kDkBoxes;  // no conv items here: gen items write dk_out, each from its image's pool sums
     p.n_gen = (unsigned)N;
@@ -801,13 +816,18 @@ esc_status esc_convattn_dense_forward(const void *x, esc_dtype dt, int N, int C,
         return enqueue_forward(x, dt, N, C, H, W, 0, nullptr, Ks, 0, nullptr, nullptr, out, C, true, workspace, d.ws, s);
     char *w = (char *)workspace;
     const float *dk = dk_in;
+    float *wt = (float *)(w + d.wt_off);
+    bool table_built = false;
     if (gen != nullptr) {  // Eq. 4 line 2: one launch of the variant without conv items
         float *dk_ws = (float *)(w + d.dk_off);
-        if ((st = enqueue_dynkernel(x, dt, N, C, H, W, C_a, gen, dk_ws, workspace, d.ws, s)) != ESC_OK) return st;
+        // (the matrix path's weight table is built by the same launch, beside the pooling)
+        table_built = dense_on_bf16_mfma(C_a, Ks, dt == ESC_BF16);
+        if ((st = enqueue_dynkernel(x, dt, N, C, H, W, C_a, gen, dk_ws, workspace, d.ws, s, table_built ? lk_dense : nullptr, Ks,
+                                    (uint32_t *)wt)) != ESC_OK)
+            return st;
         dk = dk_ws;
     }
-    float *wt = (float *)(w + d.wt_off);
-    if (launch_dense_weights(lk_dense, C_a, Ks, dt == ESC_BF16, wt, s) != hipSuccess) return ESC_ERR_HIP;
+    if (!table_built && launch_dense_weights(lk_dense, C_a, Ks, dt == ESC_BF16, wt, s) != hipSuccess) return ESC_ERR_HIP;
     DenseParams p{};
     p.x = x;
     p.out = out;

@@ -30,6 +30,7 @@
 #include <type_traits>
 
 #include "esc_dense.hpp"
+#include "esc_dense_weights.hpp"
 
 namespace esc {
 namespace {
@@ -410,50 +411,13 @@ __host__ __device__ constexpr int bf_aux_cell(int Kse, int th, int nx)
 }
 inline size_t bf_lds_bytes(int Kse, int th, int nx) { return (size_t)bf_aux_cell(Kse, th, nx) * 16 + 16 * 9 * sizeof(float); }
 
-// a value as three bf16 terms by truncation (the top eight mantissa bits, the next eight, the
-// rest): exact (but for values within 2^24 of the smallest normal number)
-__device__ __forceinline__ void dn_split3(float v, uint16_t (&t)[3])
-{
-    const uint32_t hb = __float_as_uint(v) & 0xffff0000u;
-    const float r1 = v - __uint_as_float(hb);
-    const uint32_t mb = __float_as_uint(r1) & 0xffff0000u;
-    const float r2 = r1 - __uint_as_float(mb);
-    t[0] = (uint16_t)(hb >> 16), t[1] = (uint16_t)(mb >> 16), t[2] = (uint16_t)(__float_as_uint(r2) >> 16);
-}
+__device__ __forceinline__ void dn_split3(float v, uint16_t (&t)[3]) { dw_split3(v, t); }
 
-// wa[pair of columns jp][kernel row i][term][lane l][8 bf16]: lane l holds output channel l % 16,
-// tap (i, 2 jp + l / 32), input channels 8 ((l / 16) % 2) .. + 7 - the A operand of the
-// instruction; zero beyond the kernel (the last pair's second column) and beyond C_a.  Terms:
-// nw == 2: hi = bf16(w), lo = bf16(w - hi) (bf16 storage); nw == 3: the exact split (fp32 storage)
+// the A-operand table (dense_table_entry), one thread per entry
 __global__ void dense_weights_bf16_kernel(const float *lk, int Ca, int Ks, int Kse, int nw, uint32_t *wa)
 {
     const int idx = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-    const int njp = (Kse + 1) / 2;
-    if (idx >= njp * Kse * 64) return;
-    const int q = idx >> 6, l = idx & 63, co = l & 15, kg = l >> 4, off = (Kse - Ks) / 2;
-    const int jp = q / Kse, i = q - jp * Kse - off, j = 2 * jp + (kg >> 1) - off;
-    uint32_t term[3][4];
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        uint16_t t2[2][3];
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int ci = 8 * (kg & 1) + 2 * w + s;
-            const bool in = co < Ca && ci < Ca && i >= 0 && i < Ks && j >= 0 && j < Ks;
-            const float v = in ? lk[(((size_t)co * Ca + ci) * Ks + i) * Ks + j] : 0.f;
-            if (nw == 3) {
-                dn_split3(v, t2[s]);
-            } else {
-                t2[s][0] = dn_f32_to_bf16(v);
-                t2[s][1] = dn_f32_to_bf16(v - __uint_as_float((uint32_t)t2[s][0] << 16));
-                t2[s][2] = 0;
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < 3; ++t) term[t][w] = (uint32_t)t2[0][t] | ((uint32_t)t2[1][t] << 16);
-    }
-    u32x4 *dst = reinterpret_cast<u32x4 *>(wa) + (size_t)q * nw * 64 + l;
-    for (int t = 0; t < nw; ++t) dst[t * 64] = u32x4{term[t][0], term[t][1], term[t][2], term[t][3]};
+    if (idx < dense_table_entries(Kse)) dense_table_entry(lk, Ca, Ks, Kse, nw, wa, idx);
 }
 
 template <typename T, int KS, int TH>
@@ -918,7 +882,7 @@ __attribute__((visibility("hidden"))) hipError_t launch_dense_weights(const floa
 {
     const int Kse = dense_effective_ks(Ks);
     if (dense_on_bf16_mfma(Ca, Ks, bf16)) {
-        const int threads = (Kse + 1) / 2 * Kse * 64;
+        const int threads = dense_table_entries(Kse);
         hipLaunchKernelGGL(dense_weights_bf16_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, lk, Ca, Ks, Kse,
                            bf16 ? 2 : 3, reinterpret_cast<uint32_t *>(wt));
         return hipGetLastError();

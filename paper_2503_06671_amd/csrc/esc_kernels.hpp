@@ -73,6 +73,7 @@
 #include <type_traits>
 
 #include "esc_convattn.h"
+#include "esc_dense_weights.hpp"
 
 namespace esc {
 
@@ -186,6 +187,12 @@ struct FwdParams {
     // mailboxes) come back quickly; measured, a full-rate copy beside them costs more than
     // it saves.
     int copy_gentle;
+    // The variant without conv items only (the estimator launch of a dense call): its copy
+    // entries are not copy items but pieces of 256 entries of the dense kernel's A-operand
+    // table, built from aux_lk beside the pooling (aux_n entries; 0 = none).
+    const float *aux_lk;
+    uint32_t *aux_wa;
+    int aux_n, aux_Ca, aux_Ks, aux_Kse, aux_nw;
     // Carried copy: conv item j of an image (j counts its tiles channel-major) moves bytes
     // [j * carry_g * kGrain, (j + 1) * carry_g * kGrain) of the image's pass-through range
     // (loaded behind its tile, stored behind its tap loop); the copy items cover what lies
@@ -1835,7 +1842,14 @@ __global__ __launch_bounds__(kThreads, kBlocksPerCu) void forward_kernel(const F
             if constexpr (KS > 0)
                 ctx = conv_item<KS, RY, T, STAGED>(p, ctx, idx);
         } else {
-            ctx = copy_item(p, ctx, idx);
+            if (KS == 0 && p->aux_n > 0) {
+                if constexpr (KS == 0) {
+                    const int e = (int)idx * kThreads + (int)threadIdx.x;
+                    if (e < p->aux_n) dense_table_entry(p->aux_lk, p->aux_Ca, p->aux_Ks, p->aux_Kse, p->aux_nw, p->aux_wa, e);
+                }
+            } else {
+                ctx = copy_item(p, ctx, idx);
+            }
         }
         if (dynamic) {
             if (threadIdx.x == kThreads - 1) g_next[turn & 1] = k8 + kXcds * (members8 + ctx.claim);
