@@ -16,7 +16,8 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, f) for f in ("esc_oracle.c", "esc_oracle_fuse.c", "esc_oracle_dense.c", "esc_oracle_backward.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("esc_oracle.c", "esc_oracle_fuse.c", "esc_oracle_dense.c", "esc_oracle_backward.c",
+                                            "esc_oracle_ffn.c")]
 _LIB = os.path.join(_HERE, "libesc_oracle.so")
 
 F32 = 0
@@ -68,6 +69,14 @@ def _load():
         lib.esc_oracle_convattn_backward.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, cl, ci, ci, vp, vp, vp, vp,
                                                      vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.esc_oracle_convattn_backward.restype = ci
+        lib.esc_oracle_ffn_expand.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, vp]
+        lib.esc_oracle_ffn_expand.restype = None
+        lib.esc_oracle_ffn_dwbranch.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp]
+        lib.esc_oracle_ffn_dwbranch.restype = None
+        lib.esc_oracle_ffn_project.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp]
+        lib.esc_oracle_ffn_project.restype = None
+        lib.esc_oracle_convffn_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp]
+        lib.esc_oracle_convffn_forward.restype = ci
         lib.esc_oracle_f32_to_bf16.argtypes = [ctypes.c_float]
         lib.esc_oracle_f32_to_bf16.restype = ctypes.c_uint16
         lib.esc_oracle_threads.restype = ci
@@ -347,3 +356,56 @@ def convattn_backward(x: np.ndarray, go: np.ndarray, Ca: int, lk: np.ndarray, dt
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return res
+
+
+# ---------------------------------------------------------------- ConvFFN (esc_oracle_ffn.c)
+
+def ffn_expand(x: np.ndarray, w1: np.ndarray, b1=None, dtype: int = F32) -> np.ndarray:
+    """First point-wise layer with its GELU -> [N,Ch,H,W] float64."""
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    w1, b1 = _f32(w1), _f32(b1)
+    Ch = w1.shape[0]
+    assert w1.shape == (Ch, C) and (b1 is None or b1.shape == (Ch,))
+    u = np.empty((N, Ch, H, W), dtype=np.float64)
+    _load().esc_oracle_ffn_expand(_ptr(x), dtype, N, C, H, W, Ch, _ptr(w1), _ptr(b1), _ptr(u))
+    return u
+
+
+def ffn_dwbranch(u: np.ndarray, k: np.ndarray, bk=None) -> np.ndarray:
+    """u + gelu(depth-wise 3x3 of u) on a float64 [N,Ch,H,W] tensor -> float64."""
+    u = np.ascontiguousarray(u, dtype=np.float64)
+    N, Ch, H, W = u.shape
+    k, bk = _f32(k), _f32(bk)
+    assert k.shape == (Ch, 3, 3) and (bk is None or bk.shape == (Ch,))
+    v = np.empty_like(u)
+    _load().esc_oracle_ffn_dwbranch(_ptr(u), N, Ch, H, W, _ptr(k), _ptr(bk), _ptr(v))
+    return v
+
+
+def ffn_project(v: np.ndarray, w2: np.ndarray, b2=None) -> np.ndarray:
+    """Second point-wise layer on a float64 [N,Ch,H,W] tensor -> float64 [N,C,H,W]."""
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    N, Ch, H, W = v.shape
+    w2, b2 = _f32(w2), _f32(b2)
+    C = w2.shape[0]
+    assert w2.shape == (C, Ch) and (b2 is None or b2.shape == (C,))
+    y = np.empty((N, C, H, W), dtype=np.float64)
+    _load().esc_oracle_ffn_project(_ptr(v), N, C, H, W, Ch, _ptr(w2), _ptr(b2), _ptr(y))
+    return y
+
+
+def convffn_forward(x: np.ndarray, w1, k, w2, dtype: int = F32, *, b1=None, bk=None, b2=None) -> np.ndarray:
+    """ConvFFN of Eq. 3 (two point-wise layers around a depth-wise 3x3 branch) -> float64 [N,C,H,W]."""
+    x = _x(x, dtype)
+    N, C, H, W = x.shape
+    w1, b1, k, bk, w2, b2 = _f32(w1), _f32(b1), _f32(k), _f32(bk), _f32(w2), _f32(b2)
+    Ch = w1.shape[0]
+    assert w1.shape == (Ch, C) and k.shape == (Ch, 3, 3) and w2.shape == (C, Ch)
+    assert (b1 is None or b1.shape == (Ch,)) and (bk is None or bk.shape == (Ch,)) and (b2 is None or b2.shape == (C,))
+    out = np.empty((N, C, H, W), dtype=np.float64)
+    rc = _load().esc_oracle_convffn_forward(_ptr(x), dtype, N, C, H, W, Ch, _ptr(w1), _ptr(b1), _ptr(k), _ptr(bk),
+                                            _ptr(w2), _ptr(b2), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out

@@ -171,3 +171,21 @@ def make_random(seed: int, N: int, C: int, H: int, W: int, Ca: int, Ks: int, dty
                     dtype=dtype, N=N, C=C, H=H, W=W, Ca=Ca, Ks=Ks, hidden=hidden,
                     x=np.ascontiguousarray(x), lk=np.ascontiguousarray(lk), w_up=w_up, b_up=b_up,
                     w_down=w_down, b_down=b_down)
+
+
+def make_ffn_params(seed: int, C: int, Ch: int, bias: bool = True):
+    """Seeded ConvFFN parameters (Eq. 3: the feed-forward network in front of the module):
+    w1[Ch,C] ~ N(0,1/C), k[Ch,3,3] ~ N(0,1/9), w2[C,Ch] ~ N(0,1/Ch), biases ~ N(0,0.01)
+    or None.  Returns a dict of float32 arrays."""
+    rng = np.random.default_rng(seed)
+    p = {
+        "w1": rng.standard_normal((Ch, C), dtype=np.float32) * np.float32(1.0 / np.sqrt(C)),
+        "k": rng.standard_normal((Ch, 3, 3), dtype=np.float32) * np.float32(1.0 / 3.0),
+        "w2": rng.standard_normal((C, Ch), dtype=np.float32) * np.float32(1.0 / np.sqrt(Ch)),
+        "b1": None, "bk": None, "b2": None,
+    }
+    if bias:
+        p["b1"] = rng.standard_normal(Ch, dtype=np.float32) * np.float32(0.1)
+        p["bk"] = rng.standard_normal(Ch, dtype=np.float32) * np.float32(0.1)
+        p["b2"] = rng.standard_normal(C, dtype=np.float32) * np.float32(0.1)
+    return p
