@@ -165,6 +165,37 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
                                       void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ConvFFN, the feed-forward network whose output the module takes in the residual step
+ * F_{i,j} = F_{i,j-1} + ConvAttn_j(ConvFFN_j(F_{i,j-1}), LK)  (Eq. 3 line 3).  Sec. 3 names it
+ * (the convolutional feed-forward network of the work the paper cites, kernel size three)
+ * and prints no equation; as that network is described - two point-wise layers with a
+ * depth-wise convolution branch between them:
+ *
+ *   U   = gelu(w1 . x + b1)            w1 [C_h, C] row-major, b1 [C_h] or NULL; exact (erf) GELU
+ *   V   = U + gelu(k_dw (*) U + b_dw)  k_dw [C_h, 3, 3] depth-wise, cross-correlation, zero
+ *                                      padding 1; b_dw [C_h] or NULL
+ *   out = w2 . V + b2                  w2 [C, C_h] row-major, b2 [C] or NULL
+ *
+ *   x, out    [N,C,H,W] in the storage type (device); out must not overlap x or the workspace
+ *   C_h       width of the hidden layer (the paper does not print its ratio to C)
+ * All weights are device pointers to fp32, read-only.  The point-wise layers run on the
+ * matrix cores as in esc_convattn_fused_forward (fp32 storage: fp32 products; bf16 storage:
+ * bf16 instructions on the stored values, each fp32 weight as two bf16 terms), the branch
+ * in fp32 on the vector units; U and V pass through the workspace in the storage type, so
+ * with bf16 storage they are rounded to bf16 on the way, and out once more at its store.
+ * The workspace (esc_convffn_workspace_bytes, 256-byte aligned) is plain scratch: it needs
+ * no esc_workspace_init and its contents are undefined after the call.  Limits: C <= 240,
+ * C_h <= 240, C_h*H*W*element size < 2 GiB.  Three launches on `stream`.  The whole residual
+ * step is this call followed by esc_convattn_fused_forward on its output with
+ * residual = x.
+ */
+size_t esc_convffn_workspace_bytes(int N, int C_h, int H, int W, esc_dtype dt);
+esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_h,
+                               const float *w1, const float *b1, const float *k_dw, const float *b_dw,
+                               const float *w2, const float *b2,
+                               void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Eq. 4 lines 1-4 (without Conv_fuse) with the DENSE large kernel of the paper's main
  * variants (Sec. 3: LK in R^{Ks x Ks x C_a x C_a}, shared by the whole model):
  *

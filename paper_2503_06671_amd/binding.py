@@ -21,7 +21,8 @@ ESC_BF16 = 1
 EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_workspace_errors", "esc_dynkernel_gen",
            "esc_convattn_forward", "esc_convattn_forward_noalloc", "esc_fused_workspace_bytes",
            "esc_convattn_fused_forward", "esc_dense_workspace_bytes", "esc_convattn_dense_forward",
-           "esc_backward_workspace_bytes", "esc_convattn_backward", "esc_status_string")
+           "esc_backward_workspace_bytes", "esc_convattn_backward", "esc_convffn_workspace_bytes",
+           "esc_convffn_forward", "esc_status_string")
 NOALLOC_SCRATCH_BYTES = 1 << 20
 
 
@@ -85,6 +86,10 @@ def load_library():
         lib.esc_convattn_backward.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, ci, cl, ctypes.POINTER(_GenParams), vp,
                                               vp, vp, ctypes.POINTER(_GenGrads), vp, ci, vp, sz, vp]
         lib.esc_convattn_backward.restype = ci
+        lib.esc_convffn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        lib.esc_convffn_workspace_bytes.restype = sz
+        lib.esc_convffn_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.esc_convffn_forward.restype = ci
         lib.esc_status_string.argtypes = [ci]
         lib.esc_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -294,6 +299,40 @@ def convattn_fused_forward(x: torch.Tensor, Ca: int, lk: torch.Tensor, w_fuse: t
         _ptr(x), dt, N, C, H, W, int(Ca), _ptr(lk_c), _ptr(lk), Ks, stride,
         ctypes.byref(gen.c) if gen is not None else None, _ptr(dk_in), _ptr(w_fuse), _ptr(b_fuse), _ptr(residual),
         _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out
+
+
+def new_convffn_workspace(N: int, Ch: int, H: int, W: int, dtype: torch.dtype, device="cuda") -> torch.Tensor:
+    """Allocate (with torch) the scratch workspace of esc_convffn_forward (needs no preparation)."""
+    dt = ESC_F32 if dtype == torch.float32 else ESC_BF16
+    nbytes = int(load_library().esc_convffn_workspace_bytes(N, Ch, H, W, dt))
+    if nbytes == 0:
+        raise ValueError("bad shape for a workspace")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def convffn_forward(x: torch.Tensor, w1: torch.Tensor, k_dw: torch.Tensor, w2: torch.Tensor, workspace: torch.Tensor,
+                    b1: Optional[torch.Tensor] = None, b_dw: Optional[torch.Tensor] = None,
+                    b2: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """esc_convffn_forward: w1 [Ch, C], k_dw [Ch, 3, 3], w2 [C, Ch], optional biases."""
+    dt, (N, C, H, W) = _x_checked(x)
+    for t, name in ((w1, "w1"), (k_dw, "k_dw"), (w2, "w2"), (b1, "b1"), (b_dw, "b_dw"), (b2, "b2")):
+        _dev_f32(t, name)
+    if w1.dim() != 2 or w1.shape[1] != C:
+        raise ValueError(f"w1 must be [Ch, C] with C = {C}; got {tuple(w1.shape)}")
+    Ch = int(w1.shape[0])
+    if tuple(k_dw.shape) != (Ch, 3, 3) or tuple(w2.shape) != (C, Ch):
+        raise ValueError("k_dw must be [Ch, 3, 3] and w2 [C, Ch]")
+    if (b1 is not None and b1.numel() != Ch) or (b_dw is not None and b_dw.numel() != Ch) or \
+            (b2 is not None and b2.numel() != C):
+        raise ValueError("b1 and b_dw must hold Ch values, b2 C values")
+    if out is None:
+        out = torch.empty_like(x)
+    if out.dtype != x.dtype or out.shape != x.shape or not out.is_contiguous():
+        raise TypeError("out must match x in dtype and shape and be contiguous")
+    _check(load_library().esc_convffn_forward(
+        _ptr(x), dt, N, C, H, W, Ch, _ptr(w1), _ptr(b1), _ptr(k_dw), _ptr(b_dw), _ptr(w2), _ptr(b2), _ptr(out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
     return out
 
 

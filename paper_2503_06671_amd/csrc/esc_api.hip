@@ -10,6 +10,7 @@
 #include "esc_kernels.hpp"
 #include "esc_backward.hpp"
 #include "esc_dense.hpp"
+#include "esc_ffn.hpp"
 #include "esc_pointwise.hpp"
 
 namespace esc {
@@ -777,6 +778,81 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
     pp.N = N;
     pp.P = (long)plane;
     return launch_pointwise(pp, bf16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
+}
+
+// ---- ConvFFN (Eq. 3 line 3: the feed-forward network in front of the module) ----------
+
+size_t esc_convffn_workspace_bytes(int N, int C_h, int H, int W, esc_dtype dt)
+{
+    if ((dt != ESC_F32 && dt != ESC_BF16) || N < 1 || C_h < 1 || H < 1 || W < 1) return 0;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    return 2 * round_up((size_t)N * C_h * H * W * es, kWsAlign);  // U and V
+}
+
+esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_h, const float *w1,
+                               const float *b1, const float *k_dw, const float *b_dw, const float *w2,
+                               const float *b2, void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (dt != ESC_F32 && dt != ESC_BF16) return ESC_ERR_DTYPE;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || C_h < 1) return ESC_ERR_SHAPE;
+    if (x == nullptr || out == nullptr || w1 == nullptr || k_dw == nullptr || w2 == nullptr) return ESC_ERR_NULL;
+    if ((size_t)H * (size_t)W >= ((size_t)1 << 31)) return ESC_ERR_UNSUPPORTED;
+    if (C > kPointwiseMaxK || C_h > kPointwiseMaxK) return ESC_ERR_UNSUPPORTED;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    const size_t plane = (size_t)H * W;
+    // the point-wise kernel addresses an image of a tensor with 32-bit byte offsets
+    if ((size_t)C_h * plane * es >= ((size_t)1 << 31) || (size_t)C * plane * es >= ((size_t)1 << 31))
+        return ESC_ERR_UNSUPPORTED;
+    if (((uintptr_t)x % es) != 0 || ((uintptr_t)out % es) != 0) return ESC_ERR_SHAPE;
+    const size_t need = esc_convffn_workspace_bytes(N, C_h, H, W, dt);
+    if (workspace == nullptr || ((uintptr_t)workspace % kWsAlign) != 0 || workspace_bytes < need) return ESC_ERR_WORKSPACE;
+    const size_t bytes = (size_t)N * C * plane * es;
+    if (overlaps(x, bytes, out, bytes) || overlaps(workspace, workspace_bytes, out, bytes) ||
+        overlaps(workspace, workspace_bytes, x, bytes))
+        return ESC_ERR_ALIAS;
+    hipStream_t s = (hipStream_t)stream;
+    const bool bf16 = dt == ESC_BF16;
+    char *u = (char *)workspace, *v = u + need / 2;
+    // U = gelu(W1 . x + b1)
+    PointwiseParams p1{};
+    p1.src1 = x;
+    p1.src1_img_stride = (size_t)C * plane;
+    p1.K1 = C;
+    p1.w = w1;
+    p1.w_ld = C;
+    p1.bias = b1;
+    p1.dst = u;
+    p1.dst_img_stride = (size_t)C_h * plane;
+    p1.M = C_h;
+    p1.N = N;
+    p1.P = (long)plane;
+    p1.gelu = 1;
+    if (launch_pointwise(p1, bf16, s) != hipSuccess) return ESC_ERR_HIP;
+    // V = U + gelu(K (*) U + bk)
+    FfnBranchParams fb{};
+    fb.u = u;
+    fb.v = v;
+    fb.k = k_dw;
+    fb.bk = b_dw;
+    fb.Ch = C_h;
+    fb.H = H;
+    fb.W = W;
+    fb.planes = (long)N * C_h;
+    if (launch_ffn_branch(fb, bf16, s) != hipSuccess) return ESC_ERR_HIP;
+    // out = W2 . V + b2
+    PointwiseParams p2{};
+    p2.src1 = v;
+    p2.src1_img_stride = (size_t)C_h * plane;
+    p2.K1 = C_h;
+    p2.w = w2;
+    p2.w_ld = C_h;
+    p2.bias = b2;
+    p2.dst = out;
+    p2.dst_img_stride = (size_t)C * plane;
+    p2.M = C;
+    p2.N = N;
+    p2.P = (long)plane;
+    return launch_pointwise(p2, bf16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
 }
 
 size_t esc_dense_workspace_bytes(int N, int C_a, int H, int W, int Ks)

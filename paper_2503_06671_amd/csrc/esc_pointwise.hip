@@ -54,6 +54,9 @@ __device__ __forceinline__ uint16_t pw_f32_to_bf16(float f)
 __device__ __forceinline__ float pw_load1(const float *p) { return *p; }
 __device__ __forceinline__ float pw_load1(const bf16s *p) { return __uint_as_float((uint32_t)p->bits << 16); }
 
+// exact (erf) GELU, the activation of ConvFFN's first layer (Eq. 3)
+__device__ __forceinline__ float pw_gelu(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f)); }
+
 typedef __amdgpu_buffer_rsrc_t Rsrc;
 constexpr int kRawBuffer = 0x00020000;     // raw buffer (no stride, no swizzle), 32-bit data format
 constexpr int kNt = 2;                     // non-temporal
@@ -66,7 +69,7 @@ extern __shared__ __align__(16) float pw_lds[];
 // 64 ph + 32 t + l%32 of the block's tile.  Buffer accesses on resources that end with the
 // image: rows beyond M and (their offset pushed beyond every resource) pixels beyond the
 // plane read as zero and are not written; without a residual its resource is empty.
-template <typename T>
+template <typename T, bool GELU>
 __device__ __forceinline__ void store_tile(const PointwiseParams &p, const f32x16 (&acc)[2], unsigned tile,
                                            unsigned tiles_per_img, int m0, int mt, int ph, int l32, int half)
 {
@@ -95,7 +98,7 @@ __device__ __forceinline__ void store_tile(const PointwiseParams &p, const f32x1
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const unsigned co = (unsigned)(m0 + 32 * mt + 8 * (r >> 2) + 4 * half + (r & 3));
-                const float v = acc[t2][r] + rv[r];
+                const float v = (GELU ? pw_gelu(acc[t2][r]) : acc[t2][r]) + rv[r];
                 if constexpr (sizeof(T) == 4)
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rdst, (int)(co * plane_bytes + px_off), 0, kNt);
                 else
@@ -156,7 +159,7 @@ __device__ __forceinline__ void fetch_stage(const PointwiseParams &p, unsigned t
 // Loads and what is done with them are kept apart (all of a stage's loads first, their
 // uses a stage later): a value touched right after its load would make the compiler wait
 // for that load before it issues the next.
-template <typename T, bool VEC>
+template <typename T, bool VEC, bool GELU>
 __global__ __launch_bounds__(kPwThreads, (VEC && sizeof(T) == 4) ? 3 : 2) void pointwise_kernel(const PointwiseParams p)
 {
     constexpr int kPer = 16 / (int)sizeof(T);               // pixels per 16-byte piece
@@ -264,7 +267,7 @@ __global__ __launch_bounds__(kPwThreads, (VEC && sizeof(T) == 4) ? 3 : 2) void p
                     acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc[1], 0, 0, 0);
                 }
             }
-            store_tile<T>(p, acc, tile, tiles_per_img, m0, mt, ph, l32, half);
+            store_tile<T, GELU>(p, acc, tile, tiles_per_img, m0, mt, ph, l32, half);
         }
     }
 }
@@ -286,7 +289,7 @@ constexpr int kPwBfOPitch = 64;           // bf16 elements of a channel row of a
                                           // the 16-byte piece q of row ch lies at piece q ^ (ch & 7), which spreads the
                                           // rows over the banks; padded rows would cost the third block per compute unit)
 
-template <bool VEC>
+template <bool VEC, bool GELU>
 __global__ __launch_bounds__(kPwThreads, VEC ? 3 : 2) void pointwise_bf16_kernel(const PointwiseParams p)
 {
     typedef bf16s T;
@@ -427,7 +430,7 @@ __global__ __launch_bounds__(kPwThreads, VEC ? 3 : 2) void pointwise_bf16_kernel
             if (st + 1 < stages) {
                 // (more stages of this tile to come)
             } else if constexpr (!VEC) {
-                store_tile<T>(p, acc, tile, tiles_per_img, m0, mt, ph, l32, half);
+                store_tile<T, GELU>(p, acc, tile, tiles_per_img, m0, mt, ph, l32, half);
             } else if (m0 + 32 * mt < p.M) {  // wavefront-uniform
                 // lane l of accumulator tile t holds output channel m0 + 32 mt + l % 32, pixels
                 // 64 ph + 32 t + 8 q + 4 (l / 32) + (0 ... 3) in registers 4 q ... 4 q + 3
@@ -454,10 +457,11 @@ __global__ __launch_bounds__(kPwThreads, VEC ? 3 : 2) void pointwise_bf16_kernel
                 for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const float v0 = acc[t2][4 * q + 0] + __uint_as_float(rv[t2][q].x << 16);
-                        const float v1 = acc[t2][4 * q + 1] + __uint_as_float(rv[t2][q].x & 0xffff0000u);
-                        const float v2 = acc[t2][4 * q + 2] + __uint_as_float(rv[t2][q].y << 16);
-                        const float v3 = acc[t2][4 * q + 3] + __uint_as_float(rv[t2][q].y & 0xffff0000u);
+                        auto act = [](float a) { return GELU ? pw_gelu(a) : a; };
+                        const float v0 = act(acc[t2][4 * q + 0]) + __uint_as_float(rv[t2][q].x << 16);
+                        const float v1 = act(acc[t2][4 * q + 1]) + __uint_as_float(rv[t2][q].x & 0xffff0000u);
+                        const float v2 = act(acc[t2][4 * q + 2]) + __uint_as_float(rv[t2][q].y << 16);
+                        const float v3 = act(acc[t2][4 * q + 3]) + __uint_as_float(rv[t2][q].y & 0xffff0000u);
                         const u32x2 w = {(uint32_t)pw_f32_to_bf16(v0) | ((uint32_t)pw_f32_to_bf16(v1) << 16),
                                          (uint32_t)pw_f32_to_bf16(v2) | ((uint32_t)pw_f32_to_bf16(v3) << 16)};
                         *reinterpret_cast<u32x2 *>(s_o + l32 * kPwBfOPitch + 8 * ((4 * t2 + q) ^ (l32 & 7)) + 4 * half) = w;
@@ -529,11 +533,18 @@ __attribute__((visibility("hidden"))) hipError_t launch_pointwise(const Pointwis
     auto aligned = [&](const void *ptr, size_t img_stride) { return (uintptr_t)ptr % 16 == 0 && img_stride % per == 0; };
     const bool vec = (size_t)p.P % per == 0 && (p.K1 == 0 || aligned(p.src1, p.src1_img_stride)) &&
                      (p.K2 == 0 || aligned(p.src2, p.src2_img_stride));
+    if (p.gelu) {
+        if (vec)
+            return bf16 ? launch_one<pointwise_bf16_kernel<true, true>>(p, (unsigned)grid, lds, s)
+                        : launch_one<pointwise_kernel<float, true, true>>(p, (unsigned)grid, lds, s);
+        return bf16 ? launch_one<pointwise_bf16_kernel<false, true>>(p, (unsigned)grid, lds, s)
+                    : launch_one<pointwise_kernel<float, false, true>>(p, (unsigned)grid, lds, s);
+    }
     if (vec)
-        return bf16 ? launch_one<pointwise_bf16_kernel<true>>(p, (unsigned)grid, lds, s)
-                    : launch_one<pointwise_kernel<float, true>>(p, (unsigned)grid, lds, s);
-    return bf16 ? launch_one<pointwise_bf16_kernel<false>>(p, (unsigned)grid, lds, s)
-                : launch_one<pointwise_kernel<float, false>>(p, (unsigned)grid, lds, s);
+        return bf16 ? launch_one<pointwise_bf16_kernel<true, false>>(p, (unsigned)grid, lds, s)
+                    : launch_one<pointwise_kernel<float, true, false>>(p, (unsigned)grid, lds, s);
+    return bf16 ? launch_one<pointwise_bf16_kernel<false, false>>(p, (unsigned)grid, lds, s)
+                : launch_one<pointwise_kernel<float, false, false>>(p, (unsigned)grid, lds, s);
 }
 
 }  // namespace esc

@@ -6,8 +6,9 @@
 
 namespace esc {
 
-// dst[n, m, q] = bias[m] + sum_k w[m * w_ld + k] * cat[n, k, q] (+ res[n, m, q]),  m < M, q < P,
-// where cat's first K1 channels are src1's and the next K2 are src2's.  Every tensor is a
+// dst[n, m, q] = act(bias[m] + sum_k w[m * w_ld + k] * cat[n, k, q]) (+ res[n, m, q]),  m < M, q < P,
+// where cat's first K1 channels are src1's and the next K2 are src2's, and act is the
+// identity or (gelu != 0) the exact erf GELU.  Every tensor is a
 // stack of planes of P elements in the storage type; image n of a tensor starts
 // n * <its>_img_stride elements after the base (channel planes follow one another).
 struct PointwiseParams {
@@ -23,6 +24,7 @@ struct PointwiseParams {
     size_t dst_img_stride;
     int M, N;
     long P;
+    int gelu;           // != 0: GELU on the product plus bias (ConvFFN's first layer)
 };
 
 constexpr int kPointwiseMaxK = 240;  // input channels the kernel's LDS staging holds

@@ -183,6 +183,30 @@ def test_dense_forward_rejects_bad_arguments_before_launch(lib):
     assert de(ws=0x90000 - 256, ws_bytes=need) == E_ALIAS  # workspace runs into out
 
 
+def test_convffn_rejects_bad_arguments_before_launch(lib):
+    def ff(x=0x10000, dt=0, N=1, C=64, H=8, W=8, Ch=128, w1=0x20000, b1=None, k=0x28000, bk=None, w2=0x2a000, b2=None,
+           out=0x90000, ws=0x30000 * 256, ws_bytes=1 << 22):
+        return lib.esc_convffn_forward(x, dt, N, C, H, W, Ch, w1, b1, k, bk, w2, b2, out, ws, ws_bytes, None)
+    for name in ("x", "out", "w1", "k", "w2"):
+        assert ff(**{name: None}) == E_NULL, name
+    assert ff(dt=3) == E_DTYPE
+    assert ff(N=0) == E_SHAPE
+    assert ff(Ch=0) == E_SHAPE
+    assert ff(Ch=241) == E_UNSUP                          # the point-wise kernel's LDS staging holds 240 channels
+    assert ff(C=241) == E_UNSUP
+    assert ff(out=0x10000) == E_ALIAS
+    assert ff(out=0x90002) == E_SHAPE                     # misaligned for fp32 storage
+    assert ff(ws=None) == E_WS
+    need = lib.esc_convffn_workspace_bytes(1, 128, 8, 8, 0)
+    assert need % 256 == 0 and need >= 2 * 128 * 64 * 4   # U and V in the storage type
+    assert lib.esc_convffn_workspace_bytes(1, 128, 8, 8, 1) * 2 == need
+    assert lib.esc_convffn_workspace_bytes(1, 128, 8, 8, 2) == 0
+    assert lib.esc_convffn_workspace_bytes(0, 128, 8, 8, 0) == 0
+    assert ff(ws_bytes=need - 1) == E_WS
+    assert ff(ws=0x30000 * 256 + 4, ws_bytes=need + 4) == E_WS   # not 256-byte aligned
+    assert ff(ws=0x90000 - 256, ws_bytes=need) == E_ALIAS        # workspace runs into out
+
+
 def test_backward_rejects_bad_arguments_before_launch(lib):
     def bw(x=0x10000, go=0x50000, dt=0, N=1, C=64, H=8, W=8, Ca=16, lk=0x20000, Ks=13, stride=169, gen=None, dk=None,
            gx=0x90000, glk=0x28000, ggen=None, gdk=None, acc=0, ws=0x30000 * 256, ws_bytes=1 << 22):
