@@ -63,6 +63,11 @@ def parse_args():
                     help="time esc_convattn_dense_forward (dense Ks x Ks x C_a x C_a large kernel of the paper's main variants) instead")
     ap.add_argument("--backward", action="store_true",
                     help="time esc_convattn_backward (gradients of the depth-wise forward) instead")
+    ap.add_argument("--ffn", action="store_true",
+                    help="time esc_convffn_forward (ConvFFN of Eq. 3 line 3, hidden width 2 C) instead")
+    ap.add_argument("--res-step", action="store_true",
+                    help="time the whole residual step of Eq. 3 line 3: esc_convffn_forward, then "
+                         "esc_convattn_fused_forward on its output with residual = the step's input")
     ap.add_argument("--lkc", action="store_true", help="with --fused: LK^c in front of the depth-wise kernels (Eq. 5)")
     ap.add_argument("--residual", action="store_true", help="with --fused: add the residual of Eq. 3 line 3")
     return ap.parse_args()
@@ -242,10 +247,41 @@ def backward_roofline_of(wl, sec):
             "alu_tflops": f_vec / sec / 1e12, "mfma_tflops": f_mat / sec / 1e12}
 
 
+def ffn_roofline_of(wl, sec, with_module):
+    """ConvFFN (hidden width 2 C): x read once, out written once; the two point-wise layers on the
+    matrix cores (fp32 instructions for fp32 storage; bf16 storage: bf16 instructions, two per product
+    block because every weight is two bf16 terms - `achieved` counts those), the 3 x 3 branch on the
+    vector units.  with_module: the whole residual step, the fused module's work and bytes added
+    (the tensor between the two calls is written and read once more: it is an output and an input)."""
+    P = wl.N * wl.H * wl.W
+    Ch = 2 * wl.C
+    b_alg = 2.0 * P * wl.C * wl.elem_bytes
+    f_mat = 4.0 * wl.C * Ch * P
+    f_vec = 18.0 * Ch * P
+    if with_module:
+        b_alg += 3.0 * P * wl.C * wl.elem_bytes
+        f_mat += 2.0 * wl.C * wl.C * P
+        f_taps = 2.0 * wl.Ks * wl.Ks * P * wl.Ca
+    else:
+        f_taps = 0.0
+    issued = 2.0 if wl.elem_bytes == 2 else 1.0
+    mat_peak = BF16_MFMA_PEAK_TFLOPS if wl.elem_bytes == 2 else FP32_MFMA_PEAK_TFLOPS
+    taps_peak = BF16_MFMA_PEAK_TFLOPS if taps_on_matrix_cores(wl) else FP32_VECTOR_PEAK_TFLOPS
+    t = {"hbm": b_alg / (HBM_PEAK_GBS * 1e9), "mfma": issued * f_mat / (mat_peak * 1e12),
+         "alu": f_vec / (FP32_VECTOR_PEAK_TFLOPS * 1e12) + f_taps / (taps_peak * 1e12)}
+    bound = max(t, key=t.get)
+    ach = {"hbm": b_alg / sec / 1e9, "mfma": issued * f_mat / sec / 1e12, "alu": (f_vec + f_taps) / sec / 1e12}[bound]
+    peak = {"hbm": HBM_PEAK_GBS, "mfma": mat_peak, "alu": FP32_VECTOR_PEAK_TFLOPS}[bound]
+    return {"bound": bound, "achieved": ach, "peak": peak, "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+            "frac": t[bound] / sec, "algorithmic_bytes": b_alg, "algorithmic_flops_matrix": f_mat,
+            "algorithmic_flops_vector": f_vec + f_taps, "terms_per_product": issued, "hidden_channels": Ch,
+            "hbm_gbps": b_alg / sec / 1e9, "mfma_tflops": f_mat / sec / 1e12, "alu_tflops": (f_vec + f_taps) / sec / 1e12}
+
+
 class Runner:
     """Device buffers of one workload and the timing protocol."""
 
-    def __init__(self, wl, rotate_bytes, warm_cache, ca=None, fused=None, dense=False, backward=False):
+    def __init__(self, wl, rotate_bytes, warm_cache, ca=None, fused=None, dense=False, backward=False, ffn=None):
         import numpy as np
         import torch
         from paper_2503_06671_amd import binding, workloads as wk
@@ -289,10 +325,26 @@ class Runner:
             self.lk_c = dev((rng.standard_normal((wl.Ca, wl.Ca)) / np.sqrt(wl.Ca)).astype(np.float32)) if fused["lkc"] else None
             self.res = [torch.randn_like(x0) for _ in range(self.pairs)] if fused["residual"] else None
             self.ws = binding.new_fused_workspace(wl.N, self.ca, wl.H, wl.W, x0.dtype, fused["lkc"])
+        self.ffn = ffn   # None, "ffn" (ConvFFN alone) or "step" (ConvFFN, then the fused module with the residual)
+        if ffn is not None:
+            fp = wk.make_ffn_params(3000 + wl.C, wl.C, 2 * wl.C)
+            self.ffn_p = {k: dev(v) for k, v in fp.items()}
+            self.ffn_ws = binding.new_convffn_workspace(wl.N, 2 * wl.C, wl.H, wl.W, x0.dtype)
+            self.mid = torch.empty_like(x0)   # ConvFFN's output, the module's input
         self.stream = torch.cuda.Stream()
 
     def step(self, i):
         k = i % self.pairs
+        if self.ffn is not None:
+            p = self.ffn_p
+            dst = self.outs[k] if self.ffn == "ffn" else self.mid
+            self.binding.convffn_forward(self.xs[k], p["w1"], p["k"], p["w2"], self.ffn_ws, b1=p["b1"], b_dw=p["bk"],
+                                         b2=p["b2"], out=dst, stream=self.stream)
+            if self.ffn == "step":
+                self.binding.convattn_fused_forward(
+                    self.mid, self.ca, self.lk, self.w_fuse, self.ws, b_fuse=self.b_fuse, lk_c=self.lk_c,
+                    residual=self.xs[k], gen=self.gen, out=self.outs[k], stream=self.stream)
+            return
         if self.backward:
             g = dict(self.grads or {})
             g["grad_x"] = self.outs[k]
@@ -385,8 +437,11 @@ def main():
     replays = replays_for(args.steps, args.replays)
 
     fused = {"lkc": args.lkc, "residual": args.residual} if args.fused else None
+    ffn = "step" if args.res_step else "ffn" if args.ffn else None
+    if ffn == "step":
+        fused = {"lkc": args.lkc, "residual": False}   # (the residual is the step's input, not a tensor of its own)
     torch.manual_seed(7)
-    run = Runner(wl, args.rotate_bytes, args.warm_cache, fused=fused, dense=args.dense, backward=args.backward)
+    run = Runner(wl, args.rotate_bytes, args.warm_cache, fused=fused, dense=args.dense, backward=args.backward, ffn=ffn)
     t = run.time(args.steps, args.warmup, replays, eager=args.eager)
     ms_step = t["median"]
     # spot check of the last buffers against the first (same input => same bits)
@@ -395,7 +450,7 @@ def main():
     latency_us = run.single_call_latency_us()
 
     floors = None
-    if not args.no_floors and fused is None and not args.dense and not args.backward:
+    if not args.no_floors and fused is None and not args.dense and not args.backward and ffn is None:
         # the library's own pure copy (C_a = 0) on the same tensors and rotation, and a call
         # with nothing to do (1 x 1 x 1 x 1, C_a = 0): what is left above them is the method's
         copy_t = Runner(wl, args.rotate_bytes, args.warm_cache, ca=0).time(args.steps, min(args.warmup, 200), replays,
@@ -409,7 +464,10 @@ def main():
 
     sec = ms_step * 1e-3
     wl_name = wl.name
-    if fused is not None:
+    if ffn is not None:
+        wl_name += "_convffn" if ffn == "ffn" else "_residual_step" + ("_lkc" if args.lkc else "")
+        roof = ffn_roofline_of(wl, sec, ffn == "step")
+    elif fused is not None:
         wl_name += "_fused" + ("_lkc" if args.lkc else "") + ("_res" if args.residual else "")
         roof = fused_roofline_of(wl, sec, args.lkc, args.residual)
     elif args.dense:
@@ -422,7 +480,10 @@ def main():
         roof = roofline_of(wl, sec)
     traffic, traffic_src = (None, None) if args.warm_cache else profiled_traffic(wl_name)
     roof.update({
-        "kernel": (f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)"
+        "kernel": ("pointwise_kernel (first layer, GELU in its epilogue) + ffn_branch_kernel + pointwise_kernel (second layer)"
+                   + ("; then forward_kernel (F_res) + pointwise_kernel (Conv_fuse, residual)" if ffn == "step" else "")
+                   if ffn is not None else
+                   f"forward_kernel<{wl.Ks}, RY, {'float' if wl.dtype == wk.F32 else 'bf16'}> (the only kernel of a step)"
                    if fused is None and not args.dense and not args.backward else
                    "corr_mfma_kernel (grad_out x correlation on the matrix cores), sums, estimator kernels, forward_kernel on grad_out with flipped kernels and the GAP term"
                    if args.backward else
@@ -436,7 +497,8 @@ def main():
         "kernel_us": ms_step * 1e3,
     })
     res = {
-        "metric": ("convattn_dense_fwd_mpixel_per_s" if args.dense else "convattn_bwd_mpixel_per_s" if args.backward else
+        "metric": ("convffn_fwd_mpixel_per_s" if ffn == "ffn" else "esc_residual_step_fwd_mpixel_per_s" if ffn == "step" else
+                   "convattn_dense_fwd_mpixel_per_s" if args.dense else "convattn_bwd_mpixel_per_s" if args.backward else
                    "convattn_fwd_mpixel_per_s" if fused is None else "convattn_fused_fwd_mpixel_per_s"),
         "value": wl.pixels / sec / 1e6,
         "unit": "Mpixel/s",
@@ -536,6 +598,24 @@ def main():
             del r2
             torch.cuda.empty_cache()
         res["backward_workloads"] = bwd
+        # ConvFFN (hidden width 2 C) and the whole residual step of Eq. 3 line 3
+        ffs = []
+        for idx, kind in ((1, "ffn"), (2, "ffn"), (1, "step"), (2, "step")):
+            w2 = wk.make_config(idx)
+            name2 = w2.name + ("_convffn" if kind == "ffn" else "_residual_step")
+            if name2 == wl_name:
+                continue
+            r2 = Runner(w2, args.rotate_bytes, args.warm_cache, ffn=kind,
+                        fused={"lkc": False, "residual": False} if kind == "step" else None)
+            t2 = r2.time(100, 100, 15, eager=args.eager)
+            s2 = t2["median"] * 1e-3
+            rf = ffn_roofline_of(w2, s2, kind == "step")
+            ffs.append({"workload": name2, "dtype": wk.DTYPE_NAMES[w2.dtype], "us_per_step": t2["median"] * 1e3,
+                        "mpixel_per_s": w2.pixels / s2 / 1e6, "bound": rf["bound"], "frac": rf["frac"],
+                        "hbm_gbps": rf["hbm_gbps"], "mfma_tflops": rf["mfma_tflops"], "steps": 100, "warmup": 100, "replays": 15})
+            del r2
+            torch.cuda.empty_cache()
+        res["ffn_workloads"] = ffs
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)

@@ -171,7 +171,8 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
  * and prints no equation; as that network is described - two point-wise layers with a
  * depth-wise convolution branch between them:
  *
- *   U   = gelu(w1 . x + b1)            w1 [C_h, C] row-major, b1 [C_h] or NULL; exact (erf) GELU
+ *   U   = gelu(w1 . x + b1)            w1 [C_h, C] row-major, b1 [C_h] or NULL; the erf form of
+ *                                      GELU (not its tanh approximation), erf evaluated to 1.5e-7
  *   V   = U + gelu(k_dw (*) U + b_dw)  k_dw [C_h, 3, 3] depth-wise, cross-correlation, zero
  *                                      padding 1; b_dw [C_h] or NULL
  *   out = w2 . V + b2                  w2 [C, C_h] row-major, b2 [C] or NULL

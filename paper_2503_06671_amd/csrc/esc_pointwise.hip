@@ -54,8 +54,25 @@ __device__ __forceinline__ uint16_t pw_f32_to_bf16(float f)
 __device__ __forceinline__ float pw_load1(const float *p) { return *p; }
 __device__ __forceinline__ float pw_load1(const bf16s *p) { return __uint_as_float((uint32_t)p->bits << 16); }
 
-// exact (erf) GELU, the activation of ConvFFN's first layer (Eq. 3)
-__device__ __forceinline__ float pw_gelu(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f)); }
+// GELU of ConvFFN, v * Phi(v) with the erf of Phi evaluated by the rational approximation
+// 7.1.26 of Abramowitz and Stegun's handbook (|error| <= 1.5e-7 in erf, i.e. <= 1e-7 |v| in the
+// result: a hundredth of the fp32 parity bar): erf(a) = 1 - (a1 t + ... + a5 t^5) exp(-a^2),
+// t = 1 / (1 + p a), a = |v| / sqrt(2).  A reciprocal, an exponential and a dozen multiply-adds,
+// no branch - a third of the library erf's instructions, which at one GELU per hidden element
+// were a quarter of this kernel's time with bf16 storage.
+__device__ __forceinline__ float pw_gelu(float v)
+{
+    const float a = fabsf(v) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, a, 1.f));
+    float q = fmaf(1.061405429f, t, -1.453152027f);
+    q = fmaf(q, t, 1.421413741f);
+    q = fmaf(q, t, -0.284496736f);
+    q = fmaf(q, t, 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(a * a * -1.44269504088896340736f);
+    const float erf_a = fmaf(-q * t, e, 1.f);          // erf(|v| / sqrt 2) >= 0
+    const float h = 0.5f * v;
+    return fmaf(fabsf(h), erf_a, h);                   // 0.5 v (1 + sign(v) erf_a)
+}
 
 typedef __amdgpu_buffer_rsrc_t Rsrc;
 constexpr int kRawBuffer = 0x00020000;     // raw buffer (no stride, no swizzle), 32-bit data format

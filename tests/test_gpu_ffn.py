@@ -188,3 +188,18 @@ def test_replays_from_a_captured_graph(oracle):
         assert torch.equal(out, eager)
     ref = oracle.convffn_forward(x_np, p["w1"], p["k"], p["w2"], F32, b1=p["b1"], bk=p["bk"], b2=p["b2"])
     gu.assert_att_close(eager.cpu().numpy().astype(np.float64), ref, F32, "graph")
+
+
+def test_gelu_of_the_library_against_the_erf_definition():
+    # one channel, identity weights, no branch kernel: out = gelu(x) + gelu(0) = gelu(x); the library
+    # evaluates erf by a rational approximation stated to hold 1.5e-7 - measured here on a fine grid
+    import math
+    H, W = 64, 128
+    x_np = np.linspace(-9.0, 9.0, H * W, dtype=np.float32).reshape(1, 1, H, W)
+    one = np.ones((1, 1), np.float32)
+    p = {"w1": one, "b1": None, "k": np.zeros((1, 3, 3), np.float32), "bk": None, "w2": one, "b2": None}
+    got = run_ffn(x_np, F32, p).astype(np.float64).ravel()
+    want = np.array([0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in x_np.astype(np.float64).ravel()])
+    err = np.abs(got - want)
+    assert err.max() <= 1e-6, err.max()
+    assert (err <= 3e-7 * np.maximum(np.abs(want), 1.0)).all()
