@@ -813,6 +813,18 @@ esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H,
     hipStream_t s = (hipStream_t)stream;
     const bool bf16 = dt == ESC_BF16;
     char *u = (char *)workspace, *v = u + need / 2;
+    if (!bf16) {
+        // fp32 storage with up to 64 channels and a hidden layer of up to 128: the whole network in
+        // one launch, U and V staying on the chip (the workspace is not touched)
+        FfnStreamParams fs{};
+        fs.x = (const float *)x;
+        fs.out = (float *)out;
+        fs.w1 = w1, fs.b1 = b1, fs.k = k_dw, fs.bk = b_dw, fs.w2 = w2, fs.b2 = b2;
+        fs.N = N, fs.C = C, fs.H = H, fs.W = W, fs.Ch = C_h;
+        const hipError_t e = launch_ffn_stream(fs, s);
+        if (e == hipSuccess) return ESC_OK;
+        if (e != hipErrorNotSupported) return ESC_ERR_HIP;
+    }
     // U = gelu(W1 . x + b1)
     PointwiseParams p1{};
     p1.src1 = x;

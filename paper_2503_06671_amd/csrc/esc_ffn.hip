@@ -159,6 +159,272 @@ __global__ __launch_bounds__(kFbThreads) void ffn_branch_kernel(const FfnBranchP
     }
 }
 
+
+// ---- the whole network in one kernel (fp32 storage, C <= 64, Ch <= 128) ------------------
+//
+// A block streams down a strip of the image 32 columns wide (30 output columns and one
+// halo column each side) over a band of rows.  Per input row y:
+//   1. the row's C x 32 values are in LDS (fetched a row ahead);
+//   2. wavefront w forms U[32 w .. 32 w + 31][32 columns] = gelu(W1 . x + b1) with
+//      v_mfma_f32_32x32x2_f32 - its 32 x 64 tile of W1 lives in registers, in the A
+//      operand's layout - and writes it, zeroed outside the image (the branch pads U with
+//      zeros), into row y's slot of a three-row ring in LDS;
+//   3. the same wavefront applies the depth-wise branch to its own 32 hidden channels for
+//      output row y - 1 (lane = one channel and sixteen columns; rows y - 2, y - 1, y from the
+//      ring) and writes V over the ring's oldest row: the first layer, the GELU, the ring
+//      and the branch never leave the wavefront, so no block barrier is needed up to here;
+//   4. after a barrier, wavefront (mt, kh) multiplies W2's rows 32 mt .. + 31 with the 64
+//      hidden channels 64 kh .. + 63 of V (its 32 x 64 tile of W2 in registers); the kh = 1
+//      wavefronts hand their partial sums over through LDS, the kh = 0 ones add them and
+//      b2 and store 30 columns of output row y - 1 - while the kh = 1 ones already start on
+//      the next row.
+// Two barriers per row, 75 KB of LDS (two blocks per compute unit, so that one block's
+// products overlap the other's GELUs), weights read once per block.  The band's first two
+// input rows are recomputed by the band above (rows_per_band + 2 first-layer rows for
+// rows_per_band output rows), the strips' halo columns by their neighbours (32 for 30).
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kFsThreads = 256;
+constexpr int kFsC = 64;        // input (and output) channels the tiles hold
+constexpr int kFsCh = 128;      // hidden channels the tiles hold
+constexpr int kFsNp = 32;       // columns of a strip, halo included
+constexpr int kFsOut = 30;      // output columns of a strip
+constexpr int kFsPitch = 33;    // floats between two channel rows of the ring (odd: lanes on different channels, same column, hit different banks)
+constexpr int kFsXFloats = 2 * kFsC * kFsNp;
+constexpr int kFsRingFloats = 3 * kFsCh * kFsPitch;
+constexpr int kFsRedFloats = 2 * 16 * 64;
+constexpr int kFsBiasFloats = kFsCh + kFsC;
+constexpr size_t kFsLdsBytes = (size_t)(kFsXFloats + kFsRingFloats + kFsRedFloats + kFsBiasFloats) * sizeof(float);
+
+static_assert(kFsCh * (kFsC + 1) <= kFsRingFloats && kFsC * (kFsCh + 1) <= kFsRingFloats,
+              "the weights pass through the ring's space on their way into registers");
+
+extern __shared__ __align__(16) float fs_lds[];
+
+__global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStreamParams p)
+{
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int mt = wave & 1, kh = wave >> 1;
+    const int C = p.C, Ch = p.Ch, H = p.H, W = p.W;
+
+    float *sX = fs_lds;                     // [2][kFsC][kFsNp]
+    float *ring = sX + kFsXFloats;          // [3][kFsCh][kFsPitch]
+    float *red = ring + kFsRingFloats;      // [2 mt][16][64]
+    float *sB1 = red + kFsRedFloats;        // [kFsCh] first layer's biases, zeros beyond Ch
+    float *sB2 = sB1 + kFsCh;               // [kFsC] second layer's
+
+    // which strip, band and image
+    const unsigned per_img = (unsigned)p.strips * (unsigned)p.bands;
+    const unsigned n = blockIdx.x / per_img;
+    const unsigned rem = blockIdx.x - n * per_img;
+    const int band = (int)(rem / (unsigned)p.strips), strip = (int)(rem - (unsigned)band * (unsigned)p.strips);
+    const int x0 = strip * kFsOut - 1;                    // image column of the strip's column 0
+    const int y0 = band * p.rows_per_band;                // first output row
+    const int rows_out = min(p.rows_per_band, H - y0);    // >= 1
+    const size_t plane = (size_t)H * W;
+    const float *xin = p.x + (size_t)n * C * plane;
+    const unsigned plane_bytes = (unsigned)plane * 4u;
+    const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc((void *)(p.out + (size_t)n * C * plane), 0,
+                                                                          (int)((unsigned)C * plane_bytes), 0x00020000);
+
+    // ---- weights into registers, in the matrix instructions' A layout.  They pass through
+    // LDS (the ring's space, rows of an odd pitch), fetched by the block with coalesced loads:
+    // fetched by every lane for itself - thirty-two rows per load instruction - the blocks
+    // moved half a gigabyte through the L2 for 64 KB of weights ----
+    // first layer: lane holds W1[32 w + l32][2 kp + half], kp = 0 .. 31
+    float a1[32], a2[32];
+    {
+        constexpr int kP1 = kFsC + 1;
+        for (int i0 = tid; i0 < kFsCh * kFsC; i0 += 8 * kFsThreads) {
+            float v[8];
+            bool in[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {  // eight loads out together, their uses behind them
+                const int i = i0 + u * kFsThreads, row = i / kFsC, col = i - row * kFsC;
+                in[u] = row < Ch && col < C;
+                v[u] = p.w1[in[u] ? (size_t)row * C + col : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kFsThreads, row = i / kFsC, col = i - row * kFsC;
+                ring[row * kP1 + col] = in[u] ? v[u] : 0.f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kp = 0; kp < 32; ++kp) a1[kp] = ring[(32 * wave + l32) * kP1 + 2 * kp + half];
+        __syncthreads();
+        // second layer: lane holds W2[32 mt + l32][64 kh + 2 kp + half], kp = 0 .. 31
+        constexpr int kP2 = kFsCh + 1;
+        for (int i0 = tid; i0 < kFsC * kFsCh; i0 += 8 * kFsThreads) {
+            float v[8];
+            bool in[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kFsThreads, row = i / kFsCh, col = i - row * kFsCh;
+                in[u] = row < C && col < Ch;
+                v[u] = p.w2[in[u] ? (size_t)row * Ch + col : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kFsThreads, row = i / kFsCh, col = i - row * kFsCh;
+                ring[row * kP2 + col] = in[u] ? v[u] : 0.f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kp = 0; kp < 32; ++kp) a2[kp] = ring[(32 * mt + l32) * kP2 + 64 * kh + 2 * kp + half];
+        // (the barrier in front of the row loop comes before anything is written to the ring)
+    }
+    // biases into LDS (the first barrier below covers them)
+    if (tid < kFsCh) sB1[tid] = (p.b1 != nullptr && tid < Ch) ? p.b1[tid] : 0.f;
+    if (tid < kFsC) sB2[tid] = (p.b2 != nullptr && tid < C) ? p.b2[tid] : 0.f;
+    // the branch: lane = hidden channel 32 w + l32, columns 16 half .. 16 half + 15 of the strip
+    const int chb = 32 * wave + l32;
+    float kd[9], bkd;
+    {
+        const bool in = chb < Ch;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const float v = p.k[in ? (size_t)chb * 9 + t : 0];
+            kd[t] = in ? v : 0.f;
+        }
+        const float vb = p.bk != nullptr ? p.bk[in ? chb : 0] : 0.f;
+        bkd = (in && p.bk != nullptr) ? vb : 0.f;
+    }
+
+    // ---- this thread's share of an input row: column tid % 32 of channels tid / 32 + 8 i ----
+    const int xpx = tid & 31, xc0 = tid >> 5;
+    const int gx_in = x0 + xpx;
+    const bool col_in = gx_in >= 0 && gx_in < W;
+    // (the loads' results are not touched until they are put into LDS a row later: a value
+    // used right behind its load makes the compiler wait for the load there)
+    auto fetch_row = [&](int gy, float (&v)[8]) {
+        const bool row_in = gy >= 0 && gy < H;
+        const size_t off = (size_t)(row_in ? gy : 0) * W + (size_t)(col_in ? gx_in : 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = xc0 + 8 * i;
+            v[i] = xin[(size_t)(c < C ? c : 0) * plane + off];
+        }
+    };
+    auto put_row = [&](const float (&v)[8], int gy, int buf) {
+        const bool in = col_in && gy >= 0 && gy < H;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            sX[buf * (kFsC * kFsNp) + (xc0 + 8 * i) * kFsNp + xpx] = (in && xc0 + 8 * i < C) ? v[i] : 0.f;
+    };
+
+    float xr[8];
+    fetch_row(y0 - 1, xr);
+    put_row(xr, y0 - 1, 0);
+    fetch_row(y0, xr);
+    __syncthreads();
+
+    const bool ucol_in = (x0 + l32) >= 0 && (x0 + l32) < W;   // the column a lane's accumulators hold
+    const int steps = rows_out + 2;
+    for (int r = 0; r < steps; ++r) {
+        const int gy = y0 - 1 + r;   // this step's input row
+        // next row into the other buffer (read last a step ago, before that step's barriers), the row after it asked for
+        if (r + 1 < steps) {
+            put_row(xr, gy + 1, (r + 1) & 1);
+            if (r + 2 < steps) fetch_row(gy + 2, xr);
+        }
+        // ---- first layer on row gy: U tile = W1 tile . x row ----
+        {
+            f32x16 acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+            const float *bx = sX + (r & 1) * (kFsC * kFsNp) + half * kFsNp + l32;
+            // the biases of the rows this lane's accumulators hold, asked for in front of the
+            // products (read one by one where they are used, each read's latency was waited for)
+            const float *b1p = sB1 + 32 * wave + 4 * half;
+            float b1v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) b1v[i] = b1p[8 * (i >> 2) + (i & 3)];
+#pragma unroll
+            for (int kp = 0; kp < 32; ++kp)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[kp], bx[2 * kp * kFsNp], acc, 0, 0, 0);
+            const bool live = ucol_in && gy >= 0 && gy < H;
+            float *ur = ring + (r % 3) * (kFsCh * kFsPitch) + (32 * wave + 4 * half) * kFsPitch + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = 8 * (i >> 2) + (i & 3);   // (+ 4 half: in ur and b1p)
+                const float u = fb_gelu(acc[i] + b1v[i]);
+                ur[m * kFsPitch] = live ? u : 0.f;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();  // (a wavefront's LDS accesses are carried out in order)
+        // ---- the branch on output row gy - 1, this wavefront's 32 hidden channels ----
+        const int vslot = (r + 1) % 3;    // the ring's oldest row, (r - 2) % 3: V goes there
+        if (r >= 2) {
+            float a[3][18];
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const float *row = ring + ((r + 1 + i) % 3) * (kFsCh * kFsPitch) + chb * kFsPitch;
+#pragma unroll
+                for (int j = 0; j < 18; ++j) {
+                    const int px = 16 * half - 1 + j;   // -1 and 32 lie outside the strip: only halo columns need them
+                    const float v = row[px < 0 ? 0 : (px > 31 ? 31 : px)];
+                    a[i][j] = (px >= 0 && px <= 31) ? v : 0.f;
+                }
+            }
+            float vv[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                float s = bkd;
+                s = fmaf(kd[0], a[0][j], s), s = fmaf(kd[1], a[0][j + 1], s), s = fmaf(kd[2], a[0][j + 2], s);
+                s = fmaf(kd[3], a[1][j], s), s = fmaf(kd[4], a[1][j + 1], s), s = fmaf(kd[5], a[1][j + 2], s);
+                s = fmaf(kd[6], a[2][j], s), s = fmaf(kd[7], a[2][j + 1], s), s = fmaf(kd[8], a[2][j + 2], s);
+                vv[j] = a[1][j + 1] + fb_gelu(s);
+            }
+            __builtin_amdgcn_wave_barrier();  // every lane has read the oldest row before any lane overwrites it
+            float *vr = ring + vslot * (kFsCh * kFsPitch) + chb * kFsPitch + 16 * half;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) vr[j] = vv[j];
+        }
+        __syncthreads();  // V of all hidden channels (and the next input row) is in LDS
+        // ---- second layer: W2 tile (32 output channels x 64 hidden channels) . V ----
+        f32x16 acc2;
+        if (r >= 2) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc2[i] = 0.f;
+            const float *bv = ring + vslot * (kFsCh * kFsPitch) + (64 * kh + half) * kFsPitch + l32;
+#pragma unroll
+            for (int kp = 0; kp < 32; ++kp)
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[kp], bv[2 * kp * kFsPitch], acc2, 0, 0, 0);
+            if (kh == 1) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) red[(mt * 16 + i) * 64 + lane] = acc2[i];
+            }
+        }
+        __syncthreads();  // the partial sums are in LDS; nobody reads V any more
+        if (r >= 2 && kh == 0) {
+            const int gyo = gy - 1, gxo = x0 + l32;
+            const bool st_ok = l32 >= 1 && l32 <= kFsOut && gxo < W;   // (gyo < H by the loop's bound)
+            float rv[16], bv[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                rv[i] = red[(mt * 16 + i) * 64 + lane];
+                bv[i] = sB2[32 * mt + 8 * (i >> 2) + 4 * half + (i & 3)];
+            }
+            // buffer stores on a resource that is the image's output: what is not to be
+            // written gets an offset beyond it and is dropped - no branches
+            const unsigned px_off = (unsigned)(gyo * W + gxo) * 4u;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int co = 32 * mt + 8 * (i >> 2) + 4 * half + (i & 3);
+                const float v = acc2[i] + rv[i] + bv[i];
+                const unsigned off = (st_ok && co < C) ? (unsigned)co * plane_bytes + px_off : 0x80000000u;
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rout, (int)off, 0, 2 /* non-temporal */);
+            }
+        }
+    }
+}
+
 }  // namespace
 
 __attribute__((visibility("hidden"))) hipError_t launch_ffn_branch(const FfnBranchParams &p, bool bf16, hipStream_t s)
@@ -182,6 +448,42 @@ __attribute__((visibility("hidden"))) hipError_t launch_ffn_branch(const FfnBran
         else
             hipLaunchKernelGGL((ffn_branch_kernel<float, false>), dim3((unsigned)grid), dim3(kFbThreads), 0, s, p);
     }
+    return hipGetLastError();
+}
+
+__attribute__((visibility("hidden"))) hipError_t launch_ffn_stream(const FfnStreamParams &p, hipStream_t s)
+{
+    if (p.N < 1 || p.C < 1 || p.H < 1 || p.W < 1 || p.Ch < 1) return hipSuccess;
+    if (p.C > kFsC || p.Ch > kFsCh) return hipErrorNotSupported;
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return hipErrorInvalidDevice;
+        cus = n > 0 ? n : 1;
+    }
+    static bool lds_granted = false;
+    if (!lds_granted) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ffn_stream_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFsLdsBytes);
+        if (e != hipSuccess) return e;
+        lds_granted = true;
+    }
+    FfnStreamParams q = p;
+    q.strips = (p.W + kFsOut - 1) / kFsOut;
+    // the tallest bands that still give every block slot (two per compute unit) a block
+    q.rows_per_band = 4;
+    for (int rb = 32; rb > 4; rb /= 2) {
+        const long blocks = (long)p.N * q.strips * ((p.H + rb - 1) / rb);
+        if (blocks >= 2L * cus) {
+            q.rows_per_band = rb;
+            break;
+        }
+    }
+    q.bands = (p.H + q.rows_per_band - 1) / q.rows_per_band;
+    const long grid = (long)p.N * q.strips * q.bands;
+    if (grid >= (1L << 31)) return hipErrorNotSupported;
+    hipLaunchKernelGGL(ffn_stream_kernel, dim3((unsigned)grid), dim3(kFsThreads), kFsLdsBytes, s, q);
     return hipGetLastError();
 }
 

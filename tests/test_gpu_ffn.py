@@ -61,6 +61,11 @@ def check_ffn(oracle, seed, N, C, H, W, Ch, dtype, bias=True, what=""):
     (1, 64, 21, 40, 128),     # the paper's width with a hidden layer twice as wide: two passes over the inputs
     (3, 24, 10, 16, 72),      # a batch; more than 64 hidden channels
     (1, 33, 17, 32, 65),      # channel counts one beyond the stages of 32 and the passes of 64
+    (2, 70, 9, 11, 12),       # more than 64 channels: fp32 storage takes the three-launch path too (element-wise fetches)
+    (1, 8, 12, 16, 136),      # a hidden layer beyond 128: the same, with 16-byte pieces
+    (1, 64, 7, 61, 128),      # fp32: the one-launch kernel at its widest, three strips with a ragged last one
+    (2, 5, 37, 95, 7),        # fp32: several bands and strips, the last strip five columns wide
+    (1, 3, 70, 30, 4),        # fp32: exactly one strip, bands that do not divide the height
 ])
 def test_small_and_ragged_shapes(oracle, shape, dtype):
     N, C, H, W, Ch = shape
