@@ -197,8 +197,8 @@ constexpr int kFsRedFloats = 2 * 16 * 64;
 constexpr int kFsBiasFloats = kFsCh + kFsC;
 constexpr size_t kFsLdsBytes = (size_t)(kFsXFloats + kFsRingFloats + kFsRedFloats + kFsBiasFloats) * sizeof(float);
 
-static_assert(kFsCh * (kFsC + 1) <= kFsRingFloats && kFsC * (kFsCh + 1) <= kFsRingFloats,
-              "the weights pass through the ring's space on their way into registers");
+static_assert(kFsCh * (kFsC + 1) + kFsC * (kFsCh + 1) <= kFsXFloats + kFsRingFloats,
+              "the weights pass through the row buffers' and the ring's space on their way into registers");
 
 extern __shared__ __align__(16) float fs_lds[];
 
@@ -230,72 +230,6 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
     const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc((void *)(p.out + (size_t)n * C * plane), 0,
                                                                           (int)((unsigned)C * plane_bytes), 0x00020000);
 
-    // ---- weights into registers, in the matrix instructions' A layout.  They pass through
-    // LDS (the ring's space, rows of an odd pitch), fetched by the block with coalesced loads:
-    // fetched by every lane for itself - thirty-two rows per load instruction - the blocks
-    // moved half a gigabyte through the L2 for 64 KB of weights ----
-    // first layer: lane holds W1[32 w + l32][2 kp + half], kp = 0 .. 31
-    float a1[32], a2[32];
-    {
-        constexpr int kP1 = kFsC + 1;
-        for (int i0 = tid; i0 < kFsCh * kFsC; i0 += 8 * kFsThreads) {
-            float v[8];
-            bool in[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {  // eight loads out together, their uses behind them
-                const int i = i0 + u * kFsThreads, row = i / kFsC, col = i - row * kFsC;
-                in[u] = row < Ch && col < C;
-                v[u] = p.w1[in[u] ? (size_t)row * C + col : 0];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = i0 + u * kFsThreads, row = i / kFsC, col = i - row * kFsC;
-                ring[row * kP1 + col] = in[u] ? v[u] : 0.f;
-            }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kp = 0; kp < 32; ++kp) a1[kp] = ring[(32 * wave + l32) * kP1 + 2 * kp + half];
-        __syncthreads();
-        // second layer: lane holds W2[32 mt + l32][64 kh + 2 kp + half], kp = 0 .. 31
-        constexpr int kP2 = kFsCh + 1;
-        for (int i0 = tid; i0 < kFsC * kFsCh; i0 += 8 * kFsThreads) {
-            float v[8];
-            bool in[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = i0 + u * kFsThreads, row = i / kFsCh, col = i - row * kFsCh;
-                in[u] = row < C && col < Ch;
-                v[u] = p.w2[in[u] ? (size_t)row * Ch + col : 0];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = i0 + u * kFsThreads, row = i / kFsCh, col = i - row * kFsCh;
-                ring[row * kP2 + col] = in[u] ? v[u] : 0.f;
-            }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kp = 0; kp < 32; ++kp) a2[kp] = ring[(32 * mt + l32) * kP2 + 64 * kh + 2 * kp + half];
-        // (the barrier in front of the row loop comes before anything is written to the ring)
-    }
-    // biases into LDS (the first barrier below covers them)
-    if (tid < kFsCh) sB1[tid] = (p.b1 != nullptr && tid < Ch) ? p.b1[tid] : 0.f;
-    if (tid < kFsC) sB2[tid] = (p.b2 != nullptr && tid < C) ? p.b2[tid] : 0.f;
-    // the branch: lane = hidden channel 32 w + l32, columns 16 half .. 16 half + 15 of the strip
-    const int chb = 32 * wave + l32;
-    float kd[9], bkd;
-    {
-        const bool in = chb < Ch;
-#pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            const float v = p.k[in ? (size_t)chb * 9 + t : 0];
-            kd[t] = in ? v : 0.f;
-        }
-        const float vb = p.bk != nullptr ? p.bk[in ? chb : 0] : 0.f;
-        bkd = (in && p.bk != nullptr) ? vb : 0.f;
-    }
-
     // ---- this thread's share of an input row: column tid % 32 of channels tid / 32 + 8 i ----
     const int xpx = tid & 31, xc0 = tid >> 5;
     const int gx_in = x0 + xpx;
@@ -319,7 +253,62 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
     };
 
     float xr[8];
-    fetch_row(y0 - 1, xr);
+    fetch_row(y0 - 1, xr);  // the band's first input row travels while the weights are staged
+
+    // ---- weights into registers, in the matrix instructions' A layout.  They pass through
+    // LDS (the row buffers' and the ring's space, rows of an odd pitch), fetched by the block with coalesced loads:
+    // fetched by every lane for itself - thirty-two rows per load instruction - the blocks
+    // moved half a gigabyte through the L2 for 64 KB of weights ----
+    // first layer: lane holds W1[32 w + l32][2 kp + half]; second layer: W2[32 mt + l32][64 kh + 2 kp + half]
+    float a1[32], a2[32];
+    {
+        constexpr int kP1 = kFsC + 1, kP2 = kFsCh + 1;
+        float *s1 = fs_lds, *s2 = fs_lds + kFsCh * kP1;  // both matrices at once, over the row buffers and the ring
+        for (int i0 = tid; i0 < kFsCh * kFsC; i0 += 8 * kFsThreads) {
+            float v[8], w[8];
+            bool in1[8], in2[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {  // sixteen loads out together, their uses behind them
+                const int i = i0 + u * kFsThreads;
+                const int r1 = i / kFsC, c1 = i - r1 * kFsC, r2 = i / kFsCh, c2 = i - r2 * kFsCh;
+                in1[u] = r1 < Ch && c1 < C;
+                in2[u] = r2 < C && c2 < Ch;
+                v[u] = p.w1[in1[u] ? (size_t)r1 * C + c1 : 0];
+                w[u] = p.w2[in2[u] ? (size_t)r2 * Ch + c2 : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kFsThreads;
+                const int r1 = i / kFsC, c1 = i - r1 * kFsC, r2 = i / kFsCh, c2 = i - r2 * kFsCh;
+                s1[r1 * kP1 + c1] = in1[u] ? v[u] : 0.f;
+                s2[r2 * kP2 + c2] = in2[u] ? w[u] : 0.f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kp = 0; kp < 32; ++kp) {
+            a1[kp] = s1[(32 * wave + l32) * kP1 + 2 * kp + half];
+            a2[kp] = s2[(32 * mt + l32) * kP2 + 64 * kh + 2 * kp + half];
+        }
+        __syncthreads();  // everyone has its weights: the space is the row buffers' and the ring's from here on
+    }
+    // biases into LDS (the first barrier below covers them)
+    if (tid < kFsCh) sB1[tid] = (p.b1 != nullptr && tid < Ch) ? p.b1[tid] : 0.f;
+    if (tid < kFsC) sB2[tid] = (p.b2 != nullptr && tid < C) ? p.b2[tid] : 0.f;
+    // the branch: lane = hidden channel 32 w + l32, columns 16 half .. 16 half + 15 of the strip
+    const int chb = 32 * wave + l32;
+    float kd[9], bkd;
+    {
+        const bool in = chb < Ch;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const float v = p.k[in ? (size_t)chb * 9 + t : 0];
+            kd[t] = in ? v : 0.f;
+        }
+        const float vb = p.bk != nullptr ? p.bk[in ? chb : 0] : 0.f;
+        bkd = (in && p.bk != nullptr) ? vb : 0.f;
+    }
+
     put_row(xr, y0 - 1, 0);
     fetch_row(y0, xr);
     __syncthreads();
@@ -471,6 +460,9 @@ __attribute__((visibility("hidden"))) hipError_t launch_ffn_stream(const FfnStre
     }
     FfnStreamParams q = p;
     q.strips = (p.W + kFsOut - 1) / kFsOut;
+    // a block lasts as long whatever the image's size (its weights' way into registers, then six
+    // rows one after the other): with too few blocks to fill the chip the three launches are faster
+    if ((long)p.N * q.strips * ((p.H + 3) / 4) < 3L * cus / 2) return hipErrorNotSupported;
     // the tallest bands that still give every block slot (two per compute unit) a block
     q.rows_per_band = 4;
     for (int rb = 32; rb > 4; rb /= 2) {

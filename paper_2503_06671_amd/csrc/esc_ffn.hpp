@@ -22,7 +22,8 @@ hipError_t launch_ffn_branch(const FfnBranchParams &p, bool bf16, hipStream_t s)
 
 // The whole network in one launch for fp32 storage, C <= 64 and Ch <= 128 (neither U nor V
 // leaves the chip): out = w2 . V + b2, V = U + gelu(k (*) U + bk), U = gelu(w1 . x + b1).
-// Returns hipErrorNotSupported, with nothing launched, for other shapes.
+// Returns hipErrorNotSupported, with nothing launched, for other shapes and for problems of
+// too few strips and bands to fill the chip.
 struct FfnStreamParams {
     const float *x;
     float *out;

@@ -63,12 +63,17 @@ def check_ffn(oracle, seed, N, C, H, W, Ch, dtype, bias=True, what=""):
     (1, 33, 17, 32, 65),      # channel counts one beyond the stages of 32 and the passes of 64
     (2, 70, 9, 11, 12),       # more than 64 channels: fp32 storage takes the three-launch path too (element-wise fetches)
     (1, 8, 12, 16, 136),      # a hidden layer beyond 128: the same, with 16-byte pieces
-    (1, 64, 7, 61, 128),      # fp32: the one-launch kernel at its widest, three strips with a ragged last one
-    (2, 5, 37, 95, 7),        # fp32: several bands and strips, the last strip five columns wide
-    (1, 3, 70, 30, 4),        # fp32: exactly one strip, bands that do not divide the height
+    # fp32 storage, batches large enough for the one-launch kernel (it wants 384 strips x bands of four rows):
+    (64, 64, 7, 61, 128),     # at its widest, three strips with a ragged last one, two bands
+    (12, 5, 37, 95, 7),       # several bands and strips, the last strip five columns wide
+    (24, 3, 70, 30, 4),       # exactly one strip, bands that do not divide the height
+    (8, 9, 200, 64, 20),      # bands of eight rows
+    (64, 2, 100, 58, 3),      # bands of thirty-two rows, the last one four rows high
 ])
 def test_small_and_ragged_shapes(oracle, shape, dtype):
     N, C, H, W, Ch = shape
+    if N > 3 and dtype == BF16:
+        pytest.skip("a batch chosen to reach the fp32 one-launch kernel; bf16 storage is covered by the other shapes")
     if N * C * H * W == 1 and dtype == BF16:
         # one output that is a difference of terms: the intermediates' bf16 roundings (2^-9 of each term)
         # against the size of the result is not what the normwise bar measures
