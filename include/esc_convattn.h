@@ -182,13 +182,15 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
  * All weights are device pointers to fp32, read-only.  The point-wise layers run on the
  * matrix cores as in esc_convattn_fused_forward (fp32 storage: fp32 products; bf16 storage:
  * bf16 instructions on the stored values, each fp32 weight as two bf16 terms), the branch
- * in fp32 on the vector units; U and V pass through the workspace in the storage type, so
- * with bf16 storage they are rounded to bf16 on the way, and out once more at its store.
+ * in fp32 on the vector units.  fp32 storage with C <= 64, C_h <= 128 and an image (or batch)
+ * large enough to fill the chip with 30-column strips takes ONE launch in which U and V
+ * never leave the chip (the workspace is not touched); everything else takes three
+ * launches, U and V passing through the workspace in the storage type, so that with bf16
+ * storage they are rounded to bf16 on the way, and out once more at its store.
  * The workspace (esc_convffn_workspace_bytes, 256-byte aligned) is plain scratch: it needs
  * no esc_workspace_init and its contents are undefined after the call.  Limits: C <= 240,
- * C_h <= 240, C_h*H*W*element size < 2 GiB.  Three launches on `stream`.  The whole residual
- * step is this call followed by esc_convattn_fused_forward on its output with
- * residual = x.
+ * C_h <= 240, C_h*H*W*element size < 2 GiB.  The whole residual step is this call followed by
+ * esc_convattn_fused_forward on its output with residual = x.
  */
 size_t esc_convffn_workspace_bytes(int N, int C_h, int H, int W, esc_dtype dt);
 esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H, int W, int C_h,
