@@ -216,10 +216,15 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
     float *sB1 = red + kFsRedFloats;        // [kFsCh] first layer's biases, zeros beyond Ch
     float *sB2 = sB1 + kFsCh;               // [kFsC] second layer's
 
-    // which strip, band and image
+    // which strip, band and image.  Blocks are dealt to the eight dies (XCDs) in turn, each die
+    // with an L2 of its own: block b works on piece (b % 8) * (grid / 8) + b / 8 of the image, so
+    // that neighbouring strips and bands - which share cache lines (a strip's 128-byte row
+    // segments start one column left of a 30-column boundary) and halo rows - meet in one L2
+    const unsigned bq = gridDim.x / 8u, br = gridDim.x % 8u, xcd = blockIdx.x % 8u;
+    const unsigned piece = xcd * bq + (xcd < br ? xcd : br) + blockIdx.x / 8u;
     const unsigned per_img = (unsigned)p.strips * (unsigned)p.bands;
-    const unsigned n = blockIdx.x / per_img;
-    const unsigned rem = blockIdx.x - n * per_img;
+    const unsigned n = piece / per_img;
+    const unsigned rem = piece - n * per_img;
     const int band = (int)(rem / (unsigned)p.strips), strip = (int)(rem - (unsigned)band * (unsigned)p.strips);
     const int x0 = strip * kFsOut - 1;                    // image column of the strip's column 0
     const int y0 = band * p.rows_per_band;                // first output row
