@@ -250,14 +250,17 @@ def backward_roofline_of(wl, sec):
 def ffn_roofline_of(wl, sec, with_module):
     """ConvFFN (hidden width 2 C): x read once, out written once; the two point-wise layers on the
     matrix cores (fp32 instructions for fp32 storage; bf16 storage: bf16 instructions, two per product
-    block because every weight is two bf16 terms - `achieved` counts those), the 3 x 3 branch on the
-    vector units.  with_module: the whole residual step, the fused module's work and bytes added
+    block because every weight is two bf16 terms - `achieved` counts those), the 3 x 3 branch and the
+    two GELUs per hidden element on the vector units.  with_module: the whole residual step, the fused module's work and bytes added
     (the tensor between the two calls is written and read once more: it is an output and an input)."""
     P = wl.N * wl.H * wl.W
     Ch = 2 * wl.C
     b_alg = 2.0 * P * wl.C * wl.elem_bytes
     f_mat = 4.0 * wl.C * Ch * P
-    f_vec = 18.0 * Ch * P
+    # the branch's nine multiply-adds and two GELUs per hidden element; an erf-form GELU is priced at the
+    # operation count of the evaluation the kernels use (rational erf: a reciprocal, an exponential,
+    # nine multiply-adds, six other operations): 30 flops
+    f_vec = (18.0 + 2.0 * 30.0) * Ch * P
     if with_module:
         b_alg += 3.0 * P * wl.C * wl.elem_bytes
         f_mat += 2.0 * wl.C * wl.C * P

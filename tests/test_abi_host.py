@@ -336,6 +336,22 @@ def test_dense_bf16_kernels_fit_two_blocks_per_cu_without_scratch(lib):
         assert scratch == 0 and vgprs <= 256, (key, scratch, vgprs)
 
 
+def test_convffn_kernels_use_no_scratch(lib):
+    # ffn_stream_kernel runs two blocks per compute unit (256 registers a lane; its 76 KB of LDS
+    # are dynamic) with nothing in the private segment; so do the depth-wise branch kernel's four
+    # instantiations and the point-wise kernel's eight (storage type x 16-byte fetches x GELU)
+    found = {}
+    for name, scratch, vgprs, lds in kernel_notes():
+        for key in ("ffn_stream_kernel", "ffn_branch_kernel", "pointwise_kernel", "pointwise_bf16_kernel"):
+            if key + "E" in name or key + "I" in name:
+                found.setdefault(key, []).append((name, scratch, vgprs))
+    assert {k: len(v) for k, v in found.items()} == {"ffn_stream_kernel": 1, "ffn_branch_kernel": 4,
+                                                     "pointwise_kernel": 4, "pointwise_bf16_kernel": 4}, found
+    for key, items in found.items():
+        for name, scratch, vgprs in items:
+            assert scratch == 0 and vgprs <= 256, (name, scratch, vgprs)
+
+
 def test_three_bf16_terms_hold_an_fp32_value_exactly():
     # The backward's correlation feeds fp32 values to the bf16 matrix instructions as three terms
     # taken by truncation (top 16 bits of the value, of the remainder, of what is left).  The
