@@ -69,6 +69,10 @@ def check_ffn(oracle, seed, N, C, H, W, Ch, dtype, bias=True, what=""):
     (24, 3, 70, 30, 4),       # exactly one strip, bands that do not divide the height
     (8, 9, 200, 64, 20),      # bands of eight rows
     (64, 2, 100, 58, 3),      # bands of thirty-two rows, the last one four rows high
+    (400, 1, 1, 1, 1),        # single elements: one strip of one column, one band of one row
+    (200, 2, 2, 31, 3),       # a second strip that is one column wide, fewer rows than a band
+    (130, 3, 3, 5, 2),        # a strip narrower than its halo allows for
+
 ])
 def test_small_and_ragged_shapes(oracle, shape, dtype):
     N, C, H, W, Ch = shape
