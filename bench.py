@@ -66,8 +66,8 @@ def parse_args():
     ap.add_argument("--ffn", action="store_true",
                     help="time esc_convffn_forward (ConvFFN of Eq. 3 line 3, hidden width 2 C) instead")
     ap.add_argument("--res-step", action="store_true",
-                    help="time the whole residual step of Eq. 3 line 3: esc_convffn_forward, then "
-                         "esc_convattn_fused_forward on its output with residual = the step's input")
+                    help="time the whole residual step of Eq. 3 line 3 (esc_residual_step_forward: ConvFFN, then "
+                         "the fused module on its output with residual = the step's input)")
     ap.add_argument("--lkc", action="store_true", help="with --fused: LK^c in front of the depth-wise kernels (Eq. 5)")
     ap.add_argument("--residual", action="store_true", help="with --fused: add the residual of Eq. 3 line 3")
     return ap.parse_args()
@@ -333,20 +333,23 @@ class Runner:
             fp = wk.make_ffn_params(3000 + wl.C, wl.C, 2 * wl.C)
             self.ffn_p = {k: dev(v) for k, v in fp.items()}
             self.ffn_ws = binding.new_convffn_workspace(wl.N, 2 * wl.C, wl.H, wl.W, x0.dtype)
-            self.mid = torch.empty_like(x0)   # ConvFFN's output, the module's input
+            if ffn == "step":   # esc_residual_step_forward: one workspace, which begins with the fused call's
+                self.ws = binding.new_residual_step_workspace(wl.N, wl.C, wl.H, wl.W, self.ca, 2 * wl.C, x0.dtype,
+                                                              bool(fused and fused["lkc"]))
         self.stream = torch.cuda.Stream()
 
     def step(self, i):
         k = i % self.pairs
         if self.ffn is not None:
             p = self.ffn_p
-            dst = self.outs[k] if self.ffn == "ffn" else self.mid
-            self.binding.convffn_forward(self.xs[k], p["w1"], p["k"], p["w2"], self.ffn_ws, b1=p["b1"], b_dw=p["bk"],
-                                         b2=p["b2"], out=dst, stream=self.stream)
             if self.ffn == "step":
-                self.binding.convattn_fused_forward(
-                    self.mid, self.ca, self.lk, self.w_fuse, self.ws, b_fuse=self.b_fuse, lk_c=self.lk_c,
-                    residual=self.xs[k], gen=self.gen, out=self.outs[k], stream=self.stream)
+                self.binding.residual_step_forward(
+                    self.xs[k], p["w1"], p["k"], p["w2"], self.ca, self.lk, self.w_fuse, self.ws, b1=p["b1"],
+                    b_dw=p["bk"], b2=p["b2"], lk_c=self.lk_c, gen=self.gen, b_fuse=self.b_fuse, out=self.outs[k],
+                    stream=self.stream)
+            else:
+                self.binding.convffn_forward(self.xs[k], p["w1"], p["k"], p["w2"], self.ffn_ws, b1=p["b1"], b_dw=p["bk"],
+                                             b2=p["b2"], out=self.outs[k], stream=self.stream)
             return
         if self.backward:
             g = dict(self.grads or {})

@@ -199,6 +199,27 @@ esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H,
                                void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The residual step of the ESC block as one call (Eq. 3 line 3):
+ *
+ *   f_out = f_in + ConvAttn(ConvFFN(f_in), LK)
+ *
+ * i.e. esc_convffn_forward on f_in (its result stays in the workspace, in the storage type),
+ * then esc_convattn_fused_forward on that result with residual = f_in; every argument means
+ * what it means in those two calls (the estimator `gen` may be NULL: then DK = 0).  f_out must
+ * not overlap f_in or the workspace.  The workspace (esc_residual_step_workspace_bytes;
+ * with_lk_c != 0 when lk_c will be given) is prepared once with esc_workspace_init; it begins
+ * with the fused call's workspace, so esc_workspace_errors applies to it.  All arguments are
+ * checked before anything is enqueued.  Launches: those of the two calls (three to eight).
+ */
+size_t esc_residual_step_workspace_bytes(int N, int C, int H, int W, int C_a, int C_h, esc_dtype dt, int with_lk_c);
+esc_status esc_residual_step_forward(const void *f_in, esc_dtype dt, int N, int C, int H, int W, int C_h,
+                                     const float *w1, const float *b1, const float *k_dw, const float *b_dw,
+                                     const float *w2, const float *b2,
+                                     int C_a, const float *lk_c, const float *lk, int Ks, long lk_channel_stride,
+                                     const esc_gen_params *gen, const float *w_fuse, const float *b_fuse,
+                                     void *f_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Eq. 4 lines 1-4 (without Conv_fuse) with the DENSE large kernel of the paper's main
  * variants (Sec. 3: LK in R^{Ks x Ks x C_a x C_a}, shared by the whole model):
  *

@@ -22,7 +22,7 @@ EXPORTS = ("esc_workspace_bytes", "esc_workspace_init", "esc_workspace_errors", 
            "esc_convattn_forward", "esc_convattn_forward_noalloc", "esc_fused_workspace_bytes",
            "esc_convattn_fused_forward", "esc_dense_workspace_bytes", "esc_convattn_dense_forward",
            "esc_backward_workspace_bytes", "esc_convattn_backward", "esc_convffn_workspace_bytes",
-           "esc_convffn_forward", "esc_status_string")
+           "esc_convffn_forward", "esc_residual_step_workspace_bytes", "esc_residual_step_forward", "esc_status_string")
 NOALLOC_SCRATCH_BYTES = 1 << 20
 
 
@@ -90,6 +90,11 @@ def load_library():
         lib.esc_convffn_workspace_bytes.restype = sz
         lib.esc_convffn_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.esc_convffn_forward.restype = ci
+        lib.esc_residual_step_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci]
+        lib.esc_residual_step_workspace_bytes.restype = sz
+        lib.esc_residual_step_forward.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, ci, vp, vp, ci, cl,
+                                                  ctypes.POINTER(_GenParams), vp, vp, vp, vp, sz, vp]
+        lib.esc_residual_step_forward.restype = ci
         lib.esc_status_string.argtypes = [ci]
         lib.esc_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -333,6 +338,55 @@ def convffn_forward(x: torch.Tensor, w1: torch.Tensor, k_dw: torch.Tensor, w2: t
     _check(load_library().esc_convffn_forward(
         _ptr(x), dt, N, C, H, W, Ch, _ptr(w1), _ptr(b1), _ptr(k_dw), _ptr(b_dw), _ptr(w2), _ptr(b2), _ptr(out),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out
+
+
+def new_residual_step_workspace(N: int, C: int, H: int, W: int, Ca: int, Ch: int, dtype: torch.dtype, with_lk_c: bool,
+                                device="cuda", stream=None) -> torch.Tensor:
+    """Allocate (with torch) and prepare a workspace for esc_residual_step_forward."""
+    dt = ESC_F32 if dtype == torch.float32 else ESC_BF16
+    nbytes = int(load_library().esc_residual_step_workspace_bytes(N, C, H, W, Ca, Ch, dt, int(bool(with_lk_c))))
+    if nbytes == 0:
+        raise ValueError("bad shape for a workspace")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    workspace_init(ws, stream)
+    return ws
+
+
+def residual_step_forward(f_in: torch.Tensor, w1: torch.Tensor, k_dw: torch.Tensor, w2: torch.Tensor, Ca: int,
+                          lk: torch.Tensor, w_fuse: torch.Tensor, workspace: torch.Tensor,
+                          b1: Optional[torch.Tensor] = None, b_dw: Optional[torch.Tensor] = None,
+                          b2: Optional[torch.Tensor] = None, lk_c: Optional[torch.Tensor] = None,
+                          gen: Optional[GenParams] = None, b_fuse: Optional[torch.Tensor] = None,
+                          out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """esc_residual_step_forward: f_in + ConvAttn(ConvFFN(f_in), LK) (Eq. 3 line 3)."""
+    dt, (N, C, H, W) = _x_checked(f_in)
+    for t, name in ((w1, "w1"), (k_dw, "k_dw"), (w2, "w2"), (b1, "b1"), (b_dw, "b_dw"), (b2, "b2"),
+                    (w_fuse, "w_fuse"), (b_fuse, "b_fuse"), (lk_c, "lk_c")):
+        _dev_f32(t, name)
+    if w1.dim() != 2 or w1.shape[1] != C:
+        raise ValueError(f"w1 must be [Ch, C] with C = {C}; got {tuple(w1.shape)}")
+    Ch = int(w1.shape[0])
+    if tuple(k_dw.shape) != (Ch, 3, 3) or tuple(w2.shape) != (C, Ch):
+        raise ValueError("k_dw must be [Ch, 3, 3] and w2 [C, Ch]")
+    if (b1 is not None and b1.numel() != Ch) or (b_dw is not None and b_dw.numel() != Ch) or \
+            (b2 is not None and b2.numel() != C):
+        raise ValueError("b1 and b_dw must hold Ch values, b2 C values")
+    Ks, stride = _lk_checked(lk, int(Ca), None, None)
+    if gen is not None:
+        gen.check(int(Ca))
+    if w_fuse.numel() != C * C or (b_fuse is not None and b_fuse.numel() != C):
+        raise ValueError("w_fuse must be [C, C] and b_fuse [C]")
+    if lk_c is not None and lk_c.numel() != Ca * Ca:
+        raise ValueError("lk_c must be [Ca, Ca]")
+    if out is None:
+        out = torch.empty_like(f_in)
+    if out.dtype != f_in.dtype or out.shape != f_in.shape or not out.is_contiguous():
+        raise TypeError("out must match f_in in dtype and shape and be contiguous")
+    _check(load_library().esc_residual_step_forward(
+        _ptr(f_in), dt, N, C, H, W, Ch, _ptr(w1), _ptr(b1), _ptr(k_dw), _ptr(b_dw), _ptr(w2), _ptr(b2), int(Ca),
+        _ptr(lk_c), _ptr(lk), Ks, stride, ctypes.byref(gen.c) if gen is not None else None, _ptr(w_fuse), _ptr(b_fuse),
+        _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
     return out
 
 

@@ -867,6 +867,71 @@ esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H,
     return launch_pointwise(p2, bf16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
 }
 
+// ---- the residual step of Eq. 3 line 3 as one call ---------------------------------
+
+namespace {
+struct StepLayout {
+    size_t fused, mid_off, ffn_off, total;
+};
+bool step_layout(int N, int C, int H, int W, int Ca, int Ch, esc_dtype dt, bool with_lkc, StepLayout *l)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || Ch < 1) return false;
+    l->fused = esc_fused_workspace_bytes(N, Ca, H, W, dt, with_lkc ? 1 : 0);
+    const size_t ffn = esc_convffn_workspace_bytes(N, Ch, H, W, dt);
+    if (l->fused == 0 || ffn == 0) return false;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    l->mid_off = round_up(l->fused, kWsAlign);
+    l->ffn_off = l->mid_off + round_up((size_t)N * C * H * W * es, kWsAlign);
+    l->total = l->ffn_off + ffn;
+    return true;
+}
+}  // namespace
+
+size_t esc_residual_step_workspace_bytes(int N, int C, int H, int W, int C_a, int C_h, esc_dtype dt, int with_lk_c)
+{
+    StepLayout l;
+    if ((dt != ESC_F32 && dt != ESC_BF16) || C_a < 0 || C_a > C) return 0;
+    if (!step_layout(N, C, H, W, C_a, C_h, dt, with_lk_c != 0, &l)) return 0;
+    return l.total;
+}
+
+esc_status esc_residual_step_forward(const void *f_in, esc_dtype dt, int N, int C, int H, int W, int C_h,
+                                     const float *w1, const float *b1, const float *k_dw, const float *b_dw,
+                                     const float *w2, const float *b2, int C_a, const float *lk_c, const float *lk,
+                                     int Ks, long lk_channel_stride, const esc_gen_params *gen, const float *w_fuse,
+                                     const float *b_fuse, void *f_out, void *workspace, size_t workspace_bytes,
+                                     void *stream)
+{
+    esc_status st = check_common(f_in, dt, N, C, H, W, C_a);
+    if (st != ESC_OK) return st;
+    if (C_h < 1) return ESC_ERR_SHAPE;
+    if (f_out == nullptr) return ESC_ERR_NULL;
+    StepLayout l;
+    if (!step_layout(N, C, H, W, C_a, C_h, dt, lk_c != nullptr && C_a > 0, &l)) return ESC_ERR_SHAPE;
+    if ((st = check_ws(workspace, workspace_bytes, l.total)) != ESC_OK) return st;
+    const size_t es = dt == ESC_F32 ? 4 : 2;
+    const size_t bytes = (size_t)N * C * H * W * es;
+    if (overlaps(workspace, workspace_bytes, f_out, bytes) || overlaps(workspace, workspace_bytes, f_in, bytes) ||
+        overlaps(f_in, bytes, f_out, bytes))
+        return ESC_ERR_ALIAS;
+    char *w = (char *)workspace;
+    void *mid = w + l.mid_off;
+    // ConvFFN(F) into the workspace, then F + ConvAttn(that) - every further argument is checked by the two calls,
+    // the first of which enqueues nothing before its checks have passed; the second one's arguments that could
+    // still fail are checked here first, so that a refused call has enqueued nothing
+    if (w_fuse == nullptr || (C_a > 0 && lk == nullptr)) return ESC_ERR_NULL;
+    if (Ks < 1 || (Ks % 2) == 0) return Ks < 1 ? ESC_ERR_SHAPE : ESC_ERR_UNSUPPORTED;
+    if (Ks > kMaxKs || C > kPointwiseMaxK) return ESC_ERR_UNSUPPORTED;
+    if (lk_channel_stride != 0 && lk_channel_stride < (long)Ks * Ks) return ESC_ERR_SHAPE;
+    if (gen != nullptr && (st = check_gen(gen, C_a)) != ESC_OK) return st;
+    if (((uintptr_t)f_out % es) != 0) return ESC_ERR_SHAPE;
+    st = esc_convffn_forward(f_in, dt, N, C, H, W, C_h, w1, b1, k_dw, b_dw, w2, b2, mid, w + l.ffn_off,
+                             workspace_bytes - l.ffn_off, stream);
+    if (st != ESC_OK) return st;
+    return esc_convattn_fused_forward(mid, dt, N, C, H, W, C_a, lk_c, lk, Ks, lk_channel_stride, gen, nullptr, w_fuse,
+                                      b_fuse, f_in, f_out, workspace, l.fused, stream);
+}
+
 size_t esc_dense_workspace_bytes(int N, int C_a, int H, int W, int Ks)
 {
     DenseLayout d;

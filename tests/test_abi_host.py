@@ -207,6 +207,35 @@ def test_convffn_rejects_bad_arguments_before_launch(lib):
     assert ff(ws=0x90000 - 256, ws_bytes=need) == E_ALIAS        # workspace runs into out
 
 
+def test_residual_step_rejects_bad_arguments_before_launch(lib):
+    def rs(f=0x10000, dt=0, N=1, C=64, H=8, W=8, Ch=128, w1=0x20000, k=0x28000, w2=0x2a000, Ca=16, lkc=None, lk=0x2c000,
+           Ks=13, stride=169, gen=None, wf=0x2e000, out=0x90000, ws=0x30000 * 256, ws_bytes=1 << 22):
+        return lib.esc_residual_step_forward(f, dt, N, C, H, W, Ch, w1, None, k, None, w2, None, Ca, lkc, lk, Ks, stride,
+                                             gen, wf, None, out, ws, ws_bytes, None)
+    for name in ("f", "out", "w1", "k", "w2", "lk", "wf"):
+        assert rs(**{name: None}) == E_NULL, name
+    assert rs(dt=9) == E_DTYPE
+    assert rs(Ch=0) == E_SHAPE
+    assert rs(Ch=241) == E_UNSUP
+    assert rs(Ks=4) == E_UNSUP
+    assert rs(Ks=0) == E_SHAPE
+    assert rs(Ca=65) == E_SHAPE
+    assert rs(stride=10) == E_SHAPE
+    assert rs(out=0x10000) == E_ALIAS
+    assert rs(gen=gen_struct(w_up=None)) == E_NULL
+    need = lib.esc_residual_step_workspace_bytes(1, 64, 8, 8, 16, 128, 0, 0)
+    fused = lib.esc_fused_workspace_bytes(1, 16, 8, 8, 0, 0)
+    ffn = lib.esc_convffn_workspace_bytes(1, 128, 8, 8, 0)
+    # the fused call's workspace, ConvFFN's result, ConvFFN's scratch
+    assert need % 256 == 0 and need >= fused + 64 * 64 * 4 + ffn
+    assert lib.esc_residual_step_workspace_bytes(1, 64, 8, 8, 16, 128, 0, 1) > need
+    assert lib.esc_residual_step_workspace_bytes(1, 64, 8, 8, 65, 128, 0, 0) == 0
+    assert lib.esc_residual_step_workspace_bytes(1, 64, 8, 8, 16, 0, 0, 0) == 0
+    assert rs(ws=None) == E_WS
+    assert rs(ws_bytes=need - 256) == E_WS
+    assert rs(ws=0x90000 - 256, ws_bytes=need) == E_ALIAS
+
+
 def test_backward_rejects_bad_arguments_before_launch(lib):
     def bw(x=0x10000, go=0x50000, dt=0, N=1, C=64, H=8, W=8, Ca=16, lk=0x20000, Ks=13, stride=169, gen=None, dk=None,
            gx=0x90000, glk=0x28000, ggen=None, gdk=None, acc=0, ws=0x30000 * 256, ws_bytes=1 << 22):

@@ -177,6 +177,46 @@ def test_residual_step_as_two_calls(oracle, dtype, with_lkc):
     gu.assert_att_close(as_f64(gu.out_to_np(out, dtype), dtype), ref, dtype, "residual step")
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("with_lkc", [False, True])
+def test_residual_step_as_one_call(oracle, dtype, with_lkc):
+    """esc_residual_step_forward is the two calls above with ConvFFN's result kept in its workspace: the same
+    bits as the two calls, and the oracle's two steps within the bar."""
+    N, C, H, W, Ca, Ks, Ch = 2, 32, 24, 40, 8, 7, 64
+    wl = wk.make_random(41, N, C, H, W, Ca, Ks, dtype=dtype, x_mean=0.3)
+    print(f"[case] residual step, one call {wl.name} lkc={with_lkc}", flush=True)
+    p = wk.make_ffn_params(1041, C, Ch)
+    rng = np.random.default_rng(42)
+    w_fuse = (rng.standard_normal((C, C)) / np.sqrt(C)).astype(np.float32)
+    b_fuse = (rng.standard_normal(C) * 0.1).astype(np.float32)
+    lkc = (rng.standard_normal((Ca, Ca)) / np.sqrt(Ca)).astype(np.float32) if with_lkc else None
+    x = gu.to_dev_x(wl.x, dtype)
+    dev_p = {k: gu.dev(v) for k, v in p.items()}
+    # the two calls
+    ws1 = binding.new_convffn_workspace(N, Ch, H, W, x.dtype)
+    ws2 = binding.new_fused_workspace(N, Ca, H, W, x.dtype, with_lkc)
+    t = binding.convffn_forward(x, dev_p["w1"], dev_p["k"], dev_p["w2"], ws1, b1=dev_p["b1"], b_dw=dev_p["bk"], b2=dev_p["b2"])
+    two = binding.convattn_fused_forward(t, Ca, gu.dev(wl.lk), gu.dev(w_fuse), ws2, b_fuse=gu.dev(b_fuse),
+                                         lk_c=gu.dev(lkc), residual=x, gen=gu.gen_params(wl))
+    # the one call, twice in the same workspace
+    ws = binding.new_residual_step_workspace(N, C, H, W, Ca, Ch, x.dtype, with_lkc)
+    for _ in range(2):
+        one = torch.full_like(x, float("nan"))
+        binding.residual_step_forward(x, dev_p["w1"], dev_p["k"], dev_p["w2"], Ca, gu.dev(wl.lk), gu.dev(w_fuse), ws,
+                                      b1=dev_p["b1"], b_dw=dev_p["bk"], b2=dev_p["b2"], lk_c=gu.dev(lkc),
+                                      gen=gu.gen_params(wl), b_fuse=gu.dev(b_fuse), out=one)
+        assert binding.workspace_errors(ws) == 0
+        torch.cuda.synchronize()
+        assert torch.equal(one.view(torch.int16 if dtype == BF16 else torch.int32),
+                           two.view(torch.int16 if dtype == BF16 else torch.int32))
+    t_ref = oracle.convffn_forward(wl.x, p["w1"], p["k"], p["w2"], dtype, b1=p["b1"], bk=p["bk"], b2=p["b2"])
+    t_st = t_ref.astype(np.float32)
+    t_st = wk.f32_to_bf16_bits(t_st) if dtype == BF16 else t_st
+    ref, _, _ = oracle.convattn_fused_forward(t_st, Ca, wl.lk, w_fuse, dtype, b_fuse=b_fuse, lkc=lkc, residual=wl.x,
+                                              hidden=wl.hidden, w_up=wl.w_up, b_up=wl.b_up)
+    gu.assert_att_close(as_f64(gu.out_to_np(one, dtype), dtype), ref, dtype, "residual step, one call")
+
+
 def test_replays_from_a_captured_graph(oracle):
     N, C, H, W, Ch = 1, 16, 20, 32, 32
     x_np = make_x(40, N, C, H, W, F32)
