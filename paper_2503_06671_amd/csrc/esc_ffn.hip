@@ -178,10 +178,13 @@ __global__ __launch_bounds__(kFbThreads) void ffn_branch_kernel(const FfnBranchP
 //      wavefronts hand their partial sums over through LDS, the kh = 0 ones add them and
 //      b2 and store 30 columns of output row y - 1 - while the kh = 1 ones already start on
 //      the next row.
-// Two barriers per row, 75 KB of LDS (two blocks per compute unit, so that one block's
-// products overlap the other's GELUs), weights read once per block.  The band's first two
-// input rows are recomputed by the band above (rows_per_band + 2 first-layer rows for
-// rows_per_band output rows), the strips' halo columns by their neighbours (32 for 30).
+// Two barriers per row, 76 KB of LDS (two blocks per compute unit), weights read once per
+// block.  The band's first two input rows are recomputed by the band above
+// (rows_per_band + 2 first-layer rows for rows_per_band output rows), the strips' halo
+// columns by their neighbours (32 for 30).  Measured: the fp32 matrix instructions'
+// time and the vector instructions' time add up in this kernel - neither issued among
+// the other wavefront's nor among the same wavefront's vector instructions do these
+// matrix instructions run beside them - so the phases are simply written one after the other.
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
