@@ -189,7 +189,9 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
  * storage they are rounded to bf16 on the way, and out once more at its store.
  * The workspace (esc_convffn_workspace_bytes, 256-byte aligned) is plain scratch: it needs
  * no esc_workspace_init and its contents are undefined after the call.  Limits: C <= 240,
- * C_h <= 240, C_h*H*W*element size < 2 GiB.  The whole residual step is this call followed by
+ * C_h <= 960, C_h*H*W*element size < 2 GiB.  A hidden layer of more than 224 channels is
+ * multiplied by w2 224 channels at a time, each launch adding to out (with bf16 storage the
+ * partial sums are rounded to bf16 between the launches).  The whole residual step is this call followed by
  * esc_convattn_fused_forward on its output with residual = x.
  */
 size_t esc_convffn_workspace_bytes(int N, int C_h, int H, int W, esc_dtype dt);

@@ -782,6 +782,8 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
 
 // ---- ConvFFN (Eq. 3 line 3: the feed-forward network in front of the module) ----------
 
+constexpr int kFfnMaxHidden = 960;  // hidden channels (the second layer takes them 224 at a time)
+
 size_t esc_convffn_workspace_bytes(int N, int C_h, int H, int W, esc_dtype dt)
 {
     if ((dt != ESC_F32 && dt != ESC_BF16) || N < 1 || C_h < 1 || H < 1 || W < 1) return 0;
@@ -797,7 +799,7 @@ esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H,
     if (N < 1 || C < 1 || H < 1 || W < 1 || C_h < 1) return ESC_ERR_SHAPE;
     if (x == nullptr || out == nullptr || w1 == nullptr || k_dw == nullptr || w2 == nullptr) return ESC_ERR_NULL;
     if ((size_t)H * (size_t)W >= ((size_t)1 << 31)) return ESC_ERR_UNSUPPORTED;
-    if (C > kPointwiseMaxK || C_h > kPointwiseMaxK) return ESC_ERR_UNSUPPORTED;
+    if (C > kPointwiseMaxK || C_h > kFfnMaxHidden) return ESC_ERR_UNSUPPORTED;
     const size_t es = dt == ESC_F32 ? 4 : 2;
     const size_t plane = (size_t)H * W;
     // the point-wise kernel addresses an image of a tensor with 32-bit byte offsets
@@ -851,20 +853,28 @@ esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H,
     fb.W = W;
     fb.planes = (long)N * C_h;
     if (launch_ffn_branch(fb, bf16, s) != hipSuccess) return ESC_ERR_HIP;
-    // out = W2 . V + b2
-    PointwiseParams p2{};
-    p2.src1 = v;
-    p2.src1_img_stride = (size_t)C_h * plane;
-    p2.K1 = C_h;
-    p2.w = w2;
-    p2.w_ld = C_h;
-    p2.bias = b2;
-    p2.dst = out;
-    p2.dst_img_stride = (size_t)C * plane;
-    p2.M = C;
-    p2.N = N;
-    p2.P = (long)plane;
-    return launch_pointwise(p2, bf16, s) == hipSuccess ? ESC_OK : ESC_ERR_HIP;
+    // out = W2 . V + b2; a hidden layer wider than the point-wise kernel's staging holds is multiplied in
+    // chunks of its channels, each launch adding to what the launches before it left in out (out as the
+    // residual, in place: every element is read and written by the same wavefront)
+    constexpr int kChunk = 224;
+    for (int k0 = 0; k0 < C_h; k0 += kChunk) {
+        PointwiseParams p2{};
+        p2.src1 = v + (size_t)k0 * plane * es;
+        p2.src1_img_stride = (size_t)C_h * plane;
+        p2.K1 = C_h - k0 < kChunk ? C_h - k0 : kChunk;
+        p2.w = w2 + k0;
+        p2.w_ld = C_h;
+        p2.bias = k0 == 0 ? b2 : nullptr;
+        p2.res = k0 == 0 ? nullptr : out;
+        p2.res_img_stride = (size_t)C * plane;
+        p2.dst = out;
+        p2.dst_img_stride = (size_t)C * plane;
+        p2.M = C;
+        p2.N = N;
+        p2.P = (long)plane;
+        if (launch_pointwise(p2, bf16, s) != hipSuccess) return ESC_ERR_HIP;
+    }
+    return ESC_OK;
 }
 
 // ---- the residual step of Eq. 3 line 3 as one call ---------------------------------

@@ -192,8 +192,8 @@ def test_convffn_rejects_bad_arguments_before_launch(lib):
     assert ff(dt=3) == E_DTYPE
     assert ff(N=0) == E_SHAPE
     assert ff(Ch=0) == E_SHAPE
-    assert ff(Ch=241) == E_UNSUP                          # the point-wise kernel's LDS staging holds 240 channels
-    assert ff(C=241) == E_UNSUP
+    assert ff(Ch=961) == E_UNSUP                          # hidden layers up to 960 channels
+    assert ff(C=241) == E_UNSUP                           # the point-wise kernel's LDS staging holds 240 channels
     assert ff(out=0x10000) == E_ALIAS
     assert ff(out=0x90002) == E_SHAPE                     # misaligned for fp32 storage
     assert ff(ws=None) == E_WS
@@ -216,7 +216,7 @@ def test_residual_step_rejects_bad_arguments_before_launch(lib):
         assert rs(**{name: None}) == E_NULL, name
     assert rs(dt=9) == E_DTYPE
     assert rs(Ch=0) == E_SHAPE
-    assert rs(Ch=241) == E_UNSUP
+    assert rs(Ch=961) == E_UNSUP
     assert rs(Ks=4) == E_UNSUP
     assert rs(Ks=0) == E_SHAPE
     assert rs(Ca=65) == E_SHAPE

@@ -96,6 +96,15 @@ def test_widest_layers(oracle, dtype):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("shape", [(1, 192, 12, 20, 384), (2, 24, 9, 16, 449), (1, 8, 5, 7, 960)])
+def test_hidden_layers_wider_than_one_launch_of_the_second_layer(oracle, shape, dtype):
+    # the larger model of the paper's appendix has C = 192 (hidden width 384 at ratio two); the second layer takes
+    # the hidden channels 224 at a time: two, three and five launches, the last chunk one channel wide in the middle case
+    N, C, H, W, Ch = shape
+    check_ffn(oracle, 60 + C, N, C, H, W, Ch, dtype)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
 def test_bases_off_the_vector_alignment(oracle, dtype):
     # x and out start one element into their allocations: 16-byte pieces are not possible for
     # the first layer's fetches, while the workspace's tensors stay aligned
