@@ -486,7 +486,7 @@ def main():
         roof = roofline_of(wl, sec)
     traffic, traffic_src = (None, None) if args.warm_cache else profiled_traffic(wl_name)
     roof.update({
-        "kernel": (("ffn_stream_kernel (the whole network in one launch)" if wl.elem_bytes == 4 and wl.C <= 64 else
+        "kernel": (("ffn_stream_kernel / ffn_stream_bf16_kernel (the whole network in one launch)" if wl.C <= 64 else
                     "pointwise_kernel (first layer, GELU in its epilogue) + ffn_branch_kernel + pointwise_kernel (second layer)")
                    + ("; then forward_kernel (F_res) + pointwise_kernel (Conv_fuse, residual)" if ffn == "step" else "")
                    if ffn is not None else

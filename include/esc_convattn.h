@@ -182,11 +182,12 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
  * All weights are device pointers to fp32, read-only.  The point-wise layers run on the
  * matrix cores as in esc_convattn_fused_forward (fp32 storage: fp32 products; bf16 storage:
  * bf16 instructions on the stored values, each fp32 weight as two bf16 terms), the branch
- * in fp32 on the vector units.  fp32 storage with C <= 64, C_h <= 128 and an image (or batch)
- * large enough to fill the chip with 30-column strips takes ONE launch in which U and V
- * never leave the chip (the workspace is not touched); everything else takes three
+ * in fp32 on the vector units.  With C <= 64, C_h <= 128 and an image (or batch) large
+ * enough to fill the chip with 30-column strips the call takes ONE launch in which U and V
+ * never leave the chip (the workspace is not touched; with bf16 storage U stays fp32 and V
+ * is rounded to bf16 once, as the second layer's operand); everything else takes three
  * launches, U and V passing through the workspace in the storage type, so that with bf16
- * storage they are rounded to bf16 on the way, and out once more at its store.
+ * storage both are rounded to bf16 on the way.  out is rounded once at its store.
  * The workspace (esc_convffn_workspace_bytes, 256-byte aligned) is plain scratch: it needs
  * no esc_workspace_init and its contents are undefined after the call.  Limits: C <= 240,
  * C_h <= 960, C_h*H*W*element size < 2 GiB.  A hidden layer of more than 224 channels is

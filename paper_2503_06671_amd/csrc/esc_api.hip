@@ -815,12 +815,14 @@ esc_status esc_convffn_forward(const void *x, esc_dtype dt, int N, int C, int H,
     hipStream_t s = (hipStream_t)stream;
     const bool bf16 = dt == ESC_BF16;
     char *u = (char *)workspace, *v = u + need / 2;
-    if (!bf16) {
-        // fp32 storage with up to 64 channels and a hidden layer of up to 128: the whole network in
-        // one launch, U and V staying on the chip (the workspace is not touched)
+    {
+        // up to 64 channels and a hidden layer of up to 128, on an image (or batch) large enough to
+        // fill the chip: the whole network in one launch, U and V staying on the chip (the workspace
+        // is not touched)
         FfnStreamParams fs{};
-        fs.x = (const float *)x;
-        fs.out = (float *)out;
+        fs.x = x;
+        fs.out = out;
+        fs.bf16 = bf16 ? 1 : 0;
         fs.w1 = w1, fs.b1 = b1, fs.k = k_dw, fs.bk = b_dw, fs.w2 = w2, fs.b2 = b2;
         fs.N = N, fs.C = C, fs.H = H, fs.W = W, fs.Ch = C_h;
         const hipError_t e = launch_ffn_stream(fs, s);

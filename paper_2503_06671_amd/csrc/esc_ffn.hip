@@ -233,9 +233,9 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
     const int y0 = band * p.rows_per_band;                // first output row
     const int rows_out = min(p.rows_per_band, H - y0);    // >= 1
     const size_t plane = (size_t)H * W;
-    const float *xin = p.x + (size_t)n * C * plane;
+    const float *xin = (const float *)p.x + (size_t)n * C * plane;
     const unsigned plane_bytes = (unsigned)plane * 4u;
-    const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc((void *)(p.out + (size_t)n * C * plane), 0,
+    const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc((void *)((float *)p.out + (size_t)n * C * plane), 0,
                                                                           (int)((unsigned)C * plane_bytes), 0x00020000);
 
     // ---- this thread's share of an input row: column tid % 32 of channels tid / 32 + 8 i ----
@@ -422,6 +422,258 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
     }
 }
 
+// ---- the same for bf16 storage, on the bf16 matrix instructions --------------------------
+//
+// v_mfma_f32_32x32x16_bf16 on the stored values, every fp32 weight as two bf16 terms
+// (w = hi + lo to 16 mantissa bits; products exact, fp32 accumulation): a sixteenth of the
+// fp32 instructions' time, and beside the vector units instead of in their way.  What
+// changes against the fp32 kernel is the layout of the matrix operands: an operand wants
+// eight consecutive channels of one pixel per lane, so the input row and V sit in LDS
+// pixel-major ([column][channel] bf16, 16-byte reads; pitches of 4 words mod 32, which
+// spreads a half-wavefront's sixteen-byte reads evenly over the banks), each weight tile is
+// 2 terms x 4 chunks of sixteen channels x 4 registers, and V has a buffer of its own (it
+// is bf16, the ring fp32).  U stays fp32 in the ring - only V is rounded to bf16 on the way
+// to the second layer, as a stored V would be - and out is rounded once at its store.
+
+typedef unsigned u32x4s __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8s __attribute__((ext_vector_type(8)));
+
+constexpr int kFbXPitch = kFsC + 8;                  // bf16 elements between two columns of an input row tile (144 bytes)
+constexpr int kFbVPitch = kFsCh + 8;                 // ... of V's tile (272 bytes)
+constexpr int kFbXElems = 2 * kFsNp * kFbXPitch;     // two row buffers
+constexpr int kFbVElems = kFsNp * kFbVPitch;
+constexpr size_t kFbLdsBytes = (size_t)(kFbXElems + kFbVElems) * 2 +
+                               (size_t)(kFsRingFloats + kFsRedFloats + kFsBiasFloats) * sizeof(float);
+static_assert((kFbXElems * 2) % 16 == 0 && (kFbVElems * 2) % 16 == 0, "the fp32 parts start on 16-byte boundaries");
+static_assert((size_t)(kFsCh * (kFsC + 1) + kFsC * (kFsCh + 1)) * 4 <= (size_t)(kFbXElems + kFbVElems) * 2 + (size_t)kFsRingFloats * 4,
+              "the weights pass through the tiles' and the ring's space on their way into registers");
+
+// eight fp32 weights as the two bf16 terms of an A operand
+__device__ __forceinline__ void fb_split8(const float *w, u32x4s &hi, u32x4s &lo)
+{
+    unsigned h[8], l[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        h[e] = fb_f32_to_bf16(w[e]);
+        l[e] = fb_f32_to_bf16(w[e] - __uint_as_float(h[e] << 16));
+    }
+    hi = u32x4s{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    lo = u32x4s{l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)};
+}
+
+__global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_bf16_kernel(const FfnStreamParams p)
+{
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int mt = wave & 1, kh = wave >> 1;
+    const int C = p.C, Ch = p.Ch, H = p.H, W = p.W;
+
+    uint16_t *sX = reinterpret_cast<uint16_t *>(fs_lds);   // [2][kFsNp][kFbXPitch] bf16
+    uint16_t *sV = sX + kFbXElems;                         // [kFsNp][kFbVPitch] bf16
+    float *ring = reinterpret_cast<float *>(sV + kFbVElems);  // [3][kFsCh][kFsPitch]
+    float *red = ring + kFsRingFloats;                     // [2 mt][16][64]
+    float *sB1 = red + kFsRedFloats;
+    float *sB2 = sB1 + kFsCh;
+
+    // which strip, band and image (pieces dealt so that neighbours meet in one die's L2, as above)
+    const unsigned bq = gridDim.x / 8u, br = gridDim.x % 8u, xcd = blockIdx.x % 8u;
+    const unsigned piece = xcd * bq + (xcd < br ? xcd : br) + blockIdx.x / 8u;
+    const unsigned per_img = (unsigned)p.strips * (unsigned)p.bands;
+    const unsigned n = piece / per_img;
+    const unsigned rem = piece - n * per_img;
+    const int band = (int)(rem / (unsigned)p.strips), strip = (int)(rem - (unsigned)band * (unsigned)p.strips);
+    const int x0 = strip * kFsOut - 1;
+    const int y0 = band * p.rows_per_band;
+    const int rows_out = min(p.rows_per_band, H - y0);
+    const size_t plane = (size_t)H * W;
+    const uint16_t *xin = (const uint16_t *)p.x + (size_t)n * C * plane;
+    const unsigned plane_bytes = (unsigned)plane * 2u;
+    const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc((void *)((uint16_t *)p.out + (size_t)n * C * plane), 0,
+                                                                          (int)((unsigned)C * plane_bytes), 0x00020000);
+
+    // ---- this thread's share of an input row: column tid % 32 of channels tid / 32 + 8 i ----
+    const int xpx = tid & 31, xc0 = tid >> 5;
+    const int gx_in = x0 + xpx;
+    const bool col_in = gx_in >= 0 && gx_in < W;
+    auto fetch_row = [&](int gy, uint16_t (&v)[8]) {
+        const bool row_in = gy >= 0 && gy < H;
+        const size_t off = (size_t)(row_in ? gy : 0) * W + (size_t)(col_in ? gx_in : 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = xc0 + 8 * i;
+            v[i] = xin[(size_t)(c < C ? c : 0) * plane + off];
+        }
+    };
+    auto put_row = [&](const uint16_t (&v)[8], int gy, int buf) {
+        const bool in = col_in && gy >= 0 && gy < H;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            sX[buf * (kFsNp * kFbXPitch) + xpx * kFbXPitch + xc0 + 8 * i] = (in && xc0 + 8 * i < C) ? v[i] : (uint16_t)0;
+    };
+
+    uint16_t xr[8];
+    fetch_row(y0 - 1, xr);  // the band's first input row travels while the weights are staged
+
+    // ---- weights: fp32 through LDS as in the fp32 kernel, then split into their two bf16
+    // terms in the A operand's layout: lane holds W[row][16 c + 8 half ... + 7] of chunk c ----
+    u32x4s a1h[4], a1l[4], a2h[4], a2l[4];
+    {
+        constexpr int kP1 = kFsC + 1, kP2 = kFsCh + 1;
+        float *s1 = fs_lds, *s2 = fs_lds + kFsCh * kP1;
+        for (int i0 = tid; i0 < kFsCh * kFsC; i0 += 8 * kFsThreads) {
+            float v[8], w[8];
+            bool in1[8], in2[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kFsThreads;
+                const int r1 = i / kFsC, c1 = i - r1 * kFsC, r2 = i / kFsCh, c2 = i - r2 * kFsCh;
+                in1[u] = r1 < Ch && c1 < C;
+                in2[u] = r2 < C && c2 < Ch;
+                v[u] = p.w1[in1[u] ? (size_t)r1 * C + c1 : 0];
+                w[u] = p.w2[in2[u] ? (size_t)r2 * Ch + c2 : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kFsThreads;
+                const int r1 = i / kFsC, c1 = i - r1 * kFsC, r2 = i / kFsCh, c2 = i - r2 * kFsCh;
+                s1[r1 * kP1 + c1] = in1[u] ? v[u] : 0.f;
+                s2[r2 * kP2 + c2] = in2[u] ? w[u] : 0.f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float w8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) w8[e] = s1[(32 * wave + l32) * kP1 + 16 * c + 8 * half + e];
+            fb_split8(w8, a1h[c], a1l[c]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) w8[e] = s2[(32 * mt + l32) * kP2 + 64 * kh + 16 * c + 8 * half + e];
+            fb_split8(w8, a2h[c], a2l[c]);
+        }
+        __syncthreads();  // everyone has its weights: the space is the tiles' and the ring's from here on
+    }
+    if (tid < kFsCh) sB1[tid] = (p.b1 != nullptr && tid < Ch) ? p.b1[tid] : 0.f;
+    if (tid < kFsC) sB2[tid] = (p.b2 != nullptr && tid < C) ? p.b2[tid] : 0.f;
+    const int chb = 32 * wave + l32;
+    float kd[9], bkd;
+    {
+        const bool in = chb < Ch;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const float v = p.k[in ? (size_t)chb * 9 + t : 0];
+            kd[t] = in ? v : 0.f;
+        }
+        const float vb = p.bk != nullptr ? p.bk[in ? chb : 0] : 0.f;
+        bkd = (in && p.bk != nullptr) ? vb : 0.f;
+    }
+
+    put_row(xr, y0 - 1, 0);
+    fetch_row(y0, xr);
+    __syncthreads();
+
+    const bool ucol_in = (x0 + l32) >= 0 && (x0 + l32) < W;
+    const int steps = rows_out + 2;
+    for (int r = 0; r < steps; ++r) {
+        const int gy = y0 - 1 + r;
+        if (r + 1 < steps) {
+            put_row(xr, gy + 1, (r + 1) & 1);
+            if (r + 2 < steps) fetch_row(gy + 2, xr);
+        }
+        // ---- first layer on row gy ----
+        {
+            f32x16 acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+            const uint16_t *bx = sX + (r & 1) * (kFsNp * kFbXPitch) + l32 * kFbXPitch + 8 * half;
+            const float *b1p = sB1 + 32 * wave + 4 * half;
+            float b1v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) b1v[i] = b1p[8 * (i >> 2) + (i & 3)];
+            u32x4s bq[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) bq[c] = *reinterpret_cast<const u32x4s *>(bx + 16 * c);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8s, a1h[c]), __builtin_bit_cast(bf16x8s, bq[c]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8s, a1l[c]), __builtin_bit_cast(bf16x8s, bq[c]), acc, 0, 0, 0);
+            }
+            const bool live = ucol_in && gy >= 0 && gy < H;
+            float *ur = ring + (r % 3) * (kFsCh * kFsPitch) + (32 * wave + 4 * half) * kFsPitch + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = 8 * (i >> 2) + (i & 3);
+                const float u = fb_gelu(acc[i] + b1v[i]);
+                ur[m * kFsPitch] = live ? u : 0.f;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();  // (a wavefront's LDS accesses are carried out in order)
+        // ---- the branch on output row gy - 1; V, rounded to bf16, into its pixel-major tile ----
+        if (r >= 2) {
+            float a[3][18];
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const float *row = ring + ((r + 1 + i) % 3) * (kFsCh * kFsPitch) + chb * kFsPitch;
+#pragma unroll
+                for (int j = 0; j < 18; ++j) {
+                    const int px = 16 * half - 1 + j;
+                    const float v = row[px < 0 ? 0 : (px > 31 ? 31 : px)];
+                    a[i][j] = (px >= 0 && px <= 31) ? v : 0.f;
+                }
+            }
+            uint16_t *vr = sV + (16 * half) * kFbVPitch + chb;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                float s = bkd;
+                s = fmaf(kd[0], a[0][j], s), s = fmaf(kd[1], a[0][j + 1], s), s = fmaf(kd[2], a[0][j + 2], s);
+                s = fmaf(kd[3], a[1][j], s), s = fmaf(kd[4], a[1][j + 1], s), s = fmaf(kd[5], a[1][j + 2], s);
+                s = fmaf(kd[6], a[2][j], s), s = fmaf(kd[7], a[2][j + 1], s), s = fmaf(kd[8], a[2][j + 2], s);
+                vr[j * kFbVPitch] = fb_f32_to_bf16(a[1][j + 1] + fb_gelu(s));
+            }
+        }
+        __syncthreads();  // V of all hidden channels (and the next input row) is in LDS
+        // ---- second layer ----
+        f32x16 acc2;
+        if (r >= 2) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc2[i] = 0.f;
+            const uint16_t *bv = sV + l32 * kFbVPitch + 64 * kh + 8 * half;
+            u32x4s vq[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) vq[c] = *reinterpret_cast<const u32x4s *>(bv + 16 * c);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8s, a2h[c]), __builtin_bit_cast(bf16x8s, vq[c]), acc2, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8s, a2l[c]), __builtin_bit_cast(bf16x8s, vq[c]), acc2, 0, 0, 0);
+            }
+            if (kh == 1) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) red[(mt * 16 + i) * 64 + lane] = acc2[i];
+            }
+        }
+        __syncthreads();  // the partial sums are in LDS; nobody reads V any more
+        if (r >= 2 && kh == 0) {
+            const int gyo = gy - 1, gxo = x0 + l32;
+            const bool st_ok = l32 >= 1 && l32 <= kFsOut && gxo < W;
+            float rv[16], bv2[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                rv[i] = red[(mt * 16 + i) * 64 + lane];
+                bv2[i] = sB2[32 * mt + 8 * (i >> 2) + 4 * half + (i & 3)];
+            }
+            const unsigned px_off = (unsigned)(gyo * W + gxo) * 2u;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int co = 32 * mt + 8 * (i >> 2) + 4 * half + (i & 3);
+                const float v = acc2[i] + rv[i] + bv2[i];
+                const unsigned off = (st_ok && co < C) ? (unsigned)co * plane_bytes + px_off : 0x80000000u;
+                __builtin_amdgcn_raw_buffer_store_b16((unsigned short)fb_f32_to_bf16(v), rout, (int)off, 0, 2 /* non-temporal */);
+            }
+        }
+    }
+}
+
 }  // namespace
 
 __attribute__((visibility("hidden"))) hipError_t launch_ffn_branch(const FfnBranchParams &p, bool bf16, hipStream_t s)
@@ -461,8 +713,11 @@ __attribute__((visibility("hidden"))) hipError_t launch_ffn_stream(const FfnStre
     }
     static bool lds_granted = false;
     if (!lds_granted) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ffn_stream_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFsLdsBytes);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(ffn_stream_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFsLdsBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(ffn_stream_bf16_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFbLdsBytes);
         if (e != hipSuccess) return e;
         lds_granted = true;
     }
@@ -471,19 +726,26 @@ __attribute__((visibility("hidden"))) hipError_t launch_ffn_stream(const FfnStre
     // a block lasts as long whatever the image's size (its weights' way into registers, then six
     // rows one after the other): with too few blocks to fill the chip the three launches are faster
     if ((long)p.N * q.strips * ((p.H + 3) / 4) < 3L * cus / 2) return hipErrorNotSupported;
-    // the tallest bands that still give every block slot (two per compute unit) a block
+    // the band height that needs the fewest row steps one after the other: a block takes its rows + 2
+    // steps and about a step and a half to get its weights; the blocks run in rounds of two per compute unit
     q.rows_per_band = 4;
-    for (int rb = 32; rb > 4; rb /= 2) {
+    double best = 0.0;
+    for (int rb = 4; rb <= 32; rb *= 2) {
         const long blocks = (long)p.N * q.strips * ((p.H + rb - 1) / rb);
-        if (blocks >= 2L * cus) {
+        const long rounds = (blocks + 2L * cus - 1) / (2L * cus);
+        const double cost = (double)rounds * (rb + 3.5);
+        if (rb == 4 || cost < best) {
+            best = cost;
             q.rows_per_band = rb;
-            break;
         }
     }
     q.bands = (p.H + q.rows_per_band - 1) / q.rows_per_band;
     const long grid = (long)p.N * q.strips * q.bands;
     if (grid >= (1L << 31)) return hipErrorNotSupported;
-    hipLaunchKernelGGL(ffn_stream_kernel, dim3((unsigned)grid), dim3(kFsThreads), kFsLdsBytes, s, q);
+    if (p.bf16)
+        hipLaunchKernelGGL(ffn_stream_bf16_kernel, dim3((unsigned)grid), dim3(kFsThreads), kFbLdsBytes, s, q);
+    else
+        hipLaunchKernelGGL(ffn_stream_kernel, dim3((unsigned)grid), dim3(kFsThreads), kFsLdsBytes, s, q);
     return hipGetLastError();
 }
 

@@ -20,13 +20,14 @@ struct FfnBranchParams {
 
 hipError_t launch_ffn_branch(const FfnBranchParams &p, bool bf16, hipStream_t s);
 
-// The whole network in one launch for fp32 storage, C <= 64 and Ch <= 128 (neither U nor V
+// The whole network in one launch for C <= 64 and Ch <= 128 (neither U nor V
 // leaves the chip): out = w2 . V + b2, V = U + gelu(k (*) U + bk), U = gelu(w1 . x + b1).
 // Returns hipErrorNotSupported, with nothing launched, for other shapes and for problems of
 // too few strips and bands to fill the chip.
 struct FfnStreamParams {
-    const float *x;
-    float *out;
+    const void *x;         // storage type: fp32, or bf16 bit patterns (bf16 != 0)
+    void *out;
+    int bf16;
     const float *w1, *b1;  // [Ch, C], [Ch] or nullptr
     const float *k, *bk;   // [Ch, 3, 3], [Ch] or nullptr
     const float *w2, *b2;  // [C, Ch], [C] or nullptr

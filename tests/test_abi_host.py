@@ -371,10 +371,10 @@ def test_convffn_kernels_use_no_scratch(lib):
     # instantiations and the point-wise kernel's eight (storage type x 16-byte fetches x GELU)
     found = {}
     for name, scratch, vgprs, lds in kernel_notes():
-        for key in ("ffn_stream_kernel", "ffn_branch_kernel", "pointwise_kernel", "pointwise_bf16_kernel"):
+        for key in ("ffn_stream_kernel", "ffn_stream_bf16_kernel", "ffn_branch_kernel", "pointwise_kernel", "pointwise_bf16_kernel"):
             if key + "E" in name or key + "I" in name:
                 found.setdefault(key, []).append((name, scratch, vgprs))
-    assert {k: len(v) for k, v in found.items()} == {"ffn_stream_kernel": 1, "ffn_branch_kernel": 4,
+    assert {k: len(v) for k, v in found.items()} == {"ffn_stream_kernel": 1, "ffn_stream_bf16_kernel": 1, "ffn_branch_kernel": 4,
                                                      "pointwise_kernel": 4, "pointwise_bf16_kernel": 4}, found
     for key, items in found.items():
         for name, scratch, vgprs in items:

@@ -44,8 +44,16 @@ def check_ffn(oracle, seed, N, C, H, W, Ch, dtype, bias=True, what=""):
     x = make_x(seed, N, C, H, W, dtype)
     p = wk.make_ffn_params(1000 + seed, C, Ch, bias=bias)
     ref = oracle.convffn_forward(x, p["w1"], p["k"], p["w2"], dtype, b1=p["b1"], bk=p["bk"], b2=p["b2"])
-    got = run_ffn(x, dtype, p)
-    return gu.assert_att_close(as_f64(got, dtype), ref, dtype, what or f"convffn {N}x{C}x{H}x{W} Ch={Ch}")
+    got = as_f64(run_ffn(x, dtype, p), dtype)
+    if dtype == BF16 and Ch < 4:
+        # with two or three hidden channels an output is a difference of two or three terms each of which
+        # carries V's rounding to bf16 (2^-9 of the term): against such an output's own size the
+        # elementwise bound measures the cancellation, not the kernel - the normwise bar alone here
+        assert np.isfinite(got).all()
+        rel = np.abs(got - ref).max() / np.abs(ref).max()
+        assert rel <= gu.TOL[dtype], rel
+        return rel
+    return gu.assert_att_close(got, ref, dtype, what or f"convffn {N}x{C}x{H}x{W} Ch={Ch}")
 
 
 # ------------------------------------------------------------------ small and ragged shapes
@@ -63,11 +71,12 @@ def check_ffn(oracle, seed, N, C, H, W, Ch, dtype, bias=True, what=""):
     (1, 33, 17, 32, 65),      # channel counts one beyond the stages of 32 and the passes of 64
     (2, 70, 9, 11, 12),       # more than 64 channels: fp32 storage takes the three-launch path too (element-wise fetches)
     (1, 8, 12, 16, 136),      # a hidden layer beyond 128: the same, with 16-byte pieces
-    # fp32 storage, batches large enough for the one-launch kernel (it wants 384 strips x bands of four rows):
+    # batches large enough for the one-launch kernels (they want 384 strips x bands of four rows):
     (64, 64, 7, 61, 128),     # at its widest, three strips with a ragged last one, two bands
     (12, 5, 37, 95, 7),       # several bands and strips, the last strip five columns wide
     (24, 3, 70, 30, 4),       # exactly one strip, bands that do not divide the height
-    (8, 9, 200, 64, 20),      # bands of eight rows
+    (8, 9, 200, 64, 20),      # bands of sixteen rows, the last one eight rows high
+    (20, 4, 64, 60, 6),       # bands of eight rows
     (64, 2, 100, 58, 3),      # bands of thirty-two rows, the last one four rows high
     (400, 1, 1, 1, 1),        # single elements: one strip of one column, one band of one row
     (200, 2, 2, 31, 3),       # a second strip that is one column wide, fewer rows than a band
@@ -76,8 +85,6 @@ def check_ffn(oracle, seed, N, C, H, W, Ch, dtype, bias=True, what=""):
 ])
 def test_small_and_ragged_shapes(oracle, shape, dtype):
     N, C, H, W, Ch = shape
-    if N > 3 and dtype == BF16:
-        pytest.skip("a batch chosen to reach the fp32 one-launch kernel; bf16 storage is covered by the other shapes")
     if N * C * H * W == 1 and dtype == BF16:
         # one output that is a difference of terms: the intermediates' bf16 roundings (2^-9 of each term)
         # against the size of the result is not what the normwise bar measures
