@@ -52,6 +52,15 @@ __device__ __forceinline__ uint16_t fb_f32_to_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
+// two fp32 values rounded to nearest even and packed, a in the low half: the hardware's
+// packed conversion (v_cvt_pk_bf16_f32), one instruction where the shifts and adds above are a dozen
+typedef float fb_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 fb_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t fb_pack2_bf16(float a, float b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(fb_f32x2{a, b}, fb_bf16x2));
+}
+
 template <typename T>
 __device__ __forceinline__ float fb_load1(const T *p)
 {
@@ -141,10 +150,8 @@ __global__ __launch_bounds__(kFbThreads) void ffn_branch_kernel(const FfnBranchP
                 if constexpr (sizeof(T) == 4) {
                     w = u32x4{__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3])};
                 } else {
-                    w = u32x4{(uint32_t)fb_f32_to_bf16(o[0]) | ((uint32_t)fb_f32_to_bf16(o[1]) << 16),
-                              (uint32_t)fb_f32_to_bf16(o[2]) | ((uint32_t)fb_f32_to_bf16(o[3]) << 16),
-                              (uint32_t)fb_f32_to_bf16(o[4]) | ((uint32_t)fb_f32_to_bf16(o[5]) << 16),
-                              (uint32_t)fb_f32_to_bf16(o[6]) | ((uint32_t)fb_f32_to_bf16(o[7]) << 16)};
+                    w = u32x4{fb_pack2_bf16(o[0], o[1]), fb_pack2_bf16(o[2], o[3]), fb_pack2_bf16(o[4], o[5]),
+                              fb_pack2_bf16(o[6], o[7])};
                 }
                 *reinterpret_cast<u32x4 *>(dst) = w;
             } else {
@@ -623,13 +630,20 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_bf16_kernel(const Ff
                 }
             }
             uint16_t *vr = sV + (16 * half) * kFbVPitch + chb;
+            float vv[16];
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 float s = bkd;
                 s = fmaf(kd[0], a[0][j], s), s = fmaf(kd[1], a[0][j + 1], s), s = fmaf(kd[2], a[0][j + 2], s);
                 s = fmaf(kd[3], a[1][j], s), s = fmaf(kd[4], a[1][j + 1], s), s = fmaf(kd[5], a[1][j + 2], s);
                 s = fmaf(kd[6], a[2][j], s), s = fmaf(kd[7], a[2][j + 1], s), s = fmaf(kd[8], a[2][j + 2], s);
-                vr[j * kFbVPitch] = fb_f32_to_bf16(a[1][j + 1] + fb_gelu(s));
+                vv[j] = a[1][j + 1] + fb_gelu(s);
+            }
+#pragma unroll
+            for (int j = 0; j < 16; j += 2) {
+                const uint32_t pk = fb_pack2_bf16(vv[j], vv[j + 1]);
+                vr[j * kFbVPitch] = (uint16_t)pk;
+                vr[(j + 1) * kFbVPitch] = (uint16_t)(pk >> 16);
             }
         }
         __syncthreads();  // V of all hidden channels (and the next input row) is in LDS
@@ -664,11 +678,14 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_bf16_kernel(const Ff
             }
             const unsigned px_off = (unsigned)(gyo * W + gxo) * 2u;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int co = 32 * mt + 8 * (i >> 2) + 4 * half + (i & 3);
-                const float v = acc2[i] + rv[i] + bv2[i];
-                const unsigned off = (st_ok && co < C) ? (unsigned)co * plane_bytes + px_off : 0x80000000u;
-                __builtin_amdgcn_raw_buffer_store_b16((unsigned short)fb_f32_to_bf16(v), rout, (int)off, 0, 2 /* non-temporal */);
+            for (int i = 0; i < 16; i += 2) {
+                const uint32_t pk = fb_pack2_bf16(acc2[i] + rv[i] + bv2[i], acc2[i + 1] + rv[i + 1] + bv2[i + 1]);
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int co = 32 * mt + 8 * ((i + e) >> 2) + 4 * half + ((i + e) & 3);
+                    const unsigned off = (st_ok && co < C) ? (unsigned)co * plane_bytes + px_off : 0x80000000u;
+                    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(e == 0 ? pk : pk >> 16), rout, (int)off, 0, 2 /* non-temporal */);
+                }
             }
         }
     }
