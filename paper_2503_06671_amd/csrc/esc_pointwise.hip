@@ -51,6 +51,15 @@ __device__ __forceinline__ uint16_t pw_f32_to_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
+// two fp32 values rounded to nearest even and packed, a in the low half: the hardware's
+// packed conversion (v_cvt_pk_bf16_f32), one instruction where the shifts and adds above are a dozen
+typedef float pw_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 pw_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pw_pack2_bf16(float a, float b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(pw_f32x2{a, b}, pw_bf16x2));
+}
+
 __device__ __forceinline__ float pw_load1(const float *p) { return *p; }
 __device__ __forceinline__ float pw_load1(const bf16s *p) { return __uint_as_float((uint32_t)p->bits << 16); }
 
@@ -479,8 +488,7 @@ __global__ __launch_bounds__(kPwThreads, VEC ? 3 : 2) void pointwise_bf16_kernel
                         const float v1 = act(acc[t2][4 * q + 1]) + __uint_as_float(rv[t2][q].x & 0xffff0000u);
                         const float v2 = act(acc[t2][4 * q + 2]) + __uint_as_float(rv[t2][q].y << 16);
                         const float v3 = act(acc[t2][4 * q + 3]) + __uint_as_float(rv[t2][q].y & 0xffff0000u);
-                        const u32x2 w = {(uint32_t)pw_f32_to_bf16(v0) | ((uint32_t)pw_f32_to_bf16(v1) << 16),
-                                         (uint32_t)pw_f32_to_bf16(v2) | ((uint32_t)pw_f32_to_bf16(v3) << 16)};
+                        const u32x2 w = {pw_pack2_bf16(v0, v1), pw_pack2_bf16(v2, v3)};
                         *reinterpret_cast<u32x2 *>(s_o + l32 * kPwBfOPitch + 8 * ((4 * t2 + q) ^ (l32 & 7)) + 4 * half) = w;
                     }
                 __builtin_amdgcn_wave_barrier();  // (the wavefront's LDS accesses are carried out in order)
