@@ -240,6 +240,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
+// two results rounded to nearest even and packed, a in the low half: the hardware's packed
+// conversion (v_cvt_pk_bf16_f32), one instruction where the shifts and adds above are a dozen
+__device__ __forceinline__ uint32_t f32_pack2_bf16(float a, float b)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+}
+
 __device__ __forceinline__ void store1(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store1(bf16_t *p, float v) { p->bits = f32_to_bf16_bits(v); }
 
@@ -255,8 +264,8 @@ __device__ __forceinline__ void store4(bf16_t *p, const float *v)
 {
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     u32x2 w;
-    w.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-    w.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+    w.x = f32_pack2_bf16(v[0], v[1]);
+    w.y = f32_pack2_bf16(v[2], v[3]);
     __builtin_nontemporal_store(w, reinterpret_cast<u32x2 *>(p));
 }
 
@@ -1599,8 +1608,8 @@ __device__ __forceinline__ Ctx conv_item(ParamsPtr p, Ctx ctx, unsigned item_in)
 #pragma unroll
         for (int t = 0; t < RY; ++t) {
             uint2 w;
-            w.x = (uint32_t)f32_to_bf16_bits(acc[t][0]) | ((uint32_t)f32_to_bf16_bits(acc[t][1]) << 16);
-            w.y = (uint32_t)f32_to_bf16_bits(acc[t][2]) | ((uint32_t)f32_to_bf16_bits(acc[t][3]) << 16);
+            w.x = f32_pack2_bf16(acc[t][0], acc[t][1]);
+            w.y = f32_pack2_bf16(acc[t][2], acc[t][3]);
             *reinterpret_cast<uint2 *>(otile + (16 * (mb0 >> 2) + mrow) * MG::OP + 8 * ((mb0 & 3) + t) + 2 * mg4) = w;
         }
         __syncthreads();
