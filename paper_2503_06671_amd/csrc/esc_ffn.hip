@@ -171,29 +171,38 @@ __global__ __launch_bounds__(kFbThreads) void ffn_branch_kernel(const FfnBranchP
 //
 // A block streams down a strip of the image 32 columns wide (30 output columns and one
 // halo column each side) over a band of rows.  Per input row y:
-//   1. the row's C x 32 values are in LDS (fetched a row ahead);
+//   1. the row's C x 32 values are in LDS (fetched a row ahead), each as three bf16 terms
+//      (v = t0 + t1 + t2 but for 2^-24 of it), pixel-major;
 //   2. wavefront w forms U[32 w .. 32 w + 31][32 columns] = gelu(W1 . x + b1) with
-//      v_mfma_f32_32x32x2_f32 - its 32 x 64 tile of W1 lives in registers, in the A
-//      operand's layout - and writes it, zeroed outside the image (the branch pads U with
-//      zeros), into row y's slot of a three-row ring in LDS;
+//      v_mfma_f32_32x32x16_bf16 on the terms - its 32 x 64 tile of W1, three bf16 terms per
+//      weight, lives in registers in the A operand's layout; six of the nine products of
+//      terms are accumulated in fp32, what is left out lies below 2^-24 of a product: fp32
+//      accuracy (3.8e-7 against the oracle at 180 x 320) from instructions a sixteenth as long
+//      as the fp32 ones, which moreover do not hold up the vector units - and writes it,
+//      zeroed outside the image (the branch pads U with zeros), into row y's slot of a
+//      three-row ring in LDS;
 //   3. the same wavefront applies the depth-wise branch to its own 32 hidden channels for
 //      output row y - 1 (lane = one channel and sixteen columns; rows y - 2, y - 1, y from the
 //      ring) and writes V over the ring's oldest row: the first layer, the GELU, the ring
 //      and the branch never leave the wavefront, so no block barrier is needed up to here;
 //   4. after a barrier, wavefront (mt, kh) multiplies W2's rows 32 mt .. + 31 with the 64
-//      hidden channels 64 kh .. + 63 of V (its 32 x 64 tile of W2 in registers); the kh = 1
-//      wavefronts hand their partial sums over through LDS, the kh = 0 ones add them and
-//      b2 and store 30 columns of output row y - 1 - while the kh = 1 ones already start on
-//      the next row.
-// Two barriers per row, 76 KB of LDS (two blocks per compute unit), weights read once per
+//      hidden channels 64 kh .. + 63 of V (v_mfma_f32_32x32x2_f32, its 32 x 64 tile of W2 in
+//      registers: V as three pixel-major bf16 terms would not fit beside the ring with two
+//      blocks per compute unit); the kh = 1 wavefronts hand their partial sums over through
+//      LDS, the kh = 0 ones add them and b2 and store 30 columns of output row y - 1 - while
+//      the kh = 1 ones already start on the next row.
+// Two barriers per row, 73 KB of LDS (two blocks per compute unit), weights read once per
 // block.  The band's first two input rows are recomputed by the band above
 // (rows_per_band + 2 first-layer rows for rows_per_band output rows), the strips' halo
-// columns by their neighbours (32 for 30).  Measured: the fp32 matrix instructions'
-// time and the vector instructions' time add up in this kernel - neither issued among
-// the other wavefront's nor among the same wavefront's vector instructions do these
-// matrix instructions run beside them - so the phases are simply written one after the other.
+// columns by their neighbours (32 for 30).  Measured: fp32 matrix instructions' time and
+// the vector instructions' time add up in this kernel - neither issued among the other
+// wavefront's nor among the same wavefront's vector instructions do fp32 matrix
+// instructions run beside them - so the phases are simply written one after the other,
+// and the first layer moved to the bf16 instructions (46.8 -> 41.0 us at 180 x 320).
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x4s __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8s __attribute__((ext_vector_type(8)));
 
 constexpr int kFsThreads = 256;
 constexpr int kFsC = 64;        // input (and output) channels the tiles hold
@@ -201,14 +210,17 @@ constexpr int kFsCh = 128;      // hidden channels the tiles hold
 constexpr int kFsNp = 32;       // columns of a strip, halo included
 constexpr int kFsOut = 30;      // output columns of a strip
 constexpr int kFsPitch = 33;    // floats between two channel rows of the ring (odd: lanes on different channels, same column, hit different banks)
-constexpr int kFsXFloats = 2 * kFsC * kFsNp;
+constexpr int kFsXPitch = kFsC + 8;                       // bf16 elements between two columns of the input row tile (144 bytes)
+constexpr int kFsXTerm = kFsNp * kFsXPitch;               // bf16 elements of one term's tile
+constexpr int kFsXFloats = (3 * kFsXTerm * 2 + 3) / 4;    // the input row as three bf16 terms, pixel-major (one buffer)
+static_assert((3 * kFsXTerm * 2) % 16 == 0, "the ring starts on a 16-byte boundary");
 constexpr int kFsRingFloats = 3 * kFsCh * kFsPitch;
 constexpr int kFsRedFloats = 2 * 16 * 64;
 constexpr int kFsBiasFloats = kFsCh + kFsC;
 constexpr size_t kFsLdsBytes = (size_t)(kFsXFloats + kFsRingFloats + kFsRedFloats + kFsBiasFloats) * sizeof(float);
 
-static_assert(kFsCh * (kFsC + 1) + kFsC * (kFsCh + 1) <= kFsXFloats + kFsRingFloats,
-              "the weights pass through the row buffers' and the ring's space on their way into registers");
+static_assert(kFsCh * (kFsC + 1) + kFsC * (kFsCh + 1) <= kFsXFloats + kFsRingFloats + kFsRedFloats,
+              "the weights pass through the row tile's, the ring's and the partial sums' space on their way into registers");
 
 extern __shared__ __align__(16) float fs_lds[];
 
@@ -220,8 +232,8 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
     const int mt = wave & 1, kh = wave >> 1;
     const int C = p.C, Ch = p.Ch, H = p.H, W = p.W;
 
-    float *sX = fs_lds;                     // [2][kFsC][kFsNp]
-    float *ring = sX + kFsXFloats;          // [3][kFsCh][kFsPitch]
+    uint16_t *sX = reinterpret_cast<uint16_t *>(fs_lds);   // [3 terms][kFsNp][kFsXPitch] bf16
+    float *ring = fs_lds + kFsXFloats;      // [3][kFsCh][kFsPitch]
     float *red = ring + kFsRingFloats;      // [2 mt][16][64]
     float *sB1 = red + kFsRedFloats;        // [kFsCh] first layer's biases, zeros beyond Ch
     float *sB2 = sB1 + kFsCh;               // [kFsC] second layer's
@@ -260,11 +272,22 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
             v[i] = xin[(size_t)(c < C ? c : 0) * plane + off];
         }
     };
-    auto put_row = [&](const float (&v)[8], int gy, int buf) {
+    // a row into LDS as three bf16 terms per value (v = t0 + t1 + t2 but for 2^-24 of it: each term
+    // the nearest bf16 to what the terms before it left), pixel-major: the first layer's B operands
+    auto put_row = [&](const float (&v)[8], int gy) {
         const bool in = col_in && gy >= 0 && gy < H;
+        uint16_t *d = sX + xpx * kFsXPitch + xc0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            sX[buf * (kFsC * kFsNp) + (xc0 + 8 * i) * kFsNp + xpx] = (in && xc0 + 8 * i < C) ? v[i] : 0.f;
+        for (int i = 0; i < 8; i += 2) {
+            const float v0 = (in && xc0 + 8 * i < C) ? v[i] : 0.f, v1 = (in && xc0 + 8 * (i + 1) < C) ? v[i + 1] : 0.f;
+            const uint32_t t0 = fb_pack2_bf16(v0, v1);
+            const float r0 = v0 - __uint_as_float(t0 << 16), r1 = v1 - __uint_as_float(t0 & 0xffff0000u);
+            const uint32_t t1 = fb_pack2_bf16(r0, r1);
+            const uint32_t t2 = fb_pack2_bf16(r0 - __uint_as_float(t1 << 16), r1 - __uint_as_float(t1 & 0xffff0000u));
+            d[8 * i] = (uint16_t)t0, d[8 * (i + 1)] = (uint16_t)(t0 >> 16);
+            d[kFsXTerm + 8 * i] = (uint16_t)t1, d[kFsXTerm + 8 * (i + 1)] = (uint16_t)(t1 >> 16);
+            d[2 * kFsXTerm + 8 * i] = (uint16_t)t2, d[2 * kFsXTerm + 8 * (i + 1)] = (uint16_t)(t2 >> 16);
+        }
     };
 
     float xr[8];
@@ -274,8 +297,10 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
     // LDS (the row buffers' and the ring's space, rows of an odd pitch), fetched by the block with coalesced loads:
     // fetched by every lane for itself - thirty-two rows per load instruction - the blocks
     // moved half a gigabyte through the L2 for 64 KB of weights ----
-    // first layer: lane holds W1[32 w + l32][2 kp + half]; second layer: W2[32 mt + l32][64 kh + 2 kp + half]
-    float a1[32], a2[32];
+    // first layer (bf16 instructions on exact terms): lane holds W1[32 w + l32][16 c + 8 half ... + 7] of
+    // chunk c as three bf16 terms; second layer (fp32 instructions): W2[32 mt + l32][64 kh + 2 kp + half]
+    u32x4s a1t[3][4];
+    float a2[32];
     {
         constexpr int kP1 = kFsC + 1, kP2 = kFsCh + 1;
         float *s1 = fs_lds, *s2 = fs_lds + kFsCh * kP1;  // both matrices at once, over the row buffers and the ring
@@ -301,10 +326,22 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
         }
         __syncthreads();
 #pragma unroll
-        for (int kp = 0; kp < 32; ++kp) {
-            a1[kp] = s1[(32 * wave + l32) * kP1 + 2 * kp + half];
-            a2[kp] = s2[(32 * mt + l32) * kP2 + 64 * kh + 2 * kp + half];
+        for (int c = 0; c < 4; ++c) {
+            unsigned t[3][4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float w0 = s1[(32 * wave + l32) * kP1 + 16 * c + 8 * half + 2 * e];
+                const float w1 = s1[(32 * wave + l32) * kP1 + 16 * c + 8 * half + 2 * e + 1];
+                t[0][e] = fb_pack2_bf16(w0, w1);
+                const float r0 = w0 - __uint_as_float(t[0][e] << 16), r1 = w1 - __uint_as_float(t[0][e] & 0xffff0000u);
+                t[1][e] = fb_pack2_bf16(r0, r1);
+                t[2][e] = fb_pack2_bf16(r0 - __uint_as_float(t[1][e] << 16), r1 - __uint_as_float(t[1][e] & 0xffff0000u));
+            }
+#pragma unroll
+            for (int q = 0; q < 3; ++q) a1t[q][c] = u32x4s{t[q][0], t[q][1], t[q][2], t[q][3]};
         }
+#pragma unroll
+        for (int kp = 0; kp < 32; ++kp) a2[kp] = s2[(32 * mt + l32) * kP2 + 64 * kh + 2 * kp + half];
         __syncthreads();  // everyone has its weights: the space is the row buffers' and the ring's from here on
     }
     // biases into LDS (the first barrier below covers them)
@@ -324,7 +361,7 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
         bkd = (in && p.bk != nullptr) ? vb : 0.f;
     }
 
-    put_row(xr, y0 - 1, 0);
+    put_row(xr, y0 - 1);
     fetch_row(y0, xr);
     __syncthreads();
 
@@ -332,26 +369,32 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
     const int steps = rows_out + 2;
     for (int r = 0; r < steps; ++r) {
         const int gy = y0 - 1 + r;   // this step's input row
-        // next row into the other buffer (read last a step ago, before that step's barriers), the row after it asked for
-        if (r + 1 < steps) {
-            put_row(xr, gy + 1, (r + 1) & 1);
-            if (r + 2 < steps) fetch_row(gy + 2, xr);
-        }
         // ---- first layer on row gy: U tile = W1 tile . x row ----
         {
             f32x16 acc;
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-            const float *bx = sX + (r & 1) * (kFsC * kFsNp) + half * kFsNp + l32;
             // the biases of the rows this lane's accumulators hold, asked for in front of the
             // products (read one by one where they are used, each read's latency was waited for)
             const float *b1p = sB1 + 32 * wave + 4 * half;
             float b1v[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) b1v[i] = b1p[8 * (i >> 2) + (i & 3)];
+            // v_mfma_f32_32x32x16_bf16 on the terms: of the nine products of a weight's and a value's terms
+            // the six whose orders add up to at most two (the rest lies below 2^-24 of a product)
+            const uint16_t *bx = sX + l32 * kFsXPitch + 8 * half;
 #pragma unroll
-            for (int kp = 0; kp < 32; ++kp)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[kp], bx[2 * kp * kFsNp], acc, 0, 0, 0);
+            for (int c = 0; c < 4; ++c) {
+                u32x4s x3[3];
+#pragma unroll
+                for (int q = 0; q < 3; ++q) x3[q] = *reinterpret_cast<const u32x4s *>(bx + q * kFsXTerm + 16 * c);
+#pragma unroll
+                for (int qw = 2; qw >= 0; --qw)
+#pragma unroll
+                    for (int qx = 2 - qw; qx >= 0; --qx)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8s, a1t[qw][c]),
+                                                                      __builtin_bit_cast(bf16x8s, x3[qx]), acc, 0, 0, 0);
+            }
             const bool live = ucol_in && gy >= 0 && gy < H;
             float *ur = ring + (r % 3) * (kFsCh * kFsPitch) + (32 * wave + 4 * half) * kFsPitch + l32;
 #pragma unroll
@@ -390,7 +433,12 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
 #pragma unroll
             for (int j = 0; j < 16; ++j) vr[j] = vv[j];
         }
-        __syncthreads();  // V of all hidden channels (and the next input row) is in LDS
+        __syncthreads();  // V of all hidden channels is in LDS; everyone has multiplied this step's input row
+        // the next row into the (one) row tile, the row after it asked for
+        if (r + 1 < steps) {
+            put_row(xr, gy + 1);
+            if (r + 2 < steps) fetch_row(gy + 2, xr);
+        }
         // ---- second layer: W2 tile (32 output channels x 64 hidden channels) . V ----
         f32x16 acc2;
         if (r >= 2) {
@@ -405,7 +453,7 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
                 for (int i = 0; i < 16; ++i) red[(mt * 16 + i) * 64 + lane] = acc2[i];
             }
         }
-        __syncthreads();  // the partial sums are in LDS; nobody reads V any more
+        __syncthreads();  // the partial sums and the next input row are in LDS; nobody reads V any more
         if (r >= 2 && kh == 0) {
             const int gyo = gy - 1, gxo = x0 + l32;
             const bool st_ok = l32 >= 1 && l32 <= kFsOut && gxo < W;   // (gyo < H by the loop's bound)
@@ -444,9 +492,6 @@ __global__ __launch_bounds__(kFsThreads, 2) void ffn_stream_kernel(const FfnStre
 // 2 terms x 4 chunks of sixteen channels x 4 registers, and V has a buffer of its own (it
 // is bf16, the ring fp32).  U stays fp32 in the ring - only V is rounded to bf16 on the way
 // to the second layer, as a stored V would be - and out is rounded once at its store.
-
-typedef unsigned u32x4s __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8s __attribute__((ext_vector_type(8)));
 
 constexpr int kFbXPitch = kFsC + 8;                  // bf16 elements between two columns of an input row tile (144 bytes)
 constexpr int kFbVPitch = kFsCh + 8;                 // ... of V's tile (272 bytes)
