@@ -131,6 +131,32 @@ def test_bases_off_the_vector_alignment(oracle, dtype):
     gu.assert_att_close(as_f64(gu.out_to_np(out.contiguous(), dtype), dtype), ref, dtype, "unaligned bases")
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("N", [1, 16])   # one image: three launches; sixteen: the one-launch kernels
+def test_non_finite_pixels_spoil_exactly_their_neighbourhood(oracle, N, dtype):
+    # a NaN (and an Inf) in one input pixel makes U non-finite at that pixel in every hidden channel, V in
+    # its 3 x 3 neighbourhood, out there in every channel - and nothing else, whatever strip, band or tile
+    # the pixel and its neighbours fall into; the oracle's footprint is the reference
+    C, H, W, Ch = 6, 37, 95, 10
+    x = make_x(50 + N, N, C, H, W, dtype)
+    planted = [(0, 2, 0, 0, np.nan), (N - 1, 5, 36, 94, np.inf), (N // 2, 0, 3, 29, np.nan), (N // 2, 1, 4, 30, -np.inf),
+               (0, 3, 20, 60, np.nan)]
+    xf = wk.bf16_bits_to_f32(x) if dtype == BF16 else x.copy()
+    for n, c, y, xx, v in planted:
+        xf[n, c, y, xx] = v
+    x = wk.f32_to_bf16_bits(xf) if dtype == BF16 else xf
+    p = wk.make_ffn_params(1050, C, Ch)
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle.convffn_forward(x, p["w1"], p["k"], p["w2"], dtype, b1=p["b1"], bk=p["bk"], b2=p["b2"])
+    got = as_f64(run_ffn(x, dtype, p), dtype)
+    bad_ref = ~np.isfinite(ref)
+    assert bad_ref.any() and bad_ref.sum() <= len(planted) * 9 * C
+    assert np.array_equal(~np.isfinite(got), bad_ref)
+    ok = ~bad_ref
+    scale = np.abs(ref[ok]).max()
+    assert np.abs(got[ok] - ref[ok]).max() <= gu.TOL[dtype] * scale
+
+
 def test_branch_closed_form_ones(oracle):
     # w1 = 0, b1 chosen so that U = gelu(b1) = const; K = 1: V = U + gelu(U * taps inside the image);
     # w2 picks the hidden channel: the border handling in closed form, without the oracle
