@@ -427,8 +427,8 @@ def replays_for(steps, asked):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path needs no collective; "
-              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path shards over images, channels or row "
+              "bands without a collective, but only one GPU is built and timed); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
