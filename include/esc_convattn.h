@@ -182,8 +182,9 @@ esc_status esc_convattn_fused_forward(const void *x, esc_dtype dt, int N, int C,
  * All weights are device pointers to fp32, read-only.  The point-wise layers run on the
  * matrix cores as in esc_convattn_fused_forward (fp32 storage: fp32 products; bf16 storage:
  * bf16 instructions on the stored values, each fp32 weight as two bf16 terms), the branch
- * in fp32 on the vector units.  With C <= 64, C_h <= 128 and an image (or batch) large
- * enough to fill the chip with 30-column strips the call takes ONE launch in which U and V
+ * in fp32 on the vector units.  With C <= 64, C_h <= 128, an image (or batch) large enough
+ * to fill the chip with 30-column strips and a width that fills at least four fifths of its
+ * strips, the call takes ONE launch in which U and V
  * never leave the chip (the workspace is not touched; with bf16 storage U stays fp32 and V
  * is rounded to bf16 once, as the second layer's operand); everything else takes three
  * launches, U and V passing through the workspace in the storage type, so that with bf16

@@ -792,6 +792,9 @@ __attribute__((visibility("hidden"))) hipError_t launch_ffn_stream(const FfnStre
     // a block lasts as long whatever the image's size (its weights' way into registers, then six
     // rows one after the other): with too few blocks to fill the chip the three launches are faster
     if ((long)p.N * q.strips * ((p.H + 3) / 4) < 3L * cus / 2) return hipErrorNotSupported;
+    // ... and a last strip that is mostly empty costs as much as a full one: widths that fill less than
+    // four fifths of their strips keep the three launches too (64 columns are 30 + 30 + 4)
+    if (5L * p.W < 4L * q.strips * kFsOut) return hipErrorNotSupported;
     // the band height that needs the fewest row steps one after the other: a block takes its rows + 2
     // steps and about a step and a half to get its weights; the blocks run in rounds of two per compute unit
     q.rows_per_band = 4;

@@ -71,17 +71,18 @@ def check_ffn(oracle, seed, N, C, H, W, Ch, dtype, bias=True, what=""):
     (1, 33, 17, 32, 65),      # channel counts one beyond the stages of 32 and the passes of 64
     (2, 70, 9, 11, 12),       # more than 64 channels: fp32 storage takes the three-launch path too (element-wise fetches)
     (1, 8, 12, 16, 136),      # a hidden layer beyond 128: the same, with 16-byte pieces
-    # batches large enough for the one-launch kernels (they want 384 strips x bands of four rows):
-    (64, 64, 7, 61, 128),     # at its widest, three strips with a ragged last one, two bands
-    (12, 5, 37, 95, 7),       # several bands and strips, the last strip five columns wide
+    # batches large enough for the one-launch kernels (they want 384 strips x bands of four rows, and widths
+    # that fill at least four fifths of their 30-column strips):
+    (64, 64, 7, 85, 128),     # at its widest, three strips with a ragged last one, two bands
+    (12, 5, 37, 100, 7),      # several bands and strips, the last strip ten columns wide
     (24, 3, 70, 30, 4),       # exactly one strip, bands that do not divide the height
-    (8, 9, 200, 64, 20),      # bands of sixteen rows, the last one eight rows high
+    (8, 9, 200, 85, 20),      # bands of sixteen rows, the last one eight rows high
     (20, 4, 64, 60, 6),       # bands of eight rows
     (64, 2, 100, 58, 3),      # bands of thirty-two rows, the last one four rows high
-    (400, 1, 1, 1, 1),        # single elements: one strip of one column, one band of one row
-    (200, 2, 2, 31, 3),       # a second strip that is one column wide, fewer rows than a band
-    (130, 3, 3, 5, 2),        # a strip narrower than its halo allows for
-
+    (400, 1, 1, 25, 1),       # single rows: one band of one row
+    (4, 2, 37, 301, 3),       # eleven strips, the last one a single column wide
+    (390, 3, 3, 25, 2),       # fewer rows than a band
+    (16, 4, 12, 64, 8),       # a width that fills too little of its strips: three launches however large the batch
 ])
 def test_small_and_ragged_shapes(oracle, shape, dtype):
     N, C, H, W, Ch = shape
@@ -137,9 +138,9 @@ def test_non_finite_pixels_spoil_exactly_their_neighbourhood(oracle, N, dtype):
     # a NaN (and an Inf) in one input pixel makes U non-finite at that pixel in every hidden channel, V in
     # its 3 x 3 neighbourhood, out there in every channel - and nothing else, whatever strip, band or tile
     # the pixel and its neighbours fall into; the oracle's footprint is the reference
-    C, H, W, Ch = 6, 37, 95, 10
+    C, H, W, Ch = 6, 37, 100, 10
     x = make_x(50 + N, N, C, H, W, dtype)
-    planted = [(0, 2, 0, 0, np.nan), (N - 1, 5, 36, 94, np.inf), (N // 2, 0, 3, 29, np.nan), (N // 2, 1, 4, 30, -np.inf),
+    planted = [(0, 2, 0, 0, np.nan), (N - 1, 5, 36, 99, np.inf), (N // 2, 0, 3, 29, np.nan), (N // 2, 1, 4, 30, -np.inf),
                (0, 3, 20, 60, np.nan)]
     xf = wk.bf16_bits_to_f32(x) if dtype == BF16 else x.copy()
     for n, c, y, xx, v in planted:
